@@ -1,0 +1,162 @@
+"""Assembler for micro-operation (uop) programs, oracle side.
+
+Test infrastructure, not product code.  The paper names the fields of the
+instruction word (Section 4.1: opcode, size, address, flags send/recv/dynamic,
+depId, virtualFlowId) but fixes no widths; the layout used by this build is
+restated here from its written description, independently of the product's
+encoder, so that tests can build programs without touching product code.
+
+Word (4 x uint32, little endian):
+  w0  [7:0] opcode  [15:8] flags  [19:16] vflow  [21:20] vcc  [24:22] acc  [30:25] nslots
+  w1  [15:0] size   [31:16] depId
+  w2:w3 (64 bit)  [47:0] imm (signed)  [55:48] desc  [63:56] dep_count
+Descriptor (8 x uint32): tensor, box_rows, row_bytes, lds_pitch, gpitch_lo, gpitch_hi, 0, 0
+"""
+import numpy as np
+
+# opcodes
+HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
+LOAD, STORE = 8, 9
+MATVEC = 16
+
+# flags
+F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV = 1, 2, 4, 8, 16, 32
+
+MASK48 = (1 << 48) - 1
+
+
+def word(opcode, flags=0, vflow=0, vcc=0, acc=0, nslots=0, size=0, dep_id=0, imm=0, desc=0, dep_count=0):
+    assert 0 <= opcode < 256 and 0 <= flags < 256 and 0 <= vflow < 16 and 0 <= vcc < 4
+    assert 0 <= acc < 8 and 0 <= nslots < 64 and 0 <= size < 65536 and 0 <= dep_id < 65536
+    assert -(1 << 47) <= imm < (1 << 47) and 0 <= desc < 256 and 0 <= dep_count < 256
+    w0 = opcode | (flags << 8) | (vflow << 16) | (vcc << 20) | (acc << 22) | (nslots << 25)
+    w1 = size | (dep_id << 16)
+    q = (imm & MASK48) | (desc << 48) | (dep_count << 56)
+    return (w0, w1, q & 0xFFFFFFFF, q >> 32)
+
+
+def descriptor(tensor, box_rows, row_bytes, lds_pitch, gpitch):
+    assert 0 <= tensor < 256 and 0 < box_rows < (1 << 20) and 0 < row_bytes <= lds_pitch < 65536 and gpitch >= 0
+    return (tensor, box_rows, row_bytes, lds_pitch, gpitch & 0xFFFFFFFF, gpitch >> 32, 0, 0)
+
+
+def matvec_imm(B, R, lpr):
+    """Static geometry of a MATVEC: B vectors, R box rows per matrix tile, lpr 16-byte chunks per tile row."""
+    assert 1 <= B <= 8 and 1 <= R < 65536 and 1 <= lpr < 65536
+    return B | (R << 8) | (lpr << 24)
+
+
+class Program:
+    """Per-unit uop streams of n_cores cores, each with one VMC stream and vcc_per_core VCC streams."""
+
+    def __init__(self, n_cores, vcc_per_core=2):
+        self.n_cores, self.V = n_cores, vcc_per_core
+        self.streams = [[] for _ in range(n_cores * (1 + vcc_per_core))]
+        self.descs = []
+
+    def vmc(self, core):
+        return self.streams[core * (1 + self.V)]
+
+    def vcc(self, core, v):
+        return self.streams[core * (1 + self.V) + 1 + v]
+
+    def desc(self, *a, **k):
+        d = descriptor(*a, **k)
+        if d in self.descs:
+            return self.descs.index(d)
+        self.descs.append(d)
+        return len(self.descs) - 1
+
+    def finish(self):
+        """Terminate every stream with HALT and return (words[n,4] u32, stream_begin[n_streams+1] u32, descs[n,8] u32)."""
+        words, begin = [], [0]
+        for s in self.streams:
+            body = list(s)
+            if not body or (body[-1][0] & 0xFF) != HALT:
+                body.append(word(HALT))
+            words.extend(body)
+            begin.append(len(words))
+        descs = self.descs if self.descs else [descriptor(0, 1, 4, 4, 0)]
+        return (np.array(words, dtype=np.uint32).reshape(-1, 4), np.array(begin, dtype=np.uint32),
+                np.array(descs, dtype=np.uint32).reshape(-1, 8))
+
+
+def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_core=2, nt=False):
+    """A straightforward dense Y = M X program in the form of the paper's listing (Section 4.1):
+    row blocks of R rows are dealt round-robin to the (core, vcc) pairs; each row block is one MATVEC
+    over ceil(K/Kt) (matrix tile, vector tile) pairs, followed by a send+recv STORE of the result.
+    No loops, no accumulators: every address is a literal.  Tensors: 0 = M, 1 = X, 2 = Y."""
+    assert K % 4 == 0 and ld % 4 == 0 and Kt % 4 == 0
+    p = Program(n_cores, vcc_per_core)
+    lpr = Kt // 4
+    nk = -(-K // Kt)
+    m_slots = -(-R * Kt * 4 // slot_bytes)
+    x_slots = -(-B * Kt * 4 // slot_bytes)
+    y_slots = -(-B * R * 4 // slot_bytes)
+    nrb = -(-rows // R)
+    for rb in range(nrb):
+        unit = rb % (n_cores * vcc_per_core)
+        core, v = unit // vcc_per_core, unit % vcc_per_core
+        r0 = rb * R
+        rv = min(R, rows - r0)
+        vm = p.vmc(core)
+        for kt in range(nk):
+            k0 = kt * Kt
+            kv = min(Kt, K - k0)
+            dm = p.desc(0, R, kv * 4, Kt * 4, ld * 4)
+            dx = p.desc(1, B, kv * 4, Kt * 4, K * 4)
+            vm.append(word(LOAD, F_SEND | (F_NT if nt else 0), vflow=2 * v, vcc=v, nslots=m_slots, size=rv,
+                           imm=(r0 * ld + k0) * 4, desc=dm))
+            vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=x_slots, size=B, imm=k0 * 4, desc=dx))
+        dy = p.desc(2, B, rv * 4, R * 4, rows * 4)
+        vm.append(word(STORE, F_SEND | F_RECV, vflow=4 + v, vcc=v, nslots=y_slots, size=B, imm=r0 * 4, desc=dy))
+        p.vcc(core, v).append(word(MATVEC, size=nk, imm=matvec_imm(B, R, lpr)))
+    return p
+
+
+def looped_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_core=2, nt=False):
+    """The same product as dense_matvec_program, written the way Section 5 ("Dynamic address
+    generation") describes recurring patterns: a LOOP/REPEAT nest whose memory uops carry the
+    `dynamic` flag and take their offset from accumulators that control uops advance.
+    Requires rows % R == 0, K % Kt == 0 and rows/R divisible by the number of (core, vcc) pairs,
+    so that every unit runs the same nest on a contiguous range of row blocks.
+    Accumulators: 0 = matrix offset, 1 = vector offset, 2 = result offset."""
+    units = n_cores * vcc_per_core
+    nrb = rows // R
+    assert rows % R == 0 and K % Kt == 0 and nrb % units == 0
+    per = nrb // units
+    nk = K // Kt
+    p = Program(n_cores, vcc_per_core)
+    lpr = Kt // 4
+    m_slots = -(-R * Kt * 4 // slot_bytes)
+    x_slots = -(-B * Kt * 4 // slot_bytes)
+    y_slots = -(-B * R * 4 // slot_bytes)
+    dm = p.desc(0, R, Kt * 4, Kt * 4, ld * 4)
+    dx = p.desc(1, B, Kt * 4, Kt * 4, K * 4)
+    dy = p.desc(2, B, R * 4, R * 4, rows * 4)
+    for core in range(n_cores):
+        vm = p.vmc(core)
+        # the two compute cores of a memory core are served one after the other, row block by row block
+        for v in range(vcc_per_core):
+            first = (core * vcc_per_core + v) * per          # first row block of this unit
+            vm.append(word(SET, acc=0, imm=first * R * ld * 4))
+            vm.append(word(SET, acc=1, imm=0))
+            vm.append(word(SET, acc=2, imm=first * R * 4))
+            vm.append(word(LOOP, imm=per))
+            vm.append(word(LOOP, imm=nk))
+            vm.append(word(LOAD, F_SEND | F_DYNAMIC | (F_NT if nt else 0), vflow=2 * v, vcc=v, acc=0,
+                           nslots=m_slots, size=R, imm=0, desc=dm))
+            vm.append(word(LOAD, F_SEND | F_DYNAMIC, vflow=2 * v + 1, vcc=v, acc=1, nslots=x_slots, size=B,
+                           imm=0, desc=dx))
+            vm.append(word(ADD, acc=1, imm=Kt * 4))
+            vm.append(word(REPEAT, acc=0, imm=Kt * 4))
+            vm.append(word(STORE, F_SEND | F_RECV | F_DYNAMIC, vflow=4 + v, vcc=v, acc=2, nslots=y_slots, size=B,
+                           imm=0, desc=dy))
+            vm.append(word(ADD, acc=1, imm=-K * 4))
+            vm.append(word(ADD, acc=2, imm=R * 4))
+            vm.append(word(REPEAT, acc=0, imm=(R * ld - K) * 4))
+            vc = p.vcc(core, v)
+            vc.append(word(LOOP, imm=per))
+            vc.append(word(MATVEC, size=nk, imm=matvec_imm(B, R, lpr)))
+            vc.append(word(REPEAT, acc=0, imm=0))
+    return p

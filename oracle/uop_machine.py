@@ -1,0 +1,468 @@
+"""Sequential CPU interpreter of the decoupled abstract machine.
+
+Test infrastructure, not product code.  It follows the paper's description of the
+machine in the paper's order and vocabulary and shares nothing with the HIP path:
+
+* Section 4.1 ("Abstraction of GPU Hardware"): every core is a small register machine
+  running its own uop stream: memory and control uops on the virtual memory core (VMC),
+  compute and control uops on each virtual compute core (VCC).
+* Section 4.1 ("Encoding dependency in uop"): a memory uop forwards its region to a local
+  VCC when it carries `send`, consumes a region from a local VCC when it carries `recv`,
+  and has at most one dependency on another memory uop, named by `depId`.
+* Section 4.1 ("Virtual-flow-based execution") and Section 4.3 ("Parallel virtual flow
+  execution"): uops of one virtual flow go to one load/store unit and run in order there;
+  different flows may overlap.
+* Section 4.3 ("Virtual Memory Core"): a front end (CFU) keeps register state, runs control
+  uops and generates addresses, then issues to load units (LDU) and store units (STU);
+  local memory is handed out in slots tracked by a 32-bit mask; a request takes the first
+  run of contiguous free slots.
+* Section 4.3 ("Dependency Resolving"): FIFO queues m2c (VMC to VCC: loaded regions) and
+  c2m (VCC to VMC: used or produced regions); a global table indexed by depId between VMCs.
+* Section 4.3 ("Avoiding Deadlock"): slots are allocated in program order; everything
+  after allocation may complete out of order.
+* Section 5 ("Dynamic address generation"): with `dynamic`, the address field is offset by
+  an accumulator register that control uops update.
+* Section 4.1, listing of the `matvec` compute uop: for each of `size` tiles pop a matrix
+  tile and a vector tile from m2c, accumulate, push both to c2m; then pop an output
+  region, copy the accumulators into it and push it back.
+
+Where the paper is silent the readings are those written in the design document:
+16-byte words, the opcode set below, m2c delivery in program order of the `send` uops
+(tickets), and a `kind` tag on c2m messages (recycle / produced).
+
+The interpreter is driven by a scheduler that repeatedly picks one *enabled* action;
+"program" order scans the agents round-robin, "random" picks uniformly with a seed.
+The machine is deterministic in its results (memory image, per-unit traces) under every
+legal schedule; tests check that.
+"""
+from collections import deque
+from dataclasses import dataclass, field
+
+import numpy as np
+
+HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
+LOAD, STORE = 8, 9
+MATVEC = 16
+F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV = 1, 2, 4, 8, 16, 32
+KIND_FREE, KIND_DATA = 0, 1
+MAX_LOOP_DEPTH = 4
+N_ACC = 8
+
+
+class DeadlockError(RuntimeError):
+    pass
+
+
+class ProgramError(RuntimeError):
+    pass
+
+
+@dataclass
+class Uop:
+    opcode: int
+    flags: int
+    vflow: int
+    vcc: int
+    acc: int
+    nslots: int
+    size: int
+    dep_id: int
+    imm: int
+    desc: int
+    dep_count: int
+
+
+def decode(w):
+    """Split one 4 x uint32 word into its fields (layout: see the design document)."""
+    w0, w1, w2, w3 = (int(x) for x in w)
+    q = w2 | (w3 << 32)
+    imm = q & ((1 << 48) - 1)
+    if imm >> 47:
+        imm -= 1 << 48
+    return Uop(opcode=w0 & 0xFF, flags=(w0 >> 8) & 0xFF, vflow=(w0 >> 16) & 0xF, vcc=(w0 >> 20) & 0x3,
+               acc=(w0 >> 22) & 0x7, nslots=(w0 >> 25) & 0x3F, size=w1 & 0xFFFF, dep_id=w1 >> 16,
+               imm=imm, desc=(q >> 48) & 0xFF, dep_count=q >> 56)
+
+
+@dataclass
+class Desc:
+    tensor: int
+    box_rows: int
+    row_bytes: int
+    lds_pitch: int
+    gpitch: int
+
+
+def decode_desc(d):
+    d = [int(x) for x in d]
+    return Desc(d[0], d[1], d[2], d[3], d[4] | (d[5] << 32))
+
+
+def first_fit(mask, n, n_slots):
+    """Lowest p such that slots p .. p+n-1 are all free (bit clear) and p+n <= n_slots; -1 if none.
+    Section 4.3: every allocator thread probes from its own position and the vote takes the first."""
+    for p in range(0, n_slots - n + 1):
+        if all(((mask >> (p + i)) & 1) == 0 for i in range(n)):
+            return p
+    return -1
+
+
+class _Seq:
+    """Register state of one stream: program counter, loop stack, accumulators."""
+
+    def __init__(self, words, begin, end):
+        self.words, self.begin, self.end = words, begin, end
+        self.pc = begin
+        self.loops = []
+        self.acc = [0] * N_ACC
+        self.halted = False
+
+    def fetch(self):
+        if self.pc >= self.end:
+            raise ProgramError("stream ran past its end without HALT")
+        return decode(self.words[self.pc])
+
+    def control(self, u):
+        """Run a control uop; returns True if `u` was one."""
+        if u.opcode == HALT:
+            if self.loops:
+                raise ProgramError("HALT inside a loop")
+            self.halted = True
+        elif u.opcode == LOOP:
+            if u.imm < 1 or len(self.loops) >= MAX_LOOP_DEPTH:
+                raise ProgramError("bad LOOP")
+            self.loops.append([self.pc + 1, u.imm])
+            self.pc += 1
+        elif u.opcode == REPEAT:
+            if not self.loops:
+                raise ProgramError("REPEAT without LOOP")
+            self.acc[u.acc] += u.imm
+            self.loops[-1][1] -= 1
+            if self.loops[-1][1] > 0:
+                self.pc = self.loops[-1][0]
+            else:
+                self.loops.pop()
+                self.pc += 1
+        elif u.opcode == ADD:
+            self.acc[u.acc] += u.imm
+            self.pc += 1
+        elif u.opcode == SET:
+            self.acc[u.acc] = u.imm
+            self.pc += 1
+        else:
+            return False
+        return True
+
+
+@dataclass
+class Issued:
+    """A memory uop after the front end: decoded, address generated, slots allocated."""
+    pc: int
+    u: Uop
+    d: Desc
+    offset: int          # byte offset inside the tensor
+    slot: int
+    ticket: int          # position in m2c[vcc] when SEND, else -1
+
+
+class Core:
+    def __init__(self, m, idx):
+        self.m, self.idx = m, idx
+        V = m.V
+        sb = m.stream_begin
+        base = idx * (1 + V)
+        self.vmc = _Seq(m.words, int(sb[base]), int(sb[base + 1]))
+        self.vccs = [_Seq(m.words, int(sb[base + 1 + v]), int(sb[base + 2 + v])) for v in range(V)]
+        self.mask = 0
+        self.lmem = np.zeros(m.n_slots * m.slot_bytes, dtype=np.uint8)
+        self.ldu = [deque() for _ in range(m.n_ldu)]
+        self.stu = [deque() for _ in range(m.n_stu)]
+        self.m2c = [dict() for _ in range(V)]        # ticket -> message
+        self.m2c_next_ticket = [0] * V
+        self.m2c_head = [0] * V
+        self.c2m = [deque() for _ in range(V)]
+        self.mailbox = [deque() for _ in range(V)]   # produced regions waiting for their STORE
+        self.vcc_run = [None] * V                    # running compute uop (generator) per VCC
+        self.vcc_wait = [False] * V
+        self.peak_slots = 0
+        self.stats = dict(m2c_push=[0] * V, m2c_pop=[0] * V, c2m_push=[0] * V, c2m_pop=[0] * V)
+
+    # ---- slot pool -------------------------------------------------------------------------
+    def alloc(self, n):
+        p = first_fit(self.mask, n, self.m.n_slots)
+        if p < 0:
+            return -1
+        bits = ((1 << n) - 1) << p
+        assert self.mask & bits == 0
+        self.mask |= bits
+        self.peak_slots = max(self.peak_slots, bin(self.mask).count("1"))
+        return p
+
+    def free(self, p, n):
+        bits = ((1 << n) - 1) << p
+        if self.mask & bits != bits:
+            raise ProgramError("free of slots that are not allocated")
+        self.mask &= ~bits
+
+    def region(self, slot, nslots):
+        sb = self.m.slot_bytes
+        return self.lmem[slot * sb:(slot + nslots) * sb]
+
+
+class Machine:
+    def __init__(self, words, stream_begin, descs, tensors, n_cores, vcc_per_core=2, slot_bytes=8192,
+                 n_slots=19, n_ldu=2, n_stu=1, n_dep_ids=64, unit_queue_cap=8):
+        """tensors: list of numpy arrays (any dtype); they are read and written in place as bytes."""
+        self.words = np.asarray(words, dtype=np.uint32).reshape(-1, 4)
+        self.stream_begin = np.asarray(stream_begin, dtype=np.uint32)
+        self.descs = [decode_desc(d) for d in np.asarray(descs, dtype=np.uint32).reshape(-1, 8)]
+        self.tensors = [t.reshape(-1).view(np.uint8) for t in tensors]
+        self.n_cores, self.V = n_cores, vcc_per_core
+        assert len(self.stream_begin) == n_cores * (1 + vcc_per_core) + 1
+        assert 1 <= n_slots <= 32
+        self.slot_bytes, self.n_slots = slot_bytes, n_slots
+        self.n_ldu, self.n_stu, self.qcap = n_ldu, n_stu, unit_queue_cap
+        self.dep = [0] * n_dep_ids
+        self.cores = [Core(self, c) for c in range(n_cores)]
+        # per-unit traces: (pc relative to the stream, opcode, desc, tensor byte offset, rows)
+        self.trace_vmc = [[] for _ in range(n_cores)]
+        self.trace_vcc = [[[] for _ in range(vcc_per_core)] for _ in range(n_cores)]
+        self.alloc_log = [[] for _ in range(n_cores)]     # (mask before, n, position) per allocation
+        self.steps = 0
+
+    # ---- front end of the VMC ----------------------------------------------------------------
+    def _cfu_enabled_and_step(self, core, commit):
+        s = core.vmc
+        if s.halted:
+            return False
+        u = s.fetch()
+        if u.opcode in (HALT, LOOP, REPEAT, ADD, SET):
+            if commit:
+                s.control(u)
+            return True
+        if u.opcode not in (LOAD, STORE):
+            raise ProgramError("opcode %d on a memory core" % u.opcode)
+        d = self.descs[u.desc]
+        need = -(-d.box_rows * d.lds_pitch // self.slot_bytes)
+        if u.nslots != need or u.nslots < 1 or u.nslots > self.n_slots:
+            raise ProgramError("nslots does not match the descriptor box")
+        if u.size < 1 or u.size > d.box_rows or u.vcc >= self.V:
+            raise ProgramError("bad rows or vcc")
+        units = core.ldu if u.opcode == LOAD else core.stu
+        q = units[u.vflow % len(units)]
+        if len(q) >= self.qcap:
+            return False
+        if first_fit(core.mask, u.nslots, self.n_slots) < 0:
+            return False                      # in-order allocation: the front end stalls here
+        if not commit:
+            return True
+        before = core.mask
+        slot = core.alloc(u.nslots)
+        self.alloc_log[core.idx].append((before, u.nslots, slot))
+        off = u.imm + (s.acc[u.acc] if u.flags & F_DYNAMIC else 0)
+        t = self.tensors[d.tensor]
+        last = off + (u.size - 1) * d.gpitch + d.row_bytes
+        if off < 0 or last > t.size:
+            raise ProgramError("tensor access out of bounds")
+        ticket = -1
+        if u.flags & F_SEND:
+            ticket = core.m2c_next_ticket[u.vcc]
+            core.m2c_next_ticket[u.vcc] += 1
+        rec = Issued(s.pc - s.begin, u, d, off, slot, ticket)
+        self.trace_vmc[core.idx].append((rec.pc, u.opcode, u.desc, off, u.size))
+        if u.opcode == STORE and u.flags & F_SEND:
+            # the empty output region goes to the compute core at once; the store unit only
+            # waits for it to come back
+            core.region(slot, u.nslots)[:] = 0
+            self._m2c_push(core, u.vcc, ticket, (slot, u.nslots, u.size, d.row_bytes))
+        q.append(rec)
+        s.pc += 1
+        return True
+
+    def _m2c_push(self, core, v, ticket, msg):
+        assert ticket not in core.m2c[v]
+        core.m2c[v][ticket] = msg
+        core.stats["m2c_push"][v] += 1
+
+    # ---- load / store units ------------------------------------------------------------------
+    def _unit_enabled_and_step(self, core, q, commit):
+        if not q:
+            return False
+        rec = q[0]
+        u, d = rec.u, rec.d
+        if u.flags & F_DEP_RECV and self.dep[u.dep_id] < max(1, u.dep_count):
+            return False
+        if u.opcode == STORE and u.flags & F_RECV and not core.mailbox[u.vcc]:
+            return False
+        if not commit:
+            return True
+        q.popleft()
+        t = self.tensors[d.tensor]
+        reg = core.region(rec.slot, u.nslots)
+        if u.opcode == LOAD:
+            reg[:] = 0                        # the part of the box outside the valid tile reads as zero
+            for r in range(u.size):
+                g = rec.offset + r * d.gpitch
+                reg[r * d.lds_pitch:r * d.lds_pitch + d.row_bytes] = t[g:g + d.row_bytes]
+            if u.flags & F_SEND:
+                self._m2c_push(core, u.vcc, rec.ticket, (rec.slot, u.nslots, u.size, d.row_bytes))
+            # a load that is not sent on stays allocated until something frees it; not used here
+        else:
+            if u.flags & F_RECV:
+                slot, nslots = core.mailbox[u.vcc].popleft()
+                if (slot, nslots) != (rec.slot, u.nslots):
+                    raise ProgramError("store received a region it did not allocate")
+            for r in range(u.size):
+                g = rec.offset + r * d.gpitch
+                t[g:g + d.row_bytes] = reg[r * d.lds_pitch:r * d.lds_pitch + d.row_bytes]
+            core.free(rec.slot, u.nslots)
+        if u.flags & F_DEP_SEND:
+            self.dep[u.dep_id] += 1
+        return True
+
+    # ---- c2m receiver of the VMC ---------------------------------------------------------------
+    def _drain_enabled_and_step(self, core, v, commit):
+        if not core.c2m[v]:
+            return False
+        if commit:
+            kind, slot, nslots = core.c2m[v].popleft()
+            core.stats["c2m_pop"][v] += 1
+            if kind == KIND_FREE:
+                core.free(slot, nslots)
+            else:
+                core.mailbox[v].append((slot, nslots))
+        return True
+
+    # ---- compute cores -------------------------------------------------------------------------
+    def _matvec(self, core, v, u):
+        """The matvec compute uop of the listing, as a coroutine that yields at every pop_wait."""
+        B = u.imm & 0xFF
+        R = (u.imm >> 8) & 0xFFFF
+        lpr = (u.imm >> 24) & 0xFFFF
+        Kt = lpr * 4
+        c = np.zeros((B, R), dtype=np.float64)            # alloc_registers: the accumulators
+        for _ in range(u.size):
+            a = yield                                      # a = m2c.pop_wait()
+            b = yield                                      # b = m2c.pop_wait()
+            a_slot, a_n, a_rows, a_rb = a
+            b_slot, b_n, b_rows, b_rb = b
+            if b_rows != B or a_rows > R:
+                raise ProgramError("matvec: tile geometry does not match the uop")
+            at = core.region(a_slot, a_n).view(np.float32)[:R * Kt].reshape(R, Kt).astype(np.float64)
+            bt = core.region(b_slot, b_n).view(np.float32)[:B * Kt].reshape(B, Kt).astype(np.float64)
+            c += bt @ at.T                                 # matvec_tile_accumulate(a, b, c)
+            self._c2m_push(core, v, KIND_FREE, a_slot, a_n)   # c2m.push(a, b)
+            self._c2m_push(core, v, KIND_FREE, b_slot, b_n)
+        o = yield                                          # c_shared = m2c.pop_wait()
+        o_slot, o_n, o_rows, o_rb = o
+        if o_rows != B or o_rb > R * 4:
+            raise ProgramError("matvec: output region does not match the uop")
+        out = core.region(o_slot, o_n).view(np.float32)[:B * R].reshape(B, R)
+        out[:, :] = c.astype(np.float32)                   # copy(c, c_shared)
+        self._c2m_push(core, v, KIND_DATA, o_slot, o_n)    # push it back for the write-back
+
+    def _c2m_push(self, core, v, kind, slot, nslots):
+        core.c2m[v].append((kind, slot, nslots))
+        core.stats["c2m_push"][v] += 1
+
+    def _vcc_enabled_and_step(self, core, v, commit):
+        s = core.vccs[v]
+        run = core.vcc_run[v]
+        if run is None:
+            if s.halted:
+                return False
+            u = s.fetch()
+            if u.opcode in (HALT, LOOP, REPEAT, ADD, SET):
+                if commit:
+                    s.control(u)
+                return True
+            if u.opcode != MATVEC:
+                raise ProgramError("opcode %d on a compute core" % u.opcode)
+            if commit:
+                self.trace_vcc[core.idx][v].append((s.pc - s.begin, u.opcode, u.size, u.imm))
+                g = self._matvec(core, v, u)
+                next(g)                                    # runs up to the first pop_wait
+                core.vcc_run[v] = g
+            return True
+        # blocked in pop_wait: enabled when the next ticket has been delivered
+        head = core.m2c_head[v]
+        if head not in core.m2c[v]:
+            return False
+        if commit:
+            msg = core.m2c[v].pop(head)
+            core.m2c_head[v] += 1
+            core.stats["m2c_pop"][v] += 1
+            try:
+                run.send(msg)
+            except StopIteration:
+                core.vcc_run[v] = None
+                s.pc += 1
+        return True
+
+    # ---- scheduler -----------------------------------------------------------------------------
+    def _agents(self):
+        ag = []
+        for core in self.cores:
+            ag.append(lambda commit, c=core: self._cfu_enabled_and_step(c, commit))
+            for q in core.ldu + core.stu:
+                ag.append(lambda commit, c=core, q=q: self._unit_enabled_and_step(c, q, commit))
+            for v in range(self.V):
+                ag.append(lambda commit, c=core, v=v: self._drain_enabled_and_step(c, v, commit))
+                ag.append(lambda commit, c=core, v=v: self._vcc_enabled_and_step(c, v, commit))
+        return ag
+
+    def finished(self):
+        for c in self.cores:
+            if not c.vmc.halted or any(not s.halted for s in c.vccs) or any(r is not None for r in c.vcc_run):
+                return False
+            if any(c.ldu) or any(c.stu) or any(c.c2m) or any(c.mailbox):
+                return False
+        return True
+
+    def run(self, schedule="program", seed=0, max_steps=10**9):
+        """Run to completion.  Raises DeadlockError when nothing is enabled before the end."""
+        agents = self._agents()
+        rng = np.random.default_rng(seed)
+        n = len(agents)
+        while not self.finished():
+            if self.steps >= max_steps:
+                raise RuntimeError("step limit")
+            if schedule == "program":
+                # one sweep over the agents in a fixed order; every enabled one takes a step
+                progressed = 0
+                for i in range(n):
+                    if agents[i](True):
+                        progressed += 1
+                if not progressed:
+                    raise DeadlockError(self.describe())
+                self.steps += progressed - 1
+            else:
+                enabled = [i for i in range(n) if agents[i](False)]
+                if not enabled:
+                    raise DeadlockError(self.describe())
+                agents[enabled[int(rng.integers(len(enabled)))]](True)
+            self.steps += 1
+        self.check_final()
+        return self
+
+    def describe(self):
+        out = []
+        for c in self.cores:
+            if c.vmc.halted and all(s.halted for s in c.vccs):
+                continue
+            out.append("core %d: vmc pc %d mask %08x ldu %s stu %s m2c waiting %s" % (
+                c.idx, c.vmc.pc - c.vmc.begin, c.mask, [len(q) for q in c.ldu], [len(q) for q in c.stu],
+                [c.m2c_head[v] for v in range(self.V)]))
+        return "no enabled action; " + "; ".join(out[:8])
+
+    def check_final(self):
+        """Invariants at termination: every slot returned, every queue drained, pushes == pops."""
+        for c in self.cores:
+            if c.mask != 0:
+                raise ProgramError("core %d ends with slots still allocated: %08x" % (c.idx, c.mask))
+            for v in range(self.V):
+                if c.m2c[v]:
+                    raise ProgramError("m2c not drained")
+                st = c.stats
+                if st["m2c_push"][v] != st["m2c_pop"][v] or st["c2m_push"][v] != st["c2m_pop"][v]:
+                    raise ProgramError("queue pushes and pops differ")

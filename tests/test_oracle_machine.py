@@ -1,0 +1,281 @@
+"""Pins of the sequential interpreter of the decoupled abstract machine (oracle/uop_machine.py).
+
+The paper prints no worked example of the machine, so the interpreter is tied to what the
+paper and the mathematics fix: the result of a matvec program is the textbook product
+(Section 3); the machine is a FIFO dataflow network without cyclic dependencies
+(Section 4.3, "Dependency Resolving", "Avoiding Deadlock"), hence every legal schedule gives the
+same memory image and the same per-unit traces; the allocator returns the first contiguous free
+position (Section 4.3, "Virtual Memory Core"); in-order allocation that over-commits the slots
+deadlocks (Section 4.3, "Avoiding Deadlock"); dynamic addresses are the literal address plus an
+accumulator advanced by control uops (Section 5, "Dynamic address generation").
+"""
+import numpy as np
+import pytest
+
+from oracle import gemv_ref, uop_asm as A, uop_machine as UM
+
+
+def _run(p, tensors, schedule="program", seed=0, **kw):
+    w, sb, d = p.finish()
+    m = UM.Machine(w, sb, d, tensors, n_cores=p.n_cores, vcc_per_core=p.V, **kw)
+    return m.run(schedule, seed)
+
+
+def _inputs(rows, K, B, seed, ld=None):
+    rng = np.random.default_rng(seed)
+    ld = K if ld is None else ld
+    M = rng.standard_normal((rows, ld)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    return M, X, np.full((B, rows), np.nan, np.float32)
+
+
+def _check_result(M, X, Y, ld=None):
+    Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
+    # the interpreter accumulates in fp64 and rounds once to fp32 at the copy-out
+    assert np.all(np.abs(Y.astype(np.float64) - Yr) <= 6e-8 * np.abs(Yr) + 1e-12 * Ya + 1e-45)
+
+
+# ---- allocator -----------------------------------------------------------------------------------
+def test_first_fit_against_string_search_all_16bit_masks():
+    for n in (1, 2, 3, 4):
+        for mask in range(1 << 16):
+            s = format(mask, "016b")[::-1]                 # s[i] = bit i
+            assert UM.first_fit(mask, n, 16) == s.find("0" * n)
+
+
+def test_first_fit_sampled_32bit_masks_and_limits():
+    rng = np.random.default_rng(0)
+    masks = rng.integers(0, 1 << 32, 200000, dtype=np.uint64)
+    # mix in dense masks, where long runs are rare
+    masks[::2] |= rng.integers(0, 1 << 32, 100000, dtype=np.uint64)
+    for mask in masks[:60000]:
+        mask = int(mask)
+        for n in (1, 2, 4):
+            for n_slots in (32, 19):
+                s = format(mask, "032b")[::-1][:n_slots]
+                assert UM.first_fit(mask, n, n_slots) == s.find("0" * n)
+    assert UM.first_fit(0, 32, 32) == 0 and UM.first_fit(1, 32, 32) == -1
+    assert UM.first_fit(0b0110, 1, 4) == 0 and UM.first_fit(0b0111, 1, 4) == 3
+    assert UM.first_fit(0b0111, 2, 4) == -1          # no wrap-around
+
+
+# ---- word layout ----------------------------------------------------------------------------------
+def test_decode_inverts_the_assembler_field_by_field():
+    rng = np.random.default_rng(3)
+    for _ in range(2000):
+        f = dict(opcode=int(rng.integers(256)), flags=int(rng.integers(256)), vflow=int(rng.integers(16)),
+                 vcc=int(rng.integers(4)), acc=int(rng.integers(8)), nslots=int(rng.integers(64)),
+                 size=int(rng.integers(65536)), dep_id=int(rng.integers(65536)),
+                 imm=int(rng.integers(-(1 << 47), 1 << 47)), desc=int(rng.integers(256)),
+                 dep_count=int(rng.integers(256)))
+        u = UM.decode(A.word(**f))
+        assert {k: getattr(u, k) for k in f} == f
+    # extreme immediates
+    for imm in (-(1 << 47), (1 << 47) - 1, -1, 0, 1, 1 << 33, -(1 << 33) - 5):
+        assert UM.decode(A.word(A.ADD, imm=imm)).imm == imm
+
+
+# ---- result = textbook product -------------------------------------------------------------------
+@pytest.mark.parametrize("rows,K,B,R,Kt,slot,ncores", [
+    (16, 64, 1, 8, 64, 4096, 1),
+    (50, 200, 3, 8, 64, 4096, 3),        # ragged tail in rows and in K
+    (33, 100, 8, 4, 32, 1024, 2),
+    (7, 8, 2, 16, 128, 8192, 2),         # a single partial tile
+    (128, 128, 1, 8, 128, 4096, 4),
+])
+def test_dense_program_equals_gemv(rows, K, B, R, Kt, slot, ncores):
+    M, X, Y = _inputs(rows, K, B, seed=rows + K)
+    p = A.dense_matvec_program(rows, K, K, B, R, Kt, slot, ncores)
+    _run(p, [M, X, Y], slot_bytes=slot, n_slots=12)
+    _check_result(M, X, Y)
+
+
+def test_leading_dimension():
+    M, X, Y = _inputs(24, 40, 2, seed=9, ld=52)
+    p = A.dense_matvec_program(24, 40, 52, 2, 8, 16, 1024, 2)
+    _run(p, [M, X, Y], slot_bytes=1024, n_slots=8)
+    _check_result(M, X, Y, ld=52)
+
+
+def test_closed_forms_through_the_machine():
+    rows, K = 64, 256
+    M = np.repeat((np.arange(rows) % 1024).astype(np.float32)[:, None], K, axis=1)
+    X = np.ones((1, K), np.float32)
+    Y = np.zeros((1, rows), np.float32)
+    _run(A.dense_matvec_program(rows, K, K, 1, 8, 64, 2048, 3), [M, X, Y], slot_bytes=2048, n_slots=9)
+    assert np.array_equal(Y[0], K * (np.arange(rows) % 1024).astype(np.float32))
+    # a single non-zero entry picks one term: any indexing slip moves or loses it
+    for (i, j) in [(0, 0), (63, 255), (17, 130)]:
+        M = np.zeros((rows, K), np.float32)
+        M[i, j] = 2.0
+        X = np.arange(1, K + 1, dtype=np.float32)[None, :]
+        Y = np.full((1, rows), np.nan, np.float32)
+        _run(A.dense_matvec_program(rows, K, K, 1, 8, 64, 2048, 3), [M, X, Y], slot_bytes=2048, n_slots=9)
+        exp = np.zeros(rows, np.float32)
+        exp[i] = 2.0 * (j + 1)
+        assert np.array_equal(Y[0], exp)
+
+
+# ---- determinacy under every legal schedule -------------------------------------------------------
+def test_every_schedule_gives_the_same_image_and_traces():
+    rows, K, B = 40, 96, 2
+    M, X, _ = _inputs(rows, K, B, seed=4)
+    p = A.dense_matvec_program(rows, K, K, B, 8, 32, 1024, 2)
+    ref = None
+    for i in range(101):
+        Y = np.full((B, rows), np.nan, np.float32)
+        m = _run(p, [M, X, Y], "program" if i == 0 else "random", seed=i, slot_bytes=1024, n_slots=6)
+        got = (Y.tobytes(), m.trace_vmc, m.trace_vcc)
+        if ref is None:
+            ref = got
+        assert got == ref
+    _check_result(M, X, Y)
+
+
+def test_allocation_log_lowest_feasible_and_never_overlapping():
+    M, X, Y = _inputs(64, 128, 2, seed=5)
+    p = A.dense_matvec_program(64, 128, 128, 2, 8, 32, 1024, 2)
+    for seed in range(5):
+        m = _run(p, [M, X, Y], "random", seed=seed, slot_bytes=1024, n_slots=7)
+        for core in range(2):
+            assert m.alloc_log[core]
+            for before, n, pos in m.alloc_log[core]:
+                s = format(before, "032b")[::-1][:7]
+                assert pos == s.find("0" * n) and pos >= 0
+            assert m.cores[core].mask == 0 and 1 <= m.cores[core].peak_slots <= 7
+
+
+# ---- dynamic address generation -------------------------------------------------------------------
+def test_looped_program_trace_is_the_arithmetic_progression():
+    rows, K, B, R, Kt, ncores = 64, 96, 2, 4, 32, 2
+    M, X, Y = _inputs(rows, K, B, seed=6)
+    p = A.looped_matvec_program(rows, K, K, B, R, Kt, 1024, ncores)
+    m = _run(p, [M, X, Y], slot_bytes=1024, n_slots=6)
+    _check_result(M, X, Y)
+    nk, per = K // Kt, rows // R // (ncores * 2)
+    for core in range(ncores):
+        exp = []
+        for v in range(2):
+            first = (core * 2 + v) * per
+            for rb in range(first, first + per):
+                for kt in range(nk):
+                    exp.append((A.LOAD, 0, (rb * R * K + kt * Kt) * 4, R))     # desc 0: matrix
+                    exp.append((A.LOAD, 1, kt * Kt * 4, B))                    # desc 1: vector
+                exp.append((A.STORE, 2, rb * R * 4, B))                        # desc 2: result
+        got = [(op, d, off, n) for (_pc, op, d, off, n) in m.trace_vmc[core]]
+        assert got == exp
+    # the per-uop program counters repeat with the loop body: only 3 distinct memory uops per compute core
+    assert len({pc for (pc, *_r) in m.trace_vmc[0]}) == 6
+
+
+def test_looped_and_literal_programs_touch_the_same_addresses():
+    rows, K, B, R, Kt, ncores = 32, 64, 1, 4, 16, 2
+    M, X, Y1 = _inputs(rows, K, B, seed=7)
+    Y2 = Y1.copy()
+    a = _run(A.looped_matvec_program(rows, K, K, B, R, Kt, 256, ncores), [M, X, Y1], slot_bytes=256, n_slots=6)
+    b = _run(A.dense_matvec_program(rows, K, K, B, R, Kt, 256, ncores), [M, X, Y2], slot_bytes=256, n_slots=6)
+    assert Y1.tobytes() == Y2.tobytes()
+    strip = lambda tr: sorted((op, off, n) for (_pc, op, _d, off, n) in tr)
+    assert sorted(sum((strip(t) for t in a.trace_vmc), [])) == sorted(sum((strip(t) for t in b.trace_vmc), []))
+
+
+def test_control_uops():
+    p = A.Program(1, 2)
+    vm = p.vmc(0)
+    vm += [A.word(A.SET, acc=3, imm=-5), A.word(A.LOOP, imm=3), A.word(A.LOOP, imm=4), A.word(A.ADD, acc=1, imm=10),
+           A.word(A.REPEAT, acc=2, imm=1), A.word(A.REPEAT, acc=3, imm=100)]
+    w, sb, d = p.finish()
+    m = UM.Machine(w, sb, d, [], n_cores=1).run()
+    acc = m.cores[0].vmc.acc
+    assert acc[1] == 120 and acc[2] == 12 and acc[3] == 295 and acc[0] == 0
+    for bad in ([A.word(A.REPEAT)], [A.word(A.LOOP, imm=2), A.word(A.HALT)], [A.word(A.LOOP, imm=0)],
+                [A.word(A.LOOP, imm=1)] * 5, [A.word(A.MATVEC)]):
+        p = A.Program(1, 2)
+        p.vmc(0).extend(bad)
+        w, sb, d = p.finish()
+        with pytest.raises(UM.ProgramError):
+            UM.Machine(w, sb, d, [], n_cores=1).run()
+
+
+# ---- deadlock --------------------------------------------------------------------------------------
+def test_in_order_over_allocation_deadlocks():
+    # the matrix tile takes both slots of a two-slot pool; the vector tile that the compute core needs
+    # next can never be allocated, and the matrix tile is only returned after that vector tile was used
+    M, X, Y = _inputs(8, 64, 1, seed=8)
+    p = A.dense_matvec_program(8, 64, 64, 1, 8, 64, 1024, 1, vcc_per_core=1)     # matrix tile = 2 KB = 2 slots
+    w, sb, d = p.finish()
+    with pytest.raises(UM.DeadlockError):
+        UM.Machine(w, sb, d, [M, X, Y], n_cores=1, vcc_per_core=1, slot_bytes=1024, n_slots=2).run()
+    for seed in range(10):                   # one more slot and every schedule completes
+        UM.Machine(w, sb, d, [M, X, Y], n_cores=1, vcc_per_core=1, slot_bytes=1024, n_slots=3).run("random", seed)
+    _check_result(M, X, Y)
+
+
+def test_wrong_send_order_is_rejected_by_the_compute_uop():
+    # m2c delivers in program order of the send uops; two matrix tiles in a row break the listing's a, b, a, b
+    M, X, Y = _inputs(8, 64, 1, seed=8)
+    p = A.Program(1, 1)
+    dm, dx, dy = p.desc(0, 8, 128, 128, 256), p.desc(1, 1, 128, 128, 256), p.desc(2, 1, 32, 32, 32)
+    p.vmc(0).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=1, size=8, imm=0, desc=dm),
+                     A.word(A.LOAD, A.F_SEND, vflow=0, nslots=1, size=8, imm=128, desc=dm),
+                     A.word(A.LOAD, A.F_SEND, vflow=1, nslots=1, size=1, imm=0, desc=dx),
+                     A.word(A.LOAD, A.F_SEND, vflow=1, nslots=1, size=1, imm=128, desc=dx),
+                     A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=2, nslots=1, size=1, imm=0, desc=dy)])
+    p.vcc(0, 0).append(A.word(A.MATVEC, size=2, imm=A.matvec_imm(1, 8, 8)))
+    w, sb, d = p.finish()
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(w, sb, d, [M, X, Y], n_cores=1, vcc_per_core=1, slot_bytes=1024, n_slots=5).run()
+
+
+def test_missing_send_deadlocks():
+    M, X, Y = _inputs(8, 32, 1, seed=10)
+    p = A.dense_matvec_program(8, 32, 32, 1, 8, 32, 1024, 1, vcc_per_core=1)
+    vm = p.vmc(0)
+    u = UM.decode(vm[1])
+    vm[1] = A.word(A.LOAD, 0, vflow=u.vflow, vcc=u.vcc, nslots=u.nslots, size=u.size, imm=u.imm, desc=u.desc)
+    w, sb, d = p.finish()
+    with pytest.raises(UM.DeadlockError):
+        UM.Machine(w, sb, d, [M, X, Y], n_cores=1, vcc_per_core=1, slot_bytes=1024, n_slots=4).run()
+
+
+# ---- depId between memory cores --------------------------------------------------------------------
+def test_dep_id_orders_a_store_before_a_dependent_load():
+    # core 0 computes t = M1 x and signals depId 5; core 1 loads t with load.dep and computes y = M2 t
+    rng = np.random.default_rng(12)
+    M1 = rng.standard_normal((8, 16)).astype(np.float32)
+    M2 = rng.standard_normal((4, 8)).astype(np.float32)
+    x = rng.standard_normal((1, 16)).astype(np.float32)
+    for seed in range(20):
+        t = np.full((1, 8), np.nan, np.float32)
+        y = np.full((1, 4), np.nan, np.float32)
+        p = A.Program(2, 1)
+        d_m1, d_x, d_t = p.desc(0, 8, 64, 64, 64), p.desc(1, 1, 64, 64, 64), p.desc(2, 1, 32, 32, 32)
+        d_m2, d_t_in, d_y = p.desc(3, 4, 32, 32, 32), p.desc(2, 1, 32, 32, 32), p.desc(4, 1, 16, 16, 16)
+        p.vmc(0).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=1, size=8, desc=d_m1),
+                         A.word(A.LOAD, A.F_SEND, vflow=1, nslots=1, size=1, desc=d_x),
+                         A.word(A.STORE, A.F_SEND | A.F_RECV | A.F_DEP_SEND, vflow=2, nslots=1, size=1, desc=d_t,
+                                dep_id=5)])
+        p.vcc(0, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 8, 4)))
+        p.vmc(1).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=1, size=4, desc=d_m2),
+                         A.word(A.LOAD, A.F_SEND | A.F_DEP_RECV, vflow=1, nslots=1, size=1, desc=d_t_in, dep_id=5,
+                                dep_count=1),
+                         A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=2, nslots=1, size=1, desc=d_y)])
+        p.vcc(1, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 4, 2)))
+        w, sb, d = p.finish()
+        m = UM.Machine(w, sb, d, [M1, x, t, M2, y], n_cores=2, vcc_per_core=1, slot_bytes=512, n_slots=4)
+        m.run("random", seed)
+        t_ref, _ = gemv_ref.gemv_dense(M1, x)
+        assert np.array_equal(t, t_ref.astype(np.float32))
+        y_ref, _ = gemv_ref.gemv_dense(M2, t)
+        assert np.array_equal(y, y_ref.astype(np.float32))
+        assert m.dep[5] == 1
+
+
+def test_paper_deployment_constants_are_the_defaults():
+    # Table 1 caption and Section 4.3: one VMC and two VCCs per core, 8 KB slots, a 32-bit slot mask
+    import inspect
+    sig = inspect.signature(UM.Machine.__init__).parameters
+    assert sig["vcc_per_core"].default == 2 and sig["slot_bytes"].default == 8192
+    with pytest.raises(AssertionError):
+        UM.Machine(np.zeros((1, 4), np.uint32), np.zeros(4, np.uint32), np.zeros((1, 8), np.uint32), [],
+                   n_cores=1, n_slots=33)
