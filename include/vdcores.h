@@ -1,0 +1,158 @@
+/*
+ * vdcores.h — C ABI of the VDCores executor for AMD MI355X (gfx950).
+ *
+ * The library runs micro-operation (uop) graphs on persistent "virtual cores":
+ * one virtual memory core (VMC) and two virtual compute cores (VCC) per compute
+ * unit, connected by the dependency queues m2c / c2m, as described in Sections
+ * 3 ("Overview"), 4.1 ("Decoupled Model") and 4.3 ("GPU Executor") of the
+ * VDCores paper.  The operator it ships is the paper's running example, the
+ * tiled matrix-vector product O = M @ N (Section 3, "Execution Example";
+ * Section 4.1, listing of the `matvec` compute uop).
+ *
+ * Conventions for every entry point
+ *   - return value: 0 (VDC_OK) or a negative VDC_E* code; no exceptions, no
+ *     global state; vdc_strerror() names a code.
+ *   - "device" pointers are HIP device memory owned by the caller; the library
+ *     never allocates, frees or copies the caller's tensors.  "host" pointers
+ *     are ordinary memory read during the call only.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     vdc_run / vdc_matvec* enqueue work and return without synchronising.
+ *   - outputs are overwritten, never accumulated into.
+ *   - one executor must not be used from two host threads at once, and two
+ *     runs of one executor must not overlap on the device (they share the
+ *     depId table and the status buffer): enqueue them on one stream.
+ */
+#ifndef VDCORES_H
+#define VDCORES_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    VDC_OK = 0,
+    VDC_EINVAL = -1,    /* null or misaligned pointer, non-positive shape, unsupported size          */
+    VDC_ENOMEM = -2,    /* host or device allocation failed                                        */
+    VDC_EPROGRAM = -3,  /* the uop program is malformed (found by host-side validation)            */
+    VDC_EDEVICE = -4,   /* a HIP call failed                                                       */
+    VDC_EDEADLOCK = -5, /* the device watchdog fired: some unit waited longer than the spin limit  */
+    VDC_ELEAK = -6      /* a run ended with local-memory slots still allocated                      */
+};
+
+typedef struct vdc_executor vdc_executor; /* opaque, library-owned */
+typedef struct vdc_program vdc_program;   /* opaque, library-owned device copy of a uop graph */
+
+/* Deployment constants of the virtual cores.  Zero in any field selects the default, which is the
+ * paper's deployment (Table 1 caption: 1 VMC + 2 VCCs per SM/CU, 8 KB slots; Section 4.3: 128
+ * threads per execution unit, 32-bit slot mask). */
+typedef struct {
+    int32_t device;         /* HIP device ordinal; -1 => host-only executor (see vdc_create)           */
+    int32_t n_cores;        /* virtual-core triples (workgroups); 0 => one per compute unit           */
+    int32_t vcc_per_core;   /* 1 or 2; default 2                                                      */
+    int32_t threads_per_eu; /* must be 128 (two wave64) or 0                                          */
+    int32_t slot_bytes;     /* local-memory slot size, power of two, 1024..16384; default 8192        */
+    int32_t n_slots;        /* slots per core, 1..32; default = as many as fit in the CU's LDS        */
+    int32_t n_ldu;          /* load units per VMC, 1..2; default 2                                    */
+    int32_t n_stu;          /* store units per VMC, must be 1 or 0 (=1)                               */
+    int32_t n_dep_ids;      /* size of the global depId table; default 1024                           */
+    int32_t watchdog_spins; /* polls before a waiting unit reports VDC_EDEADLOCK; default 1<<22       */
+    int32_t tile_rows;      /* tuning knob of the matvec tiler: rows per matrix tile; 0 => automatic  */
+    int32_t reserved[5];    /* must be zero                                                           */
+} vdc_config;
+
+/* Create the executor on cfg->device (Section 4.3: the cores every run launches once as a persistent
+ * kernel).  cfg may be NULL (all defaults).  *out is valid only when VDC_OK is returned.
+ * With cfg->device == -1 the executor is host-only: it touches no GPU, assumes 160 KB of local memory and
+ * cfg->n_cores cores (default 256), and serves only vdc_matvec_program, vdc_program_validate, vdc_get_config
+ * and vdc_destroy; every entry point that needs the device returns VDC_EINVAL. */
+int vdc_create(vdc_executor **out, const vdc_config *cfg);
+
+/* Destroy the executor and every program created from it.  Waits for the device first. */
+int vdc_destroy(vdc_executor *ex);
+
+/* Fill *cfg with the values in effect (defaults resolved, n_cores = the CU count, ...). */
+int vdc_get_config(const vdc_executor *ex, vdc_config *cfg);
+
+/* ---- low level: uop graphs (Section 3: "uop streams for virtual cores ... connected by dependency edges") ----
+ *
+ * uops          host, n_uops words of 16 bytes (layout: csrc/vdc_isa.h)
+ * stream_begin  host, n_cores*(1+vcc_per_core)+1 offsets into uops; stream index = core*(1+V) for the
+ *               VMC of `core`, core*(1+V)+1+v for its VCC v; every stream ends with HALT
+ * descs         host, n_descs descriptors of 32 bytes
+ * tensor_bytes  host, n_tensors sizes in bytes of the tensors the program addresses (ids 0..n_tensors-1,
+ *               at most 8); every memory uop is checked against them
+ * The program is validated by walking every stream's control flow on the host: opcodes, loop nesting,
+ * tensor bounds and alignment of every executed memory uop, unit and depId ranges, matvec geometry, and
+ * the in-order slot demand of the paper's generator-side deadlock check (Section 4.2, "Dependency Graph
+ * Lowering").  Anything wrong returns VDC_EPROGRAM and no program. */
+int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const uint32_t *stream_begin,
+                       const void *descs, int32_t n_descs, const int64_t *tensor_bytes, int32_t n_tensors,
+                       vdc_program **out);
+int vdc_program_destroy(vdc_program *prog);
+
+/* The validation of vdc_program_create alone (no device copy is made).  msg (host, may be NULL) receives a
+ * NUL-terminated reason of at most msg_cap bytes when the result is VDC_EPROGRAM. */
+int vdc_program_validate(vdc_executor *ex, const void *uops, int64_t n_uops, const uint32_t *stream_begin,
+                         const void *descs, int32_t n_descs, const int64_t *tensor_bytes, int32_t n_tensors,
+                         char *msg, int32_t msg_cap);
+
+/* Run a program (Section 3: submit the uop graph to the on-GPU executors, which run until it finishes).
+ * tensor_bases: host array of n_tensors device pointers, each 16-byte aligned and at least as large as
+ * declared at vdc_program_create.  Asynchronous on hip_stream. */
+int vdc_run(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors,
+            void *hip_stream);
+
+/* As vdc_run, and every unit also records the uops it executes, in its own program order:
+ * trace (device, caller-owned): n_streams * trace_cap records of 4 x uint32
+ *        { pc relative to the stream, opcode | desc<<8 | size<<16, low, high }
+ *        (low, high) = effective byte offset into the tensor for LOAD/STORE, the uop's imm for MATVEC;
+ * trace_count (device): n_streams uint32, the number of records each stream produced (records past
+ *        trace_cap are counted but not written).  Only memory and compute uops are recorded. */
+int vdc_run_traced(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors,
+                   uint32_t *trace, uint32_t *trace_count, int32_t trace_cap, void *hip_stream);
+
+/* Wait for hip_stream, then report what the cores wrote into the status buffer: VDC_OK, or the first
+ * error a core raised (VDC_EDEADLOCK, VDC_ELEAK, VDC_EPROGRAM for a geometry the device rejected).
+ * info (host, may be NULL) receives 4 words: core, role, stream pc, detail.  Clears the status. */
+int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info);
+
+/* ---- high level: the matvec operator (Section 3, O = M @ N; tiled "along the M dimension") ----
+ *
+ * Y[b][i] = sum_j M[i*ld + j] * X[b*K + j],  0 <= i < rows, 0 <= b < B, fp32.
+ * M, X, Y: device.  K and ld multiples of 4 (rows are moved in 16-byte units), ld >= K, 1 <= B <= 8,
+ * M and X 16-byte aligned, Y 4-byte aligned.  tile_bytes = size of one matrix tile (the paper's I/O
+ * block): 2048, 4096, 8192 or 16384.  The host tiler turns the call into a uop graph (cached per
+ * shape), validates it and runs it.  Asynchronous on hip_stream. */
+int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
+               int32_t B, int32_t tile_bytes, void *hip_stream);
+
+/* Ragged batch: n_seg independent row segments stacked in M (rows row_off[s] .. row_off[s+1]-1, K floats
+ * each, contiguous); segment s is multiplied by its own vector X[s][0..K).  Y[i] for every stacked row.
+ * row_off: host, n_seg+1 non-decreasing offsets starting at 0.  The tiler splits long segments over the
+ * cores (the paper's adaptive scheduling, Section 4.2) so that every core gets the same number of bytes. */
+int vdc_matvec_ragged(vdc_executor *ex, const float *M, const int64_t *row_off, int32_t n_seg, int64_t K,
+                      const float *X, float *Y, int32_t tile_bytes, void *hip_stream);
+
+/* Emit the uop graph vdc_matvec / vdc_matvec_ragged would run, without running it (for tests and for
+ * inspection).  Any output pointer may be NULL; counts are always written.  Buffers are host memory with
+ * capacities *n_uops (16-byte words), *n_descs (32-byte descriptors) on entry; on return the needed counts.
+ * stream_begin must hold n_cores*(1+vcc_per_core)+1 entries.  Returns VDC_EINVAL if a buffer is too small
+ * (counts are still written).  row_off == NULL selects the dense operator (n_seg ignored). */
+int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
+                       const int64_t *row_off, int32_t n_seg, void *uops, int64_t *n_uops,
+                       uint32_t *stream_begin, void *descs, int32_t *n_descs);
+
+/* Run the SIMT slot allocator of the VMC (Section 4.3: every allocator thread probes from its own position,
+ * a wave vote takes the first) on n independent (mask, nslots) requests with a pool of n_slots slots:
+ * pos[i] = the lowest start of nslots[i] contiguous clear bits of masks[i], or -1.  masks, nslots, pos: device. */
+int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos,
+                    int32_t n, void *hip_stream);
+
+const char *vdc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VDCORES_H */

@@ -1,0 +1,232 @@
+"""Python binding of libvdcores.so (the C ABI declared in include/vdcores.h).
+
+Argument marshalling only: every step of the hot path runs in the library's HIP kernels.
+PyTorch is used by callers for device memory and streams; this module never computes.
+If the library has not been built, importing the binding's functions fails loudly; there is
+no CPU fallback.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvdcores.so")
+
+VDC_OK, VDC_EINVAL, VDC_ENOMEM, VDC_EPROGRAM, VDC_EDEVICE, VDC_EDEADLOCK, VDC_ELEAK = 0, -1, -2, -3, -4, -5, -6
+
+
+class VdcError(RuntimeError):
+    def __init__(self, code, what=""):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (what, strerror(code), code))
+
+
+class vdc_config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "device", "n_cores", "vcc_per_core", "threads_per_eu", "slot_bytes", "n_slots", "n_ldu", "n_stu",
+        "n_dep_ids", "watchdog_spins", "tile_rows")] + [("reserved", ctypes.c_int32 * 5)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built (python -m paper_2605_03190_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libvdcores.so is not built: run `python paper_2605_03190_amd/build.py` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        sig = {
+            "vdc_create": [pp, ctypes.POINTER(vdc_config)],
+            "vdc_destroy": [vp],
+            "vdc_get_config": [vp, ctypes.POINTER(vdc_config)],
+            "vdc_program_create": [vp, vp, i64, vp, vp, i32, vp, i32, pp],
+            "vdc_program_validate": [vp, vp, i64, vp, vp, i32, vp, i32, ctypes.c_char_p, i32],
+            "vdc_program_destroy": [vp],
+            "vdc_run": [vp, vp, vp, i32, vp],
+            "vdc_run_traced": [vp, vp, vp, i32, vp, vp, i32, vp],
+            "vdc_sync_status": [vp, vp, vp],
+            "vdc_matvec": [vp, vp, i64, i64, i64, vp, vp, i32, i32, vp],
+            "vdc_matvec_ragged": [vp, vp, vp, i32, i64, vp, vp, i32, vp],
+            "vdc_matvec_program": [vp, i64, i64, i64, i32, i32, vp, i32, vp, ctypes.POINTER(i64), vp, vp,
+                                   ctypes.POINTER(i32)],
+            "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
+        }
+        for name, args in sig.items():
+            f = getattr(L, name)
+            f.argtypes = args
+            f.restype = ctypes.c_int
+        L.vdc_strerror.argtypes = [ctypes.c_int]
+        L.vdc_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
+           "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
+           "vdc_matvec_program", "vdc_debug_alloc", "vdc_strerror"]
+
+
+def strerror(code):
+    return lib().vdc_strerror(int(code)).decode()
+
+
+def _check(rc, what):
+    if rc != VDC_OK:
+        raise VdcError(rc, what)
+
+
+def _np_ptr(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _stream_ptr(stream):
+    """hipStream_t of a torch stream (None: torch's current stream)."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(getattr(stream, "cuda_stream", stream) or 0)
+
+
+class Program:
+    def __init__(self, ex, handle):
+        self.ex, self.handle = ex, handle
+
+    def destroy(self):
+        if self.handle:
+            _check(lib().vdc_program_destroy(self.handle), "vdc_program_destroy")
+            self.handle = None
+
+
+class Executor:
+    """vdc_create / vdc_destroy and the calls that take the executor."""
+
+    def __init__(self, **cfg):
+        c = vdc_config()
+        for k, v in cfg.items():
+            setattr(c, k, v)
+        h = ctypes.c_void_p()
+        _check(lib().vdc_create(ctypes.byref(h), ctypes.byref(c)), "vdc_create")
+        self.handle = h
+        got = vdc_config()
+        _check(lib().vdc_get_config(self.handle, ctypes.byref(got)), "vdc_get_config")
+        self.cfg = got
+
+    def destroy(self):
+        if self.handle:
+            _check(lib().vdc_destroy(self.handle), "vdc_destroy")
+            self.handle = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.destroy()
+
+    @property
+    def n_streams(self):
+        return self.cfg.n_cores * (1 + self.cfg.vcc_per_core)
+
+    # ---- low level -------------------------------------------------------------------------------
+    @staticmethod
+    def _prog_arrays(words, stream_begin, descs, tensor_bytes):
+        words = np.ascontiguousarray(words, dtype=np.uint32).reshape(-1, 4)
+        sb = np.ascontiguousarray(stream_begin, dtype=np.uint32)
+        descs = np.ascontiguousarray(descs, dtype=np.uint32).reshape(-1, 8)
+        tb = np.ascontiguousarray(tensor_bytes, dtype=np.int64)
+        return words, sb, descs, tb
+
+    def program_create(self, words, stream_begin, descs, tensor_bytes):
+        words, sb, descs, tb = self._prog_arrays(words, stream_begin, descs, tensor_bytes)
+        if len(sb) != self.n_streams + 1:
+            raise VdcError(VDC_EINVAL, "vdc_program_create (stream_begin length)")
+        h = ctypes.c_void_p()
+        _check(lib().vdc_program_create(self.handle, _np_ptr(words), len(words), _np_ptr(sb), _np_ptr(descs), len(descs),
+                                        _np_ptr(tb), len(tb), ctypes.byref(h)), "vdc_program_create")
+        return Program(self, h)
+
+    def program_validate(self, words, stream_begin, descs, tensor_bytes):
+        """Returns (code, message)."""
+        words, sb, descs, tb = self._prog_arrays(words, stream_begin, descs, tensor_bytes)
+        if len(sb) != self.n_streams + 1:
+            return VDC_EINVAL, "stream_begin length"
+        buf = ctypes.create_string_buffer(256)
+        rc = lib().vdc_program_validate(self.handle, _np_ptr(words), len(words), _np_ptr(sb), _np_ptr(descs), len(descs),
+                                        _np_ptr(tb), len(tb), buf, 256)
+        return rc, buf.value.decode()
+
+    def run(self, prog, tensors, stream=None, trace_cap=0):
+        """tensors: torch CUDA tensors.  With trace_cap > 0 returns (trace, trace_count) device tensors."""
+        import torch
+        bases = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+        if trace_cap:
+            trace = torch.zeros((self.n_streams, trace_cap, 4), dtype=torch.int32, device=tensors[0].device)
+            count = torch.zeros((self.n_streams,), dtype=torch.int32, device=tensors[0].device)
+            _check(lib().vdc_run_traced(self.handle, prog.handle, bases, len(tensors), trace.data_ptr(), count.data_ptr(),
+                                        trace_cap, _stream_ptr(stream)), "vdc_run_traced")
+            return trace, count
+        _check(lib().vdc_run(self.handle, prog.handle, bases, len(tensors), _stream_ptr(stream)), "vdc_run")
+        return None
+
+    def sync_status(self, stream=None):
+        """Waits for the stream; returns (code, info[4])."""
+        info = (ctypes.c_uint32 * 4)()
+        rc = lib().vdc_sync_status(self.handle, _stream_ptr(stream), info)
+        return rc, list(info)
+
+    def check(self, stream=None):
+        rc, info = self.sync_status(stream)
+        if rc != VDC_OK:
+            raise VdcError(rc, "device run (core %d role %#x pc %d detail %#x)" % tuple(info))
+
+    # ---- high level ------------------------------------------------------------------------------
+    def matvec(self, M, X, Y, tile_bytes, K=None, stream=None):
+        """Y[b][i] = sum_j M[i][j] X[b][j].  M: [rows, ld] fp32 CUDA (K <= ld columns used), X: [B, K], Y: [B, rows]."""
+        rows, ld = M.shape
+        B, Kx = X.shape
+        K = Kx if K is None else K
+        assert M.is_cuda and X.is_cuda and Y.is_cuda and M.is_contiguous() and X.is_contiguous() and Y.is_contiguous()
+        assert M.dtype == X.dtype == Y.dtype and str(M.dtype) == "torch.float32"
+        assert Kx == K and tuple(Y.shape) == (B, rows)
+        _check(lib().vdc_matvec(self.handle, M.data_ptr(), rows, K, ld, X.data_ptr(), Y.data_ptr(), B, tile_bytes,
+                                _stream_ptr(stream)), "vdc_matvec")
+
+    def matvec_ragged(self, M, row_off, X, Y, tile_bytes, stream=None):
+        """Segment s = rows row_off[s]..row_off[s+1]-1 of M ([sum rows, K]) times X[s] ([n_seg, K]); Y: [sum rows]."""
+        row_off = np.ascontiguousarray(row_off, dtype=np.int64)
+        n_seg, K = X.shape
+        assert M.is_cuda and X.is_cuda and Y.is_cuda and M.is_contiguous() and X.is_contiguous() and Y.is_contiguous()
+        assert str(M.dtype) == "torch.float32" and M.shape[1] == K and len(row_off) == n_seg + 1
+        assert int(row_off[-1]) == M.shape[0] == Y.numel()
+        _check(lib().vdc_matvec_ragged(self.handle, M.data_ptr(), _np_ptr(row_off), n_seg, K, X.data_ptr(), Y.data_ptr(),
+                                       tile_bytes, _stream_ptr(stream)), "vdc_matvec_ragged")
+
+    def matvec_program(self, rows, K, ld, B, tile_bytes, row_off=None):
+        """The uop graph the matvec operator would run: (words[n,4], stream_begin, descs[n,8]) as numpy uint32."""
+        n_w, n_d = ctypes.c_int64(0), ctypes.c_int32(0)
+        ro = None if row_off is None else np.ascontiguousarray(row_off, dtype=np.int64)
+        ro_p = None if ro is None else _np_ptr(ro)
+        n_seg = 0 if ro is None else len(ro) - 1
+        rc = lib().vdc_matvec_program(self.handle, rows, K, ld, B, tile_bytes, ro_p, n_seg, None, ctypes.byref(n_w), None,
+                                      None, ctypes.byref(n_d))
+        _check(rc, "vdc_matvec_program (sizing)")
+        words = np.zeros((n_w.value, 4), dtype=np.uint32)
+        descs = np.zeros((n_d.value, 8), dtype=np.uint32)
+        sb = np.zeros(self.n_streams + 1, dtype=np.uint32)
+        rc = lib().vdc_matvec_program(self.handle, rows, K, ld, B, tile_bytes, ro_p, n_seg, _np_ptr(words), ctypes.byref(n_w),
+                                      _np_ptr(sb), _np_ptr(descs), ctypes.byref(n_d))
+        _check(rc, "vdc_matvec_program")
+        return words, sb, descs
+
+    def debug_alloc(self, masks, nslots, n_slots, stream=None):
+        """masks (int32/uint32 CUDA tensor), nslots (int32 CUDA tensor) -> positions (int32 CUDA tensor)."""
+        import torch
+        pos = torch.empty(masks.numel(), dtype=torch.int32, device=masks.device)
+        _check(lib().vdc_debug_alloc(self.handle, masks.data_ptr(), nslots.data_ptr(), n_slots, pos.data_ptr(),
+                                     masks.numel(), _stream_ptr(stream)), "vdc_debug_alloc")
+        return pos

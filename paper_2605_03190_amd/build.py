@@ -1,0 +1,30 @@
+"""Build step of the HIP extension: hipcc -> libvdcores.so next to this file (gfx950 only)."""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SO = os.path.join(HERE, "libvdcores.so")
+SOURCES = [os.path.join(HERE, "csrc", "vdc_kernel.hip"), os.path.join(HERE, "csrc", "vdc_host.cpp")]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
+         # packed fp32 arithmetic is kept out of the device code
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wno-unused-command-line-argument"]
+
+
+def build(verbose=False):
+    cmd = ["/opt/rocm/bin/hipcc"] + FLAGS + SOURCES + ["-o", SO]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in r.stdout.splitlines()
+                    if "packed-fp32-ops" not in l)      # the host pass does not know the device feature
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if verbose and out.strip():
+        print(out)
+    return SO
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,840 @@
+// Host side of the library: executor life cycle, program validation (a data-free walk of the whole uop
+// graph, the generator-side check of Section 4.2 "Dependency Graph Lowering"), the matvec tiler (the slice of
+// the uop generator of Section 4.2 that the matvec operator needs) and the C ABI declared in vdcores.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <deque>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/vdcores.h"
+#include "vdc_isa.h"
+#include "vdc_kernel.h"
+
+using namespace vdc;
+
+struct vdc_program {
+    vdc_executor *ex = nullptr;
+    Word *d_words = nullptr;
+    uint32_t *d_stream_begin = nullptr;
+    Desc *d_descs = nullptr;
+    int32_t n_tensors = 0;
+    int64_t tensor_bytes[kMaxTensors] = {0};
+    bool uses_dep = false;
+    uint32_t max_dep_id = 0;
+};
+
+struct MatvecKey {
+    int64_t rows, K, ld;
+    int32_t B, tile_bytes, n_seg;
+    std::vector<int64_t> row_off;
+    bool operator==(const MatvecKey &o) const {
+        return rows == o.rows && K == o.K && ld == o.ld && B == o.B && tile_bytes == o.tile_bytes && n_seg == o.n_seg &&
+               row_off == o.row_off;
+    }
+};
+
+struct vdc_executor {
+    vdc_config cfg{};
+    int cu_count = 0;
+    size_t lds_limit = 0;
+    uint32_t *d_dep = nullptr;
+    uint32_t *d_status = nullptr;
+    uint32_t *h_status = nullptr;  // pinned
+    std::vector<vdc_program *> programs;
+    std::vector<std::pair<MatvecKey, vdc_program *>> matvec_cache;
+};
+
+namespace {
+
+int hip_fail(hipError_t) { return VDC_EDEVICE; }
+#define HIP_TRY(x)                                \
+    do {                                          \
+        hipError_t e_ = (x);                      \
+        if (e_ != hipSuccess) return hip_fail(e_); \
+    } while (0)
+
+bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// ------------------------------------------------------------------------------------------------------------
+// Validation: run the abstract machine without data.  Every core's front end walks its stream in program order,
+// allocating slots from the same first-fit mask as the device; loads complete at once; a compute core consumes
+// its tickets in order and returns regions; a store completes when its region comes back.  Cores take turns
+// until all streams are at HALT.  A full sweep without progress is a deadlock: in-order execution cannot finish,
+// which is the situation the paper's generator must exclude before a program reaches the device.
+// ------------------------------------------------------------------------------------------------------------
+struct SeqH {
+    uint32_t pc = 0, begin = 0, end = 0;
+    std::vector<std::pair<uint32_t, uint32_t>> loops;  // (start, trips left)
+    int64_t acc[kNumAcc] = {0};
+    bool halted = false;
+};
+
+struct SentMsg {
+    uint32_t slot, nslots, rows, row_bytes, box_rows, lds_pitch;
+    bool is_store;
+};
+
+struct VccH {
+    SeqH s;
+    std::deque<SentMsg> m2c;      // delivered, in ticket order (loads complete at once in this model)
+    // running MATVEC
+    bool in_uop = false;
+    uint32_t left = 0, B = 0, R = 0, lpr = 0;
+    int phase = 0;                // 0: expect a, 1: expect b, 2: expect out
+    SentMsg a{};
+};
+
+struct CoreH {
+    SeqH vmc;
+    std::vector<VccH> vcc;
+    uint32_t mask = 0;
+    std::deque<SentMsg> stores_waiting;  // STOREs whose region has not come back yet (only counted)
+};
+
+struct Validator {
+    const vdc_config &cfg;
+    const Word *words;
+    int64_t n_words;
+    const uint32_t *sb;
+    const Desc *descs;
+    int32_t n_descs;
+    const int64_t *tensor_bytes;
+    int32_t n_tensors;
+    std::string err;
+    bool uses_dep = false;
+    uint32_t max_dep = 0;
+    std::vector<uint32_t> dep;
+    int64_t steps = 0;
+
+    bool fail(const std::string &m) {
+        if (err.empty()) err = m;
+        return false;
+    }
+
+    int first_fit(uint32_t mask, uint32_t n) const {
+        for (int p = 0; p + (int)n <= cfg.n_slots; p++) {
+            uint64_t bits = ((n >= 64 ? ~0ull : ((1ull << n) - 1ull)) << p);
+            if (((uint64_t)mask & bits) == 0) return p;
+        }
+        return -1;
+    }
+
+    // control uops; returns 1 handled, 2 halt, 0 not control, -1 error
+    int control(SeqH &s, const Fields &f) {
+        switch (f.opcode) {
+            case OP_HALT:
+                if (!s.loops.empty()) { fail("HALT inside a loop"); return -1; }
+                s.halted = true;
+                return 2;
+            case OP_LOOP:
+                if (f.imm < 1 || f.imm > 0xFFFFFFFFll || (int)s.loops.size() >= kMaxLoopDepth) { fail("bad LOOP"); return -1; }
+                s.loops.push_back({s.pc + 1, (uint32_t)f.imm});
+                s.pc++;
+                return 1;
+            case OP_REPEAT:
+                if (s.loops.empty()) { fail("REPEAT without LOOP"); return -1; }
+                s.acc[f.acc] += f.imm;
+                if (--s.loops.back().second > 0) s.pc = s.loops.back().first;
+                else { s.loops.pop_back(); s.pc++; }
+                return 1;
+            case OP_ADD:
+                s.acc[f.acc] += f.imm;
+                s.pc++;
+                return 1;
+            case OP_SET:
+                s.acc[f.acc] = f.imm;
+                s.pc++;
+                return 1;
+            default:
+                return 0;
+        }
+    }
+
+    bool fetch(SeqH &s, Fields &f) {
+        if (s.pc >= s.end) return fail("stream runs past its end without HALT");
+        f = decode(words[s.pc]);
+        return true;
+    }
+
+    // one front-end step of core c; returns 1 progress, 0 blocked, -1 error
+    int cfu_step(CoreH &c) {
+        SeqH &s = c.vmc;
+        if (s.halted) return 0;
+        Fields f;
+        if (!fetch(s, f)) return -1;
+        int k = control(s, f);
+        if (k < 0) return -1;
+        if (k > 0) return 1;
+        if (f.opcode != OP_LOAD && f.opcode != OP_STORE) { fail("opcode not valid on a memory core"); return -1; }
+        if ((int)f.desc >= n_descs) { fail("descriptor index out of range"); return -1; }
+        const Desc &d = descs[f.desc];
+        const bool is_load = f.opcode == OP_LOAD;
+        const uint64_t gpitch = (uint64_t)d.gpitch_lo | ((uint64_t)d.gpitch_hi << 32);
+        if ((int)d.tensor >= n_tensors) { fail("tensor id out of range"); return -1; }
+        if (d.box_rows < 1 || d.box_rows > 65535 || d.lds_pitch < 4 || d.lds_pitch > 65535 || d.row_bytes < 4 ||
+            d.row_bytes > d.lds_pitch) { fail("bad descriptor box"); return -1; }
+        if (is_load ? (d.lds_pitch % 16 || d.row_bytes % 16 || gpitch % 16) : (d.lds_pitch % 4 || d.row_bytes % 4 || gpitch % 4)) {
+            fail("descriptor alignment"); return -1;
+        }
+        if (f.size < 1 || f.size > d.box_rows) { fail("rows exceed the descriptor box"); return -1; }
+        const uint64_t box_bytes = (uint64_t)d.box_rows * d.lds_pitch;
+        const uint32_t need = (uint32_t)((box_bytes + cfg.slot_bytes - 1) / cfg.slot_bytes);
+        if (f.nslots != need || need < 1 || (int)need > cfg.n_slots) { fail("nslots does not match the descriptor box"); return -1; }
+        if ((int)f.vcc >= cfg.vcc_per_core) { fail("vcc out of range"); return -1; }
+        if (is_load && !(f.flags & F_SEND)) { fail("LOAD without SEND would never be released"); return -1; }
+        if (!is_load && !(f.flags & F_RECV)) { fail("STORE without RECV has no data to write"); return -1; }
+        if (is_load && (f.flags & F_RECV)) { fail("LOAD with RECV is not defined"); return -1; }
+        if (f.flags & (F_DEP_SEND | F_DEP_RECV)) {
+            if ((int)f.dep_id >= cfg.n_dep_ids) { fail("depId out of range"); return -1; }
+            uses_dep = true;
+            max_dep = std::max(max_dep, f.dep_id);
+        }
+        const int64_t eff = f.imm + ((f.flags & F_DYNAMIC) ? s.acc[f.acc] : 0);
+        if (eff < 0 || (eff % (is_load ? 16 : 4)) != 0) { fail("effective address negative or misaligned"); return -1; }
+        const uint64_t last = (uint64_t)eff + (uint64_t)(f.size - 1) * gpitch + d.row_bytes;
+        if (last > (uint64_t)tensor_bytes[d.tensor]) { fail("memory uop reaches beyond its tensor"); return -1; }
+        // a DEP_RECV whose counter is not there yet blocks its unit, not the front end; in this in-order model the
+        // front end waits as well, which is conservative
+        if ((f.flags & F_DEP_RECV) && dep[f.dep_id] < std::max<uint32_t>(1u, f.dep_count)) return 0;
+        int slot = first_fit(c.mask, f.nslots);
+        if (slot < 0) return 0;
+        c.mask |= (uint32_t)(((f.nslots >= 32 ? 0xFFFFFFFFull : ((1ull << f.nslots) - 1ull)) << slot));
+        SentMsg m{(uint32_t)slot, f.nslots, f.size, d.row_bytes, d.box_rows, d.lds_pitch, !is_load};
+        if (f.flags & F_SEND) c.vcc[f.vcc].m2c.push_back(m);
+        if (!is_load) {
+            if (!(f.flags & F_SEND)) { fail("STORE with RECV but without SEND: nothing hands its region to a compute core"); return -1; }
+            c.stores_waiting.push_back(m);
+            if (f.flags & F_DEP_SEND) dep[f.dep_id]++;   // counted at issue: the store itself cannot block
+        } else if (f.flags & F_DEP_SEND) {
+            dep[f.dep_id]++;
+        }
+        s.pc++;
+        return 1;
+    }
+
+    void release(CoreH &c, const SentMsg &m) {
+        c.mask &= ~(uint32_t)(((m.nslots >= 32 ? 0xFFFFFFFFull : ((1ull << m.nslots) - 1ull)) << m.slot));
+    }
+
+    int vcc_step(CoreH &c, VccH &v) {
+        if (!v.in_uop) {
+            if (v.s.halted) return 0;
+            Fields f;
+            if (!fetch(v.s, f)) return -1;
+            int k = control(v.s, f);
+            if (k < 0) return -1;
+            if (k > 0) return 1;
+            if (f.opcode != OP_MATVEC) { fail("opcode not valid on a compute core"); return -1; }
+            v.B = (uint32_t)f.imm & 0xFFu;
+            v.R = (uint32_t)(f.imm >> 8) & 0xFFFFu;
+            v.lpr = (uint32_t)(f.imm >> 24) & 0xFFFFu;
+            if (!matvec_geometry_ok(v.B, v.R, v.lpr, nullptr, nullptr)) { fail("matvec geometry not supported"); return -1; }
+            if (f.size < 1) { fail("matvec over zero tiles"); return -1; }
+            if ((uint64_t)v.B * v.R * 4 > (uint64_t)cfg.slot_bytes * cfg.n_slots) { fail("matvec output too large"); return -1; }
+            v.left = f.size;
+            v.phase = 0;
+            v.in_uop = true;
+            return 1;
+        }
+        if (v.m2c.empty()) return 0;
+        SentMsg m = v.m2c.front();
+        v.m2c.pop_front();
+        if (v.phase == 0) {
+            if (m.is_store || m.box_rows != v.R || m.lds_pitch != v.lpr * 16) { fail("matvec: matrix tile does not match the uop"); return -1; }
+            v.a = m;
+            v.phase = 1;
+        } else if (v.phase == 1) {
+            if (m.is_store || m.box_rows != v.B || m.rows != v.B || m.lds_pitch != v.lpr * 16) { fail("matvec: vector tile does not match the uop"); return -1; }
+            release(c, v.a);
+            release(c, m);
+            if (--v.left == 0) v.phase = 2; else v.phase = 0;
+        } else {
+            if (!m.is_store || m.rows != v.B || m.lds_pitch != v.R * 4 || m.row_bytes > v.R * 4) { fail("matvec: output region does not match the uop"); return -1; }
+            // produced region returns to its STORE, which writes it back and frees it
+            bool found = false;
+            for (auto it = c.stores_waiting.begin(); it != c.stores_waiting.end(); ++it)
+                if (it->slot == m.slot && it->nslots == m.nslots) { c.stores_waiting.erase(it); found = true; break; }
+            if (!found) { fail("matvec: output region has no STORE"); return -1; }
+            release(c, m);
+            v.in_uop = false;
+            v.s.pc++;
+        }
+        return 1;
+    }
+
+    bool run() {
+        const int V = cfg.vcc_per_core, C = cfg.n_cores;
+        dep.assign(cfg.n_dep_ids, 0);
+        std::vector<CoreH> cores(C);
+        for (int c = 0; c < C; c++) {
+            uint32_t base = c * (1 + V);
+            for (int k = 0; k <= V; k++) {
+                if (sb[base + k] > sb[base + k + 1] || (int64_t)sb[base + k + 1] > n_words) return fail("stream_begin is not a partition of the uops");
+            }
+            cores[c].vmc.pc = cores[c].vmc.begin = sb[base];
+            cores[c].vmc.end = sb[base + 1];
+            cores[c].vcc.resize(V);
+            for (int v = 0; v < V; v++) {
+                cores[c].vcc[v].s.pc = cores[c].vcc[v].s.begin = sb[base + 1 + v];
+                cores[c].vcc[v].s.end = sb[base + 2 + v];
+            }
+        }
+        const int64_t step_limit = 400000000;
+        std::vector<char> done(C, 0);
+        int n_done = 0;
+        while (n_done < C) {
+            bool progress = false;
+            for (int c = 0; c < C; c++) {
+                if (done[c]) continue;
+                CoreH &core = cores[c];
+                // run this core as far as it goes on its own
+                for (;;) {
+                    bool moved = false;
+                    for (;;) {
+                        int r = cfu_step(core);
+                        if (r < 0) return false;
+                        if (r == 0) break;
+                        moved = true;
+                        if (++steps > step_limit) return fail("program too long to validate");
+                    }
+                    for (auto &v : core.vcc) {
+                        for (;;) {
+                            int r = vcc_step(core, v);
+                            if (r < 0) return false;
+                            if (r == 0) break;
+                            moved = true;
+                            if (++steps > step_limit) return fail("program too long to validate");
+                        }
+                    }
+                    if (!moved) break;
+                    progress = true;
+                }
+                bool fin = core.vmc.halted;
+                for (auto &v : core.vcc) fin = fin && v.s.halted && !v.in_uop && v.m2c.empty();
+                if (fin) {
+                    if (core.mask != 0 || !core.stores_waiting.empty()) return fail("a core ends with slots still allocated");
+                    done[c] = 1;
+                    n_done++;
+                    progress = true;
+                }
+            }
+            if (!progress) return fail("deadlock under in-order execution (slots over-committed, a missing send, or a depId that is never signalled)");
+        }
+        return true;
+    }
+};
+
+// ------------------------------------------------------------------------------------------------------------
+// Matvec tiler: rows of M are cut into blocks of R rows ("tile the matrix along the M dimension", Section 3);
+// every core gets a contiguous range of blocks and deals them alternately to its compute cores; the K loop
+// and the block loop are LOOP/REPEAT nests over dynamic addresses (Section 5).
+// Tensors: 0 = M, 1 = X, 2 = Y.
+// ------------------------------------------------------------------------------------------------------------
+struct Run {        // consecutive row blocks of one segment handled by one core
+    int64_t m_off;  // byte offset of the first row in M
+    int64_t x_off;  // byte offset of the segment's vector(s) in X
+    int64_t y_off;  // byte offset of the first result in Y
+    int64_t n_full; // full blocks of R rows
+    int32_t tail;   // rows of a final partial block, 0 if none
+};
+
+struct Tiler {
+    const vdc_config &cfg;
+    int64_t K, ld, y_pitch;  // elements
+    int32_t B, R, Kt;
+    std::vector<std::vector<Word>> streams;
+    std::vector<Desc> descs;
+    bool nt = true;
+
+    uint32_t desc(uint32_t tensor, uint32_t box_rows, uint32_t row_bytes, uint32_t lds_pitch, uint64_t gpitch) {
+        Desc d{tensor, box_rows, row_bytes, lds_pitch, (uint32_t)gpitch, (uint32_t)(gpitch >> 32), 0, 0};
+        for (size_t i = 0; i < descs.size(); i++)
+            if (!memcmp(&descs[i], &d, sizeof d)) return (uint32_t)i;
+        descs.push_back(d);
+        return (uint32_t)descs.size() - 1;
+    }
+    uint32_t slots_for(uint64_t bytes) const { return (uint32_t)((bytes + cfg.slot_bytes - 1) / cfg.slot_bytes); }
+    std::vector<Word> &vmc(int core) { return streams[core * (1 + cfg.vcc_per_core)]; }
+    std::vector<Word> &vcc(int core, int v) { return streams[core * (1 + cfg.vcc_per_core) + 1 + v]; }
+
+    // virtual flows: matrix tiles of compute core v on flow v, vector tiles on flow V + v, stores on flow 2V + v
+    uint32_t flow_m(int v) const { return (uint32_t)v; }
+    uint32_t flow_x(int v) const { return (uint32_t)(cfg.vcc_per_core + v); }
+    uint32_t flow_y(int v) const { return (uint32_t)(2 * cfg.vcc_per_core + v); }
+
+    // accumulators: 0,1 matrix offset of compute core 0,1; 2 vector offset; 3,4 result offset of compute core 0,1
+    void emit_tile_pair(std::vector<Word> &vm, int v, uint32_t dm, uint32_t dx, uint32_t rows_valid) {
+        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | (nt ? F_NT : 0), flow_m(v), v, v, slots_for((uint64_t)R * Kt * 4), rows_valid, 0, 0, dm, 0));
+        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(v), v, 2, slots_for((uint64_t)B * Kt * 4), B, 0, 0, dx, 0));
+    }
+
+    // `count` iterations; in each, every compute core in `vs` takes one block of `rows_valid` rows.
+    void emit_blocks(int core, const std::vector<int> &vs, int64_t count, int64_t m_off, int64_t x_off, int64_t y_off,
+                     uint32_t rows_valid) {
+        auto &vm = vmc(core);
+        const int64_t nk_full = K / Kt, ktail = K % Kt;
+        const int n = (int)vs.size();
+        const uint32_t dm = desc(0, R, Kt * 4, Kt * 4, (uint64_t)ld * 4), dx = desc(1, B, Kt * 4, Kt * 4, (uint64_t)K * 4);
+        const uint32_t dmt = ktail ? desc(0, R, (uint32_t)ktail * 4, Kt * 4, (uint64_t)ld * 4) : 0;
+        const uint32_t dxt = ktail ? desc(1, B, (uint32_t)ktail * 4, Kt * 4, (uint64_t)K * 4) : 0;
+        const uint32_t dy = desc(2, B, rows_valid * 4, R * 4, (uint64_t)y_pitch * 4);
+        for (int i = 0; i < n; i++) {
+            vm.push_back(encode(OP_SET, 0, 0, 0, vs[i], 0, 0, 0, m_off + (int64_t)i * R * ld * 4, 0, 0));
+            vm.push_back(encode(OP_SET, 0, 0, 0, 3 + vs[i], 0, 0, 0, y_off + (int64_t)i * R * 4, 0, 0));
+        }
+        vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, x_off, 0, 0));
+        if (count > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, count, 0, 0));
+        if (nk_full > 0) {
+            if (nk_full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full, 0, 0));
+            for (int i = 0; i < n; i++) emit_tile_pair(vm, vs[i], dm, dx, rows_valid);
+            for (int i = 0; i < n; i++) vm.push_back(encode(OP_ADD, 0, 0, 0, vs[i], 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+            if (nk_full > 1) vm.push_back(encode(OP_REPEAT, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+            else vm.push_back(encode(OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+        }
+        if (ktail)
+            for (int i = 0; i < n; i++) emit_tile_pair(vm, vs[i], dmt, dxt, rows_valid);
+        for (int i = 0; i < n; i++)
+            vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DYNAMIC, flow_y(vs[i]), vs[i], 3 + vs[i], slots_for((uint64_t)B * R * 4), B, 0, 0, dy, 0));
+        if (count > 1) {
+            for (int i = 0; i < n; i++) {
+                vm.push_back(encode(OP_ADD, 0, 0, 0, vs[i], 0, 0, 0, (int64_t)n * R * ld * 4 - nk_full * Kt * 4, 0, 0));
+                vm.push_back(encode(OP_ADD, 0, 0, 0, 3 + vs[i], 0, 0, 0, (int64_t)n * R * 4, 0, 0));
+            }
+            vm.push_back(encode(OP_REPEAT, 0, 0, 0, 2, 0, 0, 0, -nk_full * Kt * 4, 0, 0));
+        }
+        const uint32_t nk = (uint32_t)(nk_full + (ktail ? 1 : 0));
+        for (int i = 0; i < n; i++) {
+            auto &vc = vcc(core, vs[i]);
+            if (count > 1) vc.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, count, 0, 0));
+            vc.push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, nk, 0, matvec_imm(B, R, Kt / 4), 0, 0));
+            if (count > 1) vc.push_back(encode(OP_REPEAT, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
+        }
+    }
+
+    void emit_core(int core, const std::vector<Run> &runs) {
+        const int V = cfg.vcc_per_core;
+        int next_v = 0;
+        for (const Run &r : runs) {
+            int64_t left = r.n_full, m = r.m_off, y = r.y_off;
+            const int64_t blk_m = (int64_t)R * ld * 4, blk_y = (int64_t)R * 4;
+            if (V == 2) {
+                if (next_v == 1 && left > 0) {  // re-align so that the paired loop starts on compute core 0
+                    emit_blocks(core, {1}, 1, m, r.x_off, y, R);
+                    m += blk_m; y += blk_y; left--; next_v = 0;
+                }
+                if (left >= 2) {
+                    emit_blocks(core, {0, 1}, left / 2, m, r.x_off, y, R);
+                    m += (left / 2) * 2 * blk_m; y += (left / 2) * 2 * blk_y; left -= (left / 2) * 2;
+                }
+                if (left == 1) {
+                    emit_blocks(core, {next_v}, 1, m, r.x_off, y, R);
+                    m += blk_m; y += blk_y; next_v ^= 1;
+                }
+                if (r.tail) {
+                    emit_blocks(core, {next_v}, 1, m, r.x_off, y, (uint32_t)r.tail);
+                    next_v ^= 1;
+                }
+            } else {
+                if (left > 0) emit_blocks(core, {0}, left, m, r.x_off, y, R);
+                m += left * blk_m; y += left * blk_y;
+                if (r.tail) emit_blocks(core, {0}, 1, m, r.x_off, y, (uint32_t)r.tail);
+            }
+        }
+    }
+};
+
+// Rows per matrix tile for a tile of tile_bytes: keep a tile row inside one wave (at most 64 chunks of 16 bytes,
+// no cross-wave reduction), keep at least 512 contiguous bytes per row when K allows, and prefer at least 4 rows
+// per right-hand vector so that the vector tiles (which come from the L2, not from HBM) stay a small part of the
+// LDS fill traffic.
+bool choose_tile(const vdc_config &cfg, int64_t K, int32_t B, int32_t tile_bytes, int32_t &R, int32_t &Kt) {
+    const int32_t chunks = tile_bytes / 16;
+    if (tile_bytes != 2048 && tile_bytes != 4096 && tile_bytes != 8192 && tile_bytes != 16384) return false;
+    int32_t lpr;
+    if (cfg.tile_rows > 0) {
+        if (chunks % cfg.tile_rows) return false;
+        lpr = chunks / cfg.tile_rows;
+    } else {
+        lpr = 64;
+        while (lpr > 32 && chunks / lpr < 4 * B) lpr >>= 1;
+        while (lpr > 1 && (int64_t)lpr * 4 >= 2 * K) lpr >>= 1;   // no tile much wider than a row
+    }
+    if (lpr < 1 || chunks % lpr) return false;
+    R = chunks / lpr;
+    Kt = lpr * 4;
+    return matvec_geometry_ok((uint32_t)B, (uint32_t)R, (uint32_t)lpr, nullptr, nullptr);
+}
+
+int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
+                 const int64_t *row_off, int32_t n_seg, std::vector<Word> &words, std::vector<uint32_t> &sb,
+                 std::vector<Desc> &descs) {
+    int32_t R = 0, Kt = 0;
+    if (!choose_tile(cfg, K, B, tile_bytes, R, Kt)) return VDC_EINVAL;
+    if ((uint64_t)((K + Kt - 1) / Kt) > 65535) return VDC_EINVAL;
+    const int C = cfg.n_cores, V = cfg.vcc_per_core;
+    Tiler t{cfg, K, ld, row_off ? 0 : rows, B, R, Kt};
+    t.streams.resize((size_t)C * (1 + V));
+    // global list of row blocks, segment by segment; core c takes blocks [c*NB/C, (c+1)*NB/C)
+    struct Seg { int64_t row0, len, first_block, n_blocks; };
+    std::vector<Seg> segs;
+    int64_t nb = 0;
+    if (row_off) {
+        for (int s = 0; s < n_seg; s++) {
+            int64_t len = row_off[s + 1] - row_off[s];
+            int64_t n = (len + R - 1) / R;
+            segs.push_back({row_off[s], len, nb, n});
+            nb += n;
+        }
+    } else {
+        segs.push_back({0, rows, 0, (rows + R - 1) / R});
+        nb = segs[0].n_blocks;
+    }
+    size_t si = 0;
+    for (int c = 0; c < C; c++) {
+        int64_t b0 = nb * c / C, b1 = nb * (c + 1) / C;
+        std::vector<Run> runs;
+        while (b0 < b1) {
+            while (si < segs.size() && segs[si].first_block + segs[si].n_blocks <= b0) si++;
+            const Seg &sg = segs[si];
+            int64_t e = std::min(b1, sg.first_block + sg.n_blocks);
+            int64_t lb0 = b0 - sg.first_block, lb1 = e - sg.first_block;   // local block range in the segment
+            int64_t r0 = lb0 * R, r1 = std::min(sg.len, lb1 * R);
+            Run r;
+            r.m_off = (sg.row0 + r0) * ld * 4;
+            r.x_off = row_off ? (int64_t)si * K * 4 : 0;
+            r.y_off = (sg.row0 + r0) * 4;
+            r.n_full = (r1 - r0) / R;
+            r.tail = (int32_t)((r1 - r0) % R);
+            runs.push_back(r);
+            b0 = e;
+        }
+        t.emit_core(c, runs);
+    }
+    words.clear();
+    sb.assign(1, 0);
+    for (auto &s : t.streams) {
+        words.insert(words.end(), s.begin(), s.end());
+        words.push_back(encode(OP_HALT, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
+        sb.push_back((uint32_t)words.size());
+    }
+    descs = t.descs;
+    if (descs.empty()) descs.push_back(Desc{0, 1, 16, 16, 0, 0, 0, 0});
+    if (descs.size() > 256) return VDC_EINVAL;
+    return VDC_OK;
+}
+
+int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
+    for (int i = 0; i < 5; i++)
+        if (c.reserved[i]) return VDC_EINVAL;
+    if (c.n_cores == 0) c.n_cores = cu_count;
+    if (c.vcc_per_core == 0) c.vcc_per_core = 2;
+    if (c.threads_per_eu == 0) c.threads_per_eu = 128;
+    if (c.slot_bytes == 0) c.slot_bytes = 8192;
+    if (c.n_ldu == 0) c.n_ldu = 2;
+    if (c.n_stu == 0) c.n_stu = 1;
+    if (c.n_dep_ids == 0) c.n_dep_ids = 1024;
+    if (c.watchdog_spins == 0) c.watchdog_spins = 1 << 22;
+    if (c.n_cores < 1 || c.n_cores > cu_count) return VDC_EINVAL;   // all cores must be co-resident
+    if (c.vcc_per_core < 1 || c.vcc_per_core > 2 || c.threads_per_eu != 128) return VDC_EINVAL;
+    if (!is_pow2(c.slot_bytes) || c.slot_bytes < 1024 || c.slot_bytes > 16384) return VDC_EINVAL;
+    if (c.n_ldu < 1 || c.n_ldu > 2 || c.n_stu != 1) return VDC_EINVAL;   // 8 waves: 256 VGPRs each
+    if (c.n_dep_ids < 1 || c.n_dep_ids > 65536 || c.watchdog_spins < 64 || c.tile_rows < 0) return VDC_EINVAL;
+    const size_t ctl = lds_control_bytes();
+    if (c.n_slots == 0) {
+        size_t fit = (lds_limit - ctl) / (size_t)c.slot_bytes;
+        c.n_slots = (int32_t)std::min<size_t>(fit, 32);
+    }
+    if (c.n_slots < 1 || c.n_slots > 32) return VDC_EINVAL;
+    if (lds_bytes_needed(c.n_slots, c.slot_bytes) > lds_limit) return VDC_EINVAL;
+    return VDC_OK;
+}
+
+int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, uint32_t *trace,
+                uint32_t *trace_count, int32_t trace_cap, hipStream_t stream) {
+    if (!ex || !prog || prog->ex != ex || !tensor_bases || n_tensors != prog->n_tensors) return VDC_EINVAL;
+    if (ex->cfg.device == -1) return VDC_EINVAL;
+    KParams p{};
+    p.words = prog->d_words;
+    p.stream_begin = prog->d_stream_begin;
+    p.descs = prog->d_descs;
+    for (int i = 0; i < n_tensors; i++) {
+        if (!tensor_bases[i] || ((uintptr_t)tensor_bases[i] & 3u)) return VDC_EINVAL;
+        p.tensors[i] = (char *)tensor_bases[i];
+    }
+    p.dep = ex->d_dep;
+    p.status = ex->d_status;
+    p.trace = trace;
+    p.trace_count = trace_count;
+    p.trace_cap = (uint32_t)trace_cap;
+    p.n_slots = ex->cfg.n_slots;
+    p.slot_bytes = ex->cfg.slot_bytes;
+    p.n_ldu = ex->cfg.n_ldu;
+    p.n_stu = ex->cfg.n_stu;
+    p.V = ex->cfg.vcc_per_core;
+    p.watchdog = (uint32_t)ex->cfg.watchdog_spins;
+    HIP_TRY(hipSetDevice(ex->cfg.device));
+    if (prog->uses_dep) HIP_TRY(launch_clear(ex->d_dep, prog->max_dep_id + 1, stream));
+    if (trace_count) HIP_TRY(launch_clear(trace_count, (uint32_t)(ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core)), stream));
+    HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, trace != nullptr, stream));
+    return VDC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vdc_create(vdc_executor **out, const vdc_config *cfg_in) {
+    if (!out) return VDC_EINVAL;
+    *out = nullptr;
+    vdc_config cfg{};
+    if (cfg_in) cfg = *cfg_in;
+    if (cfg.device == -1) {
+        // host-only executor: builds and validates programs, owns no device resources and cannot run
+        int rc = resolve_config(cfg, cfg.n_cores > 0 ? cfg.n_cores : 256, 163840);
+        if (rc != VDC_OK) return rc;
+        vdc_executor *h = new (std::nothrow) vdc_executor();
+        if (!h) return VDC_ENOMEM;
+        h->cfg = cfg;
+        h->cu_count = cfg.n_cores;
+        h->lds_limit = 163840;
+        *out = h;
+        return VDC_OK;
+    }
+    int ndev = 0;
+    HIP_TRY(hipGetDeviceCount(&ndev));
+    if (cfg.device < 0 || cfg.device >= ndev) return VDC_EINVAL;
+    HIP_TRY(hipSetDevice(cfg.device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, cfg.device));
+    int lds_max = 0;
+    HIP_TRY(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, cfg.device));
+    int rc = resolve_config(cfg, prop.multiProcessorCount, (size_t)lds_max);
+    if (rc != VDC_OK) return rc;
+    std::unique_ptr<vdc_executor> ex(new (std::nothrow) vdc_executor());
+    if (!ex) return VDC_ENOMEM;
+    ex->cfg = cfg;
+    ex->cu_count = prop.multiProcessorCount;
+    ex->lds_limit = (size_t)lds_max;
+    if (hipMalloc(&ex->d_dep, sizeof(uint32_t) * cfg.n_dep_ids) != hipSuccess) return VDC_ENOMEM;
+    if (hipMalloc(&ex->d_status, sizeof(uint32_t) * ST_WORDS) != hipSuccess) { (void)hipFree(ex->d_dep); return VDC_ENOMEM; }
+    if (hipHostMalloc(&ex->h_status, sizeof(uint32_t) * ST_WORDS) != hipSuccess) { (void)hipFree(ex->d_dep); (void)hipFree(ex->d_status); return VDC_ENOMEM; }
+    HIP_TRY(hipMemset(ex->d_dep, 0, sizeof(uint32_t) * cfg.n_dep_ids));
+    HIP_TRY(hipMemset(ex->d_status, 0, sizeof(uint32_t) * ST_WORDS));
+    HIP_TRY(prepare_executor_kernels(lds_bytes_needed(cfg.n_slots, cfg.slot_bytes)));
+    HIP_TRY(hipDeviceSynchronize());
+    *out = ex.release();
+    return VDC_OK;
+}
+
+int vdc_destroy(vdc_executor *ex) {
+    if (!ex) return VDC_EINVAL;
+    if (ex->cfg.device == -1) {
+        delete ex;
+        return VDC_OK;
+    }
+    (void)hipSetDevice(ex->cfg.device);
+    (void)hipDeviceSynchronize();
+    for (vdc_program *p : ex->programs) {
+        (void)hipFree(p->d_words);
+        (void)hipFree(p->d_stream_begin);
+        (void)hipFree(p->d_descs);
+        delete p;
+    }
+    (void)hipFree(ex->d_dep);
+    (void)hipFree(ex->d_status);
+    (void)hipHostFree(ex->h_status);
+    delete ex;
+    return VDC_OK;
+}
+
+int vdc_get_config(const vdc_executor *ex, vdc_config *cfg) {
+    if (!ex || !cfg) return VDC_EINVAL;
+    *cfg = ex->cfg;
+    return VDC_OK;
+}
+
+int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const uint32_t *stream_begin, const void *descs,
+                       int32_t n_descs, const int64_t *tensor_bytes, int32_t n_tensors, vdc_program **out) {
+    if (out) *out = nullptr;
+    if (!ex || !uops || n_uops < 1 || n_uops > 0x7FFFFFFF || !stream_begin || !descs || n_descs < 1 || n_descs > 256 ||
+        !tensor_bytes || n_tensors < 0 || n_tensors > kMaxTensors || !out)
+        return VDC_EINVAL;
+    if (ex->cfg.device == -1) return VDC_EINVAL;
+    const int n_streams = ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core);
+    if (stream_begin[0] != 0 || (int64_t)stream_begin[n_streams] != n_uops) return VDC_EPROGRAM;
+    Validator val{ex->cfg, (const Word *)uops, n_uops, stream_begin, (const Desc *)descs, n_descs, tensor_bytes, n_tensors};
+    if (!val.run()) return VDC_EPROGRAM;
+    std::unique_ptr<vdc_program> p(new (std::nothrow) vdc_program());
+    if (!p) return VDC_ENOMEM;
+    p->ex = ex;
+    p->n_tensors = n_tensors;
+    for (int i = 0; i < n_tensors; i++) p->tensor_bytes[i] = tensor_bytes[i];
+    p->uses_dep = val.uses_dep;
+    p->max_dep_id = val.max_dep;
+    HIP_TRY(hipSetDevice(ex->cfg.device));
+    const size_t wb = (size_t)n_uops * sizeof(Word), sbb = (size_t)(n_streams + 1) * 4, db = (size_t)n_descs * sizeof(Desc);
+    if (hipMalloc(&p->d_words, wb) != hipSuccess) return VDC_ENOMEM;
+    if (hipMalloc(&p->d_stream_begin, sbb) != hipSuccess) { (void)hipFree(p->d_words); return VDC_ENOMEM; }
+    if (hipMalloc(&p->d_descs, db) != hipSuccess) { (void)hipFree(p->d_words); (void)hipFree(p->d_stream_begin); return VDC_ENOMEM; }
+    hipError_t e = hipMemcpy(p->d_words, uops, wb, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(p->d_stream_begin, stream_begin, sbb, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(p->d_descs, descs, db, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(p->d_words); (void)hipFree(p->d_stream_begin); (void)hipFree(p->d_descs); return VDC_EDEVICE; }
+    ex->programs.push_back(p.get());
+    *out = p.release();
+    return VDC_OK;
+}
+
+int vdc_program_validate(vdc_executor *ex, const void *uops, int64_t n_uops, const uint32_t *stream_begin, const void *descs,
+                         int32_t n_descs, const int64_t *tensor_bytes, int32_t n_tensors, char *msg, int32_t msg_cap) {
+    if (msg && msg_cap > 0) msg[0] = 0;
+    if (!ex || !uops || n_uops < 1 || n_uops > 0x7FFFFFFF || !stream_begin || !descs || n_descs < 1 || n_descs > 256 ||
+        !tensor_bytes || n_tensors < 0 || n_tensors > kMaxTensors)
+        return VDC_EINVAL;
+    const int n_streams = ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core);
+    Validator val{ex->cfg, (const Word *)uops, n_uops, stream_begin, (const Desc *)descs, n_descs, tensor_bytes, n_tensors};
+    bool ok = stream_begin[0] == 0 && (int64_t)stream_begin[n_streams] == n_uops;
+    if (!ok) val.err = "stream_begin does not cover the uops";
+    ok = ok && val.run();
+    if (!ok && msg && msg_cap > 0) {
+        strncpy(msg, val.err.c_str(), (size_t)msg_cap - 1);
+        msg[msg_cap - 1] = 0;
+    }
+    return ok ? VDC_OK : VDC_EPROGRAM;
+}
+
+int vdc_program_destroy(vdc_program *prog) {
+    if (!prog) return VDC_EINVAL;
+    vdc_executor *ex = prog->ex;
+    (void)hipSetDevice(ex->cfg.device);
+    (void)hipDeviceSynchronize();
+    ex->programs.erase(std::remove(ex->programs.begin(), ex->programs.end(), prog), ex->programs.end());
+    for (auto it = ex->matvec_cache.begin(); it != ex->matvec_cache.end();)
+        it = (it->second == prog) ? ex->matvec_cache.erase(it) : it + 1;
+    (void)hipFree(prog->d_words);
+    (void)hipFree(prog->d_stream_begin);
+    (void)hipFree(prog->d_descs);
+    delete prog;
+    return VDC_OK;
+}
+
+int vdc_run(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, void *hip_stream) {
+    return run_program(ex, prog, tensor_bases, n_tensors, nullptr, nullptr, 0, (hipStream_t)hip_stream);
+}
+
+int vdc_run_traced(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, uint32_t *trace,
+                   uint32_t *trace_count, int32_t trace_cap, void *hip_stream) {
+    if (!trace || !trace_count || trace_cap < 1) return VDC_EINVAL;
+    return run_program(ex, prog, tensor_bases, n_tensors, trace, trace_count, trace_cap, (hipStream_t)hip_stream);
+}
+
+int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info) {
+    if (!ex || ex->cfg.device == -1) return VDC_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(ex->cfg.device));
+    HIP_TRY(hipMemcpyAsync(ex->h_status, ex->d_status, sizeof(uint32_t) * ST_WORDS, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (info) {
+        info[0] = ex->h_status[ST_CORE];
+        info[1] = ex->h_status[ST_ROLE];
+        info[2] = ex->h_status[ST_PC];
+        info[3] = ex->h_status[ST_DETAIL];
+    }
+    if (ex->h_status[ST_ABORT] == 0) return VDC_OK;
+    int code = -(int)ex->h_status[ST_CODE];
+    HIP_TRY(launch_clear(ex->d_status, ST_WORDS, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return code ? code : VDC_EDEVICE;
+}
+
+static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
+                         int32_t B, int32_t tile_bytes, const int64_t *row_off, int32_t n_seg, void *hip_stream) {
+    if (!ex || ex->cfg.device == -1 || !M || !X || !Y || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
+    if (((uintptr_t)M & 15u) || ((uintptr_t)X & 15u) || ((uintptr_t)Y & 3u)) return VDC_EINVAL;
+    MatvecKey key{rows, K, ld, B, tile_bytes, row_off ? n_seg : -1, {}};
+    if (row_off) key.row_off.assign(row_off, row_off + n_seg + 1);
+    vdc_program *prog = nullptr;
+    for (auto &kv : ex->matvec_cache)
+        if (kv.first == key) { prog = kv.second; break; }
+    if (!prog) {
+        std::vector<Word> words;
+        std::vector<uint32_t> sb;
+        std::vector<Desc> descs;
+        int rc = build_matvec(ex->cfg, rows, K, ld, B, tile_bytes, row_off, n_seg, words, sb, descs);
+        if (rc != VDC_OK) return rc;
+        const int64_t x_rows = row_off ? n_seg : B;
+        int64_t tb[3] = {((rows - 1) * ld + K) * 4, x_rows * K * 4, (int64_t)B * rows * 4};
+        rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb, 3, &prog);
+        if (rc != VDC_OK) return rc;
+        ex->matvec_cache.push_back({key, prog});
+    }
+    void *bases[3] = {(void *)M, (void *)X, (void *)Y};
+    return vdc_run(ex, prog, bases, 3, hip_stream);
+}
+
+int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y, int32_t B,
+               int32_t tile_bytes, void *hip_stream) {
+    return matvec_common(ex, M, rows, K, ld, X, Y, B, tile_bytes, nullptr, 0, hip_stream);
+}
+
+int vdc_matvec_ragged(vdc_executor *ex, const float *M, const int64_t *row_off, int32_t n_seg, int64_t K, const float *X,
+                      float *Y, int32_t tile_bytes, void *hip_stream) {
+    if (!row_off || n_seg < 1 || row_off[0] != 0) return VDC_EINVAL;
+    for (int s = 0; s < n_seg; s++)
+        if (row_off[s + 1] < row_off[s]) return VDC_EINVAL;
+    return matvec_common(ex, M, row_off[n_seg], K, K, X, Y, 1, tile_bytes, row_off, n_seg, hip_stream);
+}
+
+int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
+                       const int64_t *row_off, int32_t n_seg, void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs,
+                       int32_t *n_descs) {
+    if (!ex || !n_uops || !n_descs || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
+    if (row_off) {
+        if (n_seg < 1 || row_off[0] != 0 || row_off[n_seg] != rows || B != 1 || ld != K) return VDC_EINVAL;
+        for (int s = 0; s < n_seg; s++)
+            if (row_off[s + 1] < row_off[s]) return VDC_EINVAL;
+    }
+    std::vector<Word> words;
+    std::vector<uint32_t> sb;
+    std::vector<Desc> ds;
+    int rc = build_matvec(ex->cfg, rows, K, ld, B, tile_bytes, row_off, n_seg, words, sb, ds);
+    if (rc != VDC_OK) return rc;
+    const int64_t cap_w = *n_uops;
+    const int32_t cap_d = *n_descs;
+    *n_uops = (int64_t)words.size();
+    *n_descs = (int32_t)ds.size();
+    bool fits = true;
+    if (uops) { if (cap_w >= (int64_t)words.size()) memcpy(uops, words.data(), words.size() * sizeof(Word)); else fits = false; }
+    if (descs) { if (cap_d >= (int32_t)ds.size()) memcpy(descs, ds.data(), ds.size() * sizeof(Desc)); else fits = false; }
+    if (stream_begin) memcpy(stream_begin, sb.data(), sb.size() * sizeof(uint32_t));
+    return fits ? VDC_OK : VDC_EINVAL;
+}
+
+int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n,
+                    void *hip_stream) {
+    if (!ex || ex->cfg.device == -1 || !masks || !nslots || !pos || n < 1 || n_slots < 1 || n_slots > 32) return VDC_EINVAL;
+    HIP_TRY(hipSetDevice(ex->cfg.device));
+    HIP_TRY(launch_debug_alloc(masks, nslots, n_slots, pos, n, (hipStream_t)hip_stream));
+    return VDC_OK;
+}
+
+const char *vdc_strerror(int code) {
+    switch (code) {
+        case VDC_OK: return "ok";
+        case VDC_EINVAL: return "invalid argument";
+        case VDC_ENOMEM: return "out of memory";
+        case VDC_EPROGRAM: return "malformed uop program";
+        case VDC_EDEVICE: return "HIP error";
+        case VDC_EDEADLOCK: return "device watchdog: a unit waited past the spin limit";
+        case VDC_ELEAK: return "run ended with local-memory slots still allocated";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

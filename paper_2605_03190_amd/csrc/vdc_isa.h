@@ -1,0 +1,125 @@
+// Micro-operation (uop) instruction set of the executor: word layout, opcodes, flags, descriptors.
+//
+// The paper names the fields of the instruction word (Section 4.1: opcode, size, address, flags
+// send / recv / dynamic, depId, virtualFlowId; Section 5: accumulator-relative dynamic addresses) but
+// gives no widths; this is the layout this library defines.  Shared by the host side (tiler,
+// validator) and the device side (decoders in the kernel) of the library.
+#ifndef VDC_ISA_H
+#define VDC_ISA_H
+
+#include <stdint.h>
+
+#if defined(__HIPCC__) || defined(__HIP__)
+#define VDC_HD __host__ __device__ __forceinline__
+#else
+#define VDC_HD inline
+#endif
+
+namespace vdc {
+
+enum Opcode : uint32_t {
+    OP_HALT = 0,    // end of stream
+    OP_LOOP = 1,    // push (pc + 1, imm trips)
+    OP_REPEAT = 2,  // acc[a] += imm; next trip of the innermost loop or fall through
+    OP_ADD = 3,     // acc[a] += imm
+    OP_SET = 4,     // acc[a] = imm
+    OP_LOAD = 8,    // VMC: global -> local-memory region
+    OP_STORE = 9,   // VMC: local-memory region -> global
+    OP_MATVEC = 16  // VCC: the matvec compute uop of the listing in Section 4.1
+};
+
+enum Flag : uint32_t {
+    F_SEND = 1,      // forward the region to local compute core `vcc` (m2c)
+    F_RECV = 2,      // consume a region produced by local compute core `vcc` (c2m)
+    F_DYNAMIC = 4,   // address = imm + acc[a]
+    F_NT = 8,        // streaming hint for the load path; no semantic effect
+    F_DEP_SEND = 16, // after completion: dep[depId] += 1
+    F_DEP_RECV = 32  // before starting: wait until dep[depId] >= max(1, dep_count)
+};
+
+constexpr int kMaxLoopDepth = 4;
+constexpr int kNumAcc = 8;
+constexpr int kMaxTensors = 8;
+constexpr int kMaxSlots = 32;   // 32-bit availability mask (Section 4.3)
+
+struct Word {            // 16 bytes
+    uint32_t w0, w1, w2, w3;
+};
+
+struct Desc {            // 32 bytes: the 2-D box a memory uop moves
+    uint32_t tensor;     // tensor id
+    uint32_t box_rows;   // rows of the local-memory box
+    uint32_t row_bytes;  // valid bytes per row (multiple of 16 for LOAD, of 4 for STORE)
+    uint32_t lds_pitch;  // bytes between rows in local memory (multiple of 16)
+    uint32_t gpitch_lo;  // bytes between rows in global memory
+    uint32_t gpitch_hi;
+    uint32_t rsv0, rsv1;
+};
+
+struct Fields {
+    uint32_t opcode, flags, vflow, vcc, acc, nslots, size, dep_id, desc, dep_count;
+    int64_t imm;
+};
+
+VDC_HD Fields decode(const Word &w) {
+    Fields f;
+    f.opcode = w.w0 & 0xFFu;
+    f.flags = (w.w0 >> 8) & 0xFFu;
+    f.vflow = (w.w0 >> 16) & 0xFu;
+    f.vcc = (w.w0 >> 20) & 0x3u;
+    f.acc = (w.w0 >> 22) & 0x7u;
+    f.nslots = (w.w0 >> 25) & 0x3Fu;
+    f.size = w.w1 & 0xFFFFu;
+    f.dep_id = w.w1 >> 16;
+    uint64_t q = (uint64_t)w.w2 | ((uint64_t)w.w3 << 32);
+    f.imm = (int64_t)(q << 16) >> 16;   // sign-extend 48 bits
+    f.desc = (uint32_t)(q >> 48) & 0xFFu;
+    f.dep_count = (uint32_t)(q >> 56);
+    return f;
+}
+
+inline Word encode(uint32_t opcode, uint32_t flags, uint32_t vflow, uint32_t vcc, uint32_t acc, uint32_t nslots,
+                   uint32_t size, uint32_t dep_id, int64_t imm, uint32_t desc, uint32_t dep_count) {
+    Word w;
+    w.w0 = (opcode & 0xFFu) | ((flags & 0xFFu) << 8) | ((vflow & 0xFu) << 16) | ((vcc & 0x3u) << 20) |
+           ((acc & 0x7u) << 22) | ((nslots & 0x3Fu) << 25);
+    w.w1 = (size & 0xFFFFu) | ((dep_id & 0xFFFFu) << 16);
+    uint64_t q = ((uint64_t)imm & 0xFFFFFFFFFFFFull) | ((uint64_t)(desc & 0xFFu) << 48) |
+                 ((uint64_t)(dep_count & 0xFFu) << 56);
+    w.w2 = (uint32_t)q;
+    w.w3 = (uint32_t)(q >> 32);
+    return w;
+}
+
+// MATVEC imm: B [7:0], R [23:8] (box rows of a matrix tile), lpr [39:24] (16-byte chunks per tile row)
+inline int64_t matvec_imm(uint32_t B, uint32_t R, uint32_t lpr) {
+    return (int64_t)B | ((int64_t)R << 8) | ((int64_t)lpr << 24);
+}
+
+// The compute uop works on `threads_per_eu` = 128 threads; a matrix tile is NF passes of 128 chunks of
+// 16 bytes.  Supported geometries (anything else is rejected when the program is created):
+//   lpr in {1,2,4,...,64}  : a tile row lies inside one wave  (mode J = 0), R*lpr = NF*128
+//   lpr = 128*J, J in {1,2,4,8}: a tile row spans J passes of all 128 threads, R*J = NF
+//   NF in {1,2,4,8} (tiles of 2, 4, 8, 16 KB), 1 <= B <= 8, and J*B <= 16 (vector registers)
+inline bool matvec_geometry_ok(uint32_t B, uint32_t R, uint32_t lpr, uint32_t *nf_out, uint32_t *j_out) {
+    if (B < 1 || B > 8 || R < 1 || lpr < 1) return false;
+    uint64_t chunks = (uint64_t)R * lpr;
+    if (chunks % 128 != 0) return false;
+    uint32_t nf = (uint32_t)(chunks / 128);
+    if (nf != 1 && nf != 2 && nf != 4 && nf != 8) return false;
+    uint32_t j = 0;
+    if (lpr <= 64) {
+        if (lpr & (lpr - 1)) return false;
+    } else {
+        if (lpr % 128) return false;
+        j = lpr / 128;
+        if (j != 1 && j != 2 && j != 4 && j != 8) return false;
+        if (j > nf || j * B > 16) return false;
+    }
+    if (nf_out) *nf_out = nf;
+    if (j_out) *j_out = j;
+    return true;
+}
+
+}  // namespace vdc
+#endif

@@ -1,0 +1,53 @@
+// Interface between the host side of the library and its device code: kernel parameters and launchers.
+#ifndef VDC_KERNEL_H
+#define VDC_KERNEL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "vdc_isa.h"
+
+namespace vdc {
+
+// Words of the device status buffer (global memory, one per executor).
+enum StatusWord : int {
+    ST_ABORT = 0,   // non-zero once any core has raised an error: every spin loop on the device polls it
+    ST_CODE = 1,    // the VDC_E* code (stored negated, i.e. positive)
+    ST_CORE = 2,
+    ST_ROLE = 3,    // see Role
+    ST_PC = 4,      // stream-relative pc of the uop the unit was at
+    ST_DETAIL = 5,
+    ST_WORDS = 8
+};
+
+enum Role : uint32_t { ROLE_CFU = 0, ROLE_LDU = 1, ROLE_STU = 2, ROLE_VCC = 3 };
+
+struct KParams {
+    const Word *words;
+    const uint32_t *stream_begin;
+    const Desc *descs;
+    char *tensors[kMaxTensors];
+    uint32_t *dep;          // depId counters
+    uint32_t *status;       // ST_WORDS words
+    uint32_t *trace;        // optional: n_streams * trace_cap * 4 words
+    uint32_t *trace_count;  // optional: n_streams words
+    uint32_t trace_cap;
+    uint32_t n_slots, slot_bytes, n_ldu, n_stu, V;
+    uint32_t watchdog;
+};
+
+// Bytes of dynamic LDS one workgroup needs for n_slots slots of slot_bytes plus the control block.
+size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes);
+size_t lds_control_bytes();
+
+// Launch the persistent virtual-core kernel: one workgroup per core.
+hipError_t launch_executor(const KParams &p, uint32_t n_cores, bool traced, hipStream_t stream);
+// Raise the kernel's dynamic LDS limit; call once per device before the first launch.
+hipError_t prepare_executor_kernels(size_t lds_bytes);
+// Zero n words (a fill kernel; safe inside stream capture, unlike a memset node).
+hipError_t launch_clear(uint32_t *p, uint32_t n, hipStream_t stream);
+hipError_t launch_debug_alloc(const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n,
+                              hipStream_t stream);
+
+}  // namespace vdc
+#endif

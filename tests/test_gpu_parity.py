@@ -1,0 +1,231 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar: integer work (allocator positions, per-unit uop traces with their generated addresses) bit-exact against
+the oracle interpreter; floating point |Y_gpu - Y_ref| <= 1e-5 * sum_j |M_ij X_bj| per output against the fp64
+GEMV (products and sums in fp64).  Any accumulation order within that bound is a correct result.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_03190_amd as vdc
+import workloads
+from oracle import gemv_ref, uop_asm as A, uop_machine as UM
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _check(Y_gpu, Yr, Ya, what=""):
+    err = np.abs(Y_gpu.astype(np.float64) - Yr)
+    bound = TOL * Ya + 1e-30
+    worst = float((err / bound).max())
+    assert worst <= 1.0, "%s: error is %.3g times the bound" % (what, worst)
+    return worst
+
+
+@pytest.fixture(scope="module")
+def ex():
+    e = vdc.Executor()
+    yield e
+    e.destroy()
+
+
+def test_simt_allocator_matches_first_fit_bit_exactly(ex):
+    rng = np.random.default_rng(0)
+    n = 20000
+    masks = rng.integers(0, 1 << 32, n, dtype=np.uint64)
+    masks[::3] |= rng.integers(0, 1 << 32, len(masks[::3]), dtype=np.uint64)      # denser masks
+    masks[:64] = [(1 << i) - 1 for i in range(32)] + [0xFFFFFFFF ^ (1 << i) for i in range(32)]
+    masks = masks.astype(np.uint32)
+    for n_slots in (32, 19, 7):
+        ns = rng.integers(1, 5, n).astype(np.int32)
+        ns[:8] = [1, 2, 3, 4, 8, 16, 19, 32]
+        pos = ex.debug_alloc(_dev(masks.view(np.int32)), _dev(ns), n_slots).cpu().numpy()
+        exp = np.array([UM.first_fit(int(m), int(k), n_slots) for m, k in zip(masks, ns)], dtype=np.int32)
+        assert np.array_equal(pos, exp)
+
+
+DENSE_CASES = [
+    # rows, K, ld, B, tile_bytes
+    (128, 128, 128, 1, 4096),          # configuration 1
+    (1000, 1000, 1000, 1, 4096),       # row and K tails everywhere
+    (517, 2052, 2060, 3, 8192),        # leading dimension, odd sizes, B = 3
+    (2048, 4096, 4096, 8, 16384),
+    (70000, 128, 128, 2, 8192),        # many row blocks per core, one K tile
+    (3, 8, 8, 1, 2048),                # less than one tile
+    (4096, 512, 512, 5, 2048),
+    (1024, 8192, 8192, 7, 16384),
+]
+
+
+@pytest.mark.parametrize("rows,K,ld,B,T", DENSE_CASES)
+def test_dense_matvec_against_fp64_gemv(ex, rows, K, ld, B, T):
+    rng = np.random.default_rng(rows + K + B)
+    M = rng.standard_normal((rows, ld)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    dM, dX = _dev(M), _dev(X)
+    dY = torch.full((B, rows), float("nan"), device="cuda")
+    ex.matvec(dM, dX, dY, T, K=K)
+    ex.check()
+    Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
+    _check(dY.cpu().numpy(), Yr, Ya, "dense %s" % ((rows, K, ld, B, T),))
+
+
+def test_closed_forms_on_the_gpu(ex):
+    rows, K = 3000, 1536
+    M = np.repeat((np.arange(rows) % 1024).astype(np.float32)[:, None], K, axis=1)
+    dY = torch.empty((1, rows), device="cuda")
+    ex.matvec(_dev(M), torch.ones((1, K), device="cuda"), dY, 8192)
+    ex.check()
+    assert np.array_equal(dY.cpu().numpy()[0], (K * (np.arange(rows) % 1024)).astype(np.float32))   # exact in fp32
+    # identity block: y = x bit for bit
+    x = np.random.default_rng(1).standard_normal((2, 256)).astype(np.float32)
+    dY = torch.empty((2, 256), device="cuda")
+    ex.matvec(torch.eye(256, device="cuda"), _dev(x), dY, 4096)
+    ex.check()
+    assert np.array_equal(dY.cpu().numpy(), x)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2"])
+def test_uop_traces_and_result_match_the_interpreter(name):
+    """Configurations 1 and 2: the address trace of every unit is bit-exact against the sequential interpreter
+    running the same uop graph, and the result matches the fp64 GEMV."""
+    cfg = workloads.CONFIGS[name]
+    w_ = workloads.make(cfg, device="cuda")
+    M, X = w_.M.cpu().numpy(), w_.X.cpu().numpy()
+    with vdc.Executor(slot_bytes=cfg.slot_bytes) as ex:
+        nc, ns = ex.cfg.n_cores, ex.cfg.n_slots
+        words, sb, descs = ex.matvec_program(cfg.rows, cfg.K, cfg.K, cfg.B, cfg.tile_bytes)
+        prog = ex.program_create(words, sb, descs, [M.nbytes, X.nbytes, cfg.B * cfg.rows * 4])
+        dY = torch.full((cfg.B, cfg.rows), float("nan"), device="cuda")
+        cap = 4096
+        trace, count = ex.run(prog, [w_.M, w_.X, dY], trace_cap=cap)
+        ex.check()
+        trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+    Yo = np.full((cfg.B, cfg.rows), np.nan, np.float32)
+    m = UM.Machine(words, sb, descs, [M, X, Yo], n_cores=nc, slot_bytes=cfg.slot_bytes, n_slots=ns).run()
+    V = 2
+    for core in range(nc):
+        s = core * (1 + V)
+        exp = [(pc, op | (d << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, d, off, n) in m.trace_vmc[core]]
+        assert count[s] == len(exp) <= cap
+        assert [tuple(int(x) for x in r) for r in trace[s, :len(exp)]] == exp
+        for v in range(V):
+            exp = [(pc, op | (n << 16), imm & 0xFFFFFFFF, imm >> 32) for (pc, op, n, imm) in m.trace_vcc[core][v]]
+            assert count[s + 1 + v] == len(exp)
+            assert [tuple(int(x) for x in r) for r in trace[s + 1 + v, :len(exp)]] == exp
+    Yr, Ya = gemv_ref.gemv_dense(M, X)
+    _check(dY.cpu().numpy(), Yr, Ya, name)
+    _check(Yo, Yr, Ya, name + " (interpreter)")
+
+
+def test_programs_assembled_by_the_oracle_side_run_on_the_gpu():
+    """uop graphs that no product code produced (oracle-side assembler), through vdc_program_create / vdc_run."""
+    rng = np.random.default_rng(3)
+    with vdc.Executor(n_cores=8, slot_bytes=2048, n_slots=16) as ex:
+        for build, (rows, K, B, R, Kt) in [(A.dense_matvec_program, (200, 328, 3, 16, 64)),
+                                           (A.looped_matvec_program, (512, 384, 2, 8, 128)),
+                                           (A.dense_matvec_program, (64, 2048, 1, 1, 1024))]:
+            M = rng.standard_normal((rows, K)).astype(np.float32)
+            X = rng.standard_normal((B, K)).astype(np.float32)
+            p = build(rows, K, K, B, R, Kt, 2048, 8, nt=True)
+            words, sb, descs = p.finish()
+            prog = ex.program_create(words, sb, descs, [M.nbytes, X.nbytes, B * rows * 4])
+            dY = torch.full((B, rows), float("nan"), device="cuda")
+            trace, count = ex.run(prog, [_dev(M), _dev(X), dY], trace_cap=2048)
+            ex.check()
+            Yr, Ya = gemv_ref.gemv_dense(M, X)
+            _check(dY.cpu().numpy(), Yr, Ya, build.__name__)
+            Yo = np.zeros((B, rows), np.float32)
+            m = UM.Machine(words, sb, descs, [M, X, Yo], n_cores=8, slot_bytes=2048, n_slots=16).run()
+            trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+            for core in range(8):
+                exp = [(pc, op | (d << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, d, off, n) in m.trace_vmc[core]]
+                assert count[core * 3] == len(exp)
+                assert [tuple(int(x) for x in r) for r in trace[core * 3, :len(exp)]] == exp
+            prog.destroy()
+
+
+def test_ragged_batch(ex):
+    rng = np.random.default_rng(4)
+    K = 128
+    row_off = np.array([0, 700, 700, 716, 5000, 5001, 9000, 20000], dtype=np.int64)
+    M = rng.standard_normal((20000, K)).astype(np.float32)
+    X = rng.standard_normal((7, K)).astype(np.float32)
+    dY = torch.full((20000,), float("nan"), device="cuda")
+    ex.matvec_ragged(_dev(M), row_off, _dev(X), dY, 8192)
+    ex.check()
+    Yr, Ya = gemv_ref.gemv_ragged(M, row_off, X)
+    _check(dY.cpu().numpy(), Yr, Ya, "ragged")
+
+
+def test_dep_id_chain_between_two_memory_cores():
+    """y = M2 (M1 x): core 0 stores t = M1 x and signals depId 5; core 1 waits for it with load.dep."""
+    rng = np.random.default_rng(12)
+    M1 = rng.standard_normal((128, 64)).astype(np.float32)
+    M2 = rng.standard_normal((128, 128)).astype(np.float32)
+    x = rng.standard_normal((1, 64)).astype(np.float32)
+    p = A.Program(2, 1)
+    d_m1, d_x, d_t = p.desc(0, 128, 256, 256, 256), p.desc(1, 1, 256, 256, 256), p.desc(2, 1, 512, 512, 512)
+    d_m2, d_y = p.desc(3, 128, 512, 512, 512), p.desc(4, 1, 512, 512, 512)
+    p.vmc(0).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=8, size=128, desc=d_m1),
+                     A.word(A.LOAD, A.F_SEND, vflow=1, nslots=1, size=1, desc=d_x),
+                     A.word(A.STORE, A.F_SEND | A.F_RECV | A.F_DEP_SEND, vflow=2, nslots=1, size=1, desc=d_t, dep_id=5)])
+    p.vcc(0, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 128, 16)))
+    p.vmc(1).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=16, size=128, desc=d_m2),
+                     A.word(A.LOAD, A.F_SEND | A.F_DEP_RECV, vflow=1, nslots=1, size=1, desc=d_t, dep_id=5, dep_count=1),
+                     A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=2, nslots=1, size=1, desc=d_y)])
+    p.vcc(1, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 128, 32)))
+    words, sb, descs = p.finish()
+    with vdc.Executor(n_cores=2, vcc_per_core=1, slot_bytes=4096, n_slots=20) as ex:
+        prog = ex.program_create(words, sb, descs, [M1.nbytes, x.nbytes, 512, M2.nbytes, 512])
+        for _ in range(5):
+            dt = torch.full((1, 128), float("nan"), device="cuda")
+            dy = torch.full((1, 128), float("nan"), device="cuda")
+            ex.run(prog, [_dev(M1), _dev(x), dt, _dev(M2), dy])
+            ex.check()
+            t = dt.cpu().numpy()
+            tr, ta = gemv_ref.gemv_dense(M1, x)
+            _check(t, tr, ta, "t")
+            yr, ya = gemv_ref.gemv_dense(M2, t)          # from the t the device actually produced
+            _check(dy.cpu().numpy(), yr, ya, "y")
+
+
+def test_watchdog_reports_deadlock_and_the_grid_drains():
+    """A spin limit far below the latency of a tile load: some unit gives up, every wave leaves its loop, the
+    kernel ends normally and the error comes back through the status word; the device stays usable."""
+    rng = np.random.default_rng(7)
+    M = rng.standard_normal((4096, 4096)).astype(np.float32)
+    X = rng.standard_normal((1, 4096)).astype(np.float32)
+    dM, dX = _dev(M), _dev(X)
+    dY = torch.zeros((1, 4096), device="cuda")
+    with vdc.Executor(watchdog_spins=64) as ex:
+        ex.matvec(dM, dX, dY, 8192)
+        rc, info = ex.sync_status()
+        assert rc == vdc.VDC_EDEADLOCK, (rc, info)
+        rc, info = ex.sync_status()              # the status was cleared
+        assert rc == vdc.VDC_OK
+    with vdc.Executor() as ex:
+        ex.matvec(dM, dX, dY, 8192)
+        ex.check()
+        Yr, Ya = gemv_ref.gemv_dense(M, X)
+        _check(dY.cpu().numpy(), Yr, Ya, "after watchdog")
+
+
+def test_invalid_arguments_are_refused(ex):
+    dM = torch.zeros((64, 64), device="cuda")
+    dX = torch.zeros((1, 64), device="cuda")
+    dY = torch.zeros((1, 64), device="cuda")
+    L = vdc.lib()
+    s = 0
+    assert L.vdc_matvec(ex.handle, dM.data_ptr(), 64, 64, 64, dX.data_ptr(), dY.data_ptr(), 1, 5000, s) == vdc.VDC_EINVAL
+    assert L.vdc_matvec(ex.handle, dM.data_ptr(), 64, 62, 64, dX.data_ptr(), dY.data_ptr(), 1, 4096, s) == vdc.VDC_EINVAL
+    assert L.vdc_matvec(ex.handle, dM.data_ptr() + 4, 64, 60, 64, dX.data_ptr(), dY.data_ptr(), 1, 4096, s) == vdc.VDC_EINVAL
+    assert L.vdc_matvec(ex.handle, dM.data_ptr(), 64, 64, 64, dX.data_ptr(), dY.data_ptr(), 9, 4096, s) == vdc.VDC_EINVAL
+    assert L.vdc_matvec(ex.handle, None, 64, 64, 64, dX.data_ptr(), dY.data_ptr(), 1, 4096, s) == vdc.VDC_EINVAL
+    assert L.vdc_matvec(ex.handle, dM.data_ptr(), 0, 64, 64, dX.data_ptr(), dY.data_ptr(), 1, 4096, s) == vdc.VDC_EINVAL

@@ -1,0 +1,154 @@
+"""CPU tests of the library's host side: the C ABI loads and exports every declared symbol, the matvec tiler's
+uop graphs run to the right result on the oracle interpreter, and the validator accepts / rejects what it should.
+No compute call needs a GPU here: the executor is created host-only (device = -1)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_03190_amd as vdc
+import workloads
+from oracle import gemv_ref, uop_asm as A, uop_machine as UM
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "vdcores.h")).read()
+    declared = set(re.findall(r"\b(vdc_[a-z_]+)\s*\(", header))
+    declared -= {"vdc_config"}
+    assert declared == set(vdc.EXPORTS), declared ^ set(vdc.EXPORTS)
+    L = ctypes.CDLL(vdc.LIB_PATH)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_strerror_and_defaults_are_the_paper_deployment():
+    assert vdc.strerror(0) == "ok" and "watchdog" in vdc.strerror(vdc.VDC_EDEADLOCK)
+    with vdc.Executor(device=-1) as ex:
+        c = ex.cfg
+        # Table 1 caption: 1 VMC + 2 VCCs per CU, 8 KB slots; Section 4.3: 128 threads per execution unit, 32-bit mask
+        assert (c.vcc_per_core, c.slot_bytes, c.threads_per_eu) == (2, 8192, 128)
+        assert 1 <= c.n_slots <= 32 and c.n_slots * c.slot_bytes <= 160 * 1024
+        assert c.n_cores == 256 and c.n_ldu == 2 and c.n_stu == 1
+
+
+def test_bad_configs_are_rejected():
+    for bad in (dict(slot_bytes=3000), dict(n_slots=33), dict(vcc_per_core=3), dict(threads_per_eu=64),
+                dict(n_ldu=3), dict(slot_bytes=16384, n_slots=11)):
+        with pytest.raises(vdc.VdcError) as e:
+            vdc.Executor(device=-1, **bad)
+        assert e.value.code == vdc.VDC_EINVAL
+
+
+CASES = [
+    # rows, K, ld, B, tile_bytes, n_cores, slot_bytes, n_slots
+    (128, 128, 128, 1, 4096, 4, 4096, 12),      # cfg1 shape on four cores
+    (100, 200, 212, 3, 4096, 3, 4096, 12),      # row tail, K tail, leading dimension
+    (37, 1000, 1000, 8, 2048, 2, 2048, 16),
+    (300, 64, 64, 2, 4096, 5, 4096, 8),
+    (64, 2048, 2048, 1, 16384, 2, 8192, 10),
+    (5, 12, 12, 1, 2048, 4, 1024, 8),           # fewer row blocks than compute cores
+]
+
+
+@pytest.mark.parametrize("rows,K,ld,B,T,ncores,slot,nslots", CASES)
+def test_tiler_program_on_the_oracle_interpreter(rows, K, ld, B, T, ncores, slot, nslots):
+    rng = np.random.default_rng(rows * 7 + K)
+    M = rng.standard_normal((rows, ld)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    Y = np.full((B, rows), np.nan, np.float32)
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
+        w, sb, d = ex.matvec_program(rows, K, ld, B, T)
+        rc, msg = ex.program_validate(w, sb, d, [((rows - 1) * ld + K) * 4, X.nbytes, Y.nbytes])
+        assert rc == vdc.VDC_OK, msg
+    for sched, seed in (("program", 0), ("random", 1)):
+        Y[:] = np.nan
+        UM.Machine(w, sb, d, [M, X, Y], n_cores=ncores, slot_bytes=slot, n_slots=nslots).run(sched, seed)
+        Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
+        assert np.all(np.abs(Y - Yr) <= 1e-7 * Ya + 1e-30)
+
+
+def test_ragged_tiler_program_on_the_oracle_interpreter():
+    rng = np.random.default_rng(5)
+    K = 64
+    row_off = np.array([0, 5, 5, 40, 41, 100, 260, 277], dtype=np.int64)
+    M = rng.standard_normal((277, K)).astype(np.float32)
+    X = rng.standard_normal((7, K)).astype(np.float32)
+    Y = np.full(277, np.nan, np.float32)
+    with vdc.Executor(device=-1, n_cores=4, slot_bytes=4096, n_slots=12) as ex:
+        w, sb, d = ex.matvec_program(277, K, K, 1, 4096, row_off=row_off)
+        rc, msg = ex.program_validate(w, sb, d, [M.nbytes, X.nbytes, Y.nbytes])
+        assert rc == vdc.VDC_OK, msg
+    UM.Machine(w, sb, d, [M, X, Y], n_cores=4, slot_bytes=4096, n_slots=12).run("random", 2)
+    Yr, Ya = gemv_ref.gemv_ragged(M, row_off, X)
+    assert np.all(np.abs(Y - Yr) <= 1e-7 * Ya + 1e-30)
+
+
+def test_zipf_ragged_program_balances_bytes_over_cores():
+    # the config-4 recipe on 16 cores: every core gets the same number of row blocks, within one
+    row_off = workloads.zipf_segments(1 << 14, 64, 1.1, 3)
+    with vdc.Executor(device=-1, n_cores=16, slot_bytes=8192, n_slots=19) as ex:
+        w, sb, d = ex.matvec_program(1 << 14, 128, 128, 1, 8192, row_off=row_off)
+        rc, msg = ex.program_validate(w, sb, d, [(1 << 14) * 512, 64 * 512, (1 << 14) * 4])
+        assert rc == vdc.VDC_OK, msg
+    M = np.zeros((1 << 14, 128), np.float32)
+    X = np.zeros((64, 128), np.float32)
+    Y = np.zeros(1 << 14, np.float32)
+    m = UM.Machine(w, sb, d, [M, X, Y], n_cores=16, slot_bytes=8192, n_slots=19).run()
+    loads = [sum(1 for r in t if r[1] == UM.LOAD and r[2] == 0 or r[1] == UM.LOAD and m.descs[r[2]].tensor == 0)
+             for t in m.trace_vmc]
+    assert max(loads) - min(loads) <= 1
+
+
+def test_validator_rejects_broken_programs():
+    with vdc.Executor(device=-1, n_cores=1, vcc_per_core=1, slot_bytes=1024, n_slots=4) as ex:
+        M, X, Y = 16 * 64 * 4, 64 * 4, 16 * 4
+
+        def check(mutate, expect_ok=False):
+            p = A.dense_matvec_program(16, 64, 64, 1, 16, 32, 1024, 1, vcc_per_core=1)
+            mutate(p)
+            w, sb, d = p.finish()
+            rc, msg = ex.program_validate(w, sb, d, [M, X, Y])
+            assert (rc == vdc.VDC_OK) == expect_ok, msg
+            return msg
+
+        check(lambda p: None, expect_ok=True)
+        # address beyond the tensor
+        def far(p):
+            u = UM.decode(p.vmc(0)[0])
+            p.vmc(0)[0] = A.word(A.LOAD, u.flags, vflow=u.vflow, vcc=u.vcc, nslots=u.nslots, size=u.size, imm=M - 64, desc=u.desc)
+        assert "beyond" in check(far)
+        # a send removed: the compute core starves
+        def nosend(p):
+            u = UM.decode(p.vmc(0)[1])
+            p.vmc(0)[1] = A.word(A.LOAD, 0, vflow=u.vflow, vcc=u.vcc, nslots=u.nslots, size=u.size, imm=u.imm, desc=u.desc)
+        check(nosend)
+        # wrong slot count
+        def slots(p):
+            u = UM.decode(p.vmc(0)[0])
+            p.vmc(0)[0] = A.word(A.LOAD, u.flags, vflow=u.vflow, vcc=u.vcc, nslots=3, size=u.size, imm=u.imm, desc=u.desc)
+        assert "nslots" in check(slots)
+        # matvec geometry that no handler exists for (7 chunks per row)
+        def geom(p):
+            p.vcc(0, 0)[0] = A.word(A.MATVEC, size=2, imm=A.matvec_imm(1, 16, 7))
+        check(geom)
+        # REPEAT without LOOP, memory opcode on a compute core
+        check(lambda p: p.vmc(0).insert(0, A.word(A.REPEAT)))
+        check(lambda p: p.vcc(0, 0).insert(0, A.word(A.LOAD)))
+    # over-committed slots: the matrix tile takes the whole pool (the deadlock case of Section 4.3)
+    with vdc.Executor(device=-1, n_cores=1, vcc_per_core=1, slot_bytes=1024, n_slots=2) as ex:
+        p = A.dense_matvec_program(8, 64, 64, 1, 8, 64, 1024, 1, vcc_per_core=1)      # matrix tile = 2 KB = both slots
+        w, sb, d = p.finish()
+        rc, msg = ex.program_validate(w, sb, d, [8 * 64 * 4, 64 * 4, 32])
+        assert rc == vdc.VDC_EPROGRAM and "deadlock" in msg
+
+
+def test_device_entry_points_refuse_a_host_only_executor():
+    with vdc.Executor(device=-1, n_cores=2) as ex:
+        w, sb, d = ex.matvec_program(64, 64, 64, 1, 4096)
+        with pytest.raises(vdc.VdcError) as e:
+            ex.program_create(w, sb, d, [64 * 64 * 4, 256, 256])
+        assert e.value.code == vdc.VDC_EINVAL
