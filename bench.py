@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: one step = one pass of the whole uop graph of the matvec operator
+(vdc_matvec: fetch/decode, address generation, slot allocation, tile loads, matvec uops, result stores) over the
+resident synthetic inputs of one configuration.  Prints ONE JSON line on stdout; everything else goes to stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg5_b1|cfg3|cfg4|cfg2|cfg1]
+
+metric  = matrix elements per second on one GPU (one element = one fp32 matrix entry, each used for B vectors)
+roofline = algorithmic HBM bytes of one launch / mean duration of the executor kernel, against 8 TB/s
+cpu_baseline = the oracle (plain fp64 C loops, one thread) timed on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the factors a plain copy
+# kernel of known size gives); see profiles/ for the runs.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(rows, K, B, n_x_rows):
+    """Bytes one launch must move through HBM: every matrix entry once, the vectors once, the result once.
+    (Vector tiles re-read by other cores come from the L2 / Infinity Cache and are not counted.)"""
+    return 4 * rows * K + 4 * n_x_rows * K + 4 * B * rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported. "
+            "The number to quote is the one-GPU throughput." % args.gpus)
+        sys.exit(2)
+
+    import torch
+    import paper_2605_03190_amd as vdc
+    import workloads
+    vdc.lib()                                  # fails loudly when the HIP extension is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = workloads.CONFIGS[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    w = workloads.make(cfg, device=dev)
+    rows, K, B = cfg.rows, cfg.K, cfg.B
+    ragged = w.row_off is not None
+    Y = torch.full((rows,) if ragged else (B, rows), float("nan"), device=dev)
+    # configurations whose matrix fits the 256 MB Infinity Cache are rotated over several copies so that every
+    # launch reads from HBM ("cold")
+    n_copies = 1
+    if w.M.numel() * 4 <= 512 << 20:
+        n_copies = max(1, min(8, (2 << 30) // (w.M.numel() * 4)))
+    Ms = [w.M] + [w.M.clone() for _ in range(n_copies - 1)]
+    torch.cuda.synchronize()
+    log("inputs: %s rows=%d K=%d B=%d tile=%d ragged=%s copies=%d (%.1f s)" % (cfg.name, rows, K, B, cfg.tile_bytes, ragged, n_copies, time.time() - t0))
+
+    ex = vdc.Executor(slot_bytes=cfg.slot_bytes)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        M = Ms[i % n_copies]
+        if ragged:
+            ex.matvec_ragged(M, w.row_off, w.X, Y, cfg.tile_bytes, stream=stream)
+        else:
+            ex.matvec(M, w.X, Y, cfg.tile_bytes, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    ex.check(stream)
+
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record(stream)
+        step(i)
+        ends[i].record(stream)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_begin
+    ex.check(stream)
+    kern_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
+    kern_avg_ms = float(np.mean(kern_ms))
+    ms_per_step = t_total * 1e3 / args.steps
+    elements = rows * K
+    value = elements * args.steps / t_total
+    alg = algorithmic_bytes(rows, K, B, w.X.shape[0])
+    achieved = alg / (kern_avg_ms * 1e-3) / 1e9
+    log("steps=%d total=%.3f ms  per step %.4f ms  kernel avg %.4f ms (min %.4f max %.4f)  %.3e elements/s  %.1f GB/s = %.1f%% of %.0f"
+        % (args.steps, t_total * 1e3, ms_per_step, kern_avg_ms, min(kern_ms), max(kern_ms), value, achieved,
+           100 * achieved / HBM_PEAK_GBS, HBM_PEAK_GBS))
+
+    out = {
+        "metric": "hot-path matrix elements/sec at 1 GPU",
+        "value": value,
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s %dx%d fp32, B=%d, %d KB tiles, %d KB slots, seed %d" % (
+            cfg.name, "ragged %d segments" % cfg.n_seg if ragged else "dense", rows, K, B, cfg.tile_bytes // 1024,
+            cfg.slot_bytes // 1024, cfg.seed), "rows": rows, "K": K, "B": B, "tile_bytes": cfg.tile_bytes},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                     "kernel": "vdc_executor_kernel", "kernel_avg_ms": kern_avg_ms, "algorithmic_bytes": alg},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import gemv_ref
+        gemv_ref.build()
+        # bounded sample: the first rows of the matrix (of the first segments when ragged), all K columns, all B vectors
+        Xh = w.X.cpu().numpy()
+        probe = min(rows, 64)
+
+        def run_oracle(n):
+            Mh = w.M[:n].cpu().numpy()
+            t = time.perf_counter()
+            if ragged:
+                ro = np.minimum(w.row_off, n)
+                Yr, Ya = gemv_ref.gemv_ragged(Mh, ro, Xh)
+            else:
+                Yr, Ya = gemv_ref.gemv_dense(Mh, Xh)
+            return time.perf_counter() - t, Yr, Ya
+
+        tp, _, _ = run_oracle(probe)
+        n = int(min(rows, max(probe, probe * args.cpu_seconds / max(tp, 1e-6))))
+        if not ragged:
+            n = max(probe, n // 64 * 64)
+        tc, Yr, Ya = run_oracle(n)
+        Yg = Y[:n].cpu().numpy() if ragged else Y[:, :n].cpu().numpy()
+        worst = float((np.abs(Yg - Yr) / (1e-5 * Ya + 1e-30)).max())
+        log("oracle sample: %d rows in %.2f s -> %.3e elements/s; GPU vs oracle on the sample: error = %.3g of the bound" % (n, tc, n * K / tc, worst))
+        if worst > 1.0:
+            log("PARITY FAILURE on the sampled rows")
+            sys.exit(1)
+        out["cpu_baseline"] = {"value": n * K / tc, "unit": "elements/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d of %d rows, all %d columns, B=%d; plain fp64 C loops, one thread; %.1f s" % (n, rows, K, B, tc)}
+    ex.destroy()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

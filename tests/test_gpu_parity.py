@@ -167,26 +167,26 @@ def test_ragged_batch(ex):
 def test_dep_id_chain_between_two_memory_cores():
     """y = M2 (M1 x): core 0 stores t = M1 x and signals depId 5; core 1 waits for it with load.dep."""
     rng = np.random.default_rng(12)
-    M1 = rng.standard_normal((128, 64)).astype(np.float32)
-    M2 = rng.standard_normal((128, 128)).astype(np.float32)
+    M1 = rng.standard_normal((64, 64)).astype(np.float32)
+    M2 = rng.standard_normal((64, 64)).astype(np.float32)
     x = rng.standard_normal((1, 64)).astype(np.float32)
     p = A.Program(2, 1)
-    d_m1, d_x, d_t = p.desc(0, 128, 256, 256, 256), p.desc(1, 1, 256, 256, 256), p.desc(2, 1, 512, 512, 512)
-    d_m2, d_y = p.desc(3, 128, 512, 512, 512), p.desc(4, 1, 512, 512, 512)
-    p.vmc(0).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=8, size=128, desc=d_m1),
+    d_m1, d_x, d_t = p.desc(0, 64, 256, 256, 256), p.desc(1, 1, 256, 256, 256), p.desc(2, 1, 256, 256, 256)
+    d_m2, d_y = p.desc(3, 64, 256, 256, 256), p.desc(4, 1, 256, 256, 256)
+    p.vmc(0).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=4, size=64, desc=d_m1),
                      A.word(A.LOAD, A.F_SEND, vflow=1, nslots=1, size=1, desc=d_x),
                      A.word(A.STORE, A.F_SEND | A.F_RECV | A.F_DEP_SEND, vflow=2, nslots=1, size=1, desc=d_t, dep_id=5)])
-    p.vcc(0, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 128, 16)))
-    p.vmc(1).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=16, size=128, desc=d_m2),
+    p.vcc(0, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 64, 16)))
+    p.vmc(1).extend([A.word(A.LOAD, A.F_SEND, vflow=0, nslots=4, size=64, desc=d_m2),
                      A.word(A.LOAD, A.F_SEND | A.F_DEP_RECV, vflow=1, nslots=1, size=1, desc=d_t, dep_id=5, dep_count=1),
                      A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=2, nslots=1, size=1, desc=d_y)])
-    p.vcc(1, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 128, 32)))
+    p.vcc(1, 0).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(1, 64, 16)))
     words, sb, descs = p.finish()
     with vdc.Executor(n_cores=2, vcc_per_core=1, slot_bytes=4096, n_slots=20) as ex:
-        prog = ex.program_create(words, sb, descs, [M1.nbytes, x.nbytes, 512, M2.nbytes, 512])
+        prog = ex.program_create(words, sb, descs, [M1.nbytes, x.nbytes, 256, M2.nbytes, 256])
         for _ in range(5):
-            dt = torch.full((1, 128), float("nan"), device="cuda")
-            dy = torch.full((1, 128), float("nan"), device="cuda")
+            dt = torch.full((1, 64), float("nan"), device="cuda")
+            dy = torch.full((1, 64), float("nan"), device="cuda")
             ex.run(prog, [_dev(M1), _dev(x), dt, _dev(M2), dy])
             ex.check()
             t = dt.cpu().numpy()
