@@ -23,6 +23,7 @@ struct vdc_program {
     Word *d_words = nullptr;
     uint32_t *d_stream_begin = nullptr;
     Desc *d_descs = nullptr;
+    int32_t n_descs = 0;
     int32_t n_tensors = 0;
     int64_t tensor_bytes[kMaxTensors] = {0};
     bool uses_dep = false;
@@ -563,6 +564,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.words = prog->d_words;
     p.stream_begin = prog->d_stream_begin;
     p.descs = prog->d_descs;
+    p.n_descs = (uint32_t)prog->n_descs;
     for (int i = 0; i < n_tensors; i++) {
         if (!tensor_bases[i] || ((uintptr_t)tensor_bases[i] & 3u)) return VDC_EINVAL;
         p.tensors[i] = (char *)tensor_bases[i];
@@ -673,6 +675,7 @@ int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const
     std::unique_ptr<vdc_program> p(new (std::nothrow) vdc_program());
     if (!p) return VDC_ENOMEM;
     p->ex = ex;
+    p->n_descs = n_descs;
     p->n_tensors = n_tensors;
     for (int i = 0; i < n_tensors; i++) p->tensor_bytes[i] = tensor_bytes[i];
     p->uses_dep = val.uses_dep;

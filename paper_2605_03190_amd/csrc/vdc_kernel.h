@@ -26,6 +26,7 @@ struct KParams {
     const Word *words;
     const uint32_t *stream_begin;
     const Desc *descs;
+    uint32_t n_descs;
     char *tensors[kMaxTensors];
     uint32_t *dep;          // depId counters
     uint32_t *status;       // ST_WORDS words

@@ -14,10 +14,18 @@
 //   next n_stu waves            STU   waits for the produced region, LDS -> global, frees the slots, signals depId
 //   next 2 * V waves            VCC   v = 0..V-1, two waves (128 threads) each: the compute uop handlers
 //
-// All queues live in LDS.  A waiter polls an LDS word with s_sleep back-off (no hardware de-scheduling
-// exists); every poll loop counts its iterations and raises VDC_EDEADLOCK at the watchdog limit, and every
-// loop also leaves when another unit or core has raised an error, so the grid always drains.
+// All queues live in LDS.  A waiter polls LDS with s_sleep back-off (no hardware de-scheduling exists);
+// every poll loop counts its iterations and raises VDC_EDEADLOCK at the watchdog limit, and every loop also
+// leaves when another unit or core has raised an error, so the grid always drains.
+//
+// What keeps the per-uop cost low (the paper's Section 4.3 asks for SIMT parallelism inside each unit):
+//   * a unit reads everything it must look at (queue heads, its next record, the slot mask, the abort flag)
+//     with ONE gathered LDS read, each lane fetching a different word, and one wait;
+//   * uop words are fetched 64 at a time into a register window (one lane per word) and picked with v_readlane;
+//     descriptors live in a register file of the same kind; no indexed state lives in memory;
+//   * the slot allocator is a wave vote (ballot + count-trailing-zeros).
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "vdc_isa.h"
@@ -36,6 +44,7 @@ constexpr int kMaxUnits = 4;   // n_ldu + n_stu
 constexpr int kMaxV = 2;
 constexpr int kMaxInflight = 4;  // tiles one LDU keeps in flight
 constexpr int kMaxVm = 56;       // outstanding load instructions one LDU allows itself (vmcnt holds 63)
+constexpr int kRecWords = 12;
 
 struct UnitRec {  // a memory uop after the front end (48 bytes)
     uint32_t gaddr_lo, gaddr_hi;
@@ -51,25 +60,28 @@ struct UnitRec {  // a memory uop after the front end (48 bytes)
 };
 
 struct Ctl {
+    // --- polled together by the CFU with one gathered LDS read: keep these six words contiguous ---
+    uint32_t uq_head[kMaxUnits];   // records consumed by each unit
     uint32_t mask;                 // slot availability: bit set = in use (Section 4.3: 32-bit mask in shared memory)
     uint32_t abort;                // set when any unit of this core gives up
+    // ---
     uint32_t cfu_halted;
     uint32_t vcc_done;             // VCC waves that reached HALT
-    uint32_t c2m_tail[kMaxV];      // next c2m position, taken with an atomic add by the pushing wave
+    uint32_t uq_tail[kMaxUnits];   // records pushed to each unit
     uint32_t mbox_tail[kMaxV];
-    uint32_t mbox_head[kMaxV];
+    uint32_t w1_done[kMaxV];       // tickets the second wave of a VCC is done with
     uint32_t red_flag[kMaxV];      // cross-wave reduction hand-shake of a VCC
     uint32_t red_ack[kMaxV];
-    uint32_t uq_tail[kMaxUnits];
-    uint32_t uq_head[kMaxUnits];
-    uint32_t pad0[2];
     uint64_t m2c[kMaxV][kM2C];     // low: slot | nslots << 6 | rows << 12; high: (ticket + 1) & 0xffff | row_bytes << 16
     uint64_t c2m[kMaxV][kC2M];     // low: kind | slot << 1 | nslots << 7; high: position + 1
-    uint32_t m2c_done[kMaxV][kM2C];  // how many of the two waves of the VCC are done with the entry
     uint32_t mbox[kMaxV][kMbox];
     UnitRec uq[kMaxUnits][kUQ];
     float red[kMaxV][64];
 };
+static_assert(offsetof(Ctl, mask) == offsetof(Ctl, uq_head) + 16 && offsetof(Ctl, abort) == offsetof(Ctl, mask) + 4, "poll block");
+static_assert(offsetof(Ctl, m2c) % 8 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0, "alignment");
+static_assert(sizeof(UnitRec) == 4 * kRecWords, "record size");
+#define CTL_OFF(field) ((uint32_t)offsetof(Ctl, field))
 
 size_t lds_control_bytes() { return (sizeof(Ctl) + 255) & ~(size_t)255; }
 size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes) {
@@ -91,7 +103,10 @@ DEV f32x4 lds_ld128(uint32_t off) { return *(const __attribute__((address_space(
 DEV void lds_st128(uint32_t off, u32x4 v) { *(__attribute__((address_space(3))) u32x4 *)(lds0() + off) = v; }
 DEV float lds_ldf(uint32_t off) { return *(const __attribute__((address_space(3))) float *)(lds0() + off); }
 DEV void lds_stf(uint32_t off, float v) { *(__attribute__((address_space(3))) float *)(lds0() + off) = v; }
-DEV uint32_t lds_ld32(uint32_t off) { return *(const __attribute__((address_space(3))) uint32_t *)(lds0() + off); }
+// volatile accesses to the control words: every call is one LDS instruction, never cached or merged
+DEV uint32_t lds_vld32(uint32_t off) { return ((lds_vu32 *)(lds0() + off))[0]; }
+DEV void lds_vst32(uint32_t off, uint32_t v) { ((lds_vu32 *)(lds0() + off))[0] = v; }
+DEV void lds_vst64(uint32_t off, uint64_t v) { ((lds_vu64 *)(lds0() + off))[0] = v; }
 
 DEV void compiler_barrier() { asm volatile("" ::: "memory"); }
 DEV void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
@@ -105,11 +120,24 @@ DEV uint64_t uni64(uint64_t x) {
 typedef const __attribute__((address_space(4))) uint32_t *cptr32;
 DEV uint32_t cload(const void *p, uint32_t idx) { return uni(((cptr32)(uintptr_t)p)[idx]); }
 
+// Indexed state (accumulators, loop stack, descriptors, the uop window, queue snapshots) is kept in "lane
+// register files": a vector register whose lane i holds entry i, read with v_readlane and written with
+// v_writelane under a wave-uniform index.  Nothing of a unit's register state lives in memory.
+DEV uint32_t rf_get(uint32_t v, uint32_t idx) { return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)idx); }
+DEV uint32_t rf_set(uint32_t v, uint32_t idx, uint32_t x) {
+    x = uni(x);
+    idx = uni(idx);
+    // one scalar register operand per vector instruction on this target: the lane select goes through M0;
+    // the nops keep the required distance between the scalar writes and the lane access
+    asm("s_mov_b32 m0, %2\n\ts_nop 3\n\tv_writelane_b32 %0, %1, m0" : "+v"(v) : "s"(x), "s"(idx));
+    return v;
+}
+
 struct Ctx {
     const KParams *p;
-    __attribute__((address_space(3))) Ctl *ctl;
+    uint32_t ctl;                     // byte offset of the control block in LDS
     uint32_t core, lane, role, unit;  // unit: LDU/STU index in the unit queues, or VCC index
-    uint32_t stream_pc0;              // first word of this unit's stream (CFU, VCC)
+    uint32_t stream_pc0;              // first word of this unit's stream
     uint32_t pc;                      // current word (for error reports)
     uint32_t spins_limit;
 };
@@ -128,7 +156,7 @@ DEV void raise_error(Ctx &c, int code, uint32_t detail) {
             st[ST_DETAIL] = detail;
             __threadfence();
         }
-        ((lds_vu32 *)&c.ctl->abort)[0] = 1u;
+        lds_vst32(c.ctl + CTL_OFF(abort), 1u);
     }
 }
 
@@ -136,51 +164,49 @@ struct Spin {
     uint32_t n = 0;
 };
 
-// One back-off step of a poll loop.  Returns false when the unit must give up (error raised somewhere,
-// or the watchdog limit is reached, in which case this unit raises VDC_EDEADLOCK).
-DEV bool spin_step(Ctx &c, Spin &s, uint32_t detail) {
+// One back-off step of a poll loop.  `aborted` is the core's abort word as the caller's poll saw it.  Returns
+// false when the unit must give up: an error was raised somewhere, or the watchdog limit is reached, in which
+// case this unit raises VDC_EDEADLOCK.
+DEV bool spin_step(Ctx &c, Spin &s, uint32_t aborted, uint32_t detail) {
+    if (aborted) return false;
     __builtin_amdgcn_s_sleep(1);
     s.n++;
-    if ((s.n & 31u) == 0u) {
-        if (uni(((lds_vu32 *)&c.ctl->abort)[0])) return false;
-        if ((s.n & 1023u) == 0u) {
-            uint32_t g = uni(__hip_atomic_load(&c.p->status[ST_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            if (g) return false;
-        }
-        if (s.n >= c.spins_limit) {
-            raise_error(c, -5 /* VDC_EDEADLOCK */, detail);
-            return false;
-        }
+    if ((s.n & 255u) == 0u) {
+        uint32_t g = uni(__hip_atomic_load(&c.p->status[ST_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if (g) return false;
+    }
+    if (s.n >= c.spins_limit) {
+        raise_error(c, -5 /* VDC_EDEADLOCK */, detail);
+        return false;
     }
     return true;
 }
 
 // ------------------------------------------------------------------------------------------------
-// Register state of a stream: pc, loop stack, accumulators (Section 4.1: "a lightweight register machine")
+// Register state of a stream: pc, loop stack, accumulators (Section 4.1: "a lightweight register machine"),
+// and the uop window
 // ------------------------------------------------------------------------------------------------
-// Indexed state (accumulators, loop stack) is kept in a "lane register file": one vector register whose lane i
-// holds entry i, read with v_readlane and written with v_writelane under a wave-uniform index.  Nothing of a
-// unit's register state lives in memory.
-DEV uint32_t rf_get(uint32_t v, uint32_t idx) { return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)idx); }
-DEV uint32_t rf_set(uint32_t v, uint32_t idx, uint32_t x) {
-    x = uni(x);
-    idx = uni(idx);
-    // one scalar register operand per vector instruction on this target: the lane select goes through M0;
-    // the nops keep the required distance between the scalar writes and the lane access
-    asm("s_mov_b32 m0, %2\n\ts_nop 3\n\tv_writelane_b32 %0, %1, m0" : "+v"(v) : "s"(x), "s"(idx));
-    return v;
-}
-
 struct Seq {
-    uint32_t pc, depth;
+    uint32_t pc, depth, end;
     uint32_t rf_lo, rf_hi;   // lanes 0..7: accumulator i (low, high word); lanes 8..11: loop level d (body start, trips left)
+    uint32_t win_base;       // the window holds words win_base .. win_base + 63 (lane l = word win_base + l)
+    u32x4 win;
 };
 
-DEV void seq_init(Seq &s, uint32_t pc) {
+DEV void seq_refill(Ctx &c, Seq &s) {
+    uint32_t idx = s.pc + c.lane;
+    if (idx >= s.end) idx = s.end - 1u;     // the stream's HALT
+    s.win = ((const u32x4 *)c.p->words)[idx];
+    s.win_base = s.pc;
+}
+
+DEV void seq_init(Ctx &c, Seq &s, uint32_t pc, uint32_t end) {
     s.pc = pc;
+    s.end = end;
     s.depth = 0;
     s.rf_lo = 0;
     s.rf_hi = 0;
+    seq_refill(c, s);
 }
 
 DEV int64_t seq_acc(const Seq &s, uint32_t a) {
@@ -192,12 +218,19 @@ DEV void seq_acc_set(Seq &s, uint32_t a, int64_t v) {
     s.rf_hi = rf_set(s.rf_hi, a, (uint32_t)((uint64_t)v >> 32));
 }
 
-DEV Word fetch(const KParams *p, uint32_t pc) {
+// Instruction fetch: 64 words per global load (one per lane), then v_readlane per uop.  Loop bodies of up to 64
+// uops run entirely out of the window.
+DEV Word fetch(Ctx &c, Seq &s) {
+    uint32_t k = s.pc - s.win_base;
+    if (k >= 64u) {
+        seq_refill(c, s);
+        k = 0;
+    }
     Word w;
-    w.w0 = cload(p->words, pc * 4 + 0);
-    w.w1 = cload(p->words, pc * 4 + 1);
-    w.w2 = cload(p->words, pc * 4 + 2);
-    w.w3 = cload(p->words, pc * 4 + 3);
+    w.w0 = rf_get(s.win.x, k);
+    w.w1 = rf_get(s.win.y, k);
+    w.w2 = rf_get(s.win.z, k);
+    w.w3 = rf_get(s.win.w, k);
     return w;
 }
 
@@ -283,63 +316,22 @@ __global__ void clear_kernel(uint32_t *p, uint32_t n) {
 // ------------------------------------------------------------------------------------------------
 // Queue primitives
 // ------------------------------------------------------------------------------------------------
+DEV uint32_t slot_bits(uint32_t slot, uint32_t nslots) {
+    return (nslots >= 32u ? 0xFFFFFFFFu : ((1u << nslots) - 1u)) << slot;
+}
+
 DEV void m2c_deliver(Ctx &c, uint32_t v, uint32_t ticket, uint32_t slot, uint32_t nslots, uint32_t rows, uint32_t row_bytes) {
     if (c.lane == 0) {
         uint64_t e = (uint64_t)(slot | (nslots << 6) | (rows << 12)) |
                      ((uint64_t)(((ticket + 1u) & 0xFFFFu) | (row_bytes << 16)) << 32);
-        ((lds_vu64 *)&c.ctl->m2c[v][ticket & (kM2C - 1)])[0] = e;
+        lds_vst64(c.ctl + CTL_OFF(m2c) + (v * kM2C + (ticket & (kM2C - 1))) * 8u, e);
     }
-}
-
-struct Msg {
-    uint32_t slot, nslots, rows, row_bytes;
-};
-
-// pop_wait of the listing: block until ticket `head` of m2c[v] has been delivered.
-DEV bool m2c_pop_wait(Ctx &c, uint32_t v, uint32_t head, Msg &m) {
-    lds_vu64 *e = (lds_vu64 *)&c.ctl->m2c[v][head & (kM2C - 1)];
-    const uint32_t want = (head + 1u) & 0xFFFFu;
-    Spin s;
-    for (;;) {
-        uint64_t x = uni64(e[0]);
-        uint32_t hi = (uint32_t)(x >> 32);
-        if ((hi & 0xFFFFu) == want) {
-            uint32_t lo = (uint32_t)x;
-            m.slot = lo & 63u;
-            m.nslots = (lo >> 6) & 63u;
-            m.rows = lo >> 12;
-            m.row_bytes = hi >> 16;
-            compiler_barrier();
-            return true;
-        }
-        if (!spin_step(c, s, 0x100u | v)) return false;
-    }
-}
-
-// push to c2m[v]: the two waves of a VCC both call this when they are done with ticket `head`; the second
-// one to arrive sends the message (kind 0 = used region to recycle, 1 = produced region).
-DEV void c2m_push_when_both_done(Ctx &c, uint32_t v, uint32_t head, const Msg &m, uint32_t kind) {
-    compiler_barrier();
-    if (c.lane == 0) {
-        __attribute__((address_space(3))) uint32_t *done =
-            (__attribute__((address_space(3))) uint32_t *)&c.ctl->m2c_done[v][head & (kM2C - 1)];
-        uint32_t old = __hip_atomic_fetch_add(done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (old == 1u) {
-            __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            uint32_t pos = __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)&c.ctl->c2m_tail[v], 1u,
-                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            uint64_t e = (uint64_t)(kind | (m.slot << 1) | (m.nslots << 7)) | ((uint64_t)(pos + 1u) << 32);
-            ((lds_vu64 *)&c.ctl->c2m[v][pos & (kC2M - 1)])[0] = e;
-        }
-    }
-    compiler_barrier();
 }
 
 DEV void slots_free(Ctx &c, uint32_t slot, uint32_t nslots) {
     if (c.lane == 0) {
-        uint32_t bits = (nslots >= 32u ? 0xFFFFFFFFu : ((1u << nslots) - 1u)) << slot;
-        __hip_atomic_fetch_and((__attribute__((address_space(3))) uint32_t *)&c.ctl->mask, ~bits, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_and((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
+                               ~slot_bits(slot, nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 }
 
@@ -353,85 +345,119 @@ struct CfuState {
     uint32_t uq_tail_rf;   // lane u: records pushed to unit u
 };
 
-DEV uint32_t uq_tail_get(const CfuState &st, uint32_t u) { return rf_get(st.uq_tail_rf, u); }
-DEV void uq_tail_inc(CfuState &st, uint32_t u) { st.uq_tail_rf = rf_set(st.uq_tail_rf, u, rf_get(st.uq_tail_rf, u) + 1u); }
-
-// Receiver of one c2m queue: used regions go back to the pool, produced regions to the STORE waiting for them.
-DEV void cfu_drain_one(Ctx &c, uint32_t v, uint32_t &c2m_head, uint32_t &mbox_tail) {
-    for (;;) {
-        uint64_t x = uni64(((lds_vu64 *)&c.ctl->c2m[v][c2m_head & (kC2M - 1)])[0]);
-        if ((uint32_t)(x >> 32) != c2m_head + 1u) break;
-        c2m_head++;
-        uint32_t lo = (uint32_t)x;
-        uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
-        if ((lo & 1u) == 0u) {
-            slots_free(c, slot, nslots);
-        } else {
-            if (c.lane == 0) {
-                ((lds_vu32 *)&c.ctl->mbox[v][mbox_tail & (kMbox - 1)])[0] = slot | (nslots << 6);
-                ((lds_vu32 *)&c.ctl->mbox_tail[v])[0] = mbox_tail + 1u;
-            }
-            mbox_tail++;
-        }
-    }
+// One gathered read of everything the front end looks at: lanes 0,1 = next c2m entry of VCC 0 (low, high),
+// lanes 2,3 = of VCC 1, lanes 4..7 = uq_head[0..3], lane 8 = slot mask, lane 9 = abort.
+DEV uint32_t cfu_poll(Ctx &c, const CfuState &st) {
+    const uint32_t e0 = c.ctl + CTL_OFF(c2m) + (st.c2m_head0 & (kC2M - 1)) * 8u;
+    const uint32_t e1 = c.ctl + CTL_OFF(c2m) + (kC2M + (st.c2m_head1 & (kC2M - 1))) * 8u;
+    const uint32_t l = c.lane < 9u ? c.lane : 9u;
+    uint32_t off = c.ctl + CTL_OFF(uq_head) + (l - 4u) * 4u;
+    off = c.lane < 4u ? e1 + (c.lane - 2u) * 4u : off;
+    off = c.lane < 2u ? e0 + c.lane * 4u : off;
+    return lds_vld32(off);
 }
 
-DEV void cfu_drain(Ctx &c, CfuState &st) {
-    cfu_drain_one(c, 0u, st.c2m_head0, st.mbox_tail0);
-    if (c.p->V > 1u) cfu_drain_one(c, 1u, st.c2m_head1, st.mbox_tail1);
+// Receiver of the c2m queues (on the snapshot `snap` of cfu_poll): a used region goes back to the pool, a produced
+// region to the STORE that waits for it.  Returns the number of messages taken (at most one per queue).
+DEV uint32_t cfu_receive(Ctx &c, CfuState &st, uint32_t snap, uint32_t &mask) {
+    uint32_t taken = 0;
+    {
+        const uint32_t lo = rf_get(snap, 0), hi = rf_get(snap, 1);
+        if (hi == st.c2m_head0 + 1u) {
+            st.c2m_head0++;
+            taken++;
+            const uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
+            if ((lo & 1u) == 0u) {
+                slots_free(c, slot, nslots);
+                mask &= ~slot_bits(slot, nslots);
+            } else {
+                if (c.lane == 0) {
+                    lds_vst32(c.ctl + CTL_OFF(mbox) + (st.mbox_tail0 & (kMbox - 1)) * 4u, slot | (nslots << 6));
+                    lds_vst32(c.ctl + CTL_OFF(mbox_tail), st.mbox_tail0 + 1u);
+                }
+                st.mbox_tail0++;
+            }
+        }
+    }
+    if (c.p->V > 1u) {
+        const uint32_t lo = rf_get(snap, 2), hi = rf_get(snap, 3);
+        if (hi == st.c2m_head1 + 1u) {
+            st.c2m_head1++;
+            taken++;
+            const uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
+            if ((lo & 1u) == 0u) {
+                slots_free(c, slot, nslots);
+                mask &= ~slot_bits(slot, nslots);
+            } else {
+                if (c.lane == 0) {
+                    lds_vst32(c.ctl + CTL_OFF(mbox) + (kMbox + (st.mbox_tail1 & (kMbox - 1))) * 4u, slot | (nslots << 6));
+                    lds_vst32(c.ctl + CTL_OFF(mbox_tail) + 4u, st.mbox_tail1 + 1u);
+                }
+                st.mbox_tail1++;
+            }
+        }
+    }
+    return taken;
 }
 
 DEV void cfu_main(Ctx &c) {
-    const bool TRACE = c.p->trace != nullptr;
     const KParams *p = c.p;
+    const bool TRACE = p->trace != nullptr;
     const uint32_t stream = c.core * (1u + p->V);
     Seq s;
-    seq_init(s, cload(p->stream_begin, stream));
+    seq_init(c, s, cload(p->stream_begin, stream), cload(p->stream_begin, stream + 1u));
     c.stream_pc0 = s.pc;
     CfuState st = {0, 0, 0, 0, 0, 0, 0};
     uint32_t trace_n = 0;
     const uint32_t slot_shift = __builtin_ctz(p->slot_bytes);
+    // descriptor register file: lane d holds descriptor d (the first 64; others are read from memory)
+    uint32_t d_tensor_rf, d_box_rf, d_rowb_rf, d_pitch_rf, d_gplo_rf, d_gphi_rf;
+    {
+        const uint32_t d = c.lane < p->n_descs ? c.lane : 0u;
+        const uint32_t *dp = (const uint32_t *)(p->descs + d);
+        d_tensor_rf = dp[0]; d_box_rf = dp[1]; d_rowb_rf = dp[2]; d_pitch_rf = dp[3]; d_gplo_rf = dp[4]; d_gphi_rf = dp[5];
+    }
     bool ok = true;
 
     while (ok) {
         c.pc = s.pc;
-        Word w = fetch(p, s.pc);
+        Word w = fetch(c, s);
         Fields f = decode(w);
         int ctl = seq_control(s, f);
         if (ctl == 2) break;
         if (ctl == 1) continue;
         // ---- a memory uop: address generation, slot allocation in program order, dispatch by virtual flow ----
-        const uint32_t dbase = f.desc * 8u;
-        const uint32_t d_tensor = cload(p->descs, dbase + 0), d_box = cload(p->descs, dbase + 1);
-        const uint32_t d_rowb = cload(p->descs, dbase + 2), d_pitch = cload(p->descs, dbase + 3);
-        const uint32_t d_gp_lo = cload(p->descs, dbase + 4), d_gp_hi = cload(p->descs, dbase + 5);
+        uint32_t d_tensor, d_box, d_rowb, d_pitch, d_gp_lo, d_gp_hi;
+        if (f.desc < 64u) {
+            d_tensor = rf_get(d_tensor_rf, f.desc); d_box = rf_get(d_box_rf, f.desc); d_rowb = rf_get(d_rowb_rf, f.desc);
+            d_pitch = rf_get(d_pitch_rf, f.desc); d_gp_lo = rf_get(d_gplo_rf, f.desc); d_gp_hi = rf_get(d_gphi_rf, f.desc);
+        } else {
+            const uint32_t dbase = f.desc * 8u;
+            d_tensor = cload(p->descs, dbase + 0); d_box = cload(p->descs, dbase + 1); d_rowb = cload(p->descs, dbase + 2);
+            d_pitch = cload(p->descs, dbase + 3); d_gp_lo = cload(p->descs, dbase + 4); d_gp_hi = cload(p->descs, dbase + 5);
+        }
         const bool is_load = f.opcode == OP_LOAD;
         const uint32_t unit = is_load ? (f.vflow % p->n_ldu) : (p->n_ldu + f.vflow % p->n_stu);
-        int64_t eff = f.imm + ((f.flags & F_DYNAMIC) ? seq_acc(s, f.acc) : 0);
+        const int64_t eff = f.imm + ((f.flags & F_DYNAMIC) ? seq_acc(s, f.acc) : 0);
+        const uint32_t tail = rf_get(st.uq_tail_rf, unit);
 
-        // room in the unit's queue
+        // wait for room in the unit's queue and, in program order, for the slots (in-order allocation)
+        int slot;
         Spin sp;
         for (;;) {
-            cfu_drain(c, st);
-            uint32_t head = uni(((lds_vu32 *)&c.ctl->uq_head[unit])[0]);
-            if (uq_tail_get(st, unit) - head < (uint32_t)kUQ) break;
-            if (!spin_step(c, sp, 0x200u | unit)) { ok = false; break; }
-        }
-        if (!ok) break;
-        // in-order allocation: stall right here until the request fits
-        int slot;
-        for (;;) {
-            uint32_t mask = uni(((lds_vu32 *)&c.ctl->mask)[0]);
+            const uint32_t snap = cfu_poll(c, st);
+            uint32_t mask = rf_get(snap, 8);
+            const uint32_t taken = cfu_receive(c, st, snap, mask);
+            const bool room = tail - rf_get(snap, 4u + unit) < (uint32_t)kUQ;
             slot = slot_find(mask, f.nslots, p->n_slots, c.lane);
-            if (slot >= 0) break;
-            cfu_drain(c, st);
-            if (!spin_step(c, sp, 0x300u | f.nslots)) { ok = false; break; }
+            if (room && slot >= 0) break;
+            if (taken) continue;     // something moved: look again at once
+            if (!spin_step(c, sp, rf_get(snap, 9), 0x300u | f.nslots | (room ? 0u : 0x80u))) { ok = false; break; }
         }
         if (!ok) break;
         if (c.lane == 0) {
-            uint32_t bits = (f.nslots >= 32u ? 0xFFFFFFFFu : ((1u << f.nslots) - 1u)) << slot;
-            __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)&c.ctl->mask, bits, __ATOMIC_RELAXED,
-                                  __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
+                                  slot_bits((uint32_t)slot, f.nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         uint32_t ticket = 0xFFFFFFFFu;
         if (f.flags & F_SEND) {
@@ -447,11 +473,9 @@ DEV void cfu_main(Ctx &c) {
         {
             // the tensor table sits in the kernel arguments: a uniform index makes this a scalar load
             const uint64_t base = uni64((uint64_t)(uintptr_t)p->tensors[d_tensor & (kMaxTensors - 1)]);
-            uint64_t gaddr = base + (uint64_t)eff;
-            const uint32_t tail = uq_tail_get(st, unit);
-            uint32_t idx = tail & (kUQ - 1);
+            const uint64_t gaddr = base + (uint64_t)eff;
             if (c.lane == 0) {
-                uint32_t off = (uint32_t)((size_t)&c.ctl->uq[unit][idx] - (size_t)lds0());
+                const uint32_t off = c.ctl + CTL_OFF(uq) + (unit * kUQ + (tail & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
                 u32x4 a = {(uint32_t)gaddr, (uint32_t)(gaddr >> 32), d_gp_lo, d_gp_hi};
                 u32x4 b = {(uint32_t)slot << slot_shift, f.size | (d_box << 16), d_rowb | (d_pitch << 16), w.w0};
                 u32x4 d = {ticket, (uint32_t)slot, f.dep_id | (f.dep_count << 16), s.pc - c.stream_pc0};
@@ -459,29 +483,33 @@ DEV void cfu_main(Ctx &c) {
                 lds_st128(off + 16, b);
                 lds_st128(off + 32, d);
                 compiler_barrier();
-                ((lds_vu32 *)&c.ctl->uq_tail[unit])[0] = tail + 1u;
+                lds_vst32(c.ctl + CTL_OFF(uq_tail) + unit * 4u, tail + 1u);
             }
-            uq_tail_inc(st, unit);
+            st.uq_tail_rf = rf_set(st.uq_tail_rf, unit, tail + 1u);
         }
         s.pc++;
     }
 
     // HALT (or error): no more dispatches.  Keep receiving c2m until the units and the compute cores are done.
-    if (c.lane == 0) ((lds_vu32 *)&c.ctl->cfu_halted)[0] = 1u;
+    if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(cfu_halted), 1u);
     Spin sp;
     while (ok) {
-        cfu_drain(c, st);
-        bool done = uni(((lds_vu32 *)&c.ctl->vcc_done)[0]) == 2u * p->V;
-        for (uint32_t u = 0; u < p->n_ldu + p->n_stu; u++)
-            done = done && (uni(((lds_vu32 *)&c.ctl->uq_head[u])[0]) == uq_tail_get(st, u));
-        if (done) break;
-        if (!spin_step(c, sp, 0x400u)) ok = false;
-    }
-    if (ok) {
-        cfu_drain(c, st);
-        lds_wait();
-        uint32_t mask = uni(((lds_vu32 *)&c.ctl->mask)[0]);
-        if (mask != 0u) raise_error(c, -6 /* VDC_ELEAK */, mask);
+        const uint32_t snap = cfu_poll(c, st);
+        uint32_t mask = rf_get(snap, 8);
+        const uint32_t taken = cfu_receive(c, st, snap, mask);
+        if (taken) continue;
+        bool done = uni(lds_vld32(c.ctl + CTL_OFF(vcc_done))) == 2u * p->V;
+        for (uint32_t u = 0; u < p->n_ldu + p->n_stu; u++) done = done && (rf_get(snap, 4u + u) == rf_get(st.uq_tail_rf, u));
+        if (done) {
+            // the compute cores have returned everything and the units are idle: one last look at the queues,
+            // then the pool must be empty
+            const uint32_t last = cfu_poll(c, st);
+            uint32_t m2 = rf_get(last, 8);
+            if (cfu_receive(c, st, last, m2)) continue;
+            if (m2 != 0u) raise_error(c, -6 /* VDC_ELEAK */, m2);
+            break;
+        }
+        if (!spin_step(c, sp, rf_get(snap, 9), 0x400u)) ok = false;
     }
 }
 
@@ -531,7 +559,7 @@ DEV bool dep_wait(Ctx &c, uint32_t dep) {
     for (;;) {
         uint32_t v = uni(__hip_atomic_load(&c.p->dep[id], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT));
         if (v >= need) return true;
-        if (!spin_step(c, s, 0x500u | id)) return false;
+        if (!spin_step(c, s, uni(lds_vld32(c.ctl + CTL_OFF(abort))), 0x500u | id)) return false;
     }
 }
 
@@ -548,8 +576,19 @@ DEV void ldu_retire(Ctx &c, const Inflight &t) {
     if (flags & F_DEP_SEND) dep_signal(c, t.dep);
 }
 
+// One gathered read of what a load/store unit looks at: lane 0 = uq_tail[u], lanes 1..12 = the record at `head`,
+// lane 13 = cfu_halted, lane 14 = abort, lanes 15,16 = mbox_tail[0..1].
+DEV uint32_t unit_poll(Ctx &c, uint32_t u, uint32_t head) {
+    const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
+    uint32_t off = c.ctl + CTL_OFF(mbox_tail) + (c.lane == 16u ? 4u : 0u);
+    off = c.lane == 14u ? c.ctl + CTL_OFF(abort) : off;
+    off = c.lane == 13u ? c.ctl + CTL_OFF(cfu_halted) : off;
+    off = c.lane <= 12u ? rec + (c.lane - 1u) * 4u : off;
+    off = c.lane == 0u ? c.ctl + CTL_OFF(uq_tail) + u * 4u : off;
+    return lds_vld32(off);
+}
+
 DEV void ldu_main(Ctx &c) {
-    const KParams *p = c.p;
     const uint32_t u = c.unit;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds0();
     // tiles in flight: a ring in a lane register file (lane k = entry k), oldest at fl_head
@@ -561,25 +600,19 @@ DEV void ldu_main(Ctx &c) {
     Spin sp;
     bool ok = true;
     while (ok) {
-        uint32_t tail = uni(((lds_vu32 *)&c.ctl->uq_tail[u])[0]);
-        compiler_barrier();
-        bool have = tail != head;
+        const uint32_t snap = unit_poll(c, u, head);
+        const bool have = rf_get(snap, 0) != head;
         uint32_t ni = 0;
         UnitRec r;
         if (have) {
-            uint32_t off = (uint32_t)((size_t)&c.ctl->uq[u][head & (kUQ - 1)] - (size_t)lds0());
-            f32x4 a = lds_ld128(off), b = lds_ld128(off + 16), d = lds_ld128(off + 32);
-            r.gaddr_lo = uni(__float_as_uint(a.x)); r.gaddr_hi = uni(__float_as_uint(a.y));
-            r.gpitch_lo = uni(__float_as_uint(a.z)); r.gpitch_hi = uni(__float_as_uint(a.w));
-            r.lds_off = uni(__float_as_uint(b.x)); r.rows_box = uni(__float_as_uint(b.y));
-            r.rb_pitch = uni(__float_as_uint(b.z)); r.w0 = uni(__float_as_uint(b.w));
-            r.ticket = uni(__float_as_uint(d.x)); r.slot = uni(__float_as_uint(d.y));
-            r.dep = uni(__float_as_uint(d.z)); r.pc = uni(__float_as_uint(d.w));
-            uint32_t chunks = (r.rows_box >> 16) * ((r.rb_pitch >> 16) >> 4);
+            r.gaddr_lo = rf_get(snap, 1); r.gaddr_hi = rf_get(snap, 2); r.gpitch_lo = rf_get(snap, 3); r.gpitch_hi = rf_get(snap, 4);
+            r.lds_off = rf_get(snap, 5); r.rows_box = rf_get(snap, 6); r.rb_pitch = rf_get(snap, 7); r.w0 = rf_get(snap, 8);
+            r.ticket = rf_get(snap, 9); r.slot = rf_get(snap, 10); r.dep = rf_get(snap, 11); r.pc = rf_get(snap, 12);
+            const uint32_t chunks = (r.rows_box >> 16) * ((r.rb_pitch >> 16) >> 4);
             ni = (chunks + 63u) >> 6;
         }
         // retire the oldest tile when nothing can be issued on top of what is in flight
-        bool can_issue = have && n_fl < (uint32_t)kMaxInflight && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
+        const bool can_issue = have && n_fl < (uint32_t)kMaxInflight && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
         if (!can_issue) {
             if (n_fl > 0) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
@@ -592,11 +625,10 @@ DEV void ldu_main(Ctx &c) {
                 sp.n = 0;
                 continue;
             }
-            if (!have) {
-                if (uni(((lds_vu32 *)&c.ctl->cfu_halted)[0]) && uni(((lds_vu32 *)&c.ctl->uq_tail[u])[0]) == head) break;
-                if (!spin_step(c, sp, 0x600u | u)) ok = false;
-                continue;
-            }
+            // idle
+            if (rf_get(snap, 13) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
+            if (!spin_step(c, sp, rf_get(snap, 14), 0x600u | u)) ok = false;
+            continue;
         }
         // ---- issue the loads of record r ----
         c.pc = c.stream_pc0 + r.pc;
@@ -621,8 +653,15 @@ DEV void ldu_main(Ctx &c) {
         const uint64_t gaddr = (uint64_t)r.gaddr_lo | ((uint64_t)r.gaddr_hi << 32);
         const uint64_t gpitch = (uint64_t)r.gpitch_lo | ((uint64_t)r.gpitch_hi << 32);
         const bool nt = (flags & F_NT) != 0;
-        uint32_t row = c.lane / cpr, col = c.lane % cpr;
-        const uint32_t drow = 64u / cpr, dcol = 64u % cpr;
+        uint32_t row, col, drow, dcol;
+        if ((cpr & (cpr - 1u)) == 0u) {                      // the usual case: a power of two
+            const uint32_t sh = __builtin_ctz(cpr);
+            row = c.lane >> sh; col = c.lane & (cpr - 1u);
+            drow = 64u >> sh; dcol = 64u & (cpr - 1u);
+        } else {
+            row = c.lane / cpr; col = c.lane % cpr;
+            drow = 64u / cpr; dcol = 64u % cpr;
+        }
         const bool full = rows == box_rows && vcr == cpr && (total & 63u) == 0u;
         for (uint32_t i = 0; i < ni; i++) {
             const uint32_t q = i * 64u + c.lane;
@@ -654,7 +693,7 @@ DEV void ldu_main(Ctx &c) {
         n_fl++;
         vm_out += ni;
         head++;
-        if (c.lane == 0) ((lds_vu32 *)&c.ctl->uq_head[u])[0] = head;
+        if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
         sp.n = 0;
     }
     // never leave with loads in flight: their LDS destination belongs to this workgroup only while it lives
@@ -672,49 +711,46 @@ DEV void ldu_main(Ctx &c) {
 // STU: produced region -> global memory
 // ------------------------------------------------------------------------------------------------
 DEV void stu_main(Ctx &c) {
-    const KParams *p = c.p;
     const uint32_t u = c.unit;
     uint32_t head = 0;
-    uint32_t mbox_head[kMaxV] = {0, 0};
+    uint32_t mbox_head0 = 0, mbox_head1 = 0;
     Spin sp;
     bool ok = true;
     while (ok) {
-        uint32_t tail = uni(((lds_vu32 *)&c.ctl->uq_tail[u])[0]);
-        if (tail == head) {
-            if (uni(((lds_vu32 *)&c.ctl->cfu_halted)[0]) && uni(((lds_vu32 *)&c.ctl->uq_tail[u])[0]) == head) break;
-            if (!spin_step(c, sp, 0x700u | u)) ok = false;
+        uint32_t snap = unit_poll(c, u, head);
+        if (rf_get(snap, 0) == head) {
+            if (rf_get(snap, 13) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
+            if (!spin_step(c, sp, rf_get(snap, 14), 0x700u | u)) ok = false;
             continue;
         }
         sp.n = 0;
-        compiler_barrier();
-        uint32_t off = (uint32_t)((size_t)&c.ctl->uq[u][head & (kUQ - 1)] - (size_t)lds0());
-        f32x4 a = lds_ld128(off), b = lds_ld128(off + 16), d = lds_ld128(off + 32);
-        const uint64_t gaddr = (uint64_t)uni(__float_as_uint(a.x)) | ((uint64_t)uni(__float_as_uint(a.y)) << 32);
-        const uint64_t gpitch = (uint64_t)uni(__float_as_uint(a.z)) | ((uint64_t)uni(__float_as_uint(a.w)) << 32);
-        const uint32_t lds_off = uni(__float_as_uint(b.x)), rows = uni(__float_as_uint(b.y)) & 0xFFFFu;
-        const uint32_t rb_pitch = uni(__float_as_uint(b.z)), w0 = uni(__float_as_uint(b.w));
-        const uint32_t slot = uni(__float_as_uint(d.y)), dep = uni(__float_as_uint(d.z));
-        c.pc = c.stream_pc0 + uni(__float_as_uint(d.w));
+        const uint64_t gaddr = (uint64_t)rf_get(snap, 1) | ((uint64_t)rf_get(snap, 2) << 32);
+        const uint64_t gpitch = (uint64_t)rf_get(snap, 3) | ((uint64_t)rf_get(snap, 4) << 32);
+        const uint32_t lds_off = rf_get(snap, 5), rows = rf_get(snap, 6) & 0xFFFFu;
+        const uint32_t rb_pitch = rf_get(snap, 7), w0 = rf_get(snap, 8);
+        const uint32_t slot = rf_get(snap, 10), dep = rf_get(snap, 11);
+        c.pc = c.stream_pc0 + rf_get(snap, 12);
         const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u, nslots = (w0 >> 25) & 63u;
         if (flags & F_DEP_RECV) {
             if (!dep_wait(c, dep)) { ok = false; break; }
         }
         if (flags & F_RECV) {
             // wait for the compute core to hand the region back as "produced"
-            uint32_t mh = vcc == 0u ? mbox_head[0] : mbox_head[1];
+            const uint32_t mh = vcc == 0u ? mbox_head0 : mbox_head1;
             Spin s2;
             for (;;) {
-                if (uni(((lds_vu32 *)&c.ctl->mbox_tail[vcc])[0]) != mh) break;
-                if (!spin_step(c, s2, 0x800u | vcc)) { ok = false; break; }
+                if (rf_get(snap, 15u + vcc) != mh) break;
+                if (!spin_step(c, s2, rf_get(snap, 14), 0x800u | vcc)) { ok = false; break; }
+                snap = unit_poll(c, u, head);
             }
             if (!ok) break;
-            uint32_t got = uni(((lds_vu32 *)&c.ctl->mbox[vcc][mh & (kMbox - 1)])[0]);
+            const uint32_t got = uni(lds_vld32(c.ctl + CTL_OFF(mbox) + (vcc * kMbox + (mh & (kMbox - 1))) * 4u));
             if (got != (slot | (nslots << 6))) {
                 raise_error(c, -3 /* VDC_EPROGRAM */, 0x900u | got);
                 ok = false;
                 break;
             }
-            if (vcc == 0u) mbox_head[0]++; else mbox_head[1]++;
+            if (vcc == 0u) mbox_head0++; else mbox_head1++;
             compiler_barrier();
         }
         const uint32_t row_words = (rb_pitch & 0xFFFFu) >> 2, lds_pitch = rb_pitch >> 16;
@@ -731,19 +767,94 @@ DEV void stu_main(Ctx &c) {
             dep_signal(c, dep);
         }
         head++;
-        if (c.lane == 0) ((lds_vu32 *)&c.ctl->uq_head[u])[0] = head;
+        if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // VCC: compute uop handlers
 // ------------------------------------------------------------------------------------------------
+// The two waves of an execution unit pop the same tickets.  A region may go back to the memory core only when
+// both are done with it: the second wave publishes how far it is (w1_done), the first wave pushes to c2m every
+// ticket that both have finished, in ticket order, from a small history of what it popped.
 struct VccState {
     uint32_t head;     // next m2c ticket to pop
+    uint32_t pushed;   // (first wave) tickets already returned through c2m
+    uint32_t hist;     // (first wave) lane (ticket & 63) = kind | slot << 1 | nslots << 7 of that ticket
     uint32_t red_seq;  // cross-wave reductions done so far
     uint32_t wv;       // which of the two waves of the execution unit this is
     uint32_t t;        // thread index inside the execution unit, 0..127
 };
+
+struct Msg {
+    uint32_t slot, nslots, rows, row_bytes;
+};
+
+// lanes 0,1 = m2c entry of ticket head (low, high), lanes 2,3 = of ticket head + 1, lane 4 = w1_done, lane 5 = abort
+DEV uint32_t vcc_poll(Ctx &c, uint32_t head) {
+    const uint32_t v = c.unit;
+    const uint32_t e0 = c.ctl + CTL_OFF(m2c) + (v * kM2C + (head & (kM2C - 1))) * 8u;
+    const uint32_t e1 = c.ctl + CTL_OFF(m2c) + (v * kM2C + ((head + 1u) & (kM2C - 1))) * 8u;
+    uint32_t off = c.ctl + CTL_OFF(abort);
+    off = c.lane == 4u ? c.ctl + CTL_OFF(w1_done) + v * 4u : off;
+    off = c.lane < 4u ? e1 + (c.lane - 2u) * 4u : off;
+    off = c.lane < 2u ? e0 + c.lane * 4u : off;
+    return lds_vld32(off);
+}
+
+// c2m.push for every ticket below `limit` that has not been pushed yet (first wave only)
+DEV void vcc_push_upto(Ctx &c, VccState &vs, uint32_t limit) {
+    const uint32_t v = c.unit;
+    while ((int32_t)(limit - vs.pushed) > 0) {
+        const uint32_t payload = rf_get(vs.hist, vs.pushed & 63u);
+        if (c.lane == 0)
+            lds_vst64(c.ctl + CTL_OFF(c2m) + (v * kC2M + (vs.pushed & (kC2M - 1))) * 8u,
+                      (uint64_t)payload | ((uint64_t)(vs.pushed + 1u) << 32));
+        vs.pushed++;
+    }
+}
+
+DEV bool msg_ready(uint32_t snap, uint32_t which, uint32_t ticket, Msg &m) {
+    const uint32_t lo = rf_get(snap, which * 2u), hi = rf_get(snap, which * 2u + 1u);
+    if ((hi & 0xFFFFu) != ((ticket + 1u) & 0xFFFFu)) return false;
+    m.slot = lo & 63u;
+    m.nslots = (lo >> 6) & 63u;
+    m.rows = lo >> 12;
+    m.row_bytes = hi >> 16;
+    return true;
+}
+
+// pop_wait of the listing for `n` (1 or 2) consecutive tickets.  `kind` is what the regions will be pushed back
+// as (0 = used, 1 = produced).  While it waits, the first wave keeps returning finished regions.
+DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, Msg &m1) {
+    Spin s;
+    for (;;) {
+        const uint32_t snap = vcc_poll(c, vs.head);
+        if (vs.wv == 0u) {
+            const uint32_t w1 = rf_get(snap, 4);
+            vcc_push_upto(c, vs, (int32_t)(w1 - vs.head) < 0 ? w1 : vs.head);
+        }
+        const bool r0 = msg_ready(snap, 0, vs.head, m0);
+        const bool r1 = n < 2u || msg_ready(snap, 1, vs.head + 1u, m1);
+        if (r0 && r1) {
+            if (vs.wv == 0u) {
+                vs.hist = rf_set(vs.hist, vs.head & 63u, kind | (m0.slot << 1) | (m0.nslots << 7));
+                if (n == 2u) vs.hist = rf_set(vs.hist, (vs.head + 1u) & 63u, kind | (m1.slot << 1) | (m1.nslots << 7));
+            }
+            compiler_barrier();
+            return true;
+        }
+        if (!spin_step(c, s, rf_get(snap, 5), 0x100u | c.unit)) return false;
+    }
+}
+
+// Called after the wave has finished reading (or writing) the regions of its last `n` tickets.
+DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n) {
+    compiler_barrier();
+    vs.head += n;
+    if (vs.wv == 1u && c.lane == 0) lds_vst32(c.ctl + CTL_OFF(w1_done) + c.unit * 4u, vs.head);
+    compiler_barrier();
+}
 
 DEV float dot4(f32x4 m, f32x4 x, float acc) {
     acc = __builtin_fmaf(m.x, x.x, acc);
@@ -763,8 +874,8 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
     const KParams *p = c.p;
     const uint32_t v = c.unit;
     const uint32_t slot_shift = __builtin_ctz(p->slot_bytes);
-    constexpr int NACC = (J == 0) ? NF : NF / (J == 0 ? 1 : J);
-    constexpr int NX = (J == 0) ? 1 : J;
+    constexpr int JJ = (J == 0) ? 1 : J;
+    constexpr int NACC = NF / JJ;
     float acc[NACC][B];                      // alloc_registers(NCREGS)
 #pragma unroll
     for (int i = 0; i < NACC; i++)
@@ -776,12 +887,11 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
 
     for (uint32_t it = 0; it < size; it++) {
         Msg ma, mb;
-        if (!m2c_pop_wait(c, v, vs.head, ma)) return false;         // a = m2c.pop_wait()
-        if (!m2c_pop_wait(c, v, vs.head + 1u, mb)) return false;    // b = m2c.pop_wait()
+        if (!vcc_pop_wait(c, vs, 2u, 0u, ma, mb)) return false;      // a = m2c.pop_wait(); b = m2c.pop_wait()
         const uint32_t a_off = ma.slot << slot_shift, b_off = mb.slot << slot_shift;
-        f32x4 xv[NX][B];
+        f32x4 xv[JJ][B];
 #pragma unroll
-        for (int j = 0; j < NX; j++)
+        for (int j = 0; j < JJ; j++)
 #pragma unroll
             for (int b = 0; b < B; b++) xv[j][b] = lds_ld128(b_off + (uint32_t)b * pitch + ((uint32_t)j * 128u + c4) * 16u);
         f32x4 m[NF];
@@ -789,20 +899,17 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
         for (int i = 0; i < NF; i++) m[i] = lds_ld128(a_off + ((uint32_t)i * 128u + t) * 16u);
 #pragma unroll
         for (int i = 0; i < NF; i++) {
-            constexpr int JJ = (J == 0) ? 1 : J;
             const int ai = (J == 0) ? i : i / JJ;
             const int xi = (J == 0) ? 0 : i % JJ;
 #pragma unroll
             for (int b = 0; b < B; b++) acc[ai][b] = dot4(m[i], xv[xi][b], acc[ai][b]);   // matvec_tile_accumulate
         }
-        // all LDS reads of both tiles have returned once their values were used; hand the regions back
-        c2m_push_when_both_done(c, v, vs.head, ma, 0u);              // c2m.push(a, b)
-        c2m_push_when_both_done(c, v, vs.head + 1u, mb, 0u);
-        vs.head += 2u;
+        // every LDS read of both tiles has returned once its value was used: the regions can go back
+        vcc_done_with(c, vs, 2u);                                    // c2m.push(a, b)
     }
 
-    Msg mo;
-    if (!m2c_pop_wait(c, v, vs.head, mo)) return false;              // c_shared = m2c.pop_wait()
+    Msg mo, unused;
+    if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;      // c_shared = m2c.pop_wait()
     const uint32_t o_off = mo.slot << slot_shift;
     if (J == 0) {
         const uint32_t lsh = __builtin_ctz(lpr);
@@ -827,17 +934,17 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
                 mine = (c.lane == (uint32_t)(r * B + b)) ? x : mine;
             }
         // the two waves of the execution unit each hold half of every row sum
-        const uint32_t red_off = (uint32_t)((size_t)&c.ctl->red[v][0] - (size_t)lds0());
+        const uint32_t red_off = c.ctl + CTL_OFF(red) + v * 256u;
         Spin s;
         if (vs.wv == 1u) {
-            while (uni(((lds_vu32 *)&c.ctl->red_ack[v])[0]) != vs.red_seq)
-                if (!spin_step(c, s, 0xA00u)) return false;
+            while (uni(lds_vld32(c.ctl + CTL_OFF(red_ack) + v * 4u)) != vs.red_seq)
+                if (!spin_step(c, s, uni(lds_vld32(c.ctl + CTL_OFF(abort))), 0xA00u)) return false;
             lds_stf(red_off + c.lane * 4u, mine);
             lds_wait();
-            if (c.lane == 0) ((lds_vu32 *)&c.ctl->red_flag[v])[0] = vs.red_seq + 1u;
+            if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(red_flag) + v * 4u, vs.red_seq + 1u);
         } else {
-            while (uni(((lds_vu32 *)&c.ctl->red_flag[v])[0]) != vs.red_seq + 1u)
-                if (!spin_step(c, s, 0xB00u)) return false;
+            while (uni(lds_vld32(c.ctl + CTL_OFF(red_flag) + v * 4u)) != vs.red_seq + 1u)
+                if (!spin_step(c, s, uni(lds_vld32(c.ctl + CTL_OFF(abort))), 0xB00u)) return false;
             compiler_barrier();
             mine += lds_ldf(red_off + c.lane * 4u);
             if (c.lane < (uint32_t)(NACC * B)) {
@@ -845,13 +952,12 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
                 lds_stf(o_off + (b * R + r) * 4u, mine);
             }
             lds_wait();
-            if (c.lane == 0) ((lds_vu32 *)&c.ctl->red_ack[v])[0] = vs.red_seq + 1u;
+            if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(red_ack) + v * 4u, vs.red_seq + 1u);
         }
         vs.red_seq++;
     }
     lds_wait();
-    c2m_push_when_both_done(c, v, vs.head, mo, 1u);                   // push the produced region
-    vs.head += 1u;
+    vcc_done_with(c, vs, 1u);                                         // push the produced region
     return true;
 }
 
@@ -891,19 +997,19 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
 // The control-flow unit of a VCC runs on the execution unit's own threads (Section 4.3, "Virtual Compute Core"):
 // each of its two waves decodes the stream, runs control uops itself and then yields to the uop handler.
 DEV void vcc_main(Ctx &c, uint32_t wv) {
-    const bool TRACE = c.p->trace != nullptr;
     const KParams *p = c.p;
+    const bool TRACE = p->trace != nullptr;
     const uint32_t stream = c.core * (1u + p->V) + 1u + c.unit;
     Seq s;
-    seq_init(s, cload(p->stream_begin, stream));
+    seq_init(c, s, cload(p->stream_begin, stream), cload(p->stream_begin, stream + 1u));
     c.stream_pc0 = s.pc;
     VccState vs;
-    vs.head = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
+    vs.head = 0; vs.pushed = 0; vs.hist = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
     uint32_t trace_n = 0;
     bool ok = true;
     while (ok) {
         c.pc = s.pc;
-        Word w = fetch(p, s.pc);
+        Word w = fetch(c, s);
         Fields f = decode(w);
         int ctl = seq_control(s, f);
         if (ctl == 2) break;
@@ -917,9 +1023,21 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         }
         s.pc++;
     }
+    if (ok && wv == 0u) {
+        // return whatever the second wave was still holding when this wave ran out of uops
+        Spin sp;
+        while (vs.pushed != vs.head) {
+            const uint32_t snap = vcc_poll(c, vs.head);
+            const uint32_t w1 = rf_get(snap, 4);
+            vcc_push_upto(c, vs, (int32_t)(w1 - vs.head) < 0 ? w1 : vs.head);
+            if (vs.pushed == vs.head) break;
+            if (!spin_step(c, sp, rf_get(snap, 5), 0xF00u)) break;
+        }
+    }
+    compiler_barrier();
     if (c.lane == 0)
-        __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)&c.ctl->vcc_done, 1u, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(vcc_done)), 1u,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -931,15 +1049,14 @@ __global__ void __launch_bounds__(512) vdc_executor_kernel(const KParams p) {
     c.p = &p;
     c.core = blockIdx.x;
     c.lane = threadIdx.x & 63u;
-    c.ctl = (__attribute__((address_space(3))) Ctl *)(lds0() + p.n_slots * p.slot_bytes);
+    c.ctl = p.n_slots * p.slot_bytes;
     c.spins_limit = p.watchdog;
     c.stream_pc0 = 0;
     c.pc = 0;
     // the control block starts at zero (slots need no initialisation)
     {
         const uint32_t words = (uint32_t)(sizeof(Ctl) / 4);
-        lds_vu32 *z = (lds_vu32 *)c.ctl;
-        for (uint32_t i = threadIdx.x; i < words; i += blockDim.x) z[i] = 0u;
+        for (uint32_t i = threadIdx.x; i < words; i += blockDim.x) lds_vst32(c.ctl + i * 4u, 0u);
     }
     __syncthreads();   // the only workgroup barrier: before the roles diverge
 
