@@ -109,6 +109,11 @@ DEV void lds_vst32(uint32_t off, uint32_t v) { ((lds_vu32 *)(lds0() + off))[0] =
 DEV void lds_vst64(uint32_t off, uint64_t v) { ((lds_vu64 *)(lds0() + off))[0] = v; }
 
 DEV void compiler_barrier() { asm volatile("" ::: "memory"); }
+// Placed right after every "if (lane == 0) { ... }" block: an opaque statement at the point where the lanes meet
+// again, so that the optimiser cannot fold that join into later joins (which would make later, wave-uniform values
+// look as if they depended on the per-lane branch).
+// The wave barrier is a convergent operation (so it is never cloned into the arms of the branch) and emits no code.
+DEV void reconverge() { __builtin_amdgcn_wave_barrier(); }
 DEV void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 DEV uint32_t uni(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 DEV uint64_t uni64(uint64_t x) {
@@ -158,6 +163,7 @@ DEV void raise_error(Ctx &c, int code, uint32_t detail) {
         }
         lds_vst32(c.ctl + CTL_OFF(abort), 1u);
     }
+    reconverge();
 }
 
 struct Spin {
@@ -273,7 +279,12 @@ DEV int seq_control(Seq &s, const Fields &f) {
     }
 }
 
+// A note that holds for every "if (lane == 0) { ... }" block in this file: a wave-uniform value that is used both
+// inside such a block and after it is computed BEFORE the block.  Otherwise the optimiser may compute it once in
+// each arm and merge the two copies behind the branch, and a value merged behind a divergent branch counts as
+// divergent: the loops around it would then be compiled with per-lane masks instead of scalar branches.
 DEV void trace_put(Ctx &c, uint32_t stream, uint32_t &count, uint32_t pc_rel, uint32_t info, uint64_t v) {
+    const uint32_t next = uni(count + 1u);
     if (c.lane == 0) {
         if (count < c.p->trace_cap) {
             uint32_t *t = c.p->trace + ((size_t)stream * c.p->trace_cap + count) * 4;
@@ -282,9 +293,10 @@ DEV void trace_put(Ctx &c, uint32_t stream, uint32_t &count, uint32_t pc_rel, ui
             t[2] = (uint32_t)v;
             t[3] = (uint32_t)(v >> 32);
         }
-        c.p->trace_count[stream] = count + 1;
+        c.p->trace_count[stream] = next;
     }
-    count++;
+    reconverge();
+    count = next;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -326,6 +338,7 @@ DEV void m2c_deliver(Ctx &c, uint32_t v, uint32_t ticket, uint32_t slot, uint32_
                      ((uint64_t)(((ticket + 1u) & 0xFFFFu) | (row_bytes << 16)) << 32);
         lds_vst64(c.ctl + CTL_OFF(m2c) + (v * kM2C + (ticket & (kM2C - 1))) * 8u, e);
     }
+    reconverge();
 }
 
 DEV void slots_free(Ctx &c, uint32_t slot, uint32_t nslots) {
@@ -333,6 +346,7 @@ DEV void slots_free(Ctx &c, uint32_t slot, uint32_t nslots) {
         __hip_atomic_fetch_and((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
                                ~slot_bits(slot, nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
+    reconverge();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -371,11 +385,13 @@ DEV uint32_t cfu_receive(Ctx &c, CfuState &st, uint32_t snap, uint32_t &mask) {
                 slots_free(c, slot, nslots);
                 mask &= ~slot_bits(slot, nslots);
             } else {
+                const uint32_t next = uni(st.mbox_tail0 + 1u);
                 if (c.lane == 0) {
                     lds_vst32(c.ctl + CTL_OFF(mbox) + (st.mbox_tail0 & (kMbox - 1)) * 4u, slot | (nslots << 6));
-                    lds_vst32(c.ctl + CTL_OFF(mbox_tail), st.mbox_tail0 + 1u);
+                    lds_vst32(c.ctl + CTL_OFF(mbox_tail), next);
                 }
-                st.mbox_tail0++;
+                reconverge();
+                st.mbox_tail0 = next;
             }
         }
     }
@@ -389,56 +405,102 @@ DEV uint32_t cfu_receive(Ctx &c, CfuState &st, uint32_t snap, uint32_t &mask) {
                 slots_free(c, slot, nslots);
                 mask &= ~slot_bits(slot, nslots);
             } else {
+                const uint32_t next = uni(st.mbox_tail1 + 1u);
                 if (c.lane == 0) {
                     lds_vst32(c.ctl + CTL_OFF(mbox) + (kMbox + (st.mbox_tail1 & (kMbox - 1))) * 4u, slot | (nslots << 6));
-                    lds_vst32(c.ctl + CTL_OFF(mbox_tail) + 4u, st.mbox_tail1 + 1u);
+                    lds_vst32(c.ctl + CTL_OFF(mbox_tail) + 4u, next);
                 }
-                st.mbox_tail1++;
+                reconverge();
+                st.mbox_tail1 = next;
             }
         }
     }
     return taken;
 }
 
+// The decoded uop window of the front end: lane l describes word win_base + l.  Decoding (field extraction,
+// descriptor lookup, flow -> unit mapping, tensor base + literal address) is done for 64 uops at once, one per
+// lane, when the window is (re)filled; executing a uop then only picks its lane with v_readlane.
+struct DecWin {
+    uint32_t base;       // first word in the window
+    uint32_t ctl;        // opcode [7:0] | flags [15:8] | unit [17:16] | vcc [19:18] | acc [22:20] | nslots [28:23] | tensor [31:29]
+    uint32_t a_lo, a_hi; // memory uop: tensor base + literal offset; control uop: the immediate
+    uint32_t gp_lo, gp_hi;
+    uint32_t rows_box;   // size | box_rows << 16
+    uint32_t rb_pitch;   // row_bytes | lds_pitch << 16
+    uint32_t w0;
+    uint32_t dep;        // depId | dep_count << 16 | desc << 24
+};
+
+DEV void cfu_refill(Ctx &c, DecWin &d, uint32_t pc, uint32_t end) {
+    const KParams *p = c.p;
+    uint32_t idx = pc + c.lane;
+    if (idx >= end) idx = end - 1u;             // the stream's HALT
+    const u32x4 raw = ((const u32x4 *)p->words)[idx];
+    Word w = {raw.x, raw.y, raw.z, raw.w};
+    const Fields f = decode(w);
+    const bool is_mem = f.opcode == OP_LOAD || f.opcode == OP_STORE;
+    const uint32_t di = (is_mem && f.desc < p->n_descs) ? f.desc : 0u;
+    const uint32_t *dp = (const uint32_t *)(p->descs + di);
+    const uint32_t d_tensor = dp[0], d_box = dp[1], d_rowb = dp[2], d_pitch = dp[3];
+    uint64_t tbase = 0;
+#pragma unroll
+    for (int t = 0; t < kMaxTensors; t++) tbase = ((d_tensor & (kMaxTensors - 1)) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tbase;
+    const uint32_t unit = f.opcode == OP_LOAD ? (p->n_ldu > 1u ? (f.vflow & 1u) : 0u) : p->n_ldu;
+    const uint64_t a = (uint64_t)f.imm + (is_mem ? tbase : 0ull);
+    d.base = pc;
+    d.ctl = f.opcode | (f.flags << 8) | (unit << 16) | (f.vcc << 18) | (f.acc << 20) | (f.nslots << 23) | ((d_tensor & 7u) << 29);
+    d.a_lo = (uint32_t)a;
+    d.a_hi = (uint32_t)(a >> 32);
+    d.gp_lo = dp[4];
+    d.gp_hi = dp[5];
+    d.rows_box = f.size | (d_box << 16);
+    d.rb_pitch = d_rowb | (d_pitch << 16);
+    d.w0 = w.w0;
+    d.dep = f.dep_id | (f.dep_count << 16) | (f.desc << 24);
+}
+
 DEV void cfu_main(Ctx &c) {
     const KParams *p = c.p;
     const bool TRACE = p->trace != nullptr;
-    const uint32_t stream = c.core * (1u + p->V);
+    const uint32_t V = p->V, n_slots = p->n_slots, n_units = p->n_ldu + p->n_stu;
+    const uint32_t stream = c.core * (1u + V);
     Seq s;
-    seq_init(c, s, cload(p->stream_begin, stream), cload(p->stream_begin, stream + 1u));
+    s.pc = cload(p->stream_begin, stream);
+    s.end = cload(p->stream_begin, stream + 1u);
+    s.depth = 0; s.rf_lo = 0; s.rf_hi = 0; s.win_base = 0; s.win = u32x4{0u, 0u, 0u, 0u};
     c.stream_pc0 = s.pc;
     CfuState st = {0, 0, 0, 0, 0, 0, 0};
     uint32_t trace_n = 0;
     const uint32_t slot_shift = __builtin_ctz(p->slot_bytes);
-    // descriptor register file: lane d holds descriptor d (the first 64; others are read from memory)
-    uint32_t d_tensor_rf, d_box_rf, d_rowb_rf, d_pitch_rf, d_gplo_rf, d_gphi_rf;
-    {
-        const uint32_t d = c.lane < p->n_descs ? c.lane : 0u;
-        const uint32_t *dp = (const uint32_t *)(p->descs + d);
-        d_tensor_rf = dp[0]; d_box_rf = dp[1]; d_rowb_rf = dp[2]; d_pitch_rf = dp[3]; d_gplo_rf = dp[4]; d_gphi_rf = dp[5];
-    }
+    DecWin d;
+    cfu_refill(c, d, s.pc, s.end);
     bool ok = true;
 
     while (ok) {
         c.pc = s.pc;
-        Word w = fetch(c, s);
-        Fields f = decode(w);
-        int ctl = seq_control(s, f);
-        if (ctl == 2) break;
-        if (ctl == 1) continue;
-        // ---- a memory uop: address generation, slot allocation in program order, dispatch by virtual flow ----
-        uint32_t d_tensor, d_box, d_rowb, d_pitch, d_gp_lo, d_gp_hi;
-        if (f.desc < 64u) {
-            d_tensor = rf_get(d_tensor_rf, f.desc); d_box = rf_get(d_box_rf, f.desc); d_rowb = rf_get(d_rowb_rf, f.desc);
-            d_pitch = rf_get(d_pitch_rf, f.desc); d_gp_lo = rf_get(d_gplo_rf, f.desc); d_gp_hi = rf_get(d_gphi_rf, f.desc);
-        } else {
-            const uint32_t dbase = f.desc * 8u;
-            d_tensor = cload(p->descs, dbase + 0); d_box = cload(p->descs, dbase + 1); d_rowb = cload(p->descs, dbase + 2);
-            d_pitch = cload(p->descs, dbase + 3); d_gp_lo = cload(p->descs, dbase + 4); d_gp_hi = cload(p->descs, dbase + 5);
+        uint32_t k = s.pc - d.base;
+        if (k >= 64u) {
+            cfu_refill(c, d, s.pc, s.end);
+            k = 0;
         }
-        const bool is_load = f.opcode == OP_LOAD;
-        const uint32_t unit = is_load ? (f.vflow % p->n_ldu) : (p->n_ldu + f.vflow % p->n_stu);
-        const int64_t eff = f.imm + ((f.flags & F_DYNAMIC) ? seq_acc(s, f.acc) : 0);
+        const uint32_t ctlw = rf_get(d.ctl, k);
+        const uint32_t opcode = ctlw & 0xFFu;
+        const uint32_t acc = (ctlw >> 20) & 7u;
+        const uint64_t a = (uint64_t)rf_get(d.a_lo, k) | ((uint64_t)rf_get(d.a_hi, k) << 32);
+        if (opcode < (uint32_t)OP_LOAD) {
+            Fields f;
+            f.opcode = opcode;
+            f.acc = acc;
+            f.imm = (int64_t)a;
+            const int r = seq_control(s, f);
+            if (r == 2) break;
+            continue;
+        }
+        // ---- a memory uop: address generation, slot allocation in program order, dispatch by virtual flow ----
+        const uint32_t flags = (ctlw >> 8) & 0xFFu, unit = (ctlw >> 16) & 3u, vcc = (ctlw >> 18) & 3u, nslots = (ctlw >> 23) & 63u;
+        const bool is_load = opcode == (uint32_t)OP_LOAD;
+        const uint64_t gaddr = a + ((flags & F_DYNAMIC) ? (uint64_t)seq_acc(s, acc) : 0ull);
         const uint32_t tail = rf_get(st.uq_tail_rf, unit);
 
         // wait for room in the unit's queue and, in program order, for the slots (in-order allocation)
@@ -449,57 +511,63 @@ DEV void cfu_main(Ctx &c) {
             uint32_t mask = rf_get(snap, 8);
             const uint32_t taken = cfu_receive(c, st, snap, mask);
             const bool room = tail - rf_get(snap, 4u + unit) < (uint32_t)kUQ;
-            slot = slot_find(mask, f.nslots, p->n_slots, c.lane);
+            slot = slot_find(mask, nslots, n_slots, c.lane);
             if (room && slot >= 0) break;
             if (taken) continue;     // something moved: look again at once
-            if (!spin_step(c, sp, rf_get(snap, 9), 0x300u | f.nslots | (room ? 0u : 0x80u))) { ok = false; break; }
+            if (!spin_step(c, sp, rf_get(snap, 9), 0x300u | nslots | (room ? 0u : 0x80u))) { ok = false; break; }
         }
         if (!ok) break;
-        if (c.lane == 0) {
-            __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
-                                  slot_bits((uint32_t)slot, f.nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
         uint32_t ticket = 0xFFFFFFFFu;
-        if (f.flags & F_SEND) {
-            if (f.vcc == 0u) ticket = st.ticket0++;
+        if (flags & F_SEND) {
+            if (vcc == 0u) ticket = st.ticket0++;
             else ticket = st.ticket1++;
         }
-        if (TRACE) trace_put(c, stream, trace_n, s.pc - c.stream_pc0, f.opcode | (f.desc << 8) | (f.size << 16), (uint64_t)eff);
-        if (!is_load && (f.flags & F_SEND)) {
-            // the empty output region goes to the compute core at once; the store unit only waits for it to return
-            m2c_deliver(c, f.vcc, ticket, (uint32_t)slot, f.nslots, f.size, d_rowb);
+        const uint32_t rows_box = rf_get(d.rows_box, k), rb_pitch = rf_get(d.rb_pitch, k);
+        const uint32_t w0 = rf_get(d.w0, k), dep = rf_get(d.dep, k);
+        const uint32_t gp_lo = rf_get(d.gp_lo, k), gp_hi = rf_get(d.gp_hi, k);
+        if (TRACE) {
+            const uint64_t tb = uni64((uint64_t)(uintptr_t)p->tensors[ctlw >> 29]);
+            trace_put(c, stream, trace_n, s.pc - c.stream_pc0, opcode | ((dep >> 24) << 8) | ((rows_box & 0xFFFFu) << 16), gaddr - tb);
         }
-        // hand the decoded uop to its unit
-        {
-            // the tensor table sits in the kernel arguments: a uniform index makes this a scalar load
-            const uint64_t base = uni64((uint64_t)(uintptr_t)p->tensors[d_tensor & (kMaxTensors - 1)]);
-            const uint64_t gaddr = base + (uint64_t)eff;
-            if (c.lane == 0) {
-                const uint32_t off = c.ctl + CTL_OFF(uq) + (unit * kUQ + (tail & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
-                u32x4 a = {(uint32_t)gaddr, (uint32_t)(gaddr >> 32), d_gp_lo, d_gp_hi};
-                u32x4 b = {(uint32_t)slot << slot_shift, f.size | (d_box << 16), d_rowb | (d_pitch << 16), w.w0};
-                u32x4 d = {ticket, (uint32_t)slot, f.dep_id | (f.dep_count << 16), s.pc - c.stream_pc0};
-                lds_st128(off, a);
-                lds_st128(off + 16, b);
-                lds_st128(off + 32, d);
-                compiler_barrier();
-                lds_vst32(c.ctl + CTL_OFF(uq_tail) + unit * 4u, tail + 1u);
+        // everything that is written happens in one lane: slot mask, the early hand-over of an output region,
+        // the decoded uop for its unit
+        const uint32_t tail_next = uni(tail + 1u), pc_rel = uni(s.pc - c.stream_pc0), pc_next = uni(s.pc + 1u);
+        const uint32_t uslot = uni((uint32_t)slot);
+        if (c.lane == 0) {
+            __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
+                                  slot_bits(uslot, nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (!is_load && (flags & F_SEND)) {
+                // the empty output region goes to the compute core at once; the store unit only waits for it to return
+                const uint64_t e = (uint64_t)(uslot | (nslots << 6) | ((rows_box & 0xFFFFu) << 12)) |
+                                   ((uint64_t)(((ticket + 1u) & 0xFFFFu) | ((rb_pitch & 0xFFFFu) << 16)) << 32);
+                lds_vst64(c.ctl + CTL_OFF(m2c) + (vcc * kM2C + (ticket & (kM2C - 1))) * 8u, e);
             }
-            st.uq_tail_rf = rf_set(st.uq_tail_rf, unit, tail + 1u);
+            const uint32_t off = c.ctl + CTL_OFF(uq) + (unit * kUQ + (tail & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
+            u32x4 ra = {(uint32_t)gaddr, (uint32_t)(gaddr >> 32), gp_lo, gp_hi};
+            u32x4 rb = {uslot << slot_shift, rows_box, rb_pitch, w0};
+            u32x4 rd = {ticket, uslot, dep & 0xFFFFFFu, pc_rel};
+            lds_st128(off, ra);
+            lds_st128(off + 16, rb);
+            lds_st128(off + 32, rd);
+            compiler_barrier();
+            lds_vst32(c.ctl + CTL_OFF(uq_tail) + unit * 4u, tail_next);
         }
-        s.pc++;
+        reconverge();
+        st.uq_tail_rf = rf_set(st.uq_tail_rf, unit, tail_next);
+        s.pc = pc_next;
     }
 
     // HALT (or error): no more dispatches.  Keep receiving c2m until the units and the compute cores are done.
     if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(cfu_halted), 1u);
+    reconverge();
     Spin sp;
     while (ok) {
         const uint32_t snap = cfu_poll(c, st);
         uint32_t mask = rf_get(snap, 8);
         const uint32_t taken = cfu_receive(c, st, snap, mask);
         if (taken) continue;
-        bool done = uni(lds_vld32(c.ctl + CTL_OFF(vcc_done))) == 2u * p->V;
-        for (uint32_t u = 0; u < p->n_ldu + p->n_stu; u++) done = done && (rf_get(snap, 4u + u) == rf_get(st.uq_tail_rf, u));
+        bool done = uni(lds_vld32(c.ctl + CTL_OFF(vcc_done))) == 2u * V;
+        for (uint32_t u = 0; u < n_units; u++) done = done && (rf_get(snap, 4u + u) == rf_get(st.uq_tail_rf, u));
         if (done) {
             // the compute cores have returned everything and the units are idle: one last look at the queues,
             // then the pool must be empty
@@ -553,7 +621,7 @@ struct Inflight {   // what an LDU must do once the loads of a tile have landed
 };
 
 DEV bool dep_wait(Ctx &c, uint32_t dep) {
-    uint32_t id = dep & 0xFFFFu, need = dep >> 16;
+    uint32_t id = dep & 0xFFFFu, need = (dep >> 16) & 0xFFu;
     if (need == 0u) need = 1u;
     Spin s;
     for (;;) {
@@ -567,6 +635,7 @@ DEV void dep_signal(Ctx &c, uint32_t dep) {
     if (c.lane == 0) {
         __hip_atomic_fetch_add(&c.p->dep[dep & 0xFFFFu], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
+    reconverge();
 }
 
 DEV void ldu_retire(Ctx &c, const Inflight &t) {
@@ -600,6 +669,7 @@ DEV void ldu_main(Ctx &c) {
     Spin sp;
     bool ok = true;
     while (ok) {
+        head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head);
         const uint32_t snap = unit_poll(c, u, head);
         const bool have = rf_get(snap, 0) != head;
         uint32_t ni = 0;
@@ -611,6 +681,7 @@ DEV void ldu_main(Ctx &c) {
             const uint32_t chunks = (r.rows_box >> 16) * ((r.rb_pitch >> 16) >> 4);
             ni = (chunks + 63u) >> 6;
         }
+        ni = uni(ni);
         // retire the oldest tile when nothing can be issued on top of what is in flight
         const bool can_issue = have && n_fl < (uint32_t)kMaxInflight && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
         if (!can_issue) {
@@ -663,13 +734,30 @@ DEV void ldu_main(Ctx &c) {
             drow = 64u / cpr; dcol = 64u % cpr;
         }
         const bool full = rows == box_rows && vcr == cpr && (total & 63u) == 0u;
-        for (uint32_t i = 0; i < ni; i++) {
-            const uint32_t q = i * 64u + c.lane;
+        if (full && dcol == 0u) {
+            // the usual case: whole tile, a power-of-two row of at most 64 chunks.  Every instruction moves 64 / cpr
+            // whole rows, so the per-lane address just advances by a uniform step
             const char *g = (const char *)(uintptr_t)(gaddr + (uint64_t)row * gpitch + (uint64_t)col * 16u);
-            const uint32_t dst = lds_base + r.lds_off + i * 1024u;
-            if (full) {
-                load_lds_b128(dst, g, nt);
+            const uint64_t step = uni64((uint64_t)drow * gpitch);
+            uint32_t dst = uni(lds_base + r.lds_off);
+            if (nt) {
+                for (uint32_t i = 0; i < ni; i++) {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(dst), "v"(g) : "memory");
+                    dst += 1024u;
+                    g += step;
+                }
             } else {
+                for (uint32_t i = 0; i < ni; i++) {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(g) : "memory");
+                    dst += 1024u;
+                    g += step;
+                }
+            }
+        } else {
+            for (uint32_t i = 0; i < ni; i++) {
+                const uint32_t q = i * 64u + c.lane;
+                const char *g = (const char *)(uintptr_t)(gaddr + (uint64_t)row * gpitch + (uint64_t)col * 16u);
+                const uint32_t dst = lds_base + r.lds_off + i * 1024u;
                 const bool inside = q < total;
                 const bool valid = inside && row < rows && col < vcr;
                 if (valid) load_lds_b128(dst, g, nt);
@@ -677,10 +765,10 @@ DEV void ldu_main(Ctx &c) {
                     u32x4 z = {0u, 0u, 0u, 0u};
                     lds_st128(r.lds_off + q * 16u, z);       // the box outside the valid tile reads as zero
                 }
+                row += drow;
+                col += dcol;
+                if (col >= cpr) { col -= cpr; row++; }
             }
-            row += drow;
-            col += dcol;
-            if (col >= cpr) { col -= cpr; row++; }
         }
         {
             const uint32_t k = (fl_head + n_fl) & (kMaxInflight - 1);
@@ -694,6 +782,7 @@ DEV void ldu_main(Ctx &c) {
         vm_out += ni;
         head++;
         if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
+        reconverge();
         sp.n = 0;
     }
     // never leave with loads in flight: their LDS destination belongs to this workgroup only while it lives
@@ -768,6 +857,7 @@ DEV void stu_main(Ctx &c) {
         }
         head++;
         if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
+        reconverge();
     }
 }
 
@@ -807,10 +897,12 @@ DEV void vcc_push_upto(Ctx &c, VccState &vs, uint32_t limit) {
     const uint32_t v = c.unit;
     while ((int32_t)(limit - vs.pushed) > 0) {
         const uint32_t payload = rf_get(vs.hist, vs.pushed & 63u);
+        const uint32_t next = uni(vs.pushed + 1u);
         if (c.lane == 0)
             lds_vst64(c.ctl + CTL_OFF(c2m) + (v * kC2M + (vs.pushed & (kC2M - 1))) * 8u,
-                      (uint64_t)payload | ((uint64_t)(vs.pushed + 1u) << 32));
-        vs.pushed++;
+                      (uint64_t)payload | ((uint64_t)next << 32));
+        reconverge();
+        vs.pushed = next;
     }
 }
 
@@ -853,6 +945,7 @@ DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n) {
     compiler_barrier();
     vs.head += n;
     if (vs.wv == 1u && c.lane == 0) lds_vst32(c.ctl + CTL_OFF(w1_done) + c.unit * 4u, vs.head);
+    reconverge();
     compiler_barrier();
 }
 
@@ -942,6 +1035,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
             lds_stf(red_off + c.lane * 4u, mine);
             lds_wait();
             if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(red_flag) + v * 4u, vs.red_seq + 1u);
+            reconverge();
         } else {
             while (uni(lds_vld32(c.ctl + CTL_OFF(red_flag) + v * 4u)) != vs.red_seq + 1u)
                 if (!spin_step(c, s, uni(lds_vld32(c.ctl + CTL_OFF(abort))), 0xB00u)) return false;
@@ -953,6 +1047,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
             }
             lds_wait();
             if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(red_ack) + v * 4u, vs.red_seq + 1u);
+            reconverge();
         }
         vs.red_seq++;
     }
@@ -981,12 +1076,14 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     const uint32_t j = lpr <= 64u ? 0u : lpr >> 7;
     switch (B) {
         case 1: return matvec_dispatch_b<1>(c, vs, f.size, R, lpr, nf, j);
+#ifndef VDC_ONLY_B1_AND_B8   /* set only by throw-away experiment builds to shorten the compile */
         case 2: return matvec_dispatch_b<2>(c, vs, f.size, R, lpr, nf, j);
         case 3: return matvec_dispatch_b<3>(c, vs, f.size, R, lpr, nf, j);
         case 4: return matvec_dispatch_b<4>(c, vs, f.size, R, lpr, nf, j);
         case 5: return matvec_dispatch_b<5>(c, vs, f.size, R, lpr, nf, j);
         case 6: return matvec_dispatch_b<6>(c, vs, f.size, R, lpr, nf, j);
         case 7: return matvec_dispatch_b<7>(c, vs, f.size, R, lpr, nf, j);
+#endif
         case 8: return matvec_dispatch_b<8>(c, vs, f.size, R, lpr, nf, j);
         default:
             raise_error(c, -3 /* VDC_EPROGRAM */, 0xD00u);
@@ -1038,6 +1135,7 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
     if (c.lane == 0)
         __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(vcc_done)), 1u,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    reconverge();
 }
 
 // ------------------------------------------------------------------------------------------------
