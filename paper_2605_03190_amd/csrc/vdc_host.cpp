@@ -47,6 +47,9 @@ struct vdc_executor {
     uint32_t *d_dep = nullptr;
     uint32_t *d_status = nullptr;
     uint32_t *h_status = nullptr;  // pinned
+#ifdef VDC_PROFILE
+    unsigned long long *d_prof = nullptr;
+#endif
     std::vector<vdc_program *> programs;
     std::vector<std::pair<MatvecKey, vdc_program *>> matvec_cache;
 };
@@ -369,12 +372,6 @@ struct Tiler {
     uint32_t flow_x(int v) const { return (uint32_t)(cfg.vcc_per_core + v); }
     uint32_t flow_y(int v) const { return (uint32_t)(2 * cfg.vcc_per_core + v); }
 
-    // accumulators: 0,1 matrix offset of compute core 0,1; 2 vector offset; 3,4 result offset of compute core 0,1
-    void emit_tile_pair(std::vector<Word> &vm, int v, uint32_t dm, uint32_t dx, uint32_t rows_valid) {
-        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | (nt ? F_NT : 0), flow_m(v), v, v, slots_for((uint64_t)R * Kt * 4), rows_valid, 0, 0, dm, 0));
-        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(v), v, 2, slots_for((uint64_t)B * Kt * 4), B, 0, 0, dx, 0));
-    }
-
     // `count` iterations; in each, every compute core in `vs` takes one block of `rows_valid` rows.
     void emit_blocks(int core, const std::vector<int> &vs, int64_t count, int64_t m_off, int64_t x_off, int64_t y_off,
                      uint32_t rows_valid) {
@@ -385,31 +382,64 @@ struct Tiler {
         const uint32_t dmt = ktail ? desc(0, R, (uint32_t)ktail * 4, Kt * 4, (uint64_t)ld * 4) : 0;
         const uint32_t dxt = ktail ? desc(1, B, (uint32_t)ktail * 4, Kt * 4, (uint64_t)K * 4) : 0;
         const uint32_t dy = desc(2, B, rows_valid * 4, R * 4, (uint64_t)y_pitch * 4);
-        for (int i = 0; i < n; i++) {
-            vm.push_back(encode(OP_SET, 0, 0, 0, vs[i], 0, 0, 0, m_off + (int64_t)i * R * ld * 4, 0, 0));
-            vm.push_back(encode(OP_SET, 0, 0, 0, 3 + vs[i], 0, 0, 0, y_off + (int64_t)i * R * 4, 0, 0));
-        }
-        vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, x_off, 0, 0));
-        if (count > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, count, 0, 0));
-        if (nk_full > 0) {
-            if (nk_full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full, 0, 0));
-            for (int i = 0; i < n; i++) emit_tile_pair(vm, vs[i], dm, dx, rows_valid);
-            for (int i = 0; i < n; i++) vm.push_back(encode(OP_ADD, 0, 0, 0, vs[i], 0, 0, 0, (int64_t)Kt * 4, 0, 0));
-            if (nk_full > 1) vm.push_back(encode(OP_REPEAT, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
-            else vm.push_back(encode(OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
-        }
-        if (ktail)
-            for (int i = 0; i < n; i++) emit_tile_pair(vm, vs[i], dmt, dxt, rows_valid);
-        for (int i = 0; i < n; i++)
-            vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DYNAMIC, flow_y(vs[i]), vs[i], 3 + vs[i], slots_for((uint64_t)B * R * 4), B, 0, 0, dy, 0));
-        if (count > 1) {
+        const uint32_t nk = (uint32_t)(nk_full + (ktail ? 1 : 0));
+        const uint32_t m_slots = slots_for((uint64_t)R * Kt * 4), x_slots = slots_for((uint64_t)B * Kt * 4), y_slots = slots_for((uint64_t)B * R * 4);
+        const uint32_t m_flags = F_SEND | F_DYNAMIC | (nt ? F_NT : 0);
+        if (count <= 8) {
+            // Few iterations: the block loop is unrolled, every block's addresses are literals plus ONE accumulator
+            // (2: the offset along K, shared by the matrix and the vector tiles), so that the K loop costs a single
+            // control uop per trip.
+            for (int64_t it = 0; it < count; it++) {
+                vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, 0, 0, 0));
+                auto tile_pairs = [&](uint32_t d_m, uint32_t d_x) {
+                    for (int i = 0; i < n; i++) {
+                        const int v = vs[i];
+                        const int64_t blk = it * n + i;
+                        vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, 2, m_slots, rows_valid, 0, m_off + blk * R * ld * 4, d_m, 0));
+                        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(v), v, 2, x_slots, B, 0, x_off, d_x, 0));
+                    }
+                };
+                if (nk_full > 0) {
+                    if (nk_full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full, 0, 0));
+                    tile_pairs(dm, dx);
+                    vm.push_back(encode(nk_full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                }
+                if (ktail) tile_pairs(dmt, dxt);
+                for (int i = 0; i < n; i++) {
+                    const int v = vs[i];
+                    vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, y_off + (it * n + i) * R * 4, dy, 0));
+                }
+            }
+        } else {
+            // accumulators: 0,1 matrix offset of compute core 0,1; 2 vector offset; 3,4 result offset of compute core 0,1
+            for (int i = 0; i < n; i++) {
+                vm.push_back(encode(OP_SET, 0, 0, 0, vs[i], 0, 0, 0, m_off + (int64_t)i * R * ld * 4, 0, 0));
+                vm.push_back(encode(OP_SET, 0, 0, 0, 3 + vs[i], 0, 0, 0, y_off + (int64_t)i * R * 4, 0, 0));
+            }
+            vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, x_off, 0, 0));
+            vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, count, 0, 0));
+            auto tile_pairs = [&](uint32_t d_m, uint32_t d_x) {
+                for (int i = 0; i < n; i++) {
+                    const int v = vs[i];
+                    vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, v, m_slots, rows_valid, 0, 0, d_m, 0));
+                    vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(v), v, 2, x_slots, B, 0, 0, d_x, 0));
+                }
+            };
+            if (nk_full > 0) {
+                if (nk_full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full, 0, 0));
+                tile_pairs(dm, dx);
+                for (int i = 0; i < n; i++) vm.push_back(encode(OP_ADD, 0, 0, 0, vs[i], 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                vm.push_back(encode(nk_full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+            }
+            if (ktail) tile_pairs(dmt, dxt);
+            for (int i = 0; i < n; i++)
+                vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DYNAMIC, flow_y(vs[i]), vs[i], 3 + vs[i], y_slots, B, 0, 0, dy, 0));
             for (int i = 0; i < n; i++) {
                 vm.push_back(encode(OP_ADD, 0, 0, 0, vs[i], 0, 0, 0, (int64_t)n * R * ld * 4 - nk_full * Kt * 4, 0, 0));
                 vm.push_back(encode(OP_ADD, 0, 0, 0, 3 + vs[i], 0, 0, 0, (int64_t)n * R * 4, 0, 0));
             }
             vm.push_back(encode(OP_REPEAT, 0, 0, 0, 2, 0, 0, 0, -nk_full * Kt * 4, 0, 0));
         }
-        const uint32_t nk = (uint32_t)(nk_full + (ktail ? 1 : 0));
         for (int i = 0; i < n; i++) {
             auto &vc = vcc(core, vs[i]);
             if (count > 1) vc.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, count, 0, 0));
@@ -545,7 +575,7 @@ int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     if (c.vcc_per_core < 1 || c.vcc_per_core > 2 || c.threads_per_eu != 128) return VDC_EINVAL;
     if (!is_pow2(c.slot_bytes) || c.slot_bytes < 1024 || c.slot_bytes > 16384) return VDC_EINVAL;
     if (c.n_ldu < 1 || c.n_ldu > 2 || c.n_stu != 1) return VDC_EINVAL;   // 8 waves: 256 VGPRs each
-    if (c.n_dep_ids < 1 || c.n_dep_ids > 65536 || c.watchdog_spins < 64 || c.tile_rows < 0) return VDC_EINVAL;
+    if (c.n_dep_ids < 1 || c.n_dep_ids > 65536 || c.watchdog_spins < 1 || c.tile_rows < 0) return VDC_EINVAL;
     const size_t ctl = lds_control_bytes();
     if (c.n_slots == 0) {
         size_t fit = (lds_limit - ctl) / (size_t)c.slot_bytes;
@@ -580,6 +610,10 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.n_stu = ex->cfg.n_stu;
     p.V = ex->cfg.vcc_per_core;
     p.watchdog = (uint32_t)ex->cfg.watchdog_spins;
+#ifdef VDC_PROFILE
+    if (!ex->d_prof && hipMalloc(&ex->d_prof, 8 * 8 * 8 * (size_t)ex->cfg.n_cores) != hipSuccess) return VDC_ENOMEM;
+    p.prof = ex->d_prof;
+#endif
     HIP_TRY(hipSetDevice(ex->cfg.device));
     if (prog->uses_dep) HIP_TRY(launch_clear(ex->d_dep, prog->max_dep_id + 1, stream));
     if (trace_count) HIP_TRY(launch_clear(trace_count, (uint32_t)(ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core)), stream));
@@ -826,6 +860,12 @@ int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslo
     HIP_TRY(launch_debug_alloc(masks, nslots, n_slots, pos, n, (hipStream_t)hip_stream));
     return VDC_OK;
 }
+
+#ifdef VDC_PROFILE
+int vdc_prof_read(vdc_executor *ex, unsigned long long *out) {
+    return hipMemcpy(out, ex->d_prof, 8 * 8 * 8 * (size_t)ex->cfg.n_cores, hipMemcpyDeviceToHost) == hipSuccess ? 0 : VDC_EDEVICE;
+}
+#endif
 
 const char *vdc_strerror(int code) {
     switch (code) {

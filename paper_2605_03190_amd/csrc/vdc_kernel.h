@@ -35,6 +35,9 @@ struct KParams {
     uint32_t trace_cap;
     uint32_t n_slots, slot_bytes, n_ldu, n_stu, V;
     uint32_t watchdog;
+#ifdef VDC_PROFILE
+    unsigned long long *prof;   // cores * 8 waves * 8 counters (profiling builds only)
+#endif
 };
 
 // Bytes of dynamic LDS one workgroup needs for n_slots slots of slot_bytes plus the control block.

@@ -33,6 +33,21 @@
 
 namespace vdc {
 
+// Cycle-bucket instrumentation for throw-away profiling builds (-DVDC_PROFILE); the product build compiles none of it.
+#ifdef VDC_PROFILE
+#define PROF_DECL(...) unsigned long long __VA_ARGS__
+#define PROF_NOW() __builtin_readcyclecounter()
+#define PROF_ADD(var, t0) var += PROF_NOW() - (t0)
+#define PROF_INC(var) var++
+#define PROF_OUT(c, wave, k, v) do { if ((c).lane == 0) (c).p->prof[((c).core * 8 + (wave)) * 8 + (k)] = (v); } while (0)
+#else
+#define PROF_DECL(...)
+#define PROF_NOW() 0ull
+#define PROF_ADD(var, t0)
+#define PROF_INC(var)
+#define PROF_OUT(c, wave, k, v)
+#endif
+
 // ------------------------------------------------------------------------------------------------
 // LDS layout: [0, n_slots * slot_bytes) the slots, then the control block.
 // ------------------------------------------------------------------------------------------------
@@ -44,43 +59,49 @@ constexpr int kMaxUnits = 4;   // n_ldu + n_stu
 constexpr int kMaxV = 2;
 constexpr int kMaxInflight = 4;  // tiles one LDU keeps in flight
 constexpr int kMaxVm = 56;       // outstanding load instructions one LDU allows itself (vmcnt holds 63)
-constexpr int kRecWords = 12;
+constexpr int kRecWords = 4;
+constexpr int kStatWords = 8;
+constexpr int kWin = 64;        // uops in the decoded window
 
-struct UnitRec {  // a memory uop after the front end (48 bytes)
-    uint32_t gaddr_lo, gaddr_hi;
-    uint32_t gpitch_lo, gpitch_hi;
-    uint32_t lds_off;    // byte offset of the region in LDS
-    uint32_t rows_box;   // valid rows | box_rows << 16
-    uint32_t rb_pitch;   // valid row_bytes | lds_pitch << 16
-    uint32_t w0;         // first word of the uop: opcode, flags, vflow, vcc, acc, nslots
-    uint32_t ticket;     // m2c position when SEND
-    uint32_t slot;
-    uint32_t dep;        // depId | dep_count << 16
-    uint32_t pc;
+struct UnitRec {  // the per-execution part of a memory uop after the front end (16 bytes)
+    uint32_t gaddr_lo, gaddr_hi;   // effective global address
+    uint32_t info;                 // slot [5:0] | window lane [11:6] | table [12]
+    uint32_t ticket;               // m2c position when SEND
+};
+
+struct StatRec {  // the static part, written for all 64 uops of a window at once when it is decoded (32 bytes)
+    uint32_t gp_lo, gp_hi;   // bytes between rows in global memory
+    uint32_t rows_box;       // valid rows | box_rows << 16
+    uint32_t rb_pitch;       // valid row_bytes | lds_pitch << 16
+    uint32_t w0;             // first word of the uop: opcode, flags, vflow, vcc, acc, nslots
+    uint32_t dep;            // depId | dep_count << 16
+    uint32_t pc;             // stream-relative pc
+    uint32_t rsv;
 };
 
 struct Ctl {
     // --- polled together by the CFU with one gathered LDS read: keep these six words contiguous ---
-    uint32_t uq_head[kMaxUnits];   // records consumed by each unit
+    uint32_t uq_head[kMaxUnits];   // records picked up by each unit
     uint32_t mask;                 // slot availability: bit set = in use (Section 4.3: 32-bit mask in shared memory)
     uint32_t abort;                // set when any unit of this core gives up
     // ---
     uint32_t cfu_halted;
     uint32_t vcc_done;             // VCC waves that reached HALT
     uint32_t uq_tail[kMaxUnits];   // records pushed to each unit
-    uint32_t mbox_tail[kMaxV];
+    uint32_t uq_done[kMaxUnits];   // records completed by each unit (store units)
     uint32_t w1_done[kMaxV];       // tickets the second wave of a VCC is done with
     uint32_t red_flag[kMaxV];      // cross-wave reduction hand-shake of a VCC
     uint32_t red_ack[kMaxV];
+    uint32_t pad0[2];
     uint64_t m2c[kMaxV][kM2C];     // low: slot | nslots << 6 | rows << 12; high: (ticket + 1) & 0xffff | row_bytes << 16
     uint64_t c2m[kMaxV][kC2M];     // low: kind | slot << 1 | nslots << 7; high: position + 1
-    uint32_t mbox[kMaxV][kMbox];
     UnitRec uq[kMaxUnits][kUQ];
+    StatRec stat[2][kWin];         // two tables: the window being executed and the previous one
     float red[kMaxV][64];
 };
 static_assert(offsetof(Ctl, mask) == offsetof(Ctl, uq_head) + 16 && offsetof(Ctl, abort) == offsetof(Ctl, mask) + 4, "poll block");
-static_assert(offsetof(Ctl, m2c) % 8 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0, "alignment");
-static_assert(sizeof(UnitRec) == 4 * kRecWords, "record size");
+static_assert(offsetof(Ctl, m2c) % 8 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0 && offsetof(Ctl, stat) % 16 == 0, "alignment");
+static_assert(sizeof(UnitRec) == 4 * kRecWords && sizeof(StatRec) == 4 * kStatWords, "record size");
 #define CTL_OFF(field) ((uint32_t)offsetof(Ctl, field))
 
 size_t lds_control_bytes() { return (sizeof(Ctl) + 255) & ~(size_t)255; }
@@ -353,86 +374,33 @@ DEV void slots_free(Ctx &c, uint32_t slot, uint32_t nslots) {
 // CFU: the front end of the virtual memory core
 // ------------------------------------------------------------------------------------------------
 struct CfuState {
-    uint32_t c2m_head0, c2m_head1;
-    uint32_t mbox_tail0, mbox_tail1;
     uint32_t ticket0, ticket1;
     uint32_t uq_tail_rf;   // lane u: records pushed to unit u
+    uint32_t mark_rf0;     // lane u: uq_tail[u] when the window that used stat table 0 was left
+    uint32_t mark_rf1;     //         ... stat table 1
+    uint32_t n_refill;
 };
 
-// One gathered read of everything the front end looks at: lanes 0,1 = next c2m entry of VCC 0 (low, high),
-// lanes 2,3 = of VCC 1, lanes 4..7 = uq_head[0..3], lane 8 = slot mask, lane 9 = abort.
-DEV uint32_t cfu_poll(Ctx &c, const CfuState &st) {
-    const uint32_t e0 = c.ctl + CTL_OFF(c2m) + (st.c2m_head0 & (kC2M - 1)) * 8u;
-    const uint32_t e1 = c.ctl + CTL_OFF(c2m) + (kC2M + (st.c2m_head1 & (kC2M - 1))) * 8u;
-    const uint32_t l = c.lane < 9u ? c.lane : 9u;
-    uint32_t off = c.ctl + CTL_OFF(uq_head) + (l - 4u) * 4u;
-    off = c.lane < 4u ? e1 + (c.lane - 2u) * 4u : off;
-    off = c.lane < 2u ? e0 + c.lane * 4u : off;
-    return lds_vld32(off);
-}
-
-// Receiver of the c2m queues (on the snapshot `snap` of cfu_poll): a used region goes back to the pool, a produced
-// region to the STORE that waits for it.  Returns the number of messages taken (at most one per queue).
-DEV uint32_t cfu_receive(Ctx &c, CfuState &st, uint32_t snap, uint32_t &mask) {
-    uint32_t taken = 0;
-    {
-        const uint32_t lo = rf_get(snap, 0), hi = rf_get(snap, 1);
-        if (hi == st.c2m_head0 + 1u) {
-            st.c2m_head0++;
-            taken++;
-            const uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
-            if ((lo & 1u) == 0u) {
-                slots_free(c, slot, nslots);
-                mask &= ~slot_bits(slot, nslots);
-            } else {
-                const uint32_t next = uni(st.mbox_tail0 + 1u);
-                if (c.lane == 0) {
-                    lds_vst32(c.ctl + CTL_OFF(mbox) + (st.mbox_tail0 & (kMbox - 1)) * 4u, slot | (nslots << 6));
-                    lds_vst32(c.ctl + CTL_OFF(mbox_tail), next);
-                }
-                reconverge();
-                st.mbox_tail0 = next;
-            }
-        }
-    }
-    if (c.p->V > 1u) {
-        const uint32_t lo = rf_get(snap, 2), hi = rf_get(snap, 3);
-        if (hi == st.c2m_head1 + 1u) {
-            st.c2m_head1++;
-            taken++;
-            const uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
-            if ((lo & 1u) == 0u) {
-                slots_free(c, slot, nslots);
-                mask &= ~slot_bits(slot, nslots);
-            } else {
-                const uint32_t next = uni(st.mbox_tail1 + 1u);
-                if (c.lane == 0) {
-                    lds_vst32(c.ctl + CTL_OFF(mbox) + (kMbox + (st.mbox_tail1 & (kMbox - 1))) * 4u, slot | (nslots << 6));
-                    lds_vst32(c.ctl + CTL_OFF(mbox_tail) + 4u, next);
-                }
-                reconverge();
-                st.mbox_tail1 = next;
-            }
-        }
-    }
-    return taken;
+// One gathered read of what the front end looks at: lanes 0..3 = uq_head[0..3], lane 4 = slot mask, lane 5 = abort.
+DEV uint32_t cfu_poll(Ctx &c) {
+    const uint32_t l = c.lane < 5u ? c.lane : 5u;
+    return lds_vld32(c.ctl + CTL_OFF(uq_head) + l * 4u);
 }
 
 // The decoded uop window of the front end: lane l describes word win_base + l.  Decoding (field extraction,
 // descriptor lookup, flow -> unit mapping, tensor base + literal address) is done for 64 uops at once, one per
-// lane, when the window is (re)filled; executing a uop then only picks its lane with v_readlane.
+// lane, when the window is (re)filled; executing a uop then only picks its lane with v_readlane.  The fields a
+// load/store unit needs but the front end does not (row pitch, box, flags, depId) go straight from the decoding
+// lane into a table in LDS; the per-execution record handed to the unit only names the table entry.
 struct DecWin {
     uint32_t base;       // first word in the window
     uint32_t ctl;        // opcode [7:0] | flags [15:8] | unit [17:16] | vcc [19:18] | acc [22:20] | nslots [28:23] | tensor [31:29]
     uint32_t a_lo, a_hi; // memory uop: tensor base + literal offset; control uop: the immediate
-    uint32_t gp_lo, gp_hi;
-    uint32_t rows_box;   // size | box_rows << 16
-    uint32_t rb_pitch;   // row_bytes | lds_pitch << 16
-    uint32_t w0;
-    uint32_t dep;        // depId | dep_count << 16 | desc << 24
+    uint32_t aux;        // valid rows [15:0] | valid row_bytes [31:16]   (for the early hand-over of an output region, and the trace)
+    uint32_t desc;       // descriptor index (trace only)
 };
 
-DEV void cfu_refill(Ctx &c, DecWin &d, uint32_t pc, uint32_t end) {
+DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) {
     const KParams *p = c.p;
     uint32_t idx = pc + c.lane;
     if (idx >= end) idx = end - 1u;             // the stream's HALT
@@ -442,7 +410,7 @@ DEV void cfu_refill(Ctx &c, DecWin &d, uint32_t pc, uint32_t end) {
     const bool is_mem = f.opcode == OP_LOAD || f.opcode == OP_STORE;
     const uint32_t di = (is_mem && f.desc < p->n_descs) ? f.desc : 0u;
     const uint32_t *dp = (const uint32_t *)(p->descs + di);
-    const uint32_t d_tensor = dp[0], d_box = dp[1], d_rowb = dp[2], d_pitch = dp[3];
+    const uint32_t d_tensor = dp[0], d_box = dp[1], d_rowb = dp[2], d_pitch = dp[3], d_gplo = dp[4], d_gphi = dp[5];
     uint64_t tbase = 0;
 #pragma unroll
     for (int t = 0; t < kMaxTensors; t++) tbase = ((d_tensor & (kMaxTensors - 1)) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tbase;
@@ -452,36 +420,52 @@ DEV void cfu_refill(Ctx &c, DecWin &d, uint32_t pc, uint32_t end) {
     d.ctl = f.opcode | (f.flags << 8) | (unit << 16) | (f.vcc << 18) | (f.acc << 20) | (f.nslots << 23) | ((d_tensor & 7u) << 29);
     d.a_lo = (uint32_t)a;
     d.a_hi = (uint32_t)(a >> 32);
-    d.gp_lo = dp[4];
-    d.gp_hi = dp[5];
-    d.rows_box = f.size | (d_box << 16);
-    d.rb_pitch = d_rowb | (d_pitch << 16);
-    d.w0 = w.w0;
-    d.dep = f.dep_id | (f.dep_count << 16) | (f.desc << 24);
+    d.aux = f.size | (d_rowb << 16);
+    d.desc = f.desc;
+    // The table this window writes was last used two windows ago.  Its records may still sit in a unit's queue:
+    // wait until every unit has picked up everything that was dispatched from that window.
+    const uint32_t t = st.n_refill & 1u;
+    const uint32_t filled = st.uq_tail_rf;
+    if (t == 0u) st.mark_rf1 = filled; else st.mark_rf0 = filled;     // the window being left used the other table
+    const uint32_t mark = t == 0u ? st.mark_rf0 : st.mark_rf1;
+    Spin sp;
+    for (;;) {
+        const uint32_t snap = cfu_poll(c);
+        const bool behind = c.lane < (uint32_t)kMaxUnits && (int32_t)(snap - mark) < 0;
+        if (__ballot(behind) == 0ull) break;
+        if (!spin_step(c, sp, rf_get(snap, 5), 0x250u)) return false;
+    }
+    const uint32_t off = c.ctl + CTL_OFF(stat) + (t * kWin + c.lane) * (uint32_t)sizeof(StatRec);
+    u32x4 s0 = {d_gplo, d_gphi, f.size | (d_box << 16), d_rowb | (d_pitch << 16)};
+    u32x4 s1 = {w.w0, f.dep_id | (f.dep_count << 16), idx - c.stream_pc0, 0u};
+    lds_st128(off, s0);
+    lds_st128(off + 16, s1);
+    compiler_barrier();
+    st.n_refill++;
+    return true;
 }
 
 DEV void cfu_main(Ctx &c) {
     const KParams *p = c.p;
     const bool TRACE = p->trace != nullptr;
-    const uint32_t V = p->V, n_slots = p->n_slots, n_units = p->n_ldu + p->n_stu;
-    const uint32_t stream = c.core * (1u + V);
+    const uint32_t n_slots = p->n_slots, n_ldu = p->n_ldu, n_units = p->n_ldu + p->n_stu;
+    const uint32_t stream = c.core * (1u + p->V);
     Seq s;
     s.pc = cload(p->stream_begin, stream);
     s.end = cload(p->stream_begin, stream + 1u);
     s.depth = 0; s.rf_lo = 0; s.rf_hi = 0; s.win_base = 0; s.win = u32x4{0u, 0u, 0u, 0u};
     c.stream_pc0 = s.pc;
-    CfuState st = {0, 0, 0, 0, 0, 0, 0};
+    CfuState st = {0, 0, 0, 0, 0, 0};
     uint32_t trace_n = 0;
-    const uint32_t slot_shift = __builtin_ctz(p->slot_bytes);
     DecWin d;
-    cfu_refill(c, d, s.pc, s.end);
-    bool ok = true;
+    bool ok = cfu_refill(c, d, st, s.pc, s.end);
+    PROF_DECL(pt0 = PROF_NOW(), p_wait = 0, p_n = 0, p_polls = 0, p_ctl = 0);
 
     while (ok) {
         c.pc = s.pc;
         uint32_t k = s.pc - d.base;
-        if (k >= 64u) {
-            cfu_refill(c, d, s.pc, s.end);
+        if (k >= (uint32_t)kWin) {
+            if (!cfu_refill(c, d, st, s.pc, s.end)) { ok = false; break; }
             k = 0;
         }
         const uint32_t ctlw = rf_get(d.ctl, k);
@@ -495,60 +479,57 @@ DEV void cfu_main(Ctx &c) {
             f.imm = (int64_t)a;
             const int r = seq_control(s, f);
             if (r == 2) break;
+            PROF_INC(p_ctl);
             continue;
         }
         // ---- a memory uop: address generation, slot allocation in program order, dispatch by virtual flow ----
         const uint32_t flags = (ctlw >> 8) & 0xFFu, unit = (ctlw >> 16) & 3u, vcc = (ctlw >> 18) & 3u, nslots = (ctlw >> 23) & 63u;
-        const bool is_load = opcode == (uint32_t)OP_LOAD;
         const uint64_t gaddr = a + ((flags & F_DYNAMIC) ? (uint64_t)seq_acc(s, acc) : 0ull);
         const uint32_t tail = rf_get(st.uq_tail_rf, unit);
 
         // wait for room in the unit's queue and, in program order, for the slots (in-order allocation)
         int slot;
         Spin sp;
+        PROF_DECL(pw0 = PROF_NOW());
+        PROF_INC(p_n);
         for (;;) {
-            const uint32_t snap = cfu_poll(c, st);
-            uint32_t mask = rf_get(snap, 8);
-            const uint32_t taken = cfu_receive(c, st, snap, mask);
-            const bool room = tail - rf_get(snap, 4u + unit) < (uint32_t)kUQ;
-            slot = slot_find(mask, nslots, n_slots, c.lane);
+            PROF_INC(p_polls);
+            const uint32_t snap = cfu_poll(c);
+            const bool room = tail - rf_get(snap, unit) < (uint32_t)kUQ;
+            slot = slot_find(rf_get(snap, 4), nslots, n_slots, c.lane);
             if (room && slot >= 0) break;
-            if (taken) continue;     // something moved: look again at once
-            if (!spin_step(c, sp, rf_get(snap, 9), 0x300u | nslots | (room ? 0u : 0x80u))) { ok = false; break; }
+            if (!spin_step(c, sp, rf_get(snap, 5), 0x300u | nslots | (room ? 0u : 0x80u))) { ok = false; break; }
         }
+        PROF_ADD(p_wait, pw0);
         if (!ok) break;
         uint32_t ticket = 0xFFFFFFFFu;
         if (flags & F_SEND) {
             if (vcc == 0u) ticket = st.ticket0++;
             else ticket = st.ticket1++;
         }
-        const uint32_t rows_box = rf_get(d.rows_box, k), rb_pitch = rf_get(d.rb_pitch, k);
-        const uint32_t w0 = rf_get(d.w0, k), dep = rf_get(d.dep, k);
-        const uint32_t gp_lo = rf_get(d.gp_lo, k), gp_hi = rf_get(d.gp_hi, k);
         if (TRACE) {
             const uint64_t tb = uni64((uint64_t)(uintptr_t)p->tensors[ctlw >> 29]);
-            trace_put(c, stream, trace_n, s.pc - c.stream_pc0, opcode | ((dep >> 24) << 8) | ((rows_box & 0xFFFFu) << 16), gaddr - tb);
+            trace_put(c, stream, trace_n, s.pc - c.stream_pc0, opcode | (rf_get(d.desc, k) << 8) | ((rf_get(d.aux, k) & 0xFFFFu) << 16), gaddr - tb);
         }
         // everything that is written happens in one lane: slot mask, the early hand-over of an output region,
-        // the decoded uop for its unit
-        const uint32_t tail_next = uni(tail + 1u), pc_rel = uni(s.pc - c.stream_pc0), pc_next = uni(s.pc + 1u);
+        // the record for the unit
+        const uint32_t tail_next = uni(tail + 1u), pc_next = uni(s.pc + 1u);
         const uint32_t uslot = uni((uint32_t)slot);
+        const uint32_t info = uslot | (k << 6) | (((st.n_refill - 1u) & 1u) << 12);
+        const bool early = opcode == (uint32_t)OP_STORE && (flags & F_SEND);
+        const uint32_t aux = early ? rf_get(d.aux, k) : 0u;
         if (c.lane == 0) {
             __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
                                   slot_bits(uslot, nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (!is_load && (flags & F_SEND)) {
+            if (early) {
                 // the empty output region goes to the compute core at once; the store unit only waits for it to return
-                const uint64_t e = (uint64_t)(uslot | (nslots << 6) | ((rows_box & 0xFFFFu) << 12)) |
-                                   ((uint64_t)(((ticket + 1u) & 0xFFFFu) | ((rb_pitch & 0xFFFFu) << 16)) << 32);
+                const uint64_t e = (uint64_t)(uslot | (nslots << 6) | ((aux & 0xFFFFu) << 12)) |
+                                   ((uint64_t)(((ticket + 1u) & 0xFFFFu) | (aux & 0xFFFF0000u)) << 32);
                 lds_vst64(c.ctl + CTL_OFF(m2c) + (vcc * kM2C + (ticket & (kM2C - 1))) * 8u, e);
             }
             const uint32_t off = c.ctl + CTL_OFF(uq) + (unit * kUQ + (tail & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
-            u32x4 ra = {(uint32_t)gaddr, (uint32_t)(gaddr >> 32), gp_lo, gp_hi};
-            u32x4 rb = {uslot << slot_shift, rows_box, rb_pitch, w0};
-            u32x4 rd = {ticket, uslot, dep & 0xFFFFFFu, pc_rel};
-            lds_st128(off, ra);
-            lds_st128(off + 16, rb);
-            lds_st128(off + 32, rd);
+            u32x4 rec = {(uint32_t)gaddr, (uint32_t)(gaddr >> 32), info, ticket};
+            lds_st128(off, rec);
             compiler_barrier();
             lds_vst32(c.ctl + CTL_OFF(uq_tail) + unit * 4u, tail_next);
         }
@@ -556,28 +537,21 @@ DEV void cfu_main(Ctx &c) {
         st.uq_tail_rf = rf_set(st.uq_tail_rf, unit, tail_next);
         s.pc = pc_next;
     }
+    PROF_OUT(c, 0, 0, PROF_NOW() - pt0); PROF_OUT(c, 0, 1, p_wait); PROF_OUT(c, 0, 2, p_n); PROF_OUT(c, 0, 3, p_polls); PROF_OUT(c, 0, 4, p_ctl);
 
-    // HALT (or error): no more dispatches.  Keep receiving c2m until the units and the compute cores are done.
+    // HALT (or error): no more dispatches.  The store unit goes on receiving c2m; wait until every unit is done with
+    // what it was given.
     if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(cfu_halted), 1u);
     reconverge();
     Spin sp;
     while (ok) {
-        const uint32_t snap = cfu_poll(c, st);
-        uint32_t mask = rf_get(snap, 8);
-        const uint32_t taken = cfu_receive(c, st, snap, mask);
-        if (taken) continue;
-        bool done = uni(lds_vld32(c.ctl + CTL_OFF(vcc_done))) == 2u * V;
-        for (uint32_t u = 0; u < n_units; u++) done = done && (rf_get(snap, 4u + u) == rf_get(st.uq_tail_rf, u));
-        if (done) {
-            // the compute cores have returned everything and the units are idle: one last look at the queues,
-            // then the pool must be empty
-            const uint32_t last = cfu_poll(c, st);
-            uint32_t m2 = rf_get(last, 8);
-            if (cfu_receive(c, st, last, m2)) continue;
-            if (m2 != 0u) raise_error(c, -6 /* VDC_ELEAK */, m2);
-            break;
-        }
-        if (!spin_step(c, sp, rf_get(snap, 9), 0x400u)) ok = false;
+        const uint32_t snap = cfu_poll(c);
+        bool done = true;
+        for (uint32_t u = 0; u < n_ldu; u++) done = done && (rf_get(snap, u) == rf_get(st.uq_tail_rf, u));
+        for (uint32_t u = n_ldu; u < n_units; u++)
+            done = done && (uni(lds_vld32(c.ctl + CTL_OFF(uq_done) + u * 4u)) == rf_get(st.uq_tail_rf, u));
+        if (done) break;
+        if (!spin_step(c, sp, rf_get(snap, 5), 0x400u)) ok = false;
     }
 }
 
@@ -645,21 +619,27 @@ DEV void ldu_retire(Ctx &c, const Inflight &t) {
     if (flags & F_DEP_SEND) dep_signal(c, t.dep);
 }
 
-// One gathered read of what a load/store unit looks at: lane 0 = uq_tail[u], lanes 1..12 = the record at `head`,
-// lane 13 = cfu_halted, lane 14 = abort, lanes 15,16 = mbox_tail[0..1].
-DEV uint32_t unit_poll(Ctx &c, uint32_t u, uint32_t head) {
+// One gathered read of what a load unit looks at: lane 0 = uq_tail[u], lanes 1..4 = the record at `head`,
+// lane 5 = cfu_halted, lane 6 = abort.
+DEV uint32_t ldu_poll(Ctx &c, uint32_t u, uint32_t head) {
     const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
-    uint32_t off = c.ctl + CTL_OFF(mbox_tail) + (c.lane == 16u ? 4u : 0u);
-    off = c.lane == 14u ? c.ctl + CTL_OFF(abort) : off;
-    off = c.lane == 13u ? c.ctl + CTL_OFF(cfu_halted) : off;
-    off = c.lane <= 12u ? rec + (c.lane - 1u) * 4u : off;
+    uint32_t off = c.ctl + CTL_OFF(abort);
+    off = c.lane == 5u ? c.ctl + CTL_OFF(cfu_halted) : off;
+    off = c.lane <= 4u ? rec + (c.lane - 1u) * 4u : off;
     off = c.lane == 0u ? c.ctl + CTL_OFF(uq_tail) + u * 4u : off;
     return lds_vld32(off);
+}
+
+// The static part of a record: lanes 0..7 = the StatRec the record's info word points at.
+DEV uint32_t stat_fetch(Ctx &c, uint32_t info) {
+    const uint32_t base = c.ctl + CTL_OFF(stat) + (((info >> 12) & 1u) * kWin + ((info >> 6) & 63u)) * (uint32_t)sizeof(StatRec);
+    return lds_vld32(base + (c.lane & 7u) * 4u);
 }
 
 DEV void ldu_main(Ctx &c) {
     const uint32_t u = c.unit;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds0();
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     // tiles in flight: a ring in a lane register file (lane k = entry k), oldest at fl_head
     uint32_t fl_w0 = 0, fl_ticket = 0, fl_dep = 0, fl_sn = 0, fl_rr = 0;
     uint32_t fl_head = 0;
@@ -668,16 +648,20 @@ DEV void ldu_main(Ctx &c) {
     uint32_t head = 0;
     Spin sp;
     bool ok = true;
+    PROF_DECL(pt0 = PROF_NOW(), p_idle = 0, p_vm = 0, p_issue = 0, p_n = 0, p_idle_n = 0);
     while (ok) {
         head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head);
-        const uint32_t snap = unit_poll(c, u, head);
+        const uint32_t snap = ldu_poll(c, u, head);
         const bool have = rf_get(snap, 0) != head;
         uint32_t ni = 0;
-        UnitRec r;
+        struct { uint32_t gaddr_lo, gaddr_hi, gpitch_lo, gpitch_hi, lds_off, rows_box, rb_pitch, w0, ticket, slot, dep, pc; } r = {};
         if (have) {
-            r.gaddr_lo = rf_get(snap, 1); r.gaddr_hi = rf_get(snap, 2); r.gpitch_lo = rf_get(snap, 3); r.gpitch_hi = rf_get(snap, 4);
-            r.lds_off = rf_get(snap, 5); r.rows_box = rf_get(snap, 6); r.rb_pitch = rf_get(snap, 7); r.w0 = rf_get(snap, 8);
-            r.ticket = rf_get(snap, 9); r.slot = rf_get(snap, 10); r.dep = rf_get(snap, 11); r.pc = rf_get(snap, 12);
+            const uint32_t info = rf_get(snap, 3);
+            const uint32_t stat = stat_fetch(c, info);
+            r.gaddr_lo = rf_get(snap, 1); r.gaddr_hi = rf_get(snap, 2); r.ticket = rf_get(snap, 4);
+            r.slot = info & 63u; r.lds_off = r.slot << slot_shift;
+            r.gpitch_lo = rf_get(stat, 0); r.gpitch_hi = rf_get(stat, 1); r.rows_box = rf_get(stat, 2); r.rb_pitch = rf_get(stat, 3);
+            r.w0 = rf_get(stat, 4); r.dep = rf_get(stat, 5); r.pc = rf_get(stat, 6);
             const uint32_t chunks = (r.rows_box >> 16) * ((r.rb_pitch >> 16) >> 4);
             ni = (chunks + 63u) >> 6;
         }
@@ -688,20 +672,27 @@ DEV void ldu_main(Ctx &c) {
             if (n_fl > 0) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
                 Inflight o = {rf_get(fl_w0, k), rf_get(fl_ticket, k), rf_get(fl_dep, k), rf_get(fl_sn, k), rf_get(fl_rr, k)};
+                PROF_DECL(q0 = PROF_NOW());
                 wait_vmcnt_le(vm_out - (o.slot_ninstr >> 8));
                 vm_out -= o.slot_ninstr >> 8;
                 ldu_retire(c, o);
+                PROF_ADD(p_vm, q0);
                 fl_head++;
                 n_fl--;
                 sp.n = 0;
                 continue;
             }
             // idle
-            if (rf_get(snap, 13) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
-            if (!spin_step(c, sp, rf_get(snap, 14), 0x600u | u)) ok = false;
+            if (rf_get(snap, 5) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
+            PROF_DECL(q1 = PROF_NOW());
+            if (!spin_step(c, sp, rf_get(snap, 6), 0x600u | u)) ok = false;
+            PROF_ADD(p_idle, q1);
+            PROF_INC(p_idle_n);
             continue;
         }
         // ---- issue the loads of record r ----
+        PROF_DECL(qi0 = PROF_NOW());
+        PROF_INC(p_n);
         c.pc = c.stream_pc0 + r.pc;
         const uint32_t flags = (r.w0 >> 8) & 0xFFu;
         if (flags & F_DEP_RECV) {
@@ -784,7 +775,9 @@ DEV void ldu_main(Ctx &c) {
         if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
         reconverge();
         sp.n = 0;
+        PROF_ADD(p_issue, qi0);
     }
+    PROF_OUT(c, 1 + u, 0, PROF_NOW() - pt0); PROF_OUT(c, 1 + u, 1, p_idle); PROF_OUT(c, 1 + u, 2, p_vm); PROF_OUT(c, 1 + u, 3, p_issue); PROF_OUT(c, 1 + u, 4, p_n); PROF_OUT(c, 1 + u, 5, p_idle_n);
     // never leave with loads in flight: their LDS destination belongs to this workgroup only while it lives
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (ok) {
@@ -797,67 +790,138 @@ DEV void ldu_main(Ctx &c) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// STU: produced region -> global memory
+// STU: receiver of the c2m queues, and produced region -> global memory
 // ------------------------------------------------------------------------------------------------
+// lanes 0,1 = next c2m entry of VCC 0 (low, high), lanes 2,3 = of VCC 1, lane 4 = uq_tail[u], lanes 5..8 = the
+// record at `head`, lane 9 = cfu_halted, lane 10 = abort, lane 11 = vcc_done, lane 12 = slot mask
+DEV uint32_t stu_poll(Ctx &c, uint32_t u, uint32_t head, uint32_t c2m_head0, uint32_t c2m_head1) {
+    const uint32_t e0 = c.ctl + CTL_OFF(c2m) + (c2m_head0 & (kC2M - 1)) * 8u;
+    const uint32_t e1 = c.ctl + CTL_OFF(c2m) + (kC2M + (c2m_head1 & (kC2M - 1))) * 8u;
+    const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
+    uint32_t off = c.ctl + CTL_OFF(mask);
+    off = c.lane == 11u ? c.ctl + CTL_OFF(vcc_done) : off;
+    off = c.lane == 10u ? c.ctl + CTL_OFF(abort) : off;
+    off = c.lane == 9u ? c.ctl + CTL_OFF(cfu_halted) : off;
+    off = c.lane <= 8u ? rec + (c.lane - 5u) * 4u : off;
+    off = c.lane == 4u ? c.ctl + CTL_OFF(uq_tail) + u * 4u : off;
+    off = c.lane < 4u ? e1 + (c.lane - 2u) * 4u : off;
+    off = c.lane < 2u ? e0 + c.lane * 4u : off;
+    return lds_vld32(off);
+}
+
+// Take the next message of one c2m queue out of the snapshot: a used region goes back to the pool (Section 4.3:
+// "recycled"), a produced region is kept for the STORE that waits for it ("written back").
+DEV bool stu_receive(Ctx &c, uint32_t lo, uint32_t hi, uint32_t &c2m_head, uint32_t &box_rf, uint32_t &box_tail) {
+    if (hi != c2m_head + 1u) return false;
+    c2m_head++;
+    const uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
+    if ((lo & 1u) == 0u) {
+        slots_free(c, slot, nslots);
+    } else {
+        box_rf = rf_set(box_rf, box_tail & (kMbox - 1), slot | (nslots << 6));
+        box_tail++;
+    }
+    return true;
+}
+
 DEV void stu_main(Ctx &c) {
     const uint32_t u = c.unit;
-    uint32_t head = 0;
-    uint32_t mbox_head0 = 0, mbox_head1 = 0;
+    const uint32_t V = c.p->V;
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
+    uint32_t head = 0, done = 0;
+    uint32_t c2m_head0 = 0, c2m_head1 = 0;
+    uint32_t box_rf0 = 0, box_rf1 = 0;              // produced regions waiting for their STORE: lane (i & 31) = entry i
+    uint32_t box_head0 = 0, box_tail0 = 0, box_head1 = 0, box_tail1 = 0;
+    bool have = false;                              // a STORE has been picked up and is waiting
+    uint32_t r_glo = 0, r_ghi = 0, r_info = 0, stat = 0;
     Spin sp;
     bool ok = true;
     while (ok) {
-        uint32_t snap = unit_poll(c, u, head);
-        if (rf_get(snap, 0) == head) {
-            if (rf_get(snap, 13) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
-            if (!spin_step(c, sp, rf_get(snap, 14), 0x700u | u)) ok = false;
+        head = uni(head); done = uni(done); c2m_head0 = uni(c2m_head0); c2m_head1 = uni(c2m_head1);
+        box_head0 = uni(box_head0); box_tail0 = uni(box_tail0); box_head1 = uni(box_head1); box_tail1 = uni(box_tail1);
+        const uint32_t snap = stu_poll(c, u, head, c2m_head0, c2m_head1);
+        bool moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0);
+        if (V > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
+        if (!have && rf_get(snap, 4) != head) {
+            // pick the next STORE up: from here on its queue entry and its static record may be reused
+            r_glo = rf_get(snap, 5); r_ghi = rf_get(snap, 6); r_info = rf_get(snap, 7);
+            stat = stat_fetch(c, r_info);
+            stat = stat + 0u;
+            lds_wait();
+            head++;
+            if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
+            reconverge();
+            have = true;
+            moved = true;
+        }
+        if (have) {
+            const uint32_t w0 = rf_get(stat, 4), dep = rf_get(stat, 5);
+            const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u, nslots = (w0 >> 25) & 63u;
+            const uint32_t slot = r_info & 63u;
+            c.pc = c.stream_pc0 + rf_get(stat, 6);
+            bool ready = true;
+            if (flags & F_DEP_RECV) {
+                uint32_t need = (dep >> 16) & 0xFFu;
+                if (need == 0u) need = 1u;
+                ready = uni(__hip_atomic_load(&c.p->dep[dep & 0xFFFFu], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT)) >= need;
+            }
+            if (ready && (flags & F_RECV)) {
+                // wait for the compute core to hand the region back as "produced"
+                const uint32_t bh = vcc == 0u ? box_head0 : box_head1, bt = vcc == 0u ? box_tail0 : box_tail1;
+                ready = bh != bt;
+                if (ready) {
+                    const uint32_t got = rf_get(vcc == 0u ? box_rf0 : box_rf1, bh & (kMbox - 1));
+                    if (got != (slot | (nslots << 6))) {
+                        raise_error(c, -3 /* VDC_EPROGRAM */, 0x900u | got);
+                        ok = false;
+                        break;
+                    }
+                    if (vcc == 0u) box_head0++; else box_head1++;
+                }
+            }
+            if (ready) {
+                const uint64_t gaddr = (uint64_t)r_glo | ((uint64_t)r_ghi << 32);
+                const uint64_t gpitch = (uint64_t)rf_get(stat, 0) | ((uint64_t)rf_get(stat, 1) << 32);
+                const uint32_t rows = rf_get(stat, 2) & 0xFFFFu, rb_pitch = rf_get(stat, 3);
+                const uint32_t row_words = (rb_pitch & 0xFFFFu) >> 2, lds_pitch = rb_pitch >> 16;
+                const uint32_t lds_off = slot << slot_shift;
+                const uint32_t total = rows * row_words;
+                compiler_barrier();
+                for (uint32_t i = c.lane; i < total; i += 64u) {
+                    uint32_t rr = i / row_words, cc = i % row_words;
+                    float v = lds_ldf(lds_off + rr * lds_pitch + cc * 4u);
+                    *(float *)(uintptr_t)(gaddr + (uint64_t)rr * gpitch + (uint64_t)cc * 4u) = v;
+                }
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                slots_free(c, slot, nslots);
+                if (flags & F_DEP_SEND) {
+                    __threadfence();
+                    dep_signal(c, dep);
+                }
+                done++;
+                if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_done) + u * 4u, done);
+                reconverge();
+                have = false;
+                moved = true;
+            }
+        }
+        if (moved) {
+            sp.n = 0;
             continue;
         }
-        sp.n = 0;
-        const uint64_t gaddr = (uint64_t)rf_get(snap, 1) | ((uint64_t)rf_get(snap, 2) << 32);
-        const uint64_t gpitch = (uint64_t)rf_get(snap, 3) | ((uint64_t)rf_get(snap, 4) << 32);
-        const uint32_t lds_off = rf_get(snap, 5), rows = rf_get(snap, 6) & 0xFFFFu;
-        const uint32_t rb_pitch = rf_get(snap, 7), w0 = rf_get(snap, 8);
-        const uint32_t slot = rf_get(snap, 10), dep = rf_get(snap, 11);
-        c.pc = c.stream_pc0 + rf_get(snap, 12);
-        const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u, nslots = (w0 >> 25) & 63u;
-        if (flags & F_DEP_RECV) {
-            if (!dep_wait(c, dep)) { ok = false; break; }
-        }
-        if (flags & F_RECV) {
-            // wait for the compute core to hand the region back as "produced"
-            const uint32_t mh = vcc == 0u ? mbox_head0 : mbox_head1;
-            Spin s2;
-            for (;;) {
-                if (rf_get(snap, 15u + vcc) != mh) break;
-                if (!spin_step(c, s2, rf_get(snap, 14), 0x800u | vcc)) { ok = false; break; }
-                snap = unit_poll(c, u, head);
-            }
-            if (!ok) break;
-            const uint32_t got = uni(lds_vld32(c.ctl + CTL_OFF(mbox) + (vcc * kMbox + (mh & (kMbox - 1))) * 4u));
-            if (got != (slot | (nslots << 6))) {
-                raise_error(c, -3 /* VDC_EPROGRAM */, 0x900u | got);
-                ok = false;
+        // nothing to do right now.  The unit leaves last: the front end has halted, every STORE is written, the compute
+        // cores are done and both c2m queues are empty; then every slot must be free again.
+        if (!have && rf_get(snap, 9) && rf_get(snap, 11) == 2u * V && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) {
+            const uint32_t last = stu_poll(c, u, head, c2m_head0, c2m_head1);
+            const bool more = rf_get(last, 1) == c2m_head0 + 1u || (V > 1u && rf_get(last, 3) == c2m_head1 + 1u);
+            if (!more) {
+                const uint32_t mask = rf_get(last, 12);
+                if (mask != 0u) raise_error(c, -6 /* VDC_ELEAK */, mask);
                 break;
             }
-            if (vcc == 0u) mbox_head0++; else mbox_head1++;
-            compiler_barrier();
+            continue;
         }
-        const uint32_t row_words = (rb_pitch & 0xFFFFu) >> 2, lds_pitch = rb_pitch >> 16;
-        const uint32_t total = rows * row_words;
-        for (uint32_t i = c.lane; i < total; i += 64u) {
-            uint32_t rr = i / row_words, cc = i % row_words;
-            float v = lds_ldf(lds_off + rr * lds_pitch + cc * 4u);
-            *(float *)(uintptr_t)(gaddr + (uint64_t)rr * gpitch + (uint64_t)cc * 4u) = v;
-        }
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        slots_free(c, slot, nslots);
-        if (flags & F_DEP_SEND) {
-            __threadfence();
-            dep_signal(c, dep);
-        }
-        head++;
-        if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
-        reconverge();
+        if (!spin_step(c, sp, rf_get(snap, 10), 0x700u | (have ? 0x80u : 0u))) ok = false;
     }
 }
 
@@ -874,6 +938,7 @@ struct VccState {
     uint32_t red_seq;  // cross-wave reductions done so far
     uint32_t wv;       // which of the two waves of the execution unit this is
     uint32_t t;        // thread index inside the execution unit, 0..127
+    PROF_DECL(p_pop, p_spins, p_n);
 };
 
 struct Msg {
@@ -920,6 +985,7 @@ DEV bool msg_ready(uint32_t snap, uint32_t which, uint32_t ticket, Msg &m) {
 // as (0 = used, 1 = produced).  While it waits, the first wave keeps returning finished regions.
 DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, Msg &m1) {
     Spin s;
+    PROF_DECL(q0 = PROF_NOW());
     for (;;) {
         const uint32_t snap = vcc_poll(c, vs.head);
         if (vs.wv == 0u) {
@@ -934,6 +1000,9 @@ DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, 
                 if (n == 2u) vs.hist = rf_set(vs.hist, (vs.head + 1u) & 63u, kind | (m1.slot << 1) | (m1.nslots << 7));
             }
             compiler_barrier();
+            PROF_ADD(vs.p_pop, q0);
+            PROF_ADD(vs.p_spins, 0ull - s.n + PROF_NOW());
+            PROF_INC(vs.p_n);
             return true;
         }
         if (!spin_step(c, s, rf_get(snap, 5), 0x100u | c.unit)) return false;
@@ -1102,6 +1171,10 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
     c.stream_pc0 = s.pc;
     VccState vs;
     vs.head = 0; vs.pushed = 0; vs.hist = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
+#ifdef VDC_PROFILE
+    vs.p_pop = vs.p_spins = vs.p_n = 0;
+#endif
+    PROF_DECL(pt0 = PROF_NOW());
     uint32_t trace_n = 0;
     bool ok = true;
     while (ok) {
@@ -1120,6 +1193,7 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         }
         s.pc++;
     }
+    PROF_OUT(c, 4 + c.unit * 2 + wv, 0, PROF_NOW() - pt0); PROF_OUT(c, 4 + c.unit * 2 + wv, 1, vs.p_pop); PROF_OUT(c, 4 + c.unit * 2 + wv, 2, vs.p_n); PROF_OUT(c, 4 + c.unit * 2 + wv, 3, vs.p_spins);
     if (ok && wv == 0u) {
         // return whatever the second wave was still holding when this wave ran out of uops
         Spin sp;

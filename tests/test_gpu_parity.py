@@ -197,14 +197,14 @@ def test_dep_id_chain_between_two_memory_cores():
 
 
 def test_watchdog_reports_deadlock_and_the_grid_drains():
-    """A spin limit far below the latency of a tile load: some unit gives up, every wave leaves its loop, the
+    """A spin limit of two polls, far below the latency of a tile load: some unit gives up, every wave leaves its loop, the
     kernel ends normally and the error comes back through the status word; the device stays usable."""
     rng = np.random.default_rng(7)
     M = rng.standard_normal((4096, 4096)).astype(np.float32)
     X = rng.standard_normal((1, 4096)).astype(np.float32)
     dM, dX = _dev(M), _dev(X)
     dY = torch.zeros((1, 4096), device="cuda")
-    with vdc.Executor(watchdog_spins=64) as ex:
+    with vdc.Executor(watchdog_spins=2) as ex:
         ex.matvec(dM, dX, dY, 8192)
         rc, info = ex.sync_status()
         assert rc == vdc.VDC_EDEADLOCK, (rc, info)
