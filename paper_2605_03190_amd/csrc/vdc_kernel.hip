@@ -92,7 +92,8 @@ struct Ctl {
     uint32_t w1_done[kMaxV];       // tickets the second wave of a VCC is done with
     uint32_t red_flag[kMaxV];      // cross-wave reduction hand-shake of a VCC
     uint32_t red_ack[kMaxV];
-    uint32_t pad0[2];
+    uint32_t win_gen;              // number of windows the front end has decoded so far
+    uint32_t pad0[1];
     uint64_t m2c[kMaxV][kM2C];     // low: slot | nslots << 6 | rows << 12; high: (ticket + 1) & 0xffff | row_bytes << 16
     uint64_t c2m[kMaxV][kC2M];     // low: kind | slot << 1 | nslots << 7; high: position + 1
     UnitRec uq[kMaxUnits][kUQ];
@@ -441,8 +442,14 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
     lds_st128(off, s0);
     lds_st128(off + 16, s1);
     compiler_barrier();
-    st.n_refill++;
+    st.n_refill = uni(st.n_refill + 1u);
+    if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(win_gen), st.n_refill);   // units drop what they remember of older windows
+    reconverge();
     return true;
+}
+
+DEV uint32_t lanes_below(uint64_t m, uint32_t lane) {   // how many bits of m are set below `lane`
+    return (uint32_t)__builtin_popcountll(m & ((1ull << lane) - 1ull));
 }
 
 DEV void cfu_main(Ctx &c) {
@@ -462,6 +469,7 @@ DEV void cfu_main(Ctx &c) {
     PROF_DECL(pt0 = PROF_NOW(), p_wait = 0, p_n = 0, p_polls = 0, p_ctl = 0);
 
     while (ok) {
+        s.pc = uni(s.pc); s.depth = uni(s.depth); st.ticket0 = uni(st.ticket0); st.ticket1 = uni(st.ticket1); trace_n = uni(trace_n);
         c.pc = s.pc;
         uint32_t k = s.pc - d.base;
         if (k >= (uint32_t)kWin) {
@@ -470,71 +478,127 @@ DEV void cfu_main(Ctx &c) {
         }
         const uint32_t ctlw = rf_get(d.ctl, k);
         const uint32_t opcode = ctlw & 0xFFu;
-        const uint32_t acc = (ctlw >> 20) & 7u;
-        const uint64_t a = (uint64_t)rf_get(d.a_lo, k) | ((uint64_t)rf_get(d.a_hi, k) << 32);
         if (opcode < (uint32_t)OP_LOAD) {
             Fields f;
             f.opcode = opcode;
-            f.acc = acc;
-            f.imm = (int64_t)a;
+            f.acc = (ctlw >> 20) & 7u;
+            f.imm = (int64_t)((uint64_t)rf_get(d.a_lo, k) | ((uint64_t)rf_get(d.a_hi, k) << 32));
             const int r = seq_control(s, f);
             if (r == 2) break;
             PROF_INC(p_ctl);
             continue;
         }
-        // ---- a memory uop: address generation, slot allocation in program order, dispatch by virtual flow ----
-        const uint32_t flags = (ctlw >> 8) & 0xFFu, unit = (ctlw >> 16) & 3u, vcc = (ctlw >> 18) & 3u, nslots = (ctlw >> 23) & 63u;
-        const uint64_t gaddr = a + ((flags & F_DYNAMIC) ? (uint64_t)seq_acc(s, acc) : 0ull);
-        const uint32_t tail = rf_get(st.uq_tail_rf, unit);
+        // ---- memory uops.  The run of consecutive memory uops that starts here is handled as one batch, lane
+        // (k + j) working on the j-th of them: address generation, queue positions and tickets are computed by all
+        // lanes at once; only the slot allocation walks the batch in program order (in-order allocation). ----
+        const uint32_t my_op = d.ctl & 0xFFu, my_flags = (d.ctl >> 8) & 0xFFu, my_unit = (d.ctl >> 16) & 3u;
+        const uint32_t my_vcc = (d.ctl >> 18) & 3u, my_acc = (d.ctl >> 20) & 7u, my_nslots = (d.ctl >> 23) & 63u;
+        const uint64_t mem_lanes = __ballot(my_op >= (uint32_t)OP_LOAD);
+        const uint64_t not_mem = ~(mem_lanes >> k);             // bit j clear = word k + j is a memory uop
+        uint32_t n = not_mem ? (uint32_t)__builtin_ctzll(not_mem) : (uint32_t)kWin;
+        n = n < 1u ? 1u : n;
+        n = n > (uint32_t)kUQ ? (uint32_t)kUQ : n;
+        n = n > (uint32_t)kWin - k ? (uint32_t)kWin - k : n;
+        // dynamic addresses: every lane picks its own accumulator out of the register file
+        const uint32_t acc_lo = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_lo);
+        const uint32_t acc_hi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_hi);
+        const uint64_t my_acc64 = (my_flags & F_DYNAMIC) ? ((uint64_t)acc_lo | ((uint64_t)acc_hi << 32)) : 0ull;
+        const uint64_t my_gaddr = ((uint64_t)d.a_lo | ((uint64_t)d.a_hi << 32)) + my_acc64;
+        const uint32_t tail0 = rf_get(st.uq_tail_rf, 0), tail1 = rf_get(st.uq_tail_rf, 1), tail2 = rf_get(st.uq_tail_rf, 2);
 
-        // wait for room in the unit's queue and, in program order, for the slots (in-order allocation)
-        int slot;
+        uint32_t slot_vec = 0;       // lane (k + j): first slot of the j-th uop of the batch
+        uint32_t alloc_bits = 0;
         Spin sp;
         PROF_DECL(pw0 = PROF_NOW());
-        PROF_INC(p_n);
         for (;;) {
             PROF_INC(p_polls);
             const uint32_t snap = cfu_poll(c);
-            const bool room = tail - rf_get(snap, unit) < (uint32_t)kUQ;
-            slot = slot_find(rf_get(snap, 4), nslots, n_slots, c.lane);
-            if (room && slot >= 0) break;
-            if (!spin_step(c, sp, rf_get(snap, 5), 0x300u | nslots | (room ? 0u : 0x80u))) { ok = false; break; }
+            // room in the unit queues for the whole batch?  Otherwise fall back to its first uop alone.
+            uint32_t nb = n;
+            {
+                const bool inb = c.lane >= k && c.lane < k + nb;
+                const uint32_t c0 = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == 0u));
+                const uint32_t c1 = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == 1u));
+                const uint32_t c2 = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == 2u));
+                const bool room_all = tail0 + c0 - rf_get(snap, 0) <= (uint32_t)kUQ && tail1 + c1 - rf_get(snap, 1) <= (uint32_t)kUQ &&
+                                      tail2 + c2 - rf_get(snap, 2) <= (uint32_t)kUQ;
+                if (!room_all) nb = 1u;
+            }
+            const uint32_t unit_k = (ctlw >> 16) & 3u;
+            const uint32_t tail_k = unit_k == 0u ? tail0 : (unit_k == 1u ? tail1 : tail2);
+            const bool room_first = tail_k - rf_get(snap, unit_k) < (uint32_t)kUQ;
+            // slots, uop by uop in program order
+            uint32_t mask = rf_get(snap, 4);
+            uint32_t got = 0;
+            alloc_bits = 0;
+            if (room_first) {
+                for (; got < nb; got++) {
+                    const uint32_t ns = rf_get(my_nslots, k + got);
+                    const int pos = slot_find(mask, ns, n_slots, c.lane);
+                    if (pos < 0) break;
+                    const uint32_t bits = slot_bits((uint32_t)pos, ns);
+                    mask |= bits;
+                    alloc_bits |= bits;
+                    slot_vec = rf_set(slot_vec, k + got, (uint32_t)pos);
+                }
+            }
+            if (got > 0u) { n = got; break; }
+            if (!spin_step(c, sp, rf_get(snap, 5), 0x300u | rf_get(my_nslots, k) | (room_first ? 0u : 0x80u))) { ok = false; break; }
         }
         PROF_ADD(p_wait, pw0);
         if (!ok) break;
-        uint32_t ticket = 0xFFFFFFFFu;
-        if (flags & F_SEND) {
-            if (vcc == 0u) ticket = st.ticket0++;
-            else ticket = st.ticket1++;
-        }
-        if (TRACE) {
-            const uint64_t tb = uni64((uint64_t)(uintptr_t)p->tensors[ctlw >> 29]);
-            trace_put(c, stream, trace_n, s.pc - c.stream_pc0, opcode | (rf_get(d.desc, k) << 8) | ((rf_get(d.aux, k) & 0xFFFFu) << 16), gaddr - tb);
-        }
-        // everything that is written happens in one lane: slot mask, the early hand-over of an output region,
-        // the record for the unit
-        const uint32_t tail_next = uni(tail + 1u), pc_next = uni(s.pc + 1u);
-        const uint32_t uslot = uni((uint32_t)slot);
-        const uint32_t info = uslot | (k << 6) | (((st.n_refill - 1u) & 1u) << 12);
-        const bool early = opcode == (uint32_t)OP_STORE && (flags & F_SEND);
-        const uint32_t aux = early ? rf_get(d.aux, k) : 0u;
-        if (c.lane == 0) {
-            __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
-                                  slot_bits(uslot, nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (early) {
-                // the empty output region goes to the compute core at once; the store unit only waits for it to return
-                const uint64_t e = (uint64_t)(uslot | (nslots << 6) | ((aux & 0xFFFFu) << 12)) |
-                                   ((uint64_t)(((ticket + 1u) & 0xFFFFu) | (aux & 0xFFFF0000u)) << 32);
-                lds_vst64(c.ctl + CTL_OFF(m2c) + (vcc * kM2C + (ticket & (kM2C - 1))) * 8u, e);
+        n = uni(n);
+        alloc_bits = uni(alloc_bits);
+        PROF_ADD(p_n, 0ull - n + PROF_NOW());
+        // positions in the unit queues and tickets, in program order
+        const bool inb = c.lane >= k && c.lane < k + n;
+        const uint64_t b0 = __ballot(inb && my_unit == 0u), b1 = __ballot(inb && my_unit == 1u), b2 = __ballot(inb && my_unit == 2u);
+        const uint64_t t0m = __ballot(inb && (my_flags & F_SEND) && my_vcc == 0u), t1m = __ballot(inb && (my_flags & F_SEND) && my_vcc == 1u);
+        const uint32_t cnt0 = (uint32_t)__builtin_popcountll(b0), cnt1 = (uint32_t)__builtin_popcountll(b1), cnt2 = (uint32_t)__builtin_popcountll(b2);
+        const uint32_t my_pos = my_unit == 0u ? tail0 + lanes_below(b0, c.lane) : (my_unit == 1u ? tail1 + lanes_below(b1, c.lane) : tail2 + lanes_below(b2, c.lane));
+        const uint32_t my_ticket = (my_flags & F_SEND) ? (my_vcc == 0u ? st.ticket0 + lanes_below(t0m, c.lane) : st.ticket1 + lanes_below(t1m, c.lane)) : 0xFFFFFFFFu;
+        const uint32_t new_t0 = uni(st.ticket0 + (uint32_t)__builtin_popcountll(t0m)), new_t1 = uni(st.ticket1 + (uint32_t)__builtin_popcountll(t1m));
+        const uint32_t table = (st.n_refill - 1u) & 1u;
+        const uint32_t trace_next = uni(trace_n + n), pc_next = uni(s.pc + n);
+        // per-lane new tails for lanes 0..2 (lane u = unit u)
+        const uint32_t add_vec = c.lane == 0u ? cnt0 : (c.lane == 1u ? cnt1 : (c.lane == 2u ? cnt2 : 0u));
+        const uint32_t new_tails = st.uq_tail_rf + add_vec;
+        if (inb) {
+            if (TRACE) {
+                const uint32_t tidx = trace_n + (c.lane - k);
+                uint64_t tb = 0;
+#pragma unroll
+                for (int t = 0; t < kMaxTensors; t++) tb = ((d.ctl >> 29) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tb;
+                if (tidx < p->trace_cap) {
+                    const uint64_t eff = my_gaddr - tb;
+                    u32x4 tr = {s.pc + (c.lane - k) - c.stream_pc0, my_op | (d.desc << 8) | ((d.aux & 0xFFFFu) << 16), (uint32_t)eff, (uint32_t)(eff >> 32)};
+                    *(u32x4 *)(p->trace + ((size_t)stream * p->trace_cap + tidx) * 4) = tr;
+                }
             }
-            const uint32_t off = c.ctl + CTL_OFF(uq) + (unit * kUQ + (tail & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
-            u32x4 rec = {(uint32_t)gaddr, (uint32_t)(gaddr >> 32), info, ticket};
+            if (my_op == (uint32_t)OP_STORE && (my_flags & F_SEND)) {
+                // the empty output region goes to the compute core at once; the store unit only waits for it to return
+                const uint64_t e = (uint64_t)(slot_vec | (my_nslots << 6) | ((d.aux & 0xFFFFu) << 12)) |
+                                   ((uint64_t)(((my_ticket + 1u) & 0xFFFFu) | (d.aux & 0xFFFF0000u)) << 32);
+                lds_vst64(c.ctl + CTL_OFF(m2c) + (my_vcc * kM2C + (my_ticket & (kM2C - 1))) * 8u, e);
+            }
+            const uint32_t off = c.ctl + CTL_OFF(uq) + (my_unit * kUQ + (my_pos & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
+            u32x4 rec = {(uint32_t)my_gaddr, (uint32_t)(my_gaddr >> 32), slot_vec | (c.lane << 6) | (table << 12), my_ticket};
             lds_st128(off, rec);
-            compiler_barrier();
-            lds_vst32(c.ctl + CTL_OFF(uq_tail) + unit * 4u, tail_next);
         }
         reconverge();
-        st.uq_tail_rf = rf_set(st.uq_tail_rf, unit, tail_next);
+        compiler_barrier();
+        if (c.lane < n_units) lds_vst32(c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, new_tails);     // after the records
+        reconverge();
+        if (c.lane == 0) {
+            __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)), alloc_bits,
+                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (TRACE) p->trace_count[stream] = trace_next;
+        }
+        reconverge();
+        st.uq_tail_rf = new_tails;
+        st.ticket0 = new_t0;
+        st.ticket1 = new_t1;
+        trace_n = trace_next;
         s.pc = pc_next;
     }
     PROF_OUT(c, 0, 0, PROF_NOW() - pt0); PROF_OUT(c, 0, 1, p_wait); PROF_OUT(c, 0, 2, p_n); PROF_OUT(c, 0, 3, p_polls); PROF_OUT(c, 0, 4, p_ctl);
@@ -588,12 +652,6 @@ DEV void load_lds_b128(uint32_t lds_addr_wave, const char *gptr, bool nt) {
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr_wave), "v"(gptr) : "memory");
 }
 
-struct Inflight {   // what an LDU must do once the loads of a tile have landed
-    uint32_t w0, ticket, dep;
-    uint32_t slot_ninstr;   // slot | load instructions << 8
-    uint32_t rows_rb;       // valid rows | valid row_bytes << 16
-};
-
 DEV bool dep_wait(Ctx &c, uint32_t dep) {
     uint32_t id = dep & 0xFFFFu, need = (dep >> 16) & 0xFFu;
     if (need == 0u) need = 1u;
@@ -612,18 +670,28 @@ DEV void dep_signal(Ctx &c, uint32_t dep) {
     reconverge();
 }
 
+// What an LDU must do once the loads of a tile have landed: the m2c message is built when the loads are issued.
+struct Inflight {
+    uint32_t msg_lo, msg_hi;   // the m2c entry
+    uint32_t ctl;              // load instructions [7:0] | SEND [8] | DEP_SEND [9] | m2c entry offset / 8 [19:10]
+    uint32_t dep;
+};
+
 DEV void ldu_retire(Ctx &c, const Inflight &t) {
-    const uint32_t flags = (t.w0 >> 8) & 0xFFu, vcc = (t.w0 >> 20) & 3u, nslots = (t.w0 >> 25) & 63u;
     lds_wait();   // zero fill of this tile (ds_write) is done as well
-    if (flags & F_SEND) m2c_deliver(c, vcc, t.ticket, t.slot_ninstr & 0xFFu, nslots, t.rows_rb & 0xFFFFu, t.rows_rb >> 16);
-    if (flags & F_DEP_SEND) dep_signal(c, t.dep);
+    if (t.ctl & 0x100u) {
+        if (c.lane == 0) lds_vst64(c.ctl + CTL_OFF(m2c) + ((t.ctl >> 10) & 0x3FFu) * 8u, (uint64_t)t.msg_lo | ((uint64_t)t.msg_hi << 32));
+        reconverge();
+    }
+    if (t.ctl & 0x200u) dep_signal(c, t.dep);
 }
 
 // One gathered read of what a load unit looks at: lane 0 = uq_tail[u], lanes 1..4 = the record at `head`,
-// lane 5 = cfu_halted, lane 6 = abort.
+// lane 5 = cfu_halted, lane 6 = abort, lane 7 = win_gen.
 DEV uint32_t ldu_poll(Ctx &c, uint32_t u, uint32_t head) {
     const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
-    uint32_t off = c.ctl + CTL_OFF(abort);
+    uint32_t off = c.ctl + CTL_OFF(win_gen);
+    off = c.lane == 6u ? c.ctl + CTL_OFF(abort) : off;
     off = c.lane == 5u ? c.ctl + CTL_OFF(cfu_halted) : off;
     off = c.lane <= 4u ? rec + (c.lane - 1u) * 4u : off;
     off = c.lane == 0u ? c.ctl + CTL_OFF(uq_tail) + u * 4u : off;
@@ -641,7 +709,11 @@ DEV void ldu_main(Ctx &c) {
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds0();
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     // tiles in flight: a ring in a lane register file (lane k = entry k), oldest at fl_head
-    uint32_t fl_w0 = 0, fl_ticket = 0, fl_dep = 0, fl_sn = 0, fl_rr = 0;
+    uint32_t fl_lo = 0, fl_hi = 0, fl_ctl = 0, fl_dep = 0;
+    // the static records of the two uops seen last (a loop body alternates between very few): lanes 0..7 of a register.
+    // Keys are (table, window lane); both are dropped whenever the front end has decoded a new window, which the
+    // poll sees in the same snapshot as any record dispatched from it.
+    uint32_t sc_key0 = 0xFFFFFFFFu, sc_key1 = 0xFFFFFFFFu, sc_val0 = 0, sc_val1 = 0, sc_gen = 0;
     uint32_t fl_head = 0;
     uint32_t n_fl = 0;
     uint32_t vm_out = 0;      // load instructions issued and not yet known complete
@@ -651,13 +723,26 @@ DEV void ldu_main(Ctx &c) {
     PROF_DECL(pt0 = PROF_NOW(), p_idle = 0, p_vm = 0, p_issue = 0, p_n = 0, p_idle_n = 0);
     while (ok) {
         head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head);
+        sc_key0 = uni(sc_key0); sc_key1 = uni(sc_key1); sc_gen = uni(sc_gen);
         const uint32_t snap = ldu_poll(c, u, head);
         const bool have = rf_get(snap, 0) != head;
+        if (rf_get(snap, 7) != sc_gen) {
+            sc_gen = rf_get(snap, 7);
+            sc_key0 = sc_key1 = 0xFFFFFFFFu;
+        }
         uint32_t ni = 0;
         struct { uint32_t gaddr_lo, gaddr_hi, gpitch_lo, gpitch_hi, lds_off, rows_box, rb_pitch, w0, ticket, slot, dep, pc; } r = {};
         if (have) {
             const uint32_t info = rf_get(snap, 3);
-            const uint32_t stat = stat_fetch(c, info);
+            const uint32_t key = (info >> 6) & 0x7Fu;
+            uint32_t stat;
+            if (key & 1u) {
+                if (sc_key1 != key) { sc_val1 = stat_fetch(c, info); sc_key1 = key; }
+                stat = sc_val1;
+            } else {
+                if (sc_key0 != key) { sc_val0 = stat_fetch(c, info); sc_key0 = key; }
+                stat = sc_val0;
+            }
             r.gaddr_lo = rf_get(snap, 1); r.gaddr_hi = rf_get(snap, 2); r.ticket = rf_get(snap, 4);
             r.slot = info & 63u; r.lds_off = r.slot << slot_shift;
             r.gpitch_lo = rf_get(stat, 0); r.gpitch_hi = rf_get(stat, 1); r.rows_box = rf_get(stat, 2); r.rb_pitch = rf_get(stat, 3);
@@ -671,10 +756,10 @@ DEV void ldu_main(Ctx &c) {
         if (!can_issue) {
             if (n_fl > 0) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
-                Inflight o = {rf_get(fl_w0, k), rf_get(fl_ticket, k), rf_get(fl_dep, k), rf_get(fl_sn, k), rf_get(fl_rr, k)};
+                Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
                 PROF_DECL(q0 = PROF_NOW());
-                wait_vmcnt_le(vm_out - (o.slot_ninstr >> 8));
-                vm_out -= o.slot_ninstr >> 8;
+                wait_vmcnt_le(vm_out - (o.ctl & 0xFFu));
+                vm_out -= o.ctl & 0xFFu;
                 ldu_retire(c, o);
                 PROF_ADD(p_vm, q0);
                 fl_head++;
@@ -702,7 +787,7 @@ DEV void ldu_main(Ctx &c) {
             vm_out = 0;
             for (; n_fl > 0; n_fl--, fl_head++) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
-                Inflight o = {rf_get(fl_w0, k), rf_get(fl_ticket, k), rf_get(fl_dep, k), rf_get(fl_sn, k), rf_get(fl_rr, k)};
+                Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
                 ldu_retire(c, o);
             }
             if (!dep_wait(c, r.dep)) { ok = false; break; }
@@ -763,11 +848,12 @@ DEV void ldu_main(Ctx &c) {
         }
         {
             const uint32_t k = (fl_head + n_fl) & (kMaxInflight - 1);
-            fl_w0 = rf_set(fl_w0, k, r.w0);
-            fl_ticket = rf_set(fl_ticket, k, r.ticket);
-            fl_dep = rf_set(fl_dep, k, r.dep);
-            fl_sn = rf_set(fl_sn, k, r.slot | (ni << 8));
-            fl_rr = rf_set(fl_rr, k, rows | (row_bytes << 16));
+            const uint32_t vcc = (r.w0 >> 20) & 3u, nslots = (r.w0 >> 25) & 63u;
+            fl_lo = rf_set(fl_lo, k, r.slot | (nslots << 6) | (rows << 12));
+            fl_hi = rf_set(fl_hi, k, ((r.ticket + 1u) & 0xFFFFu) | (row_bytes << 16));
+            fl_ctl = rf_set(fl_ctl, k, ni | ((flags & F_SEND) ? 0x100u : 0u) | ((flags & F_DEP_SEND) ? 0x200u : 0u) |
+                                       ((vcc * kM2C + (r.ticket & (kM2C - 1))) << 10));
+            if (flags & F_DEP_SEND) fl_dep = rf_set(fl_dep, k, r.dep);
         }
         n_fl++;
         vm_out += ni;
@@ -783,7 +869,7 @@ DEV void ldu_main(Ctx &c) {
     if (ok) {
         for (; n_fl > 0; n_fl--, fl_head++) {
             const uint32_t k = fl_head & (kMaxInflight - 1);
-            Inflight o = {rf_get(fl_w0, k), rf_get(fl_ticket, k), rf_get(fl_dep, k), rf_get(fl_sn, k), rf_get(fl_rr, k)};
+            Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
             ldu_retire(c, o);
         }
     }
