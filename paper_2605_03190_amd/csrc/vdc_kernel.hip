@@ -704,51 +704,82 @@ DEV uint32_t stat_fetch(Ctx &c, uint32_t info) {
     return lds_vld32(base + (c.lane & 7u) * 4u);
 }
 
+// Everything about a LOAD that does not change from one execution to the next, derived once from its static record
+// and kept for the two uops a unit saw last (a loop body alternates between very few).
+struct LduEnt {
+    uint32_t key;               // table | window lane, 0xffffffff = empty
+    uint32_t val;               // the static record itself: lanes 0..7
+    uint32_t ni;                // load instructions per tile
+    uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path
+    uint32_t step_lo, step_hi;  // fast path: address step per load instruction
+    uint32_t msg_lo, msg_hi;    // m2c entry without slot and ticket
+    uint32_t m2c_base;          // vcc * kM2C
+    uint32_t off_lo, off_hi;    // fast path, per lane: offset of the lane's first chunk from the tile address
+};
+
+DEV void ldu_derive(Ctx &c, LduEnt &e, uint32_t key, uint32_t info) {
+    e.key = key;
+    e.val = stat_fetch(c, info);
+    const uint64_t gpitch = (uint64_t)rf_get(e.val, 0) | ((uint64_t)rf_get(e.val, 1) << 32);
+    const uint32_t rows_box = rf_get(e.val, 2), rb_pitch = rf_get(e.val, 3), w0 = rf_get(e.val, 4);
+    const uint32_t rows = rows_box & 0xFFFFu, box_rows = rows_box >> 16, row_bytes = rb_pitch & 0xFFFFu, lds_pitch = rb_pitch >> 16;
+    const uint32_t cpr = lds_pitch >> 4, vcr = row_bytes >> 4, total = box_rows * cpr;
+    const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u, nslots = (w0 >> 25) & 63u;
+    e.ni = (total + 63u) >> 6;
+    const bool pow2 = (cpr & (cpr - 1u)) == 0u && cpr <= 64u;
+    const bool fast = pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u;
+    e.bits = ((flags & F_NT) ? 1u : 0u) | ((flags & F_SEND) ? 2u : 0u) | ((flags & F_DEP_SEND) ? 4u : 0u) |
+             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u);
+    uint32_t sh = 0, drow = 0;
+    if (pow2) { sh = __builtin_ctz(cpr); drow = 64u >> sh; }
+    const uint64_t step = (uint64_t)drow * gpitch;
+    e.step_lo = (uint32_t)step;
+    e.step_hi = (uint32_t)(step >> 32);
+    e.msg_lo = (nslots << 6) | (rows << 12);
+    e.msg_hi = row_bytes << 16;
+    e.m2c_base = vcc * kM2C;
+    const uint64_t off = (uint64_t)(c.lane >> sh) * gpitch + (uint64_t)(c.lane & (cpr - 1u)) * 16u;
+    e.off_lo = (uint32_t)off;
+    e.off_hi = (uint32_t)(off >> 32);
+}
+
 DEV void ldu_main(Ctx &c) {
     const uint32_t u = c.unit;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds0();
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     // tiles in flight: a ring in a lane register file (lane k = entry k), oldest at fl_head
     uint32_t fl_lo = 0, fl_hi = 0, fl_ctl = 0, fl_dep = 0;
-    // the static records of the two uops seen last (a loop body alternates between very few): lanes 0..7 of a register.
-    // Keys are (table, window lane); both are dropped whenever the front end has decoded a new window, which the
-    // poll sees in the same snapshot as any record dispatched from it.
-    uint32_t sc_key0 = 0xFFFFFFFFu, sc_key1 = 0xFFFFFFFFu, sc_val0 = 0, sc_val1 = 0, sc_gen = 0;
     uint32_t fl_head = 0;
     uint32_t n_fl = 0;
     uint32_t vm_out = 0;      // load instructions issued and not yet known complete
     uint32_t head = 0;
+    // Keys are (table, window lane); both entries are dropped whenever the front end has decoded a new window,
+    // which the poll sees in the same snapshot as any record dispatched from it.
+    LduEnt e0 = {}, e1 = {};
+    e0.key = e1.key = 0xFFFFFFFFu;
+    uint32_t seen_gen = 0;
     Spin sp;
     bool ok = true;
     PROF_DECL(pt0 = PROF_NOW(), p_idle = 0, p_vm = 0, p_issue = 0, p_n = 0, p_idle_n = 0);
     while (ok) {
-        head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head);
-        sc_key0 = uni(sc_key0); sc_key1 = uni(sc_key1); sc_gen = uni(sc_gen);
+        head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head); seen_gen = uni(seen_gen);
         const uint32_t snap = ldu_poll(c, u, head);
         const bool have = rf_get(snap, 0) != head;
-        if (rf_get(snap, 7) != sc_gen) {
-            sc_gen = rf_get(snap, 7);
-            sc_key0 = sc_key1 = 0xFFFFFFFFu;
+        if (rf_get(snap, 7) != seen_gen) {
+            seen_gen = rf_get(snap, 7);
+            e0.key = e1.key = 0xFFFFFFFFu;
         }
-        uint32_t ni = 0;
-        struct { uint32_t gaddr_lo, gaddr_hi, gpitch_lo, gpitch_hi, lds_off, rows_box, rb_pitch, w0, ticket, slot, dep, pc; } r = {};
+        uint32_t ni = 0, info = 0, key = 0;
         if (have) {
-            const uint32_t info = rf_get(snap, 3);
-            const uint32_t key = (info >> 6) & 0x7Fu;
-            uint32_t stat;
+            info = rf_get(snap, 3);
+            key = (info >> 6) & 0x7Fu;
             if (key & 1u) {
-                if (sc_key1 != key) { sc_val1 = stat_fetch(c, info); sc_key1 = key; }
-                stat = sc_val1;
+                if (e1.key != key) ldu_derive(c, e1, key, info);
+                ni = e1.ni;
             } else {
-                if (sc_key0 != key) { sc_val0 = stat_fetch(c, info); sc_key0 = key; }
-                stat = sc_val0;
+                if (e0.key != key) ldu_derive(c, e0, key, info);
+                ni = e0.ni;
             }
-            r.gaddr_lo = rf_get(snap, 1); r.gaddr_hi = rf_get(snap, 2); r.ticket = rf_get(snap, 4);
-            r.slot = info & 63u; r.lds_off = r.slot << slot_shift;
-            r.gpitch_lo = rf_get(stat, 0); r.gpitch_hi = rf_get(stat, 1); r.rows_box = rf_get(stat, 2); r.rb_pitch = rf_get(stat, 3);
-            r.w0 = rf_get(stat, 4); r.dep = rf_get(stat, 5); r.pc = rf_get(stat, 6);
-            const uint32_t chunks = (r.rows_box >> 16) * ((r.rb_pitch >> 16) >> 4);
-            ni = (chunks + 63u) >> 6;
         }
         ni = uni(ni);
         // retire the oldest tile when nothing can be issued on top of what is in flight
@@ -775,12 +806,16 @@ DEV void ldu_main(Ctx &c) {
             PROF_INC(p_idle_n);
             continue;
         }
-        // ---- issue the loads of record r ----
+        // ---- issue the loads of the record ----
         PROF_DECL(qi0 = PROF_NOW());
         PROF_INC(p_n);
-        c.pc = c.stream_pc0 + r.pc;
-        const uint32_t flags = (r.w0 >> 8) & 0xFFu;
-        if (flags & F_DEP_RECV) {
+        const bool odd = (key & 1u) != 0u;
+        const uint32_t val = odd ? e1.val : e0.val, bits = odd ? e1.bits : e0.bits;
+        const uint32_t e_msg_lo = odd ? e1.msg_lo : e0.msg_lo, e_msg_hi = odd ? e1.msg_hi : e0.msg_hi, e_m2c = odd ? e1.m2c_base : e0.m2c_base;
+        const uint64_t gaddr = (uint64_t)rf_get(snap, 1) | ((uint64_t)rf_get(snap, 2) << 32);
+        const uint32_t ticket = rf_get(snap, 4), slot = info & 63u, lds_off = slot << slot_shift;
+        c.pc = c.stream_pc0 + rf_get(val, 6);
+        if (bits & 8u) {
             // an unresolved dependency blocks this unit, and only this unit (Section 4.3).  Whatever is already in
             // flight is delivered first: the awaited signal may depend on it
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -790,33 +825,16 @@ DEV void ldu_main(Ctx &c) {
                 Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
                 ldu_retire(c, o);
             }
-            if (!dep_wait(c, r.dep)) { ok = false; break; }
+            if (!dep_wait(c, rf_get(val, 5))) { ok = false; break; }
         }
-        const uint32_t rows = r.rows_box & 0xFFFFu, box_rows = r.rows_box >> 16;
-        const uint32_t row_bytes = r.rb_pitch & 0xFFFFu, lds_pitch = r.rb_pitch >> 16;
-        const uint32_t cpr = lds_pitch >> 4;                 // 16-byte chunks per row of the box
-        const uint32_t vcr = row_bytes >> 4;                 // valid chunks per row
-        const uint32_t total = box_rows * cpr;
-        const uint64_t gaddr = (uint64_t)r.gaddr_lo | ((uint64_t)r.gaddr_hi << 32);
-        const uint64_t gpitch = (uint64_t)r.gpitch_lo | ((uint64_t)r.gpitch_hi << 32);
-        const bool nt = (flags & F_NT) != 0;
-        uint32_t row, col, drow, dcol;
-        if ((cpr & (cpr - 1u)) == 0u) {                      // the usual case: a power of two
-            const uint32_t sh = __builtin_ctz(cpr);
-            row = c.lane >> sh; col = c.lane & (cpr - 1u);
-            drow = 64u >> sh; dcol = 64u & (cpr - 1u);
-        } else {
-            row = c.lane / cpr; col = c.lane % cpr;
-            drow = 64u / cpr; dcol = 64u % cpr;
-        }
-        const bool full = rows == box_rows && vcr == cpr && (total & 63u) == 0u;
-        if (full && dcol == 0u) {
+        if (bits & 16u) {
             // the usual case: whole tile, a power-of-two row of at most 64 chunks.  Every instruction moves 64 / cpr
             // whole rows, so the per-lane address just advances by a uniform step
-            const char *g = (const char *)(uintptr_t)(gaddr + (uint64_t)row * gpitch + (uint64_t)col * 16u);
-            const uint64_t step = uni64((uint64_t)drow * gpitch);
-            uint32_t dst = uni(lds_base + r.lds_off);
-            if (nt) {
+            const uint64_t off = (uint64_t)(odd ? e1.off_lo : e0.off_lo) | ((uint64_t)(odd ? e1.off_hi : e0.off_hi) << 32);
+            const char *g = (const char *)(uintptr_t)(gaddr + off);
+            const uint64_t step = uni64((uint64_t)(odd ? e1.step_lo : e0.step_lo) | ((uint64_t)(odd ? e1.step_hi : e0.step_hi) << 32));
+            uint32_t dst = uni(lds_base + lds_off);
+            if (bits & 1u) {
                 for (uint32_t i = 0; i < ni; i++) {
                     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(dst), "v"(g) : "memory");
                     dst += 1024u;
@@ -830,16 +848,25 @@ DEV void ldu_main(Ctx &c) {
                 }
             }
         } else {
+            const uint64_t gpitch = (uint64_t)rf_get(val, 0) | ((uint64_t)rf_get(val, 1) << 32);
+            const uint32_t rows_box = rf_get(val, 2), rb_pitch = rf_get(val, 3);
+            const uint32_t rows = rows_box & 0xFFFFu, box_rows = rows_box >> 16;
+            const uint32_t cpr = (rb_pitch >> 16) >> 4;          // 16-byte chunks per row of the box
+            const uint32_t vcr = (rb_pitch & 0xFFFFu) >> 4;      // valid chunks per row
+            const uint32_t total = box_rows * cpr;
+            const bool nt = (bits & 1u) != 0u;
+            uint32_t row = c.lane / cpr, col = c.lane % cpr;
+            const uint32_t drow = 64u / cpr, dcol = 64u % cpr;
             for (uint32_t i = 0; i < ni; i++) {
                 const uint32_t q = i * 64u + c.lane;
                 const char *g = (const char *)(uintptr_t)(gaddr + (uint64_t)row * gpitch + (uint64_t)col * 16u);
-                const uint32_t dst = lds_base + r.lds_off + i * 1024u;
+                const uint32_t dst = lds_base + lds_off + i * 1024u;
                 const bool inside = q < total;
                 const bool valid = inside && row < rows && col < vcr;
                 if (valid) load_lds_b128(dst, g, nt);
                 if (inside && !valid) {
                     u32x4 z = {0u, 0u, 0u, 0u};
-                    lds_st128(r.lds_off + q * 16u, z);       // the box outside the valid tile reads as zero
+                    lds_st128(lds_off + q * 16u, z);             // the box outside the valid tile reads as zero
                 }
                 row += drow;
                 col += dcol;
@@ -848,12 +875,10 @@ DEV void ldu_main(Ctx &c) {
         }
         {
             const uint32_t k = (fl_head + n_fl) & (kMaxInflight - 1);
-            const uint32_t vcc = (r.w0 >> 20) & 3u, nslots = (r.w0 >> 25) & 63u;
-            fl_lo = rf_set(fl_lo, k, r.slot | (nslots << 6) | (rows << 12));
-            fl_hi = rf_set(fl_hi, k, ((r.ticket + 1u) & 0xFFFFu) | (row_bytes << 16));
-            fl_ctl = rf_set(fl_ctl, k, ni | ((flags & F_SEND) ? 0x100u : 0u) | ((flags & F_DEP_SEND) ? 0x200u : 0u) |
-                                       ((vcc * kM2C + (r.ticket & (kM2C - 1))) << 10));
-            if (flags & F_DEP_SEND) fl_dep = rf_set(fl_dep, k, r.dep);
+            fl_lo = rf_set(fl_lo, k, e_msg_lo | slot);
+            fl_hi = rf_set(fl_hi, k, e_msg_hi | ((ticket + 1u) & 0xFFFFu));
+            fl_ctl = rf_set(fl_ctl, k, ni | ((bits & 2u) ? 0x100u : 0u) | ((bits & 4u) ? 0x200u : 0u) | ((e_m2c + (ticket & (kM2C - 1))) << 10));
+            if (bits & 4u) fl_dep = rf_set(fl_dep, k, rf_get(val, 5));
         }
         n_fl++;
         vm_out += ni;
