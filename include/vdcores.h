@@ -54,7 +54,7 @@ typedef struct {
     int32_t threads_per_eu; /* must be 128 (two wave64) or 0                                          */
     int32_t slot_bytes;     /* local-memory slot size, power of two, 1024..16384; default 8192        */
     int32_t n_slots;        /* slots per core, 1..32; default = as many as fit in the CU's LDS        */
-    int32_t n_ldu;          /* load units per VMC, 1..2; default 2                                    */
+    int32_t n_ldu;          /* load units per VMC: 1, 2 or 4; default 4                                   */
     int32_t n_stu;          /* store units per VMC, must be 1 or 0 (=1)                               */
     int32_t n_dep_ids;      /* size of the global depId table; default 1024                           */
     int32_t watchdog_spins; /* polls before a waiting unit reports VDC_EDEADLOCK; default 1<<22       */

@@ -567,14 +567,14 @@ int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     if (c.vcc_per_core == 0) c.vcc_per_core = 2;
     if (c.threads_per_eu == 0) c.threads_per_eu = 128;
     if (c.slot_bytes == 0) c.slot_bytes = 8192;
-    if (c.n_ldu == 0) c.n_ldu = 2;
+    if (c.n_ldu == 0) c.n_ldu = 4;
     if (c.n_stu == 0) c.n_stu = 1;
     if (c.n_dep_ids == 0) c.n_dep_ids = 1024;
     if (c.watchdog_spins == 0) c.watchdog_spins = 1 << 22;
     if (c.n_cores < 1 || c.n_cores > cu_count) return VDC_EINVAL;   // all cores must be co-resident
     if (c.vcc_per_core < 1 || c.vcc_per_core > 2 || c.threads_per_eu != 128) return VDC_EINVAL;
     if (!is_pow2(c.slot_bytes) || c.slot_bytes < 1024 || c.slot_bytes > 16384) return VDC_EINVAL;
-    if (c.n_ldu < 1 || c.n_ldu > 2 || c.n_stu != 1) return VDC_EINVAL;   // 8 waves: 256 VGPRs each
+    if ((c.n_ldu != 1 && c.n_ldu != 2 && c.n_ldu != 4) || c.n_stu != 1) return VDC_EINVAL;   // at most 10 waves per core
     if (c.n_dep_ids < 1 || c.n_dep_ids > 65536 || c.watchdog_spins < 1 || c.tile_rows < 0) return VDC_EINVAL;
     const size_t ctl = lds_control_bytes();
     if (c.n_slots == 0) {

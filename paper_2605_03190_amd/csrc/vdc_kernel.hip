@@ -8,7 +8,7 @@
 //
 //   wave 0                      CFU   fetch / decode / control uops / address generation / slot allocation /
 //                                     dispatch by virtual flow / receiver of the c2m queues
-//   waves 1 .. n_ldu (<= 2)     LDU   direct-to-LDS 128-bit loads (global_load_lds_dwordx4), several tiles in
+//   waves 1 .. n_ldu (<= 4)     LDU   direct-to-LDS 128-bit loads (global_load_lds_dwordx4), several tiles in
 //                                     flight per unit, completion observed with s_waitcnt vmcnt(N), then the
 //                                     region is delivered into its m2c ticket
 //   next n_stu waves            STU   waits for the produced region, LDS -> global, frees the slots, signals depId
@@ -55,7 +55,7 @@ constexpr int kUQ = 8;         // records per unit queue (CFU -> LDU/STU)
 constexpr int kM2C = 32;       // m2c ring entries per VCC (>= slots, so a delivery never finds it full)
 constexpr int kC2M = 64;       // c2m ring entries per VCC
 constexpr int kMbox = 32;      // produced regions waiting for their STORE, per VCC
-constexpr int kMaxUnits = 4;   // n_ldu + n_stu
+constexpr int kMaxUnits = 8;   // n_ldu + n_stu
 constexpr int kMaxV = 2;
 constexpr int kMaxInflight = 4;  // tiles one LDU keeps in flight
 constexpr int kMaxVm = 56;       // outstanding load instructions one LDU allows itself (vmcnt holds 63)
@@ -80,7 +80,7 @@ struct StatRec {  // the static part, written for all 64 uops of a window at onc
 };
 
 struct Ctl {
-    // --- polled together by the CFU with one gathered LDS read: keep these six words contiguous ---
+    // --- polled together by the CFU with one gathered LDS read: keep these ten words contiguous ---
     uint32_t uq_head[kMaxUnits];   // records picked up by each unit
     uint32_t mask;                 // slot availability: bit set = in use (Section 4.3: 32-bit mask in shared memory)
     uint32_t abort;                // set when any unit of this core gives up
@@ -100,7 +100,7 @@ struct Ctl {
     StatRec stat[2][kWin];         // two tables: the window being executed and the previous one
     float red[kMaxV][64];
 };
-static_assert(offsetof(Ctl, mask) == offsetof(Ctl, uq_head) + 16 && offsetof(Ctl, abort) == offsetof(Ctl, mask) + 4, "poll block");
+static_assert(offsetof(Ctl, mask) == offsetof(Ctl, uq_head) + 4 * kMaxUnits && offsetof(Ctl, abort) == offsetof(Ctl, mask) + 4, "poll block");
 static_assert(offsetof(Ctl, m2c) % 8 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0 && offsetof(Ctl, stat) % 16 == 0, "alignment");
 static_assert(sizeof(UnitRec) == 4 * kRecWords && sizeof(StatRec) == 4 * kStatWords, "record size");
 #define CTL_OFF(field) ((uint32_t)offsetof(Ctl, field))
@@ -382,9 +382,10 @@ struct CfuState {
     uint32_t n_refill;
 };
 
-// One gathered read of what the front end looks at: lanes 0..3 = uq_head[0..3], lane 4 = slot mask, lane 5 = abort.
+// One gathered read of what the front end looks at: lanes 0..7 = uq_head[0..7], lane 8 = slot mask, lane 9 = abort.
+constexpr uint32_t kPollMask = kMaxUnits, kPollAbort = kMaxUnits + 1;
 DEV uint32_t cfu_poll(Ctx &c) {
-    const uint32_t l = c.lane < 5u ? c.lane : 5u;
+    const uint32_t l = c.lane < kPollAbort ? c.lane : kPollAbort;
     return lds_vld32(c.ctl + CTL_OFF(uq_head) + l * 4u);
 }
 
@@ -395,7 +396,7 @@ DEV uint32_t cfu_poll(Ctx &c) {
 // lane into a table in LDS; the per-execution record handed to the unit only names the table entry.
 struct DecWin {
     uint32_t base;       // first word in the window
-    uint32_t ctl;        // opcode [7:0] | flags [15:8] | unit [17:16] | vcc [19:18] | acc [22:20] | nslots [28:23] | tensor [31:29]
+    uint32_t ctl;        // opcode [7:0] | flags [15:8] | unit [18:16] | vcc [19] | acc [22:20] | nslots [28:23] | tensor [31:29]
     uint32_t a_lo, a_hi; // memory uop: tensor base + literal offset; control uop: the immediate
     uint32_t aux;        // valid rows [15:0] | valid row_bytes [31:16]   (for the early hand-over of an output region, and the trace)
     uint32_t desc;       // descriptor index (trace only)
@@ -415,10 +416,10 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
     uint64_t tbase = 0;
 #pragma unroll
     for (int t = 0; t < kMaxTensors; t++) tbase = ((d_tensor & (kMaxTensors - 1)) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tbase;
-    const uint32_t unit = f.opcode == OP_LOAD ? (p->n_ldu > 1u ? (f.vflow & 1u) : 0u) : p->n_ldu;
+    const uint32_t unit = f.opcode == OP_LOAD ? (f.vflow & (p->n_ldu - 1u)) : p->n_ldu;   // n_ldu is 1, 2 or 4
     const uint64_t a = (uint64_t)f.imm + (is_mem ? tbase : 0ull);
     d.base = pc;
-    d.ctl = f.opcode | (f.flags << 8) | (unit << 16) | (f.vcc << 18) | (f.acc << 20) | (f.nslots << 23) | ((d_tensor & 7u) << 29);
+    d.ctl = f.opcode | (f.flags << 8) | (unit << 16) | ((f.vcc & 1u) << 19) | (f.acc << 20) | (f.nslots << 23) | ((d_tensor & 7u) << 29);
     d.a_lo = (uint32_t)a;
     d.a_hi = (uint32_t)(a >> 32);
     d.aux = f.size | (d_rowb << 16);
@@ -434,7 +435,7 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
         const uint32_t snap = cfu_poll(c);
         const bool behind = c.lane < (uint32_t)kMaxUnits && (int32_t)(snap - mark) < 0;
         if (__ballot(behind) == 0ull) break;
-        if (!spin_step(c, sp, rf_get(snap, 5), 0x250u)) return false;
+        if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x250u)) return false;
     }
     const uint32_t off = c.ctl + CTL_OFF(stat) + (t * kWin + c.lane) * (uint32_t)sizeof(StatRec);
     u32x4 s0 = {d_gplo, d_gphi, f.size | (d_box << 16), d_rowb | (d_pitch << 16)};
@@ -491,8 +492,8 @@ DEV void cfu_main(Ctx &c) {
         // ---- memory uops.  The run of consecutive memory uops that starts here is handled as one batch, lane
         // (k + j) working on the j-th of them: address generation, queue positions and tickets are computed by all
         // lanes at once; only the slot allocation walks the batch in program order (in-order allocation). ----
-        const uint32_t my_op = d.ctl & 0xFFu, my_flags = (d.ctl >> 8) & 0xFFu, my_unit = (d.ctl >> 16) & 3u;
-        const uint32_t my_vcc = (d.ctl >> 18) & 3u, my_acc = (d.ctl >> 20) & 7u, my_nslots = (d.ctl >> 23) & 63u;
+        const uint32_t my_op = d.ctl & 0xFFu, my_flags = (d.ctl >> 8) & 0xFFu, my_unit = (d.ctl >> 16) & 7u;
+        const uint32_t my_vcc = (d.ctl >> 19) & 1u, my_acc = (d.ctl >> 20) & 7u, my_nslots = (d.ctl >> 23) & 63u;
         const uint64_t mem_lanes = __ballot(my_op >= (uint32_t)OP_LOAD);
         const uint64_t not_mem = ~(mem_lanes >> k);             // bit j clear = word k + j is a memory uop
         uint32_t n = not_mem ? (uint32_t)__builtin_ctzll(not_mem) : (uint32_t)kWin;
@@ -504,7 +505,8 @@ DEV void cfu_main(Ctx &c) {
         const uint32_t acc_hi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_hi);
         const uint64_t my_acc64 = (my_flags & F_DYNAMIC) ? ((uint64_t)acc_lo | ((uint64_t)acc_hi << 32)) : 0ull;
         const uint64_t my_gaddr = ((uint64_t)d.a_lo | ((uint64_t)d.a_hi << 32)) + my_acc64;
-        const uint32_t tail0 = rf_get(st.uq_tail_rf, 0), tail1 = rf_get(st.uq_tail_rf, 1), tail2 = rf_get(st.uq_tail_rf, 2);
+        const uint32_t unit_k = (ctlw >> 16) & 7u;
+        const uint32_t tail_k = rf_get(st.uq_tail_rf, unit_k);
 
         uint32_t slot_vec = 0;       // lane (k + j): first slot of the j-th uop of the batch
         uint32_t alloc_bits = 0;
@@ -517,18 +519,17 @@ DEV void cfu_main(Ctx &c) {
             uint32_t nb = n;
             {
                 const bool inb = c.lane >= k && c.lane < k + nb;
-                const uint32_t c0 = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == 0u));
-                const uint32_t c1 = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == 1u));
-                const uint32_t c2 = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == 2u));
-                const bool room_all = tail0 + c0 - rf_get(snap, 0) <= (uint32_t)kUQ && tail1 + c1 - rf_get(snap, 1) <= (uint32_t)kUQ &&
-                                      tail2 + c2 - rf_get(snap, 2) <= (uint32_t)kUQ;
-                if (!room_all) nb = 1u;
+                uint32_t add = 0;     // lane u: uops of the batch that go to unit u
+                for (uint32_t uu = 0; uu < n_units; uu++) {
+                    const uint32_t cu = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == uu));
+                    add = c.lane == uu ? cu : add;
+                }
+                const bool over = c.lane < n_units && st.uq_tail_rf + add - snap > (uint32_t)kUQ;
+                if (__ballot(over) != 0ull) nb = 1u;
             }
-            const uint32_t unit_k = (ctlw >> 16) & 3u;
-            const uint32_t tail_k = unit_k == 0u ? tail0 : (unit_k == 1u ? tail1 : tail2);
             const bool room_first = tail_k - rf_get(snap, unit_k) < (uint32_t)kUQ;
             // slots, uop by uop in program order
-            uint32_t mask = rf_get(snap, 4);
+            uint32_t mask = rf_get(snap, kPollMask);
             uint32_t got = 0;
             alloc_bits = 0;
             if (room_first) {
@@ -543,7 +544,7 @@ DEV void cfu_main(Ctx &c) {
                 }
             }
             if (got > 0u) { n = got; break; }
-            if (!spin_step(c, sp, rf_get(snap, 5), 0x300u | rf_get(my_nslots, k) | (room_first ? 0u : 0x80u))) { ok = false; break; }
+            if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | rf_get(my_nslots, k) | (room_first ? 0u : 0x80u))) { ok = false; break; }
         }
         PROF_ADD(p_wait, pw0);
         if (!ok) break;
@@ -552,17 +553,19 @@ DEV void cfu_main(Ctx &c) {
         PROF_ADD(p_n, 0ull - n + PROF_NOW());
         // positions in the unit queues and tickets, in program order
         const bool inb = c.lane >= k && c.lane < k + n;
-        const uint64_t b0 = __ballot(inb && my_unit == 0u), b1 = __ballot(inb && my_unit == 1u), b2 = __ballot(inb && my_unit == 2u);
+        uint32_t my_rank = 0, add_vec = 0;
+        for (uint32_t uu = 0; uu < n_units; uu++) {
+            const uint64_t bu = __ballot(inb && my_unit == uu);
+            my_rank = my_unit == uu ? lanes_below(bu, c.lane) : my_rank;
+            add_vec = c.lane == uu ? (uint32_t)__builtin_popcountll(bu) : add_vec;
+        }
+        const uint32_t my_pos = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_unit * 4u), (int)st.uq_tail_rf) + my_rank;
         const uint64_t t0m = __ballot(inb && (my_flags & F_SEND) && my_vcc == 0u), t1m = __ballot(inb && (my_flags & F_SEND) && my_vcc == 1u);
-        const uint32_t cnt0 = (uint32_t)__builtin_popcountll(b0), cnt1 = (uint32_t)__builtin_popcountll(b1), cnt2 = (uint32_t)__builtin_popcountll(b2);
-        const uint32_t my_pos = my_unit == 0u ? tail0 + lanes_below(b0, c.lane) : (my_unit == 1u ? tail1 + lanes_below(b1, c.lane) : tail2 + lanes_below(b2, c.lane));
         const uint32_t my_ticket = (my_flags & F_SEND) ? (my_vcc == 0u ? st.ticket0 + lanes_below(t0m, c.lane) : st.ticket1 + lanes_below(t1m, c.lane)) : 0xFFFFFFFFu;
         const uint32_t new_t0 = uni(st.ticket0 + (uint32_t)__builtin_popcountll(t0m)), new_t1 = uni(st.ticket1 + (uint32_t)__builtin_popcountll(t1m));
         const uint32_t table = (st.n_refill - 1u) & 1u;
         const uint32_t trace_next = uni(trace_n + n), pc_next = uni(s.pc + n);
-        // per-lane new tails for lanes 0..2 (lane u = unit u)
-        const uint32_t add_vec = c.lane == 0u ? cnt0 : (c.lane == 1u ? cnt1 : (c.lane == 2u ? cnt2 : 0u));
-        const uint32_t new_tails = st.uq_tail_rf + add_vec;
+        const uint32_t new_tails = st.uq_tail_rf + add_vec;     // lane u = unit u
         if (inb) {
             if (TRACE) {
                 const uint32_t tidx = trace_n + (c.lane - k);
@@ -615,7 +618,7 @@ DEV void cfu_main(Ctx &c) {
         for (uint32_t u = n_ldu; u < n_units; u++)
             done = done && (uni(lds_vld32(c.ctl + CTL_OFF(uq_done) + u * 4u)) == rf_get(st.uq_tail_rf, u));
         if (done) break;
-        if (!spin_step(c, sp, rf_get(snap, 5), 0x400u)) ok = false;
+        if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x400u)) ok = false;
     }
 }
 
@@ -782,8 +785,9 @@ DEV void ldu_main(Ctx &c) {
             }
         }
         ni = uni(ni);
-        // retire the oldest tile when nothing can be issued on top of what is in flight
-        const bool can_issue = have && n_fl < (uint32_t)kMaxInflight && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
+        // retire the oldest tile when nothing can be issued on top of what is in flight; the record seen by this poll
+        // stays valid meanwhile, so it can be issued right after without looking again
+        bool can_issue = have && n_fl < (uint32_t)kMaxInflight && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
         if (!can_issue) {
             if (n_fl > 0) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
@@ -796,15 +800,17 @@ DEV void ldu_main(Ctx &c) {
                 fl_head++;
                 n_fl--;
                 sp.n = 0;
+                can_issue = have && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
+                if (!can_issue) continue;
+            } else {
+                // idle
+                if (rf_get(snap, 5) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
+                PROF_DECL(q1 = PROF_NOW());
+                if (!spin_step(c, sp, rf_get(snap, 6), 0x600u | u)) ok = false;
+                PROF_ADD(p_idle, q1);
+                PROF_INC(p_idle_n);
                 continue;
             }
-            // idle
-            if (rf_get(snap, 5) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
-            PROF_DECL(q1 = PROF_NOW());
-            if (!spin_step(c, sp, rf_get(snap, 6), 0x600u | u)) ok = false;
-            PROF_ADD(p_idle, q1);
-            PROF_INC(p_idle_n);
-            continue;
         }
         // ---- issue the loads of the record ----
         PROF_DECL(qi0 = PROF_NOW());
@@ -1326,7 +1332,7 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
 // ------------------------------------------------------------------------------------------------
 // The persistent kernel: every wave takes its role and runs it to the end of the uop graph
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(512) vdc_executor_kernel(const KParams p) {
+__global__ void __launch_bounds__(640) vdc_executor_kernel(const KParams p) {
     const uint32_t wave = uni(threadIdx.x >> 6);
     Ctx c;
     c.p = &p;

@@ -32,7 +32,7 @@ def test_strerror_and_defaults_are_the_paper_deployment():
         # Table 1 caption: 1 VMC + 2 VCCs per CU, 8 KB slots; Section 4.3: 128 threads per execution unit, 32-bit mask
         assert (c.vcc_per_core, c.slot_bytes, c.threads_per_eu) == (2, 8192, 128)
         assert 1 <= c.n_slots <= 32 and c.n_slots * c.slot_bytes <= 160 * 1024
-        assert c.n_cores == 256 and c.n_ldu == 2 and c.n_stu == 1
+        assert c.n_cores == 256 and c.n_ldu == 4 and c.n_stu == 1
 
 
 def test_bad_configs_are_rejected():
