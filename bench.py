@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the factors a plain copy
 # kernel of known size gives); see profiles/ for the runs.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg5": 8611477606}
 
 
 def log(*a):
@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run a plain device-to-device copy of MIB mebibytes --steps times: "
+                         "the known traffic that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported. "
@@ -59,6 +62,16 @@ def main():
     cfg = workloads.CONFIGS[args.workload]
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("copied %d bytes %d times (each copy reads and writes that many bytes)" % (n, args.steps))
+        return
     t0 = time.time()
     w = workloads.make(cfg, device=dev)
     rows, K, B = cfg.rows, cfg.K, cfg.B

@@ -39,7 +39,7 @@ namespace vdc {
 #define PROF_NOW() __builtin_readcyclecounter()
 #define PROF_ADD(var, t0) var += PROF_NOW() - (t0)
 #define PROF_INC(var) var++
-#define PROF_OUT(c, wave, k, v) do { if ((c).lane == 0) (c).p->prof[((c).core * 8 + (wave)) * 8 + (k)] = (v); } while (0)
+#define PROF_OUT(c, wave, k, v) do { if ((c).lane == 0) (c).p->prof[((c).core * 16 + (wave)) * 8 + (k)] = (v); } while (0)
 #else
 #define PROF_DECL(...)
 #define PROF_NOW() 0ull
@@ -763,11 +763,14 @@ DEV void ldu_main(Ctx &c) {
     uint32_t seen_gen = 0;
     Spin sp;
     bool ok = true;
-    PROF_DECL(pt0 = PROF_NOW(), p_idle = 0, p_vm = 0, p_issue = 0, p_n = 0, p_idle_n = 0);
+    PROF_DECL(pt0 = PROF_NOW(), p_idle = 0, p_vm = 0, p_issue = 0, p_n = 0, p_idle_n = 0, p_poll = 0, p_iter = 0);
     while (ok) {
+        PROF_INC(p_iter);
         head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head); seen_gen = uni(seen_gen);
+        PROF_DECL(qp0 = PROF_NOW());
         const uint32_t snap = ldu_poll(c, u, head);
         const bool have = rf_get(snap, 0) != head;
+        PROF_ADD(p_poll, qp0);
         if (rf_get(snap, 7) != seen_gen) {
             seen_gen = rf_get(snap, 7);
             e0.key = e1.key = 0xFFFFFFFFu;
@@ -894,7 +897,7 @@ DEV void ldu_main(Ctx &c) {
         sp.n = 0;
         PROF_ADD(p_issue, qi0);
     }
-    PROF_OUT(c, 1 + u, 0, PROF_NOW() - pt0); PROF_OUT(c, 1 + u, 1, p_idle); PROF_OUT(c, 1 + u, 2, p_vm); PROF_OUT(c, 1 + u, 3, p_issue); PROF_OUT(c, 1 + u, 4, p_n); PROF_OUT(c, 1 + u, 5, p_idle_n);
+    PROF_OUT(c, 1 + u, 0, PROF_NOW() - pt0); PROF_OUT(c, 1 + u, 1, p_idle); PROF_OUT(c, 1 + u, 2, p_vm); PROF_OUT(c, 1 + u, 3, p_issue); PROF_OUT(c, 1 + u, 4, p_n); PROF_OUT(c, 1 + u, 5, p_idle_n); PROF_OUT(c, 1 + u, 6, p_poll); PROF_OUT(c, 1 + u, 7, p_iter);
     // never leave with loads in flight: their LDS destination belongs to this workgroup only while it lives
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (ok) {
@@ -1310,7 +1313,7 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         }
         s.pc++;
     }
-    PROF_OUT(c, 4 + c.unit * 2 + wv, 0, PROF_NOW() - pt0); PROF_OUT(c, 4 + c.unit * 2 + wv, 1, vs.p_pop); PROF_OUT(c, 4 + c.unit * 2 + wv, 2, vs.p_n); PROF_OUT(c, 4 + c.unit * 2 + wv, 3, vs.p_spins);
+    PROF_OUT(c, 6 + c.unit * 2 + wv, 0, PROF_NOW() - pt0); PROF_OUT(c, 6 + c.unit * 2 + wv, 1, vs.p_pop); PROF_OUT(c, 6 + c.unit * 2 + wv, 2, vs.p_n); PROF_OUT(c, 6 + c.unit * 2 + wv, 3, vs.p_spins);
     if (ok && wv == 0u) {
         // return whatever the second wave was still holding when this wave ran out of uops
         Spin sp;
