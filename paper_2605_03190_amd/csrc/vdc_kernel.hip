@@ -36,7 +36,12 @@ namespace vdc {
 // Cycle-bucket instrumentation for throw-away profiling builds (-DVDC_PROFILE); the product build compiles none of it.
 #ifdef VDC_PROFILE
 #define PROF_DECL(...) unsigned long long __VA_ARGS__
-#define PROF_NOW() __builtin_readcyclecounter()
+static __device__ __forceinline__ unsigned long long prof_now() {
+    unsigned long long t;
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
+    return t;
+}
+#define PROF_NOW() prof_now()
 #define PROF_ADD(var, t0) var += PROF_NOW() - (t0)
 #define PROF_INC(var) var++
 #define PROF_OUT(c, wave, k, v) do { if ((c).lane == 0) (c).p->prof[((c).core * 16 + (wave)) * 8 + (k)] = (v); } while (0)
@@ -400,6 +405,15 @@ struct DecWin {
     uint32_t a_lo, a_hi; // memory uop: tensor base + literal offset; control uop: the immediate
     uint32_t aux;        // valid rows [15:0] | valid row_bytes [31:16]   (for the early hand-over of an output region, and the trace)
     uint32_t desc;       // descriptor index (trace only)
+    // What a batch of consecutive memory uops needs, worked out once per window so that dispatching a batch is a few
+    // population counts: per lane, the window lanes below it that go to the same unit / send to the same compute core;
+    // in lane u, the window lanes that go to unit u; and the slot-count mask of the lane's uop.
+    uint32_t um_lt_lo, um_lt_hi;
+    uint32_t tm_lt_lo, tm_lt_hi;
+    uint32_t uu_lo, uu_hi;
+    uint32_t want;       // (1 << nslots) - 1
+    uint64_t mem;        // wave-uniform: lanes that hold memory uops
+    uint64_t t0, t1;     // wave-uniform: lanes whose uop sends to compute core 0 / 1
 };
 
 DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) {
@@ -424,6 +438,26 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
     d.a_hi = (uint32_t)(a >> 32);
     d.aux = f.size | (d_rowb << 16);
     d.desc = f.desc;
+    {
+        const uint64_t lt = (1ull << c.lane) - 1ull;
+        const uint32_t n_units = p->n_ldu + p->n_stu;
+        uint64_t my_um = 0, uu = 0;
+        for (uint32_t u = 0; u < n_units; u++) {
+            const uint64_t b = __ballot(is_mem && unit == u);
+            my_um = unit == u ? b : my_um;
+            uu = c.lane == u ? b : uu;
+        }
+        const bool send = is_mem && (f.flags & F_SEND) != 0u;
+        d.mem = uni64(__ballot(is_mem));
+        d.t0 = uni64(__ballot(send && (f.vcc & 1u) == 0u));
+        d.t1 = uni64(__ballot(send && (f.vcc & 1u) == 1u));
+        const uint64_t tm = send ? (((f.vcc & 1u) ? d.t1 : d.t0) & lt) : 0ull;
+        my_um &= lt;
+        d.um_lt_lo = (uint32_t)my_um; d.um_lt_hi = (uint32_t)(my_um >> 32);
+        d.tm_lt_lo = (uint32_t)tm; d.tm_lt_hi = (uint32_t)(tm >> 32);
+        d.uu_lo = (uint32_t)uu; d.uu_hi = (uint32_t)(uu >> 32);
+        d.want = f.nslots >= 32u ? 0xFFFFFFFFu : ((1u << f.nslots) - 1u);
+    }
     // The table this window writes was last used two windows ago.  Its records may still sit in a unit's queue:
     // wait until every unit has picked up everything that was dispatched from that window.
     const uint32_t t = st.n_refill & 1u;
@@ -467,7 +501,7 @@ DEV void cfu_main(Ctx &c) {
     uint32_t trace_n = 0;
     DecWin d;
     bool ok = cfu_refill(c, d, st, s.pc, s.end);
-    PROF_DECL(pt0 = PROF_NOW(), p_wait = 0, p_n = 0, p_polls = 0, p_ctl = 0);
+    PROF_DECL(pt0 = PROF_NOW(), p_wait = 0, p_n = 0, p_polls = 0, p_ctl = 0, p_poll = 0, p_pre = 0, p_post = 0);
 
     while (ok) {
         s.pc = uni(s.pc); s.depth = uni(s.depth); st.ticket0 = uni(st.ticket0); st.ticket1 = uni(st.ticket1); trace_n = uni(trace_n);
@@ -490,79 +524,81 @@ DEV void cfu_main(Ctx &c) {
             continue;
         }
         // ---- memory uops.  The run of consecutive memory uops that starts here is handled as one batch, lane
-        // (k + j) working on the j-th of them: address generation, queue positions and tickets are computed by all
-        // lanes at once; only the slot allocation walks the batch in program order (in-order allocation). ----
+        // (k + j) working on the j-th of them: addresses, queue positions and tickets are computed by all lanes at
+        // once from the masks prepared when the window was decoded; only the slot allocation walks the batch in
+        // program order (in-order allocation). ----
+        PROF_DECL(qpre = PROF_NOW());
         const uint32_t my_op = d.ctl & 0xFFu, my_flags = (d.ctl >> 8) & 0xFFu, my_unit = (d.ctl >> 16) & 7u;
         const uint32_t my_vcc = (d.ctl >> 19) & 1u, my_acc = (d.ctl >> 20) & 7u, my_nslots = (d.ctl >> 23) & 63u;
-        const uint64_t mem_lanes = __ballot(my_op >= (uint32_t)OP_LOAD);
-        const uint64_t not_mem = ~(mem_lanes >> k);             // bit j clear = word k + j is a memory uop
-        uint32_t n = not_mem ? (uint32_t)__builtin_ctzll(not_mem) : (uint32_t)kWin;
-        n = n < 1u ? 1u : n;
-        n = n > (uint32_t)kUQ ? (uint32_t)kUQ : n;
-        n = n > (uint32_t)kWin - k ? (uint32_t)kWin - k : n;
-        // dynamic addresses: every lane picks its own accumulator out of the register file
+        const uint64_t not_mem = ~(d.mem >> k);                 // bit j clear = word k + j is a memory uop
+        uint32_t nmax = not_mem ? (uint32_t)__builtin_ctzll(not_mem) : (uint32_t)kWin;
+        nmax = nmax < 1u ? 1u : nmax;
+        nmax = nmax > (uint32_t)kUQ ? (uint32_t)kUQ : nmax;
+        nmax = nmax > (uint32_t)kWin - k ? (uint32_t)kWin - k : nmax;
+        nmax = uni(nmax);
+        // dynamic addresses: every lane picks its own accumulator out of the register file; its unit's queue tail too
         const uint32_t acc_lo = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_lo);
         const uint32_t acc_hi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_hi);
+        const uint32_t my_tail = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_unit * 4u), (int)st.uq_tail_rf);
         const uint64_t my_acc64 = (my_flags & F_DYNAMIC) ? ((uint64_t)acc_lo | ((uint64_t)acc_hi << 32)) : 0ull;
         const uint64_t my_gaddr = ((uint64_t)d.a_lo | ((uint64_t)d.a_hi << 32)) + my_acc64;
-        const uint32_t unit_k = (ctlw >> 16) & 7u;
-        const uint32_t tail_k = rf_get(st.uq_tail_rf, unit_k);
+        const uint64_t my_uu = (uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32);
+        const uint64_t cand = ((1ull << nmax) - 1ull) << k;     // nmax <= kUQ < 64
+        const uint32_t add_full = (uint32_t)__builtin_popcountll(my_uu & cand);   // lane u: uops of the batch for unit u
+        const uint64_t busy_hi = n_slots >= 64u ? 0ull : (~0ull << n_slots);       // positions at or beyond n_slots count as busy
 
         uint32_t slot_vec = 0;       // lane (k + j): first slot of the j-th uop of the batch
         uint32_t alloc_bits = 0;
+        uint32_t n = 0;
         Spin sp;
+        PROF_ADD(p_pre, qpre);
         PROF_DECL(pw0 = PROF_NOW());
         for (;;) {
             PROF_INC(p_polls);
+            PROF_DECL(qq0 = PROF_NOW());
             const uint32_t snap = cfu_poll(c);
+            PROF_ADD(p_poll, qq0);
             // room in the unit queues for the whole batch?  Otherwise fall back to its first uop alone.
-            uint32_t nb = n;
-            {
-                const bool inb = c.lane >= k && c.lane < k + nb;
-                uint32_t add = 0;     // lane u: uops of the batch that go to unit u
-                for (uint32_t uu = 0; uu < n_units; uu++) {
-                    const uint32_t cu = (uint32_t)__builtin_popcountll(__ballot(inb && my_unit == uu));
-                    add = c.lane == uu ? cu : add;
-                }
-                const bool over = c.lane < n_units && st.uq_tail_rf + add - snap > (uint32_t)kUQ;
-                if (__ballot(over) != 0ull) nb = 1u;
+            uint32_t nb = nmax;
+            bool room = true;
+            if (__ballot(c.lane < n_units && st.uq_tail_rf + add_full - snap > (uint32_t)kUQ) != 0ull) {
+                const uint32_t unit_k = (ctlw >> 16) & 7u;
+                nb = 1u;
+                room = rf_get(st.uq_tail_rf, unit_k) - rf_get(snap, unit_k) < (uint32_t)kUQ;
             }
-            const bool room_first = tail_k - rf_get(snap, unit_k) < (uint32_t)kUQ;
-            // slots, uop by uop in program order
-            uint32_t mask = rf_get(snap, kPollMask);
+            // slots, uop by uop in program order: lane p probes position p, the lowest free run wins (Section 4.3)
+            uint64_t occ = (uint64_t)rf_get(snap, kPollMask) | busy_hi;
             uint32_t got = 0;
             alloc_bits = 0;
-            if (room_first) {
+            if (room) {
                 for (; got < nb; got++) {
-                    const uint32_t ns = rf_get(my_nslots, k + got);
-                    const int pos = slot_find(mask, ns, n_slots, c.lane);
-                    if (pos < 0) break;
-                    const uint32_t bits = slot_bits((uint32_t)pos, ns);
-                    mask |= bits;
+                    const uint32_t want = rf_get(d.want, k + got);
+                    const uint32_t vote = (uint32_t)__ballot(((uint32_t)(occ >> c.lane) & want) == 0u);   // lanes 0..31
+                    if (vote == 0u) break;
+                    const uint32_t pos = (uint32_t)__builtin_ctz(vote);
+                    const uint32_t bits = want << pos;
+                    occ |= bits;
                     alloc_bits |= bits;
-                    slot_vec = rf_set(slot_vec, k + got, (uint32_t)pos);
+                    slot_vec = rf_set(slot_vec, k + got, pos);
                 }
             }
             if (got > 0u) { n = got; break; }
-            if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | rf_get(my_nslots, k) | (room_first ? 0u : 0x80u))) { ok = false; break; }
+            if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | rf_get(my_nslots, k) | (room ? 0u : 0x80u))) { ok = false; break; }
         }
         PROF_ADD(p_wait, pw0);
         if (!ok) break;
         n = uni(n);
         alloc_bits = uni(alloc_bits);
-        PROF_ADD(p_n, 0ull - n + PROF_NOW());
+        PROF_DECL(qpost = PROF_NOW());
         // positions in the unit queues and tickets, in program order
-        const bool inb = c.lane >= k && c.lane < k + n;
-        uint32_t my_rank = 0, add_vec = 0;
-        for (uint32_t uu = 0; uu < n_units; uu++) {
-            const uint64_t bu = __ballot(inb && my_unit == uu);
-            my_rank = my_unit == uu ? lanes_below(bu, c.lane) : my_rank;
-            add_vec = c.lane == uu ? (uint32_t)__builtin_popcountll(bu) : add_vec;
-        }
-        const uint32_t my_pos = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_unit * 4u), (int)st.uq_tail_rf) + my_rank;
-        const uint64_t t0m = __ballot(inb && (my_flags & F_SEND) && my_vcc == 0u), t1m = __ballot(inb && (my_flags & F_SEND) && my_vcc == 1u);
-        const uint32_t my_ticket = (my_flags & F_SEND) ? (my_vcc == 0u ? st.ticket0 + lanes_below(t0m, c.lane) : st.ticket1 + lanes_below(t1m, c.lane)) : 0xFFFFFFFFu;
-        const uint32_t new_t0 = uni(st.ticket0 + (uint32_t)__builtin_popcountll(t0m)), new_t1 = uni(st.ticket1 + (uint32_t)__builtin_popcountll(t1m));
+        const uint64_t bm = uni64(((1ull << n) - 1ull) << k);
+        const bool inb = ((bm >> c.lane) & 1ull) != 0ull;
+        const uint32_t my_rank = (uint32_t)__builtin_popcountll(((uint64_t)d.um_lt_lo | ((uint64_t)d.um_lt_hi << 32)) & bm);
+        const uint32_t my_toff = (uint32_t)__builtin_popcountll(((uint64_t)d.tm_lt_lo | ((uint64_t)d.tm_lt_hi << 32)) & bm);
+        const uint32_t add_vec = (uint32_t)__builtin_popcountll(my_uu & bm);
+        const uint32_t my_pos = my_tail + my_rank;
+        const uint32_t my_ticket = (my_flags & F_SEND) ? (my_vcc == 0u ? st.ticket0 : st.ticket1) + my_toff : 0xFFFFFFFFu;
+        const uint32_t new_t0 = uni(st.ticket0 + (uint32_t)__builtin_popcountll(d.t0 & bm)), new_t1 = uni(st.ticket1 + (uint32_t)__builtin_popcountll(d.t1 & bm));
         const uint32_t table = (st.n_refill - 1u) & 1u;
         const uint32_t trace_next = uni(trace_n + n), pc_next = uni(s.pc + n);
         const uint32_t new_tails = st.uq_tail_rf + add_vec;     // lane u = unit u
@@ -603,8 +639,9 @@ DEV void cfu_main(Ctx &c) {
         st.ticket1 = new_t1;
         trace_n = trace_next;
         s.pc = pc_next;
+        PROF_ADD(p_post, qpost);
     }
-    PROF_OUT(c, 0, 0, PROF_NOW() - pt0); PROF_OUT(c, 0, 1, p_wait); PROF_OUT(c, 0, 2, p_n); PROF_OUT(c, 0, 3, p_polls); PROF_OUT(c, 0, 4, p_ctl);
+    PROF_OUT(c, 0, 0, PROF_NOW() - pt0); PROF_OUT(c, 0, 1, p_wait); PROF_OUT(c, 0, 2, p_n); PROF_OUT(c, 0, 3, p_polls); PROF_OUT(c, 0, 4, p_ctl); PROF_OUT(c, 0, 5, p_poll); PROF_OUT(c, 0, 6, p_pre); PROF_OUT(c, 0, 7, p_post);
 
     // HALT (or error): no more dispatches.  The store unit goes on receiving c2m; wait until every unit is done with
     // what it was given.
@@ -625,25 +662,28 @@ DEV void cfu_main(Ctx &c) {
 // ------------------------------------------------------------------------------------------------
 // LDU: tile loads, global -> LDS, without going through registers
 // ------------------------------------------------------------------------------------------------
+// Waits until at most n of this wave's loads are outstanding.  The count in s_waitcnt is an immediate, so the
+// threshold is rounded down to one of a few levels (waiting for fewer is always safe); nested uniform branches
+// rather than a switch, which the compiler lowers to a long chain here.
 DEV void wait_vmcnt_le(uint32_t n) {
-#define VDC_VM_CASE(k) \
-    case k:            \
-        asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); \
-        break;
-    switch (n) {
-        VDC_VM_CASE(0) VDC_VM_CASE(1) VDC_VM_CASE(2) VDC_VM_CASE(3) VDC_VM_CASE(4) VDC_VM_CASE(5) VDC_VM_CASE(6) VDC_VM_CASE(7)
-        VDC_VM_CASE(8) VDC_VM_CASE(9) VDC_VM_CASE(10) VDC_VM_CASE(11) VDC_VM_CASE(12) VDC_VM_CASE(13) VDC_VM_CASE(14)
-        VDC_VM_CASE(15) VDC_VM_CASE(16) VDC_VM_CASE(17) VDC_VM_CASE(18) VDC_VM_CASE(19) VDC_VM_CASE(20) VDC_VM_CASE(21)
-        VDC_VM_CASE(22) VDC_VM_CASE(23) VDC_VM_CASE(24) VDC_VM_CASE(25) VDC_VM_CASE(26) VDC_VM_CASE(27) VDC_VM_CASE(28)
-        VDC_VM_CASE(29) VDC_VM_CASE(30) VDC_VM_CASE(31) VDC_VM_CASE(32) VDC_VM_CASE(33) VDC_VM_CASE(34) VDC_VM_CASE(35)
-        VDC_VM_CASE(36) VDC_VM_CASE(37) VDC_VM_CASE(38) VDC_VM_CASE(39) VDC_VM_CASE(40) VDC_VM_CASE(41) VDC_VM_CASE(42)
-        VDC_VM_CASE(43) VDC_VM_CASE(44) VDC_VM_CASE(45) VDC_VM_CASE(46) VDC_VM_CASE(47) VDC_VM_CASE(48) VDC_VM_CASE(49)
-        VDC_VM_CASE(50) VDC_VM_CASE(51) VDC_VM_CASE(52) VDC_VM_CASE(53) VDC_VM_CASE(54) VDC_VM_CASE(55) VDC_VM_CASE(56)
-        default:
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            break;
+#define VDC_W(k) asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory")
+    if (n < 16u) {
+        if (n < 8u) {
+            if (n < 4u) {
+                if (n < 2u) { if (n < 1u) VDC_W(0); else VDC_W(1); }
+                else { if (n < 3u) VDC_W(2); else VDC_W(3); }
+            } else { if (n < 6u) VDC_W(4); else VDC_W(6); }
+        } else { if (n < 12u) VDC_W(8); else VDC_W(12); }
+    } else if (n < 32u) {
+        if (n < 24u) { if (n < 20u) VDC_W(16); else VDC_W(20); }
+        else { if (n < 28u) VDC_W(24); else VDC_W(28); }
+    } else if (n < 48u) {
+        if (n < 40u) { if (n < 36u) VDC_W(32); else VDC_W(36); }
+        else { if (n < 44u) VDC_W(40); else VDC_W(44); }
+    } else {
+        if (n < 52u) VDC_W(48); else if (n < 56u) VDC_W(52); else VDC_W(56);
     }
-#undef VDC_VM_CASE
+#undef VDC_W
 }
 
 DEV void load_lds_b128(uint32_t lds_addr_wave, const char *gptr, bool nt) {
@@ -1354,14 +1394,19 @@ __global__ void __launch_bounds__(640) vdc_executor_kernel(const KParams p) {
 
     if (wave == 0u) {
         c.role = ROLE_CFU; c.unit = 0;
+        // the front end is a long dependent chain of cheap instructions: let it win the issue arbitration against the
+        // compute wave that shares its SIMD
+        __builtin_amdgcn_s_setprio(3);
         cfu_main(c);
     } else if (wave <= p.n_ldu) {
         c.role = ROLE_LDU; c.unit = wave - 1u;
         c.stream_pc0 = cload(p.stream_begin, c.core * (1u + p.V));
+        __builtin_amdgcn_s_setprio(2);
         ldu_main(c);
     } else if (wave <= p.n_ldu + p.n_stu) {
         c.role = ROLE_STU; c.unit = wave - 1u;
         c.stream_pc0 = cload(p.stream_begin, c.core * (1u + p.V));
+        __builtin_amdgcn_s_setprio(2);
         stu_main(c);
     } else {
         const uint32_t k = wave - 1u - p.n_ldu - p.n_stu;
