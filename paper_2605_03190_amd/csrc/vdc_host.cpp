@@ -611,7 +611,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.V = ex->cfg.vcc_per_core;
     p.watchdog = (uint32_t)ex->cfg.watchdog_spins;
 #ifdef VDC_PROFILE
-    if (!ex->d_prof && hipMalloc(&ex->d_prof, 8 * 16 * 8 * (size_t)ex->cfg.n_cores) != hipSuccess) return VDC_ENOMEM;
+    if (!ex->d_prof && hipMalloc(&ex->d_prof, 8 * (16 * 8 * (size_t)ex->cfg.n_cores + 2 * 65536 + 8)) != hipSuccess) return VDC_ENOMEM;
     p.prof = ex->d_prof;
 #endif
     HIP_TRY(hipSetDevice(ex->cfg.device));
@@ -862,6 +862,9 @@ int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslo
 }
 
 #ifdef VDC_PROFILE
+int vdc_prof_events(vdc_executor *ex, unsigned long long *out) {   // 2 * 65536 + 1 words: the observer's log, then its count
+    return hipMemcpy(out, ex->d_prof + 16 * 8 * (size_t)ex->cfg.n_cores, 8 * (2 * 65536 + 1), hipMemcpyDeviceToHost) == hipSuccess ? 0 : VDC_EDEVICE;
+}
 int vdc_prof_read(vdc_executor *ex, unsigned long long *out) {
     return hipMemcpy(out, ex->d_prof, 8 * 16 * 8 * (size_t)ex->cfg.n_cores, hipMemcpyDeviceToHost) == hipSuccess ? 0 : VDC_EDEVICE;
 }

@@ -33,14 +33,17 @@
 
 namespace vdc {
 
-// Cycle-bucket instrumentation for throw-away profiling builds (-DVDC_PROFILE); the product build compiles none of it.
+// Instrumentation for throw-away profiling builds; the product build compiles none of it.  -DVDC_PROFILE adds an
+// observer wave (see observer_main); -DVDC_PROFILE_BUCKETS also adds per-unit cycle buckets, which slow the units.
 #ifdef VDC_PROFILE
-#define PROF_DECL(...) unsigned long long __VA_ARGS__
 static __device__ __forceinline__ unsigned long long prof_now() {
     unsigned long long t;
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
     return t;
 }
+#endif
+#if defined(VDC_PROFILE) && defined(VDC_PROFILE_BUCKETS)
+#define PROF_DECL(...) unsigned long long __VA_ARGS__
 #define PROF_NOW() prof_now()
 #define PROF_ADD(var, t0) var += PROF_NOW() - (t0)
 #define PROF_INC(var) var++
@@ -94,7 +97,7 @@ struct Ctl {
     uint32_t vcc_done;             // VCC waves that reached HALT
     uint32_t uq_tail[kMaxUnits];   // records pushed to each unit
     uint32_t uq_done[kMaxUnits];   // records completed by each unit (store units)
-    uint32_t w1_done[kMaxV];       // tickets the second wave of a VCC is done with
+    uint32_t rsv0[kMaxV];
     uint32_t red_flag[kMaxV];      // cross-wave reduction hand-shake of a VCC
     uint32_t red_ack[kMaxV];
     uint32_t win_gen;              // number of windows the front end has decoded so far
@@ -104,11 +107,25 @@ struct Ctl {
     UnitRec uq[kMaxUnits][kUQ];
     StatRec stat[2][kWin];         // two tables: the window being executed and the previous one
     float red[kMaxV][64];
+    uint32_t arrive[kMaxV][32];    // per group of tickets: how many of a VCC's two waves are done with it (counts up, odd -> even)
+#ifdef VDC_PROFILE
+    uint32_t phase[16];            // profiling builds: what each wave is doing right now (see observer_main)
+#endif
 };
 static_assert(offsetof(Ctl, mask) == offsetof(Ctl, uq_head) + 4 * kMaxUnits && offsetof(Ctl, abort) == offsetof(Ctl, mask) + 4, "poll block");
 static_assert(offsetof(Ctl, m2c) % 8 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0 && offsetof(Ctl, stat) % 16 == 0, "alignment");
 static_assert(sizeof(UnitRec) == 4 * kRecWords && sizeof(StatRec) == 4 * kStatWords, "record size");
 #define CTL_OFF(field) ((uint32_t)offsetof(Ctl, field))
+#if defined(VDC_PROFILE) && defined(VDC_PROFILE_PHASES)
+#define PHASE(c, w, id) do { if ((c).lane == 0) lds_vst32((c).ctl + CTL_OFF(phase) + (w) * 4u, (id)); reconverge(); } while (0)
+#define OBS(c, w, v)
+#elif defined(VDC_PROFILE)
+#define PHASE(c, w, id)
+#define OBS(c, w, v) lds_st32_lanes(1ull, (c).ctl + CTL_OFF(phase) + (w) * 4u, (v))
+#else
+#define PHASE(c, w, id)
+#define OBS(c, w, v)
+#endif
 
 size_t lds_control_bytes() { return (sizeof(Ctl) + 255) & ~(size_t)255; }
 size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes) {
@@ -132,10 +149,47 @@ DEV float lds_ldf(uint32_t off) { return *(const __attribute__((address_space(3)
 DEV void lds_stf(uint32_t off, float v) { *(__attribute__((address_space(3))) float *)(lds0() + off) = v; }
 // volatile accesses to the control words: every call is one LDS instruction, never cached or merged
 DEV uint32_t lds_vld32(uint32_t off) { return ((lds_vu32 *)(lds0() + off))[0]; }
+DEV uint64_t lds_vld64(uint32_t off) { return ((lds_vu64 *)(lds0() + off))[0]; }
 DEV void lds_vst32(uint32_t off, uint32_t v) { ((lds_vu32 *)(lds0() + off))[0] = v; }
 DEV void lds_vst64(uint32_t off, uint64_t v) { ((lds_vu64 *)(lds0() + off))[0] = v; }
 
 DEV void compiler_barrier() { asm volatile("" ::: "memory"); }
+// LDS stores by a wave-uniform set of lanes without control flow: the execution mask is narrowed for the one
+// instruction and restored.  A branch costs this target about as much as four scalar instructions, taken or not, and
+// a per-lane "if" also makes the compiler restructure every loop around it; the hot loops therefore avoid both.
+DEV void lds_st32_lanes(uint64_t lanes, uint32_t off, uint32_t v) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_write_b32 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lanes), "v"(off), "v"(v) : "memory");
+}
+DEV void lds_st64_lanes(uint64_t lanes, uint32_t off, uint64_t v) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_write_b64 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lanes), "v"(off), "v"(v) : "memory");
+}
+DEV void lds_st128_lanes(uint64_t lanes, uint32_t off, u32x4 v) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_write_b128 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lanes), "v"(off), "v"(v) : "memory");
+}
+DEV void lds_and32_lanes(uint64_t lanes, uint32_t off, uint32_t v) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_and_b32 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lanes), "v"(off), "v"(v) : "memory");
+}
+// LDS atomic add by lane 0 alone; returns the value before the add, wave-uniform.
+DEV uint32_t lds_add_rtn_lane0(uint32_t off, uint32_t v) {
+    uint64_t saved;
+    uint32_t r;
+    asm volatile("s_mov_b64 %1, exec\n\ts_mov_b64 exec, 1\n\tds_add_rtn_u32 %0, %2, %3\n\ts_mov_b64 exec, %1\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(r), "=&s"(saved) : "v"(off), "v"(v) : "memory");
+    return __builtin_amdgcn_readfirstlane(r);
+}
+DEV void lds_or32_lanes(uint64_t lanes, uint32_t off, uint32_t v) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_or_b32 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lanes), "v"(off), "v"(v) : "memory");
+}
 // Placed right after every "if (lane == 0) { ... }" block: an opaque statement at the point where the lanes meet
 // again, so that the optimiser cannot fold that join into later joins (which would make later, wave-uniform values
 // look as if they depended on the per-lane branch).
@@ -327,22 +381,23 @@ DEV void trace_put(Ctx &c, uint32_t stream, uint32_t &count, uint32_t pc_rel, ui
 }
 
 // ------------------------------------------------------------------------------------------------
-// SIMT slot allocator (Section 4.3): lane p probes position p; a wave vote takes the first free run.
+// Slot allocator (Section 4.3): first fit on the bitmask, lowest position first.
 // ------------------------------------------------------------------------------------------------
-DEV int slot_find(uint32_t mask, uint32_t n, uint32_t n_slots, uint32_t lane) {
-    // positions at or beyond n_slots count as busy
-    uint64_t busy = (uint64_t)mask | (~0ull << n_slots);
-    uint64_t ones = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
-    bool ok = lane < 32u && ((busy >> lane) & ones) == 0ull;
-    uint64_t vote = __ballot(ok);
-    if (vote == 0ull) return -1;
-    return (int)__builtin_ctzll(vote);
+// `busy` has a set bit for every taken position and for every position at or beyond n_slots; everything is
+// wave-uniform, so this runs on the scalar unit: f ends with bit p set iff positions p .. p + n - 1 are all free, and
+// the lowest such p wins.  (The vote of 32 probing lanes that the paper describes computes the same position.)
+DEV int slot_find(uint64_t busy, uint32_t n) {
+    uint64_t f = ~busy;
+    for (uint32_t i = 1; i < n; i++) f &= f >> 1;
+    if (f == 0ull) return -1;
+    return (int)__builtin_ctzll(f);
 }
+DEV uint64_t slots_beyond(uint32_t n_slots) { return n_slots >= 64u ? 0ull : (~0ull << n_slots); }
 
 __global__ void debug_alloc_kernel(const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n) {
     uint32_t lane = threadIdx.x & 63u;
     for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        int p = slot_find(masks[i], (uint32_t)nslots[i], (uint32_t)n_slots, lane);
+        int p = slot_find((uint64_t)uni(masks[i]) | slots_beyond((uint32_t)n_slots), uni((uint32_t)nslots[i]));
         if (lane == 0) pos[i] = p;
     }
 }
@@ -411,7 +466,7 @@ struct DecWin {
     uint32_t um_lt_lo, um_lt_hi;
     uint32_t tm_lt_lo, tm_lt_hi;
     uint32_t uu_lo, uu_hi;
-    uint32_t want;       // (1 << nslots) - 1
+    uint32_t nsp_lo, nsp_hi;   // byte j: nslots of the uop j lanes further on (j = 0..7), 0 beyond the window
     uint64_t mem;        // wave-uniform: lanes that hold memory uops
     uint64_t t0, t1;     // wave-uniform: lanes whose uop sends to compute core 0 / 1
 };
@@ -456,7 +511,13 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
         d.um_lt_lo = (uint32_t)my_um; d.um_lt_hi = (uint32_t)(my_um >> 32);
         d.tm_lt_lo = (uint32_t)tm; d.tm_lt_hi = (uint32_t)(tm >> 32);
         d.uu_lo = (uint32_t)uu; d.uu_hi = (uint32_t)(uu >> 32);
-        d.want = f.nslots >= 32u ? 0xFFFFFFFFu : ((1u << f.nslots) - 1u);
+        uint64_t nsp = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < 8u; j++) {
+            const uint32_t o = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((c.lane + j) & 63u) * 4u), (int)f.nslots);
+            nsp |= (uint64_t)((c.lane + j < (uint32_t)kWin) ? (o & 0xFFu) : 0u) << (8u * j);
+        }
+        d.nsp_lo = (uint32_t)nsp; d.nsp_hi = (uint32_t)(nsp >> 32);
     }
     // The table this window writes was last used two windows ago.  Its records may still sit in a unit's queue:
     // wait until every unit has picked up everything that was dispatched from that window.
@@ -503,39 +564,74 @@ DEV void cfu_main(Ctx &c) {
     bool ok = cfu_refill(c, d, st, s.pc, s.end);
     PROF_DECL(pt0 = PROF_NOW(), p_wait = 0, p_n = 0, p_polls = 0, p_ctl = 0, p_poll = 0, p_pre = 0, p_post = 0);
 
+    // The innermost loop frame is kept in scalars (top_start, top_left); outer frames wait in lanes 8.. of the
+    // register file.  Accumulators are updated by a masked vector add, so that a control uop never moves a value
+    // from the vector to the scalar side and back.
+    uint32_t top_start = 0, top_left = 0;
+    const uint64_t unit_lanes = (1ull << n_units) - 1ull;
+    const uint64_t busy_hi = slots_beyond(n_slots);
+    const uint32_t ctl_uq = c.ctl + CTL_OFF(uq), ctl_m2c = c.ctl + CTL_OFF(m2c);
     while (ok) {
-        s.pc = uni(s.pc); s.depth = uni(s.depth); st.ticket0 = uni(st.ticket0); st.ticket1 = uni(st.ticket1); trace_n = uni(trace_n);
         c.pc = s.pc;
+        PHASE(c, 0u, 1u);
         uint32_t k = s.pc - d.base;
-        if (k >= (uint32_t)kWin) {
+        if (__builtin_expect(k >= (uint32_t)kWin, 0)) {
+            PHASE(c, 0u, 7u);
             if (!cfu_refill(c, d, st, s.pc, s.end)) { ok = false; break; }
             k = 0;
         }
         const uint32_t ctlw = rf_get(d.ctl, k);
         const uint32_t opcode = ctlw & 0xFFu;
         if (opcode < (uint32_t)OP_LOAD) {
-            Fields f;
-            f.opcode = opcode;
-            f.acc = (ctlw >> 20) & 7u;
-            f.imm = (int64_t)((uint64_t)rf_get(d.a_lo, k) | ((uint64_t)rf_get(d.a_hi, k) << 32));
-            const int r = seq_control(s, f);
-            if (r == 2) break;
-            PROF_INC(p_ctl);
+            // ---- control uops ----
+            const uint32_t imm_lo = rf_get(d.a_lo, k), imm_hi = rf_get(d.a_hi, k);
+            if (__builtin_expect(opcode <= (uint32_t)OP_LOOP, 0)) {
+                if (opcode == (uint32_t)OP_HALT) break;
+                if (s.depth > 0u) {
+                    s.rf_lo = rf_set(s.rf_lo, 7u + s.depth, top_start);
+                    s.rf_hi = rf_set(s.rf_hi, 7u + s.depth, top_left);
+                }
+                top_start = s.pc + 1u;
+                top_left = imm_lo;
+                s.depth++;
+                s.pc++;
+                continue;
+            }
+            // REPEAT, ADD, SET: the accumulator
+            {
+                const bool me = c.lane == ((ctlw >> 20) & 7u);
+                const uint64_t cur = (uint64_t)s.rf_lo | ((uint64_t)s.rf_hi << 32);
+                const uint64_t imm = (uint64_t)imm_lo | ((uint64_t)imm_hi << 32);
+                const uint64_t nv = opcode == (uint32_t)OP_SET ? imm : cur + imm;
+                s.rf_lo = me ? (uint32_t)nv : s.rf_lo;
+                s.rf_hi = me ? (uint32_t)(nv >> 32) : s.rf_hi;
+            }
+            const bool rep = opcode == (uint32_t)OP_REPEAT;
+            const uint32_t left = rep ? top_left - 1u : top_left;
+            const bool back = rep && left > 0u;
+            s.pc = back ? top_start : s.pc + 1u;
+            top_left = left;
+            if (__builtin_expect(rep && left == 0u, 0)) {
+                s.depth--;
+                if (s.depth > 0u) {
+                    top_start = rf_get(s.rf_lo, 7u + s.depth);
+                    top_left = rf_get(s.rf_hi, 7u + s.depth);
+                }
+            }
             continue;
         }
         // ---- memory uops.  The run of consecutive memory uops that starts here is handled as one batch, lane
         // (k + j) working on the j-th of them: addresses, queue positions and tickets are computed by all lanes at
         // once from the masks prepared when the window was decoded; only the slot allocation walks the batch in
-        // program order (in-order allocation). ----
-        PROF_DECL(qpre = PROF_NOW());
+        // program order (in-order allocation), on the scalar unit. ----
+        PHASE(c, 0u, 2u);
         const uint32_t my_op = d.ctl & 0xFFu, my_flags = (d.ctl >> 8) & 0xFFu, my_unit = (d.ctl >> 16) & 7u;
         const uint32_t my_vcc = (d.ctl >> 19) & 1u, my_acc = (d.ctl >> 20) & 7u, my_nslots = (d.ctl >> 23) & 63u;
         const uint64_t not_mem = ~(d.mem >> k);                 // bit j clear = word k + j is a memory uop
-        uint32_t nmax = not_mem ? (uint32_t)__builtin_ctzll(not_mem) : (uint32_t)kWin;
-        nmax = nmax < 1u ? 1u : nmax;
+        uint32_t nmax = (uint32_t)__builtin_ctzll(not_mem | (1ull << 63));
         nmax = nmax > (uint32_t)kUQ ? (uint32_t)kUQ : nmax;
         nmax = nmax > (uint32_t)kWin - k ? (uint32_t)kWin - k : nmax;
-        nmax = uni(nmax);
+        nmax = nmax < 1u ? 1u : nmax;
         // dynamic addresses: every lane picks its own accumulator out of the register file; its unit's queue tail too
         const uint32_t acc_lo = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_lo);
         const uint32_t acc_hi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_hi);
@@ -545,103 +641,106 @@ DEV void cfu_main(Ctx &c) {
         const uint64_t my_uu = (uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32);
         const uint64_t cand = ((1ull << nmax) - 1ull) << k;     // nmax <= kUQ < 64
         const uint32_t add_full = (uint32_t)__builtin_popcountll(my_uu & cand);   // lane u: uops of the batch for unit u
-        const uint64_t busy_hi = n_slots >= 64u ? 0ull : (~0ull << n_slots);       // positions at or beyond n_slots count as busy
+        const uint64_t nsp = (uint64_t)rf_get(d.nsp_lo, k) | ((uint64_t)rf_get(d.nsp_hi, k) << 32);   // slot counts of the batch
+        const bool small_regions = (nsp & 0xFCFCFCFCFCFCFCFCull) == 0ull;    // every uop of the batch takes at most 3 slots
+        const uint32_t unit_k = (ctlw >> 16) & 7u;
 
-        uint32_t slot_vec = 0;       // lane (k + j): first slot of the j-th uop of the batch
+        uint64_t pos_pack = 0;       // byte j: first slot of the j-th uop of the batch
         uint32_t alloc_bits = 0;
         uint32_t n = 0;
         Spin sp;
-        PROF_ADD(p_pre, qpre);
-        PROF_DECL(pw0 = PROF_NOW());
+        PHASE(c, 0u, 3u);
         for (;;) {
-            PROF_INC(p_polls);
-            PROF_DECL(qq0 = PROF_NOW());
             const uint32_t snap = cfu_poll(c);
-            PROF_ADD(p_poll, qq0);
-            // room in the unit queues for the whole batch?  Otherwise fall back to its first uop alone.
-            uint32_t nb = nmax;
-            bool room = true;
-            if (__ballot(c.lane < n_units && st.uq_tail_rf + add_full - snap > (uint32_t)kUQ) != 0ull) {
-                const uint32_t unit_k = (ctlw >> 16) & 7u;
-                nb = 1u;
-                room = rf_get(st.uq_tail_rf, unit_k) - rf_get(snap, unit_k) < (uint32_t)kUQ;
-            }
-            // slots, uop by uop in program order: lane p probes position p, the lowest free run wins (Section 4.3)
+            // room in the unit queues for the whole batch?  Otherwise only its first uop is tried, if its unit has room.
+            const uint32_t used = st.uq_tail_rf - snap;          // lane u: records unit u has not picked up yet
+            const bool over = __ballot(c.lane < n_units && used + add_full > (uint32_t)kUQ) != 0ull;
+            const bool first_full = __ballot(c.lane == unit_k && used >= (uint32_t)kUQ) != 0ull;
+            uint32_t lim = over ? 1u : nmax;
+            lim = first_full ? 0u : lim;
+            // slots, uop by uop in program order: first fit, lowest position (Section 4.3)
             uint64_t occ = (uint64_t)rf_get(snap, kPollMask) | busy_hi;
             uint32_t got = 0;
             alloc_bits = 0;
-            if (room) {
-                for (; got < nb; got++) {
-                    const uint32_t want = rf_get(d.want, k + got);
-                    const uint32_t vote = (uint32_t)__ballot(((uint32_t)(occ >> c.lane) & want) == 0u);   // lanes 0..31
-                    if (vote == 0u) break;
-                    const uint32_t pos = (uint32_t)__builtin_ctz(vote);
-                    const uint32_t bits = want << pos;
+            pos_pack = 0;
+            if (__builtin_expect(small_regions, 1)) {
+                while (got < lim) {
+                    const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
+                    const uint64_t f1 = ~occ, f2 = f1 & (f1 >> 1), f3 = f2 & (f1 >> 2);
+                    const uint64_t r = ns == 1u ? f1 : (ns == 2u ? f2 : f3);
+                    const bool fit = r != 0ull;
+                    const uint32_t pos = (uint32_t)__builtin_ctzll(r | (1ull << 63)) & 31u;
+                    const uint32_t bits = fit ? (((1u << ns) - 1u) << pos) : 0u;
                     occ |= bits;
                     alloc_bits |= bits;
-                    slot_vec = rf_set(slot_vec, k + got, pos);
+                    pos_pack |= (uint64_t)pos << (8u * got);
+                    lim = fit ? lim : 0u;
+                    got += fit ? 1u : 0u;
+                }
+            } else {
+                for (; got < lim; got++) {
+                    const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
+                    const int pos = slot_find(occ, ns);
+                    if (pos < 0) break;
+                    const uint64_t bits = ((1ull << ns) - 1ull) << (uint32_t)pos;
+                    occ |= bits;
+                    alloc_bits |= (uint32_t)bits;
+                    pos_pack |= (uint64_t)(uint32_t)pos << (8u * got);
                 }
             }
-            if (got > 0u) { n = got; break; }
-            if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | rf_get(my_nslots, k) | (room ? 0u : 0x80u))) { ok = false; break; }
+            n = got;
+            if (got > 0u) break;
+            PHASE(c, 0u, (first_full || over) ? 0u : ((uint32_t)__builtin_popcountll(~occ) >= ((uint32_t)nsp & 0xFFu) ? 4u : 5u));
+            if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | ((uint32_t)nsp & 0x3Fu) | (first_full ? 0x80u : 0u))) { ok = false; break; }
         }
-        PROF_ADD(p_wait, pw0);
         if (!ok) break;
-        n = uni(n);
-        alloc_bits = uni(alloc_bits);
-        PROF_DECL(qpost = PROF_NOW());
+        PHASE(c, 0u, 6u);
         // positions in the unit queues and tickets, in program order
-        const uint64_t bm = uni64(((1ull << n) - 1ull) << k);
-        const bool inb = ((bm >> c.lane) & 1ull) != 0ull;
+        const uint64_t bm = ((1ull << n) - 1ull) << k;
+        const uint32_t slot_vec = (uint32_t)(pos_pack >> (((c.lane - k) & 7u) * 8u)) & 0xFFu;   // lane (k + j): first slot of the j-th uop
         const uint32_t my_rank = (uint32_t)__builtin_popcountll(((uint64_t)d.um_lt_lo | ((uint64_t)d.um_lt_hi << 32)) & bm);
         const uint32_t my_toff = (uint32_t)__builtin_popcountll(((uint64_t)d.tm_lt_lo | ((uint64_t)d.tm_lt_hi << 32)) & bm);
         const uint32_t add_vec = (uint32_t)__builtin_popcountll(my_uu & bm);
         const uint32_t my_pos = my_tail + my_rank;
-        const uint32_t my_ticket = (my_flags & F_SEND) ? (my_vcc == 0u ? st.ticket0 : st.ticket1) + my_toff : 0xFFFFFFFFu;
-        const uint32_t new_t0 = uni(st.ticket0 + (uint32_t)__builtin_popcountll(d.t0 & bm)), new_t1 = uni(st.ticket1 + (uint32_t)__builtin_popcountll(d.t1 & bm));
+        const bool my_send = (my_flags & F_SEND) != 0u;
+        const uint32_t my_ticket = my_send ? (my_vcc == 0u ? st.ticket0 : st.ticket1) + my_toff : 0xFFFFFFFFu;
+        const uint32_t new_t0 = st.ticket0 + (uint32_t)__builtin_popcountll(d.t0 & bm), new_t1 = st.ticket1 + (uint32_t)__builtin_popcountll(d.t1 & bm);
         const uint32_t table = (st.n_refill - 1u) & 1u;
-        const uint32_t trace_next = uni(trace_n + n), pc_next = uni(s.pc + n);
         const uint32_t new_tails = st.uq_tail_rf + add_vec;     // lane u = unit u
-        if (inb) {
-            if (TRACE) {
-                const uint32_t tidx = trace_n + (c.lane - k);
-                uint64_t tb = 0;
+        if (__builtin_expect(TRACE, 0)) {
+            const bool inb = ((bm >> c.lane) & 1ull) != 0ull;
+            const uint32_t tidx = trace_n + (c.lane - k);
+            uint64_t tb = 0;
 #pragma unroll
-                for (int t = 0; t < kMaxTensors; t++) tb = ((d.ctl >> 29) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tb;
-                if (tidx < p->trace_cap) {
-                    const uint64_t eff = my_gaddr - tb;
-                    u32x4 tr = {s.pc + (c.lane - k) - c.stream_pc0, my_op | (d.desc << 8) | ((d.aux & 0xFFFFu) << 16), (uint32_t)eff, (uint32_t)(eff >> 32)};
-                    *(u32x4 *)(p->trace + ((size_t)stream * p->trace_cap + tidx) * 4) = tr;
-                }
+            for (int t = 0; t < kMaxTensors; t++) tb = ((d.ctl >> 29) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tb;
+            if (inb && tidx < p->trace_cap) {
+                const uint64_t eff = my_gaddr - tb;
+                u32x4 tr = {s.pc + (c.lane - k) - c.stream_pc0, my_op | (d.desc << 8) | ((d.aux & 0xFFFFu) << 16), (uint32_t)eff, (uint32_t)(eff >> 32)};
+                *(u32x4 *)(p->trace + ((size_t)stream * p->trace_cap + tidx) * 4) = tr;
             }
-            if (my_op == (uint32_t)OP_STORE && (my_flags & F_SEND)) {
-                // the empty output region goes to the compute core at once; the store unit only waits for it to return
-                const uint64_t e = (uint64_t)(slot_vec | (my_nslots << 6) | ((d.aux & 0xFFFFu) << 12)) |
-                                   ((uint64_t)(((my_ticket + 1u) & 0xFFFFu) | (d.aux & 0xFFFF0000u)) << 32);
-                lds_vst64(c.ctl + CTL_OFF(m2c) + (my_vcc * kM2C + (my_ticket & (kM2C - 1))) * 8u, e);
-            }
-            const uint32_t off = c.ctl + CTL_OFF(uq) + (my_unit * kUQ + (my_pos & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
+            reconverge();
+            if (c.lane == 0) p->trace_count[stream] = trace_n + n;
+            reconverge();
+            trace_n += n;
+        }
+        {
+            // a STORE that sends: the empty output region goes to the compute core at once; the store unit only waits
+            // for it to return
+            const uint64_t early = __ballot(my_op == (uint32_t)OP_STORE && my_send) & bm;
+            const uint64_t e = (uint64_t)(slot_vec | (my_nslots << 6) | ((d.aux & 0xFFFFu) << 12)) |
+                               ((uint64_t)(((my_ticket + 1u) & 0xFFFFu) | (d.aux & 0xFFFF0000u)) << 32);
+            lds_st64_lanes(early, ctl_m2c + (my_vcc * kM2C + (my_ticket & (kM2C - 1))) * 8u, e);
+            const uint32_t off = ctl_uq + (my_unit * kUQ + (my_pos & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
             u32x4 rec = {(uint32_t)my_gaddr, (uint32_t)(my_gaddr >> 32), slot_vec | (c.lane << 6) | (table << 12), my_ticket};
-            lds_st128(off, rec);
+            lds_st128_lanes(bm, off, rec);
+            lds_st32_lanes(unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, new_tails);     // after the records
+            lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), alloc_bits);
         }
-        reconverge();
-        compiler_barrier();
-        if (c.lane < n_units) lds_vst32(c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, new_tails);     // after the records
-        reconverge();
-        if (c.lane == 0) {
-            __hip_atomic_fetch_or((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)), alloc_bits,
-                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (TRACE) p->trace_count[stream] = trace_next;
-        }
-        reconverge();
         st.uq_tail_rf = new_tails;
         st.ticket0 = new_t0;
         st.ticket1 = new_t1;
-        trace_n = trace_next;
-        s.pc = pc_next;
-        PROF_ADD(p_post, qpost);
+        s.pc += n;
     }
-    PROF_OUT(c, 0, 0, PROF_NOW() - pt0); PROF_OUT(c, 0, 1, p_wait); PROF_OUT(c, 0, 2, p_n); PROF_OUT(c, 0, 3, p_polls); PROF_OUT(c, 0, 4, p_ctl); PROF_OUT(c, 0, 5, p_poll); PROF_OUT(c, 0, 6, p_pre); PROF_OUT(c, 0, 7, p_post);
 
     // HALT (or error): no more dispatches.  The store unit goes on receiving c2m; wait until every unit is done with
     // what it was given.
@@ -808,6 +907,7 @@ DEV void ldu_main(Ctx &c) {
         PROF_INC(p_iter);
         head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head); seen_gen = uni(seen_gen);
         PROF_DECL(qp0 = PROF_NOW());
+        PHASE(c, 1u + u, 1u);
         const uint32_t snap = ldu_poll(c, u, head);
         const bool have = rf_get(snap, 0) != head;
         PROF_ADD(p_poll, qp0);
@@ -836,9 +936,12 @@ DEV void ldu_main(Ctx &c) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
                 Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
                 PROF_DECL(q0 = PROF_NOW());
+                PHASE(c, 1u + u, 3u);
                 wait_vmcnt_le(vm_out - (o.ctl & 0xFFu));
                 vm_out -= o.ctl & 0xFFu;
+                PHASE(c, 1u + u, 4u);
                 ldu_retire(c, o);
+                OBS(c, 1u + u, fl_head + 1u);
                 PROF_ADD(p_vm, q0);
                 fl_head++;
                 n_fl--;
@@ -849,6 +952,7 @@ DEV void ldu_main(Ctx &c) {
                 // idle
                 if (rf_get(snap, 5) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
                 PROF_DECL(q1 = PROF_NOW());
+                PHASE(c, 1u + u, 5u);
                 if (!spin_step(c, sp, rf_get(snap, 6), 0x600u | u)) ok = false;
                 PROF_ADD(p_idle, q1);
                 PROF_INC(p_idle_n);
@@ -858,6 +962,7 @@ DEV void ldu_main(Ctx &c) {
         // ---- issue the loads of the record ----
         PROF_DECL(qi0 = PROF_NOW());
         PROF_INC(p_n);
+        PHASE(c, 1u + u, 2u);
         const bool odd = (key & 1u) != 0u;
         const uint32_t val = odd ? e1.val : e0.val, bits = odd ? e1.bits : e0.bits;
         const uint32_t e_msg_lo = odd ? e1.msg_lo : e0.msg_lo, e_msg_hi = odd ? e1.msg_hi : e0.msg_hi, e_m2c = odd ? e1.m2c_base : e0.m2c_base;
@@ -883,19 +988,33 @@ DEV void ldu_main(Ctx &c) {
             const char *g = (const char *)(uintptr_t)(gaddr + off);
             const uint64_t step = uni64((uint64_t)(odd ? e1.step_lo : e0.step_lo) | ((uint64_t)(odd ? e1.step_hi : e0.step_hi) << 32));
             uint32_t dst = uni(lds_base + lds_off);
+            // Four instructions per trip, straight-line: back to back they issue about four times faster than one per
+            // loop trip (a taken branch costs about as much as one of these loads)
+#define VDC_LOAD4(NT)                                                                                              \
+    asm volatile("s_mov_b32 m0, %[dst]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[g], off" NT "\n\t"                   \
+                 "s_add_u32 m0, m0, 0x400\n\tv_lshl_add_u64 %[g], %[g], 0, %[step]\n\tglobal_load_lds_dwordx4 %[g], off" NT "\n\t" \
+                 "s_add_u32 m0, m0, 0x400\n\tv_lshl_add_u64 %[g], %[g], 0, %[step]\n\tglobal_load_lds_dwordx4 %[g], off" NT "\n\t" \
+                 "s_add_u32 m0, m0, 0x400\n\tv_lshl_add_u64 %[g], %[g], 0, %[step]\n\tglobal_load_lds_dwordx4 %[g], off" NT "\n\t" \
+                 "v_lshl_add_u64 %[g], %[g], 0, %[step]"                                                           \
+                 : [g] "+v"(ga) : [dst] "s"(dst), [step] "s"(step) : "memory", "scc")
+            uint64_t ga = (uint64_t)(uintptr_t)g;
+            uint32_t i = 0;
             if (bits & 1u) {
-                for (uint32_t i = 0; i < ni; i++) {
-                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(dst), "v"(g) : "memory");
+                for (; i + 4u <= ni; i += 4u) { VDC_LOAD4(" nt"); dst += 4096u; }
+                for (; i < ni; i++) {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(dst), "v"(ga) : "memory");
                     dst += 1024u;
-                    g += step;
+                    ga += step;
                 }
             } else {
-                for (uint32_t i = 0; i < ni; i++) {
-                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(g) : "memory");
+                for (; i + 4u <= ni; i += 4u) { VDC_LOAD4(""); dst += 4096u; }
+                for (; i < ni; i++) {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(ga) : "memory");
                     dst += 1024u;
-                    g += step;
+                    ga += step;
                 }
             }
+#undef VDC_LOAD4
         } else {
             const uint64_t gpitch = (uint64_t)rf_get(val, 0) | ((uint64_t)rf_get(val, 1) << 32);
             const uint32_t rows_box = rf_get(val, 2), rb_pitch = rf_get(val, 3);
@@ -922,6 +1041,7 @@ DEV void ldu_main(Ctx &c) {
                 if (col >= cpr) { col -= cpr; row++; }
             }
         }
+        PHASE(c, 1u + u, 6u);
         {
             const uint32_t k = (fl_head + n_fl) & (kMaxInflight - 1);
             fl_lo = rf_set(fl_lo, k, e_msg_lo | slot);
@@ -984,6 +1104,27 @@ DEV bool stu_receive(Ctx &c, uint32_t lo, uint32_t hi, uint32_t &c2m_head, uint3
     return true;
 }
 
+// The used regions at the front of both c2m queues, all at once: lane 16 v + j looks at the j-th entry after the head
+// of compute core v's queue; the run of valid "used" entries that starts at each head is recycled with one LDS atomic
+// (the lanes of the run each clear their own region's bits).  Returns how many entries were taken per queue.
+DEV void stu_recycle(Ctx &c, uint32_t V, uint32_t &c2m_head0, uint32_t &c2m_head1, bool &moved, bool &produced_next) {
+    const uint32_t v = (c.lane >> 4) & 1u, j = c.lane & 15u;
+    const uint32_t hv = v ? c2m_head1 : c2m_head0;
+    const uint64_t ent = lds_vld64(c.ctl + CTL_OFF(c2m) + (v * kC2M + ((hv + j) & (kC2M - 1))) * 8u);
+    const uint32_t lo = (uint32_t)ent, hi = (uint32_t)(ent >> 32);
+    const bool valid = c.lane < 32u && v < V && hi == hv + j + 1u;
+    const uint32_t vm = (uint32_t)__ballot(valid && (lo & 1u) == 0u);
+    const uint32_t n0 = (uint32_t)__builtin_ctz(~(vm & 0xFFFFu)), n1 = (uint32_t)__builtin_ctz(~(vm >> 16));   // each <= 16
+    const uint64_t take = (uint64_t)(((1u << n0) - 1u) | (((1u << n1) - 1u) << 16));
+    const uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
+    lds_and32_lanes(take, c.ctl + CTL_OFF(mask), ~slot_bits(slot, nslots));
+    c2m_head0 += n0;
+    c2m_head1 += n1;
+    moved = (n0 | n1) != 0u;
+    // is the entry right after the run a valid "produced" one?
+    produced_next = __ballot(valid && (lo & 1u) != 0u && j == (v ? n1 : n0)) != 0ull;
+}
+
 DEV void stu_main(Ctx &c) {
     const uint32_t u = c.unit;
     const uint32_t V = c.p->V;
@@ -997,11 +1138,16 @@ DEV void stu_main(Ctx &c) {
     Spin sp;
     bool ok = true;
     while (ok) {
-        head = uni(head); done = uni(done); c2m_head0 = uni(c2m_head0); c2m_head1 = uni(c2m_head1);
-        box_head0 = uni(box_head0); box_tail0 = uni(box_tail0); box_head1 = uni(box_head1); box_tail1 = uni(box_tail1);
+        PHASE(c, 1u + c.p->n_ldu, 1u);
+        bool moved, produced_next;
+        stu_recycle(c, V, c2m_head0, c2m_head1, moved, produced_next);
+        if (moved) OBS(c, 5u, c2m_head0 | (c2m_head1 << 16));
         const uint32_t snap = stu_poll(c, u, head, c2m_head0, c2m_head1);
-        bool moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0);
-        if (V > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
+        PHASE(c, 1u + c.p->n_ldu, 2u);
+        if (__builtin_expect(produced_next, 0)) {
+            moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0) || moved;
+            if (V > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
+        }
         if (!have && rf_get(snap, 4) != head) {
             // pick the next STORE up: from here on its queue entry and its static record may be reused
             r_glo = rf_get(snap, 5); r_ghi = rf_get(snap, 6); r_info = rf_get(snap, 7);
@@ -1009,8 +1155,7 @@ DEV void stu_main(Ctx &c) {
             stat = stat + 0u;
             lds_wait();
             head++;
-            if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
-            reconverge();
+            lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_head) + u * 4u, head);
             have = true;
             moved = true;
         }
@@ -1059,8 +1204,7 @@ DEV void stu_main(Ctx &c) {
                     dep_signal(c, dep);
                 }
                 done++;
-                if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_done) + u * 4u, done);
-                reconverge();
+                lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_done) + u * 4u, done);
                 have = false;
                 moved = true;
             }
@@ -1081,6 +1225,7 @@ DEV void stu_main(Ctx &c) {
             }
             continue;
         }
+        PHASE(c, 1u + c.p->n_ldu, 5u);
         if (!spin_step(c, sp, rf_get(snap, 10), 0x700u | (have ? 0x80u : 0u))) ok = false;
     }
 }
@@ -1088,13 +1233,14 @@ DEV void stu_main(Ctx &c) {
 // ------------------------------------------------------------------------------------------------
 // VCC: compute uop handlers
 // ------------------------------------------------------------------------------------------------
-// The two waves of an execution unit pop the same tickets.  A region may go back to the memory core only when
-// both are done with it: the second wave publishes how far it is (w1_done), the first wave pushes to c2m every
-// ticket that both have finished, in ticket order, from a small history of what it popped.
+// The two waves of an execution unit pop the same tickets, in the same groups.  A region may go back to the memory
+// core only when both are done with it: each wave counts itself in on the group's arrival word, and the one that
+// arrives second pushes the group's tickets to c2m at once (c2m positions are ticket numbers, so groups may be
+// pushed in any order; the receiver takes them in order).
 struct VccState {
     uint32_t head;     // next m2c ticket to pop
-    uint32_t pushed;   // (first wave) tickets already returned through c2m
-    uint32_t hist;     // (first wave) lane (ticket & 63) = kind | slot << 1 | nslots << 7 of that ticket
+    uint32_t group;    // groups of tickets finished so far
+    uint32_t pay0, pay1;   // kind | slot << 1 | nslots << 7 of the tickets popped last
     uint32_t red_seq;  // cross-wave reductions done so far
     uint32_t wv;       // which of the two waves of the execution unit this is
     uint32_t t;        // thread index inside the execution unit, 0..127
@@ -1105,30 +1251,15 @@ struct Msg {
     uint32_t slot, nslots, rows, row_bytes;
 };
 
-// lanes 0,1 = m2c entry of ticket head (low, high), lanes 2,3 = of ticket head + 1, lane 4 = w1_done, lane 5 = abort
+// lanes 0,1 = m2c entry of ticket head (low, high), lanes 2,3 = of ticket head + 1, lane 5 = abort
 DEV uint32_t vcc_poll(Ctx &c, uint32_t head) {
     const uint32_t v = c.unit;
     const uint32_t e0 = c.ctl + CTL_OFF(m2c) + (v * kM2C + (head & (kM2C - 1))) * 8u;
     const uint32_t e1 = c.ctl + CTL_OFF(m2c) + (v * kM2C + ((head + 1u) & (kM2C - 1))) * 8u;
     uint32_t off = c.ctl + CTL_OFF(abort);
-    off = c.lane == 4u ? c.ctl + CTL_OFF(w1_done) + v * 4u : off;
     off = c.lane < 4u ? e1 + (c.lane - 2u) * 4u : off;
     off = c.lane < 2u ? e0 + c.lane * 4u : off;
     return lds_vld32(off);
-}
-
-// c2m.push for every ticket below `limit` that has not been pushed yet (first wave only)
-DEV void vcc_push_upto(Ctx &c, VccState &vs, uint32_t limit) {
-    const uint32_t v = c.unit;
-    while ((int32_t)(limit - vs.pushed) > 0) {
-        const uint32_t payload = rf_get(vs.hist, vs.pushed & 63u);
-        const uint32_t next = uni(vs.pushed + 1u);
-        if (c.lane == 0)
-            lds_vst64(c.ctl + CTL_OFF(c2m) + (v * kC2M + (vs.pushed & (kC2M - 1))) * 8u,
-                      (uint64_t)payload | ((uint64_t)next << 32));
-        reconverge();
-        vs.pushed = next;
-    }
 }
 
 DEV bool msg_ready(uint32_t snap, uint32_t which, uint32_t ticket, Msg &m) {
@@ -1146,20 +1277,17 @@ DEV bool msg_ready(uint32_t snap, uint32_t which, uint32_t ticket, Msg &m) {
 DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, Msg &m1) {
     Spin s;
     PROF_DECL(q0 = PROF_NOW());
+    PHASE(c, 6u + c.unit * 2u + vs.wv, 1u);
     for (;;) {
         const uint32_t snap = vcc_poll(c, vs.head);
-        if (vs.wv == 0u) {
-            const uint32_t w1 = rf_get(snap, 4);
-            vcc_push_upto(c, vs, (int32_t)(w1 - vs.head) < 0 ? w1 : vs.head);
-        }
         const bool r0 = msg_ready(snap, 0, vs.head, m0);
         const bool r1 = n < 2u || msg_ready(snap, 1, vs.head + 1u, m1);
         if (r0 && r1) {
-            if (vs.wv == 0u) {
-                vs.hist = rf_set(vs.hist, vs.head & 63u, kind | (m0.slot << 1) | (m0.nslots << 7));
-                if (n == 2u) vs.hist = rf_set(vs.hist, (vs.head + 1u) & 63u, kind | (m1.slot << 1) | (m1.nslots << 7));
-            }
+            vs.pay0 = kind | (m0.slot << 1) | (m0.nslots << 7);
+            vs.pay1 = kind | (m1.slot << 1) | (m1.nslots << 7);
             compiler_barrier();
+            PHASE(c, 6u + c.unit * 2u + vs.wv, 2u);
+            OBS(c, 6u + c.unit * 2u + vs.wv, vs.head + n);
             PROF_ADD(vs.p_pop, q0);
             PROF_ADD(vs.p_spins, 0ull - s.n + PROF_NOW());
             PROF_INC(vs.p_n);
@@ -1169,12 +1297,21 @@ DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, 
     }
 }
 
-// Called after the wave has finished reading (or writing) the regions of its last `n` tickets.
+// Called after the wave has finished reading (or writing) the regions of its last `n` (1 or 2) tickets: c2m.push,
+// by whichever of the two waves gets here second.
 DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n) {
     compiler_barrier();
+    const uint32_t v = c.unit;
+    const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
+    if (before & 1u) {
+        // lane j < n writes ticket head + j
+        const uint32_t tk = vs.head + c.lane;
+        const uint32_t payload = c.lane == 0u ? vs.pay0 : vs.pay1;
+        lds_st64_lanes((1ull << n) - 1ull, c.ctl + CTL_OFF(c2m) + (v * kC2M + (tk & (kC2M - 1))) * 8u,
+                       (uint64_t)payload | ((uint64_t)(tk + 1u) << 32));
+    }
     vs.head += n;
-    if (vs.wv == 1u && c.lane == 0) lds_vst32(c.ctl + CTL_OFF(w1_done) + c.unit * 4u, vs.head);
-    reconverge();
+    vs.group++;
     compiler_barrier();
 }
 
@@ -1330,8 +1467,8 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
     seq_init(c, s, cload(p->stream_begin, stream), cload(p->stream_begin, stream + 1u));
     c.stream_pc0 = s.pc;
     VccState vs;
-    vs.head = 0; vs.pushed = 0; vs.hist = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
-#ifdef VDC_PROFILE
+    vs.head = 0; vs.group = 0; vs.pay0 = 0; vs.pay1 = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
+#if defined(VDC_PROFILE) && defined(VDC_PROFILE_BUCKETS)
     vs.p_pop = vs.p_spins = vs.p_n = 0;
 #endif
     PROF_DECL(pt0 = PROF_NOW());
@@ -1354,17 +1491,6 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         s.pc++;
     }
     PROF_OUT(c, 6 + c.unit * 2 + wv, 0, PROF_NOW() - pt0); PROF_OUT(c, 6 + c.unit * 2 + wv, 1, vs.p_pop); PROF_OUT(c, 6 + c.unit * 2 + wv, 2, vs.p_n); PROF_OUT(c, 6 + c.unit * 2 + wv, 3, vs.p_spins);
-    if (ok && wv == 0u) {
-        // return whatever the second wave was still holding when this wave ran out of uops
-        Spin sp;
-        while (vs.pushed != vs.head) {
-            const uint32_t snap = vcc_poll(c, vs.head);
-            const uint32_t w1 = rf_get(snap, 4);
-            vcc_push_upto(c, vs, (int32_t)(w1 - vs.head) < 0 ? w1 : vs.head);
-            if (vs.pushed == vs.head) break;
-            if (!spin_step(c, sp, rf_get(snap, 5), 0xF00u)) break;
-        }
-    }
     compiler_barrier();
     if (c.lane == 0)
         __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(vcc_done)), 1u,
@@ -1375,7 +1501,60 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
 // ------------------------------------------------------------------------------------------------
 // The persistent kernel: every wave takes its role and runs it to the end of the uop graph
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(640) vdc_executor_kernel(const KParams p) {
+#ifdef VDC_PROFILE
+// Profiling builds only: an extra wave of core 0 that only reads.  It samples the control words (and the ticket
+// halves of the m2c rings) as fast as it can and logs every change with a time stamp: (cycles, word | value << 32).
+constexpr uint32_t kObsCap = 1u << 16;
+DEV void observer_main(Ctx &c, uint32_t V) {
+    if (c.core != 0u) return;
+    unsigned long long *log = c.p->prof + (size_t)gridDim.x * 16 * 8;
+#ifdef VDC_PROFILE_PHASES
+    // statistical profile: sample every wave's phase word as fast as possible; lane w counts how often wave w was
+    // seen in each phase
+    uint32_t h[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint32_t off = c.ctl + CTL_OFF(phase) + (c.lane & 15u) * 4u;
+    off = c.lane == 16u ? c.ctl + CTL_OFF(abort) : off;
+    off = c.lane == 17u ? c.ctl + CTL_OFF(cfu_halted) : off;
+    off = c.lane == 18u ? c.ctl + CTL_OFF(vcc_done) : off;
+    uint32_t it = 0;
+    for (; it < (1u << 24); it++) {
+        const uint32_t ph = lds_vld32(off);
+#pragma unroll
+        for (uint32_t i = 0; i < 8u; i++) h[i] += ph == i ? 1u : 0u;
+        if (rf_get(ph, 16) != 0u || (rf_get(ph, 17) != 0u && rf_get(ph, 18) == 2u * V)) break;
+    }
+    if (c.lane < 16u)
+        for (uint32_t i = 0; i < 8u; i++) log[c.lane * 8u + i] = h[i];
+    if (c.lane == 0) log[(size_t)kObsCap * 2] = it;
+    return;
+#endif
+    uint32_t prev_a = 0, n = 0;
+    const uint32_t off = c.ctl + (c.lane < 36u ? c.lane * 4u : CTL_OFF(phase) + ((c.lane - 36u) & 15u) * 4u);
+    for (uint32_t it = 0; it < (1u << 22); it++) {
+        const uint32_t a = lds_vld32(off);
+        unsigned long long t;
+        asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
+        const bool ca = a != prev_a && c.lane < 52u;
+        const uint64_t ma = __ballot(ca);
+        prev_a = a;
+        if (rf_get(a, 9) != 0u || (rf_get(a, 10) != 0u && rf_get(a, 11) == 2u * V)) break;
+        if (ma == 0ull) continue;
+        if (ca) {
+            const uint32_t idx = n + lanes_below(ma, c.lane);
+            if (idx < kObsCap) { log[idx * 2] = t; log[idx * 2 + 1] = (unsigned long long)c.lane | ((unsigned long long)a << 32); }
+        }
+        n = uni(n + (uint32_t)__builtin_popcountll(ma));
+    }
+    if (c.lane == 0) log[(size_t)kObsCap * 2] = n;
+}
+#endif
+
+#ifdef VDC_PROFILE
+#define VDC_MAX_THREADS 704
+#else
+#define VDC_MAX_THREADS 640
+#endif
+__global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) {
     const uint32_t wave = uni(threadIdx.x >> 6);
     Ctx c;
     c.p = &p;
@@ -1408,6 +1587,10 @@ __global__ void __launch_bounds__(640) vdc_executor_kernel(const KParams p) {
         c.stream_pc0 = cload(p.stream_begin, c.core * (1u + p.V));
         __builtin_amdgcn_s_setprio(2);
         stu_main(c);
+#ifdef VDC_PROFILE
+    } else if (wave == 1u + p.n_ldu + p.n_stu + 2u * p.V) {
+        observer_main(c, p.V);
+#endif
     } else {
         const uint32_t k = wave - 1u - p.n_ldu - p.n_stu;
         c.role = ROLE_VCC; c.unit = k >> 1;
@@ -1420,7 +1603,11 @@ hipError_t prepare_executor_kernels(size_t lds_bytes) {
 }
 
 hipError_t launch_executor(const KParams &p, uint32_t n_cores, bool traced, hipStream_t stream) {
+#ifdef VDC_PROFILE
+    const uint32_t waves = 2u + p.n_ldu + p.n_stu + 2u * p.V;   // one more: the observer
+#else
     const uint32_t waves = 1u + p.n_ldu + p.n_stu + 2u * p.V;
+#endif
     const size_t lds = lds_bytes_needed(p.n_slots, p.slot_bytes);
     (void)traced;   // tracing is switched by p.trace
     hipLaunchKernelGGL(vdc_executor_kernel, dim3(n_cores), dim3(waves * 64u), lds, stream, p);
