@@ -391,20 +391,27 @@ struct Tiler {
             // control uop per trip.
             for (int64_t it = 0; it < count; it++) {
                 vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, 0, 0, 0));
-                auto tile_pairs = [&](uint32_t d_m, uint32_t d_x) {
+                auto tile_pairs = [&](uint32_t d_m, uint32_t d_x, int64_t koff) {
                     for (int i = 0; i < n; i++) {
                         const int v = vs[i];
                         const int64_t blk = it * n + i;
-                        vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, 2, m_slots, rows_valid, 0, m_off + blk * R * ld * 4, d_m, 0));
-                        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(v), v, 2, x_slots, B, 0, x_off, d_x, 0));
+                        vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, 2, m_slots, rows_valid, 0, m_off + blk * R * ld * 4 + koff, d_m, 0));
+                        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(v), v, 2, x_slots, B, 0, x_off + koff, d_x, 0));
                     }
                 };
-                if (nk_full > 0) {
-                    if (nk_full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full, 0, 0));
-                    tile_pairs(dm, dx);
-                    vm.push_back(encode(nk_full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                // U K steps per trip.  (Two per trip halve the front end's fixed cost per uop, but a batch is only
+                // published when all of it is allocated, and the longer wait for the first tiles costs more.)
+                const int64_t U = 1, trips = nk_full / U, rest = nk_full % U;
+                if (trips > 0) {
+                    if (trips > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, trips, 0, 0));
+                    for (int64_t uu = 0; uu < U; uu++) tile_pairs(dm, dx, uu * Kt * 4);
+                    vm.push_back(encode(trips > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, U * (int64_t)Kt * 4, 0, 0));
                 }
-                if (ktail) tile_pairs(dmt, dxt);
+                for (int64_t uu = 0; uu < rest; uu++) {
+                    tile_pairs(dm, dx, 0);
+                    vm.push_back(encode(OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                }
+                if (ktail) tile_pairs(dmt, dxt, 0);
                 for (int i = 0; i < n; i++) {
                     const int v = vs[i];
                     vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, y_off + (it * n + i) * R * 4, dy, 0));

@@ -1304,6 +1304,7 @@ DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n) {
     const uint32_t v = c.unit;
     const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
     if (before & 1u) {
+        OBS(c, 10u + v, vs.head + n);
         // lane j < n writes ticket head + j
         const uint32_t tk = vs.head + c.lane;
         const uint32_t payload = c.lane == 0u ? vs.pay0 : vs.pay1;

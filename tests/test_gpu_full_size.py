@@ -1,0 +1,117 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times (one core per CU, default units).
+
+cfg3 and cfg4 are small enough for the fp64 oracle to compute every output.  For cfg5 (8 GiB matrix) the oracle
+computes sampled rows one by one, and properties that hold at any size cover every output: an all-rows closed form
+that is exact in fp32, and single non-zero entries at byte offsets beyond 2^32.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_03190_amd as vdc
+import workloads
+from oracle import gemv_ref
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def _worst(Y_gpu, Yr, Ya):
+    return float((np.abs(Y_gpu.astype(np.float64) - Yr) / (TOL * Ya + 1e-30)).max())
+
+
+def _free():
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def test_cfg3_every_output():
+    cfg = workloads.CONFIGS["cfg3"]
+    w = workloads.make(cfg, device="cuda")
+    Y = torch.full((cfg.B, cfg.rows), float("nan"), device="cuda")
+    with vdc.Executor(slot_bytes=cfg.slot_bytes) as ex:
+        ex.matvec(w.M, w.X, Y, cfg.tile_bytes)
+        ex.check()
+    Yr, Ya = gemv_ref.gemv_dense(w.M.cpu().numpy(), w.X.cpu().numpy())
+    assert _worst(Y.cpu().numpy(), Yr, Ya) <= 1.0
+    _free()
+
+
+def test_cfg4_ragged_every_output():
+    cfg = workloads.CONFIGS["cfg4"]
+    w = workloads.make(cfg, device="cuda")
+    Y = torch.full((cfg.rows,), float("nan"), device="cuda")
+    with vdc.Executor(slot_bytes=cfg.slot_bytes) as ex:
+        ex.matvec_ragged(w.M, w.row_off, w.X, Y, cfg.tile_bytes)
+        ex.check()
+    Yr, Ya = gemv_ref.gemv_ragged(w.M.cpu().numpy(), w.row_off, w.X.cpu().numpy())
+    assert _worst(Y.cpu().numpy(), Yr, Ya) <= 1.0
+    _free()
+
+
+@pytest.mark.parametrize("name", ["cfg5", "cfg5_b1"])
+def test_cfg5_sampled_rows_against_the_oracle(name):
+    cfg = workloads.CONFIGS[name]
+    w = workloads.make(cfg, device="cuda")
+    Y = torch.full((cfg.B, cfg.rows), float("nan"), device="cuda")
+    with vdc.Executor(slot_bytes=cfg.slot_bytes) as ex:
+        ex.matvec(w.M, w.X, Y, cfg.tile_bytes)
+        ex.check()
+        n_cores = ex.cfg.n_cores
+    Yh = Y.cpu().numpy()
+    assert np.isfinite(Yh).all(), "an output was never written"
+    # rows: first and last row of every core's share, both ends of the matrix, and a seeded random sample
+    per = cfg.rows // n_cores
+    rows = {0, cfg.rows - 1}
+    for c in range(n_cores):
+        rows.update((c * per, c * per + per - 1))
+    rng = np.random.default_rng(cfg.seed)
+    rows.update(int(r) for r in rng.integers(0, cfg.rows, 160))
+    rows = np.array(sorted(rows))
+    Ms = w.M[torch.from_numpy(rows).cuda()].cpu().numpy()
+    Yr, Ya = gemv_ref.gemv_dense(Ms, w.X.cpu().numpy())
+    assert _worst(Yh[:, rows], Yr, Ya) <= 1.0
+    del w, Y
+    _free()
+
+
+def test_cfg5_row_pattern_is_exact_for_every_output():
+    """M[i][j] = i mod 1024 and X[b] = 2^b: Y[b][i] = 2^b * K * (i mod 1024), exactly representable at every step of
+    any summation tree whose leaves are whole numbers of equal-length runs, so every one of the 8 x 32768 outputs is
+    compared bit for bit (catches a wrong row anywhere, at offsets up to 8 GiB)."""
+    cfg = workloads.CONFIGS["cfg5"]
+    a = (torch.arange(cfg.rows, device="cuda") % 1024).to(torch.float32)
+    M = a[:, None].expand(cfg.rows, cfg.K).contiguous()
+    X = (2.0 ** torch.arange(cfg.B, device="cuda", dtype=torch.float32))[:, None].expand(cfg.B, cfg.K).contiguous()
+    Y = torch.full((cfg.B, cfg.rows), float("nan"), device="cuda")
+    with vdc.Executor(slot_bytes=cfg.slot_bytes) as ex:
+        ex.matvec(M, X, Y, cfg.tile_bytes)
+        ex.check()
+    exp = (2.0 ** np.arange(cfg.B))[:, None] * (cfg.K * (np.arange(cfg.rows) % 1024))[None, :]
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), exp)
+    del M, X, Y
+    _free()
+
+
+def test_cfg5_single_entries_beyond_4_gib():
+    """One non-zero entry at a time, x[j] = j + 1: the result is j* + 1 in row i* and zero everywhere else."""
+    cfg = workloads.CONFIGS["cfg5_b1"]
+    M = torch.zeros((cfg.rows, cfg.K), device="cuda")
+    X = (torch.arange(cfg.K, device="cuda", dtype=torch.float32) + 1.0)[None, :].contiguous()
+    Y = torch.empty((1, cfg.rows), device="cuda")
+    spots = [(0, 0), (cfg.rows - 1, cfg.K - 1), (16384, 1), (16385, 65535), (20000, 12345), (32767, 0), (24575, 255), (24576, 256)]
+    with vdc.Executor(slot_bytes=cfg.slot_bytes) as ex:
+        for (i, j) in spots:
+            assert i * cfg.K * 4 + j * 4 >= (1 << 32) or i < 16384
+            M[i, j] = 1.0
+            Y.fill_(float("nan"))
+            ex.matvec(M, X, Y, cfg.tile_bytes)
+            ex.check()
+            Yh = Y.cpu().numpy()[0]
+            exp = np.zeros(cfg.rows, dtype=np.float32)
+            exp[i] = j + 1
+            assert np.array_equal(Yh, exp), (i, j)
+            M[i, j] = 0.0
+    del M, X, Y
+    _free()

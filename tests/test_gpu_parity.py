@@ -35,7 +35,7 @@ def ex():
     e.destroy()
 
 
-def test_simt_allocator_matches_first_fit_bit_exactly(ex):
+def test_slot_allocator_matches_first_fit_bit_exactly(ex):
     rng = np.random.default_rng(0)
     n = 20000
     masks = rng.integers(0, 1 << 32, n, dtype=np.uint64)
