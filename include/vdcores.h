@@ -144,6 +144,16 @@ int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, in
                        const int64_t *row_off, int32_t n_seg, void *uops, int64_t *n_uops,
                        uint32_t *stream_begin, void *descs, int32_t *n_descs);
 
+/* A dense matrix with far fewer row blocks than there are compute cores is also cut along K: each (K range,
+ * row block) pair is a work item, and the partial sums pass from range to range through a library-owned workspace
+ * with depId signals (Section 4.1, dependencies between memory uops; Section 4.3, the global depId queue).  The
+ * emitted program then names a fourth tensor, 3 = the workspace.  This call gives its size in *bytes (0: the shape
+ * is not split, the program uses tensors 0..2 only) and, if init != NULL, its initial content (host buffer of
+ * capacity *bytes on entry).  vdc_matvec allocates and initialises the workspace itself; the call is for running
+ * vdc_matvec_program's output elsewhere. */
+int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
+                         void *init, int64_t *bytes);
+
 /* Run the SIMT slot allocator of the VMC (Section 4.3: every allocator thread probes from its own position,
  * a wave vote takes the first) on n independent (mask, nslots) requests with a pool of n_slots slots:
  * pos[i] = the lowest start of nslots[i] contiguous clear bits of masks[i], or -1.  masks, nslots, pos: device. */

@@ -55,6 +55,7 @@ def lib():
             "vdc_matvec_ragged": [vp, vp, vp, i32, i64, vp, vp, i32, vp],
             "vdc_matvec_program": [vp, i64, i64, i64, i32, i32, vp, i32, vp, ctypes.POINTER(i64), vp, vp,
                                    ctypes.POINTER(i32)],
+            "vdc_matvec_workspace": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64)],
             "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
         }
         for name, args in sig.items():
@@ -69,7 +70,7 @@ def lib():
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
            "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
-           "vdc_matvec_program", "vdc_debug_alloc", "vdc_strerror"]
+           "vdc_matvec_program", "vdc_matvec_workspace", "vdc_debug_alloc", "vdc_strerror"]
 
 
 def strerror(code):
@@ -222,6 +223,15 @@ class Executor:
                                       _np_ptr(sb), _np_ptr(descs), ctypes.byref(n_d))
         _check(rc, "vdc_matvec_program")
         return words, sb, descs
+
+    def matvec_workspace(self, rows, K, ld, B, tile_bytes):
+        """Initial content (numpy float32, possibly empty) of tensor 3 of the program matvec_program returns."""
+        n = ctypes.c_int64(0)
+        _check(lib().vdc_matvec_workspace(self.handle, rows, K, ld, B, tile_bytes, None, ctypes.byref(n)), "vdc_matvec_workspace (sizing)")
+        ws = np.zeros(n.value // 4, dtype=np.float32)
+        if n.value:
+            _check(lib().vdc_matvec_workspace(self.handle, rows, K, ld, B, tile_bytes, _np_ptr(ws), ctypes.byref(n)), "vdc_matvec_workspace")
+        return ws
 
     def debug_alloc(self, masks, nslots, n_slots, stream=None):
         """masks (int32/uint32 CUDA tensor), nslots (int32 CUDA tensor) -> positions (int32 CUDA tensor)."""

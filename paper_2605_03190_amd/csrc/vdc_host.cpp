@@ -28,6 +28,7 @@ struct vdc_program {
     int64_t tensor_bytes[kMaxTensors] = {0};
     bool uses_dep = false;
     uint32_t max_dep_id = 0;
+    void *d_workspace = nullptr;   // matvec programs that split K: the [I | 0] tile and the partial results
 };
 
 struct MatvecKey {
@@ -455,6 +456,64 @@ struct Tiler {
         }
     }
 
+    // One K range [kt0, kt1) (in tiles; the last range also takes the K tail) of one row block per compute core in
+    // `vs`.  Split s > 0 adds the partial sums of split s - 1 as one more tile step: the matrix tile is [I | 0] from
+    // the workspace (tensor 3) and the vector tile is the previous partial result, fetched with a load that waits for
+    // its depId (Section 4.1: a load with an inter-memory-uop dependency).  Every split but the last stores to the
+    // workspace and signals its own depId; the last stores to Y.  The order of the additions is fixed by the program.
+    void emit_split(int core, const std::vector<int> &vs, const std::vector<int64_t> &rbs, int s, int S, int64_t kt0, int64_t kt1,
+                    int64_t rows_total, int64_t NB, int64_t prow, int64_t p_base) {
+        auto &vm = vmc(core);
+        const int64_t nk_all = K / Kt, ktail = K % Kt;
+        const int n = (int)vs.size();
+        const int64_t full = std::min(kt1, nk_all) - kt0;            // full tiles of this range
+        const bool with_tail = ktail && kt1 > nk_all;
+        const uint32_t m_slots = slots_for((uint64_t)R * Kt * 4), x_slots = slots_for((uint64_t)B * Kt * 4), y_slots = slots_for((uint64_t)B * R * 4);
+        const uint32_t m_flags = F_SEND | F_DYNAMIC | (nt ? F_NT : 0);
+        const uint32_t dx = desc(1, B, Kt * 4, Kt * 4, (uint64_t)K * 4);
+        const uint32_t dxt = ktail ? desc(1, B, (uint32_t)ktail * 4, Kt * 4, (uint64_t)K * 4) : 0;
+        const uint32_t d_id = desc(3, R, Kt * 4, Kt * 4, (uint64_t)Kt * 4);                    // [I | 0]
+        const uint32_t d_pl = desc(3, B, R * 4, Kt * 4, (uint64_t)prow * 4);                   // previous partial as a vector tile
+        const uint32_t d_ps = desc(3, B, R * 4, R * 4, (uint64_t)prow * 4);                    // partial result store
+        vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, kt0 * Kt * 4, 0, 0));
+        std::vector<uint32_t> rows_valid(n);
+        for (int i = 0; i < n; i++) rows_valid[i] = (uint32_t)std::min<int64_t>(R, rows_total - rbs[i] * R);
+        auto tile_pairs = [&](bool tail) {
+            for (int i = 0; i < n; i++) {
+                const int v = vs[i];
+                const uint32_t d_m = tail ? desc(0, R, (uint32_t)ktail * 4, Kt * 4, (uint64_t)ld * 4) : desc(0, R, Kt * 4, Kt * 4, (uint64_t)ld * 4);
+                vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, 2, m_slots, rows_valid[i], 0, rbs[i] * R * ld * 4, d_m, 0));
+                vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(v), v, 2, x_slots, B, 0, 0, tail ? dxt : dx, 0));
+            }
+        };
+        if (full > 0) {
+            if (full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, full, 0, 0));
+            tile_pairs(false);
+            vm.push_back(encode(full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+        }
+        if (with_tail) tile_pairs(true);
+        if (s > 0) {
+            for (int i = 0; i < n; i++) {
+                const int v = vs[i];
+                vm.push_back(encode(OP_LOAD, F_SEND, flow_m(v), v, 0, m_slots, R, 0, 0, d_id, 0));
+                vm.push_back(encode(OP_LOAD, F_SEND | F_DEP_RECV, flow_x(v), v, 0, x_slots, B, (uint32_t)((s - 1) * NB + rbs[i]),
+                                    p_base + ((int64_t)(s - 1) * B * prow + rbs[i] * R) * 4, d_pl, 1));
+            }
+        }
+        for (int i = 0; i < n; i++) {
+            const int v = vs[i];
+            if (s < S - 1) {
+                vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, flow_y(v), v, 0, y_slots, B, (uint32_t)(s * NB + rbs[i]),
+                                    p_base + ((int64_t)s * B * prow + rbs[i] * R) * 4, d_ps, 0));
+            } else {
+                const uint32_t dy = desc(2, B, rows_valid[i] * 4, R * 4, (uint64_t)y_pitch * 4);
+                vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, rbs[i] * R * 4, dy, 0));
+            }
+            const uint32_t nk = (uint32_t)(full + (with_tail ? 1 : 0) + (s > 0 ? 1 : 0));
+            vcc(core, v).push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, nk, 0, matvec_imm(B, R, Kt / 4), 0, 0));
+        }
+    }
+
     void emit_core(int core, const std::vector<Run> &runs) {
         const int V = cfg.vcc_per_core;
         int next_v = 0;
@@ -509,6 +568,32 @@ bool choose_tile(const vdc_config &cfg, int64_t K, int32_t B, int32_t tile_bytes
     return matvec_geometry_ok((uint32_t)B, (uint32_t)R, (uint32_t)lpr, nullptr, nullptr);
 }
 
+// When a dense matrix has far fewer row blocks than there are compute cores, K is cut into S ranges and every
+// (range, row block) pair becomes a work item; the partial sums travel from range to range through a workspace and
+// depId signals (Section 4.1, inter-memory-uop dependencies).  S == 1: no split.
+struct SplitPlan {
+    int S = 1;
+    int64_t NB = 0, prow = 0, ident_floats = 0, bytes = 0;   // workspace: [I | 0] tile, then S - 1 partial results [B][prow]
+};
+
+SplitPlan plan_split(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, int32_t R, int32_t Kt, bool ragged) {
+    SplitPlan sp;
+    sp.NB = (rows + R - 1) / R;
+    if (ragged || (R & 3) || R > Kt) return sp;
+    const int64_t lanes = (int64_t)cfg.n_cores * cfg.vcc_per_core, nk = (K + Kt - 1) / Kt;
+    if (sp.NB * 2 > lanes) return sp;
+    int64_t S = lanes / sp.NB;
+    S = std::min<int64_t>(S, 16);
+    S = std::min<int64_t>(S, nk / 4);                               // at least four tiles per range
+    S = std::min<int64_t>(S, (int64_t)cfg.n_dep_ids / sp.NB + 1);   // one depId per (range but the last, row block)
+    if (S < 2) return sp;
+    sp.S = (int)S;
+    sp.prow = sp.NB * R;
+    sp.ident_floats = (int64_t)R * Kt;
+    sp.bytes = (sp.ident_floats + (int64_t)(S - 1) * B * sp.prow) * 4;
+    return sp;
+}
+
 int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                  const int64_t *row_off, int32_t n_seg, std::vector<Word> &words, std::vector<uint32_t> &sb,
                  std::vector<Desc> &descs) {
@@ -533,6 +618,25 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
         segs.push_back({0, rows, 0, (rows + R - 1) / R});
         nb = segs[0].n_blocks;
     }
+    const SplitPlan sp = plan_split(cfg, rows, K, B, R, Kt, row_off != nullptr);
+    if (sp.S > 1) {
+        // items in the order (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  An item only waits for the
+        // item NB places before it, which an earlier position of the same or of an earlier core holds: no cycles.
+        const int64_t NI = sp.NB * sp.S, nk = (K + Kt - 1) / Kt;
+        for (int c = 0; c < C; c++) {
+            int64_t i0 = NI * c / C, i1 = NI * (c + 1) / C;
+            int next_v = 0;
+            while (i0 < i1) {
+                const int s0 = (int)(i0 / sp.NB);
+                std::vector<int> vs{V == 2 ? next_v : 0};
+                std::vector<int64_t> rbs{i0 % sp.NB};
+                if (V == 2 && i0 + 1 < i1 && (int)((i0 + 1) / sp.NB) == s0) { vs = {0, 1}; rbs.push_back((i0 + 1) % sp.NB); }
+                else next_v ^= 1;
+                t.emit_split(c, vs, rbs, s0, sp.S, nk * s0 / sp.S, nk * (s0 + 1) / sp.S, rows, sp.NB, sp.prow, sp.ident_floats * 4);
+                i0 += (int64_t)vs.size();
+            }
+        }
+    } else {
     size_t si = 0;
     for (int c = 0; c < C; c++) {
         int64_t b0 = nb * c / C, b1 = nb * (c + 1) / C;
@@ -553,6 +657,7 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
             b0 = e;
         }
         t.emit_core(c, runs);
+    }
     }
     words.clear();
     sb.assign(1, 0);
@@ -764,6 +869,7 @@ int vdc_program_destroy(vdc_program *prog) {
     (void)hipFree(prog->d_words);
     (void)hipFree(prog->d_stream_begin);
     (void)hipFree(prog->d_descs);
+    (void)hipFree(prog->d_workspace);
     delete prog;
     return VDC_OK;
 }
@@ -797,6 +903,18 @@ int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info) {
     return code ? code : VDC_EDEVICE;
 }
 
+// Initial content of the workspace (tensor 3) of a matvec program that splits K: the tile [I | 0] (R rows of Kt
+// floats), then the partial results, zero.  Empty when the program does not split.
+static void workspace_init(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, int32_t tile_bytes, bool ragged, std::vector<float> &ws) {
+    ws.clear();
+    int32_t R = 0, Kt = 0;
+    if (!choose_tile(cfg, K, B, tile_bytes, R, Kt)) return;
+    const SplitPlan sp = plan_split(cfg, rows, K, B, R, Kt, ragged);
+    if (sp.S < 2) return;
+    ws.assign((size_t)(sp.bytes / 4), 0.0f);
+    for (int r = 0; r < R; r++) ws[(size_t)r * Kt + r] = 1.0f;
+}
+
 static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
                          int32_t B, int32_t tile_bytes, const int64_t *row_off, int32_t n_seg, void *hip_stream) {
     if (!ex || ex->cfg.device == -1 || !M || !X || !Y || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
@@ -813,13 +931,20 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
         int rc = build_matvec(ex->cfg, rows, K, ld, B, tile_bytes, row_off, n_seg, words, sb, descs);
         if (rc != VDC_OK) return rc;
         const int64_t x_rows = row_off ? n_seg : B;
-        int64_t tb[3] = {((rows - 1) * ld + K) * 4, x_rows * K * 4, (int64_t)B * rows * 4};
-        rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb, 3, &prog);
+        std::vector<float> ws;
+        workspace_init(ex->cfg, rows, K, B, tile_bytes, row_off != nullptr, ws);
+        int64_t tb[4] = {((rows - 1) * ld + K) * 4, x_rows * K * 4, (int64_t)B * rows * 4, (int64_t)ws.size() * 4};
+        rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb,
+                                ws.empty() ? 3 : 4, &prog);
         if (rc != VDC_OK) return rc;
+        if (!ws.empty()) {
+            if (hipMalloc(&prog->d_workspace, ws.size() * 4) != hipSuccess) { vdc_program_destroy(prog); return VDC_ENOMEM; }
+            if (hipMemcpy(prog->d_workspace, ws.data(), ws.size() * 4, hipMemcpyHostToDevice) != hipSuccess) { vdc_program_destroy(prog); return VDC_EDEVICE; }
+        }
         ex->matvec_cache.push_back({key, prog});
     }
-    void *bases[3] = {(void *)M, (void *)X, (void *)Y};
-    return vdc_run(ex, prog, bases, 3, hip_stream);
+    void *bases[4] = {(void *)M, (void *)X, (void *)Y, prog->d_workspace};
+    return vdc_run(ex, prog, bases, prog->d_workspace ? 4 : 3, hip_stream);
 }
 
 int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y, int32_t B,
@@ -858,6 +983,20 @@ int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, in
     if (descs) { if (cap_d >= (int32_t)ds.size()) memcpy(descs, ds.data(), ds.size() * sizeof(Desc)); else fits = false; }
     if (stream_begin) memcpy(stream_begin, sb.data(), sb.size() * sizeof(uint32_t));
     return fits ? VDC_OK : VDC_EINVAL;
+}
+
+int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes, void *init,
+                         int64_t *bytes) {
+    if (!ex || !bytes || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
+    std::vector<float> ws;
+    workspace_init(ex->cfg, rows, K, B, tile_bytes, false, ws);
+    const int64_t cap = *bytes;
+    *bytes = (int64_t)ws.size() * 4;
+    if (init && !ws.empty()) {
+        if (cap < *bytes) return VDC_EINVAL;
+        memcpy(init, ws.data(), ws.size() * 4);
+    }
+    return VDC_OK;
 }
 
 int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n,

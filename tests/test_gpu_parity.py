@@ -60,6 +60,11 @@ DENSE_CASES = [
     (3, 8, 8, 1, 2048),                # less than one tile
     (4096, 512, 512, 5, 2048),
     (1024, 8192, 8192, 7, 16384),
+    # few row blocks, long rows: K is cut into ranges chained by depId signals between memory cores
+    (64, 65536, 65536, 1, 16384),
+    (256, 32768, 32768, 3, 8192),
+    (100, 8200, 8204, 2, 4096),        # row tail and K tail in a split program
+    (16, 4096, 4096, 8, 16384),
 ]
 
 

@@ -51,6 +51,10 @@ CASES = [
     (300, 64, 64, 2, 4096, 5, 4096, 8),
     (64, 2048, 2048, 1, 16384, 2, 8192, 10),
     (5, 12, 12, 1, 2048, 4, 1024, 8),           # fewer row blocks than compute cores
+    # few row blocks, long rows: the tiler also cuts K and chains the partial sums through depId signals
+    (32, 4096, 4096, 1, 4096, 8, 4096, 12),     # two K ranges
+    (16, 8192, 8200, 3, 8192, 8, 8192, 10),     # one row block, sixteen K ranges
+    (38, 2000, 2000, 2, 4096, 6, 4096, 12),     # row tail and K tail in a split program
 ]
 
 
@@ -62,13 +66,23 @@ def test_tiler_program_on_the_oracle_interpreter(rows, K, ld, B, T, ncores, slot
     Y = np.full((B, rows), np.nan, np.float32)
     with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
         w, sb, d = ex.matvec_program(rows, K, ld, B, T)
-        rc, msg = ex.program_validate(w, sb, d, [((rows - 1) * ld + K) * 4, X.nbytes, Y.nbytes])
+        ws0 = ex.matvec_workspace(rows, K, ld, B, T)
+        sizes = [((rows - 1) * ld + K) * 4, X.nbytes, Y.nbytes] + ([ws0.nbytes] if ws0.size else [])
+        rc, msg = ex.program_validate(w, sb, d, sizes)
         assert rc == vdc.VDC_OK, msg
+    split = ws0.size > 0
+    assert split == (rows <= 38 and K >= 2000)
+    if split:
+        ops = np.asarray(w)[:, 0] & 0xFF
+        flags = (np.asarray(w)[:, 0] >> 8) & 0xFF
+        assert ((ops == 8) & ((flags & 32) != 0)).any() and ((ops == 9) & ((flags & 16) != 0)).any()   # load.dep and signalling stores
     for sched, seed in (("program", 0), ("random", 1)):
         Y[:] = np.nan
-        UM.Machine(w, sb, d, [M, X, Y], n_cores=ncores, slot_bytes=slot, n_slots=nslots).run(sched, seed)
+        ws = ws0.copy()
+        UM.Machine(w, sb, d, [M, X, Y] + ([ws] if split else []), n_cores=ncores, slot_bytes=slot, n_slots=nslots).run(sched, seed)
         Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
-        assert np.all(np.abs(Y - Yr) <= 1e-7 * Ya + 1e-30)
+        # partial sums pass through fp32 once per K range
+        assert np.all(np.abs(Y - Yr) <= (2e-6 if split else 1e-7) * Ya + 1e-30)
 
 
 def test_ragged_tiler_program_on_the_oracle_interpreter():
