@@ -457,10 +457,10 @@ struct Tiler {
     }
 
     // One K range [kt0, kt1) (in tiles; the last range also takes the K tail) of one row block per compute core in
-    // `vs`.  Split s > 0 adds the partial sums of split s - 1 as one more tile step: the matrix tile is [I | 0] from
-    // the workspace (tensor 3) and the vector tile is the previous partial result, fetched with a load that waits for
-    // its depId (Section 4.1: a load with an inter-memory-uop dependency).  Every split but the last stores to the
-    // workspace and signals its own depId; the last stores to Y.  The order of the additions is fixed by the program.
+    // `vs`.  Every range but the last stores its partial sums to the workspace (tensor 3) and signals its own depId.
+    // The last range then adds them, one more tile step each: the matrix tile is [I | 0] from the workspace and the
+    // vector tile is a partial result, fetched with a load that waits for its depId (Section 4.1: a load with an
+    // inter-memory-uop dependency), and stores to Y.  The order of the additions is fixed by the program.
     void emit_split(int core, const std::vector<int> &vs, const std::vector<int64_t> &rbs, int s, int S, int64_t kt0, int64_t kt1,
                     int64_t rows_total, int64_t NB, int64_t prow, int64_t p_base) {
         auto &vm = vmc(core);
@@ -492,13 +492,14 @@ struct Tiler {
             vm.push_back(encode(full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
         }
         if (with_tail) tile_pairs(true);
-        if (s > 0) {
-            for (int i = 0; i < n; i++) {
-                const int v = vs[i];
-                vm.push_back(encode(OP_LOAD, F_SEND, flow_m(v), v, 0, m_slots, R, 0, 0, d_id, 0));
-                vm.push_back(encode(OP_LOAD, F_SEND | F_DEP_RECV, flow_x(v), v, 0, x_slots, B, (uint32_t)((s - 1) * NB + rbs[i]),
-                                    p_base + ((int64_t)(s - 1) * B * prow + rbs[i] * R) * 4, d_pl, 1));
-            }
+        if (s == S - 1) {
+            for (int sp = 0; sp < S - 1; sp++)
+                for (int i = 0; i < n; i++) {
+                    const int v = vs[i];
+                    vm.push_back(encode(OP_LOAD, F_SEND, flow_m(v), v, 0, m_slots, R, 0, 0, d_id, 0));
+                    vm.push_back(encode(OP_LOAD, F_SEND | F_DEP_RECV, flow_x(v), v, 0, x_slots, B, (uint32_t)(sp * NB + rbs[i]),
+                                        p_base + ((int64_t)sp * B * prow + rbs[i] * R) * 4, d_pl, 1));
+                }
         }
         for (int i = 0; i < n; i++) {
             const int v = vs[i];
@@ -509,7 +510,7 @@ struct Tiler {
                 const uint32_t dy = desc(2, B, rows_valid[i] * 4, R * 4, (uint64_t)y_pitch * 4);
                 vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, rbs[i] * R * 4, dy, 0));
             }
-            const uint32_t nk = (uint32_t)(full + (with_tail ? 1 : 0) + (s > 0 ? 1 : 0));
+            const uint32_t nk = (uint32_t)(full + (with_tail ? 1 : 0) + (s == S - 1 ? S - 1 : 0));
             vcc(core, v).push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, nk, 0, matvec_imm(B, R, Kt / 4), 0, 0));
         }
     }
@@ -620,8 +621,9 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
     }
     const SplitPlan sp = plan_split(cfg, rows, K, B, R, Kt, row_off != nullptr);
     if (sp.S > 1) {
-        // items in the order (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  An item only waits for the
-        // item NB places before it, which an earlier position of the same or of an earlier core holds: no cycles.
+        // items in the order (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  Only items of the last
+        // range wait, and only for items of earlier ranges, which earlier positions of the same or of earlier cores
+        // hold: no cycles.
         const int64_t NI = sp.NB * sp.S, nk = (K + Kt - 1) / Kt;
         for (int c = 0; c < C; c++) {
             int64_t i0 = NI * c / C, i1 = NI * (c + 1) / C;
