@@ -75,7 +75,7 @@ int vdc_destroy(vdc_executor *ex);
 /* Fill *cfg with the values in effect (defaults resolved, n_cores = the CU count, ...). */
 int vdc_get_config(const vdc_executor *ex, vdc_config *cfg);
 
-/* ---- low level: uop graphs (Section 3: "uop streams for virtual cores ... connected by dependency edges") ----
+/* ---- low level: uop graphs (Section 3: one uop stream per virtual core, the streams tied together by dependency edges) ----
  *
  * uops          host, n_uops words of 16 bytes (layout: csrc/vdc_isa.h)
  * stream_begin  host, n_cores*(1+vcc_per_core)+1 offsets into uops; stream index = core*(1+V) for the
@@ -118,7 +118,7 @@ int vdc_run_traced(vdc_executor *ex, const vdc_program *prog, void *const *tenso
  * info (host, may be NULL) receives 4 words: core, role, stream pc, detail.  Clears the status. */
 int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info);
 
-/* ---- high level: the matvec operator (Section 3, O = M @ N; tiled "along the M dimension") ----
+/* ---- high level: the matvec operator (Section 3, O = M @ N, the matrix cut into tiles along its row dimension) ----
  *
  * Y[b][i] = sum_j M[i*ld + j] * X[b*K + j],  0 <= i < rows, 0 <= b < B, fp32.
  * M, X, Y: device.  K and ld multiples of 4 (rows are moved in 16-byte units), ld >= K, 1 <= B <= 8,

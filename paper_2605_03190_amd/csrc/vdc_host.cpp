@@ -336,7 +336,7 @@ struct Validator {
 };
 
 // ------------------------------------------------------------------------------------------------------------
-// Matvec tiler: rows of M are cut into blocks of R rows ("tile the matrix along the M dimension", Section 3);
+// Matvec tiler: rows of M are cut into blocks of R rows (Section 3 tiles the matrix along its row dimension);
 // every core gets a contiguous range of blocks and deals them alternately to its compute cores; the K loop
 // and the block loop are LOOP/REPEAT nests over dynamic addresses (Section 5).
 // Tensors: 0 = M, 1 = X, 2 = Y.

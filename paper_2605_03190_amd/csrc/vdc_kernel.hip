@@ -270,7 +270,7 @@ DEV bool spin_step(Ctx &c, Spin &s, uint32_t aborted, uint32_t detail) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Register state of a stream: pc, loop stack, accumulators (Section 4.1: "a lightweight register machine"),
+// Register state of a stream: pc, loop stack, accumulators (Section 4.1 models every core as a small register machine),
 // and the uop window
 // ------------------------------------------------------------------------------------------------
 struct Seq {
