@@ -356,6 +356,7 @@ struct Tiler {
     std::vector<std::vector<Word>> streams;
     std::vector<Desc> descs;
     bool nt = true;
+    bool k_skew = false;   // measured on cfg5: no gain (the vector tiles are not what the cores wait for)
 
     uint32_t desc(uint32_t tensor, uint32_t box_rows, uint32_t row_bytes, uint32_t lds_pitch, uint64_t gpitch) {
         Desc d{tensor, box_rows, row_bytes, lds_pitch, (uint32_t)gpitch, (uint32_t)(gpitch >> 32), 0, 0};
@@ -402,17 +403,19 @@ struct Tiler {
                 };
                 // U K steps per trip.  (Two per trip halve the front end's fixed cost per uop, but a batch is only
                 // published when all of it is allocated, and the longer wait for the first tiles costs more.)
-                const int64_t U = 1, trips = nk_full / U, rest = nk_full % U;
-                if (trips > 0) {
+                // Every core starts its sweep over K at a different tile (and wraps around): cores that run in step
+                // would otherwise all ask the L2 for the same vector tile at the same moment.
+                const int64_t k0 = (k_skew && nk_full >= 8) ? ((int64_t)core * nk_full / cfg.n_cores) : 0;
+                auto sweep = [&](int64_t first, int64_t trips) {
+                    if (trips <= 0) return;
+                    vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, first * Kt * 4, 0, 0));
                     if (trips > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, trips, 0, 0));
-                    for (int64_t uu = 0; uu < U; uu++) tile_pairs(dm, dx, uu * Kt * 4);
-                    vm.push_back(encode(trips > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, U * (int64_t)Kt * 4, 0, 0));
-                }
-                for (int64_t uu = 0; uu < rest; uu++) {
                     tile_pairs(dm, dx, 0);
-                    vm.push_back(encode(OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
-                }
-                if (ktail) tile_pairs(dmt, dxt, 0);
+                    vm.push_back(encode(trips > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                };
+                sweep(k0, nk_full - k0);
+                if (ktail) tile_pairs(dmt, dxt, 0);      // acc 2 is at the end of the last full tile here
+                sweep(0, k0);
                 for (int i = 0; i < n; i++) {
                     const int v = vs[i];
                     vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, y_off + (it * n + i) * R * 4, dy, 0));

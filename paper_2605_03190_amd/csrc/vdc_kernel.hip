@@ -821,23 +821,9 @@ struct Inflight {
 
 DEV void ldu_retire(Ctx &c, const Inflight &t) {
     lds_wait();   // zero fill of this tile (ds_write) is done as well
-    if (t.ctl & 0x100u) {
-        if (c.lane == 0) lds_vst64(c.ctl + CTL_OFF(m2c) + ((t.ctl >> 10) & 0x3FFu) * 8u, (uint64_t)t.msg_lo | ((uint64_t)t.msg_hi << 32));
-        reconverge();
-    }
-    if (t.ctl & 0x200u) dep_signal(c, t.dep);
-}
-
-// One gathered read of what a load unit looks at: lane 0 = uq_tail[u], lanes 1..4 = the record at `head`,
-// lane 5 = cfu_halted, lane 6 = abort, lane 7 = win_gen.
-DEV uint32_t ldu_poll(Ctx &c, uint32_t u, uint32_t head) {
-    const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
-    uint32_t off = c.ctl + CTL_OFF(win_gen);
-    off = c.lane == 6u ? c.ctl + CTL_OFF(abort) : off;
-    off = c.lane == 5u ? c.ctl + CTL_OFF(cfu_halted) : off;
-    off = c.lane <= 4u ? rec + (c.lane - 1u) * 4u : off;
-    off = c.lane == 0u ? c.ctl + CTL_OFF(uq_tail) + u * 4u : off;
-    return lds_vld32(off);
+    lds_st64_lanes((t.ctl & 0x100u) ? 1ull : 0ull, c.ctl + CTL_OFF(m2c) + ((t.ctl >> 10) & 0x3FFu) * 8u,
+                   (uint64_t)t.msg_lo | ((uint64_t)t.msg_hi << 32));
+    if (__builtin_expect((t.ctl & 0x200u) != 0u, 0)) dep_signal(c, t.dep);
 }
 
 // The static part of a record: lanes 0..7 = the StatRec the record's info word points at.
@@ -896,38 +882,45 @@ DEV void ldu_main(Ctx &c) {
     uint32_t vm_out = 0;      // load instructions issued and not yet known complete
     uint32_t head = 0;
     // Keys are (table, window lane); both entries are dropped whenever the front end has decoded a new window,
-    // which the poll sees in the same snapshot as any record dispatched from it.
-    LduEnt e0 = {}, e1 = {};
-    e0.key = e1.key = 0xFFFFFFFFu;
+    // which the poll sees in the same snapshot as any record dispatched from it.  `cur` is the entry of the uop
+    // the unit handled last, with its wave-uniform fields in scalar registers.
+    LduEnt e0 = {}, e1 = {}, cur = {};
+    e0.key = e1.key = cur.key = 0xFFFFFFFFu;
     uint32_t seen_gen = 0;
+    // what the poll reads: lane 0 = uq_tail[u], lanes 1..4 = the record at `head`, lane 5 = cfu_halted,
+    // lane 6 = abort, lane 7.. = win_gen
+    uint32_t poll_off = c.ctl + CTL_OFF(win_gen);
+    poll_off = c.lane == 6u ? c.ctl + CTL_OFF(abort) : poll_off;
+    poll_off = c.lane == 5u ? c.ctl + CTL_OFF(cfu_halted) : poll_off;
+    poll_off = c.lane <= 4u ? c.ctl + CTL_OFF(uq) + u * kUQ * (uint32_t)sizeof(UnitRec) + (c.lane - 1u) * 4u : poll_off;
+    poll_off = c.lane == 0u ? c.ctl + CTL_OFF(uq_tail) + u * 4u : poll_off;
+    const uint32_t poll_rec = (c.lane >= 1u && c.lane <= 4u) ? (uint32_t)sizeof(UnitRec) : 0u;
     Spin sp;
     bool ok = true;
-    PROF_DECL(pt0 = PROF_NOW(), p_idle = 0, p_vm = 0, p_issue = 0, p_n = 0, p_idle_n = 0, p_poll = 0, p_iter = 0);
     while (ok) {
-        PROF_INC(p_iter);
-        head = uni(head); n_fl = uni(n_fl); vm_out = uni(vm_out); fl_head = uni(fl_head); seen_gen = uni(seen_gen);
-        PROF_DECL(qp0 = PROF_NOW());
         PHASE(c, 1u + u, 1u);
-        const uint32_t snap = ldu_poll(c, u, head);
+        const uint32_t snap = lds_vld32(poll_off + poll_rec * (head & (kUQ - 1)));
         const bool have = rf_get(snap, 0) != head;
-        PROF_ADD(p_poll, qp0);
-        if (rf_get(snap, 7) != seen_gen) {
-            seen_gen = rf_get(snap, 7);
-            e0.key = e1.key = 0xFFFFFFFFu;
+        const uint32_t gen = rf_get(snap, 7);
+        if (__builtin_expect(gen != seen_gen, 0)) {
+            seen_gen = gen;
+            e0.key = e1.key = cur.key = 0xFFFFFFFFu;
         }
-        uint32_t ni = 0, info = 0, key = 0;
-        if (have) {
-            info = rf_get(snap, 3);
-            key = (info >> 6) & 0x7Fu;
+        const uint32_t info = rf_get(snap, 3);
+        const uint32_t key = (info >> 6) & 0x7Fu;
+        if (have && key != cur.key) {
             if (key & 1u) {
                 if (e1.key != key) ldu_derive(c, e1, key, info);
-                ni = e1.ni;
+                cur = e1;
             } else {
                 if (e0.key != key) ldu_derive(c, e0, key, info);
-                ni = e0.ni;
+                cur = e0;
             }
+            cur.ni = uni(cur.ni); cur.bits = uni(cur.bits); cur.key = uni(cur.key);
+            cur.step_lo = uni(cur.step_lo); cur.step_hi = uni(cur.step_hi);
+            cur.msg_lo = uni(cur.msg_lo); cur.msg_hi = uni(cur.msg_hi); cur.m2c_base = uni(cur.m2c_base);
         }
-        ni = uni(ni);
+        const uint32_t ni = cur.ni;
         // retire the oldest tile when nothing can be issued on top of what is in flight; the record seen by this poll
         // stays valid meanwhile, so it can be issued right after without looking again
         bool can_issue = have && n_fl < (uint32_t)kMaxInflight && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
@@ -935,14 +928,12 @@ DEV void ldu_main(Ctx &c) {
             if (n_fl > 0) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
                 Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
-                PROF_DECL(q0 = PROF_NOW());
                 PHASE(c, 1u + u, 3u);
                 wait_vmcnt_le(vm_out - (o.ctl & 0xFFu));
                 vm_out -= o.ctl & 0xFFu;
                 PHASE(c, 1u + u, 4u);
                 ldu_retire(c, o);
                 OBS(c, 1u + u, fl_head + 1u);
-                PROF_ADD(p_vm, q0);
                 fl_head++;
                 n_fl--;
                 sp.n = 0;
@@ -951,21 +942,15 @@ DEV void ldu_main(Ctx &c) {
             } else {
                 // idle
                 if (rf_get(snap, 5) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
-                PROF_DECL(q1 = PROF_NOW());
                 PHASE(c, 1u + u, 5u);
                 if (!spin_step(c, sp, rf_get(snap, 6), 0x600u | u)) ok = false;
-                PROF_ADD(p_idle, q1);
-                PROF_INC(p_idle_n);
                 continue;
             }
         }
         // ---- issue the loads of the record ----
-        PROF_DECL(qi0 = PROF_NOW());
-        PROF_INC(p_n);
         PHASE(c, 1u + u, 2u);
-        const bool odd = (key & 1u) != 0u;
-        const uint32_t val = odd ? e1.val : e0.val, bits = odd ? e1.bits : e0.bits;
-        const uint32_t e_msg_lo = odd ? e1.msg_lo : e0.msg_lo, e_msg_hi = odd ? e1.msg_hi : e0.msg_hi, e_m2c = odd ? e1.m2c_base : e0.m2c_base;
+        const uint32_t val = cur.val, bits = cur.bits;
+        const uint32_t e_msg_lo = cur.msg_lo, e_msg_hi = cur.msg_hi, e_m2c = cur.m2c_base;
         const uint64_t gaddr = (uint64_t)rf_get(snap, 1) | ((uint64_t)rf_get(snap, 2) << 32);
         const uint32_t ticket = rf_get(snap, 4), slot = info & 63u, lds_off = slot << slot_shift;
         c.pc = c.stream_pc0 + rf_get(val, 6);
@@ -984,10 +969,10 @@ DEV void ldu_main(Ctx &c) {
         if (bits & 16u) {
             // the usual case: whole tile, a power-of-two row of at most 64 chunks.  Every instruction moves 64 / cpr
             // whole rows, so the per-lane address just advances by a uniform step
-            const uint64_t off = (uint64_t)(odd ? e1.off_lo : e0.off_lo) | ((uint64_t)(odd ? e1.off_hi : e0.off_hi) << 32);
+            const uint64_t off = (uint64_t)cur.off_lo | ((uint64_t)cur.off_hi << 32);
             const char *g = (const char *)(uintptr_t)(gaddr + off);
-            const uint64_t step = uni64((uint64_t)(odd ? e1.step_lo : e0.step_lo) | ((uint64_t)(odd ? e1.step_hi : e0.step_hi) << 32));
-            uint32_t dst = uni(lds_base + lds_off);
+            const uint64_t step = (uint64_t)cur.step_lo | ((uint64_t)cur.step_hi << 32);
+            uint32_t dst = lds_base + lds_off;
             // Four instructions per trip, straight-line: back to back they issue about four times faster than one per
             // loop trip (a taken branch costs about as much as one of these loads)
 #define VDC_LOAD4(NT)                                                                                              \
@@ -1052,12 +1037,9 @@ DEV void ldu_main(Ctx &c) {
         n_fl++;
         vm_out += ni;
         head++;
-        if (c.lane == 0) lds_vst32(c.ctl + CTL_OFF(uq_head) + u * 4u, head);
-        reconverge();
+        lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_head) + u * 4u, head);
         sp.n = 0;
-        PROF_ADD(p_issue, qi0);
     }
-    PROF_OUT(c, 1 + u, 0, PROF_NOW() - pt0); PROF_OUT(c, 1 + u, 1, p_idle); PROF_OUT(c, 1 + u, 2, p_vm); PROF_OUT(c, 1 + u, 3, p_issue); PROF_OUT(c, 1 + u, 4, p_n); PROF_OUT(c, 1 + u, 5, p_idle_n); PROF_OUT(c, 1 + u, 6, p_poll); PROF_OUT(c, 1 + u, 7, p_iter);
     // never leave with loads in flight: their LDS destination belongs to this workgroup only while it lives
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (ok) {
@@ -1235,11 +1217,11 @@ DEV void stu_main(Ctx &c) {
 // ------------------------------------------------------------------------------------------------
 // The two waves of an execution unit pop the same tickets, in the same groups.  A region may go back to the memory
 // core only when both are done with it: each wave counts itself in on the group's arrival word, and the one that
-// arrives second pushes the group's tickets to c2m at once (c2m positions are ticket numbers, so groups may be
-// pushed in any order; the receiver takes them in order).
+// arrives second hands the group's regions back at once.
 struct VccState {
     uint32_t head;     // next m2c ticket to pop
     uint32_t group;    // groups of tickets finished so far
+    uint32_t c2m_pos;  // produced regions pushed to c2m so far (both waves count alike)
     uint32_t pay0, pay1;   // kind | slot << 1 | nslots << 7 of the tickets popped last
     uint32_t red_seq;  // cross-wave reductions done so far
     uint32_t wv;       // which of the two waves of the execution unit this is
@@ -1298,19 +1280,25 @@ DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, 
 }
 
 // Called after the wave has finished reading (or writing) the regions of its last `n` (1 or 2) tickets: c2m.push,
-// by whichever of the two waves gets here second.
-DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n) {
+// by whichever of the two waves gets here second.  For a used region the message to the memory core is nothing but
+// "these slots are free again", so it is delivered as the LDS atomic that clears the slots' bits in the availability
+// mask; a produced region goes through the c2m ring to the store unit, which has a STORE waiting for it.
+DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n, uint32_t kind) {
     compiler_barrier();
     const uint32_t v = c.unit;
     const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
     if (before & 1u) {
         OBS(c, 10u + v, vs.head + n);
-        // lane j < n writes ticket head + j
-        const uint32_t tk = vs.head + c.lane;
-        const uint32_t payload = c.lane == 0u ? vs.pay0 : vs.pay1;
-        lds_st64_lanes((1ull << n) - 1ull, c.ctl + CTL_OFF(c2m) + (v * kC2M + (tk & (kC2M - 1))) * 8u,
-                       (uint64_t)payload | ((uint64_t)(tk + 1u) << 32));
+        const uint32_t payload = c.lane == 0u ? vs.pay0 : vs.pay1;     // lane j < n: ticket head + j
+        if (kind == 0u) {
+            lds_and32_lanes((1ull << n) - 1ull, c.ctl + CTL_OFF(mask), ~slot_bits((payload >> 1) & 63u, (payload >> 7) & 63u));
+        } else {
+            const uint32_t pos = vs.c2m_pos + c.lane;
+            lds_st64_lanes((1ull << n) - 1ull, c.ctl + CTL_OFF(c2m) + (v * kC2M + (pos & (kC2M - 1))) * 8u,
+                           (uint64_t)payload | ((uint64_t)(pos + 1u) << 32));
+        }
     }
+    if (kind != 0u) vs.c2m_pos += n;
     vs.head += n;
     vs.group++;
     compiler_barrier();
@@ -1365,7 +1353,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
             for (int b = 0; b < B; b++) acc[ai][b] = dot4(m[i], xv[xi][b], acc[ai][b]);   // matvec_tile_accumulate
         }
         // every LDS read of both tiles has returned once its value was used: the regions can go back
-        vcc_done_with(c, vs, 2u);                                    // c2m.push(a, b)
+        vcc_done_with(c, vs, 2u, 0u);                                // c2m.push(a, b)
     }
 
     Msg mo, unused;
@@ -1419,7 +1407,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
         vs.red_seq++;
     }
     lds_wait();
-    vcc_done_with(c, vs, 1u);                                         // push the produced region
+    vcc_done_with(c, vs, 1u, 1u);                                     // push the produced region
     return true;
 }
 
@@ -1468,7 +1456,7 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
     seq_init(c, s, cload(p->stream_begin, stream), cload(p->stream_begin, stream + 1u));
     c.stream_pc0 = s.pc;
     VccState vs;
-    vs.head = 0; vs.group = 0; vs.pay0 = 0; vs.pay1 = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
+    vs.head = 0; vs.group = 0; vs.c2m_pos = 0; vs.pay0 = 0; vs.pay1 = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
 #if defined(VDC_PROFILE) && defined(VDC_PROFILE_BUCKETS)
     vs.p_pop = vs.p_spins = vs.p_n = 0;
 #endif
