@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--tile-bytes", type=int, default=0, help="override the configuration's tile (I/O block) size: 2048, 4096, 8192 or 16384")
+    ap.add_argument("--slot-bytes", type=int, default=0, help="override the configuration's slot size")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device-to-device copy of MIB mebibytes --steps times: "
                          "the known traffic that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -60,6 +62,9 @@ def main():
     vdc.lib()                                  # fails loudly when the HIP extension is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = workloads.CONFIGS[args.workload]
+    if args.tile_bytes or args.slot_bytes:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, tile_bytes=args.tile_bytes or cfg.tile_bytes, slot_bytes=args.slot_bytes or cfg.slot_bytes)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.calibrate_copy:
@@ -67,10 +72,13 @@ def main():
         src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
+        t0 = time.perf_counter()
         for _ in range(args.steps):
             dst.copy_(src)
         torch.cuda.synchronize()
-        log("copied %d bytes %d times (each copy reads and writes that many bytes)" % (n, args.steps))
+        dt = (time.perf_counter() - t0) / args.steps
+        log("copied %d bytes %d times (each copy reads and writes that many bytes): %.3f ms per copy, %.0f GB/s read + %.0f GB/s written"
+            % (n, args.steps, dt * 1e3, n / dt / 1e9, n / dt / 1e9))
         return
     t0 = time.time()
     w = workloads.make(cfg, device=dev)

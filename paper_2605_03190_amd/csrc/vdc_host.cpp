@@ -356,6 +356,7 @@ struct Tiler {
     std::vector<std::vector<Word>> streams;
     std::vector<Desc> descs;
     bool nt = true;
+    int k_unroll = 1;      // measured: 2 saves front-end work but makes every load unit alternate between two static records; slower
     bool k_skew = false;   // measured on cfg5: no gain (the vector tiles are not what the cores wait for)
 
     uint32_t desc(uint32_t tensor, uint32_t box_rows, uint32_t row_bytes, uint32_t lds_pitch, uint64_t gpitch) {
@@ -406,12 +407,19 @@ struct Tiler {
                 // Every core starts its sweep over K at a different tile (and wraps around): cores that run in step
                 // would otherwise all ask the L2 for the same vector tile at the same moment.
                 const int64_t k0 = (k_skew && nk_full >= 8) ? ((int64_t)core * nk_full / cfg.n_cores) : 0;
-                auto sweep = [&](int64_t first, int64_t trips) {
-                    if (trips <= 0) return;
+                // k_unroll K steps per loop trip: one control uop per k_unroll steps (the front end still dispatches
+                // at most kBatch memory uops at a time, see the kernel)
+                auto sweep = [&](int64_t first, int64_t steps) {
+                    if (steps <= 0) return;
                     vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, first * Kt * 4, 0, 0));
+                    const int64_t U = steps >= 2 * k_unroll ? k_unroll : 1, trips = steps / U, rest = steps % U;
                     if (trips > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, trips, 0, 0));
-                    tile_pairs(dm, dx, 0);
-                    vm.push_back(encode(trips > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                    for (int64_t uu = 0; uu < U; uu++) tile_pairs(dm, dx, uu * Kt * 4);
+                    vm.push_back(encode(trips > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, U * (int64_t)Kt * 4, 0, 0));
+                    for (int64_t uu = 0; uu < rest; uu++) {
+                        tile_pairs(dm, dx, 0);
+                        vm.push_back(encode(OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                    }
                 };
                 sweep(k0, nk_full - k0);
                 if (ktail) tile_pairs(dmt, dxt, 0);      // acc 2 is at the end of the last full tile here

@@ -60,6 +60,7 @@ static __device__ __forceinline__ unsigned long long prof_now() {
 // LDS layout: [0, n_slots * slot_bytes) the slots, then the control block.
 // ------------------------------------------------------------------------------------------------
 constexpr int kUQ = 8;         // records per unit queue (CFU -> LDU/STU)
+constexpr int kBatch = 4;      // memory uops the front end dispatches at once (a batch is published in one piece: more is later)
 constexpr int kM2C = 32;       // m2c ring entries per VCC (>= slots, so a delivery never finds it full)
 constexpr int kC2M = 64;       // c2m ring entries per VCC
 constexpr int kMbox = 32;      // produced regions waiting for their STORE, per VCC
@@ -629,7 +630,7 @@ DEV void cfu_main(Ctx &c) {
         const uint32_t my_vcc = (d.ctl >> 19) & 1u, my_acc = (d.ctl >> 20) & 7u, my_nslots = (d.ctl >> 23) & 63u;
         const uint64_t not_mem = ~(d.mem >> k);                 // bit j clear = word k + j is a memory uop
         uint32_t nmax = (uint32_t)__builtin_ctzll(not_mem | (1ull << 63));
-        nmax = nmax > (uint32_t)kUQ ? (uint32_t)kUQ : nmax;
+        nmax = nmax > (uint32_t)kBatch ? (uint32_t)kBatch : nmax;
         nmax = nmax > (uint32_t)kWin - k ? (uint32_t)kWin - k : nmax;
         nmax = nmax < 1u ? 1u : nmax;
         // dynamic addresses: every lane picks its own accumulator out of the register file; its unit's queue tail too
@@ -909,7 +910,7 @@ DEV void ldu_main(Ctx &c) {
         const uint32_t info = rf_get(snap, 3);
         const uint32_t key = (info >> 6) & 0x7Fu;
         if (have && key != cur.key) {
-            if (key & 1u) {
+            if (((key >> 2) ^ key) & 1u) {   // two entries: loop bodies alternate between lanes 1, 2 or 4 apart
                 if (e1.key != key) ldu_derive(c, e1, key, info);
                 cur = e1;
             } else {
