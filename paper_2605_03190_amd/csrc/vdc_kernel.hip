@@ -1502,13 +1502,13 @@ DEV void observer_main(Ctx &c, uint32_t V) {
     // statistical profile: sample every wave's phase word as fast as possible; lane w counts how often wave w was
     // seen in each phase
     uint32_t h[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    uint32_t off = c.ctl + CTL_OFF(phase) + (c.lane & 15u) * 4u;
-    off = c.lane == 16u ? c.ctl + CTL_OFF(abort) : off;
-    off = c.lane == 17u ? c.ctl + CTL_OFF(cfu_halted) : off;
-    off = c.lane == 18u ? c.ctl + CTL_OFF(vcc_done) : off;
+    uint32_t poff = c.ctl + CTL_OFF(phase) + (c.lane & 15u) * 4u;
+    poff = c.lane == 16u ? c.ctl + CTL_OFF(abort) : poff;
+    poff = c.lane == 17u ? c.ctl + CTL_OFF(cfu_halted) : poff;
+    poff = c.lane == 18u ? c.ctl + CTL_OFF(vcc_done) : poff;
     uint32_t it = 0;
     for (; it < (1u << 24); it++) {
-        const uint32_t ph = lds_vld32(off);
+        const uint32_t ph = lds_vld32(poff);
 #pragma unroll
         for (uint32_t i = 0; i < 8u; i++) h[i] += ph == i ? 1u : 0u;
         if (rf_get(ph, 16) != 0u || (rf_get(ph, 17) != 0u && rf_get(ph, 18) == 2u * V)) break;
