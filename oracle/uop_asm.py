@@ -18,9 +18,10 @@ import numpy as np
 HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
 LOAD, STORE = 8, 9
 MATVEC = 16
+ROPE = 17
 
 # flags
-F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV = 1, 2, 4, 8, 16, 32
+F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
 
 MASK48 = (1 << 48) - 1
 
@@ -44,6 +45,12 @@ def matvec_imm(B, R, lpr):
     """Static geometry of a MATVEC: B vectors, R box rows per matrix tile, lpr 16-byte chunks per tile row."""
     assert 1 <= B <= 8 and 1 <= R < 65536 and 1 <= lpr < 65536
     return B | (R << 8) | (lpr << 24)
+
+
+def rope_imm(B, R):
+    """Static geometry of a ROPE: B vectors, R values (R / 2 pairs) per vector in the tile."""
+    assert 1 <= B <= 8 and 2 <= R < 65536 and R % 2 == 0
+    return B | (R << 8)
 
 
 class Program:
@@ -81,11 +88,16 @@ class Program:
                 np.array(descs, dtype=np.uint32).reshape(-1, 8))
 
 
-def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_core=2, nt=False):
+def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_core=2, nt=False, rope=False):
     """A straightforward dense Y = M X program in the form of the paper's listing (Section 4.1):
     row blocks of R rows are dealt round-robin to the (core, vcc) pairs; each row block is one MATVEC
     over ceil(K/Kt) (matrix tile, vector tile) pairs, followed by a send+recv STORE of the result.
-    No loops, no accumulators: every address is a literal.  Tensors: 0 = M, 1 = X, 2 = Y."""
+    No loops, no accumulators: every address is a literal.  Tensors: 0 = M, 1 = X, 2 = Y.
+
+    rope=True builds the fused form of the running example of Section 3 (O = M @ N; R = rope(O, T)):
+    the matvec result never goes to memory; a store.local / load.local pair hands its region on to a
+    ROPE uop of the same compute core, which also gets the tile of tensor 3 = T ([B][rows], cos and
+    sin interleaved per pair of rows) and writes its result to Y."""
     assert K % 4 == 0 and ld % 4 == 0 and Kt % 4 == 0
     p = Program(n_cores, vcc_per_core)
     lpr = Kt // 4
@@ -109,8 +121,17 @@ def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_cor
                            imm=(r0 * ld + k0) * 4, desc=dm))
             vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=x_slots, size=B, imm=k0 * 4, desc=dx))
         dy = p.desc(2, B, rv * 4, R * 4, rows * 4)
+        if rope:
+            assert rv % 2 == 0 and (rv * 4) % 16 == 0
+            do = p.desc(2, B, R * 4, R * 4, rows * 4)        # geometry of the region that is handed on (no memory access)
+            dt = p.desc(3, B, rv * 4, R * 4, rows * 4)
+            vm.append(word(STORE, F_SEND | F_RECV | F_LOCAL, vflow=4 + v, vcc=v, nslots=y_slots, size=B, imm=0, desc=do))
+            vm.append(word(LOAD, F_SEND | F_LOCAL, vflow=4 + v, vcc=v, nslots=0, size=B, imm=0, desc=do))
+            vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=y_slots, size=B, imm=r0 * 4, desc=dt))
         vm.append(word(STORE, F_SEND | F_RECV, vflow=4 + v, vcc=v, nslots=y_slots, size=B, imm=r0 * 4, desc=dy))
         p.vcc(core, v).append(word(MATVEC, size=nk, imm=matvec_imm(B, R, lpr)))
+        if rope:
+            p.vcc(core, v).append(word(ROPE, size=1, imm=rope_imm(B, R)))
     return p
 
 

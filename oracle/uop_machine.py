@@ -25,6 +25,11 @@ machine in the paper's order and vocabulary and shares nothing with the HIP path
 * Section 4.1, listing of the `matvec` compute uop: for each of `size` tiles pop a matrix
   tile and a vector tile from m2c, accumulate, push both to c2m; then pop an output
   region, copy the accumulators into it and push it back.
+* Section 3 ("Execution Example") and Section 4.2: fused operators keep an intermediate
+  result on chip: a store.local takes the produced region back from the compute core but
+  writes nothing, and the load.local behind it on the same flow hands the very same region
+  to a compute core again.  The `rope` uop of the example turns pairs of values by the
+  angles whose cosines and sines a second tile holds.
 
 Where the paper is silent the readings are those written in the design document:
 16-byte words, the opcode set below, m2c delivery in program order of the `send` uops
@@ -42,8 +47,8 @@ import numpy as np
 
 HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
 LOAD, STORE = 8, 9
-MATVEC = 16
-F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV = 1, 2, 4, 8, 16, 32
+MATVEC, ROPE = 16, 17
+F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
 KIND_FREE, KIND_DATA = 0, 1
 MAX_LOOP_DEPTH = 4
 N_ACC = 8
@@ -182,6 +187,7 @@ class Core:
         self.m2c_head = [0] * V
         self.c2m = [deque() for _ in range(V)]
         self.mailbox = [deque() for _ in range(V)]   # produced regions waiting for their STORE
+        self.parked = deque()                        # regions a store.local took back, waiting for their load.local
         self.vcc_run = [None] * V                    # running compute uop (generator) per VCC
         self.vcc_wait = [False] * V
         self.peak_slots = 0
@@ -243,26 +249,32 @@ class Machine:
         if u.opcode not in (LOAD, STORE):
             raise ProgramError("opcode %d on a memory core" % u.opcode)
         d = self.descs[u.desc]
-        need = -(-d.box_rows * d.lds_pitch // self.slot_bytes)
-        if u.nslots != need or u.nslots < 1 or u.nslots > self.n_slots:
+        local = bool(u.flags & F_LOCAL)
+        load_local = local and u.opcode == LOAD          # hands an existing region on: allocates and reads nothing
+        need = 0 if load_local else -(-d.box_rows * d.lds_pitch // self.slot_bytes)
+        if u.nslots != need or (u.nslots < 1 and not load_local) or u.nslots > self.n_slots:
             raise ProgramError("nslots does not match the descriptor box")
         if u.size < 1 or u.size > d.box_rows or u.vcc >= self.V:
             raise ProgramError("bad rows or vcc")
-        units = core.ldu if u.opcode == LOAD else core.stu
+        if local and (not u.flags & F_SEND or (u.opcode == STORE and not u.flags & F_RECV) or u.flags & F_DYNAMIC or u.imm):
+            raise ProgramError("malformed local memory uop")
+        units = core.ldu if (u.opcode == LOAD and not local) else core.stu
         q = units[u.vflow % len(units)]
         if len(q) >= self.qcap:
             return False
-        if first_fit(core.mask, u.nslots, self.n_slots) < 0:
+        if not load_local and first_fit(core.mask, u.nslots, self.n_slots) < 0:
             return False                      # in-order allocation: the front end stalls here
         if not commit:
             return True
-        before = core.mask
-        slot = core.alloc(u.nslots)
-        self.alloc_log[core.idx].append((before, u.nslots, slot))
+        slot = -1
+        if not load_local:
+            before = core.mask
+            slot = core.alloc(u.nslots)
+            self.alloc_log[core.idx].append((before, u.nslots, slot))
         off = u.imm + (s.acc[u.acc] if u.flags & F_DYNAMIC else 0)
         t = self.tensors[d.tensor]
         last = off + (u.size - 1) * d.gpitch + d.row_bytes
-        if off < 0 or last > t.size:
+        if not local and (off < 0 or last > t.size):
             raise ProgramError("tensor access out of bounds")
         ticket = -1
         if u.flags & F_SEND:
@@ -294,9 +306,25 @@ class Machine:
             return False
         if u.opcode == STORE and u.flags & F_RECV and not core.mailbox[u.vcc]:
             return False
+        if u.opcode == LOAD and u.flags & F_LOCAL and not core.parked:
+            return False
         if not commit:
             return True
         q.popleft()
+        if u.flags & F_LOCAL:
+            if u.opcode == STORE:
+                # store.local: take the produced region back, write nothing, keep it allocated
+                got = core.mailbox[u.vcc].popleft()
+                if got != (rec.slot, u.nslots):
+                    raise ProgramError("store received a region it did not allocate")
+                core.parked.append(got)
+            else:
+                # load.local: the oldest kept region goes to a compute core as a delivered tile
+                slot, nslots = core.parked.popleft()
+                self._m2c_push(core, u.vcc, rec.ticket, (slot, nslots, u.size, d.row_bytes))
+            if u.flags & F_DEP_SEND:
+                self.dep[u.dep_id] += 1
+            return True
         t = self.tensors[d.tensor]
         reg = core.region(rec.slot, u.nslots)
         if u.opcode == LOAD:
@@ -361,6 +389,27 @@ class Machine:
         out[:, :] = c.astype(np.float32)                   # copy(c, c_shared)
         self._c2m_push(core, v, KIND_DATA, o_slot, o_n)    # push it back for the write-back
 
+    def _rope(self, core, v, u):
+        """The rope compute uop of the running example (Section 3): pop the value tile, the tile of cosines
+        and sines and an output region, each [B][R] fp32; turn every pair (2i, 2i + 1) by its angle."""
+        B = u.imm & 0xFF
+        R = (u.imm >> 8) & 0xFFFF
+        o = yield
+        t = yield
+        out = yield
+        if o[2] != B or t[2] != B or out[2] != B or R % 2:
+            raise ProgramError("rope: tile geometry does not match the uop")
+        ov = core.region(o[0], o[1]).view(np.float32)[:B * R].reshape(B, R).astype(np.float64)
+        tv = core.region(t[0], t[1]).view(np.float32)[:B * R].reshape(B, R).astype(np.float64)
+        r = np.empty((B, R), dtype=np.float64)
+        x, y, c, s = ov[:, 0::2], ov[:, 1::2], tv[:, 0::2], tv[:, 1::2]
+        r[:, 0::2] = x * c - y * s
+        r[:, 1::2] = x * s + y * c
+        core.region(out[0], out[1]).view(np.float32)[:B * R].reshape(B, R)[:, :] = r.astype(np.float32)
+        self._c2m_push(core, v, KIND_FREE, o[0], o[1])
+        self._c2m_push(core, v, KIND_FREE, t[0], t[1])
+        self._c2m_push(core, v, KIND_DATA, out[0], out[1])
+
     def _c2m_push(self, core, v, kind, slot, nslots):
         core.c2m[v].append((kind, slot, nslots))
         core.stats["c2m_push"][v] += 1
@@ -376,11 +425,11 @@ class Machine:
                 if commit:
                     s.control(u)
                 return True
-            if u.opcode != MATVEC:
+            if u.opcode not in (MATVEC, ROPE):
                 raise ProgramError("opcode %d on a compute core" % u.opcode)
             if commit:
                 self.trace_vcc[core.idx][v].append((s.pc - s.begin, u.opcode, u.size, u.imm))
-                g = self._matvec(core, v, u)
+                g = self._matvec(core, v, u) if u.opcode == MATVEC else self._rope(core, v, u)
                 next(g)                                    # runs up to the first pop_wait
                 core.vcc_run[v] = g
             return True
@@ -415,7 +464,7 @@ class Machine:
         for c in self.cores:
             if not c.vmc.halted or any(not s.halted for s in c.vccs) or any(r is not None for r in c.vcc_run):
                 return False
-            if any(c.ldu) or any(c.stu) or any(c.c2m) or any(c.mailbox):
+            if any(c.ldu) or any(c.stu) or any(c.c2m) or any(c.mailbox) or c.parked:
                 return False
         return True
 
