@@ -128,6 +128,14 @@ int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info);
 int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
                int32_t B, int32_t tile_bytes, void *hip_stream);
 
+/* The running example of Section 3 in its fused form: O = M X as above, then R = rope(O, T), with O never leaving
+ * local memory (Section 4.2: a store.local / load.local pair hands the matvec's output region to the rope uop of
+ * the same compute core).  T: device, [B][rows] floats: for vector b and the pair of rows (2i, 2i+1), T[b][2i] is the
+ * cosine and T[b][2i+1] the sine of the pair's angle;  Y[b][2i] = O[b][2i] cos - O[b][2i+1] sin,
+ * Y[b][2i+1] = O[b][2i] sin + O[b][2i+1] cos.  rows must be a multiple of 4; T 16-byte aligned.  Dense only. */
+int vdc_matvec_rope(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X,
+                    const float *T, float *Y, int32_t B, int32_t tile_bytes, void *hip_stream);
+
 /* Ragged batch: n_seg independent row segments stacked in M (rows row_off[s] .. row_off[s+1]-1, K floats
  * each, contiguous); segment s is multiplied by its own vector X[s][0..K).  Y[i] for every stacked row.
  * row_off: host, n_seg+1 non-decreasing offsets starting at 0.  The tiler splits long segments over the
@@ -143,6 +151,10 @@ int vdc_matvec_ragged(vdc_executor *ex, const float *M, const int64_t *row_off, 
 int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                        const int64_t *row_off, int32_t n_seg, void *uops, int64_t *n_uops,
                        uint32_t *stream_begin, void *descs, int32_t *n_descs);
+
+/* The same for vdc_matvec_rope (tensors 0 = M, 1 = X, 2 = Y, 3 = T). */
+int vdc_matvec_rope_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
+                            void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs);
 
 /* A dense matrix with far fewer row blocks than there are compute cores is also cut along K: each (K range,
  * row block) pair is a work item, and the partial sums pass from range to range through a library-owned workspace

@@ -55,6 +55,8 @@ def lib():
             "vdc_matvec_ragged": [vp, vp, vp, i32, i64, vp, vp, i32, vp],
             "vdc_matvec_program": [vp, i64, i64, i64, i32, i32, vp, i32, vp, ctypes.POINTER(i64), vp, vp,
                                    ctypes.POINTER(i32)],
+            "vdc_matvec_rope": [vp, vp, i64, i64, i64, vp, vp, vp, i32, i32, vp],
+            "vdc_matvec_rope_program": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_matvec_workspace": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64)],
             "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
         }
@@ -70,7 +72,7 @@ def lib():
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
            "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
-           "vdc_matvec_program", "vdc_matvec_workspace", "vdc_debug_alloc", "vdc_strerror"]
+           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_debug_alloc", "vdc_strerror"]
 
 
 def strerror(code):
@@ -197,6 +199,16 @@ class Executor:
         _check(lib().vdc_matvec(self.handle, M.data_ptr(), rows, K, ld, X.data_ptr(), Y.data_ptr(), B, tile_bytes,
                                 _stream_ptr(stream)), "vdc_matvec")
 
+    def matvec_rope(self, M, X, T, Y, tile_bytes, K=None, stream=None):
+        """Y = rope(M X, T): T and Y are [B, rows]; T holds (cos, sin) for every pair of rows."""
+        rows, ld = M.shape
+        B, Kx = X.shape
+        K = Kx if K is None else K
+        assert all(t.is_cuda and t.is_contiguous() and str(t.dtype) == "torch.float32" for t in (M, X, T, Y))
+        assert Kx == K and tuple(Y.shape) == (B, rows) and tuple(T.shape) == (B, rows)
+        _check(lib().vdc_matvec_rope(self.handle, M.data_ptr(), rows, K, ld, X.data_ptr(), T.data_ptr(), Y.data_ptr(), B, tile_bytes,
+                                     _stream_ptr(stream)), "vdc_matvec_rope")
+
     def matvec_ragged(self, M, row_off, X, Y, tile_bytes, stream=None):
         """Segment s = rows row_off[s]..row_off[s+1]-1 of M ([sum rows, K]) times X[s] ([n_seg, K]); Y: [sum rows]."""
         row_off = np.ascontiguousarray(row_off, dtype=np.int64)
@@ -206,6 +218,18 @@ class Executor:
         assert int(row_off[-1]) == M.shape[0] == Y.numel()
         _check(lib().vdc_matvec_ragged(self.handle, M.data_ptr(), _np_ptr(row_off), n_seg, K, X.data_ptr(), Y.data_ptr(),
                                        tile_bytes, _stream_ptr(stream)), "vdc_matvec_ragged")
+
+    def matvec_rope_program(self, rows, K, ld, B, tile_bytes):
+        """The uop graph matvec_rope would run."""
+        n_w, n_d = ctypes.c_int64(0), ctypes.c_int32(0)
+        f = lib().vdc_matvec_rope_program
+        _check(f(self.handle, rows, K, ld, B, tile_bytes, None, ctypes.byref(n_w), None, None, ctypes.byref(n_d)), "vdc_matvec_rope_program (sizing)")
+        words = np.zeros((n_w.value, 4), dtype=np.uint32)
+        descs = np.zeros((n_d.value, 8), dtype=np.uint32)
+        sb = np.zeros(self.n_streams + 1, dtype=np.uint32)
+        _check(f(self.handle, rows, K, ld, B, tile_bytes, _np_ptr(words), ctypes.byref(n_w), _np_ptr(sb), _np_ptr(descs), ctypes.byref(n_d)),
+               "vdc_matvec_rope_program")
+        return words, sb, descs
 
     def matvec_program(self, rows, K, ld, B, tile_bytes, row_off=None):
         """The uop graph the matvec operator would run: (words[n,4], stream_begin, descs[n,8]) as numpy uint32."""

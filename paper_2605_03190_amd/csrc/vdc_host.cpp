@@ -35,9 +35,10 @@ struct MatvecKey {
     int64_t rows, K, ld;
     int32_t B, tile_bytes, n_seg;
     std::vector<int64_t> row_off;
+    bool rope = false;
     bool operator==(const MatvecKey &o) const {
         return rows == o.rows && K == o.K && ld == o.ld && B == o.B && tile_bytes == o.tile_bytes && n_seg == o.n_seg &&
-               row_off == o.row_off;
+               row_off == o.row_off && rope == o.rope;
     }
 };
 
@@ -83,6 +84,7 @@ struct SeqH {
 struct SentMsg {
     uint32_t slot, nslots, rows, row_bytes, box_rows, lds_pitch;
     bool is_store;
+    bool is_local = false;        // the region of a store.local
 };
 
 struct VccH {
@@ -91,8 +93,8 @@ struct VccH {
     // running MATVEC
     bool in_uop = false;
     uint32_t left = 0, B = 0, R = 0, lpr = 0;
-    int phase = 0;                // 0: expect a, 1: expect b, 2: expect out
-    SentMsg a{};
+    int phase = 0;                // MATVEC: 0 expect a, 1 expect b, 2 expect out; ROPE: 10 expect values, 11 expect angles, 12 expect out
+    SentMsg a{}, b{};
 };
 
 struct CoreH {
@@ -100,6 +102,7 @@ struct CoreH {
     std::vector<VccH> vcc;
     uint32_t mask = 0;
     std::deque<SentMsg> stores_waiting;  // STOREs whose region has not come back yet (only counted)
+    std::deque<SentMsg> parked;          // regions a store.local took back, waiting for their load.local
 };
 
 struct Validator {
@@ -180,6 +183,27 @@ struct Validator {
         if ((int)f.desc >= n_descs) { fail("descriptor index out of range"); return -1; }
         const Desc &d = descs[f.desc];
         const bool is_load = f.opcode == OP_LOAD;
+        const bool local = (f.flags & F_LOCAL) != 0;
+        if (local) {
+            // store.local / load.local: no memory access.  The load names no region of its own: it hands on the oldest
+            // region a store.local of this core has taken back.
+            if ((f.flags & (F_DYNAMIC | F_DEP_SEND | F_DEP_RECV | F_NT)) || f.imm != 0 || !(f.flags & F_SEND) || (!is_load && !(f.flags & F_RECV)) ||
+                (is_load && (f.flags & F_RECV))) { fail("malformed local memory uop"); return -1; }
+            if ((int)f.vcc >= cfg.vcc_per_core) { fail("vcc out of range"); return -1; }
+            if (d.box_rows < 1 || d.box_rows > 65535 || d.lds_pitch < 4 || d.lds_pitch > 65535 || d.row_bytes < 4 || d.row_bytes > d.lds_pitch ||
+                f.size < 1 || f.size > d.box_rows) { fail("bad descriptor box"); return -1; }
+        }
+        if (local && is_load) {
+            if (f.nslots != 0) { fail("load.local allocates nothing: nslots must be 0"); return -1; }
+            if (c.parked.empty()) return 0;
+            SentMsg m = c.parked.front();
+            c.parked.pop_front();
+            if ((uint64_t)d.box_rows * d.lds_pitch > (uint64_t)m.nslots * cfg.slot_bytes) { fail("load.local: the region is smaller than the box it is handed on as"); return -1; }
+            m.rows = f.size; m.row_bytes = d.row_bytes; m.box_rows = d.box_rows; m.lds_pitch = d.lds_pitch; m.is_store = false; m.is_local = false;
+            c.vcc[f.vcc].m2c.push_back(m);
+            s.pc++;
+            return 1;
+        }
         const uint64_t gpitch = (uint64_t)d.gpitch_lo | ((uint64_t)d.gpitch_hi << 32);
         if ((int)d.tensor >= n_tensors) { fail("tensor id out of range"); return -1; }
         if (d.box_rows < 1 || d.box_rows > 65535 || d.lds_pitch < 4 || d.lds_pitch > 65535 || d.row_bytes < 4 ||
@@ -203,14 +227,14 @@ struct Validator {
         const int64_t eff = f.imm + ((f.flags & F_DYNAMIC) ? s.acc[f.acc] : 0);
         if (eff < 0 || (eff % (is_load ? 16 : 4)) != 0) { fail("effective address negative or misaligned"); return -1; }
         const uint64_t last = (uint64_t)eff + (uint64_t)(f.size - 1) * gpitch + d.row_bytes;
-        if (last > (uint64_t)tensor_bytes[d.tensor]) { fail("memory uop reaches beyond its tensor"); return -1; }
+        if (!local && last > (uint64_t)tensor_bytes[d.tensor]) { fail("memory uop reaches beyond its tensor"); return -1; }
         // a DEP_RECV whose counter is not there yet blocks its unit, not the front end; in this in-order model the
         // front end waits as well, which is conservative
         if ((f.flags & F_DEP_RECV) && dep[f.dep_id] < std::max<uint32_t>(1u, f.dep_count)) return 0;
         int slot = first_fit(c.mask, f.nslots);
         if (slot < 0) return 0;
         c.mask |= (uint32_t)(((f.nslots >= 32 ? 0xFFFFFFFFull : ((1ull << f.nslots) - 1ull)) << slot));
-        SentMsg m{(uint32_t)slot, f.nslots, f.size, d.row_bytes, d.box_rows, d.lds_pitch, !is_load};
+        SentMsg m{(uint32_t)slot, f.nslots, f.size, d.row_bytes, d.box_rows, d.lds_pitch, !is_load, local};
         if (f.flags & F_SEND) c.vcc[f.vcc].m2c.push_back(m);
         if (!is_load) {
             if (!(f.flags & F_SEND)) { fail("STORE with RECV but without SEND: nothing hands its region to a compute core"); return -1; }
@@ -227,6 +251,18 @@ struct Validator {
         c.mask &= ~(uint32_t)(((m.nslots >= 32 ? 0xFFFFFFFFull : ((1ull << m.nslots) - 1ull)) << m.slot));
     }
 
+    // a produced region returns to its STORE: written back and freed, or (store.local) kept for the load.local
+    bool store_returns(CoreH &c, const SentMsg &m) {
+        for (auto it = c.stores_waiting.begin(); it != c.stores_waiting.end(); ++it)
+            if (it->slot == m.slot && it->nslots == m.nslots) {
+                const bool local = it->is_local;
+                c.stores_waiting.erase(it);
+                if (local) c.parked.push_back(m); else release(c, m);
+                return true;
+            }
+        return fail("a compute uop's output region has no STORE");
+    }
+
     int vcc_step(CoreH &c, VccH &v) {
         if (!v.in_uop) {
             if (v.s.halted) return 0;
@@ -235,6 +271,14 @@ struct Validator {
             int k = control(v.s, f);
             if (k < 0) return -1;
             if (k > 0) return 1;
+            if (f.opcode == OP_ROPE) {
+                v.B = (uint32_t)f.imm & 0xFFu;
+                v.R = (uint32_t)(f.imm >> 8) & 0xFFFFu;
+                if (!rope_geometry_ok(v.B, v.R)) { fail("rope geometry not supported"); return -1; }
+                v.phase = 10;
+                v.in_uop = true;
+                return 1;
+            }
             if (f.opcode != OP_MATVEC) { fail("opcode not valid on a compute core"); return -1; }
             v.B = (uint32_t)f.imm & 0xFFu;
             v.R = (uint32_t)(f.imm >> 8) & 0xFFFFu;
@@ -250,6 +294,21 @@ struct Validator {
         if (v.m2c.empty()) return 0;
         SentMsg m = v.m2c.front();
         v.m2c.pop_front();
+        if (v.phase >= 10) {
+            if (v.phase < 12) {
+                if (m.is_store || m.rows != v.B || m.box_rows != v.B || m.lds_pitch != v.R * 4) { fail("rope: input tile does not match the uop"); return -1; }
+                if (v.phase == 10) v.a = m; else v.b = m;
+                v.phase++;
+            } else {
+                if (!m.is_store || m.rows != v.B || m.lds_pitch != v.R * 4 || m.row_bytes > v.R * 4) { fail("rope: output region does not match the uop"); return -1; }
+                release(c, v.a);
+                release(c, v.b);
+                if (!store_returns(c, m)) return -1;
+                v.in_uop = false;
+                v.s.pc++;
+            }
+            return 1;
+        }
         if (v.phase == 0) {
             if (m.is_store || m.box_rows != v.R || m.lds_pitch != v.lpr * 16) { fail("matvec: matrix tile does not match the uop"); return -1; }
             v.a = m;
@@ -261,12 +320,7 @@ struct Validator {
             if (--v.left == 0) v.phase = 2; else v.phase = 0;
         } else {
             if (!m.is_store || m.rows != v.B || m.lds_pitch != v.R * 4 || m.row_bytes > v.R * 4) { fail("matvec: output region does not match the uop"); return -1; }
-            // produced region returns to its STORE, which writes it back and frees it
-            bool found = false;
-            for (auto it = c.stores_waiting.begin(); it != c.stores_waiting.end(); ++it)
-                if (it->slot == m.slot && it->nslots == m.nslots) { c.stores_waiting.erase(it); found = true; break; }
-            if (!found) { fail("matvec: output region has no STORE"); return -1; }
-            release(c, m);
+            if (!store_returns(c, m)) return -1;
             v.in_uop = false;
             v.s.pc++;
         }
@@ -323,7 +377,7 @@ struct Validator {
                 bool fin = core.vmc.halted;
                 for (auto &v : core.vcc) fin = fin && v.s.halted && !v.in_uop && v.m2c.empty();
                 if (fin) {
-                    if (core.mask != 0 || !core.stores_waiting.empty()) return fail("a core ends with slots still allocated");
+                    if (core.mask != 0 || !core.stores_waiting.empty() || !core.parked.empty()) return fail("a core ends with slots still allocated");
                     done[c] = 1;
                     n_done++;
                     progress = true;
@@ -356,6 +410,7 @@ struct Tiler {
     std::vector<std::vector<Word>> streams;
     std::vector<Desc> descs;
     bool nt = true;
+    bool rope = false;     // fused form: O = M X stays in local memory and a ROPE uop turns it (tensor 3 = T) before the store
     int k_unroll = 1;      // measured: 2 saves front-end work but makes every load unit alternate between two static records; slower
     bool k_skew = false;   // measured on cfg5: no gain (the vector tiles are not what the cores wait for)
 
@@ -374,6 +429,20 @@ struct Tiler {
     uint32_t flow_m(int v) const { return (uint32_t)v; }
     uint32_t flow_x(int v) const { return (uint32_t)(cfg.vcc_per_core + v); }
     uint32_t flow_y(int v) const { return (uint32_t)(2 * cfg.vcc_per_core + v); }
+
+    // What follows the K loop of one row block on the memory core: the store of the result, or, fused with rope
+    // (Section 3's running example), store.local + load.local hand the matvec's region on to the ROPE uop of the same
+    // compute core, a load brings the (cos, sin) tile, and the store writes what ROPE produced.
+    void emit_result(std::vector<Word> &vm, int v, uint32_t flags_dyn, uint32_t acc, int64_t y_off, uint32_t dy, uint32_t rows_valid, uint32_t y_slots) {
+        if (rope) {
+            const uint32_t d_o = desc(2, B, R * 4, R * 4, (uint64_t)y_pitch * 4);                 // geometry only: no memory access
+            const uint32_t d_t = desc(3, B, rows_valid * 4, R * 4, (uint64_t)y_pitch * 4);
+            vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_LOCAL, flow_y(v), v, 0, y_slots, B, 0, 0, d_o, 0));
+            vm.push_back(encode(OP_LOAD, F_SEND | F_LOCAL, flow_y(v), v, 0, 0, B, 0, 0, d_o, 0));
+            vm.push_back(encode(OP_LOAD, F_SEND | flags_dyn, flow_x(v), v, acc, y_slots, B, 0, y_off, d_t, 0));
+        }
+        vm.push_back(encode(OP_STORE, F_SEND | F_RECV | flags_dyn, flow_y(v), v, acc, y_slots, B, 0, y_off, dy, 0));
+    }
 
     // `count` iterations; in each, every compute core in `vs` takes one block of `rows_valid` rows.
     void emit_blocks(int core, const std::vector<int> &vs, int64_t count, int64_t m_off, int64_t x_off, int64_t y_off,
@@ -424,10 +493,7 @@ struct Tiler {
                 sweep(k0, nk_full - k0);
                 if (ktail) tile_pairs(dmt, dxt, 0);      // acc 2 is at the end of the last full tile here
                 sweep(0, k0);
-                for (int i = 0; i < n; i++) {
-                    const int v = vs[i];
-                    vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, y_off + (it * n + i) * R * 4, dy, 0));
-                }
+                for (int i = 0; i < n; i++) emit_result(vm, vs[i], 0, 0, y_off + (it * n + i) * R * 4, dy, rows_valid, y_slots);
             }
         } else {
             // accumulators: 0,1 matrix offset of compute core 0,1; 2 vector offset; 3,4 result offset of compute core 0,1
@@ -451,8 +517,7 @@ struct Tiler {
                 vm.push_back(encode(nk_full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
             }
             if (ktail) tile_pairs(dmt, dxt);
-            for (int i = 0; i < n; i++)
-                vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DYNAMIC, flow_y(vs[i]), vs[i], 3 + vs[i], y_slots, B, 0, 0, dy, 0));
+            for (int i = 0; i < n; i++) emit_result(vm, vs[i], F_DYNAMIC, 3 + vs[i], 0, dy, rows_valid, y_slots);
             for (int i = 0; i < n; i++) {
                 vm.push_back(encode(OP_ADD, 0, 0, 0, vs[i], 0, 0, 0, (int64_t)n * R * ld * 4 - nk_full * Kt * 4, 0, 0));
                 vm.push_back(encode(OP_ADD, 0, 0, 0, 3 + vs[i], 0, 0, 0, (int64_t)n * R * 4, 0, 0));
@@ -463,6 +528,7 @@ struct Tiler {
             auto &vc = vcc(core, vs[i]);
             if (count > 1) vc.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, count, 0, 0));
             vc.push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, nk, 0, matvec_imm(B, R, Kt / 4), 0, 0));
+            if (rope) vc.push_back(encode(OP_ROPE, 0, 0, 0, 0, 0, 1, 0, rope_imm(B, R), 0, 0));
             if (count > 1) vc.push_back(encode(OP_REPEAT, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
         }
     }
@@ -608,12 +674,14 @@ SplitPlan plan_split(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, 
 
 int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                  const int64_t *row_off, int32_t n_seg, std::vector<Word> &words, std::vector<uint32_t> &sb,
-                 std::vector<Desc> &descs) {
+                 std::vector<Desc> &descs, bool rope = false) {
     int32_t R = 0, Kt = 0;
     if (!choose_tile(cfg, K, B, tile_bytes, R, Kt)) return VDC_EINVAL;
     if ((uint64_t)((K + Kt - 1) / Kt) > 65535) return VDC_EINVAL;
     const int C = cfg.n_cores, V = cfg.vcc_per_core;
     Tiler t{cfg, K, ld, row_off ? 0 : rows, B, R, Kt};
+    t.rope = rope;
+    if (rope && (row_off || (rows & 3) || (R & 3) || !rope_geometry_ok((uint32_t)B, (uint32_t)R))) return VDC_EINVAL;
     t.streams.resize((size_t)C * (1 + V));
     // global list of row blocks, segment by segment; core c takes blocks [c*NB/C, (c+1)*NB/C)
     struct Seg { int64_t row0, len, first_block, n_blocks; };
@@ -630,7 +698,7 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
         segs.push_back({0, rows, 0, (rows + R - 1) / R});
         nb = segs[0].n_blocks;
     }
-    const SplitPlan sp = plan_split(cfg, rows, K, B, R, Kt, row_off != nullptr);
+    const SplitPlan sp = rope ? SplitPlan{} : plan_split(cfg, rows, K, B, R, Kt, row_off != nullptr);
     if (sp.S > 1) {
         // items in the order (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  Only items of the last
         // range wait, and only for items of earlier ranges, which earlier positions of the same or of earlier cores
@@ -929,10 +997,12 @@ static void workspace_init(const vdc_config &cfg, int64_t rows, int64_t K, int32
 }
 
 static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
-                         int32_t B, int32_t tile_bytes, const int64_t *row_off, int32_t n_seg, void *hip_stream) {
+                         int32_t B, int32_t tile_bytes, const int64_t *row_off, int32_t n_seg, void *hip_stream,
+                         const float *T = nullptr, bool rope = false) {
     if (!ex || ex->cfg.device == -1 || !M || !X || !Y || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
     if (((uintptr_t)M & 15u) || ((uintptr_t)X & 15u) || ((uintptr_t)Y & 3u)) return VDC_EINVAL;
-    MatvecKey key{rows, K, ld, B, tile_bytes, row_off ? n_seg : -1, {}};
+    if (rope && (!T || ((uintptr_t)T & 15u) || row_off)) return VDC_EINVAL;
+    MatvecKey key{rows, K, ld, B, tile_bytes, row_off ? n_seg : -1, {}, rope};
     if (row_off) key.row_off.assign(row_off, row_off + n_seg + 1);
     vdc_program *prog = nullptr;
     for (auto &kv : ex->matvec_cache)
@@ -941,14 +1011,14 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
         std::vector<Word> words;
         std::vector<uint32_t> sb;
         std::vector<Desc> descs;
-        int rc = build_matvec(ex->cfg, rows, K, ld, B, tile_bytes, row_off, n_seg, words, sb, descs);
+        int rc = build_matvec(ex->cfg, rows, K, ld, B, tile_bytes, row_off, n_seg, words, sb, descs, rope);
         if (rc != VDC_OK) return rc;
         const int64_t x_rows = row_off ? n_seg : B;
         std::vector<float> ws;
-        workspace_init(ex->cfg, rows, K, B, tile_bytes, row_off != nullptr, ws);
-        int64_t tb[4] = {((rows - 1) * ld + K) * 4, x_rows * K * 4, (int64_t)B * rows * 4, (int64_t)ws.size() * 4};
+        if (!rope) workspace_init(ex->cfg, rows, K, B, tile_bytes, row_off != nullptr, ws);
+        int64_t tb[4] = {((rows - 1) * ld + K) * 4, x_rows * K * 4, (int64_t)B * rows * 4, rope ? (int64_t)B * rows * 4 : (int64_t)ws.size() * 4};
         rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb,
-                                ws.empty() ? 3 : 4, &prog);
+                                (ws.empty() && !rope) ? 3 : 4, &prog);
         if (rc != VDC_OK) return rc;
         if (!ws.empty()) {
             if (hipMalloc(&prog->d_workspace, ws.size() * 4) != hipSuccess) { vdc_program_destroy(prog); return VDC_ENOMEM; }
@@ -956,13 +1026,18 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
         }
         ex->matvec_cache.push_back({key, prog});
     }
-    void *bases[4] = {(void *)M, (void *)X, (void *)Y, prog->d_workspace};
-    return vdc_run(ex, prog, bases, prog->d_workspace ? 4 : 3, hip_stream);
+    void *bases[4] = {(void *)M, (void *)X, (void *)Y, rope ? (void *)T : prog->d_workspace};
+    return vdc_run(ex, prog, bases, (rope || prog->d_workspace) ? 4 : 3, hip_stream);
 }
 
 int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y, int32_t B,
                int32_t tile_bytes, void *hip_stream) {
     return matvec_common(ex, M, rows, K, ld, X, Y, B, tile_bytes, nullptr, 0, hip_stream);
+}
+
+int vdc_matvec_rope(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, const float *T, float *Y,
+                    int32_t B, int32_t tile_bytes, void *hip_stream) {
+    return matvec_common(ex, M, rows, K, ld, X, Y, B, tile_bytes, nullptr, 0, hip_stream, T, true);
 }
 
 int vdc_matvec_ragged(vdc_executor *ex, const float *M, const int64_t *row_off, int32_t n_seg, int64_t K, const float *X,
@@ -973,9 +1048,24 @@ int vdc_matvec_ragged(vdc_executor *ex, const float *M, const int64_t *row_off, 
     return matvec_common(ex, M, row_off[n_seg], K, K, X, Y, 1, tile_bytes, row_off, n_seg, hip_stream);
 }
 
+static int matvec_program_common(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
+                                 const int64_t *row_off, int32_t n_seg, void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs,
+                                 int32_t *n_descs, bool rope);
+
 int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                        const int64_t *row_off, int32_t n_seg, void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs,
                        int32_t *n_descs) {
+    return matvec_program_common(ex, rows, K, ld, B, tile_bytes, row_off, n_seg, uops, n_uops, stream_begin, descs, n_descs, false);
+}
+
+int vdc_matvec_rope_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes, void *uops,
+                            int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs) {
+    return matvec_program_common(ex, rows, K, ld, B, tile_bytes, nullptr, 0, uops, n_uops, stream_begin, descs, n_descs, true);
+}
+
+static int matvec_program_common(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
+                                 const int64_t *row_off, int32_t n_seg, void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs,
+                                 int32_t *n_descs, bool rope) {
     if (!ex || !n_uops || !n_descs || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
     if (row_off) {
         if (n_seg < 1 || row_off[0] != 0 || row_off[n_seg] != rows || B != 1 || ld != K) return VDC_EINVAL;
@@ -985,7 +1075,7 @@ int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, in
     std::vector<Word> words;
     std::vector<uint32_t> sb;
     std::vector<Desc> ds;
-    int rc = build_matvec(ex->cfg, rows, K, ld, B, tile_bytes, row_off, n_seg, words, sb, ds);
+    int rc = build_matvec(ex->cfg, rows, K, ld, B, tile_bytes, row_off, n_seg, words, sb, ds, rope);
     if (rc != VDC_OK) return rc;
     const int64_t cap_w = *n_uops;
     const int32_t cap_d = *n_descs;

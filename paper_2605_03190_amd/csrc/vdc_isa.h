@@ -25,7 +25,8 @@ enum Opcode : uint32_t {
     OP_SET = 4,     // acc[a] = imm
     OP_LOAD = 8,    // VMC: global -> local-memory region
     OP_STORE = 9,   // VMC: local-memory region -> global
-    OP_MATVEC = 16  // VCC: the matvec compute uop of the listing in Section 4.1
+    OP_MATVEC = 16, // VCC: the matvec compute uop of the listing in Section 4.1
+    OP_ROPE = 17    // VCC: the rope uop of the running example (Section 3): turn pairs of values by given angles
 };
 
 enum Flag : uint32_t {
@@ -34,7 +35,10 @@ enum Flag : uint32_t {
     F_DYNAMIC = 4,   // address = imm + acc[a]
     F_NT = 8,        // streaming hint for the load path; no semantic effect
     F_DEP_SEND = 16, // after completion: dep[depId] += 1
-    F_DEP_RECV = 32  // before starting: wait until dep[depId] >= max(1, dep_count)
+    F_DEP_RECV = 32, // before starting: wait until dep[depId] >= max(1, dep_count)
+    F_LOCAL = 64     // store.local / load.local (Section 4.2): the region stays in local memory.  A STORE takes the
+                     // produced region back and keeps it; the next LOAD with this flag on the same flow hands it to a
+                     // compute core again (no allocation: nslots = 0; no memory access)
 };
 
 constexpr int kMaxLoopDepth = 4;
@@ -95,6 +99,11 @@ inline Word encode(uint32_t opcode, uint32_t flags, uint32_t vflow, uint32_t vcc
 inline int64_t matvec_imm(uint32_t B, uint32_t R, uint32_t lpr) {
     return (int64_t)B | ((int64_t)R << 8) | ((int64_t)lpr << 24);
 }
+
+// ROPE imm: B [7:0], R [23:8]: the value tile, the tile of (cos, sin) pairs and the output region are all [B][R]
+// fp32 with a row pitch of R * 4 bytes; R even, B * R <= 1024
+inline int64_t rope_imm(uint32_t B, uint32_t R) { return (int64_t)B | ((int64_t)R << 8); }
+inline bool rope_geometry_ok(uint32_t B, uint32_t R) { return B >= 1 && B <= 8 && R >= 2 && (R & 1u) == 0 && B * R <= 1024; }
 
 // The compute uop works on `threads_per_eu` = 128 threads; a matrix tile is NF passes of 128 chunks of
 // 16 bytes.  Supported geometries (anything else is rejected when the program is created):

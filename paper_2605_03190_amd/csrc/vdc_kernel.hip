@@ -388,6 +388,7 @@ DEV void trace_put(Ctx &c, uint32_t stream, uint32_t &count, uint32_t pc_rel, ui
 // wave-uniform, so this runs on the scalar unit: f ends with bit p set iff positions p .. p + n - 1 are all free, and
 // the lowest such p wins.  (The vote of 32 probing lanes that the paper describes computes the same position.)
 DEV int slot_find(uint64_t busy, uint32_t n) {
+    if (n == 0u) return 0;          // nothing to allocate (load.local)
     uint64_t f = ~busy;
     for (uint32_t i = 1; i < n; i++) f &= f >> 1;
     if (f == 0ull) return -1;
@@ -486,7 +487,9 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
     uint64_t tbase = 0;
 #pragma unroll
     for (int t = 0; t < kMaxTensors; t++) tbase = ((d_tensor & (kMaxTensors - 1)) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tbase;
-    const uint32_t unit = f.opcode == OP_LOAD ? (f.vflow & (p->n_ldu - 1u)) : p->n_ldu;   // n_ldu is 1, 2 or 4
+    // loads go to the load unit of their flow (n_ldu is 1, 2 or 4); stores, and the load.local that hands a kept
+    // region on, to the store unit
+    const uint32_t unit = (f.opcode == OP_LOAD && !(f.flags & F_LOCAL)) ? (f.vflow & (p->n_ldu - 1u)) : p->n_ldu;
     const uint64_t a = (uint64_t)f.imm + (is_mem ? tbase : 0ull);
     d.base = pc;
     d.ctl = f.opcode | (f.flags << 8) | (unit << 16) | ((f.vcc & 1u) << 19) | (f.acc << 20) | (f.nslots << 23) | ((d_tensor & 7u) << 29);
@@ -668,7 +671,7 @@ DEV void cfu_main(Ctx &c) {
                 while (got < lim) {
                     const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
                     const uint64_t f1 = ~occ, f2 = f1 & (f1 >> 1), f3 = f2 & (f1 >> 2);
-                    const uint64_t r = ns == 1u ? f1 : (ns == 2u ? f2 : f3);
+                    const uint64_t r = ns == 1u ? f1 : (ns == 2u ? f2 : (ns == 0u ? ~0ull : f3));   // ns == 0: load.local, nothing to allocate
                     const bool fit = r != 0ull;
                     const uint32_t pos = (uint32_t)__builtin_ctzll(r | (1ull << 63)) & 31u;
                     const uint32_t bits = fit ? (((1u << ns) - 1u) << pos) : 0u;
@@ -1117,7 +1120,8 @@ DEV void stu_main(Ctx &c) {
     uint32_t box_rf0 = 0, box_rf1 = 0;              // produced regions waiting for their STORE: lane (i & 31) = entry i
     uint32_t box_head0 = 0, box_tail0 = 0, box_head1 = 0, box_tail1 = 0;
     bool have = false;                              // a STORE has been picked up and is waiting
-    uint32_t r_glo = 0, r_ghi = 0, r_info = 0, stat = 0;
+    uint32_t r_glo = 0, r_ghi = 0, r_info = 0, r_ticket = 0, stat = 0;
+    uint32_t park_rf = 0, park_head = 0, park_tail = 0;   // regions a store.local took back, waiting for their load.local
     Spin sp;
     bool ok = true;
     while (ok) {
@@ -1133,7 +1137,7 @@ DEV void stu_main(Ctx &c) {
         }
         if (!have && rf_get(snap, 4) != head) {
             // pick the next STORE up: from here on its queue entry and its static record may be reused
-            r_glo = rf_get(snap, 5); r_ghi = rf_get(snap, 6); r_info = rf_get(snap, 7);
+            r_glo = rf_get(snap, 5); r_ghi = rf_get(snap, 6); r_info = rf_get(snap, 7); r_ticket = rf_get(snap, 8);
             stat = stat_fetch(c, r_info);
             stat = stat + 0u;
             lds_wait();
@@ -1148,6 +1152,23 @@ DEV void stu_main(Ctx &c) {
             const uint32_t slot = r_info & 63u;
             c.pc = c.stream_pc0 + rf_get(stat, 6);
             bool ready = true;
+            if ((flags & F_LOCAL) && (w0 & 0xFFu) == (uint32_t)OP_LOAD) {
+                // load.local: the oldest kept region goes to the compute core as a delivered tile
+                if (park_head == park_tail) {
+                    raise_error(c, -3 /* VDC_EPROGRAM */, 0x980u);
+                    ok = false;
+                    break;
+                }
+                const uint32_t got = rf_get(park_rf, park_head & (kMbox - 1));
+                park_head++;
+                const uint32_t rows = rf_get(stat, 2) & 0xFFFFu, row_bytes = rf_get(stat, 3) & 0xFFFFu;
+                m2c_deliver(c, vcc, r_ticket, got & 63u, (got >> 6) & 63u, rows, row_bytes);
+                done++;
+                lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_done) + u * 4u, done);
+                have = false;
+                sp.n = 0;
+                continue;
+            }
             if (flags & F_DEP_RECV) {
                 uint32_t need = (dep >> 16) & 0xFFu;
                 if (need == 0u) need = 1u;
@@ -1167,7 +1188,15 @@ DEV void stu_main(Ctx &c) {
                     if (vcc == 0u) box_head0++; else box_head1++;
                 }
             }
-            if (ready) {
+            if (ready && (flags & F_LOCAL)) {
+                // store.local: nothing is written and nothing is freed; the region waits for its load.local
+                park_rf = rf_set(park_rf, park_tail & (kMbox - 1), slot | (nslots << 6));
+                park_tail++;
+                done++;
+                lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_done) + u * 4u, done);
+                have = false;
+                moved = true;
+            } else if (ready) {
                 const uint64_t gaddr = (uint64_t)r_glo | ((uint64_t)r_ghi << 32);
                 const uint64_t gpitch = (uint64_t)rf_get(stat, 0) | ((uint64_t)rf_get(stat, 1) << 32);
                 const uint32_t rows = rf_get(stat, 2) & 0xFFFFu, rb_pitch = rf_get(stat, 3);
@@ -1447,6 +1476,45 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     }
 }
 
+// The rope uop of the running example (Section 3): the value tile, the tile of (cos, sin) pairs and the output region
+// are all [B][R] fp32, rows back to back, so pair p of the tile lies at byte 8 p of each.  Thread t turns pairs
+// t, t + 128, ... (at most four).
+DEV bool rope_uop(Ctx &c, VccState &vs, uint32_t B, uint32_t R) {
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
+    Msg mo, mt;
+    if (!vcc_pop_wait(c, vs, 2u, 0u, mo, mt)) return false;
+    const uint32_t o_off = mo.slot << slot_shift, t_off = mt.slot << slot_shift;
+    const uint32_t pairs = B * R / 2u;
+    float rx[4], ry[4];
+#pragma unroll
+    for (uint32_t q = 0; q < 4u; q++) {
+        const uint32_t pr = vs.t + q * 128u;
+        rx[q] = 0.0f; ry[q] = 0.0f;
+        if (pr < pairs) {
+            const float x = lds_ldf(o_off + pr * 8u), y = lds_ldf(o_off + pr * 8u + 4u);
+            const float cs = lds_ldf(t_off + pr * 8u), sn = lds_ldf(t_off + pr * 8u + 4u);
+            rx[q] = __builtin_fmaf(x, cs, -(y * sn));
+            ry[q] = __builtin_fmaf(x, sn, y * cs);
+        }
+    }
+    // the results are in registers, so every read of the two input tiles has returned: they can go back
+    vcc_done_with(c, vs, 2u, 0u);
+    Msg mout, unused;
+    if (!vcc_pop_wait(c, vs, 1u, 1u, mout, unused)) return false;
+    const uint32_t out_off = mout.slot << slot_shift;
+#pragma unroll
+    for (uint32_t q = 0; q < 4u; q++) {
+        const uint32_t pr = vs.t + q * 128u;
+        if (pr < pairs) {
+            lds_stf(out_off + pr * 8u, rx[q]);
+            lds_stf(out_off + pr * 8u + 4u, ry[q]);
+        }
+    }
+    lds_wait();
+    vcc_done_with(c, vs, 1u, 1u);
+    return true;
+}
+
 // The control-flow unit of a VCC runs on the execution unit's own threads (Section 4.3, "Virtual Compute Core"):
 // each of its two waves decodes the stream, runs control uops itself and then yields to the uop handler.
 DEV void vcc_main(Ctx &c, uint32_t wv) {
@@ -1474,6 +1542,8 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         if (TRACE && wv == 0u) trace_put(c, stream, trace_n, s.pc - c.stream_pc0, f.opcode | (f.size << 16), (uint64_t)f.imm);
         if (f.opcode == OP_MATVEC) {
             ok = matvec_dispatch(c, vs, f);
+        } else if (f.opcode == OP_ROPE) {
+            ok = rope_uop(c, vs, (uint32_t)f.imm & 0xFFu, (uint32_t)(f.imm >> 8) & 0xFFFFu);
         } else {
             raise_error(c, -3 /* VDC_EPROGRAM */, 0xE00u | f.opcode);
             ok = false;

@@ -10,7 +10,7 @@ import torch
 
 import paper_2605_03190_amd as vdc
 import workloads
-from oracle import gemv_ref, uop_asm as A, uop_machine as UM
+from oracle import gemv_ref, rope_ref, uop_asm as A, uop_machine as UM
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-5
@@ -154,6 +154,56 @@ def test_programs_assembled_by_the_oracle_side_run_on_the_gpu():
                 assert count[core * 3] == len(exp)
                 assert [tuple(int(x) for x in r) for r in trace[core * 3, :len(exp)]] == exp
             prog.destroy()
+
+
+ROPE_CASES = [
+    # rows, K, ld, B, tile_bytes
+    (128, 128, 128, 1, 4096),
+    (1000, 1000, 1000, 1, 4096),       # row tail and K tail
+    (516, 2052, 2060, 3, 8192),
+    (2048, 4096, 4096, 8, 16384),
+    (70000, 128, 128, 2, 8192),        # many row blocks per compute core: the looped form
+    (4096, 8192, 8192, 5, 16384),
+]
+
+
+@pytest.mark.parametrize("rows,K,ld,B,T", ROPE_CASES)
+def test_fused_matvec_rope_against_the_two_oracles(ex, rows, K, ld, B, T):
+    """R = rope(M X, T) with M X kept in local memory (store.local / load.local) against fp64 gemv followed by the fp64
+    rotation.  The intermediate is fp32 on the device, so its rounding scale is part of the bound."""
+    rng = np.random.default_rng(rows + K + B)
+    M = rng.standard_normal((rows, ld)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    Tt = rope_ref.table(rng.uniform(-np.pi, np.pi, (B, rows // 2)))
+    dY = torch.full((B, rows), float("nan"), device="cuda")
+    ex.matvec_rope(_dev(M), _dev(X), _dev(Tt), dY, T, K=K)
+    ex.check()
+    O, Oa = gemv_ref.gemv_dense(M, X, ld=ld)
+    Rr, Ra = rope_ref.rope(O, Tt)
+    # |error| <= 1e-5 * (sum of magnitudes behind each of the two values that are combined)
+    scale = np.empty_like(Oa)
+    scale[:, 0::2] = Oa[:, 0::2] + Oa[:, 1::2]
+    scale[:, 1::2] = scale[:, 0::2]
+    _check(dY.cpu().numpy(), Rr, scale + Ra, "rope %s" % ((rows, K, ld, B, T),))
+
+
+def test_fused_program_assembled_by_the_oracle_side_runs_on_the_gpu():
+    rows, K, B, R, Kt = 64, 128, 2, 16, 64
+    rng = np.random.default_rng(77)
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    Tt = rope_ref.table(rng.uniform(-np.pi, np.pi, (B, rows // 2)))
+    with vdc.Executor(n_cores=2, slot_bytes=4096) as e2:
+        w, sb, d = A.dense_matvec_program(rows, K, K, B, R, Kt, 4096, n_cores=2, rope=True).finish()
+        prog = e2.program_create(w, sb, d, [M.nbytes, X.nbytes, 4 * B * rows, Tt.nbytes])
+        dY = torch.full((B, rows), float("nan"), device="cuda")
+        e2.run(prog, [_dev(M), _dev(X), dY, _dev(Tt)])
+        e2.check()
+        Y = np.full((B, rows), np.nan, np.float32)
+        UM.Machine(w, sb, d, [M, X, Y, Tt], n_cores=2, slot_bytes=4096, n_slots=e2.cfg.n_slots).run("random", 5)
+        # the interpreter keeps the intermediate in fp32 as well: the two agree to fp32 rounding of the rotation
+        assert np.allclose(dY.cpu().numpy(), Y, rtol=0, atol=2e-5)
+        prog.destroy()
 
 
 def test_ragged_batch(ex):

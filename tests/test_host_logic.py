@@ -10,7 +10,7 @@ import pytest
 
 import paper_2605_03190_amd as vdc
 import workloads
-from oracle import gemv_ref, uop_asm as A, uop_machine as UM
+from oracle import gemv_ref, rope_ref, uop_asm as A, uop_machine as UM
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -83,6 +83,36 @@ def test_tiler_program_on_the_oracle_interpreter(rows, K, ld, B, T, ncores, slot
         Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
         # partial sums pass through fp32 once per K range
         assert np.all(np.abs(Y - Yr) <= (2e-6 if split else 1e-7) * Ya + 1e-30)
+
+
+@pytest.mark.parametrize("rows,K,ld,B,T,ncores,slot,nslots", [
+    (128, 128, 128, 1, 4096, 4, 4096, 12),
+    (100, 200, 212, 3, 4096, 3, 4096, 12),      # row tail (a multiple of 4), K tail, leading dimension
+    (640, 64, 64, 2, 4096, 2, 4096, 10),        # many row blocks per compute core: the looped form
+    (64, 1024, 1024, 8, 16384, 2, 8192, 10),
+])
+def test_fused_matvec_rope_program_on_the_oracle_interpreter(rows, K, ld, B, T, ncores, slot, nslots):
+    rng = np.random.default_rng(rows + 3 * K)
+    M = rng.standard_normal((rows, ld)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    Tt = rope_ref.table(rng.uniform(-3.0, 3.0, (B, rows // 2)))
+    Y = np.full((B, rows), np.nan, np.float32)
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
+        w, sb, d = ex.matvec_rope_program(rows, K, ld, B, T)
+        rc, msg = ex.program_validate(w, sb, d, [((rows - 1) * ld + K) * 4, X.nbytes, Y.nbytes, Tt.nbytes])
+        assert rc == vdc.VDC_OK, msg
+        with pytest.raises(vdc.VdcError):
+            ex.matvec_rope_program(rows + 2, K, ld, B, T)          # rows must be a multiple of 4
+    ops, flags = w[:, 0] & 0xFF, (w[:, 0] >> 8) & 0xFF
+    assert (ops == A.ROPE).any() and ((ops == A.STORE) & ((flags & A.F_LOCAL) != 0)).any() and ((ops == A.LOAD) & ((flags & A.F_LOCAL) != 0)).any()
+    O, Oa = gemv_ref.gemv_dense(M, X, ld=ld)
+    Rr, Ra = rope_ref.rope(O, Tt)
+    for sched, seed in (("program", 0), ("random", 1)):
+        Y[:] = np.nan
+        m = UM.Machine(w, sb, d, [M, X, Y, Tt], n_cores=ncores, slot_bytes=slot, n_slots=nslots)
+        m.run(sched, seed)
+        m.check_final()
+        assert np.all(np.abs(Y - Rr) <= 1e-6 * (Ra + Oa) + 1e-30)
 
 
 def test_ragged_tiler_program_on_the_oracle_interpreter():
