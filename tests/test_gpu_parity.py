@@ -206,6 +206,43 @@ def test_fused_program_assembled_by_the_oracle_side_runs_on_the_gpu():
         prog.destroy()
 
 
+def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):
+    """vdc_run enqueues kernels only (counters are cleared by a fill kernel, never by a memset node), so a caller may
+    capture it; every replay, with eager work and synchronisations in between, must equal the eager result."""
+    rows, K, B, T = 1024, 2048, 2, 8192
+    rng = np.random.default_rng(9)
+    dM = _dev(rng.standard_normal((rows, K)).astype(np.float32))
+    dY = torch.full((B, rows), float("nan"), device="cuda")
+    dY2 = torch.full((B, 64), float("nan"), device="cuda")              # a second, split-K run in the same graph (uses depIds)
+    dM2 = _dev(rng.standard_normal((64, 16384)).astype(np.float32))
+    dX2 = _dev(rng.standard_normal((B, 16384)).astype(np.float32))
+    xs = [_dev(rng.standard_normal((B, K)).astype(np.float32)) for _ in range(3)]
+    dX = xs[0].clone()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        ex.matvec(dM, dX, dY, T, stream=s)                              # builds and caches the programs outside the capture
+        ex.matvec(dM2, dX2, dY2, 16384, stream=s)
+        ex.check(s)
+        eager2 = dY2.clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            ex.matvec(dM, dX, dY, T, stream=s)
+            ex.matvec(dM2, dX2, dY2, 16384, stream=s)
+    torch.cuda.synchronize()
+    for x in xs:
+        dX.copy_(x)
+        dY.fill_(float("nan")); dY2.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ex.check()
+        want = torch.empty_like(dY)
+        ex.matvec(dM, x, want, T)                                       # eager, between the replays
+        ex.check()
+        assert torch.equal(dY, want)
+        assert torch.equal(dY2, eager2)
+
+
 def test_ragged_batch(ex):
     rng = np.random.default_rng(4)
     K = 128
