@@ -21,7 +21,7 @@ MATVEC = 16
 ROPE = 17
 
 # flags
-F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL, F_MCAST = 1, 2, 4, 8, 16, 32, 64, 128
+F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
 
 MASK48 = (1 << 48) - 1
 

@@ -31,10 +31,6 @@ machine in the paper's order and vocabulary and shares nothing with the HIP path
   to a compute core again.  The `rope` uop of the example turns pairs of values by the
   angles whose cosines and sines a second tile holds.
 
-An extension of this build: a load with `mcast` sends its one region to every compute core
-of its memory core (one ticket in each m2c); the region goes back to the pool when each of
-them has pushed it to c2m.  It stands for as many identical loads, in one region.
-
 Where the paper is silent the readings are those written in the design document:
 16-byte words, the opcode set below, m2c delivery in program order of the `send` uops
 (tickets), and a `kind` tag on c2m messages (recycle / produced).
@@ -52,7 +48,7 @@ import numpy as np
 HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
 LOAD, STORE = 8, 9
 MATVEC, ROPE = 16, 17
-F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL, F_MCAST = 1, 2, 4, 8, 16, 32, 64, 128
+F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
 KIND_FREE, KIND_DATA = 0, 1
 MAX_LOOP_DEPTH = 4
 N_ACC = 8
@@ -171,7 +167,7 @@ class Issued:
     d: Desc
     offset: int          # byte offset inside the tensor
     slot: int
-    ticket: object       # position in m2c[vcc] when SEND (one per compute core when MCAST), else -1
+    ticket: int          # position in m2c[vcc] when SEND, else -1
 
 
 class Core:
@@ -192,7 +188,6 @@ class Core:
         self.c2m = [deque() for _ in range(V)]
         self.mailbox = [deque() for _ in range(V)]   # produced regions waiting for their STORE
         self.parked = deque()                        # regions a store.local took back, waiting for their load.local
-        self.shared = {}                             # first slot of a multicast region -> compute cores still holding it
         self.vcc_run = [None] * V                    # running compute uop (generator) per VCC
         self.vcc_wait = [False] * V
         self.peak_slots = 0
@@ -282,14 +277,7 @@ class Machine:
         if not local and (off < 0 or last > t.size):
             raise ProgramError("tensor access out of bounds")
         ticket = -1
-        if u.flags & F_MCAST:
-            if u.opcode != LOAD or local or not u.flags & F_SEND:
-                raise ProgramError("mcast is defined for sending loads only")
-            ticket = []
-            for v in range(self.V):
-                ticket.append(core.m2c_next_ticket[v])
-                core.m2c_next_ticket[v] += 1
-        elif u.flags & F_SEND:
+        if u.flags & F_SEND:
             ticket = core.m2c_next_ticket[u.vcc]
             core.m2c_next_ticket[u.vcc] += 1
         rec = Issued(s.pc - s.begin, u, d, off, slot, ticket)
@@ -344,11 +332,7 @@ class Machine:
             for r in range(u.size):
                 g = rec.offset + r * d.gpitch
                 reg[r * d.lds_pitch:r * d.lds_pitch + d.row_bytes] = t[g:g + d.row_bytes]
-            if u.flags & F_MCAST:
-                core.shared[rec.slot] = self.V                # goes back when every compute core has returned it
-                for v in range(self.V):
-                    self._m2c_push(core, v, rec.ticket[v], (rec.slot, u.nslots, u.size, d.row_bytes))
-            elif u.flags & F_SEND:
+            if u.flags & F_SEND:
                 self._m2c_push(core, u.vcc, rec.ticket, (rec.slot, u.nslots, u.size, d.row_bytes))
             # a load that is not sent on stays allocated until something frees it; not used here
         else:
@@ -372,11 +356,6 @@ class Machine:
             kind, slot, nslots = core.c2m[v].popleft()
             core.stats["c2m_pop"][v] += 1
             if kind == KIND_FREE:
-                if slot in core.shared:
-                    core.shared[slot] -= 1
-                    if core.shared[slot] > 0:
-                        return True
-                    del core.shared[slot]
                 core.free(slot, nslots)
             else:
                 core.mailbox[v].append((slot, nslots))
@@ -485,7 +464,7 @@ class Machine:
         for c in self.cores:
             if not c.vmc.halted or any(not s.halted for s in c.vccs) or any(r is not None for r in c.vcc_run):
                 return False
-            if any(c.ldu) or any(c.stu) or any(c.c2m) or any(c.mailbox) or c.parked or c.shared:
+            if any(c.ldu) or any(c.stu) or any(c.c2m) or any(c.mailbox) or c.parked:
                 return False
         return True
 

@@ -279,60 +279,3 @@ def test_paper_deployment_constants_are_the_defaults():
     with pytest.raises(AssertionError):
         UM.Machine(np.zeros((1, 4), np.uint32), np.zeros(4, np.uint32), np.zeros((1, 8), np.uint32), [],
                    n_cores=1, n_slots=33)
-
-
-def _shared_vector_program(rows, K, B, R, Kt, n_cores, mcast):
-    """Pairs of row blocks on the two compute cores of a memory core; with mcast the vector tile is loaded once
-    per K step and sent to both, else once for each."""
-    p = A.Program(n_cores, 2)
-    lpr, nk = Kt // 4, K // Kt
-    dm = p.desc(0, R, Kt * 4, Kt * 4, K * 4)
-    dx = p.desc(1, B, Kt * 4, Kt * 4, K * 4)
-    dy = p.desc(2, B, R * 4, R * 4, rows * 4)
-    for pair in range(rows // R // 2):
-        core = pair % n_cores
-        vm = p.vmc(core)
-        for kt in range(nk):
-            for v in range(2):
-                vm.append(A.word(A.LOAD, A.F_SEND, vflow=v, vcc=v, nslots=1, size=R, imm=((pair * 2 + v) * R * K + kt * Kt) * 4, desc=dm))
-                if not mcast:
-                    vm.append(A.word(A.LOAD, A.F_SEND, vflow=2 + v, vcc=v, nslots=1, size=B, imm=kt * Kt * 4, desc=dx))
-            if mcast:
-                vm.append(A.word(A.LOAD, A.F_SEND | A.F_MCAST, vflow=2, vcc=0, nslots=1, size=B, imm=kt * Kt * 4, desc=dx))
-        for v in range(2):
-            vm.append(A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=4 + v, vcc=v, nslots=1, size=B, imm=(pair * 2 + v) * R * 4, desc=dy))
-            p.vcc(core, v).append(A.word(A.MATVEC, size=nk, imm=A.matvec_imm(B, R, lpr)))
-    return p.finish()
-
-
-def test_a_multicast_load_stands_for_one_load_per_compute_core():
-    rows, K, B, R, Kt, slot = 64, 128, 2, 8, 32, 1024
-    rng = np.random.default_rng(21)
-    M = rng.standard_normal((rows, K)).astype(np.float32)
-    X = rng.standard_normal((B, K)).astype(np.float32)
-    images, peaks = {}, {}
-    for mcast in (False, True):
-        w, sb, d = _shared_vector_program(rows, K, B, R, Kt, 2, mcast)
-        for sched, seed in [("program", 0)] + [("random", s) for s in range(1, 16)]:
-            Y = np.full((B, rows), np.nan, np.float32)
-            m = UM.Machine(w, sb, d, [M, X, Y], n_cores=2, slot_bytes=slot, n_slots=12)
-            m.run(sched, seed)
-            m.check_final()
-            assert all(c.mask == 0 and not c.shared for c in m.cores)
-            images.setdefault(mcast, Y.copy())
-            assert np.array_equal(images[mcast], Y)                    # determinate
-            peaks[mcast] = max(peaks.get(mcast, 0), max(c.peak_slots for c in m.cores))
-    assert np.array_equal(images[False], images[True])                 # the same values reach the same sums in the same order
-    Yr, Ya = gemv_ref.gemv_dense(M, X)
-    assert np.all(np.abs(images[True] - Yr) <= 1e-7 * Ya)
-    # a region that both compute cores read is held until the second one returns it, never freed twice
-    w, sb, d = _shared_vector_program(rows, K, B, R, Kt, 2, True)
-    m = UM.Machine(w, sb, d, [M, X, np.zeros((B, rows), np.float32)], n_cores=2, slot_bytes=slot, n_slots=3)
-    m.run("random", 5)                                                  # three slots: two matrix tiles + the shared vector tile
-    m.check_final()
-    with pytest.raises(UM.ProgramError):
-        p = A.Program(1, 2)
-        dsc = p.desc(0, 1, 16, 16, 16)
-        p.vmc(0).append(A.word(A.STORE, A.F_SEND | A.F_RECV | A.F_MCAST, vflow=0, vcc=0, nslots=1, size=1, desc=dsc))
-        ww, ss, dd = p.finish()
-        UM.Machine(ww, ss, dd, [np.zeros(4, np.float32)], n_cores=1, slot_bytes=1024, n_slots=4).run("program", 0)
