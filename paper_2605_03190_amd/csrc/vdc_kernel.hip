@@ -671,7 +671,7 @@ DEV void cfu_main(Ctx &c) {
                 while (got < lim) {
                     const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
                     const uint64_t f1 = ~occ, f2 = f1 & (f1 >> 1), f3 = f2 & (f1 >> 2);
-                    const uint64_t r = ns == 1u ? f1 : (ns == 2u ? f2 : (ns == 0u ? ~0ull : f3));   // ns == 0: load.local, nothing to allocate
+                    const uint64_t r = ns <= 1u ? f1 : (ns == 2u ? f2 : f3);   // ns == 0 (load.local) takes no bits; it passes as soon as any slot is free
                     const bool fit = r != 0ull;
                     const uint32_t pos = (uint32_t)__builtin_ctzll(r | (1ull << 63)) & 31u;
                     const uint32_t bits = fit ? (((1u << ns) - 1u) << pos) : 0u;
