@@ -668,19 +668,49 @@ DEV void cfu_main(Ctx &c) {
             alloc_bits = 0;
             pos_pack = 0;
             if (__builtin_expect(small_regions, 1)) {
-                while (got < lim) {
-                    const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
-                    const uint64_t f1 = ~occ, f2 = f1 & (f1 >> 1), f3 = f2 & (f1 >> 2);
-                    const uint64_t r = ns <= 1u ? f1 : (ns == 2u ? f2 : f3);   // ns == 0 (load.local) takes no bits; it passes as soon as any slot is free
-                    const bool fit = r != 0ull;
-                    const uint32_t pos = (uint32_t)__builtin_ctzll(r | (1ull << 63)) & 31u;
-                    const uint32_t bits = fit ? (((1u << ns) - 1u) << pos) : 0u;
-                    occ |= bits;
-                    alloc_bits |= bits;
-                    pos_pack |= (uint64_t)pos << (8u * got);
-                    lim = fit ? lim : 0u;
-                    got += fit ? 1u : 0u;
-                }
+                // the same first fit as slot_find for regions of at most 3 slots, all of the batch, written out for the
+                // scalar unit: two dozen instructions and one taken branch per uop (this loop is the busiest scalar
+                // code of the whole executor, and the compiler's version is half as long again)
+                uint32_t sh, ns, pos, pb, bits32, pack32 = 0;
+                uint64_t f, g, h, bits64;
+                const uint32_t nsp32 = (uint32_t)nsp;
+                static_assert(kBatch <= 4, "the packed slot counts and positions of a batch are 32 bits here");
+                asm volatile(
+                    "s_mov_b32 %[got], 0\n\t"
+                    "s_mov_b32 %[alloc], 0\n\t"
+                    "s_cmp_eq_u32 %[lim], 0\n\t"
+                    "s_cbranch_scc1 2f\n"
+                    "1:\n\t"
+                    "s_lshl_b32 %[sh], %[got], 3\n\t"
+                    "s_lshr_b32 %[ns], %[nsp], %[sh]\n\t"
+                    "s_and_b32 %[ns], %[ns], 3\n\t"
+                    "s_not_b64 %[f], %[occ]\n\t"
+                    "s_lshr_b64 %[g], %[f], 1\n\t"
+                    "s_and_b64 %[g], %[g], %[f]\n\t"
+                    "s_lshr_b64 %[h], %[f], 2\n\t"
+                    "s_and_b64 %[h], %[h], %[g]\n\t"
+                    "s_cmp_eq_u32 %[ns], 2\n\t"
+                    "s_cselect_b64 %[f], %[g], %[f]\n\t"
+                    "s_cmp_eq_u32 %[ns], 3\n\t"
+                    "s_cselect_b64 %[f], %[h], %[f]\n\t"
+                    "s_cmp_eq_u64 %[f], 0\n\t"
+                    "s_cbranch_scc1 2f\n\t"
+                    "s_ff1_i32_b64 %[pos], %[f]\n\t"
+                    "s_bfm_b64 %[b64], %[ns], %[pos]\n\t"
+                    "s_or_b64 %[occ], %[occ], %[b64]\n\t"
+                    "s_bfm_b32 %[b32], %[ns], %[pos]\n\t"
+                    "s_or_b32 %[alloc], %[alloc], %[b32]\n\t"
+                    "s_lshl_b32 %[pb], %[pos], %[sh]\n\t"
+                    "s_or_b32 %[pack], %[pack], %[pb]\n\t"
+                    "s_add_u32 %[got], %[got], 1\n\t"
+                    "s_cmp_lt_u32 %[got], %[lim]\n\t"
+                    "s_cbranch_scc1 1b\n"
+                    "2:"
+                    : [got] "=&s"(got), [alloc] "=&s"(alloc_bits), [pack] "+s"(pack32), [occ] "+s"(occ), [sh] "=&s"(sh), [ns] "=&s"(ns),
+                      [pos] "=&s"(pos), [pb] "=&s"(pb), [b32] "=&s"(bits32), [f] "=&s"(f), [g] "=&s"(g), [h] "=&s"(h), [b64] "=&s"(bits64)
+                    : [nsp] "s"(nsp32), [lim] "s"(lim)
+                    : "scc");
+                pos_pack = pack32;
             } else {
                 for (; got < lim; got++) {
                     const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
