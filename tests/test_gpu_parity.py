@@ -81,6 +81,49 @@ def test_dense_matvec_against_fp64_gemv(ex, rows, K, ld, B, T):
     _check(dY.cpu().numpy(), Yr, Ya, "dense %s" % ((rows, K, ld, B, T),))
 
 
+@pytest.mark.parametrize("cfg", [
+    dict(n_ldu=1), dict(n_ldu=2), dict(vcc_per_core=1), dict(vcc_per_core=1, n_ldu=1), dict(n_slots=6), dict(n_cores=7),
+    dict(slot_bytes=4096, n_slots=32), dict(slot_bytes=16384), dict(tile_rows=64), dict(n_cores=128),
+])
+def test_other_deployment_constants(cfg):
+    """The executor with fewer load units, one compute core per memory core, few slots, odd core counts, other slot
+    sizes, another tile shape, half the chip: same results (dense with tails, ragged, split along K, fused rope)."""
+    rng = np.random.default_rng(31)
+    with vdc.Executor(**cfg) as e:
+        for rows, K, ld, B, T in ((1000, 1000, 1000, 1, 4096), (517, 2052, 2060, 3, 8192), (2048, 4096, 4096, 8, 16384), (64, 32768, 32768, 2, 16384)):
+            if T < e.cfg.slot_bytes and cfg.get("slot_bytes") == 16384 and B * 256 * 4 > 16384:
+                continue
+            M = rng.standard_normal((rows, ld)).astype(np.float32)
+            X = rng.standard_normal((B, K)).astype(np.float32)
+            dY = torch.full((B, rows), float("nan"), device="cuda")
+            e.matvec(_dev(M), _dev(X), dY, T, K=K)
+            e.check()
+            Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
+            _check(dY.cpu().numpy(), Yr, Ya, "dense %s with %s" % ((rows, K, ld, B, T), cfg))
+        K = 128
+        row_off = np.array([0, 700, 700, 716, 5000, 5001, 9000, 20000], dtype=np.int64)
+        M = rng.standard_normal((20000, K)).astype(np.float32)
+        X = rng.standard_normal((7, K)).astype(np.float32)
+        dY = torch.full((20000,), float("nan"), device="cuda")
+        e.matvec_ragged(_dev(M), row_off, _dev(X), dY, 8192)
+        e.check()
+        Yr, Ya = gemv_ref.gemv_ragged(M, row_off, X)
+        _check(dY.cpu().numpy(), Yr, Ya, "ragged with %s" % (cfg,))
+        rows, K, B = 516, 1028, 3
+        M = rng.standard_normal((rows, K)).astype(np.float32)
+        X = rng.standard_normal((B, K)).astype(np.float32)
+        Tt = rope_ref.table(rng.uniform(-3, 3, (B, rows // 2)))
+        dY = torch.full((B, rows), float("nan"), device="cuda")
+        e.matvec_rope(_dev(M), _dev(X), _dev(Tt), dY, 8192)
+        e.check()
+        O, Oa = gemv_ref.gemv_dense(M, X)
+        Rr, Ra = rope_ref.rope(O, Tt)
+        scale = np.empty_like(Oa)
+        scale[:, 0::2] = Oa[:, 0::2] + Oa[:, 1::2]
+        scale[:, 1::2] = scale[:, 0::2]
+        _check(dY.cpu().numpy(), Rr, scale + Ra, "rope with %s" % (cfg,))
+
+
 def test_closed_forms_on_the_gpu(ex):
     rows, K = 3000, 1536
     M = np.repeat((np.arange(rows) % 1024).astype(np.float32)[:, None], K, axis=1)
