@@ -12,8 +12,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x",
          "-Wno-unused-command-line-argument"]
 
 
-def build(verbose=False):
-    cmd = ["/opt/rocm/bin/hipcc"] + FLAGS + SOURCES + ["-o", SO]
+SO_OBSERVER = os.path.join(HERE, "libvdcores_obs.so")   # profiling build with the observer wave; not used by the product path
+
+
+def build(verbose=False, observer=False):
+    """observer=True builds the instrumented library that stage_latency.py loads (an extra read-only wave per core 0)."""
+    cmd = ["/opt/rocm/bin/hipcc"] + FLAGS + (["-DVDC_PROFILE"] if observer else []) + SOURCES + ["-o", SO_OBSERVER if observer else SO]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -23,8 +27,8 @@ def build(verbose=False):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return SO
+    return SO_OBSERVER if observer else SO
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, observer="--observer" in sys.argv))
