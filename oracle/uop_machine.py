@@ -30,6 +30,11 @@ machine in the paper's order and vocabulary and shares nothing with the HIP path
   writes nothing, and the load.local behind it on the same flow hands the very same region
   to a compute core again.  The `rope` uop of the example turns pairs of values by the
   angles whose cosines and sines a second tile holds.
+* Section 6.3 ("Memory virtual core overhead"): memory uops measured without any arithmetic
+  behind them.  Three compute uops without arithmetic stand behind the loads and stores
+  of that measurement here: `drop` returns every region it pops as used, `fill` writes one
+  32-bit word all over every output region it pops, `copy` pops a loaded region and an
+  output region and moves the bytes of the first into the second.
 
 Where the paper is silent the readings are those written in the design document:
 16-byte words, the opcode set below, m2c delivery in program order of the `send` uops
@@ -47,7 +52,7 @@ import numpy as np
 
 HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
 LOAD, STORE = 8, 9
-MATVEC, ROPE = 16, 17
+MATVEC, ROPE, DROP, COPY, FILL = 16, 17, 18, 19, 20
 F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
 KIND_FREE, KIND_DATA = 0, 1
 MAX_LOOP_DEPTH = 4
@@ -410,6 +415,37 @@ class Machine:
         self._c2m_push(core, v, KIND_FREE, t[0], t[1])
         self._c2m_push(core, v, KIND_DATA, out[0], out[1])
 
+    def _drop(self, core, v, u):
+        """`size` loaded regions are popped and handed back as used, untouched."""
+        for _ in range(u.size):
+            a = yield
+            self._c2m_push(core, v, KIND_FREE, a[0], a[1])
+
+    def _fill(self, core, v, u):
+        """`size` output regions are popped; the first 16 * chunks bytes of each become copies of one 32-bit word."""
+        value = u.imm & 0xFFFFFFFF
+        nbytes = ((u.imm >> 32) & 0xFFFF) * 16
+        for _ in range(u.size):
+            o = yield
+            reg = core.region(o[0], o[1])
+            if nbytes > reg.size:
+                raise ProgramError("fill: more bytes than the region holds")
+            reg[:nbytes].view(np.uint32)[:] = value
+            self._c2m_push(core, v, KIND_DATA, o[0], o[1])
+
+    def _copy(self, core, v, u):
+        """`size` times: pop a loaded region and an output region, move the first 16 * chunks bytes across."""
+        nbytes = (u.imm & 0xFFFF) * 16
+        for _ in range(u.size):
+            a = yield
+            o = yield
+            src, dst = core.region(a[0], a[1]), core.region(o[0], o[1])
+            if nbytes > src.size or nbytes > dst.size:
+                raise ProgramError("copy: more bytes than a region holds")
+            dst[:nbytes] = src[:nbytes]
+            self._c2m_push(core, v, KIND_FREE, a[0], a[1])
+            self._c2m_push(core, v, KIND_DATA, o[0], o[1])
+
     def _c2m_push(self, core, v, kind, slot, nslots):
         core.c2m[v].append((kind, slot, nslots))
         core.stats["c2m_push"][v] += 1
@@ -425,13 +461,17 @@ class Machine:
                 if commit:
                     s.control(u)
                 return True
-            if u.opcode not in (MATVEC, ROPE):
+            handlers = {MATVEC: self._matvec, ROPE: self._rope, DROP: self._drop, COPY: self._copy, FILL: self._fill}
+            if u.opcode not in handlers:
                 raise ProgramError("opcode %d on a compute core" % u.opcode)
             if commit:
                 self.trace_vcc[core.idx][v].append((s.pc - s.begin, u.opcode, u.size, u.imm))
-                g = self._matvec(core, v, u) if u.opcode == MATVEC else self._rope(core, v, u)
-                next(g)                                    # runs up to the first pop_wait
-                core.vcc_run[v] = g
+                g = handlers[u.opcode](core, v, u)
+                try:
+                    next(g)                                # runs up to the first pop_wait
+                    core.vcc_run[v] = g
+                except StopIteration:                      # a uop over zero regions
+                    s.pc += 1
             return True
         # blocked in pop_wait: enabled when the next ticket has been delivered
         head = core.m2c_head[v]

@@ -34,26 +34,13 @@
 namespace vdc {
 
 // Instrumentation for throw-away profiling builds; the product build compiles none of it.  -DVDC_PROFILE adds an
-// observer wave (see observer_main); -DVDC_PROFILE_BUCKETS also adds per-unit cycle buckets, which slow the units.
+// observer wave (see observer_main).
 #ifdef VDC_PROFILE
 static __device__ __forceinline__ unsigned long long prof_now() {
     unsigned long long t;
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
     return t;
 }
-#endif
-#if defined(VDC_PROFILE) && defined(VDC_PROFILE_BUCKETS)
-#define PROF_DECL(...) unsigned long long __VA_ARGS__
-#define PROF_NOW() prof_now()
-#define PROF_ADD(var, t0) var += PROF_NOW() - (t0)
-#define PROF_INC(var) var++
-#define PROF_OUT(c, wave, k, v) do { if ((c).lane == 0) (c).p->prof[((c).core * 16 + (wave)) * 8 + (k)] = (v); } while (0)
-#else
-#define PROF_DECL(...)
-#define PROF_NOW() 0ull
-#define PROF_ADD(var, t0)
-#define PROF_INC(var)
-#define PROF_OUT(c, wave, k, v)
 #endif
 
 // ------------------------------------------------------------------------------------------------
@@ -566,7 +553,6 @@ DEV void cfu_main(Ctx &c) {
     uint32_t trace_n = 0;
     DecWin d;
     bool ok = cfu_refill(c, d, st, s.pc, s.end);
-    PROF_DECL(pt0 = PROF_NOW(), p_wait = 0, p_n = 0, p_polls = 0, p_ctl = 0, p_poll = 0, p_pre = 0, p_post = 0);
 
     // The innermost loop frame is kept in scalars (top_start, top_left); outer frames wait in lanes 8.. of the
     // register file.  Accumulators are updated by a masked vector add, so that a control uop never moves a value
@@ -1286,7 +1272,6 @@ struct VccState {
     uint32_t red_seq;  // cross-wave reductions done so far
     uint32_t wv;       // which of the two waves of the execution unit this is
     uint32_t t;        // thread index inside the execution unit, 0..127
-    PROF_DECL(p_pop, p_spins, p_n);
 };
 
 struct Msg {
@@ -1318,7 +1303,6 @@ DEV bool msg_ready(uint32_t snap, uint32_t which, uint32_t ticket, Msg &m) {
 // as (0 = used, 1 = produced).  While it waits, the first wave keeps returning finished regions.
 DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, Msg &m1) {
     Spin s;
-    PROF_DECL(q0 = PROF_NOW());
     PHASE(c, 6u + c.unit * 2u + vs.wv, 1u);
     for (;;) {
         const uint32_t snap = vcc_poll(c, vs.head);
@@ -1330,9 +1314,6 @@ DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, 
             compiler_barrier();
             PHASE(c, 6u + c.unit * 2u + vs.wv, 2u);
             OBS(c, 6u + c.unit * 2u + vs.wv, vs.head + n);
-            PROF_ADD(vs.p_pop, q0);
-            PROF_ADD(vs.p_spins, 0ull - s.n + PROF_NOW());
-            PROF_INC(vs.p_n);
             return true;
         }
         if (!spin_step(c, s, rf_get(snap, 5), 0x100u | c.unit)) return false;
@@ -1556,10 +1537,6 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
     c.stream_pc0 = s.pc;
     VccState vs;
     vs.head = 0; vs.group = 0; vs.c2m_pos = 0; vs.pay0 = 0; vs.pay1 = 0; vs.red_seq = 0; vs.wv = wv; vs.t = wv * 64u + c.lane;
-#if defined(VDC_PROFILE) && defined(VDC_PROFILE_BUCKETS)
-    vs.p_pop = vs.p_spins = vs.p_n = 0;
-#endif
-    PROF_DECL(pt0 = PROF_NOW());
     uint32_t trace_n = 0;
     bool ok = true;
     while (ok) {
@@ -1580,7 +1557,6 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         }
         s.pc++;
     }
-    PROF_OUT(c, 6 + c.unit * 2 + wv, 0, PROF_NOW() - pt0); PROF_OUT(c, 6 + c.unit * 2 + wv, 1, vs.p_pop); PROF_OUT(c, 6 + c.unit * 2 + wv, 2, vs.p_n); PROF_OUT(c, 6 + c.unit * 2 + wv, 3, vs.p_spins);
     compiler_barrier();
     if (c.lane == 0)
         __hip_atomic_fetch_add((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(vcc_done)), 1u,

@@ -279,3 +279,48 @@ def test_paper_deployment_constants_are_the_defaults():
     with pytest.raises(AssertionError):
         UM.Machine(np.zeros((1, 4), np.uint32), np.zeros(4, np.uint32), np.zeros((1, 8), np.uint32), [],
                    n_cores=1, n_slots=33)
+
+
+# ---- memory uops with no arithmetic behind them (Section 6.3, "Memory virtual core overhead") -------
+# Closed forms: a copy leaves the destination equal to the source byte for byte and touches nothing past
+# the range; a fill leaves copies of one word; a read leaves memory as it was.  The traces are the blocks
+# of the range in order, which is written out here by hand and not taken from the assembler.
+@pytest.mark.parametrize("nbytes,tile,ncores", [(4096, 1024, 2), (7 * 1024 + 512, 2048, 2), (48, 1024, 1), (64 * 1024 + 16, 4096, 3)])
+def test_copy_program_is_the_identity_on_its_range(nbytes, tile, ncores):
+    rng = np.random.default_rng(nbytes)
+    src = rng.integers(0, 256, nbytes + 64, dtype=np.uint8)
+    for i in range(4):
+        dst = np.full(nbytes + 64, 0xA5, np.uint8)
+        p = A.stream_program("copy", nbytes, tile, 1024, ncores, row_bytes=512)
+        m = _run(p, [src, dst], "program" if i == 0 else "random", seed=i, slot_bytes=1024, n_slots=9)
+        assert np.array_equal(dst[:nbytes], src[:nbytes]) and np.all(dst[nbytes:] == 0xA5)
+        m.check_final()
+
+
+def test_fill_and_read_programs():
+    nbytes, tile = 9 * 1024 + 32, 2048
+    dst = np.full(nbytes + 32, 0x11, np.uint8)
+    p = A.stream_program("fill", nbytes, tile, 1024, 2, value=0xDEADBEEF, row_bytes=1024)
+    m = _run(p, [dst], "random", seed=1, slot_bytes=1024, n_slots=5)
+    assert np.all(dst[:nbytes].view(np.uint32) == 0xDEADBEEF) and np.all(dst[nbytes:] == 0x11)
+    m.check_final()
+    src = np.arange(nbytes, dtype=np.uint8)
+    keep = src.copy()
+    p = A.stream_program("read", nbytes, tile, 1024, 2, row_bytes=1024)
+    m = _run(p, [src], "random", seed=2, slot_bytes=1024, n_slots=5)
+    assert np.array_equal(src, keep)
+    m.check_final()
+    # the loads of all cores together cover the range exactly once, block by block
+    got = sorted((off, rows) for core in m.trace_vmc for (_pc, op, _d, off, rows) in core if op == UM.LOAD)
+    want = [(o, min(tile, nbytes - 32 - o) // 1024) for o in range(0, nbytes - 32, tile)] + [(nbytes - 32, 1)]
+    assert got == want
+    assert sum(u[2] for core in m.trace_vcc for s in core for u in s) == len(want)
+
+
+def test_stream_uops_reject_more_bytes_than_the_region_holds():
+    p = A.Program(1, 1)
+    d = p.desc(0, 1, 64, 64, 64)
+    p.vmc(0).append(A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=4, nslots=1, size=1, imm=0, desc=d))
+    p.vcc(0, 0).append(A.word(A.FILL, size=1, imm=A.fill_imm(1, 2048)))
+    with pytest.raises(UM.ProgramError):
+        _run(p, [np.zeros(64, np.uint8)], slot_bytes=1024, n_slots=4)
