@@ -166,8 +166,27 @@ int vdc_matvec_rope_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t l
 int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                          void *init, int64_t *bytes);
 
-/* Run the SIMT slot allocator of the VMC (Section 4.3: every allocator thread probes from its own position,
- * a wave vote takes the first) on n independent (mask, nslots) requests with a pool of n_slots slots:
+/* Memory uops with nothing to compute behind them (Section 6.3, "Memory virtual core overhead": the cost of the
+ * memory core by I/O block size).  The byte range of `bytes` bytes is cut into blocks of tile_bytes, each moved by
+ * one memory uop (the rest of the range: one shorter block of whole 1 KB rows, then one of a single short row); the
+ * blocks are dealt to the compute cores in contiguous runs, and every compute core runs one uop that only pops and
+ * returns regions.
+ *   mode 0, read : every block of src is loaded into local memory and dropped; memory is left as it was.
+ *   mode 1, fill : every 32-bit word of dst[0, bytes) becomes `value` (filled in local memory, then stored).
+ *   mode 2, copy : dst[0, bytes) = src[0, bytes) (loaded, moved to an output region, stored); the ranges must not overlap.
+ * src, dst: device, 16-byte aligned, caller-owned; the one the mode does not use is ignored.  bytes >= 16 and a
+ * multiple of 16; tile_bytes a power of two, 256 .. 32768, that fits the slots (twice for copy).  Asynchronous on
+ * hip_stream; programs are cached by (mode, bytes, value, tile_bytes).  VDC_EINVAL for anything else. */
+int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64_t bytes, uint32_t value,
+               int32_t tile_bytes, void *hip_stream);
+
+/* The uop program vdc_stream runs (tensors: 0 = src, or dst for fill; 1 = dst for copy), handed out like
+ * vdc_matvec_program does. */
+int vdc_stream_program(vdc_executor *ex, int32_t mode, int64_t bytes, uint32_t value, int32_t tile_bytes, void *uops,
+                       int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs);
+
+/* Run the slot allocator of the VMC (Section 4.3, "Virtual Memory Core": the first run of contiguous free slots in
+ * the availability mask) on n independent (mask, nslots) requests with a pool of n_slots slots:
  * pos[i] = the lowest start of nslots[i] contiguous clear bits of masks[i], or -1.  masks, nslots, pos: device. */
 int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos,
                     int32_t n, void *hip_stream);

@@ -58,6 +58,8 @@ def lib():
             "vdc_matvec_rope": [vp, vp, i64, i64, i64, vp, vp, vp, i32, i32, vp],
             "vdc_matvec_rope_program": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_matvec_workspace": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64)],
+            "vdc_stream": [vp, i32, vp, vp, i64, ctypes.c_uint32, i32, vp],
+            "vdc_stream_program": [vp, i32, i64, ctypes.c_uint32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
         }
         for name, args in sig.items():
@@ -72,7 +74,8 @@ def lib():
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
            "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
-           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_debug_alloc", "vdc_strerror"]
+           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_stream",
+           "vdc_stream_program", "vdc_debug_alloc", "vdc_strerror"]
 
 
 def strerror(code):
@@ -256,6 +259,26 @@ class Executor:
         if n.value:
             _check(lib().vdc_matvec_workspace(self.handle, rows, K, ld, B, tile_bytes, _np_ptr(ws), ctypes.byref(n)), "vdc_matvec_workspace")
         return ws
+
+    STREAM_MODES = {"read": 0, "fill": 1, "copy": 2}
+
+    def stream(self, mode, src, dst, nbytes, tile_bytes, value=0, stream=None):
+        """Memory uops with nothing to compute behind them: mode "read" (src), "fill" (dst, value) or "copy" (src, dst);
+        src, dst: CUDA tensors or None.  Asynchronous."""
+        _check(lib().vdc_stream(self.handle, self.STREAM_MODES[mode], src.data_ptr() if src is not None else None,
+                                dst.data_ptr() if dst is not None else None, nbytes, value, tile_bytes, _stream_ptr(stream)), "vdc_stream")
+
+    def stream_program(self, mode, nbytes, tile_bytes, value=0):
+        """The uop graph stream() would run."""
+        n_w, n_d = ctypes.c_int64(0), ctypes.c_int32(0)
+        f, m = lib().vdc_stream_program, self.STREAM_MODES[mode]
+        _check(f(self.handle, m, nbytes, value, tile_bytes, None, ctypes.byref(n_w), None, None, ctypes.byref(n_d)), "vdc_stream_program (sizing)")
+        words = np.zeros((n_w.value, 4), dtype=np.uint32)
+        descs = np.zeros((n_d.value, 8), dtype=np.uint32)
+        sb = np.zeros(self.n_streams + 1, dtype=np.uint32)
+        _check(f(self.handle, m, nbytes, value, tile_bytes, _np_ptr(words), ctypes.byref(n_w), _np_ptr(sb), _np_ptr(descs), ctypes.byref(n_d)),
+               "vdc_stream_program")
+        return words, sb, descs
 
     def debug_alloc(self, masks, nslots, n_slots, stream=None):
         """masks (int32/uint32 CUDA tensor), nslots (int32 CUDA tensor) -> positions (int32 CUDA tensor)."""

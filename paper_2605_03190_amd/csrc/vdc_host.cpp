@@ -54,6 +54,8 @@ struct vdc_executor {
 #endif
     std::vector<vdc_program *> programs;
     std::vector<std::pair<MatvecKey, vdc_program *>> matvec_cache;
+    struct StreamKey { int32_t mode; int64_t bytes; uint32_t value; int32_t tile_bytes; };
+    std::vector<std::pair<StreamKey, vdc_program *>> stream_cache;
 };
 
 namespace {
@@ -93,7 +95,9 @@ struct VccH {
     // running MATVEC
     bool in_uop = false;
     uint32_t left = 0, B = 0, R = 0, lpr = 0;
-    int phase = 0;                // MATVEC: 0 expect a, 1 expect b, 2 expect out; ROPE: 10 expect values, 11 expect angles, 12 expect out
+    int phase = 0;                // MATVEC: 0 expect a, 1 expect b, 2 expect out; ROPE: 10 expect values, 11 expect angles, 12 expect out;
+                                  // DROP: 20; FILL: 21; COPY: 22 expect in, 23 expect out
+    uint32_t chunks = 0;
     SentMsg a{}, b{};
 };
 
@@ -279,6 +283,15 @@ struct Validator {
                 v.in_uop = true;
                 return 1;
             }
+            if (f.opcode == OP_DROP || f.opcode == OP_COPY || f.opcode == OP_FILL) {
+                if (f.size < 1) { fail("stream uop over zero regions"); return -1; }
+                v.chunks = f.opcode == OP_COPY ? (uint32_t)f.imm & 0xFFFFu : f.opcode == OP_FILL ? (uint32_t)(f.imm >> 32) & 0xFFFFu : 0u;
+                if (f.opcode != OP_DROP && (v.chunks < 1 || v.chunks > kMaxStreamChunks)) { fail("stream uop: bad byte count"); return -1; }
+                v.left = f.size;
+                v.phase = f.opcode == OP_DROP ? 20 : f.opcode == OP_FILL ? 21 : 22;
+                v.in_uop = true;
+                return 1;
+            }
             if (f.opcode != OP_MATVEC) { fail("opcode not valid on a compute core"); return -1; }
             v.B = (uint32_t)f.imm & 0xFFu;
             v.R = (uint32_t)(f.imm >> 8) & 0xFFFFu;
@@ -294,6 +307,23 @@ struct Validator {
         if (v.m2c.empty()) return 0;
         SentMsg m = v.m2c.front();
         v.m2c.pop_front();
+        if (v.phase >= 20) {
+            const uint64_t need = (uint64_t)v.chunks * 16, have = (uint64_t)m.nslots * cfg.slot_bytes;
+            if (v.phase == 20 || v.phase == 22) {
+                if (m.is_store) { fail("stream uop: expected a loaded region"); return -1; }
+                if (need > have) { fail("copy: more bytes than the loaded region holds"); return -1; }
+                if (v.phase == 20) release(c, m); else v.a = m;
+            } else {
+                if (!m.is_store) { fail("stream uop: expected an output region"); return -1; }
+                if (need > have) { fail("stream uop: more bytes than the output region holds"); return -1; }
+                if (v.phase == 23) release(c, v.a);
+                if (!store_returns(c, m)) return -1;
+            }
+            if (v.phase == 22) { v.phase = 23; return 1; }
+            if (v.phase == 23) v.phase = 22;
+            if (--v.left == 0) { v.in_uop = false; v.s.pc++; }
+            return 1;
+        }
         if (v.phase >= 10) {
             if (v.phase < 12) {
                 if (m.is_store || m.rows != v.B || m.box_rows != v.B || m.lds_pitch != v.R * 4) { fail("rope: input tile does not match the uop"); return -1; }
@@ -753,6 +783,88 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
     return VDC_OK;
 }
 
+// Memory uops with no arithmetic behind them (Section 6.3, "Memory virtual core overhead"): the byte range
+// [0, bytes) in blocks of tile_bytes.  mode 0: every block is loaded (tensor 0) and dropped; mode 1: every block of
+// tensor 0 is written with copies of `value`; mode 2: every block is loaded from tensor 0, moved to an output region and
+// stored to the same place in tensor 1.  Compute core (c, v) takes a contiguous run of blocks; the memory core's
+// stream walks the runs of its compute cores side by side, two blocks of each per loop trip, with one accumulator
+// as the running offset (Section 5, "Dynamic address generation").  What is left of the range after the last whole block
+// goes to the last compute core: whole rows of it as one short block, the rest as a block of one short row.
+int build_stream(const vdc_config &cfg, int32_t mode, int64_t bytes, uint32_t value, int32_t tile_bytes, std::vector<Word> &words,
+                 std::vector<uint32_t> &sb, std::vector<Desc> &descs) {
+    if (mode < 0 || mode > 2 || bytes < 16 || (bytes & 15) || !is_pow2(tile_bytes) || tile_bytes < 256 ||
+        (uint32_t)tile_bytes > kMaxStreamChunks * 16u) return VDC_EINVAL;
+    const int C = cfg.n_cores, V = cfg.vcc_per_core;
+    Tiler t{cfg, 0, 0, 0, 1, 1, 4};
+    t.streams.resize((size_t)C * (1 + V));
+    const uint32_t row_bytes = (uint32_t)std::min(tile_bytes, 1024), box_rows = (uint32_t)tile_bytes / row_bytes;
+    const uint32_t nslots = t.slots_for((uint64_t)tile_bytes);
+    if ((int64_t)nslots * (mode == 2 ? 2 : 1) > cfg.n_slots) return VDC_EINVAL;
+    const uint32_t d_in = mode != 1 ? t.desc(0, box_rows, row_bytes, row_bytes, row_bytes) : 0;
+    const uint32_t d_out = mode != 0 ? t.desc(mode == 1 ? 0 : 1, box_rows, row_bytes, row_bytes, row_bytes) : 0;
+    auto emit_block = [&](std::vector<Word> &vm, int v, int j, bool dyn, int64_t off, uint32_t din, uint32_t dout, uint32_t ns, uint32_t rows) {
+        const uint32_t fd = dyn ? F_DYNAMIC : 0;
+        if (mode != 1) vm.push_back(encode(OP_LOAD, F_SEND | F_NT | fd, (j & 1) ? t.flow_x(v) : t.flow_m(v), v, 0, ns, rows, 0, off, din, 0));
+        if (mode != 0) vm.push_back(encode(OP_STORE, F_SEND | F_RECV | fd, t.flow_y(v), v, 0, ns, rows, 0, off, dout, 0));
+    };
+    auto emit_uop = [&](std::vector<Word> &vc, int64_t n, uint32_t chunks) {
+        for (; n > 0; n -= 65535) {
+            const uint32_t k = (uint32_t)std::min<int64_t>(n, 65535);
+            vc.push_back(mode == 0 ? encode(OP_DROP, 0, 0, 0, 0, 0, k, 0, 0, 0, 0)
+                         : mode == 1 ? encode(OP_FILL, 0, 0, 0, 0, 0, k, 0, fill_imm(value, chunks), 0, 0)
+                                     : encode(OP_COPY, 0, 0, 0, 0, 0, k, 0, copy_imm(chunks), 0, 0));
+        }
+    };
+    const int64_t NBk = bytes / tile_bytes, U = (int64_t)C * V;
+    for (int c = 0; c < C; c++) {
+        std::vector<Word> &vm = t.vmc(c);
+        int64_t n[2] = {0, 0}, s0[2] = {0, 0};
+        for (int v = 0; v < V; v++) {
+            const int64_t u = (int64_t)c * V + v;
+            n[v] = NBk / U + (u < NBk % U ? 1 : 0);
+            s0[v] = u * (NBk / U) + std::min(u, NBk % U);
+        }
+        const int64_t common = V == 2 ? std::min(n[0], n[1]) : n[0];
+        const int64_t trips = common / 2;
+        if (trips > 0xFFFFFFFFll) return VDC_EINVAL;
+        if (trips > 0) {
+            vm.push_back(encode(OP_SET, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
+            vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, trips, 0, 0));
+            for (int j = 0; j < 2; j++)
+                for (int v = 0; v < V; v++) emit_block(vm, v, j, true, (s0[v] + j) * tile_bytes, d_in, d_out, nslots, box_rows);
+            vm.push_back(encode(OP_REPEAT, 0, 0, 0, 0, 0, 0, 0, 2ll * tile_bytes, 0, 0));
+        }
+        for (int64_t i = 2 * trips; i < std::max(n[0], n[1]); i++)
+            for (int v = 0; v < V; v++)
+                if (i < n[v]) emit_block(vm, v, (int)(i & 1), false, (s0[v] + i) * tile_bytes, d_in, d_out, nslots, box_rows);
+        for (int v = 0; v < V; v++) emit_uop(t.vcc(c, v), n[v], (uint32_t)tile_bytes / 16u);
+    }
+    // the rest of the range
+    int64_t off = NBk * tile_bytes;
+    const int64_t rest_rows = (bytes - off) / row_bytes;
+    std::vector<Word> &vm = t.vmc(C - 1);
+    if (rest_rows > 0) {
+        emit_block(vm, V - 1, 0, false, off, d_in, d_out, nslots, (uint32_t)rest_rows);
+        emit_uop(t.vcc(C - 1, V - 1), 1, (uint32_t)(rest_rows * row_bytes / 16));
+        off += rest_rows * row_bytes;
+    }
+    if (off < bytes) {
+        const uint32_t rb = (uint32_t)(bytes - off);
+        const uint32_t di = mode != 1 ? t.desc(0, 1, rb, rb, rb) : 0, dout = mode != 0 ? t.desc(mode == 1 ? 0 : 1, 1, rb, rb, rb) : 0;
+        emit_block(vm, V - 1, 1, false, off, di, dout, t.slots_for(rb), 1);
+        emit_uop(t.vcc(C - 1, V - 1), 1, rb / 16u);
+    }
+    words.clear();
+    sb.assign(1, 0);
+    for (auto &st : t.streams) {
+        words.insert(words.end(), st.begin(), st.end());
+        words.push_back(encode(OP_HALT, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
+        sb.push_back((uint32_t)words.size());
+    }
+    descs = t.descs;
+    return VDC_OK;
+}
+
 int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     for (int i = 0; i < 5; i++)
         if (c.reserved[i]) return VDC_EINVAL;
@@ -947,6 +1059,8 @@ int vdc_program_destroy(vdc_program *prog) {
     ex->programs.erase(std::remove(ex->programs.begin(), ex->programs.end(), prog), ex->programs.end());
     for (auto it = ex->matvec_cache.begin(); it != ex->matvec_cache.end();)
         it = (it->second == prog) ? ex->matvec_cache.erase(it) : it + 1;
+    for (auto it = ex->stream_cache.begin(); it != ex->stream_cache.end();)
+        it = (it->second == prog) ? ex->stream_cache.erase(it) : it + 1;
     (void)hipFree(prog->d_words);
     (void)hipFree(prog->d_stream_begin);
     (void)hipFree(prog->d_descs);
@@ -1100,6 +1214,49 @@ int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, 
         memcpy(init, ws.data(), ws.size() * 4);
     }
     return VDC_OK;
+}
+
+int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64_t bytes, uint32_t value, int32_t tile_bytes,
+               void *hip_stream) {
+    if (!ex || ex->cfg.device == -1 || mode < 0 || mode > 2) return VDC_EINVAL;
+    if ((mode != 1 && (!src || ((uintptr_t)src & 15u))) || (mode != 0 && (!dst || ((uintptr_t)dst & 15u)))) return VDC_EINVAL;
+    if (mode != 1) value = 0;
+    vdc_program *prog = nullptr;
+    for (auto &kv : ex->stream_cache)
+        if (kv.first.mode == mode && kv.first.bytes == bytes && kv.first.value == value && kv.first.tile_bytes == tile_bytes) { prog = kv.second; break; }
+    if (!prog) {
+        std::vector<Word> words;
+        std::vector<uint32_t> sb;
+        std::vector<Desc> descs;
+        int rc = build_stream(ex->cfg, mode, bytes, value, tile_bytes, words, sb, descs);
+        if (rc != VDC_OK) return rc;
+        int64_t tb[2] = {bytes, bytes};
+        rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb,
+                                mode == 2 ? 2 : 1, &prog);
+        if (rc != VDC_OK) return rc;
+        ex->stream_cache.push_back({{mode, bytes, value, tile_bytes}, prog});
+    }
+    void *bases[2] = {mode == 1 ? dst : (void *)src, dst};
+    return vdc_run(ex, prog, bases, mode == 2 ? 2 : 1, hip_stream);
+}
+
+int vdc_stream_program(vdc_executor *ex, int32_t mode, int64_t bytes, uint32_t value, int32_t tile_bytes, void *uops, int64_t *n_uops,
+                       uint32_t *stream_begin, void *descs, int32_t *n_descs) {
+    if (!ex || !n_uops || !n_descs) return VDC_EINVAL;
+    std::vector<Word> words;
+    std::vector<uint32_t> sb;
+    std::vector<Desc> ds;
+    int rc = build_stream(ex->cfg, mode, bytes, mode == 1 ? value : 0, tile_bytes, words, sb, ds);
+    if (rc != VDC_OK) return rc;
+    const int64_t cap_w = *n_uops;
+    const int32_t cap_d = *n_descs;
+    *n_uops = (int64_t)words.size();
+    *n_descs = (int32_t)ds.size();
+    bool fits = true;
+    if (uops) { if (cap_w >= (int64_t)words.size()) memcpy(uops, words.data(), words.size() * sizeof(Word)); else fits = false; }
+    if (descs) { if (cap_d >= (int32_t)ds.size()) memcpy(descs, ds.data(), ds.size() * sizeof(Desc)); else fits = false; }
+    if (stream_begin) memcpy(stream_begin, sb.data(), sb.size() * sizeof(uint32_t));
+    return fits ? VDC_OK : VDC_EINVAL;
 }
 
 int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n,

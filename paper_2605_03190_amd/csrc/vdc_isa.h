@@ -26,7 +26,11 @@ enum Opcode : uint32_t {
     OP_LOAD = 8,    // VMC: global -> local-memory region
     OP_STORE = 9,   // VMC: local-memory region -> global
     OP_MATVEC = 16, // VCC: the matvec compute uop of the listing in Section 4.1
-    OP_ROPE = 17    // VCC: the rope uop of the running example (Section 3): turn pairs of values by given angles
+    OP_ROPE = 17,   // VCC: the rope uop of the running example (Section 3): turn pairs of values by given angles
+    // compute uops without arithmetic, for measuring memory uops alone (Section 6.3, "Memory virtual core overhead")
+    OP_DROP = 18,   // VCC: pop `size` loaded regions, hand each back as used
+    OP_COPY = 19,   // VCC: `size` times: pop a loaded region and an output region, move bytes across, hand both back
+    OP_FILL = 20    // VCC: pop `size` output regions, write one 32-bit word all over each, hand it back as produced
 };
 
 enum Flag : uint32_t {
@@ -104,6 +108,12 @@ inline int64_t matvec_imm(uint32_t B, uint32_t R, uint32_t lpr) {
 // fp32 with a row pitch of R * 4 bytes; R even, B * R <= 1024
 inline int64_t rope_imm(uint32_t B, uint32_t R) { return (int64_t)B | ((int64_t)R << 8); }
 inline bool rope_geometry_ok(uint32_t B, uint32_t R) { return B >= 1 && B <= 8 && R >= 2 && (R & 1u) == 0 && B * R <= 1024; }
+
+// COPY imm: chunks [15:0]; FILL imm: value [31:0], chunks [47:32]; a chunk is 16 bytes, counted from the start of the
+// region.  1 <= chunks, and the bytes must fit the region (checked against the allocation when the program is created).
+inline int64_t copy_imm(uint32_t chunks) { return (int64_t)chunks; }
+inline int64_t fill_imm(uint32_t value, uint32_t chunks) { return (int64_t)value | ((int64_t)chunks << 32); }
+constexpr uint32_t kMaxStreamChunks = 2048;   // 32 KB: sixteen passes of the 128 threads of an execution unit
 
 // The compute uop works on `threads_per_eu` = 128 threads; a matrix tile is NF passes of 128 chunks of
 // 16 bytes.  Supported geometries (anything else is rejected when the program is created):

@@ -7,11 +7,12 @@
 // wave64 wavefronts of one workgroup as follows:
 //
 //   wave 0                      CFU   fetch / decode / control uops / address generation / slot allocation /
-//                                     dispatch by virtual flow / receiver of the c2m queues
+//                                     dispatch by virtual flow
 //   waves 1 .. n_ldu (<= 4)     LDU   direct-to-LDS 128-bit loads (global_load_lds_dwordx4), several tiles in
 //                                     flight per unit, completion observed with s_waitcnt vmcnt(N), then the
 //                                     region is delivered into its m2c ticket
-//   next n_stu waves            STU   waits for the produced region, LDS -> global, frees the slots, signals depId
+//   next n_stu waves            STU   receiver of the c2m queues; waits for the produced region, LDS -> global,
+//                                     frees the slots, signals depId; store.local / load.local
 //   next 2 * V waves            VCC   v = 0..V-1, two waves (128 threads) each: the compute uop handlers
 //
 // All queues live in LDS.  A waiter polls LDS with s_sleep back-off (no hardware de-scheduling exists);
@@ -23,7 +24,10 @@
 //     with ONE gathered LDS read, each lane fetching a different word, and one wait;
 //   * uop words are fetched 64 at a time into a register window (one lane per word) and picked with v_readlane;
 //     descriptors live in a register file of the same kind; no indexed state lives in memory;
-//   * the slot allocator is a wave vote (ballot + count-trailing-zeros).
+//   * the slot mask is one scalar register in the front end: "first run of n free slots" is n - 1 shift-and-and
+//     steps and a count-trailing-zeros, and a batch of up to four memory uops is allocated in one straight-line pass;
+//   * nothing on the hot paths branches per lane: stores by single lanes are exec-masked LDS instructions, and a
+//     compute core that is done with a used region clears its bits in the slot mask itself, with one LDS atomic.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -1218,15 +1222,40 @@ DEV void stu_main(Ctx &c) {
                 const uint32_t rows = rf_get(stat, 2) & 0xFFFFu, rb_pitch = rf_get(stat, 3);
                 const uint32_t row_words = (rb_pitch & 0xFFFFu) >> 2, lds_pitch = rb_pitch >> 16;
                 const uint32_t lds_off = slot << slot_shift;
-                const uint32_t total = rows * row_words;
                 compiler_barrier();
-                for (uint32_t i = c.lane; i < total; i += 64u) {
-                    uint32_t rr = i / row_words, cc = i % row_words;
-                    float v = lds_ldf(lds_off + rr * lds_pitch + cc * 4u);
-                    *(float *)(uintptr_t)(gaddr + (uint64_t)rr * gpitch + (uint64_t)cc * 4u) = v;
+                if (((r_glo | (uint32_t)gpitch | rb_pitch | (rb_pitch >> 16)) & 15u) == 0u) {
+                    // whole 16-byte chunks: lane l takes chunks l, l + 64, ... of the box, four at a time
+                    const uint32_t cpr = (rb_pitch & 0xFFFFu) >> 4, total = rows * cpr;
+                    const uint32_t dr = 64u / cpr, dc = 64u % cpr;
+                    uint32_t rr = c.lane / cpr, cc = c.lane % cpr;
+                    for (uint32_t i0 = 0; i0 < total; i0 += 256u) {
+                        f32x4 v[4];
+                        uint64_t ga[4];
+                        bool on[4];
+#pragma unroll
+                        for (int q = 0; q < 4; q++) {
+                            on[q] = i0 + (uint32_t)q * 64u + c.lane < total;
+                            ga[q] = gaddr + (uint64_t)rr * gpitch + (uint64_t)cc * 16u;
+                            v[q] = lds_ld128(on[q] ? lds_off + rr * lds_pitch + cc * 16u : lds_off);
+                            cc += dc; rr += dr;
+                            if (cc >= cpr) { cc -= cpr; rr++; }
+                        }
+#pragma unroll
+                        for (int q = 0; q < 4; q++)
+                            if (on[q]) *(f32x4 *)(uintptr_t)ga[q] = v[q];
+                    }
+                } else {
+                    const uint32_t total = rows * row_words;
+                    for (uint32_t i = c.lane; i < total; i += 64u) {
+                        uint32_t rr = i / row_words, cc = i % row_words;
+                        float v = lds_ldf(lds_off + rr * lds_pitch + cc * 4u);
+                        *(float *)(uintptr_t)(gaddr + (uint64_t)rr * gpitch + (uint64_t)cc * 4u) = v;
+                    }
                 }
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                // the data is in registers on its way out: the region is free as soon as the reads have returned
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 slots_free(c, slot, nslots);
+                if (flags & F_DEP_SEND) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 if (flags & F_DEP_SEND) {
                     __threadfence();
                     dep_signal(c, dep);
@@ -1526,6 +1555,63 @@ DEV bool rope_uop(Ctx &c, VccState &vs, uint32_t B, uint32_t R) {
     return true;
 }
 
+// Compute uops without arithmetic, which leave the memory uops around them as the only work (Section 6.3, "Memory
+// virtual core overhead").  A region is at most kStreamPasses * 128 chunks of 16 bytes: thread t moves chunks
+// t, t + 128, ...
+constexpr uint32_t kStreamPasses = 16;
+
+DEV bool drop_uop(Ctx &c, VccState &vs, uint32_t size) {
+    // one region at a time, as the uop is defined: popping two at once would need both resident, which a small pool
+    // of slots may not allow
+    Msg m, unused;
+    for (; size != 0u; size--) {
+        if (!vcc_pop_wait(c, vs, 1u, 0u, m, unused)) return false;
+        vcc_done_with(c, vs, 1u, 0u);
+    }
+    return true;
+}
+
+DEV bool fill_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t value, uint32_t chunks) {
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
+    const u32x4 v = u32x4{value, value, value, value};
+    Msg mo, unused;
+    for (; size != 0u; size--) {
+        if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
+        const uint32_t off = mo.slot << slot_shift;
+        for (uint32_t ch = vs.t; ch < chunks; ch += 128u) lds_st128(off + ch * 16u, v);
+        lds_wait();
+        vcc_done_with(c, vs, 1u, 1u);
+    }
+    return true;
+}
+
+DEV bool copy_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t chunks) {
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
+    Msg mi, mo, unused;
+    for (; size != 0u; size--) {
+        if (!vcc_pop_wait(c, vs, 1u, 0u, mi, unused)) return false;
+        const uint32_t in_off = mi.slot << slot_shift;
+        f32x4 r[kStreamPasses];
+#pragma unroll
+        for (uint32_t q = 0; q < kStreamPasses; q++) {
+            const uint32_t ch = vs.t + q * 128u;
+            r[q] = lds_ld128(ch < chunks ? in_off + ch * 16u : in_off);
+        }
+        lds_wait();
+        vcc_done_with(c, vs, 1u, 0u);
+        if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
+        const uint32_t out_off = mo.slot << slot_shift;
+#pragma unroll
+        for (uint32_t q = 0; q < kStreamPasses; q++) {
+            const uint32_t ch = vs.t + q * 128u;
+            if (ch < chunks) *(__attribute__((address_space(3))) f32x4 *)(lds0() + out_off + ch * 16u) = r[q];
+        }
+        lds_wait();
+        vcc_done_with(c, vs, 1u, 1u);
+    }
+    return true;
+}
+
 // The control-flow unit of a VCC runs on the execution unit's own threads (Section 4.3, "Virtual Compute Core"):
 // each of its two waves decodes the stream, runs control uops itself and then yields to the uop handler.
 DEV void vcc_main(Ctx &c, uint32_t wv) {
@@ -1551,6 +1637,12 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
             ok = matvec_dispatch(c, vs, f);
         } else if (f.opcode == OP_ROPE) {
             ok = rope_uop(c, vs, (uint32_t)f.imm & 0xFFu, (uint32_t)(f.imm >> 8) & 0xFFFFu);
+        } else if (f.opcode == OP_DROP) {
+            ok = drop_uop(c, vs, f.size);
+        } else if (f.opcode == OP_FILL) {
+            ok = fill_uop(c, vs, f.size, (uint32_t)f.imm, (uint32_t)(f.imm >> 32) & 0xFFFFu);
+        } else if (f.opcode == OP_COPY) {
+            ok = copy_uop(c, vs, f.size, (uint32_t)f.imm & 0xFFFFu);
         } else {
             raise_error(c, -3 /* VDC_EPROGRAM */, 0xE00u | f.opcode);
             ok = false;

@@ -249,6 +249,84 @@ def test_fused_program_assembled_by_the_oracle_side_runs_on_the_gpu():
         prog.destroy()
 
 
+STREAM_CASES = [
+    # mode, bytes, tile_bytes
+    ("copy", 64 << 20, 16384),
+    ("copy", (5 << 20) + 7 * 1024 + 48, 8192),     # uneven runs, a short block and a short row
+    ("copy", 3 * 4096, 4096),                      # fewer blocks than compute cores
+    ("copy", 48, 2048),                            # less than one row
+    ("copy", (1 << 20) + 256, 256),                # tiles below a row of 1 KB
+    ("fill", (9 << 20) + 1024 + 16, 16384),
+    ("fill", 1 << 20, 4096),
+    ("read", (33 << 20) + 2048 - 16, 16384),
+]
+
+
+@pytest.mark.parametrize("mode,nbytes,T", STREAM_CASES)
+def test_memory_uops_alone_move_every_byte_exactly(ex, mode, nbytes, T):
+    """Byte work: bit-exact.  The expected image is the closed form (copy: the source; fill: the word; read: nothing
+    changes), and bytes past the range stay as they were."""
+    g = torch.Generator(device="cuda").manual_seed(nbytes)
+    src = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, device="cuda", generator=g)
+    keep = src.clone()
+    dst = torch.full((nbytes + 64,), 0xEE, dtype=torch.uint8, device="cuda")
+    for _ in range(2):                       # the second run takes the cached program
+        ex.stream(mode, src if mode != "fill" else None, dst if mode != "read" else None, nbytes, T, value=0xC0FFEE11)
+        ex.check()
+    assert torch.equal(src, keep)
+    if mode == "copy":
+        assert torch.equal(dst[:nbytes], src[:nbytes])
+    if mode == "fill":
+        assert bool((dst[:nbytes].view(torch.int32) == np.int32(np.uint32(0xC0FFEE11).view(np.int32))).all())
+    if mode == "read":
+        assert bool((dst == 0xEE).all())
+    assert bool((dst[nbytes:] == 0xEE).all())
+
+
+def test_stream_traces_match_the_interpreter_and_oracle_assembled_streams_run():
+    """The per-unit traces of a copy are bit-exact against the interpreter running the same uops; then stream programs
+    that the oracle-side assembler built (no product tiler) run on the GPU."""
+    nbytes, T = 300 * 1024 + 512 + 32, 4096
+    rng = np.random.default_rng(11)
+    src = rng.integers(0, 256, nbytes, dtype=np.uint8)
+    with vdc.Executor(n_cores=8, slot_bytes=2048, n_slots=12) as ex:
+        words, sb, descs = ex.stream_program("copy", nbytes, T)
+        prog = ex.program_create(words, sb, descs, [nbytes, nbytes])
+        dsrc, ddst = _dev(src), torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        trace, count = ex.run(prog, [dsrc, ddst], trace_cap=1024)
+        ex.check()
+        assert np.array_equal(ddst.cpu().numpy(), src)
+        out = np.zeros(nbytes, np.uint8)
+        m = UM.Machine(words, sb, descs, [src, out], n_cores=8, slot_bytes=2048, n_slots=12).run()
+        assert np.array_equal(out, src)
+        trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+        for core in range(8):
+            exp = [(pc, op | (d << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, d, off, n) in m.trace_vmc[core]]
+            assert count[core * 3] == len(exp)
+            assert [tuple(int(x) for x in r) for r in trace[core * 3, :len(exp)]] == exp
+            for v in range(2):
+                exp = [(pc, op | (n << 16), imm & 0xFFFFFFFF, imm >> 32) for (pc, op, n, imm) in m.trace_vcc[core][v]]
+                assert count[core * 3 + 1 + v] == len(exp)
+                assert [tuple(int(x) for x in r) for r in trace[core * 3 + 1 + v, :len(exp)]] == exp
+        prog.destroy()
+        for mode in ("copy", "fill", "read"):
+            p = A.stream_program(mode, nbytes, T, 2048, 8, value=0x0BADF00D, row_bytes=512)
+            words, sb, descs = p.finish()
+            prog = ex.program_create(words, sb, descs, [nbytes, nbytes] if mode == "copy" else [nbytes])
+            ddst = torch.full((nbytes,), 0x77, dtype=torch.uint8, device="cuda")
+            ex.run(prog, {"copy": [dsrc, ddst], "fill": [ddst], "read": [dsrc]}[mode])
+            ex.check()
+            got = ddst.cpu().numpy()
+            if mode == "copy":
+                assert np.array_equal(got, src)
+            elif mode == "fill":
+                assert np.all(got.view(np.uint32) == 0x0BADF00D)
+            else:
+                assert np.all(got == 0x77)
+            assert np.array_equal(dsrc.cpu().numpy(), src)
+            prog.destroy()
+
+
 def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):
     """vdc_run enqueues kernels only (counters are cleared by a fill kernel, never by a memset node), so a caller may
     capture it; every replay, with eager work and synchronisations in between, must equal the eager result."""

@@ -196,3 +196,56 @@ def test_device_entry_points_refuse_a_host_only_executor():
         with pytest.raises(vdc.VdcError) as e:
             ex.program_create(w, sb, d, [64 * 64 * 4, 256, 256])
         assert e.value.code == vdc.VDC_EINVAL
+
+
+# ---- memory uops with nothing to compute behind them (Section 6.3, "Memory virtual core overhead") ----
+@pytest.mark.parametrize("mode,nbytes,T,ncores,slot,nslots", [
+    ("copy", 64 * 1024, 4096, 2, 4096, 8),                 # whole blocks, looped
+    ("copy", 37 * 4096 + 3 * 1024 + 48, 4096, 3, 4096, 6),  # uneven runs, a short block and a short row
+    ("copy", 48, 1024, 2, 1024, 4),                        # less than one row
+    ("copy", 5 * 256, 256, 1, 1024, 4),                    # tiles below a row of 1 KB
+    ("fill", 21 * 8192 + 1024 + 16, 8192, 2, 8192, 5),
+    ("read", 33 * 2048 + 2048 - 16, 2048, 2, 2048, 4),
+])
+def test_stream_program_on_the_oracle_interpreter(mode, nbytes, T, ncores, slot, nslots):
+    rng = np.random.default_rng(nbytes)
+    src = rng.integers(0, 256, nbytes + 32, dtype=np.uint8)
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
+        w, sb, d = ex.stream_program(mode, nbytes, T, value=0x01020304)
+        rc, msg = ex.program_validate(w, sb, d, [nbytes, nbytes] if mode == "copy" else [nbytes])
+        assert rc == vdc.VDC_OK, msg
+    ops = w[:, 0] & 0xFF
+    assert (ops == {"read": A.DROP, "fill": A.FILL, "copy": A.COPY}[mode]).any()
+    for sched, seed in (("program", 0), ("random", 1)):
+        dst = np.full(nbytes + 32, 0xEE, np.uint8)
+        keep = src.copy()
+        tensors = {"read": [src], "fill": [dst], "copy": [src, dst]}[mode]
+        m = UM.Machine(w, sb, d, tensors, n_cores=ncores, slot_bytes=slot, n_slots=nslots)
+        m.run(sched, seed)
+        m.check_final()
+        assert np.array_equal(src, keep)
+        if mode == "copy":
+            assert np.array_equal(dst[:nbytes], src[:nbytes])
+        if mode == "fill":
+            assert np.all(dst[:nbytes].view(np.uint32) == 0x01020304)
+        assert np.all(dst[nbytes:] == 0xEE)
+        # every byte of the range is moved exactly once
+        for op in ([A.LOAD] if mode != "fill" else []) + ([A.STORE] if mode != "read" else []):
+            seen = np.zeros(nbytes, np.uint8)
+            for core in m.trace_vmc:
+                for (_pc, o, di, off, rows) in core:
+                    if o == op:
+                        seen[off:off + rows * int(d[di][2])] += 1
+            assert np.all(seen == 1)
+
+
+def test_stream_program_rejects_bad_arguments():
+    with vdc.Executor(device=-1, n_cores=2, slot_bytes=4096, n_slots=4) as ex:
+        for bad in (dict(nbytes=0), dict(nbytes=40), dict(T=3000), dict(T=128), dict(T=65536)):
+            a = dict(nbytes=4096, T=4096)
+            a.update(bad)
+            with pytest.raises(vdc.VdcError):
+                ex.stream_program("copy", a["nbytes"], a["T"])
+        with pytest.raises(vdc.VdcError):
+            ex.stream_program("copy", 1 << 20, 16384)      # an input and an output region of 16 KB need eight slots
+        ex.stream_program("read", 1 << 20, 16384)
