@@ -180,6 +180,12 @@ int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, 
 int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64_t bytes, uint32_t value,
                int32_t tile_bytes, void *hip_stream);
 
+/* What Section 6.3 measures the memory uops against: the same bytes moved by plain 128-bit load and store
+ * instructions of an ordinary grid-stride kernel (no virtual cores, no local memory).  Modes, pointers, bytes and
+ * value as for vdc_stream; a read folds what it loads into a word nobody looks at.  Asynchronous on hip_stream. */
+int vdc_raw_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64_t bytes, uint32_t value,
+                   void *hip_stream);
+
 /* The uop program vdc_stream runs (tensors: 0 = src, or dst for fill; 1 = dst for copy), handed out like
  * vdc_matvec_program does. */
 int vdc_stream_program(vdc_executor *ex, int32_t mode, int64_t bytes, uint32_t value, int32_t tile_bytes, void *uops,

@@ -59,6 +59,7 @@ def lib():
             "vdc_matvec_rope_program": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_matvec_workspace": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64)],
             "vdc_stream": [vp, i32, vp, vp, i64, ctypes.c_uint32, i32, vp],
+            "vdc_raw_stream": [vp, i32, vp, vp, i64, ctypes.c_uint32, vp],
             "vdc_stream_program": [vp, i32, i64, ctypes.c_uint32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
         }
@@ -74,7 +75,7 @@ def lib():
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
            "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
-           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_stream",
+           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_stream", "vdc_raw_stream",
            "vdc_stream_program", "vdc_debug_alloc", "vdc_strerror"]
 
 
@@ -267,6 +268,11 @@ class Executor:
         src, dst: CUDA tensors or None.  Asynchronous."""
         _check(lib().vdc_stream(self.handle, self.STREAM_MODES[mode], src.data_ptr() if src is not None else None,
                                 dst.data_ptr() if dst is not None else None, nbytes, value, tile_bytes, _stream_ptr(stream)), "vdc_stream")
+
+    def raw_stream(self, mode, src, dst, nbytes, value=0, stream=None):
+        """The same bytes as stream(), moved by an ordinary grid-stride kernel: what stream() is measured against."""
+        _check(lib().vdc_raw_stream(self.handle, self.STREAM_MODES[mode], src.data_ptr() if src is not None else None,
+                                    dst.data_ptr() if dst is not None else None, nbytes, value, _stream_ptr(stream)), "vdc_raw_stream")
 
     def stream_program(self, mode, nbytes, tile_bytes, value=0):
         """The uop graph stream() would run."""

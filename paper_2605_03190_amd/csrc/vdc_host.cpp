@@ -963,10 +963,10 @@ int vdc_create(vdc_executor **out, const vdc_config *cfg_in) {
     ex->cu_count = prop.multiProcessorCount;
     ex->lds_limit = (size_t)lds_max;
     if (hipMalloc(&ex->d_dep, sizeof(uint32_t) * cfg.n_dep_ids) != hipSuccess) return VDC_ENOMEM;
-    if (hipMalloc(&ex->d_status, sizeof(uint32_t) * ST_WORDS) != hipSuccess) { (void)hipFree(ex->d_dep); return VDC_ENOMEM; }
+    if (hipMalloc(&ex->d_status, sizeof(uint32_t) * (ST_WORDS + 4)) != hipSuccess) { (void)hipFree(ex->d_dep); return VDC_ENOMEM; }
     if (hipHostMalloc(&ex->h_status, sizeof(uint32_t) * ST_WORDS) != hipSuccess) { (void)hipFree(ex->d_dep); (void)hipFree(ex->d_status); return VDC_ENOMEM; }
     HIP_TRY(hipMemset(ex->d_dep, 0, sizeof(uint32_t) * cfg.n_dep_ids));
-    HIP_TRY(hipMemset(ex->d_status, 0, sizeof(uint32_t) * ST_WORDS));
+    HIP_TRY(hipMemset(ex->d_status, 0, sizeof(uint32_t) * (ST_WORDS + 4)));   // the last four words: the sink of vdc_raw_stream
     HIP_TRY(prepare_executor_kernels(lds_bytes_needed(cfg.n_slots, cfg.slot_bytes)));
     HIP_TRY(hipDeviceSynchronize());
     *out = ex.release();
@@ -985,6 +985,7 @@ int vdc_destroy(vdc_executor *ex) {
         (void)hipFree(p->d_words);
         (void)hipFree(p->d_stream_begin);
         (void)hipFree(p->d_descs);
+        (void)hipFree(p->d_workspace);
         delete p;
     }
     (void)hipFree(ex->d_dep);
@@ -1238,6 +1239,14 @@ int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64
     }
     void *bases[2] = {mode == 1 ? dst : (void *)src, dst};
     return vdc_run(ex, prog, bases, mode == 2 ? 2 : 1, hip_stream);
+}
+
+int vdc_raw_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64_t bytes, uint32_t value, void *hip_stream) {
+    if (!ex || ex->cfg.device == -1 || mode < 0 || mode > 2 || bytes < 16 || (bytes & 15)) return VDC_EINVAL;
+    if ((mode != 1 && (!src || ((uintptr_t)src & 15u))) || (mode != 0 && (!dst || ((uintptr_t)dst & 15u)))) return VDC_EINVAL;
+    HIP_TRY(hipSetDevice(ex->cfg.device));
+    HIP_TRY(launch_raw_stream(mode, src, dst, (uint64_t)bytes, value, ex->d_status + ST_WORDS, ex->cu_count * 8, (hipStream_t)hip_stream));
+    return VDC_OK;
 }
 
 int vdc_stream_program(vdc_executor *ex, int32_t mode, int64_t bytes, uint32_t value, int32_t tile_bytes, void *uops, int64_t *n_uops,

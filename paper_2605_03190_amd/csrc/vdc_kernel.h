@@ -50,6 +50,8 @@ hipError_t launch_executor(const KParams &p, uint32_t n_cores, bool traced, hipS
 hipError_t prepare_executor_kernels(size_t lds_bytes);
 // Zero n words (a fill kernel; safe inside stream capture, unlike a memset node).
 hipError_t launch_clear(uint32_t *p, uint32_t n, hipStream_t stream);
+hipError_t launch_raw_stream(int mode, const void *src, void *dst, uint64_t bytes, uint32_t value, uint32_t *sink, int blocks,
+                             hipStream_t stream);
 hipError_t launch_debug_alloc(const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n,
                               hipStream_t stream);
 

@@ -161,13 +161,21 @@ DEV void lds_st64_lanes(uint64_t lanes, uint32_t off, uint64_t v) {
 }
 DEV void lds_st128_lanes(uint64_t lanes, uint32_t off, u32x4 v) {
     uint64_t saved;
-    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_write_b128 %2, %3\n\ts_mov_b64 exec, %0"
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_write_b128 %2, %3\n\ts_nop 0\n\ts_mov_b64 exec, %0"
                  : "=&s"(saved) : "s"(lanes), "v"(off), "v"(v) : "memory");
 }
 DEV void lds_and32_lanes(uint64_t lanes, uint32_t off, uint32_t v) {
     uint64_t saved;
     asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tds_and_b32 %2, %3\n\ts_mov_b64 exec, %0"
                  : "=&s"(saved) : "s"(lanes), "v"(off), "v"(v) : "memory");
+}
+// The same for a 16-byte store to global memory.  The two scalar instructions behind the store are the wait states
+// this target asks for between a store of more than 8 bytes and a vector instruction that overwrites its data
+// registers; the compiler cannot see into the block to add them itself.
+DEV void gst128_lanes(uint64_t lanes, uint64_t addr, f32x4 v) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tglobal_store_dwordx4 %2, %3, off\n\ts_nop 0\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lanes), "v"(addr), "v"(v) : "memory");
 }
 // LDS atomic add by lane 0 alone; returns the value before the add, wave-uniform.
 DEV uint32_t lds_add_rtn_lane0(uint32_t off, uint32_t v) {
@@ -1157,6 +1165,7 @@ DEV void stu_main(Ctx &c) {
         }
         if (!have && rf_get(snap, 4) != head) {
             // pick the next STORE up: from here on its queue entry and its static record may be reused
+            PHASE(c, 1u + c.p->n_ldu, 3u);
             r_glo = rf_get(snap, 5); r_ghi = rf_get(snap, 6); r_info = rf_get(snap, 7); r_ticket = rf_get(snap, 8);
             stat = stat_fetch(c, r_info);
             stat = stat + 0u;
@@ -1223,26 +1232,43 @@ DEV void stu_main(Ctx &c) {
                 const uint32_t row_words = (rb_pitch & 0xFFFFu) >> 2, lds_pitch = rb_pitch >> 16;
                 const uint32_t lds_off = slot << slot_shift;
                 compiler_barrier();
+                PHASE(c, 1u + c.p->n_ldu, 4u);
                 if (((r_glo | (uint32_t)gpitch | rb_pitch | (rb_pitch >> 16)) & 15u) == 0u) {
-                    // whole 16-byte chunks: lane l takes chunks l, l + 64, ... of the box, four at a time
+                    // whole 16-byte chunks: lane l takes chunks l, l + 64, ... of the box, four at a time.  The lane's
+                    // offsets into the region and into memory advance by uniform steps (plus a uniform correction when
+                    // the column wraps into the next row): no multiplication or division per chunk, and no branch
                     const uint32_t cpr = (rb_pitch & 0xFFFFu) >> 4, total = rows * cpr;
-                    const uint32_t dr = 64u / cpr, dc = 64u % cpr;
-                    uint32_t rr = c.lane / cpr, cc = c.lane % cpr;
+                    uint32_t rr, cc, dr, dc;
+                    if ((cpr & (cpr - 1u)) == 0u) {
+                        const uint32_t sh = (uint32_t)__builtin_ctz(cpr);
+                        rr = c.lane >> sh; cc = c.lane & (cpr - 1u);
+                        dr = 64u >> sh; dc = 64u & (cpr - 1u);
+                    } else {
+                        rr = c.lane / cpr; cc = c.lane - rr * cpr;
+                        dr = 64u / cpr; dc = 64u - dr * cpr;
+                    }
+                    const uint32_t l_step = dr * lds_pitch + dc * 16u, l_wrap = lds_pitch - cpr * 16u;
+                    const uint64_t g_step = (uint64_t)dr * gpitch + (uint64_t)dc * 16u, g_wrap = gpitch - (uint64_t)cpr * 16u;
+                    uint32_t loff = lds_off + rr * lds_pitch + cc * 16u;
+                    uint64_t goff = gaddr + (uint64_t)rr * gpitch + (uint64_t)cc * 16u;
                     for (uint32_t i0 = 0; i0 < total; i0 += 256u) {
                         f32x4 v[4];
                         uint64_t ga[4];
-                        bool on[4];
+                        uint64_t on[4];
 #pragma unroll
                         for (int q = 0; q < 4; q++) {
-                            on[q] = i0 + (uint32_t)q * 64u + c.lane < total;
-                            ga[q] = gaddr + (uint64_t)rr * gpitch + (uint64_t)cc * 16u;
-                            v[q] = lds_ld128(on[q] ? lds_off + rr * lds_pitch + cc * 16u : lds_off);
-                            cc += dc; rr += dr;
-                            if (cc >= cpr) { cc -= cpr; rr++; }
+                            const bool in = i0 + (uint32_t)q * 64u + c.lane < total;
+                            on[q] = __ballot(in);
+                            ga[q] = goff;
+                            v[q] = lds_ld128(in ? loff : lds_off);
+                            cc += dc;
+                            const bool wrap = cc >= cpr;
+                            cc -= wrap ? cpr : 0u;
+                            loff += l_step + (wrap ? l_wrap : 0u);
+                            goff += g_step + (wrap ? g_wrap : 0ull);
                         }
 #pragma unroll
-                        for (int q = 0; q < 4; q++)
-                            if (on[q]) *(f32x4 *)(uintptr_t)ga[q] = v[q];
+                        for (int q = 0; q < 4; q++) gst128_lanes(on[q], ga[q], v[q]);
                     }
                 } else {
                     const uint32_t total = rows * row_words;
@@ -1282,7 +1308,7 @@ DEV void stu_main(Ctx &c) {
             }
             continue;
         }
-        PHASE(c, 1u + c.p->n_ldu, 5u);
+        PHASE(c, 1u + c.p->n_ldu, have ? 6u : 5u);
         if (!spin_step(c, sp, rf_get(snap, 10), 0x700u | (have ? 0x80u : 0u))) ok = false;
     }
 }
@@ -1774,6 +1800,51 @@ hipError_t launch_executor(const KParams &p, uint32_t n_cores, bool traced, hipS
 
 hipError_t launch_clear(uint32_t *ptr, uint32_t n, hipStream_t stream) {
     hipLaunchKernelGGL(clear_kernel, dim3((n + 255u) / 256u), dim3(256), 0, stream, ptr, n);
+    return hipGetLastError();
+}
+
+// What the memory uops are measured against (Section 6.3, "Memory virtual core overhead"): the same bytes moved by plain
+// 128-bit load and store instructions, no virtual cores.  Every thread walks the range with the grid as its stride,
+// four chunks per trip.
+template <int MODE>
+__global__ void __launch_bounds__(256) raw_stream_kernel(const u32x4 *src, u32x4 *dst, uint64_t chunks, uint32_t value, uint32_t *sink) {
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    const u32x4 fill = u32x4{value, value, value, value};
+    uint32_t keep = 0;
+    for (; i + 3u * stride < chunks; i += 4u * stride) {
+        if (MODE == 1) {
+#pragma unroll
+            for (int q = 0; q < 4; q++) __builtin_nontemporal_store(fill, &dst[i + q * stride]);
+        } else {
+            u32x4 v[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) v[q] = __builtin_nontemporal_load(&src[i + q * stride]);
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                if (MODE == 2) __builtin_nontemporal_store(v[q], &dst[i + q * stride]);
+                else keep |= v[q].x ^ v[q].y ^ v[q].z ^ v[q].w;
+            }
+        }
+    }
+    for (; i < chunks; i += stride) {
+        if (MODE == 1) dst[i] = fill;
+        else {
+            const u32x4 v = src[i];
+            if (MODE == 2) dst[i] = v;
+            else keep |= v.x ^ v.y ^ v.z ^ v.w;
+        }
+    }
+    // a read must leave a trace or the compiler drops it: the fold of everything read goes out when a flag in memory,
+    // which the host keeps at zero, says so
+    if (MODE == 0 && *sink != 0u) sink[1 + (blockIdx.x & 1u)] = keep;
+}
+
+hipError_t launch_raw_stream(int mode, const void *src, void *dst, uint64_t bytes, uint32_t value, uint32_t *sink, int blocks, hipStream_t stream) {
+    const uint64_t chunks = bytes / 16u;
+    if (mode == 0) hipLaunchKernelGGL(raw_stream_kernel<0>, dim3(blocks), dim3(256), 0, stream, (const u32x4 *)src, (u32x4 *)dst, chunks, value, sink);
+    else if (mode == 1) hipLaunchKernelGGL(raw_stream_kernel<1>, dim3(blocks), dim3(256), 0, stream, (const u32x4 *)src, (u32x4 *)dst, chunks, value, sink);
+    else hipLaunchKernelGGL(raw_stream_kernel<2>, dim3(blocks), dim3(256), 0, stream, (const u32x4 *)src, (u32x4 *)dst, chunks, value, sink);
     return hipGetLastError();
 }
 

@@ -283,6 +283,23 @@ def test_memory_uops_alone_move_every_byte_exactly(ex, mode, nbytes, T):
     assert bool((dst[nbytes:] == 0xEE).all())
 
 
+def test_plain_kernel_the_memory_uops_are_measured_against(ex):
+    nbytes = (3 << 20) + 16 * 37
+    g = torch.Generator(device="cuda").manual_seed(5)
+    src = torch.randint(0, 256, (nbytes + 16,), dtype=torch.uint8, device="cuda", generator=g)
+    keep = src.clone()
+    dst = torch.full((nbytes + 16,), 0xEE, dtype=torch.uint8, device="cuda")
+    ex.raw_stream("copy", src, dst, nbytes)
+    assert torch.equal(dst[:nbytes], src[:nbytes]) and bool((dst[nbytes:] == 0xEE).all())
+    ex.raw_stream("fill", None, dst, nbytes, value=0x01020304)
+    assert bool((dst[:nbytes].view(torch.int32) == 0x01020304).all()) and bool((dst[nbytes:] == 0xEE).all())
+    ex.raw_stream("read", src, None, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep)
+    with pytest.raises(vdc.VdcError):
+        ex.raw_stream("copy", src, dst, 24)
+
+
 def test_stream_traces_match_the_interpreter_and_oracle_assembled_streams_run():
     """The per-unit traces of a copy are bit-exact against the interpreter running the same uops; then stream programs
     that the oracle-side assembler built (no product tiler) run on the GPU."""
