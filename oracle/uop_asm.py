@@ -20,6 +20,7 @@ LOAD, STORE = 8, 9
 MATVEC = 16
 ROPE = 17
 DROP, COPY, FILL = 18, 19, 20
+ATTN, ATTN_MERGE = 21, 22
 
 # flags
 F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
@@ -64,6 +65,13 @@ def fill_imm(value, nbytes):
     """FILL: the first nbytes (a multiple of 16) of the output region become copies of the 32-bit word `value`."""
     assert nbytes % 16 == 0 and 0 < nbytes // 16 < 32768 and 0 <= value < (1 << 32)
     return value | ((nbytes // 16) << 32)
+
+
+def attn_imm(d, R, scale):
+    """ATTN: head dimension d (a multiple of 4), R box rows per key / value tile, fp32 scale of the scores."""
+    assert d % 4 == 0 and 0 < d // 4 < 256 and 0 < R < 256
+    bits = int(np.array([scale], dtype=np.float32).view(np.uint32)[0])
+    return (d // 4) | (R << 8) | (bits << 16)
 
 
 class Program:
@@ -253,3 +261,72 @@ def _emit_stream_uop(p, core, v, mode, last, value):
         p.vcc(core, v).append(word(FILL, size=n, imm=fill_imm(value, nb)))
     else:
         p.vcc(core, v).append(word(COPY, size=n, imm=copy_imm(nb)))
+
+
+def attn_decode_program(row_off, d, R, slot_bytes, n_cores, vcc_per_core=2, chunk_tiles=4, scale=None):
+    """Decode attention with one query per request over ragged contexts (Section 6.2, "Dynamic Attention
+    Length"), written as uops.  Tensors: 0 = K and 1 = V ([rows][d], the contexts back to back), 2 = Q
+    ([n_seg][d]), 3 = O ([n_seg][d]), 4 = W, the partial rows ([n_items][d + 4]).  A context is cut into tiles of
+    R rows and into items of chunk_tiles tiles; items are dealt round-robin to the (core, vcc) pairs.  An item
+    loads its query row, its (key tile, value tile) pairs and stores its partial row, signalling the request's
+    depId; request s is merged by pair s mod (number of pairs): a load.dep of its partial rows that waits for all
+    of them, and the store of the result.  All merges come after all items in every stream, so a waiting load
+    never stands in front of a producer.  Every address is a literal."""
+    n_seg = len(row_off) - 1
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    p = Program(n_cores, vcc_per_core)
+    units = n_cores * vcc_per_core
+    kv_slots = -(-R * d * 4 // slot_bytes)
+    q_slots = -(-d * 4 // slot_bytes)
+    w_slots = -(-(d + 4) * 4 // slot_bytes)
+    steps = [[] for _ in range(units)]          # per pair: lists of memory uops dispatched together
+    merges = [[] for _ in range(units)]
+    item = 0
+    n_items = []
+    for s in range(n_seg):
+        L = int(row_off[s + 1] - row_off[s])
+        tiles = -(-L // R)
+        first_item = item
+        for t0 in range(0, tiles, chunk_tiles):
+            t1 = min(tiles, t0 + chunk_tiles)
+            unit = item % units
+            core, v = unit // vcc_per_core, unit % vcc_per_core
+            dq = p.desc(2, 1, d * 4, d * 4, d * 4)
+            steps[unit].append([word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=q_slots, size=1, imm=s * d * 4, desc=dq)])
+            for t in range(t0, t1):
+                r0 = int(row_off[s]) + t * R
+                rv = min(R, int(row_off[s + 1]) - r0)
+                dk = p.desc(0, R, d * 4, d * 4, d * 4)
+                dv = p.desc(1, R, d * 4, d * 4, d * 4)
+                steps[unit].append([word(LOAD, F_SEND | F_NT, vflow=2 * v, vcc=v, nslots=kv_slots, size=rv, imm=r0 * d * 4, desc=dk),
+                                    word(LOAD, F_SEND | F_NT, vflow=2 * v + 1, vcc=v, nslots=kv_slots, size=rv, imm=r0 * d * 4, desc=dv)])
+            dw = p.desc(4, 1, (d + 4) * 4, (d + 4) * 4, (d + 4) * 4)
+            steps[unit].append([word(STORE, F_SEND | F_RECV | F_DEP_SEND, vflow=4 + v, vcc=v, nslots=w_slots, size=1, dep_id=s,
+                                     imm=item * (d + 4) * 4, desc=dw)])
+            p.vcc(core, v).append(word(ATTN, size=t1 - t0, imm=attn_imm(d, R, scale)))
+            item += 1
+        n_items.append((first_item, item - first_item))
+    for s in range(n_seg):
+        first_item, P = n_items[s]
+        assert 1 <= P <= 255
+        unit = s % units
+        v = unit % vcc_per_core
+        dt = p.desc(4, P, (d + 4) * 4, (d + 4) * 4, (d + 4) * 4)
+        do = p.desc(3, 1, d * 4, d * 4, d * 4)
+        t_slots = -(-P * (d + 4) * 4 // slot_bytes)
+        merges[unit].append([word(LOAD, F_SEND | F_DEP_RECV, vflow=2 * v + 1, vcc=v, nslots=t_slots, size=P, dep_id=s, dep_count=P,
+                                  imm=first_item * (d + 4) * 4, desc=dt),
+                             word(STORE, F_SEND | F_RECV, vflow=4 + v, vcc=v, nslots=q_slots, size=1, imm=s * d * 4, desc=do)])
+    for unit in range(units):                   # the compute streams: items first, then merges
+        core, v = unit // vcc_per_core, unit % vcc_per_core
+        for s in range(n_seg):
+            if s % units == unit:
+                p.vcc(core, v).append(word(ATTN_MERGE, size=n_items[s][1], imm=d // 4))
+    for core in range(n_cores):                 # the memory stream: the pairs' steps in turn
+        for lists in (steps, merges):
+            mine = [lists[core * vcc_per_core + v] for v in range(vcc_per_core)]
+            for i in range(max(len(x) for x in mine)):
+                for x in mine:
+                    if i < len(x):
+                        p.vmc(core).extend(x[i])
+    return p, item

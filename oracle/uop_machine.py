@@ -35,6 +35,14 @@ machine in the paper's order and vocabulary and shares nothing with the HIP path
   of that measurement here: `drop` returns every region it pops as used, `fill` writes one
   32-bit word all over every output region it pops, `copy` pops a loaded region and an
   output region and moves the bytes of the first into the second.
+* Section 4.1 names an `attn` compute uop (fused attention score computation) and Section 4.3
+  ("Virtual Memory Core") says a FlashAttention uop frees slots in another order than they were
+  allocated.  `attn` here serves one query over part of a context: it pops the query tile and keeps
+  it, then for each of `size` (key tile, value tile) pairs updates a running maximum m, a running
+  sum l of exp(score - m) and the sums o of exp(score - m) times the value rows, hands the query
+  tile back (the oldest allocation goes back last), and writes (o, m, l) to an output region.
+  `attn_merge` pops a tile of such partial rows of one request and an output region and writes
+  sum_i exp(m_i - M) o_i / sum_i exp(m_i - M) l_i with M = max_i m_i.
 
 Where the paper is silent the readings are those written in the design document:
 16-byte words, the opcode set below, m2c delivery in program order of the `send` uops
@@ -52,7 +60,7 @@ import numpy as np
 
 HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
 LOAD, STORE = 8, 9
-MATVEC, ROPE, DROP, COPY, FILL = 16, 17, 18, 19, 20
+MATVEC, ROPE, DROP, COPY, FILL, ATTN, ATTN_MERGE = 16, 17, 18, 19, 20, 21, 22
 F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
 KIND_FREE, KIND_DATA = 0, 1
 MAX_LOOP_DEPTH = 4
@@ -196,6 +204,7 @@ class Core:
         self.vcc_run = [None] * V                    # running compute uop (generator) per VCC
         self.vcc_wait = [False] * V
         self.peak_slots = 0
+        self.free_log = []                           # (position, n) in the order the regions came back
         self.stats = dict(m2c_push=[0] * V, m2c_pop=[0] * V, c2m_push=[0] * V, c2m_pop=[0] * V)
 
     # ---- slot pool -------------------------------------------------------------------------
@@ -214,6 +223,7 @@ class Core:
         if self.mask & bits != bits:
             raise ProgramError("free of slots that are not allocated")
         self.mask &= ~bits
+        self.free_log.append((p, n))
 
     def region(self, slot, nslots):
         sb = self.m.slot_bytes
@@ -446,6 +456,60 @@ class Machine:
             self._c2m_push(core, v, KIND_FREE, a[0], a[1])
             self._c2m_push(core, v, KIND_DATA, o[0], o[1])
 
+    def _attn(self, core, v, u):
+        """One query over `size` (key tile, value tile) pairs of a context; imm = d/4 [7:0], R [15:8], the bits of
+        the fp32 scale [47:16].  Writes the row (o[0..d), m, l, 0, 0) of fp32 to the output region."""
+        d = (u.imm & 0xFF) * 4
+        R = (u.imm >> 8) & 0xFF
+        scale = float(np.array([(u.imm >> 16) & 0xFFFFFFFF], dtype=np.uint32).view(np.float32)[0])
+        q = yield
+        if q[2] != 1 or q[3] != d * 4:
+            raise ProgramError("attn: the query tile is not one row of d values")
+        qv = core.region(q[0], q[1]).view(np.float32)[:d].astype(np.float64)
+        m, l, o = -np.inf, 0.0, np.zeros(d)
+        for _ in range(u.size):
+            k = yield
+            kv = core.region(k[0], k[1]).view(np.float32)[:R * d].reshape(R, d).astype(np.float64)
+            rows = k[2]
+            if rows < 1 or rows > R or k[3] != d * 4:
+                raise ProgramError("attn: key tile geometry does not match the uop")
+            score = scale * (kv[:rows] @ qv)
+            w = yield
+            if w[2] != rows or w[3] != d * 4:
+                raise ProgramError("attn: value tile geometry does not match the key tile")
+            vv = core.region(w[0], w[1]).view(np.float32)[:R * d].reshape(R, d).astype(np.float64)
+            m_new = max(m, float(score.max()))
+            p = np.exp(score - m_new)
+            alpha = np.exp(m - m_new)                      # 0 on the first tile
+            l = l * alpha + p.sum()
+            o = o * alpha + p @ vv[:rows]
+            m = m_new
+            self._c2m_push(core, v, KIND_FREE, k[0], k[1])
+            self._c2m_push(core, v, KIND_FREE, w[0], w[1])
+        self._c2m_push(core, v, KIND_FREE, q[0], q[1])     # allocated first, handed back last
+        out = yield
+        if out[3] < (d + 4) * 4:
+            raise ProgramError("attn: the output region is smaller than a partial row")
+        row = core.region(out[0], out[1]).view(np.float32)
+        row[:d] = o.astype(np.float32)
+        row[d:d + 4] = (np.float32(m), np.float32(l), 0.0, 0.0)
+        self._c2m_push(core, v, KIND_DATA, out[0], out[1])
+
+    def _attn_merge(self, core, v, u):
+        """`size` partial rows (o, m, l, 0, 0) of one request become its result; imm = d/4."""
+        d = (u.imm & 0xFF) * 4
+        t = yield
+        out = yield
+        if t[2] != u.size or t[3] != (d + 4) * 4:
+            raise ProgramError("attn_merge: the tile is not `size` partial rows")
+        part = core.region(t[0], t[1]).view(np.float32)[:u.size * (d + 4)].reshape(u.size, d + 4).astype(np.float64)
+        M = part[:, d].max()
+        w = np.exp(part[:, d] - M)
+        res = (w @ part[:, :d]) / (w @ part[:, d + 1])
+        core.region(out[0], out[1]).view(np.float32)[:d] = res.astype(np.float32)
+        self._c2m_push(core, v, KIND_FREE, t[0], t[1])
+        self._c2m_push(core, v, KIND_DATA, out[0], out[1])
+
     def _c2m_push(self, core, v, kind, slot, nslots):
         core.c2m[v].append((kind, slot, nslots))
         core.stats["c2m_push"][v] += 1
@@ -461,7 +525,8 @@ class Machine:
                 if commit:
                     s.control(u)
                 return True
-            handlers = {MATVEC: self._matvec, ROPE: self._rope, DROP: self._drop, COPY: self._copy, FILL: self._fill}
+            handlers = {MATVEC: self._matvec, ROPE: self._rope, DROP: self._drop, COPY: self._copy, FILL: self._fill,
+                        ATTN: self._attn, ATTN_MERGE: self._attn_merge}
             if u.opcode not in handlers:
                 raise ProgramError("opcode %d on a compute core" % u.opcode)
             if commit:
