@@ -166,6 +166,27 @@ int vdc_matvec_rope_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t l
 int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                          void *init, int64_t *bytes);
 
+/* Decode attention with one query per request over contexts of uneven length (Section 6.2, "Dynamic Attention
+ * Length"), run as a uop graph around the attn compute uop (Section 4.1; a FlashAttention-style uop whose slots come
+ * back in another order than they were allocated, Section 4.3):
+ *     O[s][t] = sum_r p_r V[r][t],  p = softmax_r(scale * sum_j Q[s][j] K[r][j]),  r in [row_off[s], row_off[s + 1])
+ * Q [n_seg][d], O [n_seg][d], K and V [row_off[n_seg]][d] (the contexts back to back): device, fp32, row-major,
+ * 16-byte aligned, caller-owned; row_off: host, n_seg + 1 offsets, row_off[0] = 0, every request at least one row.
+ * d = 128; tile_bytes in {4096, 8192, 16384} (8, 16, 32 context rows per key / value tile); n_seg <= n_dep_ids.
+ * A context is cut into items of consecutive tiles that balance over the compute cores; every item leaves a partial row
+ * (weighted values, running maximum, running sum) in a library-owned workspace and signals the request's depId; one
+ * compute core per request merges its rows.  fp32 arithmetic, exp() of differences to the running maximum only.
+ * Asynchronous on hip_stream; programs are cached by (row_off, d, scale, tile_bytes).  Errors: VDC_EINVAL (arguments),
+ * VDC_ENOMEM, VDC_EPROGRAM, VDC_EDEVICE. */
+int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const float *V, const int64_t *row_off,
+                    int32_t n_seg, int32_t d, float scale, float *O, int32_t tile_bytes, void *hip_stream);
+
+/* The uop program vdc_attn_decode runs, handed out like vdc_matvec_program does.  Tensors: 0 = K, 1 = V, 2 = Q, 3 = O,
+ * 4 = the workspace of *n_items rows of d + 4 floats (no initial content needed). */
+int vdc_attn_decode_program(vdc_executor *ex, const int64_t *row_off, int32_t n_seg, int32_t d, float scale,
+                            int32_t tile_bytes, void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs,
+                            int32_t *n_descs, int64_t *n_items);
+
 /* Memory uops with nothing to compute behind them (Section 6.3, "Memory virtual core overhead": the cost of the
  * memory core by I/O block size).  The byte range of `bytes` bytes is cut into blocks of tile_bytes, each moved by
  * one memory uop (the rest of the range: one shorter block of whole 1 KB rows, then one of a single short row); the

@@ -58,6 +58,9 @@ def lib():
             "vdc_matvec_rope": [vp, vp, i64, i64, i64, vp, vp, vp, i32, i32, vp],
             "vdc_matvec_rope_program": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_matvec_workspace": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64)],
+            "vdc_attn_decode": [vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, i32, vp],
+            "vdc_attn_decode_program": [vp, vp, i32, i32, ctypes.c_float, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32),
+                                        ctypes.POINTER(i64)],
             "vdc_stream": [vp, i32, vp, vp, i64, ctypes.c_uint32, i32, vp],
             "vdc_raw_stream": [vp, i32, vp, vp, i64, ctypes.c_uint32, vp],
             "vdc_stream_program": [vp, i32, i64, ctypes.c_uint32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
@@ -75,7 +78,8 @@ def lib():
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
            "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
-           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_stream", "vdc_raw_stream",
+           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_attn_decode", "vdc_attn_decode_program",
+           "vdc_stream", "vdc_raw_stream",
            "vdc_stream_program", "vdc_debug_alloc", "vdc_strerror"]
 
 
@@ -260,6 +264,30 @@ class Executor:
         if n.value:
             _check(lib().vdc_matvec_workspace(self.handle, rows, K, ld, B, tile_bytes, _np_ptr(ws), ctypes.byref(n)), "vdc_matvec_workspace")
         return ws
+
+    def attn_decode(self, Q, K, V, row_off, O, tile_bytes, scale=None, stream=None):
+        """O[s] = softmax(scale * K_s Q[s]) V_s per request s; Q, O: [n_seg][d], K, V: [rows][d] CUDA fp32 tensors;
+        row_off: host offsets (n_seg + 1).  Asynchronous."""
+        ro = np.ascontiguousarray(row_off, dtype=np.int64)
+        d = Q.shape[1]
+        scale = float(d) ** -0.5 if scale is None else float(scale)
+        _check(lib().vdc_attn_decode(self.handle, Q.data_ptr(), K.data_ptr(), V.data_ptr(), _np_ptr(ro), len(ro) - 1, d, scale,
+                                     O.data_ptr(), tile_bytes, _stream_ptr(stream)), "vdc_attn_decode")
+
+    def attn_decode_program(self, row_off, d, tile_bytes, scale=None):
+        """The uop graph attn_decode would run: (words, stream_begin, descs, n_items)."""
+        ro = np.ascontiguousarray(row_off, dtype=np.int64)
+        scale = float(d) ** -0.5 if scale is None else float(scale)
+        n_w, n_d, n_i = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int64(0)
+        f = lib().vdc_attn_decode_program
+        _check(f(self.handle, _np_ptr(ro), len(ro) - 1, d, scale, tile_bytes, None, ctypes.byref(n_w), None, None, ctypes.byref(n_d),
+                 ctypes.byref(n_i)), "vdc_attn_decode_program (sizing)")
+        words = np.zeros((n_w.value, 4), dtype=np.uint32)
+        descs = np.zeros((n_d.value, 8), dtype=np.uint32)
+        sb = np.zeros(self.n_streams + 1, dtype=np.uint32)
+        _check(f(self.handle, _np_ptr(ro), len(ro) - 1, d, scale, tile_bytes, _np_ptr(words), ctypes.byref(n_w), _np_ptr(sb), _np_ptr(descs),
+                 ctypes.byref(n_d), ctypes.byref(n_i)), "vdc_attn_decode_program")
+        return words, sb, descs, n_i.value
 
     STREAM_MODES = {"read": 0, "fill": 1, "copy": 2}
 

@@ -54,6 +54,8 @@ struct vdc_executor {
 #endif
     std::vector<vdc_program *> programs;
     std::vector<std::pair<MatvecKey, vdc_program *>> matvec_cache;
+    struct AttnKey { std::vector<int64_t> row_off; int32_t d; float scale; int32_t tile_bytes; };
+    std::vector<std::pair<AttnKey, vdc_program *>> attn_cache;
     struct StreamKey { int32_t mode; int64_t bytes; uint32_t value; int32_t tile_bytes; };
     std::vector<std::pair<StreamKey, vdc_program *>> stream_cache;
 };
@@ -96,7 +98,9 @@ struct VccH {
     bool in_uop = false;
     uint32_t left = 0, B = 0, R = 0, lpr = 0;
     int phase = 0;                // MATVEC: 0 expect a, 1 expect b, 2 expect out; ROPE: 10 expect values, 11 expect angles, 12 expect out;
-                                  // DROP: 20; FILL: 21; COPY: 22 expect in, 23 expect out
+                                  // DROP: 20; FILL: 21; COPY: 22 expect in, 23 expect out;
+                                  // ATTN: 30 expect q, 31 expect K tile, 32 expect V tile, 33 expect out; ATTN_MERGE: 40 expect rows, 41 expect out
+    SentMsg q{};
     uint32_t chunks = 0;
     SentMsg a{}, b{};
 };
@@ -292,6 +296,16 @@ struct Validator {
                 v.in_uop = true;
                 return 1;
             }
+            if (f.opcode == OP_ATTN || f.opcode == OP_ATTN_MERGE) {
+                v.lpr = (uint32_t)f.imm & 0xFFu;
+                v.R = f.opcode == OP_ATTN ? (uint32_t)(f.imm >> 8) & 0xFFu : 8u;
+                if (!attn_geometry_ok(v.lpr, v.R)) { fail("attn geometry not supported"); return -1; }
+                if (f.size < 1 || (f.opcode == OP_ATTN_MERGE && f.size > kAttnMaxPartials)) { fail("attn: bad size"); return -1; }
+                v.left = f.size;
+                v.phase = f.opcode == OP_ATTN ? 30 : 40;
+                v.in_uop = true;
+                return 1;
+            }
             if (f.opcode != OP_MATVEC) { fail("opcode not valid on a compute core"); return -1; }
             v.B = (uint32_t)f.imm & 0xFFu;
             v.R = (uint32_t)(f.imm >> 8) & 0xFFFFu;
@@ -307,6 +321,41 @@ struct Validator {
         if (v.m2c.empty()) return 0;
         SentMsg m = v.m2c.front();
         v.m2c.pop_front();
+        if (v.phase >= 30) {
+            const uint32_t row = v.lpr * 16, prow = row + 16;     // bytes of a key / value row, of a partial row
+            switch (v.phase) {
+                case 30:
+                    if (m.is_store || m.rows != 1 || m.row_bytes != row) { fail("attn: the query tile is not one row of d values"); return -1; }
+                    v.q = m; v.phase = 31;
+                    break;
+                case 31:
+                    if (m.is_store || m.box_rows != v.R || m.lds_pitch != row || m.row_bytes != row) { fail("attn: key tile does not match the uop"); return -1; }
+                    v.a = m; v.phase = 32;
+                    break;
+                case 32:
+                    if (m.is_store || m.box_rows != v.R || m.lds_pitch != row || m.row_bytes != row || m.rows != v.a.rows) { fail("attn: value tile does not match the key tile"); return -1; }
+                    release(c, v.a);
+                    release(c, m);
+                    if (--v.left == 0) { release(c, v.q); v.phase = 33; } else v.phase = 31;
+                    break;
+                case 33:
+                    if (!m.is_store || m.rows != 1 || m.row_bytes != prow) { fail("attn: the output region is not one partial row"); return -1; }
+                    if (!store_returns(c, m)) return -1;
+                    v.in_uop = false; v.s.pc++;
+                    break;
+                case 40:
+                    if (m.is_store || m.rows != v.left || m.row_bytes != prow || m.lds_pitch != prow) { fail("attn_merge: the tile is not `size` partial rows"); return -1; }
+                    v.a = m; v.phase = 41;
+                    break;
+                default:
+                    if (!m.is_store || m.rows != 1 || m.row_bytes != row) { fail("attn_merge: the output region is not one row of d values"); return -1; }
+                    release(c, v.a);
+                    if (!store_returns(c, m)) return -1;
+                    v.in_uop = false; v.s.pc++;
+                    break;
+            }
+            return 1;
+        }
         if (v.phase >= 20) {
             const uint64_t need = (uint64_t)v.chunks * 16, have = (uint64_t)m.nslots * cfg.slot_bytes;
             if (v.phase == 20 || v.phase == 22) {
@@ -865,6 +914,103 @@ int build_stream(const vdc_config &cfg, int32_t mode, int64_t bytes, uint32_t va
     return VDC_OK;
 }
 
+// Decode attention, one query per request, over ragged contexts (Section 6.2, "Dynamic Attention Length"), as a uop
+// graph.  Tensors: 0 = K, 1 = V ([rows][d], the contexts back to back), 2 = Q ([n_seg][d]), 3 = O ([n_seg][d]),
+// 4 = W, the partial rows ([n_items][d + 4]).  A context is cut into tiles of R rows and into items of at most
+// `chunk` tiles, so that the items balance over the compute cores however uneven the contexts are (a single long
+// context is shared by many cores; at most kAttnMaxPartials items per request).  Consecutive items go to the same
+// compute core, in proportion to their tiles.  An item is: LOAD the query row, `n` x {LOAD key tile, LOAD value tile},
+// STORE the partial row and signal the request's depId.  Request s is then merged on one compute core: a load.dep of
+// its partial rows that waits for all of them, an ATTN_MERGE, the STORE of the result.  Every stream holds all its
+// items before its first merge, and items wait for nothing: a waiting load never stands in front of a producer
+// (Section 4.3, "Avoiding Deadlock").  The memory core's stream takes the steps of its compute cores in turn.
+int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int32_t d, float scale, int32_t tile_bytes,
+               std::vector<Word> &words, std::vector<uint32_t> &sb, std::vector<Desc> &descs, int64_t &n_items) {
+    if (!row_off || n_seg < 1 || n_seg > cfg.n_dep_ids || d != 128 || row_off[0] != 0) return VDC_EINVAL;
+    if (tile_bytes != 4096 && tile_bytes != 8192 && tile_bytes != 16384) return VDC_EINVAL;
+    const uint32_t lpr = (uint32_t)d / 4, R = (uint32_t)tile_bytes / ((uint32_t)d * 4), row = (uint32_t)d * 4, prow = row + 16;
+    if (!attn_geometry_ok(lpr, R)) return VDC_EINVAL;
+    const int C = cfg.n_cores, V = cfg.vcc_per_core;
+    const int64_t units = (int64_t)C * V;
+    int64_t NT = 0, maxT = 0;
+    for (int s = 0; s < n_seg; s++) {
+        const int64_t L = row_off[s + 1] - row_off[s];
+        if (L < 1) return VDC_EINVAL;
+        const int64_t T = (L + R - 1) / R;
+        NT += T;
+        maxT = std::max(maxT, T);
+    }
+    int64_t chunk = std::max<int64_t>(1, (NT + 4 * units - 1) / (4 * units));
+    chunk = std::max(chunk, (maxT + kAttnMaxPartials - 1) / kAttnMaxPartials);
+    if (chunk > 65535) return VDC_EINVAL;
+    Tiler t{cfg, 0, 0, 0, 1, 1, 4};
+    t.streams.resize((size_t)C * (1 + V));
+    uint32_t scale_bits;
+    memcpy(&scale_bits, &scale, 4);
+    const uint32_t kv_slots = t.slots_for((uint64_t)tile_bytes), q_slots = t.slots_for(row), w_slots = t.slots_for(prow);
+    const uint32_t d_k = t.desc(0, R, row, row, row), d_v = t.desc(1, R, row, row, row), d_q = t.desc(2, 1, row, row, row);
+    const uint32_t d_o = t.desc(3, 1, row, row, row), d_w = t.desc(4, 1, prow, prow, prow);
+    std::vector<std::vector<std::vector<Word>>> steps((size_t)units), merges((size_t)units);   // per compute core: groups of memory uops
+    struct SegItems { int64_t first, count; };
+    std::vector<SegItems> seg_items((size_t)n_seg);
+    int64_t item = 0, tiles_before = 0;
+    for (int s = 0; s < n_seg; s++) {
+        const int64_t L = row_off[s + 1] - row_off[s], T = (L + R - 1) / R;
+        seg_items[s].first = item;
+        for (int64_t t0 = 0; t0 < T; t0 += chunk) {
+            const int64_t t1 = std::min(T, t0 + chunk);
+            const int64_t u = std::min(units - 1, tiles_before * units / NT);
+            const int v = (int)(u % V);
+            auto &st = steps[(size_t)u];
+            st.push_back({encode(OP_LOAD, F_SEND, t.flow_x(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_q, 0)});
+            for (int64_t ti = t0; ti < t1; ti++) {
+                const int64_t r0 = row_off[s] + ti * R;
+                const uint32_t rv = (uint32_t)std::min<int64_t>(R, row_off[s + 1] - r0);
+                st.push_back({encode(OP_LOAD, F_SEND | F_NT, t.flow_m(v), v, 0, kv_slots, rv, 0, r0 * row, d_k, 0),
+                              encode(OP_LOAD, F_SEND | F_NT, t.flow_x(v), v, 0, kv_slots, rv, 0, r0 * row, d_v, 0)});
+            }
+            st.push_back({encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, t.flow_y(v), v, 0, w_slots, 1, (uint32_t)s, item * prow, d_w, 0)});
+            t.vcc((int)(u / V), v).push_back(encode(OP_ATTN, 0, 0, 0, 0, 0, (uint32_t)(t1 - t0), 0, attn_imm(lpr, R, scale_bits), 0, 0));
+            tiles_before += t1 - t0;
+            item++;
+        }
+        seg_items[s].count = item - seg_items[s].first;
+        if (seg_items[s].count > kAttnMaxPartials) return VDC_EINVAL;
+    }
+    n_items = item;
+    for (int s = 0; s < n_seg; s++) {
+        const int64_t u = (int64_t)s * units / n_seg;
+        const int v = (int)(u % V);
+        const uint32_t P = (uint32_t)seg_items[s].count;
+        const uint32_t d_t = t.desc(4, P, prow, prow, prow);
+        const uint32_t t_slots = t.slots_for((uint64_t)P * prow);
+        if ((int)(t_slots + q_slots) > cfg.n_slots) return VDC_EINVAL;
+        merges[(size_t)u].push_back({encode(OP_LOAD, F_SEND | F_DEP_RECV, t.flow_x(v), v, 0, t_slots, P, (uint32_t)s, seg_items[s].first * prow, d_t, P),
+                                     encode(OP_STORE, F_SEND | F_RECV, t.flow_y(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_o, 0)});
+        t.vcc((int)(u / V), v).push_back(encode(OP_ATTN_MERGE, 0, 0, 0, 0, 0, P, 0, (int64_t)lpr, 0, 0));
+    }
+    for (int c = 0; c < C; c++)
+        for (auto *lists : {&steps, &merges}) {
+            size_t longest = 0;
+            for (int v = 0; v < V; v++) longest = std::max(longest, (*lists)[(size_t)c * V + v].size());
+            for (size_t i = 0; i < longest; i++)
+                for (int v = 0; v < V; v++) {
+                    auto &l = (*lists)[(size_t)c * V + v];
+                    if (i < l.size()) t.vmc(c).insert(t.vmc(c).end(), l[i].begin(), l[i].end());
+                }
+        }
+    words.clear();
+    sb.assign(1, 0);
+    for (auto &st : t.streams) {
+        words.insert(words.end(), st.begin(), st.end());
+        words.push_back(encode(OP_HALT, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
+        sb.push_back((uint32_t)words.size());
+    }
+    descs = t.descs;
+    if (descs.size() > 256) return VDC_EINVAL;
+    return VDC_OK;
+}
+
 int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     for (int i = 0; i < 5; i++)
         if (c.reserved[i]) return VDC_EINVAL;
@@ -1062,6 +1208,8 @@ int vdc_program_destroy(vdc_program *prog) {
         it = (it->second == prog) ? ex->matvec_cache.erase(it) : it + 1;
     for (auto it = ex->stream_cache.begin(); it != ex->stream_cache.end();)
         it = (it->second == prog) ? ex->stream_cache.erase(it) : it + 1;
+    for (auto it = ex->attn_cache.begin(); it != ex->attn_cache.end();)
+        it = (it->second == prog) ? ex->attn_cache.erase(it) : it + 1;
     (void)hipFree(prog->d_words);
     (void)hipFree(prog->d_stream_begin);
     (void)hipFree(prog->d_descs);
@@ -1215,6 +1363,51 @@ int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, 
         memcpy(init, ws.data(), ws.size() * 4);
     }
     return VDC_OK;
+}
+
+int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const float *V, const int64_t *row_off, int32_t n_seg,
+                    int32_t d, float scale, float *O, int32_t tile_bytes, void *hip_stream) {
+    if (!ex || ex->cfg.device == -1 || !Q || !K || !V || !O || !row_off || n_seg < 1) return VDC_EINVAL;
+    if (((uintptr_t)Q & 15u) || ((uintptr_t)K & 15u) || ((uintptr_t)V & 15u) || ((uintptr_t)O & 15u)) return VDC_EINVAL;
+    vdc_program *prog = nullptr;
+    for (auto &kv : ex->attn_cache)
+        if (kv.first.d == d && kv.first.scale == scale && kv.first.tile_bytes == tile_bytes && (int32_t)kv.first.row_off.size() == n_seg + 1 &&
+            std::equal(kv.first.row_off.begin(), kv.first.row_off.end(), row_off)) { prog = kv.second; break; }
+    if (!prog) {
+        std::vector<Word> words;
+        std::vector<uint32_t> sb;
+        std::vector<Desc> descs;
+        int64_t n_items = 0;
+        int rc = build_attn(ex->cfg, row_off, n_seg, d, scale, tile_bytes, words, sb, descs, n_items);
+        if (rc != VDC_OK) return rc;
+        const int64_t rows = row_off[n_seg], row = (int64_t)d * 4;
+        int64_t tb[5] = {rows * row, rows * row, n_seg * row, n_seg * row, n_items * (row + 16)};
+        rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb, 5, &prog);
+        if (rc != VDC_OK) return rc;
+        if (hipMalloc(&prog->d_workspace, (size_t)tb[4]) != hipSuccess) { vdc_program_destroy(prog); return VDC_ENOMEM; }
+        ex->attn_cache.push_back({{std::vector<int64_t>(row_off, row_off + n_seg + 1), d, scale, tile_bytes}, prog});
+    }
+    void *bases[5] = {(void *)K, (void *)V, (void *)Q, (void *)O, prog->d_workspace};
+    return vdc_run(ex, prog, bases, 5, hip_stream);
+}
+
+int vdc_attn_decode_program(vdc_executor *ex, const int64_t *row_off, int32_t n_seg, int32_t d, float scale, int32_t tile_bytes,
+                            void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs, int64_t *n_items) {
+    if (!ex || !n_uops || !n_descs || !n_items) return VDC_EINVAL;
+    std::vector<Word> words;
+    std::vector<uint32_t> sb;
+    std::vector<Desc> ds;
+    int rc = build_attn(ex->cfg, row_off, n_seg, d, scale, tile_bytes, words, sb, ds, *n_items);
+    if (rc != VDC_OK) return rc;
+    const int64_t cap_w = *n_uops;
+    const int32_t cap_d = *n_descs;
+    *n_uops = (int64_t)words.size();
+    *n_descs = (int32_t)ds.size();
+    bool fits = true;
+    if (uops) { if (cap_w >= (int64_t)words.size()) memcpy(uops, words.data(), words.size() * sizeof(Word)); else fits = false; }
+    if (descs) { if (cap_d >= (int32_t)ds.size()) memcpy(descs, ds.data(), ds.size() * sizeof(Desc)); else fits = false; }
+    if (stream_begin) memcpy(stream_begin, sb.data(), sb.size() * sizeof(uint32_t));
+    return fits ? VDC_OK : VDC_EINVAL;
 }
 
 int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64_t bytes, uint32_t value, int32_t tile_bytes,

@@ -30,7 +30,13 @@ enum Opcode : uint32_t {
     // compute uops without arithmetic, for measuring memory uops alone (Section 6.3, "Memory virtual core overhead")
     OP_DROP = 18,   // VCC: pop `size` loaded regions, hand each back as used
     OP_COPY = 19,   // VCC: `size` times: pop a loaded region and an output region, move bytes across, hand both back
-    OP_FILL = 20    // VCC: pop `size` output regions, write one 32-bit word all over each, hand it back as produced
+    OP_FILL = 20,   // VCC: pop `size` output regions, write one 32-bit word all over each, hand it back as produced
+    // decode attention (the attn uop of Section 4.1; FlashAttention-style, slots freed out of order, Section 4.3)
+    OP_ATTN = 21,        // VCC: pop the query tile and keep it; `size` times {pop a key tile, pop a value tile, update the
+                         // running maximum m, sum l and weighted values o}; hand the query tile back; pop the output
+                         // region, write the row (o[0..d), m, l, 0, 0), hand it back as produced
+    OP_ATTN_MERGE = 22   // VCC: pop a tile of `size` such rows of one request and an output region; write
+                         // sum_i exp(m_i - M) o_i / sum_i exp(m_i - M) l_i, M = max_i m_i
 };
 
 enum Flag : uint32_t {
@@ -114,6 +120,13 @@ inline bool rope_geometry_ok(uint32_t B, uint32_t R) { return B >= 1 && B <= 8 &
 inline int64_t copy_imm(uint32_t chunks) { return (int64_t)chunks; }
 inline int64_t fill_imm(uint32_t value, uint32_t chunks) { return (int64_t)value | ((int64_t)chunks << 32); }
 constexpr uint32_t kMaxStreamChunks = 2048;   // 32 KB: sixteen passes of the 128 threads of an execution unit
+
+// ATTN imm: lpr [7:0] = d / 4 (16-byte chunks per row of a key / value tile), R [15:8] (box rows of those tiles), the bits
+// of the fp32 factor on the scores [47:16].  ATTN_MERGE imm: lpr [7:0].  Supported: d = 128 (lpr = 32), R in {8, 16, 32}
+// (tiles of 4, 8, 16 KB), at most 64 partial rows per merge.
+inline int64_t attn_imm(uint32_t lpr, uint32_t R, uint32_t scale_bits) { return (int64_t)lpr | ((int64_t)R << 8) | ((int64_t)scale_bits << 16); }
+inline bool attn_geometry_ok(uint32_t lpr, uint32_t R) { return lpr == 32 && (R == 8 || R == 16 || R == 32); }
+constexpr uint32_t kAttnMaxPartials = 64;
 
 // The compute uop works on `threads_per_eu` = 128 threads; a matrix tile is NF passes of 128 chunks of
 // 16 bytes.  Supported geometries (anything else is rejected when the program is created):

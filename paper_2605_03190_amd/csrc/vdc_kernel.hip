@@ -1638,6 +1638,111 @@ DEV bool copy_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t chunks) {
     return true;
 }
 
+// A region that was popped earlier and kept (its ticket already counted in vs.head) goes back as used: the same
+// arrival protocol as vcc_done_with, with the payload the caller saved at the pop.
+DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
+    compiler_barrier();
+    const uint32_t v = c.unit;
+    const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
+    if (before & 1u) lds_and32_lanes(1ull, c.ctl + CTL_OFF(mask), ~slot_bits((payload >> 1) & 63u, (payload >> 7) & 63u));
+    vs.group++;
+    compiler_barrier();
+}
+
+// The attn uop (Section 4.1) for decoding: one query row of 128 values against `size` (key tile, value tile) pairs of
+// R rows, FlashAttention-style: a running maximum m of the scores, a running sum l of exp(score - m) and the running
+// sums o of exp(score - m) times the value rows.  Both waves of the execution unit compute every score (G = 64 / R
+// lanes share a key row, so m and l come out bit-identical in the two waves and no exchange between them is
+// needed); wave w then owns columns 64 w .. 64 w + 63 of o, one per lane.  The query tile is allocated first and
+// handed back last, after every key and value tile: slots return in another order than they went out (Section 4.3).
+// Rows of a short last tile score minus infinity.
+template <int R>
+DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
+    constexpr uint32_t G = 64u / (uint32_t)R;      // lanes per key row: 2, 4, 8
+    constexpr int NC = 32 / (int)G;                // 16-byte chunks of the row per lane
+    constexpr uint32_t ROW = 512u;                 // bytes per row of a key / value tile
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
+    Msg mq, unused;
+    if (!vcc_pop_wait(c, vs, 1u, 0u, mq, unused)) return false;
+    const uint32_t q_pay = vs.pay0;
+    vs.head += 1u;                                 // popped; handed back at the end
+    const uint32_t q_off = mq.slot << slot_shift;
+    // lane (row, sub) takes chunks (j G + sub + row) mod 32 of its key row, j = 0 .. NC - 1: the rotation by the row
+    // spreads the lanes of one read over the banks (rows are 512 bytes apart, so equal columns would all collide)
+    const uint32_t sub = c.lane & (G - 1u), row = c.lane / G, rot = sub + row;
+    f32x4 qv[NC];
+#pragma unroll
+    for (int j = 0; j < NC; j++) qv[j] = lds_ld128(q_off + (((uint32_t)j * G + rot) & 31u) * 16u);
+    const uint32_t col = vs.wv * 64u + c.lane;
+    float m = -__builtin_inff(), l = 0.0f, o = 0.0f;
+    for (uint32_t it = 0; it < size; it++) {
+        Msg mk, mv;
+        if (!vcc_pop_wait(c, vs, 2u, 0u, mk, mv)) return false;
+        const uint32_t k_off = (mk.slot << slot_shift) + row * ROW, v_off = (mv.slot << slot_shift) + col * 4u;
+        float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NC; j += 2) {
+            s0 = dot4(lds_ld128(k_off + (((uint32_t)j * G + rot) & 31u) * 16u), qv[j], s0);
+            s1 = dot4(lds_ld128(k_off + (((uint32_t)(j + 1) * G + rot) & 31u) * 16u), qv[j + 1], s1);
+        }
+        float s = s0 + s1;
+#pragma unroll
+        for (uint32_t st = G >> 1; st > 0u; st >>= 1) s += __shfl_xor(s, (int)st, 64);
+        s = row < mk.rows ? s * scale : -__builtin_inff();
+        float tm = s;
+#pragma unroll
+        for (uint32_t st = 32u; st >= G; st >>= 1) tm = __builtin_fmaxf(tm, __shfl_xor(tm, (int)st, 64));
+        const float m_new = __builtin_fmaxf(m, tm);
+        const float p = expf(s - m_new);
+        float ps = p;
+#pragma unroll
+        for (uint32_t st = 32u; st >= G; st >>= 1) ps += __shfl_xor(ps, (int)st, 64);
+        const float alpha = expf(m - m_new);     // 0 on the first tile
+        l = __builtin_fmaf(l, alpha, ps);
+        o *= alpha;
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            const float pr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), r * (int)G));
+            o = __builtin_fmaf(pr, lds_ldf(v_off + (uint32_t)r * ROW), o);
+        }
+        m = m_new;
+        vcc_done_with(c, vs, 2u, 0u);
+    }
+    vcc_return_kept(c, vs, q_pay);
+    Msg mo;
+    if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
+    const uint32_t out_off = mo.slot << slot_shift;
+    lds_stf(out_off + col * 4u, o);
+    if (vs.t < 4u) lds_stf(out_off + ROW + vs.t * 4u, vs.t == 0u ? m : (vs.t == 1u ? l : 0.0f));
+    lds_wait();
+    vcc_done_with(c, vs, 1u, 1u);
+    return true;
+}
+
+// attn_merge: `P` partial rows (o[0..128), m, l, 0, 0) of one request become its result; thread t owns column t.
+DEV bool attn_merge_uop(Ctx &c, VccState &vs, uint32_t P) {
+    constexpr uint32_t PROW = 528u;
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
+    Msg mt, mo, unused;
+    if (!vcc_pop_wait(c, vs, 1u, 0u, mt, unused)) return false;
+    const uint32_t t_off = mt.slot << slot_shift;
+    float M = -__builtin_inff();
+    for (uint32_t i = 0; i < P; i++) M = __builtin_fmaxf(M, lds_ldf(t_off + i * PROW + 512u));
+    float num = 0.0f, den = 0.0f;
+    for (uint32_t i = 0; i < P; i++) {
+        const float w = expf(lds_ldf(t_off + i * PROW + 512u) - M);
+        num = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + vs.t * 4u), num);
+        den = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + 516u), den);
+    }
+    const float res = num / den;
+    vcc_done_with(c, vs, 1u, 0u);
+    if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
+    lds_stf((mo.slot << slot_shift) + vs.t * 4u, res);
+    lds_wait();
+    vcc_done_with(c, vs, 1u, 1u);
+    return true;
+}
+
 // The control-flow unit of a VCC runs on the execution unit's own threads (Section 4.3, "Virtual Compute Core"):
 // each of its two waves decodes the stream, runs control uops itself and then yields to the uop handler.
 DEV void vcc_main(Ctx &c, uint32_t wv) {
@@ -1663,6 +1768,17 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
             ok = matvec_dispatch(c, vs, f);
         } else if (f.opcode == OP_ROPE) {
             ok = rope_uop(c, vs, (uint32_t)f.imm & 0xFFu, (uint32_t)(f.imm >> 8) & 0xFFFFu);
+        } else if (f.opcode == OP_ATTN) {
+            const uint32_t R = (uint32_t)(f.imm >> 8) & 0xFFu;
+            const float scale = __builtin_bit_cast(float, (uint32_t)(f.imm >> 16));
+            if (((uint32_t)f.imm & 0xFFu) != 32u || (R != 8u && R != 16u && R != 32u)) {
+                raise_error(c, -3 /* VDC_EPROGRAM */, 0xE00u | f.opcode);
+                ok = false;
+            } else {
+                ok = R == 32u ? attn_uop<32>(c, vs, f.size, scale) : R == 16u ? attn_uop<16>(c, vs, f.size, scale) : attn_uop<8>(c, vs, f.size, scale);
+            }
+        } else if (f.opcode == OP_ATTN_MERGE) {
+            ok = attn_merge_uop(c, vs, f.size);
         } else if (f.opcode == OP_DROP) {
             ok = drop_uop(c, vs, f.size);
         } else if (f.opcode == OP_FILL) {

@@ -10,7 +10,7 @@ import torch
 
 import paper_2605_03190_amd as vdc
 import workloads
-from oracle import gemv_ref, rope_ref, uop_asm as A, uop_machine as UM
+from oracle import attn_ref, gemv_ref, rope_ref, uop_asm as A, uop_machine as UM
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-5
@@ -342,6 +342,102 @@ def test_stream_traces_match_the_interpreter_and_oracle_assembled_streams_run():
                 assert np.all(got == 0x77)
             assert np.array_equal(dsrc.cpu().numpy(), src)
             prog.destroy()
+
+
+def _attn_inputs(lengths, seed, d=128):
+    rng = np.random.default_rng(seed)
+    ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    Q = rng.standard_normal((len(lengths), d)).astype(np.float32)
+    K = rng.standard_normal((int(ro[-1]), d)).astype(np.float32)
+    V = rng.standard_normal((int(ro[-1]), d)).astype(np.float32)
+    return Q, K, V, ro
+
+
+def _check_attn(O_gpu, Q, K, V, ro, scale, what):
+    """|O - O_ref| <= (2 * 1e-5 * S + 2e-5) * A: S bounds the rounding of a score (it enters through exp, twice: in
+    the weight and in the normalisation), A = sum_r p_r |V_rt| is the scale of the weighted sum itself."""
+    Or, Ar, S = attn_ref.attn_decode(Q, K, V, ro, scale)
+    bound = (2.0 * TOL * S[:, None] + 2e-5) * Ar + 1e-30
+    worst = float((np.abs(O_gpu.astype(np.float64) - Or) / bound).max())
+    assert worst <= 1.0, "%s: error is %.3g times the bound" % (what, worst)
+
+
+ATTN_CASES = [
+    # context lengths, tile_bytes
+    ([1], 4096),
+    ([40, 7, 300, 9, 64], 4096),                   # tails; one request shared by several compute cores
+    ([600], 8192),
+    ([33] * 9, 16384),
+    ([512], 16384),                                # the paper's regimes: 1 x 512,
+    ([512] * 64, 16384),                           # 64 x 512,
+    ("rand", 16384),                               # 64 x random[256, 1024],
+    ([65536], 16384),                              # 1 x 65536
+    ([5000, 1, 17], 8192),
+]
+
+
+@pytest.mark.parametrize("lengths,T", ATTN_CASES)
+def test_decode_attention_against_the_fp64_definition(ex, lengths, T):
+    if lengths == "rand":
+        lengths = list(np.random.default_rng(64).integers(256, 1025, 64))
+    Q, K, V, ro = _attn_inputs(lengths, seed=len(lengths) + T)
+    dO = torch.full((len(lengths), 128), float("nan"), device="cuda")
+    dQ, dK, dV = _dev(Q), _dev(K), _dev(V)
+    for _ in range(2):                             # the second run takes the cached program
+        ex.attn_decode(dQ, dK, dV, ro, dO, T)
+        ex.check()
+    _check_attn(dO.cpu().numpy(), Q, K, V, ro, 128 ** -0.5, "attention %s" % (lengths[:4],))
+
+
+def test_attention_traces_match_the_interpreter_and_oracle_assembled_programs_run():
+    lengths = [70, 9, 130, 33]
+    Q, K, V, ro = _attn_inputs(lengths, seed=8)
+    d = 128
+    with vdc.Executor(n_cores=4, slot_bytes=4096, n_slots=12) as ex:
+        words, sb, descs, n_items = ex.attn_decode_program(ro, d, 4096)
+        prog = ex.program_create(words, sb, descs, [K.nbytes, V.nbytes, Q.nbytes, Q.nbytes, n_items * (d + 4) * 4])
+        dO = torch.full((len(lengths), d), float("nan"), device="cuda")
+        dW = torch.full((n_items, d + 4), float("nan"), device="cuda")
+        trace, count = ex.run(prog, [_dev(K), _dev(V), _dev(Q), dO, dW], trace_cap=512)
+        ex.check()
+        _check_attn(dO.cpu().numpy(), Q, K, V, ro, d ** -0.5, "tiler program")
+        Oo, Wo = np.zeros((len(lengths), d), np.float32), np.zeros((n_items, d + 4), np.float32)
+        m = UM.Machine(words, sb, descs, [K, V, Q, Oo, Wo], n_cores=4, slot_bytes=4096, n_slots=12, n_dep_ids=1024).run()
+        trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+        for core in range(4):
+            exp = [(pc, op | (dd << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, dd, off, n) in m.trace_vmc[core]]
+            assert count[core * 3] == len(exp)
+            assert [tuple(int(x) for x in r) for r in trace[core * 3, :len(exp)]] == exp
+            for v in range(2):
+                exp = [(pc, op | (n << 16), imm & 0xFFFFFFFF, imm >> 32) for (pc, op, n, imm) in m.trace_vcc[core][v]]
+                assert count[core * 3 + 1 + v] == len(exp)
+                assert [tuple(int(x) for x in r) for r in trace[core * 3 + 1 + v, :len(exp)]] == exp
+        # the partial rows agree with the interpreter's (same tiling, fp32 against fp64 arithmetic)
+        Wg = dW.cpu().numpy()
+        assert np.allclose(Wg[:, 128:130], Wo[:, 128:130], rtol=1e-4, atol=1e-5) and np.all(Wg[:, 130:] == 0)
+        prog.destroy()
+        # a program from the oracle-side assembler (another way of cutting and dealing the work)
+        p, n_items = A.attn_decode_program(ro, d, 8, 4096, 4, chunk_tiles=3)
+        words, sb, descs = p.finish()
+        prog = ex.program_create(words, sb, descs, [K.nbytes, V.nbytes, Q.nbytes, Q.nbytes, n_items * (d + 4) * 4])
+        dO.fill_(float("nan"))
+        dW = torch.full((n_items, d + 4), float("nan"), device="cuda")
+        ex.run(prog, [_dev(K), _dev(V), _dev(Q), dO, dW])
+        ex.check()
+        _check_attn(dO.cpu().numpy(), Q, K, V, ro, d ** -0.5, "oracle-assembled program")
+        prog.destroy()
+
+
+def test_attention_refuses_what_it_does_not_support(ex):
+    Q, K, V, ro = _attn_inputs([10, 20], seed=1)
+    dQ, dK, dV, dO = _dev(Q), _dev(K), _dev(V), torch.zeros((2, 128), device="cuda")
+    for bad in (dict(T=2048), dict(ro=np.array([0, 10, 10])), dict(ro=np.array([1, 10, 30]))):
+        a = dict(T=4096, ro=ro)
+        a.update(bad)
+        with pytest.raises(vdc.VdcError):
+            ex.attn_decode(dQ, dK, dV, a["ro"], dO, a["T"])
+    with pytest.raises(vdc.VdcError):
+        ex.attn_decode(dQ[:, :64].contiguous(), dK, dV, ro, dO, 4096)      # d = 64
 
 
 def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):

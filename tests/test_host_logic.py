@@ -249,3 +249,58 @@ def test_stream_program_rejects_bad_arguments():
         with pytest.raises(vdc.VdcError):
             ex.stream_program("copy", 1 << 20, 16384)      # an input and an output region of 16 KB need eight slots
         ex.stream_program("read", 1 << 20, 16384)
+
+
+# ---- decode attention over ragged contexts (Section 6.2, "Dynamic Attention Length") -----------------
+@pytest.mark.parametrize("lengths,T,ncores,slot,nslots", [
+    ([1], 4096, 1, 4096, 8),
+    ([40, 7, 300, 9, 64], 4096, 2, 4096, 10),          # one long request shared by the compute cores, short ones whole
+    ([600], 8192, 4, 8192, 8),                         # a single request on eight compute cores
+    ([33] * 9, 16384, 2, 8192, 10),                    # more requests than compute cores; a tile holds most of a context
+])
+def test_attention_program_on_the_oracle_interpreter(lengths, T, ncores, slot, nslots):
+    from oracle import attn_ref
+    d = 128
+    rng = np.random.default_rng(sum(lengths))
+    ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    Q = rng.standard_normal((len(lengths), d)).astype(np.float32)
+    K = rng.standard_normal((int(ro[-1]), d)).astype(np.float32)
+    V = rng.standard_normal((int(ro[-1]), d)).astype(np.float32)
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
+        w, sb, ds, n_items = ex.attn_decode_program(ro, d, T)
+        rc, msg = ex.program_validate(w, sb, ds, [K.nbytes, V.nbytes, Q.nbytes, Q.nbytes, n_items * (d + 4) * 4])
+        assert rc == vdc.VDC_OK, msg
+        for bad in (dict(d=64), dict(T=2048), dict(ro=np.array([0, 5, 5]))):
+            a = dict(ro=ro, d=d, T=T)
+            a.update(bad)
+            with pytest.raises(vdc.VdcError):
+                ex.attn_decode_program(a["ro"], a["d"], a["T"])
+    ops = w[:, 0] & 0xFF
+    assert (ops == A.ATTN).sum() == n_items and (ops == A.ATTN_MERGE).sum() == len(lengths)
+    # items balance: no compute core holds more than its share of the tiles plus one item
+    Or, Ar, S = attn_ref.attn_decode(Q, K, V, ro, d ** -0.5)
+    for sched, seed in (("program", 0), ("random", 1)):
+        O = np.full((len(lengths), d), np.nan, np.float32)
+        W = np.full((n_items, d + 4), np.nan, np.float32)
+        m = UM.Machine(w, sb, ds, [K, V, Q, O, W], n_cores=ncores, slot_bytes=slot, n_slots=nslots, n_dep_ids=1024)
+        m.run(sched, seed)
+        m.check_final()
+        assert np.all(np.abs(O - Or) <= 4e-7 * Ar + 1e-30)
+
+
+def test_attention_items_balance_over_the_compute_cores():
+    # the uneven regime: 64 requests of 256..1024 rows on 16 cores; and one long request alone
+    rng = np.random.default_rng(3)
+    for lengths in (rng.integers(256, 1025, 64), np.array([65536])):
+        ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+        with vdc.Executor(device=-1, n_cores=16) as ex:
+            w, sb, ds, n_items = ex.attn_decode_program(ro, 128, 16384)
+        ops, size = w[:, 0] & 0xFF, w[:, 1] & 0xFFFF
+        per_vcc = []
+        for c in range(16):
+            for v in range(2):
+                a, b = sb[c * 3 + 1 + v], sb[c * 3 + 2 + v]
+                per_vcc.append(int(size[a:b][ops[a:b] == A.ATTN].sum()))
+        total = sum(-(-int(L) // 32) for L in lengths)
+        assert sum(per_vcc) == total
+        assert max(per_vcc) <= total / 32 + max(1, -(-total // 128)) + 1
