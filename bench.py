@@ -4,6 +4,7 @@
 resident synthetic inputs of one configuration.  Prints ONE JSON line on stdout; everything else goes to stderr.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg5_b1|cfg3|cfg4|cfg2|cfg1]
+    python bench.py --workload attn_0.5k|attn_0.5k_b|attn_64k|attn_rand [--heads 8]     (decode attention, see below)
 
 metric  = matrix elements per second on one GPU (one element = one fp32 matrix entry, each used for B vectors)
 roofline = algorithmic HBM bytes of one launch / mean duration of the executor kernel, against 8 TB/s
@@ -37,6 +38,92 @@ def algorithmic_bytes(rows, K, B, n_x_rows):
     return 4 * rows * K + 4 * n_x_rows * K + 4 * B * rows
 
 
+# The four regimes of the paper's uneven-context study (Section 6.2, "Dynamic Attention Length"): context rows per request.
+ATTN_REGIMES = {
+    "attn_0.5k": ("1 x 512", lambda: [512]),
+    "attn_0.5k_b": ("64 x 512", lambda: [512] * 64),
+    "attn_64k": ("1 x 65536", lambda: [65536]),
+    "attn_rand": ("64 x random[256,1024]", lambda: list(np.random.default_rng(2605).integers(256, 1025, 64))),
+}
+
+
+def bench_attention(args):
+    """Decode attention with one query per request (vdc_attn_decode) on one regime.  The paper does not say how many
+    heads its model has: every request has `heads` key/value heads of 128 values with one query head each, and every
+    (request, head) pair is one context of the ragged batch.  One element = one fp32 key or value entry, read once."""
+    import torch
+    import paper_2605_03190_amd as vdc
+    vdc.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    label, make = ATTN_REGIMES[args.workload]
+    d = 128
+    lengths = np.repeat(make(), args.heads)
+    ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    rows = int(ro[-1])
+    tile = args.tile_bytes or 16384
+    g = torch.Generator(device="cuda").manual_seed(rows)
+    # batches that fit the Infinity Cache are rotated over several copies so that every launch reads from HBM
+    n_copies = max(1, min(8, (2 << 30) // (2 * rows * d * 4))) if 2 * rows * d * 4 <= 512 << 20 else 1
+    Q = torch.randn((len(lengths), d), device="cuda", generator=g)
+    Ks = [torch.randn((rows, d), device="cuda", generator=g) for _ in range(n_copies)]
+    Vs = [torch.randn((rows, d), device="cuda", generator=g) for _ in range(n_copies)]
+    O = torch.full((len(lengths), d), float("nan"), device="cuda")
+    ex = vdc.Executor(slot_bytes=args.slot_bytes or 8192)
+    stream = torch.cuda.current_stream()
+    for i in range(args.warmup):
+        ex.attn_decode(Q, Ks[i % n_copies], Vs[i % n_copies], ro, O, tile, stream=stream)
+    ex.check(stream)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record(stream)
+        ex.attn_decode(Q, Ks[i % n_copies], Vs[i % n_copies], ro, O, tile, stream=stream)
+        ends[i].record(stream)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_begin
+    ex.check(stream)
+    kern_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
+    kern_avg_ms = float(np.mean(kern_ms))
+    elements = 2 * rows * d
+    alg = 4 * elements + 2 * 4 * len(lengths) * d
+    achieved = alg / (kern_avg_ms * 1e-3) / 1e9
+    value = elements * args.steps / t_total
+    log("%s: %d contexts, %d rows; per step %.4f ms, kernel avg %.4f ms (min %.4f max %.4f)  %.1f GB/s = %.1f%% of %.0f"
+        % (args.workload, len(lengths), rows, t_total * 1e3 / args.steps, kern_avg_ms, min(kern_ms), max(kern_ms), achieved,
+           100 * achieved / HBM_PEAK_GBS, HBM_PEAK_GBS))
+    out = {
+        "metric": "decode-attention key/value elements/sec at 1 GPU", "value": value, "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_total * 1e3 / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: decode attention, %s context rows per request, %d heads of %d, fp32, %d KB tiles" % (
+            args.workload, label, args.heads, d, tile // 1024), "contexts": len(lengths), "rows": rows, "tile_bytes": tile},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "vdc_executor_kernel", "kernel_avg_ms": kern_avg_ms, "algorithmic_bytes": alg},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import attn_ref
+        # bounded sample: the leading contexts of the batch, whole, up to about 64K rows
+        n = max(1, int(np.searchsorted(ro, 65536, side="right")) - 1)
+        last = (args.steps - 1) % n_copies
+        r1 = int(ro[n])
+        Qh, Kh, Vh = Q[:n].cpu().numpy(), Ks[last][:r1].cpu().numpy(), Vs[last][:r1].cpu().numpy()
+        t = time.perf_counter()
+        Or, Ar, S = attn_ref.attn_decode(Qh, Kh, Vh, ro[:n + 1], d ** -0.5)
+        tc = time.perf_counter() - t
+        worst = float((np.abs(O[:n].cpu().numpy() - Or) / ((2e-5 * S[:, None] + 2e-5) * Ar + 1e-30)).max())
+        log("oracle sample: %d contexts, %d rows in %.2f s; GPU vs oracle on the sample: error = %.3g of the bound" % (n, r1, tc, worst))
+        if worst > 1.0:
+            log("PARITY FAILURE on the sampled contexts")
+            sys.exit(1)
+        out["cpu_baseline"] = {"value": 2 * r1 * d / tc, "unit": "elements/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d of %d contexts (%d rows); fp64 definition in numpy, one thread; %.1f s" % (n, len(lengths), r1, tc)}
+    ex.destroy()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +134,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--tile-bytes", type=int, default=0, help="override the configuration's tile (I/O block) size: 2048, 4096, 8192 or 16384")
     ap.add_argument("--slot-bytes", type=int, default=0, help="override the configuration's slot size")
+    ap.add_argument("--heads", type=int, default=8, help="attention workloads: key/value heads per request")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device-to-device copy of MIB mebibytes --steps times: "
                          "the known traffic that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -55,6 +143,9 @@ def main():
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported. "
             "The number to quote is the one-GPU throughput." % args.gpus)
         sys.exit(2)
+
+    if args.workload in ATTN_REGIMES:
+        return bench_attention(args)
 
     import torch
     import paper_2605_03190_amd as vdc

@@ -177,6 +177,14 @@ DEV void gst128_lanes(uint64_t lanes, uint64_t addr, f32x4 v) {
     asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tglobal_store_dwordx4 %2, %3, off\n\ts_nop 0\n\ts_mov_b64 exec, %0"
                  : "=&s"(saved) : "s"(lanes), "v"(addr), "v"(v) : "memory");
 }
+// The same store at device scope (sc1): it is written through, so that once it has completed (vmcnt) every compute
+// unit of the device reads the new data from memory, whichever L2 it sits behind.  A store that is followed by a
+// depId signal uses this form; the alternative, a release fence, writes back the whole L2 of the signalling side.
+DEV void gst128_lanes_device(uint64_t lanes, uint64_t addr, f32x4 v) {
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\tglobal_store_dwordx4 %2, %3, off sc1\n\ts_nop 0\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lanes), "v"(addr), "v"(v) : "memory");
+}
 // LDS atomic add by lane 0 alone; returns the value before the add, wave-uniform.
 DEV uint32_t lds_add_rtn_lane0(uint32_t off, uint32_t v) {
     uint64_t saved;
@@ -831,15 +839,22 @@ DEV bool dep_wait(Ctx &c, uint32_t dep) {
     if (need == 0u) need = 1u;
     Spin s;
     for (;;) {
-        uint32_t v = uni(__hip_atomic_load(&c.p->dep[id], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT));
-        if (v >= need) return true;
+        // the counter is polled relaxed; one acquire at device scope (an invalidate of this side's caches) once it is there
+        uint32_t v = uni(__hip_atomic_load(&c.p->dep[id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if (v >= need) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            return true;
+        }
         if (!spin_step(c, s, uni(lds_vld32(c.ctl + CTL_OFF(abort))), 0x500u | id)) return false;
     }
 }
 
-DEV void dep_signal(Ctx &c, uint32_t dep) {
+// `written_through`: the data the signal covers was stored at device scope and has completed, so the counter needs no
+// release semantics of its own; otherwise the increment is a release at device scope (an L2 write-back).
+DEV void dep_signal(Ctx &c, uint32_t dep, bool written_through) {
     if (c.lane == 0) {
-        __hip_atomic_fetch_add(&c.p->dep[dep & 0xFFFFu], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (written_through) __hip_atomic_fetch_add(&c.p->dep[dep & 0xFFFFu], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else __hip_atomic_fetch_add(&c.p->dep[dep & 0xFFFFu], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
     reconverge();
 }
@@ -855,7 +870,7 @@ DEV void ldu_retire(Ctx &c, const Inflight &t) {
     lds_wait();   // zero fill of this tile (ds_write) is done as well
     lds_st64_lanes((t.ctl & 0x100u) ? 1ull : 0ull, c.ctl + CTL_OFF(m2c) + ((t.ctl >> 10) & 0x3FFu) * 8u,
                    (uint64_t)t.msg_lo | ((uint64_t)t.msg_hi << 32));
-    if (__builtin_expect((t.ctl & 0x200u) != 0u, 0)) dep_signal(c, t.dep);
+    if (__builtin_expect((t.ctl & 0x200u) != 0u, 0)) dep_signal(c, t.dep, false);
 }
 
 // The static part of a record: lanes 0..7 = the StatRec the record's info word points at.
@@ -1201,7 +1216,7 @@ DEV void stu_main(Ctx &c) {
             if (flags & F_DEP_RECV) {
                 uint32_t need = (dep >> 16) & 0xFFu;
                 if (need == 0u) need = 1u;
-                ready = uni(__hip_atomic_load(&c.p->dep[dep & 0xFFFFu], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT)) >= need;
+                ready = uni(__hip_atomic_load(&c.p->dep[dep & 0xFFFFu], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >= need;   // the store reads nothing from memory: order alone is needed
             }
             if (ready && (flags & F_RECV)) {
                 // wait for the compute core to hand the region back as "produced"
@@ -1233,6 +1248,7 @@ DEV void stu_main(Ctx &c) {
                 const uint32_t lds_off = slot << slot_shift;
                 compiler_barrier();
                 PHASE(c, 1u + c.p->n_ldu, 4u);
+                bool through = false;            // stored at device scope (only the 16-byte path does that)
                 if (((r_glo | (uint32_t)gpitch | rb_pitch | (rb_pitch >> 16)) & 15u) == 0u) {
                     // whole 16-byte chunks: lane l takes chunks l, l + 64, ... of the box, four at a time.  The lane's
                     // offsets into the region and into memory advance by uniform steps (plus a uniform correction when
@@ -1267,9 +1283,15 @@ DEV void stu_main(Ctx &c) {
                             loff += l_step + (wrap ? l_wrap : 0u);
                             goff += g_step + (wrap ? g_wrap : 0ull);
                         }
+                        if (flags & F_DEP_SEND) {
 #pragma unroll
-                        for (int q = 0; q < 4; q++) gst128_lanes(on[q], ga[q], v[q]);
+                            for (int q = 0; q < 4; q++) gst128_lanes_device(on[q], ga[q], v[q]);
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 4; q++) gst128_lanes(on[q], ga[q], v[q]);
+                        }
                     }
+                    through = true;
                 } else {
                     const uint32_t total = rows * row_words;
                     for (uint32_t i = c.lane; i < total; i += 64u) {
@@ -1281,10 +1303,10 @@ DEV void stu_main(Ctx &c) {
                 // the data is in registers on its way out: the region is free as soon as the reads have returned
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 slots_free(c, slot, nslots);
-                if (flags & F_DEP_SEND) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 if (flags & F_DEP_SEND) {
-                    __threadfence();
-                    dep_signal(c, dep);
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    if (!through) __threadfence();
+                    dep_signal(c, dep, through);
                 }
                 done++;
                 lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_done) + u * 4u, done);
@@ -1651,15 +1673,17 @@ DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
 
 // The attn uop (Section 4.1) for decoding: one query row of 128 values against `size` (key tile, value tile) pairs of
 // R rows, FlashAttention-style: a running maximum m of the scores, a running sum l of exp(score - m) and the running
-// sums o of exp(score - m) times the value rows.  Both waves of the execution unit compute every score (G = 64 / R
-// lanes share a key row, so m and l come out bit-identical in the two waves and no exchange between them is
-// needed); wave w then owns columns 64 w .. 64 w + 63 of o, one per lane.  The query tile is allocated first and
-// handed back last, after every key and value tile: slots return in another order than they went out (Section 4.3).
-// Rows of a short last tile score minus infinity.
+// sums o of exp(score - m) times the value rows.  Both waves of the execution unit compute every score (so m and l
+// come out bit-identical in the two waves and no exchange between them is needed): the key tile is taken in NP passes
+// of RP <= 16 rows, G = 64 / RP lanes sharing a row.  Wave w then owns columns 64 w .. 64 w + 63 of o, one per lane.
+// The query tile is allocated first and handed back last, after every key and value tile: slots return in another
+// order than they went out (Section 4.3).  Rows of a short last tile score minus infinity.
 template <int R>
 DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
-    constexpr uint32_t G = 64u / (uint32_t)R;      // lanes per key row: 2, 4, 8
-    constexpr int NC = 32 / (int)G;                // 16-byte chunks of the row per lane
+    constexpr int RP = R > 16 ? 16 : R;            // key rows per pass
+    constexpr int NP = R / RP;                     // passes per tile
+    constexpr uint32_t G = 64u / (uint32_t)RP;     // lanes per key row: 4 or 8
+    constexpr int NC = 32 / (int)G;                // 16-byte chunks of the row per lane: 8 or 4
     constexpr uint32_t ROW = 512u;                 // bytes per row of a key / value tile
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     Msg mq, unused;
@@ -1667,7 +1691,7 @@ DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
     const uint32_t q_pay = vs.pay0;
     vs.head += 1u;                                 // popped; handed back at the end
     const uint32_t q_off = mq.slot << slot_shift;
-    // lane (row, sub) takes chunks (j G + sub + row) mod 32 of its key row, j = 0 .. NC - 1: the rotation by the row
+    // lane (row, sub) takes chunks (j G + sub + row) mod 32 of its key rows, j = 0 .. NC - 1: the rotation by the row
     // spreads the lanes of one read over the banks (rows are 512 bytes apart, so equal columns would all collide)
     const uint32_t sub = c.lane & (G - 1u), row = c.lane / G, rot = sub + row;
     f32x4 qv[NC];
@@ -1679,31 +1703,55 @@ DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
         Msg mk, mv;
         if (!vcc_pop_wait(c, vs, 2u, 0u, mk, mv)) return false;
         const uint32_t k_off = (mk.slot << slot_shift) + row * ROW, v_off = (mv.slot << slot_shift) + col * 4u;
-        float s0 = 0.0f, s1 = 0.0f;
+        // the chunk offsets are recomputed per tile (three cheap instructions each): kept across tiles they would
+        // take registers that the loads in flight need
+        uint32_t rot_t = rot;
+        asm volatile("" : "+v"(rot_t));
+        float s[NP];
 #pragma unroll
-        for (int j = 0; j < NC; j += 2) {
-            s0 = dot4(lds_ld128(k_off + (((uint32_t)j * G + rot) & 31u) * 16u), qv[j], s0);
-            s1 = dot4(lds_ld128(k_off + (((uint32_t)(j + 1) * G + rot) & 31u) * 16u), qv[j + 1], s1);
+        for (int h = 0; h < NP; h++) {
+            f32x4 kv[NC];
+#pragma unroll
+            for (int j = 0; j < NC; j++) kv[j] = lds_ld128(k_off + (uint32_t)h * RP * ROW + (((uint32_t)j * G + rot_t) & 31u) * 16u);
+            float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+            for (int j = 0; j < NC; j += 2) {
+                s0 = dot4(kv[j], qv[j], s0);
+                s1 = dot4(kv[j + 1], qv[j + 1], s1);
+            }
+            float x = s0 + s1;
+#pragma unroll
+            for (uint32_t st = G >> 1; st > 0u; st >>= 1) x += __shfl_xor(x, (int)st, 64);
+            s[h] = (uint32_t)h * RP + row < mk.rows ? x * scale : -__builtin_inff();
+            compiler_barrier();      // one pass of key reads in flight at a time: the registers for more are not there
         }
-        float s = s0 + s1;
+        float tm = s[0];
 #pragma unroll
-        for (uint32_t st = G >> 1; st > 0u; st >>= 1) s += __shfl_xor(s, (int)st, 64);
-        s = row < mk.rows ? s * scale : -__builtin_inff();
-        float tm = s;
+        for (int h = 1; h < NP; h++) tm = __builtin_fmaxf(tm, s[h]);
 #pragma unroll
         for (uint32_t st = 32u; st >= G; st >>= 1) tm = __builtin_fmaxf(tm, __shfl_xor(tm, (int)st, 64));
         const float m_new = __builtin_fmaxf(m, tm);
-        const float p = expf(s - m_new);
-        float ps = p;
+        float p[NP], ps = 0.0f;
+#pragma unroll
+        for (int h = 0; h < NP; h++) {
+            p[h] = expf(s[h] - m_new);
+            ps += p[h];
+        }
 #pragma unroll
         for (uint32_t st = 32u; st >= G; st >>= 1) ps += __shfl_xor(ps, (int)st, 64);
         const float alpha = expf(m - m_new);     // 0 on the first tile
         l = __builtin_fmaf(l, alpha, ps);
         o *= alpha;
 #pragma unroll
-        for (int r = 0; r < R; r++) {
-            const float pr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), r * (int)G));
-            o = __builtin_fmaf(pr, lds_ldf(v_off + (uint32_t)r * ROW), o);
+        for (int r0 = 0; r0 < R; r0 += 8) {
+            float vv[8];
+#pragma unroll
+            for (int r = 0; r < 8; r++) vv[r] = lds_ldf(v_off + (uint32_t)(r0 + r) * ROW);
+#pragma unroll
+            for (int r = 0; r < 8; r++) {
+                const float pr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p[(r0 + r) / RP]), ((r0 + r) % RP) * (int)G));
+                o = __builtin_fmaf(pr, vv[r], o);
+            }
         }
         m = m_new;
         vcc_done_with(c, vs, 2u, 0u);
