@@ -1671,6 +1671,44 @@ DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
     compiler_barrier();
 }
 
+// Cross-lane reductions of the attn uop without a trip through the LDS crossbar: data-parallel-primitive (DPP)
+// operands move values inside a row of 16 lanes, v_readlane takes one value per row of 16 to the scalar side.
+template <int CTRL>
+DEV float dpp_f32(float x) {   // x as seen through the DPP control CTRL (all rows, all banks)
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL, int BANKS>
+DEV float dpp_f32_banks(float x, float other) {   // lanes of the quads in BANKS see x through CTRL, the rest see `other`
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, other), __builtin_bit_cast(int, x), CTRL, 0xF, BANKS, false));
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;            // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kDppRor4 = 0x124, kDppRor8 = 0x128;          // row_ror:4, row_ror:8
+constexpr int kDppShl4 = 0x104, kDppShr4 = 0x114;          // row_shl:4, row_shr:4
+
+// Sum over the G = 4 or 8 consecutive lanes that share a key row; every lane of the group gets the sum.
+template <int G>
+DEV float group_sum(float x) {
+    x += dpp_f32<kDppXor1>(x);
+    x += dpp_f32<kDppXor2>(x);
+    if (G == 8) x += dpp_f32_banks<kDppShl4, 0x5>(x, 0.0f) + dpp_f32_banks<kDppShr4, 0xA>(x, 0.0f);   // lane ^ 4
+    return x;
+}
+// All 64 lanes get the maximum (MAX) or the sum of x over the key rows, x being equal inside each group of G lanes.
+template <int G, bool MAX>
+DEV float rows_reduce(float x) {
+    if (G == 4) {
+        const float y = dpp_f32<kDppRor4>(x);
+        x = MAX ? __builtin_fmaxf(x, y) : x + y;
+    }
+    const float z = dpp_f32<kDppRor8>(x);
+    x = MAX ? __builtin_fmaxf(x, z) : x + z;
+    const float t0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+    const float t1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+    const float t2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 32));
+    const float t3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 48));
+    return MAX ? __builtin_fmaxf(__builtin_fmaxf(t0, t1), __builtin_fmaxf(t2, t3)) : (t0 + t1) + (t2 + t3);
+}
+
 // The attn uop (Section 4.1) for decoding: one query row of 128 values against `size` (key tile, value tile) pairs of
 // R rows, FlashAttention-style: a running maximum m of the scores, a running sum l of exp(score - m) and the running
 // sums o of exp(score - m) times the value rows.  Both waves of the execution unit compute every score (so m and l
@@ -1719,26 +1757,21 @@ DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
                 s0 = dot4(kv[j], qv[j], s0);
                 s1 = dot4(kv[j + 1], qv[j + 1], s1);
             }
-            float x = s0 + s1;
-#pragma unroll
-            for (uint32_t st = G >> 1; st > 0u; st >>= 1) x += __shfl_xor(x, (int)st, 64);
+            const float x = group_sum<(int)G>(s0 + s1);
             s[h] = (uint32_t)h * RP + row < mk.rows ? x * scale : -__builtin_inff();
             compiler_barrier();      // one pass of key reads in flight at a time: the registers for more are not there
         }
         float tm = s[0];
 #pragma unroll
         for (int h = 1; h < NP; h++) tm = __builtin_fmaxf(tm, s[h]);
-#pragma unroll
-        for (uint32_t st = 32u; st >= G; st >>= 1) tm = __builtin_fmaxf(tm, __shfl_xor(tm, (int)st, 64));
-        const float m_new = __builtin_fmaxf(m, tm);
+        const float m_new = __builtin_fmaxf(m, rows_reduce<(int)G, true>(tm));
         float p[NP], ps = 0.0f;
 #pragma unroll
         for (int h = 0; h < NP; h++) {
             p[h] = expf(s[h] - m_new);
             ps += p[h];
         }
-#pragma unroll
-        for (uint32_t st = 32u; st >= G; st >>= 1) ps += __shfl_xor(ps, (int)st, 64);
+        ps = rows_reduce<(int)G, false>(ps);
         const float alpha = expf(m - m_new);     // 0 on the first tile
         l = __builtin_fmaf(l, alpha, ps);
         o *= alpha;
