@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the factors a plain copy
 # kernel of known size gives); see profiles/ for the runs.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"cfg5": 8613373790}
+MEASURED_TRAFFIC_BYTES = {"cfg5": 8621044473}
 
 
 def log(*a):
@@ -127,8 +127,8 @@ def bench_attention(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
