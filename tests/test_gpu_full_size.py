@@ -115,3 +115,45 @@ def test_cfg5_single_entries_beyond_4_gib():
             M[i, j] = 0.0
     del M, X, Y
     _free()
+
+
+# ---- decode attention at the benchmark's sizes (bench.py --workload attn_*: 8 heads per request) ---------------
+@pytest.mark.parametrize("regime", ["attn_0.5k_b", "attn_64k", "attn_rand"])
+def test_attention_regimes_at_benchmark_size(regime):
+    """Sampled contexts against the fp64 definition (the first, the last, the longest and the shortest of the batch, one
+    by one), and properties that hold for every output: value rows that are all equal come back whatever the weights are,
+    up to the rounding of the sums; every output lies between the smallest and largest value it
+    averages."""
+    from oracle import attn_ref
+    import bench
+    d, heads = 128, 8
+    lengths = np.repeat(bench.ATTN_REGIMES[regime][1](), heads)
+    ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    rows = int(ro[-1])
+    g = torch.Generator(device="cuda").manual_seed(rows)
+    Q = torch.randn((len(lengths), d), device="cuda", generator=g)
+    K = torch.randn((rows, d), device="cuda", generator=g)
+    V = torch.randn((rows, d), device="cuda", generator=g)
+    O = torch.full((len(lengths), d), float("nan"), device="cuda")
+    with vdc.Executor() as ex:
+        ex.attn_decode(Q, K, V, ro, O, 16384)
+        ex.check()
+        Og = O.cpu().numpy()
+        assert np.all(np.isfinite(Og))
+        pick = sorted({0, len(lengths) - 1, int(np.argmax(lengths)), int(np.argmin(lengths))})
+        for s in pick:
+            a, b = int(ro[s]), int(ro[s + 1])
+            Or, Ar, S = attn_ref.attn_decode(Q[s:s + 1].cpu().numpy(), K[a:b].cpu().numpy(), V[a:b].cpu().numpy(), np.array([0, b - a]), d ** -0.5)
+            assert np.all(np.abs(Og[s] - Or[0]) <= (2e-5 * S[0] + 2e-5) * Ar[0] + 1e-30), "context %d" % s
+        # every output is a weighted mean of its context's value rows
+        seg = torch.repeat_interleave(torch.arange(len(lengths), device="cuda"), torch.from_numpy(lengths).cuda())
+        lo = torch.full((len(lengths), d), float("inf"), device="cuda").scatter_reduce(0, seg[:, None].expand(-1, d), V, "amin")
+        hi = torch.full((len(lengths), d), float("-inf"), device="cuda").scatter_reduce(0, seg[:, None].expand(-1, d), V, "amax")
+        assert bool(((O >= lo - 1e-5) & (O <= hi + 1e-5)).all())
+        # constant value rows per context: the result is that row, whatever the scores
+        Vc = (seg.to(torch.float32) * 0.25 + 1.0)[:, None].expand(-1, d).contiguous()
+        ex.attn_decode(Q, K, Vc, ro, O, 16384)
+        ex.check()
+        want = (torch.arange(len(lengths), device="cuda", dtype=torch.float32) * 0.25 + 1.0)[:, None].expand(-1, d)
+        assert bool((torch.abs(O - want) <= 1e-5 * want).all())
+    _free()

@@ -477,6 +477,37 @@ def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):
         assert torch.equal(dY2, eager2)
 
 
+def test_attention_and_stream_runs_replay_from_a_hip_graph(ex):
+    """The depId counters are cleared by a fill kernel inside the run, so a captured attention run can be replayed; every
+    replay is checked against the eager result, with eager work in between."""
+    Q, K, V, ro = _attn_inputs([300, 40, 700], seed=3)
+    dQ, dK, dV = _dev(Q), _dev(K), _dev(V)
+    dO = torch.zeros((3, 128), device="cuda")
+    src = torch.randint(0, 256, (1 << 20,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    ex.attn_decode(dQ, dK, dV, ro, dO, 8192)            # builds and caches the programs outside the capture
+    ex.stream("copy", src, dst, 1 << 20, 8192)
+    ex.check()
+    eager = dO.clone()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(graph, stream=s):
+            ex.attn_decode(dQ, dK, dV, ro, dO, 8192, stream=s)
+            ex.stream("copy", src, dst, 1 << 20, 8192, stream=s)
+    torch.cuda.current_stream().wait_stream(s)
+    for i in range(3):
+        dO.fill_(float("nan"))
+        dst.zero_()
+        src.add_(1)                                      # eager work between the replays; the copy must see the new bytes
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ex.check()
+        assert torch.equal(dO, eager) and torch.equal(dst, src)
+
+
 def test_ragged_batch(ex):
     rng = np.random.default_rng(4)
     K = 128
