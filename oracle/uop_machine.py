@@ -44,7 +44,7 @@ machine in the paper's order and vocabulary and shares nothing with the HIP path
   `attn_merge` pops a tile of such partial rows of one request and an output region and writes
   sum_i exp(m_i - M) o_i / sum_i exp(m_i - M) l_i with M = max_i m_i.
 
-Where the paper is silent the readings are those written in the design document:
+Where the paper is silent this build reads it as follows:
 16-byte words, the opcode set below, m2c delivery in program order of the `send` uops
 (tickets), and a `kind` tag on c2m messages (recycle / produced).
 
@@ -91,7 +91,8 @@ class Uop:
 
 
 def decode(w):
-    """Split one 4 x uint32 word into its fields (layout: see the design document)."""
+    """Split one 4 x uint32 word into its fields: w0 = opcode [7:0], flags [15:8], vflow [19:16], vcc [21:20],
+    acc [24:22], nslots [30:25]; w1 = size [15:0], depId [31:16]; w2:w3 = imm [47:0] signed, desc [55:48], dep_count [63:56]."""
     w0, w1, w2, w3 = (int(x) for x in w)
     q = w2 | (w3 << 32)
     imm = q & ((1 << 48) - 1)
