@@ -1422,6 +1422,42 @@ DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n, uint32_t kind) {
     compiler_barrier();
 }
 
+// Cross-lane reductions of the compute uops without a trip through the LDS crossbar: data-parallel-primitive (DPP)
+// operands move values inside a row of 16 lanes (and from the last lane of a row into the next rows), v_readlane takes
+// one value per row of 16 to the scalar side.
+template <int CTRL>
+DEV float dpp_f32(float x) {   // x as seen through the DPP control CTRL (all rows, all banks)
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL, int BANKS>
+DEV float dpp_f32_banks(float x, float other) {   // lanes of the quads in BANKS see x through CTRL, the rest see `other`
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, other), __builtin_bit_cast(int, x), CTRL, 0xF, BANKS, false));
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;            // quad_perm [1,0,3,2], [2,3,0,1]
+constexpr int kDppRor4 = 0x124, kDppRor8 = 0x128;          // row_ror:4, row_ror:8
+constexpr int kDppShl4 = 0x104, kDppShr4 = 0x114;          // row_shl:4, row_shr:4
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;    // lane 15 of every row -> the next row; lane 31 -> rows 2 and 3
+
+// Sum of x over each group of `lpr` consecutive lanes (lpr = 1, 2, 4, ..., 64, wave-uniform); the LAST lane of every
+// group holds the sum afterwards (for lpr <= 16 every lane does).  Steps that do not apply add zero: no branches.
+DEV float lane_group_sum(float x, uint32_t lpr) {
+    const float a1 = dpp_f32<kDppXor1>(x);
+    x += lpr >= 2u ? a1 : 0.0f;
+    const float a2 = dpp_f32<kDppXor2>(x);
+    x += lpr >= 4u ? a2 : 0.0f;
+    const float a4x = dpp_f32_banks<kDppShl4, 0x5>(x, 0.0f) + dpp_f32_banks<kDppShr4, 0xA>(x, 0.0f);   // lane ^ 4
+    const float a4r = dpp_f32<kDppRor4>(x);
+    x += lpr == 8u ? a4x : (lpr >= 16u ? a4r : 0.0f);
+    const float a8 = dpp_f32<kDppRor8>(x);
+    x += lpr >= 16u ? a8 : 0.0f;
+    const float a16 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kDppBcast15, 0xA, 0xF, false));
+    x += lpr >= 32u ? a16 : 0.0f;
+    const float a32 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kDppBcast31, 0xC, 0xF, false));
+    x += lpr >= 64u ? a32 : 0.0f;
+    return x;
+}
+
+
 DEV float dot4(f32x4 m, f32x4 x, float acc) {
     acc = __builtin_fmaf(m.x, x.x, acc);
     acc = __builtin_fmaf(m.y, x.y, acc);
@@ -1484,9 +1520,8 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
         for (int i = 0; i < NF; i++)
 #pragma unroll
             for (int b = 0; b < B; b++) {
-                float x = acc[i][b];
-                for (uint32_t s = lpr >> 1; s > 0u; s >>= 1) x += __shfl_xor(x, (int)s, 64);
-                if (c4 == 0u) lds_stf(o_off + ((uint32_t)b * R + (uint32_t)i * rpp + (t >> lsh)) * 4u, x);   // copy(c, c_shared)
+                const float x = lane_group_sum(acc[i][b], lpr);
+                if (c4 == lpr - 1u) lds_stf(o_off + ((uint32_t)b * R + (uint32_t)i * rpp + (t >> lsh)) * 4u, x);   // copy(c, c_shared)
             }
     } else {
         float mine = 0.0f;
@@ -1670,20 +1705,6 @@ DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
     vs.group++;
     compiler_barrier();
 }
-
-// Cross-lane reductions of the attn uop without a trip through the LDS crossbar: data-parallel-primitive (DPP)
-// operands move values inside a row of 16 lanes, v_readlane takes one value per row of 16 to the scalar side.
-template <int CTRL>
-DEV float dpp_f32(float x) {   // x as seen through the DPP control CTRL (all rows, all banks)
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
-}
-template <int CTRL, int BANKS>
-DEV float dpp_f32_banks(float x, float other) {   // lanes of the quads in BANKS see x through CTRL, the rest see `other`
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, other), __builtin_bit_cast(int, x), CTRL, 0xF, BANKS, false));
-}
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E;            // quad_perm [1,0,3,2], [2,3,0,1]
-constexpr int kDppRor4 = 0x124, kDppRor8 = 0x128;          // row_ror:4, row_ror:8
-constexpr int kDppShl4 = 0x104, kDppShr4 = 0x114;          // row_shl:4, row_shr:4
 
 // Sum over the G = 4 or 8 consecutive lanes that share a key row; every lane of the group gets the sum.
 template <int G>
