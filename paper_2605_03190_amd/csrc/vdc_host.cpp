@@ -574,6 +574,21 @@ struct Tiler {
                 sweep(0, k0);
                 for (int i = 0; i < n; i++) emit_result(vm, vs[i], 0, 0, y_off + (it * n + i) * R * 4, dy, rows_valid, y_slots);
             }
+        } else if (nk == 1) {
+            // One tile per row block (K fits a tile): no loop over K.  One accumulator runs over the matrix tiles and one
+            // over the results; the compute cores are told apart by the literal part of the address, the vector tile's
+            // address is a literal.  Two control uops per trip, and the memory uops of a trip stand together.
+            vm.push_back(encode(OP_SET, 0, 0, 0, 0, 0, 0, 0, m_off, 0, 0));
+            vm.push_back(encode(OP_SET, 0, 0, 0, 3, 0, 0, 0, y_off, 0, 0));
+            vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, count, 0, 0));
+            for (int i = 0; i < n; i++) {
+                const int v = vs[i];
+                vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, 0, m_slots, rows_valid, 0, (int64_t)i * R * ld * 4, nk_full ? dm : dmt, 0));
+                vm.push_back(encode(OP_LOAD, F_SEND, flow_x(v), v, 0, x_slots, B, 0, x_off, nk_full ? dx : dxt, 0));
+            }
+            for (int i = 0; i < n; i++) emit_result(vm, vs[i], F_DYNAMIC, 3, (int64_t)i * R * 4, dy, rows_valid, y_slots);
+            vm.push_back(encode(OP_ADD, 0, 0, 0, 3, 0, 0, 0, (int64_t)n * R * 4, 0, 0));
+            vm.push_back(encode(OP_REPEAT, 0, 0, 0, 0, 0, 0, 0, (int64_t)n * R * ld * 4, 0, 0));
         } else {
             // accumulators: 0,1 matrix offset of compute core 0,1; 2 vector offset; 3,4 result offset of compute core 0,1
             for (int i = 0; i < n; i++) {
