@@ -124,7 +124,10 @@ int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info);
  * M, X, Y: device.  K and ld multiples of 4 (rows are moved in 16-byte units), ld >= K, 1 <= B <= 8,
  * M and X 16-byte aligned, Y 4-byte aligned.  tile_bytes = size of one matrix tile (the paper's I/O
  * block): 2048, 4096, 8192 or 16384.  The host tiler turns the call into a uop graph (cached per
- * shape), validates it and runs it.  Asynchronous on hip_stream. */
+ * shape), validates it and runs it.  Asynchronous on hip_stream.
+ * The first call for a shape builds and uploads the program (device allocations, a synchronous copy); later calls
+ * for the same shape only enqueue kernels, so a caller may capture them in a HIP graph.  The same holds for the
+ * other operators below (vdc_matvec_rope, vdc_matvec_ragged, vdc_attn_decode, vdc_stream). */
 int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
                int32_t B, int32_t tile_bytes, void *hip_stream);
 
