@@ -24,6 +24,7 @@ ATTN, ATTN_MERGE = 21, 22
 
 # flags
 F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
+F_DEVICE = 128     # the access is made at device scope (a hint for real caches; no effect on the abstract machine)
 
 MASK48 = (1 << 48) - 1
 
@@ -330,3 +331,52 @@ def attn_decode_program(row_off, d, R, slot_bytes, n_cores, vcc_per_core=2, chun
                     if i < len(x):
                         p.vmc(core).extend(x[i])
     return p, item
+
+
+def chain_matvec_program(dims, B, R, Kt, slot_bytes, n_cores, vcc_per_core=2):
+    """A chain of matvec operators in ONE uop graph: Y_0 = M_0 X, Y_l = M_l Y_(l-1), every layer's tiles waiting only
+    for the tiles of the layer before that they read (Section 4.1, "Encoding dependency in uop": a memory uop may depend
+    on one other memory uop through a depId; Section 3: operators are composed by their memory uops, not by kernel
+    boundaries).  dims = (K_0, rows_0, rows_1, ...): M_l is [dims[l + 1]][dims[l]].  Tensors: 0 = W, the matrices back
+    to back; 1 and 2 = A, the activations back to back ([B][dims[0]] = X, then every Y_l as [B][dims[l + 1]]), read as
+    tensor 1 and written as tensor 2.  Row blocks of R rows are dealt round-robin to the (core, vcc) pairs, layer after
+    layer.  The vector tile kt of layer l + 1 is rows kt Kt .. kt Kt + Kt - 1 of Y_l: the Kt / R row blocks of layer
+    l that produce them signal depId (l, kt) with their stores, and every load of that tile waits for all of them.
+    Requires Kt % R == 0 and every dim a multiple of Kt.  Every address is a literal."""
+    L = len(dims) - 1
+    assert Kt % R == 0 and all(d % Kt == 0 for d in dims)
+    p = Program(n_cores, vcc_per_core)
+    units = n_cores * vcc_per_core
+    m_slots = -(-R * Kt * 4 // slot_bytes)
+    x_slots = -(-B * Kt * 4 // slot_bytes)
+    y_slots = -(-B * R * 4 // slot_bytes)
+    w_off = [0]
+    a_off = [0]
+    for l in range(L):
+        w_off.append(w_off[-1] + dims[l + 1] * dims[l] * 4)
+        a_off.append(a_off[-1] + B * dims[l] * 4)
+    dep_base = [0]
+    for l in range(L):
+        dep_base.append(dep_base[-1] + dims[l + 1] // Kt)
+    for l in range(L):
+        K, rows = dims[l], dims[l + 1]
+        nk = K // Kt
+        dm = p.desc(0, R, Kt * 4, Kt * 4, K * 4)
+        dx = p.desc(1, B, Kt * 4, Kt * 4, K * 4)
+        dy = p.desc(2, B, R * 4, R * 4, rows * 4)
+        for rb in range(rows // R):
+            unit = rb % units
+            core, v = unit // vcc_per_core, unit % vcc_per_core
+            vm = p.vmc(core)
+            for kt in range(nk):
+                vm.append(word(LOAD, F_SEND | F_NT, vflow=2 * v, vcc=v, nslots=m_slots, size=R, imm=w_off[l] + (rb * R * K + kt * Kt) * 4, desc=dm))
+                if l == 0:
+                    vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=x_slots, size=B, imm=kt * Kt * 4, desc=dx))
+                else:
+                    vm.append(word(LOAD, F_SEND | F_DEP_RECV | F_DEVICE, vflow=2 * v + 1, vcc=v, nslots=x_slots, size=B,
+                                   dep_id=dep_base[l - 1] + kt, dep_count=Kt // R, imm=a_off[l] + kt * Kt * 4, desc=dx))
+            last = l == L - 1
+            vm.append(word(STORE, F_SEND | F_RECV | (0 if last else F_DEP_SEND | F_DEVICE), vflow=4 + v, vcc=v, nslots=y_slots, size=B,
+                           dep_id=0 if last else dep_base[l] + rb * R // Kt, imm=a_off[l + 1] + rb * R * 4, desc=dy))
+            p.vcc(core, v).append(word(MATVEC, size=nk, imm=matvec_imm(B, R, Kt // 4)))
+    return p, w_off, a_off

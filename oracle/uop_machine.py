@@ -62,6 +62,7 @@ HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
 LOAD, STORE = 8, 9
 MATVEC, ROPE, DROP, COPY, FILL, ATTN, ATTN_MERGE = 16, 17, 18, 19, 20, 21, 22
 F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
+F_DEVICE = 128     # a hint for real caches (access at device scope); nothing to do in this machine
 KIND_FREE, KIND_DATA = 0, 1
 MAX_LOOP_DEPTH = 4
 N_ACC = 8
