@@ -169,6 +169,25 @@ int vdc_matvec_rope_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t l
 int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                          void *init, int64_t *bytes);
 
+/* A chain of matvec operators as ONE uop graph and one launch (Section 3: operators are composed through their memory
+ * uops, with no kernel boundary between them; Section 4.1: a memory uop may depend on one other through a depId):
+ *     Y_0 = M_0 X,   Y_l = M_l Y_(l-1),   l = 1 .. L-1.
+ * dims (host, L + 1 entries): dims[0] = columns of M_0, dims[l + 1] = rows of M_l; all multiples of 4.
+ * W (device, 16-byte aligned): the matrices back to back, M_l as [dims[l + 1]][dims[l]] fp32, row-major.
+ * A (device, 16-byte aligned): the activations back to back, X as [B][dims[0]], then every Y_l as [B][dims[l + 1]];
+ *   the caller writes X, the run writes every Y_l (all of them stay readable).  1 <= B <= 8, L <= 64.
+ * A layer starts on a vector tile as soon as the row blocks of the layer before that produce it have been stored: their
+ * stores signal the tile's depId and the first loads of the tile wait for it; nothing waits for a whole layer.  Needs
+ * one depId per vector tile of layers 1 .. L-1 (n_dep_ids of the executor).  Asynchronous on hip_stream; programs are
+ * cached by (dims, B, tile_bytes).  VDC_EINVAL for shapes the tiler cannot chain. */
+int vdc_matvec_chain(vdc_executor *ex, const float *W, float *A, const int64_t *dims, int32_t L, int32_t B,
+                     int32_t tile_bytes, void *hip_stream);
+
+/* The uop program vdc_matvec_chain runs (tensors: 0 = W, 1 = A read, 2 = A written), handed out like
+ * vdc_matvec_program does. */
+int vdc_matvec_chain_program(vdc_executor *ex, const int64_t *dims, int32_t L, int32_t B, int32_t tile_bytes, void *uops,
+                             int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs);
+
 /* Decode attention with one query per request over contexts of uneven length (Section 6.2, "Dynamic Attention
  * Length"), run as a uop graph around the attn compute uop (Section 4.1; a FlashAttention-style uop whose slots come
  * back in another order than they were allocated, Section 4.3):

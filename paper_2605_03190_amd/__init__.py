@@ -58,6 +58,8 @@ def lib():
             "vdc_matvec_rope": [vp, vp, i64, i64, i64, vp, vp, vp, i32, i32, vp],
             "vdc_matvec_rope_program": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_matvec_workspace": [vp, i64, i64, i64, i32, i32, vp, ctypes.POINTER(i64)],
+            "vdc_matvec_chain": [vp, vp, vp, vp, i32, i32, i32, vp],
+            "vdc_matvec_chain_program": [vp, vp, i32, i32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_attn_decode": [vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, i32, vp],
             "vdc_attn_decode_program": [vp, vp, i32, i32, ctypes.c_float, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32),
                                         ctypes.POINTER(i64)],
@@ -78,7 +80,7 @@ def lib():
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
            "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
-           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_attn_decode", "vdc_attn_decode_program",
+           "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_matvec_chain", "vdc_matvec_chain_program", "vdc_attn_decode", "vdc_attn_decode_program",
            "vdc_stream", "vdc_raw_stream",
            "vdc_stream_program", "vdc_debug_alloc", "vdc_strerror"]
 
@@ -264,6 +266,26 @@ class Executor:
         if n.value:
             _check(lib().vdc_matvec_workspace(self.handle, rows, K, ld, B, tile_bytes, _np_ptr(ws), ctypes.byref(n)), "vdc_matvec_workspace")
         return ws
+
+    def matvec_chain(self, W, A, dims, B, tile_bytes, stream=None):
+        """Y_0 = M_0 X, Y_l = M_l Y_(l-1) in one launch.  W: the matrices back to back; A: X then every Y_l, back to back
+        (CUDA fp32 tensors); dims = (K_0, rows_0, rows_1, ...).  Asynchronous."""
+        d = np.ascontiguousarray(dims, dtype=np.int64)
+        _check(lib().vdc_matvec_chain(self.handle, W.data_ptr(), A.data_ptr(), _np_ptr(d), len(d) - 1, B, tile_bytes, _stream_ptr(stream)),
+               "vdc_matvec_chain")
+
+    def matvec_chain_program(self, dims, B, tile_bytes):
+        """The uop graph matvec_chain would run."""
+        d = np.ascontiguousarray(dims, dtype=np.int64)
+        n_w, n_d = ctypes.c_int64(0), ctypes.c_int32(0)
+        f = lib().vdc_matvec_chain_program
+        _check(f(self.handle, _np_ptr(d), len(d) - 1, B, tile_bytes, None, ctypes.byref(n_w), None, None, ctypes.byref(n_d)), "vdc_matvec_chain_program (sizing)")
+        words = np.zeros((n_w.value, 4), dtype=np.uint32)
+        descs = np.zeros((n_d.value, 8), dtype=np.uint32)
+        sb = np.zeros(self.n_streams + 1, dtype=np.uint32)
+        _check(f(self.handle, _np_ptr(d), len(d) - 1, B, tile_bytes, _np_ptr(words), ctypes.byref(n_w), _np_ptr(sb), _np_ptr(descs), ctypes.byref(n_d)),
+               "vdc_matvec_chain_program")
+        return words, sb, descs
 
     def attn_decode(self, Q, K, V, row_off, O, tile_bytes, scale=None, stream=None):
         """O[s] = softmax(scale * K_s Q[s]) V_s per request s; Q, O: [n_seg][d], K, V: [rows][d] CUDA fp32 tensors;

@@ -54,6 +54,8 @@ struct vdc_executor {
 #endif
     std::vector<vdc_program *> programs;
     std::vector<std::pair<MatvecKey, vdc_program *>> matvec_cache;
+    struct ChainKey { std::vector<int64_t> dims; int32_t B, tile_bytes; };
+    std::vector<std::pair<ChainKey, vdc_program *>> chain_cache;
     struct AttnKey { std::vector<int64_t> row_off; int32_t d; float scale; int32_t tile_bytes; };
     std::vector<std::pair<AttnKey, vdc_program *>> attn_cache;
     struct StreamKey { int32_t mode; int64_t bytes; uint32_t value; int32_t tile_bytes; };
@@ -195,7 +197,7 @@ struct Validator {
         if (local) {
             // store.local / load.local: no memory access.  The load names no region of its own: it hands on the oldest
             // region a store.local of this core has taken back.
-            if ((f.flags & (F_DYNAMIC | F_DEP_SEND | F_DEP_RECV | F_NT)) || f.imm != 0 || !(f.flags & F_SEND) || (!is_load && !(f.flags & F_RECV)) ||
+            if ((f.flags & (F_DYNAMIC | F_DEP_SEND | F_DEP_RECV | F_NT | F_DEVICE)) || f.imm != 0 || !(f.flags & F_SEND) || (!is_load && !(f.flags & F_RECV)) ||
                 (is_load && (f.flags & F_RECV))) { fail("malformed local memory uop"); return -1; }
             if ((int)f.vcc >= cfg.vcc_per_core) { fail("vcc out of range"); return -1; }
             if (d.box_rows < 1 || d.box_rows > 65535 || d.lds_pitch < 4 || d.lds_pitch > 65535 || d.row_bytes < 4 || d.row_bytes > d.lds_pitch ||
@@ -847,6 +849,134 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
     return VDC_OK;
 }
 
+// A chain of matvec operators in ONE uop graph (Section 3: operators are composed through their memory uops, not through
+// kernel boundaries; Section 4.1, "Encoding dependency in uop"): Y_0 = M_0 X, Y_l = M_l Y_(l-1).  dims[0] = K_0,
+// dims[l + 1] = rows of M_l.  Tensors: 0 = W, the matrices back to back (M_l is [dims[l + 1]][dims[l]], row-major);
+// 1 and 2 = A, the activations back to back (X as [B][dims[0]], then every Y_l as [B][dims[l + 1]]), read as tensor 1
+// and written as tensor 2.  Every layer is tiled like a single matvec (choose_tile) and its row blocks are dealt to the
+// cores in contiguous ranges.  The vector tile kt of layer l + 1 is a range of rows of Y_l: the row blocks of layer l
+// inside that range signal depId (l, kt) with their stores (written through at device scope), and a core's first pass
+// over the vector tiles of a layer waits for them tile by tile, so a layer starts on a tile as soon as that tile is
+// complete, not when the layer before it has ended.  Later row blocks of the same core and layer need no wait: their
+// loads follow the waiting ones on the same load unit.  All vector tiles of layers after the first are read at device
+// scope.  Within a stream a layer's uops precede the next layer's, and layer 0 waits for nothing: by induction over
+// the layers no wait can last forever (Section 4.3, "Avoiding Deadlock").
+struct ChainLayer {
+    int64_t K, rows, w_off, x_off, y_off;
+    int32_t R, Kt, R_prev, Kt_next;
+    int64_t rows_prev;
+    int32_t dep_in, dep_out;     // first depId of this layer's vector tiles / of its outputs; -1: none
+};
+
+int build_chain(const vdc_config &cfg, const int64_t *dims, int32_t L, int32_t B, int32_t tile_bytes, std::vector<Word> &words,
+                std::vector<uint32_t> &sb, std::vector<Desc> &descs, int64_t &w_bytes, int64_t &a_bytes) {
+    if (!dims || L < 1 || L > 64 || B < 1 || B > 8) return VDC_EINVAL;
+    for (int l = 0; l <= L; l++)
+        if (dims[l] < 4 || (dims[l] & 3)) return VDC_EINVAL;
+    const int C = cfg.n_cores, V = cfg.vcc_per_core;
+    std::vector<ChainLayer> ly((size_t)L);
+    int64_t w = 0, a = 0;
+    int32_t dep = 0;
+    for (int l = 0; l < L; l++) {
+        ChainLayer &c = ly[(size_t)l];
+        c.K = dims[l]; c.rows = dims[l + 1];
+        if (!choose_tile(cfg, c.K, B, tile_bytes, c.R, c.Kt)) return VDC_EINVAL;
+        if ((uint64_t)((c.K + c.Kt - 1) / c.Kt) > 65535) return VDC_EINVAL;
+        c.w_off = w; c.x_off = a; c.y_off = a + (int64_t)B * c.K * 4;
+        w += c.rows * c.K * 4;
+        a += (int64_t)B * c.K * 4;
+    }
+    a += (int64_t)B * dims[L] * 4;
+    w_bytes = w; a_bytes = a;
+    for (int l = 0; l < L; l++) {
+        ChainLayer &c = ly[(size_t)l];
+        c.dep_in = -1; c.dep_out = -1; c.Kt_next = 0; c.R_prev = 0; c.rows_prev = 0;
+        if (l > 0) { c.dep_in = ly[(size_t)l - 1].dep_out; c.R_prev = ly[(size_t)l - 1].R; c.rows_prev = ly[(size_t)l - 1].rows; }
+        if (l + 1 < L) {
+            c.Kt_next = ly[(size_t)l + 1].Kt;
+            if (c.Kt_next % c.R) return VDC_EINVAL;                       // a row block must lie inside one vector tile of the next layer
+            if (c.Kt_next / c.R > 255) return VDC_EINVAL;
+            c.dep_out = dep;
+            dep += (int32_t)((c.rows + c.Kt_next - 1) / c.Kt_next);
+        }
+    }
+    if (dep > cfg.n_dep_ids) return VDC_EINVAL;
+    Tiler t{cfg, 0, 0, 0, B, 1, 4};
+    t.streams.resize((size_t)C * (1 + V));
+    for (int l = 0; l < L; l++) {
+        const ChainLayer &c = ly[(size_t)l];
+        const int64_t NB = (c.rows + c.R - 1) / c.R, nk_full = c.K / c.Kt, ktail = c.K % c.Kt;
+        const uint32_t nk = (uint32_t)(nk_full + (ktail ? 1 : 0));
+        const uint32_t R = (uint32_t)c.R, Kt = (uint32_t)c.Kt;
+        const uint32_t dm = t.desc(0, R, Kt * 4, Kt * 4, (uint64_t)c.K * 4), dx = t.desc(1, (uint32_t)B, Kt * 4, Kt * 4, (uint64_t)c.K * 4);
+        const uint32_t dmt = ktail ? t.desc(0, R, (uint32_t)ktail * 4, Kt * 4, (uint64_t)c.K * 4) : 0;
+        const uint32_t dxt = ktail ? t.desc(1, (uint32_t)B, (uint32_t)ktail * 4, Kt * 4, (uint64_t)c.K * 4) : 0;
+        const uint32_t m_slots = t.slots_for((uint64_t)R * Kt * 4), x_slots = t.slots_for((uint64_t)B * Kt * 4), y_slots = t.slots_for((uint64_t)B * R * 4);
+        const uint32_t x_flags = l > 0 ? (uint32_t)F_DEVICE : 0u;
+        for (int core = 0; core < C; core++) {
+            const int64_t b0 = NB * core / C, b1 = NB * (core + 1) / C;
+            auto &vm = t.vmc(core);
+            bool first = true;
+            for (int64_t b = b0; b < b1; b += V) {
+                const int n = (int)std::min<int64_t>(V, b1 - b);
+                auto rows_valid = [&](int64_t blk) { return (uint32_t)std::min<int64_t>(R, c.rows - blk * R); };
+                if (first && l > 0) {
+                    // the core's first pass over this layer's vector tiles: every tile waits for the row blocks of the
+                    // layer before that produce it
+                    for (uint32_t kt = 0; kt < nk; kt++) {
+                        const bool tail = ktail && kt == nk - 1;
+                        const int64_t in_tile = std::min<int64_t>(Kt, c.rows_prev - (int64_t)kt * Kt);
+                        const uint32_t producers = (uint32_t)((in_tile + c.R_prev - 1) / c.R_prev);
+                        for (int i = 0; i < n; i++) {
+                            const int64_t blk = b + i;
+                            vm.push_back(encode(OP_LOAD, F_SEND | F_NT, t.flow_m(i), i, 0, m_slots, rows_valid(blk), 0,
+                                                c.w_off + (blk * R * c.K + (int64_t)kt * Kt) * 4, tail ? dmt : dm, 0));
+                            vm.push_back(encode(OP_LOAD, F_SEND | F_DEP_RECV | F_DEVICE, t.flow_x(i), i, 0, x_slots, (uint32_t)B,
+                                                (uint32_t)(c.dep_in + (int32_t)kt), c.x_off + (int64_t)kt * Kt * 4, tail ? dxt : dx, producers));
+                        }
+                    }
+                } else {
+                    // one accumulator (2) runs along K for the matrix and the vector tiles of the row blocks of this step
+                    vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, 0, 0, 0));
+                    auto pairs = [&](uint32_t d_m, uint32_t d_x) {
+                        for (int i = 0; i < n; i++) {
+                            const int64_t blk = b + i;
+                            vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | F_NT, t.flow_m(i), i, 2, m_slots, rows_valid(blk), 0, c.w_off + blk * R * c.K * 4, d_m, 0));
+                            vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | x_flags, t.flow_x(i), i, 2, x_slots, (uint32_t)B, 0, c.x_off, d_x, 0));
+                        }
+                    };
+                    if (nk_full > 0) {
+                        if (nk_full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full, 0, 0));
+                        pairs(dm, dx);
+                        vm.push_back(encode(nk_full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                    }
+                    if (ktail) pairs(dmt, dxt);
+                }
+                first = false;
+                for (int i = 0; i < n; i++) {
+                    const int64_t blk = b + i;
+                    const uint32_t dy = t.desc(2, (uint32_t)B, rows_valid(blk) * 4, R * 4, (uint64_t)c.rows * 4);
+                    const bool sig = c.dep_out >= 0;
+                    vm.push_back(encode(OP_STORE, F_SEND | F_RECV | (sig ? (uint32_t)(F_DEP_SEND | F_DEVICE) : 0u), t.flow_y(i), i, 0, y_slots, (uint32_t)B,
+                                        sig ? (uint32_t)(c.dep_out + (int32_t)(blk * R / c.Kt_next)) : 0u, c.y_off + blk * R * 4, dy, 0));
+                    t.vcc(core, i).push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, nk, 0, matvec_imm((uint32_t)B, R, Kt / 4), 0, 0));
+                }
+            }
+        }
+    }
+    words.clear();
+    sb.assign(1, 0);
+    for (auto &st : t.streams) {
+        words.insert(words.end(), st.begin(), st.end());
+        words.push_back(encode(OP_HALT, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
+        sb.push_back((uint32_t)words.size());
+    }
+    descs = t.descs;
+    if (descs.empty()) descs.push_back(Desc{0, 1, 16, 16, 0, 0, 0, 0});
+    if (descs.size() > 256) return VDC_EINVAL;
+    return VDC_OK;
+}
+
 // Memory uops with no arithmetic behind them (Section 6.3, "Memory virtual core overhead"): the byte range
 // [0, bytes) in blocks of tile_bytes.  mode 0: every block is loaded (tensor 0) and dropped; mode 1: every block of
 // tensor 0 is written with copies of `value`; mode 2: every block is loaded from tensor 0, moved to an output region and
@@ -1223,6 +1353,8 @@ int vdc_program_destroy(vdc_program *prog) {
         it = (it->second == prog) ? ex->matvec_cache.erase(it) : it + 1;
     for (auto it = ex->stream_cache.begin(); it != ex->stream_cache.end();)
         it = (it->second == prog) ? ex->stream_cache.erase(it) : it + 1;
+    for (auto it = ex->chain_cache.begin(); it != ex->chain_cache.end();)
+        it = (it->second == prog) ? ex->chain_cache.erase(it) : it + 1;
     for (auto it = ex->attn_cache.begin(); it != ex->attn_cache.end();)
         it = (it->second == prog) ? ex->attn_cache.erase(it) : it + 1;
     (void)hipFree(prog->d_words);
@@ -1378,6 +1510,49 @@ int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, 
         memcpy(init, ws.data(), ws.size() * 4);
     }
     return VDC_OK;
+}
+
+int vdc_matvec_chain(vdc_executor *ex, const float *W, float *A, const int64_t *dims, int32_t L, int32_t B, int32_t tile_bytes,
+                     void *hip_stream) {
+    if (!ex || ex->cfg.device == -1 || !W || !A || !dims || L < 1 || ((uintptr_t)W & 15u) || ((uintptr_t)A & 15u)) return VDC_EINVAL;
+    vdc_program *prog = nullptr;
+    for (auto &kv : ex->chain_cache)
+        if (kv.first.B == B && kv.first.tile_bytes == tile_bytes && (int32_t)kv.first.dims.size() == L + 1 &&
+            std::equal(kv.first.dims.begin(), kv.first.dims.end(), dims)) { prog = kv.second; break; }
+    if (!prog) {
+        std::vector<Word> words;
+        std::vector<uint32_t> sb;
+        std::vector<Desc> descs;
+        int64_t w_bytes = 0, a_bytes = 0;
+        int rc = build_chain(ex->cfg, dims, L, B, tile_bytes, words, sb, descs, w_bytes, a_bytes);
+        if (rc != VDC_OK) return rc;
+        int64_t tb[3] = {w_bytes, a_bytes, a_bytes};
+        rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb, 3, &prog);
+        if (rc != VDC_OK) return rc;
+        ex->chain_cache.push_back({{std::vector<int64_t>(dims, dims + L + 1), B, tile_bytes}, prog});
+    }
+    void *bases[3] = {(void *)W, (void *)A, (void *)A};
+    return vdc_run(ex, prog, bases, 3, hip_stream);
+}
+
+int vdc_matvec_chain_program(vdc_executor *ex, const int64_t *dims, int32_t L, int32_t B, int32_t tile_bytes, void *uops, int64_t *n_uops,
+                             uint32_t *stream_begin, void *descs, int32_t *n_descs) {
+    if (!ex || !n_uops || !n_descs) return VDC_EINVAL;
+    std::vector<Word> words;
+    std::vector<uint32_t> sb;
+    std::vector<Desc> ds;
+    int64_t w_bytes = 0, a_bytes = 0;
+    int rc = build_chain(ex->cfg, dims, L, B, tile_bytes, words, sb, ds, w_bytes, a_bytes);
+    if (rc != VDC_OK) return rc;
+    const int64_t cap_w = *n_uops;
+    const int32_t cap_d = *n_descs;
+    *n_uops = (int64_t)words.size();
+    *n_descs = (int32_t)ds.size();
+    bool fits = true;
+    if (uops) { if (cap_w >= (int64_t)words.size()) memcpy(uops, words.data(), words.size() * sizeof(Word)); else fits = false; }
+    if (descs) { if (cap_d >= (int32_t)ds.size()) memcpy(descs, ds.data(), ds.size() * sizeof(Desc)); else fits = false; }
+    if (stream_begin) memcpy(stream_begin, sb.data(), sb.size() * sizeof(uint32_t));
+    return fits ? VDC_OK : VDC_EINVAL;
 }
 
 int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const float *V, const int64_t *row_off, int32_t n_seg,

@@ -825,10 +825,12 @@ DEV void wait_vmcnt_le(uint32_t n) {
 #undef VDC_W
 }
 
-DEV void load_lds_b128(uint32_t lds_addr_wave, const char *gptr, bool nt) {
+DEV void load_lds_b128(uint32_t lds_addr_wave, const char *gptr, bool nt, bool device) {
     // LDS address = M0 + lane * 16 (wave-uniform base in M0, one 16-byte chunk per active lane)
     lds_addr_wave = uni(lds_addr_wave);
-    if (nt)
+    if (device)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off sc1" ::"s"(lds_addr_wave), "v"(gptr) : "memory");
+    else if (nt)
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_addr_wave), "v"(gptr) : "memory");
     else
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr_wave), "v"(gptr) : "memory");
@@ -885,7 +887,7 @@ struct LduEnt {
     uint32_t key;               // table | window lane, 0xffffffff = empty
     uint32_t val;               // the static record itself: lanes 0..7
     uint32_t ni;                // load instructions per tile
-    uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path
+    uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path | 32 DEVICE
     uint32_t step_lo, step_hi;  // fast path: address step per load instruction
     uint32_t msg_lo, msg_hi;    // m2c entry without slot and ticket
     uint32_t m2c_base;          // vcc * kM2C
@@ -904,7 +906,7 @@ DEV void ldu_derive(Ctx &c, LduEnt &e, uint32_t key, uint32_t info) {
     const bool pow2 = (cpr & (cpr - 1u)) == 0u && cpr <= 64u;
     const bool fast = pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u;
     e.bits = ((flags & F_NT) ? 1u : 0u) | ((flags & F_SEND) ? 2u : 0u) | ((flags & F_DEP_SEND) ? 4u : 0u) |
-             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u);
+             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u) | ((flags & F_DEVICE) ? 32u : 0u);
     uint32_t sh = 0, drow = 0;
     if (pow2) { sh = __builtin_ctz(cpr); drow = 64u >> sh; }
     const uint64_t step = (uint64_t)drow * gpitch;
@@ -1031,7 +1033,15 @@ DEV void ldu_main(Ctx &c) {
                  : [g] "+v"(ga) : [dst] "s"(dst), [step] "s"(step) : "memory", "scc")
             uint64_t ga = (uint64_t)(uintptr_t)g;
             uint32_t i = 0;
-            if (bits & 1u) {
+            if (bits & 32u) {
+                // device scope: the tile may have been written by another core during this run
+                for (; i + 4u <= ni; i += 4u) { VDC_LOAD4(" sc1"); dst += 4096u; }
+                for (; i < ni; i++) {
+                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off sc1" ::"s"(dst), "v"(ga) : "memory");
+                    dst += 1024u;
+                    ga += step;
+                }
+            } else if (bits & 1u) {
                 for (; i + 4u <= ni; i += 4u) { VDC_LOAD4(" nt"); dst += 4096u; }
                 for (; i < ni; i++) {
                     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(dst), "v"(ga) : "memory");
@@ -1063,7 +1073,7 @@ DEV void ldu_main(Ctx &c) {
                 const uint32_t dst = lds_base + lds_off + i * 1024u;
                 const bool inside = q < total;
                 const bool valid = inside && row < rows && col < vcr;
-                if (valid) load_lds_b128(dst, g, nt);
+                if (valid) load_lds_b128(dst, g, nt, (bits & 32u) != 0u);
                 if (inside && !valid) {
                     u32x4 z = {0u, 0u, 0u, 0u};
                     lds_st128(lds_off + q * 16u, z);             // the box outside the valid tile reads as zero
@@ -1283,7 +1293,7 @@ DEV void stu_main(Ctx &c) {
                             loff += l_step + (wrap ? l_wrap : 0u);
                             goff += g_step + (wrap ? g_wrap : 0ull);
                         }
-                        if (flags & F_DEP_SEND) {
+                        if (flags & (F_DEP_SEND | F_DEVICE)) {
 #pragma unroll
                             for (int q = 0; q < 4; q++) gst128_lanes_device(on[q], ga[q], v[q]);
                         } else {

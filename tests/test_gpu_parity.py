@@ -440,6 +440,70 @@ def test_attention_refuses_what_it_does_not_support(ex):
         ex.attn_decode(dQ[:, :64].contiguous(), dK, dV, ro, dO, 4096)      # d = 64
 
 
+CHAIN_CASES = [
+    # dims = (K_0, rows_0, rows_1, ...), B, tile_bytes
+    ((4096, 4096, 4096, 4096), 1, 16384),
+    ((1024, 4096, 1024), 4, 8192),
+    ((1000, 516, 2052, 12), 2, 4096),            # K tails and row tails; a last layer of one row block
+    ((8192, 32768, 8192), 1, 16384),             # several row blocks per compute core: later ones follow the waiting loads
+    ((2048, 2048, 2048, 2048, 2048, 2048, 2048, 2048, 2048), 8, 16384),
+]
+
+
+@pytest.mark.parametrize("dims,B,T", CHAIN_CASES)
+def test_chain_of_matvecs_in_one_launch(ex, dims, B, T):
+    """Every layer against the fp64 product of its own input as the GPU stored it (so the bar of a single matvec applies
+    per layer).  The chain runs twice on the same buffers with different X: a tile that was read from a cache left over
+    from the first run, or before its producers had stored it, would show in the second."""
+    rng = np.random.default_rng(sum(dims) + B)
+    L = len(dims) - 1
+    Ms = [(rng.standard_normal((dims[l + 1], dims[l])) / np.sqrt(dims[l])).astype(np.float32) for l in range(L)]
+    dW = _dev(np.concatenate([m.ravel() for m in Ms]))
+    a_off = np.concatenate([[0], np.cumsum([B * x for x in dims])])
+    dA = torch.full((int(a_off[-1]),), float("nan"), device="cuda")
+    for rep in range(2):
+        X = rng.standard_normal((B, dims[0])).astype(np.float32)
+        dA[:B * dims[0]] = _dev(X.ravel())
+        ex.matvec_chain(dW, dA, dims, B, T)
+        ex.check()
+        Ah = dA.cpu().numpy()
+        assert not np.isnan(Ah).any()
+        prev = X
+        for l in range(L):
+            Y = Ah[a_off[l + 1]:a_off[l + 2]].reshape(B, dims[l + 1])
+            Yr, Ya = gemv_ref.gemv_dense(Ms[l], prev)
+            _check(Y, Yr, Ya, "chain %s layer %d run %d" % (dims, l, rep))
+            prev = Y
+
+
+def test_chain_traces_match_the_interpreter():
+    dims, B, T = (256, 512, 128, 256), 2, 4096
+    rng = np.random.default_rng(12)
+    L = len(dims) - 1
+    Ms = [(rng.standard_normal((dims[l + 1], dims[l])) / np.sqrt(dims[l])).astype(np.float32) for l in range(L)]
+    W = np.concatenate([m.ravel() for m in Ms])
+    X = rng.standard_normal((B, dims[0])).astype(np.float32)
+    with vdc.Executor(n_cores=4, slot_bytes=4096, n_slots=12) as ex:
+        words, sb, descs = ex.matvec_chain_program(dims, B, T)
+        nA = B * sum(dims)
+        prog = ex.program_create(words, sb, descs, [W.nbytes, nA * 4, nA * 4])
+        dA = torch.full((nA,), float("nan"), device="cuda")
+        dA[:B * dims[0]] = _dev(X.ravel())
+        trace, count = ex.run(prog, [_dev(W), dA, dA], trace_cap=1024)
+        ex.check()
+        Ao = np.full(nA, np.nan, np.float32)
+        Ao[:B * dims[0]] = X.ravel()
+        m = UM.Machine(words, sb, descs, [W, Ao, Ao], n_cores=4, slot_bytes=4096, n_slots=12, n_dep_ids=1024).run()
+        trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+        for core in range(4):
+            exp = [(pc, op | (dd << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, dd, off, n) in m.trace_vmc[core]]
+            assert count[core * 3] == len(exp)
+            assert [tuple(int(x) for x in r) for r in trace[core * 3, :len(exp)]] == exp
+        # fp32 on the GPU against fp64 in the interpreter, through three layers
+        assert np.allclose(dA.cpu().numpy(), Ao, rtol=1e-4, atol=1e-5)
+        prog.destroy()
+
+
 def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):
     """vdc_run enqueues kernels only (counters are cleared by a fill kernel, never by a memset node), so a caller may
     capture it; every replay, with eager work and synchronisations in between, must equal the eager result."""

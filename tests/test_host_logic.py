@@ -304,3 +304,54 @@ def test_attention_items_balance_over_the_compute_cores():
         total = sum(-(-int(L) // 32) for L in lengths)
         assert sum(per_vcc) == total
         assert max(per_vcc) <= total / 32 + max(1, -(-total // 128)) + 1
+
+
+# ---- a chain of matvec operators in one uop graph (Section 3; Section 4.1, depId dependencies) ---------
+@pytest.mark.parametrize("dims,B,T,ncores,slot,nslots", [
+    ((256, 256), 1, 4096, 2, 4096, 8),                      # one layer: nothing waits
+    ((128, 256, 64, 192), 2, 4096, 2, 4096, 10),            # three layers, more than one row block per compute core
+    ((200, 100, 36), 1, 4096, 3, 4096, 8),                  # K tails and row tails in a chain
+    ((512, 128, 128, 128, 128), 3, 8192, 4, 8192, 8),       # fewer row blocks than compute cores from layer 0 on
+])
+def test_chain_program_on_the_oracle_interpreter(dims, B, T, ncores, slot, nslots):
+    rng = np.random.default_rng(sum(dims))
+    L = len(dims) - 1
+    Ms = [(rng.standard_normal((dims[l + 1], dims[l])) / np.sqrt(dims[l])).astype(np.float32) for l in range(L)]
+    X = rng.standard_normal((B, dims[0])).astype(np.float32)
+    W = np.concatenate([m.ravel() for m in Ms])
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
+        w, sb, d = ex.matvec_chain_program(dims, B, T)
+        a_bytes = 4 * B * sum(dims)
+        rc, msg = ex.program_validate(w, sb, d, [W.nbytes, a_bytes, a_bytes])
+        assert rc == vdc.VDC_OK, msg
+    ops, flags = w[:, 0] & 0xFF, (w[:, 0] >> 8) & 0xFF
+    if L > 1:
+        assert ((ops == A.LOAD) & ((flags & A.F_DEP_RECV) != 0)).any() and ((ops == A.STORE) & ((flags & A.F_DEP_SEND) != 0)).any()
+    else:
+        assert not (flags & (A.F_DEP_RECV | A.F_DEP_SEND)).any()
+    a_off = np.concatenate([[0], np.cumsum([B * x for x in dims])])
+    ref = None
+    for sched, seed in (("program", 0), ("random", 1), ("random", 2)):
+        Abuf = np.full(B * sum(dims), np.nan, np.float32)      # a tile read before it is written poisons the result
+        Abuf[:B * dims[0]] = X.ravel()
+        m = UM.Machine(w, sb, d, [W, Abuf, Abuf], n_cores=ncores, slot_bytes=slot, n_slots=nslots, n_dep_ids=1024)
+        m.run(sched, seed)
+        m.check_final()
+        assert not np.isnan(Abuf).any()
+        prev = X
+        for l in range(L):
+            Y = Abuf[a_off[l + 1]:a_off[l + 2]].reshape(B, dims[l + 1])
+            Yr, Ya = gemv_ref.gemv_dense(Ms[l], prev)
+            assert np.all(np.abs(Y - Yr) <= 1e-7 * Ya + 1e-30), (sched, l)
+            prev = Y
+        ref = ref if ref is not None else Abuf.tobytes()
+        assert Abuf.tobytes() == ref
+
+
+def test_chain_program_rejects_what_it_cannot_chain():
+    with vdc.Executor(device=-1, n_cores=2, n_dep_ids=4) as ex:
+        with pytest.raises(vdc.VdcError):
+            ex.matvec_chain_program((4096, 4096, 4096), 1, 16384)      # 16 vector tiles in layer 1, four depIds
+        with pytest.raises(vdc.VdcError):
+            ex.matvec_chain_program((4096, 4098), 1, 16384)            # not a multiple of 4
+        ex.matvec_chain_program((4096, 4096), 1, 16384)
