@@ -176,9 +176,9 @@ int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, 
  * W (device, 16-byte aligned): the matrices back to back, M_l as [dims[l + 1]][dims[l]] fp32, row-major.
  * A (device, 16-byte aligned): the activations back to back, X as [B][dims[0]], then every Y_l as [B][dims[l + 1]];
  *   the caller writes X, the run writes every Y_l (all of them stay readable).  1 <= B <= 8, L <= 64.
- * A layer starts on a vector tile as soon as the row blocks of the layer before that produce it have been stored: their
- * stores signal the tile's depId and the first loads of the tile wait for it; nothing waits for a whole layer.  Needs
- * one depId per vector tile of layers 1 .. L-1 (n_dep_ids of the executor).  Asynchronous on hip_stream; programs are
+ * A layer starts on a group of (at most 32) vector tiles as soon as the row blocks of the layer before that produce them
+ * have been stored: their stores signal the group's depId and the first load of the group waits for it; nothing waits
+ * for a whole layer.  Needs one depId per group of layers 1 .. L-1 (n_dep_ids of the executor).  Asynchronous on hip_stream; programs are
  * cached by (dims, B, tile_bytes).  VDC_EINVAL for shapes the tiler cannot chain. */
 int vdc_matvec_chain(vdc_executor *ex, const float *W, float *A, const int64_t *dims, int32_t L, int32_t B,
                      int32_t tile_bytes, void *hip_stream);

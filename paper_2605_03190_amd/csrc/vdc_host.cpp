@@ -854,16 +854,19 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
 // dims[l + 1] = rows of M_l.  Tensors: 0 = W, the matrices back to back (M_l is [dims[l + 1]][dims[l]], row-major);
 // 1 and 2 = A, the activations back to back (X as [B][dims[0]], then every Y_l as [B][dims[l + 1]]), read as tensor 1
 // and written as tensor 2.  Every layer is tiled like a single matvec (choose_tile) and its row blocks are dealt to the
-// cores in contiguous ranges.  The vector tile kt of layer l + 1 is a range of rows of Y_l: the row blocks of layer l
-// inside that range signal depId (l, kt) with their stores (written through at device scope), and a core's first pass
-// over the vector tiles of a layer waits for them tile by tile, so a layer starts on a tile as soon as that tile is
-// complete, not when the layer before it has ended.  Later row blocks of the same core and layer need no wait: their
+// cores in contiguous ranges.  The vector tile kt of layer l + 1 is a range of rows of Y_l.  Vector tiles are taken in
+// groups of G (at most 32, and at most 255 producing row blocks): the row blocks of layer l inside a group's rows signal
+// the group's depId with their stores (written through at device scope), and on a core's first pass over the vector
+// tiles of a layer the first load of every group waits for it, so a layer starts on a group of tiles as soon as that
+// group is complete, not when the layer before it has ended.  (A wait costs a round trip to the counter: one per
+// tile made a pass over K three times longer.)  Later row blocks of the same core and layer need no wait: their
 // loads follow the waiting ones on the same load unit.  All vector tiles of layers after the first are read at device
 // scope.  Within a stream a layer's uops precede the next layer's, and layer 0 waits for nothing: by induction over
 // the layers no wait can last forever (Section 4.3, "Avoiding Deadlock").
 struct ChainLayer {
     int64_t K, rows, w_off, x_off, y_off;
     int32_t R, Kt, R_prev, Kt_next;
+    int32_t G, G_next;           // vector tiles per dependency group: of this layer, of the next
     int64_t rows_prev;
     int32_t dep_in, dep_out;     // first depId of this layer's vector tiles / of its outputs; -1: none
 };
@@ -890,14 +893,19 @@ int build_chain(const vdc_config &cfg, const int64_t *dims, int32_t L, int32_t B
     w_bytes = w; a_bytes = a;
     for (int l = 0; l < L; l++) {
         ChainLayer &c = ly[(size_t)l];
-        c.dep_in = -1; c.dep_out = -1; c.Kt_next = 0; c.R_prev = 0; c.rows_prev = 0;
-        if (l > 0) { c.dep_in = ly[(size_t)l - 1].dep_out; c.R_prev = ly[(size_t)l - 1].R; c.rows_prev = ly[(size_t)l - 1].rows; }
+        c.dep_in = -1; c.dep_out = -1; c.Kt_next = 0; c.R_prev = 0; c.rows_prev = 0; c.G = 1; c.G_next = 1;
+        if (l > 0) {
+            c.dep_in = ly[(size_t)l - 1].dep_out; c.R_prev = ly[(size_t)l - 1].R; c.rows_prev = ly[(size_t)l - 1].rows;
+            c.G = ly[(size_t)l - 1].G_next;
+        }
         if (l + 1 < L) {
             c.Kt_next = ly[(size_t)l + 1].Kt;
             if (c.Kt_next % c.R) return VDC_EINVAL;                       // a row block must lie inside one vector tile of the next layer
-            if (c.Kt_next / c.R > 255) return VDC_EINVAL;
+            const int32_t per_tile = c.Kt_next / c.R;
+            if (per_tile > 255) return VDC_EINVAL;
+            c.G_next = std::max(1, std::min(32, 255 / per_tile));
             c.dep_out = dep;
-            dep += (int32_t)((c.rows + c.Kt_next - 1) / c.Kt_next);
+            dep += (int32_t)((c.rows + (int64_t)c.Kt_next * c.G_next - 1) / ((int64_t)c.Kt_next * c.G_next));
         }
     }
     if (dep > cfg.n_dep_ids) return VDC_EINVAL;
@@ -920,37 +928,42 @@ int build_chain(const vdc_config &cfg, const int64_t *dims, int32_t L, int32_t B
             for (int64_t b = b0; b < b1; b += V) {
                 const int n = (int)std::min<int64_t>(V, b1 - b);
                 auto rows_valid = [&](int64_t blk) { return (uint32_t)std::min<int64_t>(R, c.rows - blk * R); };
+                auto pairs = [&](uint32_t d_m, uint32_t d_x, uint32_t xf, uint32_t dep_id, uint32_t dep_count) {
+                    for (int i = 0; i < n; i++) {
+                        const int64_t blk = b + i;
+                        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | F_NT, t.flow_m(i), i, 2, m_slots, rows_valid(blk), 0, c.w_off + blk * R * c.K * 4, d_m, 0));
+                        vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | xf, t.flow_x(i), i, 2, x_slots, (uint32_t)B, dep_id, c.x_off, d_x, dep_count));
+                    }
+                };
                 if (first && l > 0) {
-                    // the core's first pass over this layer's vector tiles: every tile waits for the row blocks of the
-                    // layer before that produce it
-                    for (uint32_t kt = 0; kt < nk; kt++) {
-                        const bool tail = ktail && kt == nk - 1;
-                        const int64_t in_tile = std::min<int64_t>(Kt, c.rows_prev - (int64_t)kt * Kt);
-                        const uint32_t producers = (uint32_t)((in_tile + c.R_prev - 1) / c.R_prev);
-                        for (int i = 0; i < n; i++) {
-                            const int64_t blk = b + i;
-                            vm.push_back(encode(OP_LOAD, F_SEND | F_NT, t.flow_m(i), i, 0, m_slots, rows_valid(blk), 0,
-                                                c.w_off + (blk * R * c.K + (int64_t)kt * Kt) * 4, tail ? dmt : dm, 0));
-                            vm.push_back(encode(OP_LOAD, F_SEND | F_DEP_RECV | F_DEVICE, t.flow_x(i), i, 0, x_slots, (uint32_t)B,
-                                                (uint32_t)(c.dep_in + (int32_t)kt), c.x_off + (int64_t)kt * Kt * 4, tail ? dxt : dx, producers));
+                    // the core's first pass over this layer's vector tiles: the first tile of every group waits for the row
+                    // blocks of the layer before that produce the group; the rest of the group follows it on the same load
+                    // unit.  One accumulator (2) runs along K.
+                    for (uint32_t kt0 = 0; kt0 < nk; kt0 += (uint32_t)c.G) {
+                        const uint32_t kt1 = std::min<uint32_t>(nk, kt0 + (uint32_t)c.G);
+                        const int64_t in_group = std::min<int64_t>((int64_t)Kt * c.G, c.rows_prev - (int64_t)kt0 * Kt);
+                        const uint32_t producers = (uint32_t)((in_group + c.R_prev - 1) / c.R_prev);
+                        const bool first_is_tail = ktail && kt0 == nk - 1;
+                        vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, (int64_t)kt0 * Kt * 4, 0, 0));
+                        pairs(first_is_tail ? dmt : dm, first_is_tail ? dxt : dx, F_DEVICE | F_DEP_RECV, (uint32_t)(c.dep_in + (int32_t)(kt0 / (uint32_t)c.G)), producers);
+                        vm.push_back(encode(OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
+                        const int64_t full = std::min<int64_t>(kt1, nk_full) - (int64_t)(kt0 + 1);
+                        if (full > 0) {
+                            if (full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, full, 0, 0));
+                            pairs(dm, dx, F_DEVICE, 0, 0);
+                            vm.push_back(encode(full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
                         }
+                        if (ktail && kt1 == nk && !first_is_tail) pairs(dmt, dxt, F_DEVICE, 0, 0);
                     }
                 } else {
                     // one accumulator (2) runs along K for the matrix and the vector tiles of the row blocks of this step
                     vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, 0, 0, 0));
-                    auto pairs = [&](uint32_t d_m, uint32_t d_x) {
-                        for (int i = 0; i < n; i++) {
-                            const int64_t blk = b + i;
-                            vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | F_NT, t.flow_m(i), i, 2, m_slots, rows_valid(blk), 0, c.w_off + blk * R * c.K * 4, d_m, 0));
-                            vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC | x_flags, t.flow_x(i), i, 2, x_slots, (uint32_t)B, 0, c.x_off, d_x, 0));
-                        }
-                    };
                     if (nk_full > 0) {
                         if (nk_full > 1) vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full, 0, 0));
-                        pairs(dm, dx);
+                        pairs(dm, dx, x_flags, 0, 0);
                         vm.push_back(encode(nk_full > 1 ? OP_REPEAT : OP_ADD, 0, 0, 0, 2, 0, 0, 0, (int64_t)Kt * 4, 0, 0));
                     }
-                    if (ktail) pairs(dmt, dxt);
+                    if (ktail) pairs(dmt, dxt, x_flags, 0, 0);
                 }
                 first = false;
                 for (int i = 0; i < n; i++) {
@@ -958,7 +971,7 @@ int build_chain(const vdc_config &cfg, const int64_t *dims, int32_t L, int32_t B
                     const uint32_t dy = t.desc(2, (uint32_t)B, rows_valid(blk) * 4, R * 4, (uint64_t)c.rows * 4);
                     const bool sig = c.dep_out >= 0;
                     vm.push_back(encode(OP_STORE, F_SEND | F_RECV | (sig ? (uint32_t)(F_DEP_SEND | F_DEVICE) : 0u), t.flow_y(i), i, 0, y_slots, (uint32_t)B,
-                                        sig ? (uint32_t)(c.dep_out + (int32_t)(blk * R / c.Kt_next)) : 0u, c.y_off + blk * R * 4, dy, 0));
+                                        sig ? (uint32_t)(c.dep_out + (int32_t)(blk * R / ((int64_t)c.Kt_next * c.G_next))) : 0u, c.y_off + blk * R * 4, dy, 0));
                     t.vcc(core, i).push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, nk, 0, matvec_imm((uint32_t)B, R, Kt / 4), 0, 0));
                 }
             }

@@ -836,18 +836,23 @@ DEV void load_lds_b128(uint32_t lds_addr_wave, const char *gptr, bool nt, bool d
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr_wave), "v"(gptr) : "memory");
 }
 
-DEV bool dep_wait(Ctx &c, uint32_t dep) {
+// Is the dependency there?  One relaxed look at the counter.
+DEV bool dep_ready(Ctx &c, uint32_t dep) {
     uint32_t id = dep & 0xFFFFu, need = (dep >> 16) & 0xFFu;
     if (need == 0u) need = 1u;
+    return uni(__hip_atomic_load(&c.p->dep[id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >= need;
+}
+
+// Wait for it.  The counter is polled relaxed.  `acquire`: once it is there, one acquire at device scope (an invalidate
+// of this side's caches), for a load that reads through the caches; a load at device scope does not need it.
+DEV bool dep_wait(Ctx &c, uint32_t dep, bool acquire) {
     Spin s;
     for (;;) {
-        // the counter is polled relaxed; one acquire at device scope (an invalidate of this side's caches) once it is there
-        uint32_t v = uni(__hip_atomic_load(&c.p->dep[id], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        if (v >= need) {
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if (dep_ready(c, dep)) {
+            if (acquire) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             return true;
         }
-        if (!spin_step(c, s, uni(lds_vld32(c.ctl + CTL_OFF(abort))), 0x500u | id)) return false;
+        if (!spin_step(c, s, uni(lds_vld32(c.ctl + CTL_OFF(abort))), 0x500u | (dep & 0xFFFFu))) return false;
     }
 }
 
@@ -1005,15 +1010,22 @@ DEV void ldu_main(Ctx &c) {
         c.pc = c.stream_pc0 + rf_get(val, 6);
         if (bits & 8u) {
             // an unresolved dependency blocks this unit, and only this unit (Section 4.3).  Whatever is already in
-            // flight is delivered first: the awaited signal may depend on it
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            vm_out = 0;
-            for (; n_fl > 0; n_fl--, fl_head++) {
-                const uint32_t k = fl_head & (kMaxInflight - 1);
-                Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
-                ldu_retire(c, o);
+            // flight is delivered first: the awaited signal may depend on it.  A dependency that is already there
+            // costs one look at its counter.
+            const uint32_t dep = rf_get(val, 5);
+            const bool acquire = (bits & 32u) == 0u;
+            if (dep_ready(c, dep)) {
+                if (acquire) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                vm_out = 0;
+                for (; n_fl > 0; n_fl--, fl_head++) {
+                    const uint32_t k = fl_head & (kMaxInflight - 1);
+                    Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
+                    ldu_retire(c, o);
+                }
+                if (!dep_wait(c, dep, acquire)) { ok = false; break; }
             }
-            if (!dep_wait(c, rf_get(val, 5))) { ok = false; break; }
         }
         if (bits & 16u) {
             // the usual case: whole tile, a power-of-two row of at most 64 chunks.  Every instruction moves 64 / cpr

@@ -349,9 +349,9 @@ def test_chain_program_on_the_oracle_interpreter(dims, B, T, ncores, slot, nslot
 
 
 def test_chain_program_rejects_what_it_cannot_chain():
-    with vdc.Executor(device=-1, n_cores=2, n_dep_ids=4) as ex:
+    with vdc.Executor(device=-1, n_cores=2, n_dep_ids=1) as ex:
         with pytest.raises(vdc.VdcError):
-            ex.matvec_chain_program((4096, 4096, 4096), 1, 16384)      # 16 vector tiles in layer 1, four depIds
+            ex.matvec_chain_program((4096, 4096, 4096), 1, 16384)      # two groups of vector tiles in layer 1, one depId
         with pytest.raises(vdc.VdcError):
             ex.matvec_chain_program((4096, 4098), 1, 16384)            # not a multiple of 4
         ex.matvec_chain_program((4096, 4096), 1, 16384)
