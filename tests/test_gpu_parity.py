@@ -502,6 +502,24 @@ def test_chain_traces_match_the_interpreter():
         # fp32 on the GPU against fp64 in the interpreter, through three layers
         assert np.allclose(dA.cpu().numpy(), Ao, rtol=1e-4, atol=1e-5)
         prog.destroy()
+        # the oracle-side assembler's chain (a dependency on every vector tile, row blocks dealt round-robin), twice
+        p, w_off, a_off = A.chain_matvec_program(dims, B, 8, 128, 4096, 4)
+        words, sb, descs = p.finish()
+        prog = ex.program_create(words, sb, descs, [W.nbytes, nA * 4, nA * 4])
+        for rep in range(2):
+            X2 = rng.standard_normal((B, dims[0])).astype(np.float32)
+            dA.fill_(float("nan"))
+            dA[:B * dims[0]] = _dev(X2.ravel())
+            ex.run(prog, [_dev(W), dA, dA])
+            ex.check()
+            Ah = dA.cpu().numpy()
+            prev = X2
+            for l in range(L):
+                Y = Ah[a_off[l + 1] // 4:a_off[l + 1] // 4 + B * dims[l + 1]].reshape(B, dims[l + 1])
+                Yr, Ya = gemv_ref.gemv_dense(Ms[l], prev)
+                _check(Y, Yr, Ya, "oracle-assembled chain layer %d run %d" % (l, rep))
+                prev = Y
+        prog.destroy()
 
 
 def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):
