@@ -1224,7 +1224,9 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.prof = ex->d_prof;
 #endif
     HIP_TRY(hipSetDevice(ex->cfg.device));
-    if (prog->uses_dep) HIP_TRY(launch_clear(ex->d_dep, prog->max_dep_id + 1, stream));
+    // the depId counters are zero between runs: the core that finishes last clears the ones its program used
+    p.finished = ex->d_status + ST_WORDS + 3;
+    p.n_dep_used = prog->uses_dep ? prog->max_dep_id + 1 : 0;
     if (trace_count) HIP_TRY(launch_clear(trace_count, (uint32_t)(ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core)), stream));
     HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, trace != nullptr, stream));
     return VDC_OK;

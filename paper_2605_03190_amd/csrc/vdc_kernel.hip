@@ -1355,6 +1355,22 @@ DEV void stu_main(Ctx &c) {
         PHASE(c, 1u + c.p->n_ldu, have ? 6u : 5u);
         if (!spin_step(c, sp, rf_get(snap, 10), 0x700u | (have ? 0x80u : 0u))) ok = false;
     }
+    // The store unit is the last of its core to touch a depId counter (every signal and every wait of the core lies
+    // before the last region comes back).  The core that leaves last, of all cores, puts the counters the program used
+    // back to zero for the next run: no clearing launch between runs, also after a run that was aborted.
+    if (c.p->n_dep_used != 0u) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        uint32_t before = 0;
+        if (c.lane == 0) before = __hip_atomic_fetch_add(c.p->finished, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        reconverge();
+        before = uni(before);
+        if (before == gridDim.x - 1u) {
+            for (uint32_t i = c.lane; i < c.p->n_dep_used; i += 64u)
+                __hip_atomic_store(&c.p->dep[i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (c.lane == 0) __hip_atomic_store(c.p->finished, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            reconverge();
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -523,7 +523,7 @@ def test_chain_traces_match_the_interpreter():
 
 
 def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):
-    """vdc_run enqueues kernels only (counters are cleared by a fill kernel, never by a memset node), so a caller may
+    """vdc_run enqueues one kernel (the depId counters are put back to zero by the core that leaves last), so a caller may
     capture it; every replay, with eager work and synchronisations in between, must equal the eager result."""
     rows, K, B, T = 1024, 2048, 2, 8192
     rng = np.random.default_rng(9)
@@ -560,7 +560,7 @@ def test_runs_can_be_captured_in_a_hip_graph_and_replayed(ex):
 
 
 def test_attention_and_stream_runs_replay_from_a_hip_graph(ex):
-    """The depId counters are cleared by a fill kernel inside the run, so a captured attention run can be replayed; every
+    """The depId counters are put back to zero at the end of every run, so a captured attention run can be replayed; every
     replay is checked against the eager result, with eager work in between."""
     Q, K, V, ro = _attn_inputs([300, 40, 700], seed=3)
     dQ, dK, dV = _dev(Q), _dev(K), _dev(V)
