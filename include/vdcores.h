@@ -56,7 +56,7 @@ typedef struct {
     int32_t n_slots;        /* slots per core, 1..32; default = as many as fit in the CU's LDS        */
     int32_t n_ldu;          /* load units per VMC: 1, 2 or 4; default 4                                   */
     int32_t n_stu;          /* store units per VMC, must be 1 or 0 (=1)                               */
-    int32_t n_dep_ids;      /* size of the global depId table; default 1024                           */
+    int32_t n_dep_ids;      /* size of the global depId table; default 4096                           */
     int32_t watchdog_spins; /* polls before a waiting unit reports VDC_EDEADLOCK; default 1<<22       */
     int32_t tile_rows;      /* tuning knob of the matvec tiler: rows per matrix tile; 0 => automatic  */
     int32_t reserved[5];    /* must be zero                                                           */
@@ -194,7 +194,8 @@ int vdc_matvec_chain_program(vdc_executor *ex, const int64_t *dims, int32_t L, i
  *     O[s][t] = sum_r p_r V[r][t],  p = softmax_r(scale * sum_j Q[s][j] K[r][j]),  r in [row_off[s], row_off[s + 1])
  * Q [n_seg][d], O [n_seg][d], K and V [row_off[n_seg]][d] (the contexts back to back): device, fp32, row-major,
  * 16-byte aligned, caller-owned; row_off: host, n_seg + 1 offsets, row_off[0] = 0, every request at least one row.
- * d = 128; tile_bytes in {4096, 8192, 16384} (8, 16, 32 context rows per key / value tile); n_seg <= n_dep_ids.
+ * d = 128 or 64; tile_bytes in {4096, 8192, 16384} (tile_bytes / (4 d) context rows per key / value tile);
+ * n_seg <= n_dep_ids.
  * A context is cut into items of consecutive tiles that balance over the compute cores; every item leaves a partial row
  * (weighted values, running maximum, running sum) in a library-owned workspace and signals the request's depId; one
  * compute core per request merges its rows.  fp32 arithmetic, exp() of differences to the running maximum only.

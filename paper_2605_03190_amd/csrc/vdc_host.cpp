@@ -300,7 +300,7 @@ struct Validator {
             }
             if (f.opcode == OP_ATTN || f.opcode == OP_ATTN_MERGE) {
                 v.lpr = (uint32_t)f.imm & 0xFFu;
-                v.R = f.opcode == OP_ATTN ? (uint32_t)(f.imm >> 8) & 0xFFu : 8u;
+                v.R = f.opcode == OP_ATTN ? (uint32_t)(f.imm >> 8) & 0xFFu : 16u;     // a merge has no tile rows: any supported value
                 if (!attn_geometry_ok(v.lpr, v.R)) { fail("attn geometry not supported"); return -1; }
                 if (f.size < 1 || (f.opcode == OP_ATTN_MERGE && f.size > kAttnMaxPartials)) { fail("attn: bad size"); return -1; }
                 v.left = f.size;
@@ -1084,7 +1084,7 @@ int build_stream(const vdc_config &cfg, int32_t mode, int64_t bytes, uint32_t va
 // (Section 4.3, "Avoiding Deadlock").  The memory core's stream takes the steps of its compute cores in turn.
 int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int32_t d, float scale, int32_t tile_bytes,
                std::vector<Word> &words, std::vector<uint32_t> &sb, std::vector<Desc> &descs, int64_t &n_items) {
-    if (!row_off || n_seg < 1 || n_seg > cfg.n_dep_ids || d != 128 || row_off[0] != 0) return VDC_EINVAL;
+    if (!row_off || n_seg < 1 || n_seg > cfg.n_dep_ids || (d != 128 && d != 64) || row_off[0] != 0) return VDC_EINVAL;
     if (tile_bytes != 4096 && tile_bytes != 8192 && tile_bytes != 16384) return VDC_EINVAL;
     const uint32_t lpr = (uint32_t)d / 4, R = (uint32_t)tile_bytes / ((uint32_t)d * 4), row = (uint32_t)d * 4, prow = row + 16;
     if (!attn_geometry_ok(lpr, R)) return VDC_EINVAL;
@@ -1178,7 +1178,7 @@ int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     if (c.slot_bytes == 0) c.slot_bytes = 8192;
     if (c.n_ldu == 0) c.n_ldu = 4;
     if (c.n_stu == 0) c.n_stu = 1;
-    if (c.n_dep_ids == 0) c.n_dep_ids = 1024;
+    if (c.n_dep_ids == 0) c.n_dep_ids = 4096;
     if (c.watchdog_spins == 0) c.watchdog_spins = 1 << 22;
     if (c.n_cores < 1 || c.n_cores > cu_count) return VDC_EINVAL;   // all cores must be co-resident
     if (c.vcc_per_core < 1 || c.vcc_per_core > 2 || c.threads_per_eu != 128) return VDC_EINVAL;

@@ -125,10 +125,12 @@ inline int64_t fill_imm(uint32_t value, uint32_t chunks) { return (int64_t)value
 constexpr uint32_t kMaxStreamChunks = 2048;   // 32 KB: sixteen passes of the 128 threads of an execution unit
 
 // ATTN imm: lpr [7:0] = d / 4 (16-byte chunks per row of a key / value tile), R [15:8] (box rows of those tiles), the bits
-// of the fp32 factor on the scores [47:16].  ATTN_MERGE imm: lpr [7:0].  Supported: d = 128 (lpr = 32), R in {8, 16, 32}
-// (tiles of 4, 8, 16 KB), at most 64 partial rows per merge.
+// of the fp32 factor on the scores [47:16].  ATTN_MERGE imm: lpr [7:0].  Supported: d = 128 (lpr = 32) with R in {8, 16, 32}
+// and d = 64 (lpr = 16) with R in {16, 32, 64} (tiles of 4, 8, 16 KB), at most 64 partial rows per merge.
 inline int64_t attn_imm(uint32_t lpr, uint32_t R, uint32_t scale_bits) { return (int64_t)lpr | ((int64_t)R << 8) | ((int64_t)scale_bits << 16); }
-inline bool attn_geometry_ok(uint32_t lpr, uint32_t R) { return lpr == 32 && (R == 8 || R == 16 || R == 32); }
+inline bool attn_geometry_ok(uint32_t lpr, uint32_t R) {
+    return (lpr == 32 && (R == 8 || R == 16 || R == 32)) || (lpr == 16 && (R == 16 || R == 32 || R == 64));
+}
 constexpr uint32_t kAttnMaxPartials = 64;
 
 // The compute uop works on `threads_per_eu` = 128 threads; a matrix tile is NF passes of 128 chunks of

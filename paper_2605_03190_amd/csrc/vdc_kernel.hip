@@ -1768,33 +1768,34 @@ DEV float rows_reduce(float x) {
     return MAX ? __builtin_fmaxf(__builtin_fmaxf(t0, t1), __builtin_fmaxf(t2, t3)) : (t0 + t1) + (t2 + t3);
 }
 
-// The attn uop (Section 4.1) for decoding: one query row of 128 values against `size` (key tile, value tile) pairs of
+// The attn uop (Section 4.1) for decoding: one query row of d = 4 LPR values (128 or 64) against `size` (key tile, value tile) pairs of
 // R rows, FlashAttention-style: a running maximum m of the scores, a running sum l of exp(score - m) and the running
 // sums o of exp(score - m) times the value rows.  Both waves of the execution unit compute every score (so m and l
 // come out bit-identical in the two waves and no exchange between them is needed): the key tile is taken in NP passes
 // of RP <= 16 rows, G = 64 / RP lanes sharing a row.  Wave w then owns columns 64 w .. 64 w + 63 of o, one per lane.
 // The query tile is allocated first and handed back last, after every key and value tile: slots return in another
 // order than they went out (Section 4.3).  Rows of a short last tile score minus infinity.
-template <int R>
+template <int R, int LPR>
 DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
     constexpr int RP = R > 16 ? 16 : R;            // key rows per pass
     constexpr int NP = R / RP;                     // passes per tile
     constexpr uint32_t G = 64u / (uint32_t)RP;     // lanes per key row: 4 or 8
-    constexpr int NC = 32 / (int)G;                // 16-byte chunks of the row per lane: 8 or 4
-    constexpr uint32_t ROW = 512u;                 // bytes per row of a key / value tile
+    constexpr int NC = LPR / (int)G;               // 16-byte chunks of the row per lane: 8 or 4
+    constexpr uint32_t ROW = (uint32_t)LPR * 16u;  // bytes per row of a key / value tile (d = 4 LPR values)
+    constexpr uint32_t COLS = (uint32_t)LPR * 2u;  // columns of o a wave owns: 64 (one per lane) or 32 (the upper lanes repeat the lower)
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     Msg mq, unused;
     if (!vcc_pop_wait(c, vs, 1u, 0u, mq, unused)) return false;
     const uint32_t q_pay = vs.pay0;
     vs.head += 1u;                                 // popped; handed back at the end
     const uint32_t q_off = mq.slot << slot_shift;
-    // lane (row, sub) takes chunks (j G + sub + row) mod 32 of its key rows, j = 0 .. NC - 1: the rotation by the row
-    // spreads the lanes of one read over the banks (rows are 512 bytes apart, so equal columns would all collide)
+    // lane (row, sub) takes chunks (j G + sub + row) mod LPR of its key rows, j = 0 .. NC - 1: the rotation by the row
+    // spreads the lanes of one read over the banks (rows are 256 or 512 bytes apart, so equal columns would all collide)
     const uint32_t sub = c.lane & (G - 1u), row = c.lane / G, rot = sub + row;
     f32x4 qv[NC];
 #pragma unroll
-    for (int j = 0; j < NC; j++) qv[j] = lds_ld128(q_off + (((uint32_t)j * G + rot) & 31u) * 16u);
-    const uint32_t col = vs.wv * 64u + c.lane;
+    for (int j = 0; j < NC; j++) qv[j] = lds_ld128(q_off + (((uint32_t)j * G + rot) & (uint32_t)(LPR - 1)) * 16u);
+    const uint32_t col = vs.wv * COLS + (c.lane & (COLS - 1u));
     float m = -__builtin_inff(), l = 0.0f, o = 0.0f;
     for (uint32_t it = 0; it < size; it++) {
         Msg mk, mv;
@@ -1809,7 +1810,7 @@ DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
         for (int h = 0; h < NP; h++) {
             f32x4 kv[NC];
 #pragma unroll
-            for (int j = 0; j < NC; j++) kv[j] = lds_ld128(k_off + (uint32_t)h * RP * ROW + (((uint32_t)j * G + rot_t) & 31u) * 16u);
+            for (int j = 0; j < NC; j++) kv[j] = lds_ld128(k_off + (uint32_t)h * RP * ROW + (((uint32_t)j * G + rot_t) & (uint32_t)(LPR - 1)) * 16u);
             float s0 = 0.0f, s1 = 0.0f;
 #pragma unroll
             for (int j = 0; j < NC; j += 2) {
@@ -1852,32 +1853,33 @@ DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
     Msg mo;
     if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
     const uint32_t out_off = mo.slot << slot_shift;
-    lds_stf(out_off + col * 4u, o);
+    lds_st32_lanes(COLS == 64u ? ~0ull : 0xFFFFFFFFull, out_off + col * 4u, __builtin_bit_cast(uint32_t, o));
     if (vs.t < 4u) lds_stf(out_off + ROW + vs.t * 4u, vs.t == 0u ? m : (vs.t == 1u ? l : 0.0f));
     lds_wait();
     vcc_done_with(c, vs, 1u, 1u);
     return true;
 }
 
-// attn_merge: `P` partial rows (o[0..128), m, l, 0, 0) of one request become its result; thread t owns column t.
-DEV bool attn_merge_uop(Ctx &c, VccState &vs, uint32_t P) {
-    constexpr uint32_t PROW = 528u;
+// attn_merge: `P` partial rows (o[0..d), m, l, 0, 0) of one request become its result; thread t owns column t (d = 4 lpr).
+DEV bool attn_merge_uop(Ctx &c, VccState &vs, uint32_t P, uint32_t lpr) {
+    const uint32_t D4 = lpr * 16u, PROW = D4 + 16u;
+    const uint32_t tcol = vs.t < lpr * 4u ? vs.t : 0u;
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     Msg mt, mo, unused;
     if (!vcc_pop_wait(c, vs, 1u, 0u, mt, unused)) return false;
     const uint32_t t_off = mt.slot << slot_shift;
     float M = -__builtin_inff();
-    for (uint32_t i = 0; i < P; i++) M = __builtin_fmaxf(M, lds_ldf(t_off + i * PROW + 512u));
+    for (uint32_t i = 0; i < P; i++) M = __builtin_fmaxf(M, lds_ldf(t_off + i * PROW + D4));
     float num = 0.0f, den = 0.0f;
     for (uint32_t i = 0; i < P; i++) {
-        const float w = expf(lds_ldf(t_off + i * PROW + 512u) - M);
-        num = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + vs.t * 4u), num);
-        den = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + 516u), den);
+        const float w = expf(lds_ldf(t_off + i * PROW + D4) - M);
+        num = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + tcol * 4u), num);
+        den = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + D4 + 4u), den);
     }
     const float res = num / den;
     vcc_done_with(c, vs, 1u, 0u);
     if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
-    lds_stf((mo.slot << slot_shift) + vs.t * 4u, res);
+    if (vs.t < lpr * 4u) lds_stf((mo.slot << slot_shift) + vs.t * 4u, res);
     lds_wait();
     vcc_done_with(c, vs, 1u, 1u);
     return true;
@@ -1909,16 +1911,20 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         } else if (f.opcode == OP_ROPE) {
             ok = rope_uop(c, vs, (uint32_t)f.imm & 0xFFu, (uint32_t)(f.imm >> 8) & 0xFFFFu);
         } else if (f.opcode == OP_ATTN) {
-            const uint32_t R = (uint32_t)(f.imm >> 8) & 0xFFu;
+            const uint32_t lpr = (uint32_t)f.imm & 0xFFu, R = (uint32_t)(f.imm >> 8) & 0xFFu;
             const float scale = __builtin_bit_cast(float, (uint32_t)(f.imm >> 16));
-            if (((uint32_t)f.imm & 0xFFu) != 32u || (R != 8u && R != 16u && R != 32u)) {
+            if (lpr == 32u && R == 32u) ok = attn_uop<32, 32>(c, vs, f.size, scale);
+            else if (lpr == 32u && R == 16u) ok = attn_uop<16, 32>(c, vs, f.size, scale);
+            else if (lpr == 32u && R == 8u) ok = attn_uop<8, 32>(c, vs, f.size, scale);
+            else if (lpr == 16u && R == 64u) ok = attn_uop<64, 16>(c, vs, f.size, scale);
+            else if (lpr == 16u && R == 32u) ok = attn_uop<32, 16>(c, vs, f.size, scale);
+            else if (lpr == 16u && R == 16u) ok = attn_uop<16, 16>(c, vs, f.size, scale);
+            else {
                 raise_error(c, -3 /* VDC_EPROGRAM */, 0xE00u | f.opcode);
                 ok = false;
-            } else {
-                ok = R == 32u ? attn_uop<32>(c, vs, f.size, scale) : R == 16u ? attn_uop<16>(c, vs, f.size, scale) : attn_uop<8>(c, vs, f.size, scale);
             }
         } else if (f.opcode == OP_ATTN_MERGE) {
-            ok = attn_merge_uop(c, vs, f.size);
+            ok = attn_merge_uop(c, vs, f.size, (uint32_t)f.imm & 0xFFu);
         } else if (f.opcode == OP_DROP) {
             ok = drop_uop(c, vs, f.size);
         } else if (f.opcode == OP_FILL) {

@@ -373,20 +373,24 @@ ATTN_CASES = [
     ("rand", 16384),                               # 64 x random[256, 1024],
     ([65536], 16384),                              # 1 x 65536
     ([5000, 1, 17], 8192),
+    ([700, 3, 64, 2000], 16384, 64),               # head dimension 64: tiles of 64, 32, 16 context rows
+    ([333, 90], 8192, 64),
+    ([40, 41, 42, 43], 4096, 64),
 ]
 
 
-@pytest.mark.parametrize("lengths,T", ATTN_CASES)
-def test_decode_attention_against_the_fp64_definition(ex, lengths, T):
+@pytest.mark.parametrize("case", ATTN_CASES)
+def test_decode_attention_against_the_fp64_definition(ex, case):
+    lengths, T, d = case if len(case) == 3 else (case[0], case[1], 128)
     if lengths == "rand":
         lengths = list(np.random.default_rng(64).integers(256, 1025, 64))
-    Q, K, V, ro = _attn_inputs(lengths, seed=len(lengths) + T)
-    dO = torch.full((len(lengths), 128), float("nan"), device="cuda")
+    Q, K, V, ro = _attn_inputs(lengths, seed=len(lengths) + T, d=d)
+    dO = torch.full((len(lengths), d), float("nan"), device="cuda")
     dQ, dK, dV = _dev(Q), _dev(K), _dev(V)
     for _ in range(2):                             # the second run takes the cached program
         ex.attn_decode(dQ, dK, dV, ro, dO, T)
         ex.check()
-    _check_attn(dO.cpu().numpy(), Q, K, V, ro, 128 ** -0.5, "attention %s" % (lengths[:4],))
+    _check_attn(dO.cpu().numpy(), Q, K, V, ro, d ** -0.5, "attention %s d %d" % (lengths[:4], d))
 
 
 def test_attention_traces_match_the_interpreter_and_oracle_assembled_programs_run():
@@ -437,7 +441,7 @@ def test_attention_refuses_what_it_does_not_support(ex):
         with pytest.raises(vdc.VdcError):
             ex.attn_decode(dQ, dK, dV, a["ro"], dO, a["T"])
     with pytest.raises(vdc.VdcError):
-        ex.attn_decode(dQ[:, :64].contiguous(), dK, dV, ro, dO, 4096)      # d = 64
+        ex.attn_decode(dQ[:, :32].contiguous(), dK, dV, ro, dO, 4096)      # d = 32
 
 
 CHAIN_CASES = [

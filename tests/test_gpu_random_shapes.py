@@ -69,13 +69,14 @@ def test_random_attention_batches(ex):
         lengths = np.minimum(lengths, 5000)
         ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
         tile = int(rng.choice([4096, 8192, 16384]))
-        Q = rng.standard_normal((n, 128)).astype(np.float32)
-        K = rng.standard_normal((int(ro[-1]), 128)).astype(np.float32)
-        V = rng.standard_normal((int(ro[-1]), 128)).astype(np.float32)
-        O = torch.full((n, 128), float("nan"), device="cuda")
+        d = int(rng.choice([64, 128]))
+        Q = rng.standard_normal((n, d)).astype(np.float32)
+        K = rng.standard_normal((int(ro[-1]), d)).astype(np.float32)
+        V = rng.standard_normal((int(ro[-1]), d)).astype(np.float32)
+        O = torch.full((n, d), float("nan"), device="cuda")
         ex.attn_decode(_dev(Q), _dev(K), _dev(V), ro, O, tile)
         ex.check()
-        Or, Ar, S = attn_ref.attn_decode(Q, K, V, ro, 128 ** -0.5)
+        Or, Ar, S = attn_ref.attn_decode(Q, K, V, ro, d ** -0.5)
         worst = float((np.abs(O.cpu().numpy() - Or) / ((2e-5 * S[:, None] + 2e-5) * Ar + 1e-30)).max())
         assert worst <= 1.0, "attention case %d (%d contexts, %d rows, tile %d): %.3g" % (case, n, int(ro[-1]), tile, worst)
 

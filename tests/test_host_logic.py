@@ -252,15 +252,16 @@ def test_stream_program_rejects_bad_arguments():
 
 
 # ---- decode attention over ragged contexts (Section 6.2, "Dynamic Attention Length") -----------------
-@pytest.mark.parametrize("lengths,T,ncores,slot,nslots", [
-    ([1], 4096, 1, 4096, 8),
-    ([40, 7, 300, 9, 64], 4096, 2, 4096, 10),          # one long request shared by the compute cores, short ones whole
-    ([600], 8192, 4, 8192, 8),                         # a single request on eight compute cores
-    ([33] * 9, 16384, 2, 8192, 10),                    # more requests than compute cores; a tile holds most of a context
+@pytest.mark.parametrize("lengths,T,ncores,slot,nslots,d", [
+    ([1], 4096, 1, 4096, 8, 128),
+    ([40, 7, 300, 9, 64], 4096, 2, 4096, 10, 128),     # one long request shared by the compute cores, short ones whole
+    ([600], 8192, 4, 8192, 8, 128),                    # a single request on eight compute cores
+    ([33] * 9, 16384, 2, 8192, 10, 128),               # more requests than compute cores; a tile holds most of a context
+    ([70, 5, 400], 4096, 2, 4096, 10, 64),             # head dimension 64
+    ([129], 16384, 3, 8192, 8, 64),
 ])
-def test_attention_program_on_the_oracle_interpreter(lengths, T, ncores, slot, nslots):
+def test_attention_program_on_the_oracle_interpreter(lengths, T, ncores, slot, nslots, d):
     from oracle import attn_ref
-    d = 128
     rng = np.random.default_rng(sum(lengths))
     ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
     Q = rng.standard_normal((len(lengths), d)).astype(np.float32)
@@ -270,7 +271,7 @@ def test_attention_program_on_the_oracle_interpreter(lengths, T, ncores, slot, n
         w, sb, ds, n_items = ex.attn_decode_program(ro, d, T)
         rc, msg = ex.program_validate(w, sb, ds, [K.nbytes, V.nbytes, Q.nbytes, Q.nbytes, n_items * (d + 4) * 4])
         assert rc == vdc.VDC_OK, msg
-        for bad in (dict(d=64), dict(T=2048), dict(ro=np.array([0, 5, 5]))):
+        for bad in (dict(d=32), dict(T=2048), dict(ro=np.array([0, 5, 5]))):
             a = dict(ro=ro, d=d, T=T)
             a.update(bad)
             with pytest.raises(vdc.VdcError):

@@ -70,9 +70,8 @@ def test_ragged_matvec_programs(lengths, k4, tile, ncores, seed):
 
 @settings(**COMMON)
 @given(lengths=st.lists(st.integers(1, 200), min_size=1, max_size=7), tile=st.sampled_from([4096, 8192, 16384]),
-       ncores=st.integers(1, 4), seed=st.integers(0, 1000))
-def test_attention_programs(lengths, tile, ncores, seed):
-    d = 128
+       ncores=st.integers(1, 4), seed=st.integers(0, 1000), d=st.sampled_from([64, 128]))
+def test_attention_programs(lengths, tile, ncores, seed, d):
     ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
     rng = np.random.default_rng(seed)
     Q = rng.standard_normal((len(lengths), d)).astype(np.float32)
