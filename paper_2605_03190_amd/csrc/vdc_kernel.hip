@@ -1155,27 +1155,6 @@ DEV bool stu_receive(Ctx &c, uint32_t lo, uint32_t hi, uint32_t &c2m_head, uint3
     return true;
 }
 
-// The used regions at the front of both c2m queues, all at once: lane 16 v + j looks at the j-th entry after the head
-// of compute core v's queue; the run of valid "used" entries that starts at each head is recycled with one LDS atomic
-// (the lanes of the run each clear their own region's bits).  Returns how many entries were taken per queue.
-DEV void stu_recycle(Ctx &c, uint32_t V, uint32_t &c2m_head0, uint32_t &c2m_head1, bool &moved, bool &produced_next) {
-    const uint32_t v = (c.lane >> 4) & 1u, j = c.lane & 15u;
-    const uint32_t hv = v ? c2m_head1 : c2m_head0;
-    const uint64_t ent = lds_vld64(c.ctl + CTL_OFF(c2m) + (v * kC2M + ((hv + j) & (kC2M - 1))) * 8u);
-    const uint32_t lo = (uint32_t)ent, hi = (uint32_t)(ent >> 32);
-    const bool valid = c.lane < 32u && v < V && hi == hv + j + 1u;
-    const uint32_t vm = (uint32_t)__ballot(valid && (lo & 1u) == 0u);
-    const uint32_t n0 = (uint32_t)__builtin_ctz(~(vm & 0xFFFFu)), n1 = (uint32_t)__builtin_ctz(~(vm >> 16));   // each <= 16
-    const uint64_t take = (uint64_t)(((1u << n0) - 1u) | (((1u << n1) - 1u) << 16));
-    const uint32_t slot = (lo >> 1) & 63u, nslots = (lo >> 7) & 63u;
-    lds_and32_lanes(take, c.ctl + CTL_OFF(mask), ~slot_bits(slot, nslots));
-    c2m_head0 += n0;
-    c2m_head1 += n1;
-    moved = (n0 | n1) != 0u;
-    // is the entry right after the run a valid "produced" one?
-    produced_next = __ballot(valid && (lo & 1u) != 0u && j == (v ? n1 : n0)) != 0ull;
-}
-
 DEV void stu_main(Ctx &c) {
     const uint32_t u = c.unit;
     const uint32_t V = c.p->V;
@@ -1191,15 +1170,13 @@ DEV void stu_main(Ctx &c) {
     bool ok = true;
     while (ok) {
         PHASE(c, 1u + c.p->n_ldu, 1u);
-        bool moved, produced_next;
-        stu_recycle(c, V, c2m_head0, c2m_head1, moved, produced_next);
-        if (moved) OBS(c, 5u, c2m_head0 | (c2m_head1 << 16));
+        // the c2m queues carry produced regions only (a compute core frees a used region itself, see vcc_done_with):
+        // the poll brings the next entry of each along
         const uint32_t snap = stu_poll(c, u, head, c2m_head0, c2m_head1);
         PHASE(c, 1u + c.p->n_ldu, 2u);
-        if (__builtin_expect(produced_next, 0)) {
-            moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0) || moved;
-            if (V > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
-        }
+        bool moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0);
+        if (V > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
+        if (moved) OBS(c, 5u, c2m_head0 | (c2m_head1 << 16));
         if (!have && rf_get(snap, 4) != head) {
             // pick the next STORE up: from here on its queue entry and its static record may be reused
             PHASE(c, 1u + c.p->n_ldu, 3u);
