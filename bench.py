@@ -69,7 +69,7 @@ def bench_attention(args):
     Ks = [torch.randn((rows, d), device="cuda", generator=g) for _ in range(n_copies)]
     Vs = [torch.randn((rows, d), device="cuda", generator=g) for _ in range(n_copies)]
     O = torch.full((len(lengths), d), float("nan"), device="cuda")
-    ex = vdc.Executor(slot_bytes=args.slot_bytes or 8192)
+    ex = vdc.Executor(slot_bytes=args.slot_bytes or 8192, n_stu=args.n_stu)
     stream = torch.cuda.current_stream()
     for i in range(args.warmup):
         ex.attn_decode(Q, Ks[i % n_copies], Vs[i % n_copies], ro, O, tile, stream=stream)
@@ -134,6 +134,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--tile-bytes", type=int, default=0, help="override the configuration's tile (I/O block) size: 2048, 4096, 8192 or 16384")
     ap.add_argument("--slot-bytes", type=int, default=0, help="override the configuration's slot size")
+    ap.add_argument("--n-stu", type=int, default=0, help="store units per core: 1 or 2 (0: the library's default)")
     ap.add_argument("--heads", type=int, default=8, help="attention workloads: key/value heads per request")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device-to-device copy of MIB mebibytes --steps times: "
@@ -185,7 +186,7 @@ def main():
     torch.cuda.synchronize()
     log("inputs: %s rows=%d K=%d B=%d tile=%d ragged=%s copies=%d (%.1f s)" % (cfg.name, rows, K, B, cfg.tile_bytes, ragged, n_copies, time.time() - t0))
 
-    ex = vdc.Executor(slot_bytes=cfg.slot_bytes)
+    ex = vdc.Executor(slot_bytes=cfg.slot_bytes, n_stu=args.n_stu)
     stream = torch.cuda.current_stream()
 
     def step(i):

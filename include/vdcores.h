@@ -55,7 +55,8 @@ typedef struct {
     int32_t slot_bytes;     /* local-memory slot size, power of two, 1024..16384; default 8192        */
     int32_t n_slots;        /* slots per core, 1..32; default = as many as fit in the CU's LDS        */
     int32_t n_ldu;          /* load units per VMC: 1, 2 or 4; default 4                                   */
-    int32_t n_stu;          /* store units per VMC, must be 1 or 0 (=1)                               */
+    int32_t n_stu;          /* store units per VMC: 1, 2 or 0 (=1); 2 needs vcc_per_core = 2: unit i  */
+                            /* then serves compute core i, and a STORE must be on flow vflow % 2 = vcc */
     int32_t n_dep_ids;      /* size of the global depId table; default 4096                           */
     int32_t watchdog_spins; /* polls before a waiting unit reports VDC_EDEADLOCK; default 1<<22       */
     int32_t tile_rows;      /* tuning knob of the matvec tiler: rows per matrix tile; 0 => automatic  */

@@ -91,6 +91,7 @@ struct SentMsg {
     uint32_t slot, nslots, rows, row_bytes, box_rows, lds_pitch;
     bool is_store;
     bool is_local = false;        // the region of a store.local
+    uint32_t unit = 0;            // the store unit a STORE sits on
 };
 
 struct VccH {
@@ -112,7 +113,7 @@ struct CoreH {
     std::vector<VccH> vcc;
     uint32_t mask = 0;
     std::deque<SentMsg> stores_waiting;  // STOREs whose region has not come back yet (only counted)
-    std::deque<SentMsg> parked;          // regions a store.local took back, waiting for their load.local
+    std::deque<SentMsg> parked[2];       // per store unit: regions a store.local took back, waiting for their load.local
 };
 
 struct Validator {
@@ -134,6 +135,9 @@ struct Validator {
         if (err.empty()) err = m;
         return false;
     }
+
+    // the store unit a STORE or a local memory uop goes to: its flow, modulo the number of units
+    uint32_t stu_of(const Fields &f) const { return f.vflow & (uint32_t)(cfg.n_stu - 1); }
 
     int first_fit(uint32_t mask, uint32_t n) const {
         for (int p = 0; p + (int)n <= cfg.n_slots; p++) {
@@ -205,9 +209,9 @@ struct Validator {
         }
         if (local && is_load) {
             if (f.nslots != 0) { fail("load.local allocates nothing: nslots must be 0"); return -1; }
-            if (c.parked.empty()) return 0;
-            SentMsg m = c.parked.front();
-            c.parked.pop_front();
+            if (c.parked[stu_of(f)].empty()) return 0;
+            SentMsg m = c.parked[stu_of(f)].front();
+            c.parked[stu_of(f)].pop_front();
             if ((uint64_t)d.box_rows * d.lds_pitch > (uint64_t)m.nslots * cfg.slot_bytes) { fail("load.local: the region is smaller than the box it is handed on as"); return -1; }
             m.rows = f.size; m.row_bytes = d.row_bytes; m.box_rows = d.box_rows; m.lds_pitch = d.lds_pitch; m.is_store = false; m.is_local = false;
             c.vcc[f.vcc].m2c.push_back(m);
@@ -228,6 +232,8 @@ struct Validator {
         if ((int)f.vcc >= cfg.vcc_per_core) { fail("vcc out of range"); return -1; }
         if (is_load && !(f.flags & F_SEND)) { fail("LOAD without SEND would never be released"); return -1; }
         if (!is_load && !(f.flags & F_RECV)) { fail("STORE without RECV has no data to write"); return -1; }
+        // with two store units each receives the c2m queue of one compute core (unit i: VCC i)
+        if (!is_load && stu_of(f) != (f.vcc & (uint32_t)(cfg.n_stu - 1))) { fail("STORE on another store unit than its compute core's"); return -1; }
         if (is_load && (f.flags & F_RECV)) { fail("LOAD with RECV is not defined"); return -1; }
         if (f.flags & (F_DEP_SEND | F_DEP_RECV)) {
             if ((int)f.dep_id >= cfg.n_dep_ids) { fail("depId out of range"); return -1; }
@@ -244,7 +250,7 @@ struct Validator {
         int slot = first_fit(c.mask, f.nslots);
         if (slot < 0) return 0;
         c.mask |= (uint32_t)(((f.nslots >= 32 ? 0xFFFFFFFFull : ((1ull << f.nslots) - 1ull)) << slot));
-        SentMsg m{(uint32_t)slot, f.nslots, f.size, d.row_bytes, d.box_rows, d.lds_pitch, !is_load, local};
+        SentMsg m{(uint32_t)slot, f.nslots, f.size, d.row_bytes, d.box_rows, d.lds_pitch, !is_load, local, stu_of(f)};
         if (f.flags & F_SEND) c.vcc[f.vcc].m2c.push_back(m);
         if (!is_load) {
             if (!(f.flags & F_SEND)) { fail("STORE with RECV but without SEND: nothing hands its region to a compute core"); return -1; }
@@ -266,8 +272,9 @@ struct Validator {
         for (auto it = c.stores_waiting.begin(); it != c.stores_waiting.end(); ++it)
             if (it->slot == m.slot && it->nslots == m.nslots) {
                 const bool local = it->is_local;
+                const uint32_t unit = it->unit;
                 c.stores_waiting.erase(it);
-                if (local) c.parked.push_back(m); else release(c, m);
+                if (local) c.parked[unit].push_back(m); else release(c, m);
                 return true;
             }
         return fail("a compute uop's output region has no STORE");
@@ -458,7 +465,7 @@ struct Validator {
                 bool fin = core.vmc.halted;
                 for (auto &v : core.vcc) fin = fin && v.s.halted && !v.in_uop && v.m2c.empty();
                 if (fin) {
-                    if (core.mask != 0 || !core.stores_waiting.empty() || !core.parked.empty()) return fail("a core ends with slots still allocated");
+                    if (core.mask != 0 || !core.stores_waiting.empty() || !core.parked[0].empty() || !core.parked[1].empty()) return fail("a core ends with slots still allocated");
                     done[c] = 1;
                     n_done++;
                     progress = true;
@@ -1183,7 +1190,8 @@ int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     if (c.n_cores < 1 || c.n_cores > cu_count) return VDC_EINVAL;   // all cores must be co-resident
     if (c.vcc_per_core < 1 || c.vcc_per_core > 2 || c.threads_per_eu != 128) return VDC_EINVAL;
     if (!is_pow2(c.slot_bytes) || c.slot_bytes < 1024 || c.slot_bytes > 16384) return VDC_EINVAL;
-    if ((c.n_ldu != 1 && c.n_ldu != 2 && c.n_ldu != 4) || c.n_stu != 1) return VDC_EINVAL;   // at most 10 waves per core
+    if ((c.n_ldu != 1 && c.n_ldu != 2 && c.n_ldu != 4) || (c.n_stu != 1 && c.n_stu != 2)) return VDC_EINVAL;   // at most 11 waves per core
+    if (c.n_stu > c.vcc_per_core) return VDC_EINVAL;   // a store unit serves at least one compute core
     if (c.n_dep_ids < 1 || c.n_dep_ids > 65536 || c.watchdog_spins < 1 || c.tile_rows < 0) return VDC_EINVAL;
     const size_t ctl = lds_control_bytes();
     if (c.n_slots == 0) {

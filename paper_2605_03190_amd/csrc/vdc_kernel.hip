@@ -11,8 +11,9 @@
 //   waves 1 .. n_ldu (<= 4)     LDU   direct-to-LDS 128-bit loads (global_load_lds_dwordx4), several tiles in
 //                                     flight per unit, completion observed with s_waitcnt vmcnt(N), then the
 //                                     region is delivered into its m2c ticket
-//   next n_stu waves            STU   receiver of the c2m queues; waits for the produced region, LDS -> global,
-//                                     frees the slots, signals depId; store.local / load.local
+//   next n_stu (1 or 2) waves   STU   receiver of the c2m queues (two units: one compute core each); waits for the
+//                                     produced region, LDS -> global, frees the slots, signals depId; store.local /
+//                                     load.local
 //   next 2 * V waves            VCC   v = 0..V-1, two waves (128 threads) each: the compute uop handlers
 //
 // All queues live in LDS.  A waiter polls LDS with s_sleep back-off (no hardware de-scheduling exists);
@@ -89,7 +90,8 @@ struct Ctl {
     uint32_t vcc_done;             // VCC waves that reached HALT
     uint32_t uq_tail[kMaxUnits];   // records pushed to each unit
     uint32_t uq_done[kMaxUnits];   // records completed by each unit (store units)
-    uint32_t rsv0[kMaxV];
+    uint32_t stu_left;             // store units that have finished
+    uint32_t rsv0[kMaxV - 1];
     uint32_t red_flag[kMaxV];      // cross-wave reduction hand-shake of a VCC
     uint32_t red_ack[kMaxV];
     uint32_t win_gen;              // number of windows the front end has decoded so far
@@ -495,8 +497,8 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
 #pragma unroll
     for (int t = 0; t < kMaxTensors; t++) tbase = ((d_tensor & (kMaxTensors - 1)) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tbase;
     // loads go to the load unit of their flow (n_ldu is 1, 2 or 4); stores, and the load.local that hands a kept
-    // region on, to the store unit
-    const uint32_t unit = (f.opcode == OP_LOAD && !(f.flags & F_LOCAL)) ? (f.vflow & (p->n_ldu - 1u)) : p->n_ldu;
+    // region on, to the store unit of their flow (n_stu is 1 or 2)
+    const uint32_t unit = (f.opcode == OP_LOAD && !(f.flags & F_LOCAL)) ? (f.vflow & (p->n_ldu - 1u)) : p->n_ldu + (f.vflow & (p->n_stu - 1u));
     const uint64_t a = (uint64_t)f.imm + (is_mem ? tbase : 0ull);
     d.base = pc;
     d.ctl = f.opcode | (f.flags << 8) | (unit << 16) | ((f.vcc & 1u) << 19) | (f.acc << 20) | (f.nslots << 23) | ((d_tensor & 7u) << 29);
@@ -1123,10 +1125,11 @@ DEV void ldu_main(Ctx &c) {
 // ------------------------------------------------------------------------------------------------
 // STU: receiver of the c2m queues, and produced region -> global memory
 // ------------------------------------------------------------------------------------------------
-// lanes 0,1 = next c2m entry of VCC 0 (low, high), lanes 2,3 = of VCC 1, lane 4 = uq_tail[u], lanes 5..8 = the
-// record at `head`, lane 9 = cfu_halted, lane 10 = abort, lane 11 = vcc_done, lane 12 = slot mask
-DEV uint32_t stu_poll(Ctx &c, uint32_t u, uint32_t head, uint32_t c2m_head0, uint32_t c2m_head1) {
-    const uint32_t e0 = c.ctl + CTL_OFF(c2m) + (c2m_head0 & (kC2M - 1)) * 8u;
+// lanes 0,1 = next c2m entry of the unit's first VCC `ring0` (low, high), lanes 2,3 = of VCC 1 (looked at only by a unit
+// that serves both), lane 4 = uq_tail[u], lanes 5..8 = the record at `head`, lane 9 = cfu_halted, lane 10 = abort,
+// lane 11 = vcc_done, lane 12 = slot mask
+DEV uint32_t stu_poll(Ctx &c, uint32_t u, uint32_t ring0, uint32_t head, uint32_t c2m_head0, uint32_t c2m_head1) {
+    const uint32_t e0 = c.ctl + CTL_OFF(c2m) + (ring0 * kC2M + (c2m_head0 & (kC2M - 1))) * 8u;
     const uint32_t e1 = c.ctl + CTL_OFF(c2m) + (kC2M + (c2m_head1 & (kC2M - 1))) * 8u;
     const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
     uint32_t off = c.ctl + CTL_OFF(mask);
@@ -1158,6 +1161,10 @@ DEV bool stu_receive(Ctx &c, uint32_t lo, uint32_t hi, uint32_t &c2m_head, uint3
 DEV void stu_main(Ctx &c) {
     const uint32_t u = c.unit;
     const uint32_t V = c.p->V;
+    // One store unit receives the c2m queues of all compute cores; two take one compute core each (unit i: VCC i), and
+    // a STORE or a local uop must then sit on the unit of its compute core.
+    const bool split = c.p->n_stu == 2u;
+    const uint32_t ring0 = split ? u - c.p->n_ldu : 0u, n_rings = split ? 1u : V;
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     uint32_t head = 0, done = 0;
     uint32_t c2m_head0 = 0, c2m_head1 = 0;
@@ -1169,17 +1176,17 @@ DEV void stu_main(Ctx &c) {
     Spin sp;
     bool ok = true;
     while (ok) {
-        PHASE(c, 1u + c.p->n_ldu, 1u);
+        PHASE(c, 1u + u, 1u);
         // the c2m queues carry produced regions only (a compute core frees a used region itself, see vcc_done_with):
         // the poll brings the next entry of each along
-        const uint32_t snap = stu_poll(c, u, head, c2m_head0, c2m_head1);
-        PHASE(c, 1u + c.p->n_ldu, 2u);
+        const uint32_t snap = stu_poll(c, u, ring0, head, c2m_head0, c2m_head1);
+        PHASE(c, 1u + u, 2u);
         bool moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0);
-        if (V > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
+        if (n_rings > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
         if (moved) OBS(c, 5u, c2m_head0 | (c2m_head1 << 16));
         if (!have && rf_get(snap, 4) != head) {
             // pick the next STORE up: from here on its queue entry and its static record may be reused
-            PHASE(c, 1u + c.p->n_ldu, 3u);
+            PHASE(c, 1u + u, 3u);
             r_glo = rf_get(snap, 5); r_ghi = rf_get(snap, 6); r_info = rf_get(snap, 7); r_ticket = rf_get(snap, 8);
             stat = stat_fetch(c, r_info);
             stat = stat + 0u;
@@ -1195,6 +1202,13 @@ DEV void stu_main(Ctx &c) {
             const uint32_t slot = r_info & 63u;
             c.pc = c.stream_pc0 + rf_get(stat, 6);
             bool ready = true;
+            const uint32_t vi = vcc - ring0;        // which of this unit's c2m queues
+            if ((flags & F_RECV) && vi >= n_rings) {
+                // the region would come back on a queue another store unit receives
+                raise_error(c, -3 /* VDC_EPROGRAM */, 0x990u | vcc);
+                ok = false;
+                break;
+            }
             if ((flags & F_LOCAL) && (w0 & 0xFFu) == (uint32_t)OP_LOAD) {
                 // load.local: the oldest kept region goes to the compute core as a delivered tile
                 if (park_head == park_tail) {
@@ -1219,16 +1233,16 @@ DEV void stu_main(Ctx &c) {
             }
             if (ready && (flags & F_RECV)) {
                 // wait for the compute core to hand the region back as "produced"
-                const uint32_t bh = vcc == 0u ? box_head0 : box_head1, bt = vcc == 0u ? box_tail0 : box_tail1;
+                const uint32_t bh = vi == 0u ? box_head0 : box_head1, bt = vi == 0u ? box_tail0 : box_tail1;
                 ready = bh != bt;
                 if (ready) {
-                    const uint32_t got = rf_get(vcc == 0u ? box_rf0 : box_rf1, bh & (kMbox - 1));
+                    const uint32_t got = rf_get(vi == 0u ? box_rf0 : box_rf1, bh & (kMbox - 1));
                     if (got != (slot | (nslots << 6))) {
                         raise_error(c, -3 /* VDC_EPROGRAM */, 0x900u | got);
                         ok = false;
                         break;
                     }
-                    if (vcc == 0u) box_head0++; else box_head1++;
+                    if (vi == 0u) box_head0++; else box_head1++;
                 }
             }
             if (ready && (flags & F_LOCAL)) {
@@ -1246,7 +1260,7 @@ DEV void stu_main(Ctx &c) {
                 const uint32_t row_words = (rb_pitch & 0xFFFFu) >> 2, lds_pitch = rb_pitch >> 16;
                 const uint32_t lds_off = slot << slot_shift;
                 compiler_barrier();
-                PHASE(c, 1u + c.p->n_ldu, 4u);
+                PHASE(c, 1u + u, 4u);
                 bool through = false;            // stored at device scope (only the 16-byte path does that)
                 if (((r_glo | (uint32_t)gpitch | rb_pitch | (rb_pitch >> 16)) & 15u) == 0u) {
                     // whole 16-byte chunks: lane l takes chunks l, l + 64, ... of the box, four at a time.  The lane's
@@ -1317,24 +1331,28 @@ DEV void stu_main(Ctx &c) {
             sp.n = 0;
             continue;
         }
-        // nothing to do right now.  The unit leaves last: the front end has halted, every STORE is written, the compute
-        // cores are done and both c2m queues are empty; then every slot must be free again.
+        // nothing to do right now.  The store units leave last: the front end has halted, every STORE is written, the
+        // compute cores are done and the unit's c2m queues are empty.
         if (!have && rf_get(snap, 9) && rf_get(snap, 11) == 2u * V && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) {
-            const uint32_t last = stu_poll(c, u, head, c2m_head0, c2m_head1);
-            const bool more = rf_get(last, 1) == c2m_head0 + 1u || (V > 1u && rf_get(last, 3) == c2m_head1 + 1u);
-            if (!more) {
-                const uint32_t mask = rf_get(last, 12);
-                if (mask != 0u) raise_error(c, -6 /* VDC_ELEAK */, mask);
-                break;
-            }
+            const uint32_t last = stu_poll(c, u, ring0, head, c2m_head0, c2m_head1);
+            const bool more = rf_get(last, 1) == c2m_head0 + 1u || (n_rings > 1u && rf_get(last, 3) == c2m_head1 + 1u);
+            if (!more) break;
             continue;
         }
-        PHASE(c, 1u + c.p->n_ldu, have ? 6u : 5u);
+        PHASE(c, 1u + u, have ? 6u : 5u);
         if (!spin_step(c, sp, rf_get(snap, 10), 0x700u | (have ? 0x80u : 0u))) ok = false;
     }
-    // The store unit is the last of its core to touch a depId counter (every signal and every wait of the core lies
-    // before the last region comes back).  The core that leaves last, of all cores, puts the counters the program used
-    // back to zero for the next run: no clearing launch between runs, also after a run that was aborted.
+    // The store unit that leaves last is the last of its core to touch a slot or a depId counter (every signal and every
+    // wait of the core lies before the last region comes back).
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if (lds_add_rtn_lane0(c.ctl + CTL_OFF(stu_left), 1u) + 1u != c.p->n_stu) return;
+    // After a run that came to its end every slot must be free again.
+    if (ok) {
+        const uint32_t mask = uni(lds_vld32(c.ctl + CTL_OFF(mask)));
+        if (mask != 0u) raise_error(c, -6 /* VDC_ELEAK */, mask);
+    }
+    // The core that leaves last, of all cores, puts the counters the program used back to zero for the next run: no
+    // clearing launch between runs, also after a run that was aborted.
     if (c.p->n_dep_used != 0u) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         uint32_t before = 0;
@@ -1973,9 +1991,9 @@ DEV void observer_main(Ctx &c, uint32_t V) {
 #endif
 
 #ifdef VDC_PROFILE
-#define VDC_MAX_THREADS 704
+#define VDC_MAX_THREADS 768
 #else
-#define VDC_MAX_THREADS 640
+#define VDC_MAX_THREADS 704
 #endif
 __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) {
     const uint32_t wave = uni(threadIdx.x >> 6);

@@ -41,6 +41,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--mib", type=int, default=4096, help="size of the range in MiB")
     ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--n-stu", type=int, default=0, help="store units per core: 1 or 2 (0: the library's default)")
     args = ap.parse_args()
     import torch
     import paper_2605_03190_amd as vdc
@@ -61,7 +62,7 @@ def main():
     for T in TILES:
         slot = max(1024, min(T, 8192))
         row = "%-12s" % ("%d B" % T)
-        with vdc.Executor(slot_bytes=slot) as ex:
+        with vdc.Executor(slot_bytes=slot, n_stu=args.n_stu) as ex:
             for mode in MODES:
                 s, d = (src if mode != "fill" else None), (dst if mode != "read" else None)
                 try:

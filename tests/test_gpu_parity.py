@@ -84,10 +84,11 @@ def test_dense_matvec_against_fp64_gemv(ex, rows, K, ld, B, T):
 @pytest.mark.parametrize("cfg", [
     dict(n_ldu=1), dict(n_ldu=2), dict(vcc_per_core=1), dict(vcc_per_core=1, n_ldu=1), dict(n_slots=6), dict(n_cores=7),
     dict(slot_bytes=4096, n_slots=32), dict(slot_bytes=16384), dict(tile_rows=64), dict(n_cores=128),
+    dict(n_stu=2), dict(n_stu=2, n_ldu=2, n_cores=100),
 ])
 def test_other_deployment_constants(cfg):
     """The executor with fewer load units, one compute core per memory core, few slots, odd core counts, other slot
-    sizes, another tile shape, half the chip: same results (dense with tails, ragged, split along K, fused rope)."""
+    sizes, another tile shape, half the chip, two store units per core: same results (dense with tails, ragged, split along K, fused rope)."""
     rng = np.random.default_rng(31)
     with vdc.Executor(**cfg) as e:
         for rows, K, ld, B, T in ((1000, 1000, 1000, 1, 4096), (517, 2052, 2060, 3, 8192), (2048, 4096, 4096, 8, 16384), (64, 32768, 32768, 2, 16384)):
@@ -477,6 +478,48 @@ def test_chain_of_matvecs_in_one_launch(ex, dims, B, T):
             Y = Ah[a_off[l + 1]:a_off[l + 2]].reshape(B, dims[l + 1])
             Yr, Ya = gemv_ref.gemv_dense(Ms[l], prev)
             _check(Y, Yr, Ya, "chain %s layer %d run %d" % (dims, l, rep))
+            prev = Y
+
+
+def test_two_store_units_serve_the_other_operators_too():
+    """Attention (partials and merges signal through depId from both store units), the stream uops and a chain of
+    matvecs on an executor with two store units per core, to the same bars as with one."""
+    with vdc.Executor(n_stu=2) as e:
+        assert e.cfg.n_stu == 2
+        for lengths, T, d in (([40, 7, 300, 9, 64], 4096, 128), ([5000, 1, 17], 8192, 128), ([700, 3, 64, 2000], 16384, 64)):
+            Q, K, V, ro = _attn_inputs(lengths, seed=11 + T, d=d)
+            dO = torch.full((len(lengths), d), float("nan"), device="cuda")
+            e.attn_decode(_dev(Q), _dev(K), _dev(V), ro, dO, T)
+            e.check()
+            _check_attn(dO.cpu().numpy(), Q, K, V, ro, d ** -0.5, "attention %s, two store units" % (lengths,))
+        for mode, nbytes, T in (("copy", (5 << 20) + 7 * 1024 + 48, 8192), ("fill", (9 << 20) + 1024 + 16, 16384), ("copy", (1 << 20) + 256, 256)):
+            g = torch.Generator(device="cuda").manual_seed(nbytes)
+            src = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, device="cuda", generator=g)
+            dst = torch.full((nbytes + 64,), 0xEE, dtype=torch.uint8, device="cuda")
+            e.stream(mode, src if mode != "fill" else None, dst, nbytes, T, value=0xC0FFEE11)
+            e.check()
+            if mode == "copy":
+                assert torch.equal(dst[:nbytes], src[:nbytes])
+            else:
+                assert bool((dst[:nbytes].view(torch.int32) == np.int32(np.uint32(0xC0FFEE11).view(np.int32))).all())
+            assert bool((dst[nbytes:] == 0xEE).all())
+        dims, B, T = (1000, 516, 2052, 12), 2, 4096
+        rng = np.random.default_rng(3)
+        L = len(dims) - 1
+        Ms = [(rng.standard_normal((dims[l + 1], dims[l])) / np.sqrt(dims[l])).astype(np.float32) for l in range(L)]
+        dW = _dev(np.concatenate([m.ravel() for m in Ms]))
+        a_off = np.concatenate([[0], np.cumsum([B * x for x in dims])])
+        dA = torch.full((int(a_off[-1]),), float("nan"), device="cuda")
+        X = rng.standard_normal((B, dims[0])).astype(np.float32)
+        dA[:B * dims[0]] = _dev(X.ravel())
+        e.matvec_chain(dW, dA, dims, B, T)
+        e.check()
+        Ah = dA.cpu().numpy()
+        prev = X
+        for l in range(L):
+            Y = Ah[a_off[l + 1]:a_off[l + 2]].reshape(B, dims[l + 1])
+            Yr, Ya = gemv_ref.gemv_dense(Ms[l], prev)
+            _check(Y, Yr, Ya, "chain layer %d, two store units" % l)
             prev = Y
 
 

@@ -115,6 +115,50 @@ def test_fused_matvec_rope_program_on_the_oracle_interpreter(rows, K, ld, B, T, 
         assert np.all(np.abs(Y - Rr) <= 1e-6 * (Ra + Oa) + 1e-30)
 
 
+def test_two_store_units_per_core():
+    """With two store units each receives the return queue of one compute core: the tilers' programs (plain and fused)
+    run to the same result on the interpreter under random schedules, and a STORE moved to the other unit is refused
+    by the validator and by the interpreter."""
+    rng = np.random.default_rng(77)
+    rows, K, B, T = 200, 300, 3, 4096
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    Tt = rope_ref.table(rng.uniform(-3.0, 3.0, (B, rows // 2)))
+    O, Oa = gemv_ref.gemv_dense(M, X)
+    Rr, Ra = rope_ref.rope(O, Tt)
+    kw = dict(n_cores=3, slot_bytes=4096, n_slots=12)
+    with vdc.Executor(device=-1, n_stu=2, **kw) as ex:
+        assert ex.cfg.n_stu == 2
+        w, sb, d = ex.matvec_program(rows, K, K, B, T)
+        assert ex.program_validate(w, sb, d, [M.nbytes, X.nbytes, O.size * 4])[0] == vdc.VDC_OK
+        wr, sbr, dr = ex.matvec_rope_program(rows, K, K, B, T)
+        assert ex.program_validate(wr, sbr, dr, [M.nbytes, X.nbytes, O.size * 4, Tt.nbytes])[0] == vdc.VDC_OK
+        # the first STORE of compute core 1 on the flow of compute core 0's store unit
+        bad = np.array(w, copy=True)
+        ops, vcc = bad[:, 0] & 0xFF, (bad[:, 0] >> 20) & 3
+        i = int(np.flatnonzero((ops == A.STORE) & (vcc == 1))[0])
+        bad[i, 0] ^= 1 << 16
+        rc, msg = ex.program_validate(bad, sb, d, [M.nbytes, X.nbytes, O.size * 4])
+        assert rc == vdc.VDC_EPROGRAM and "store unit" in msg
+    for seed in range(3):
+        Y = np.full((B, rows), np.nan, np.float32)
+        m = UM.Machine(w, sb, d, [M, X, Y], n_stu=2, **kw)
+        m.run("random", seed)
+        m.check_final()
+        assert np.all(np.abs(Y - O) <= 1e-7 * Oa + 1e-30)
+        Y[:] = np.nan
+        m = UM.Machine(wr, sbr, dr, [M, X, Y, Tt], n_stu=2, **kw)
+        m.run("random", seed)
+        m.check_final()
+        assert np.all(np.abs(Y - Rr) <= 1e-6 * (Ra + Oa) + 1e-30)
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(bad, sb, d, [M, X, np.zeros((B, rows), np.float32)], n_stu=2, **kw).run()
+    with pytest.raises(vdc.VdcError):
+        vdc.Executor(device=-1, n_stu=3)
+    with pytest.raises(vdc.VdcError):
+        vdc.Executor(device=-1, n_stu=2, vcc_per_core=1)
+
+
 def test_ragged_tiler_program_on_the_oracle_interpreter():
     rng = np.random.default_rng(5)
     K = 64

@@ -73,7 +73,7 @@ def test_fused_program_on_the_interpreter(rows, K, B, R, Kt, slot, ncores):
         assert np.all(np.abs(Y - Rr) <= 1e-6 * (Ra + Oa) + 1e-30)
         images.append(Y.copy())
         traces.append((m.trace_vmc, m.trace_vcc))
-        assert all(c.mask == 0 and not c.parked for c in m.cores)
+        assert all(c.mask == 0 and not any(c.parked) for c in m.cores)
     assert all(np.array_equal(images[0], im) for im in images[1:])
     assert all(traces[0] == t for t in traces[1:])
     ops = w[:, 0] & 0xFF
