@@ -93,6 +93,15 @@ int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const
                        vdc_program **out);
 int vdc_program_destroy(vdc_program *prog);
 
+/* Which units of a core share a SIMD of the compute unit (Section 4.3 maps the virtual cores onto the threads of one
+ * thread block; on this GPU a workgroup's waves are dealt round-robin over four SIMDs, and waves on one SIMD contend for
+ * its issue slots).  placement 0 (default): every SIMD holds one compute wave next to the memory core's units, best
+ * when the compute cores set the pace.  placement 1: the front end and the store unit share their SIMDs with load
+ * units only and the compute waves pair up, best for graphs with a store per tile.  No effect on results; applies to
+ * the default deployment (4 load units, 1 store unit, 2 compute cores) and is ignored otherwise.  The operators below
+ * choose for their own programs.  VDC_EINVAL for another value. */
+int vdc_program_set_placement(vdc_program *prog, int32_t placement);
+
 /* The validation of vdc_program_create alone (no device copy is made).  msg (host, may be NULL) receives a
  * NUL-terminated reason of at most msg_cap bytes when the result is VDC_EPROGRAM. */
 int vdc_program_validate(vdc_executor *ex, const void *uops, int64_t n_uops, const uint32_t *stream_begin,

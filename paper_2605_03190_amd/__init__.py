@@ -48,6 +48,7 @@ def lib():
             "vdc_program_create": [vp, vp, i64, vp, vp, i32, vp, i32, pp],
             "vdc_program_validate": [vp, vp, i64, vp, vp, i32, vp, i32, ctypes.c_char_p, i32],
             "vdc_program_destroy": [vp],
+            "vdc_program_set_placement": [vp, i32],
             "vdc_run": [vp, vp, vp, i32, vp],
             "vdc_run_traced": [vp, vp, vp, i32, vp, vp, i32, vp],
             "vdc_sync_status": [vp, vp, vp],
@@ -79,7 +80,7 @@ def lib():
 
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
-           "vdc_program_destroy", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
+           "vdc_program_destroy", "vdc_program_set_placement", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
            "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_matvec_chain", "vdc_matvec_chain_program", "vdc_attn_decode", "vdc_attn_decode_program",
            "vdc_stream", "vdc_raw_stream",
            "vdc_stream_program", "vdc_debug_alloc", "vdc_strerror"]
@@ -114,6 +115,9 @@ class Program:
         if self.handle:
             _check(lib().vdc_program_destroy(self.handle), "vdc_program_destroy")
             self.handle = None
+
+    def set_placement(self, placement):
+        _check(lib().vdc_program_set_placement(self.handle, placement), "vdc_program_set_placement")
 
 
 class Executor:

@@ -29,6 +29,7 @@ struct vdc_program {
     bool uses_dep = false;
     uint32_t max_dep_id = 0;
     void *d_workspace = nullptr;   // matvec programs that split K: the [I | 0] tile and the partial results
+    int32_t placement = 0;         // which roles share a SIMD, see vdc_program_set_placement
 };
 
 struct MatvecKey {
@@ -1227,6 +1228,13 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.n_stu = ex->cfg.n_stu;
     p.V = ex->cfg.vcc_per_core;
     p.watchdog = (uint32_t)ex->cfg.watchdog_spins;
+    // Wave w of a workgroup runs on SIMD w % 4.  Placement 0 takes the roles in wave order (front end, load units, store
+    // unit, compute waves): with the default ten waves every SIMD then holds one compute wave.  Placement 1, for graphs
+    // bound by the front end and the store unit, keeps those two away from the compute waves: SIMD 0 = front end + load
+    // units 0, 1; SIMD 1 = store unit + load units 2, 3; SIMDs 2 and 3 = one wave of each compute core.
+    p.wave_roles = 0xFEDCBA9876543210ull;
+    if (prog->placement == 1 && ex->cfg.n_ldu == 4 && ex->cfg.n_stu == 1 && ex->cfg.vcc_per_core == 2)
+        p.wave_roles = 0xFEDCBA0000000000ull | 0x4298317650ull;
 #ifdef VDC_PROFILE
     if (!ex->d_prof && hipMalloc(&ex->d_prof, 8 * (16 * 8 * (size_t)ex->cfg.n_cores + 2 * 65536 + 8)) != hipSuccess) return VDC_ENOMEM;
     p.prof = ex->d_prof;
@@ -1457,6 +1465,12 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
             if (hipMalloc(&prog->d_workspace, ws.size() * 4) != hipSuccess) { vdc_program_destroy(prog); return VDC_ENOMEM; }
             if (hipMemcpy(prog->d_workspace, ws.data(), ws.size() * 4, hipMemcpyHostToDevice) != hipSuccess) { vdc_program_destroy(prog); return VDC_EDEVICE; }
         }
+        {
+            // one tile, one MATVEC and one STORE per row block: the front end and the store unit set the pace
+            int R = 0, Kt = 0;
+            if (!rope && choose_tile(ex->cfg, K, B, tile_bytes, R, Kt) && K <= Kt &&
+                rows / R >= 8 * (int64_t)ex->cfg.n_cores * ex->cfg.vcc_per_core) prog->placement = 1;   // and enough of them to matter
+        }
         ex->matvec_cache.push_back({key, prog});
     }
     void *bases[4] = {(void *)M, (void *)X, (void *)Y, rope ? (void *)T : prog->d_workspace};
@@ -1623,6 +1637,12 @@ int vdc_attn_decode_program(vdc_executor *ex, const int64_t *row_off, int32_t n_
     return fits ? VDC_OK : VDC_EINVAL;
 }
 
+int vdc_program_set_placement(vdc_program *prog, int32_t placement) {
+    if (!prog || (placement != 0 && placement != 1)) return VDC_EINVAL;
+    prog->placement = placement;
+    return VDC_OK;
+}
+
 int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64_t bytes, uint32_t value, int32_t tile_bytes,
                void *hip_stream) {
     if (!ex || ex->cfg.device == -1 || mode < 0 || mode > 2) return VDC_EINVAL;
@@ -1641,6 +1661,8 @@ int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64
         rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb,
                                 mode == 2 ? 2 : 1, &prog);
         if (rc != VDC_OK) return rc;
+        // a store per block: bound by the store unit and the front end (copies of 32 KB blocks by the load units again)
+        prog->placement = (mode == 1 || (mode == 2 && tile_bytes < 32768)) ? 1 : 0;
         ex->stream_cache.push_back({{mode, bytes, value, tile_bytes}, prog});
     }
     void *bases[2] = {mode == 1 ? dst : (void *)src, dst};

@@ -31,6 +31,8 @@ struct KParams {
     uint32_t *dep;          // depId counters
     uint32_t *finished;     // cores whose store unit has left (the last one clears the counters the program uses)
     uint32_t n_dep_used;    // depId counters the program uses (0: none)
+    uint64_t wave_roles;    // four bits per wave of the workgroup: the position in the role order (front end, load units,
+                            // store units, compute waves) that this wave takes
     uint32_t *status;       // ST_WORDS words
     uint32_t *trace;        // optional: n_streams * trace_cap * 4 words
     uint32_t *trace_count;  // optional: n_streams words

@@ -1996,7 +1996,9 @@ DEV void observer_main(Ctx &c, uint32_t V) {
 #define VDC_MAX_THREADS 704
 #endif
 __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) {
-    const uint32_t wave = uni(threadIdx.x >> 6);
+    // The hardware deals the waves of a workgroup round-robin over the four SIMDs of the compute unit, so which roles
+    // share a SIMD (and contend for its issue slots) is decided by which wave takes which role: the host chooses.
+    const uint32_t wave = uni((uint32_t)(p.wave_roles >> ((threadIdx.x >> 6) * 4u)) & 15u);
     Ctx c;
     c.p = &p;
     c.core = blockIdx.x;
