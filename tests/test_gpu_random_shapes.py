@@ -1,7 +1,7 @@
 """Seeded random shapes on the GPU, each against the oracle: the same operators as the other parity tests, on shapes nobody
 picked by hand (tails in every dimension, odd leading dimensions, ragged batches with empty segments, contexts from one
-row to several tiles, byte ranges with short rests, chains of uneven layers).  One executor, the launch configuration
-bench.py times."""
+row to several tiles, byte ranges with short rests, chains of uneven layers).  The launch configuration bench.py times, and the same
+with two store units per core."""
 import numpy as np
 import pytest
 import torch
@@ -16,9 +16,9 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.fixture(scope="module")
-def ex():
-    e = vdc.Executor()
+@pytest.fixture(scope="module", params=[dict(), dict(n_stu=2)], ids=["default", "two-store-units"])
+def ex(request):
+    e = vdc.Executor(**request.param)
     yield e
     e.destroy()
 
