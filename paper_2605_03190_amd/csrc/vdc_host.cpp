@@ -1235,6 +1235,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.wave_roles = 0xFEDCBA9876543210ull;
     if (prog->placement == 1 && ex->cfg.n_ldu == 4 && ex->cfg.n_stu == 1 && ex->cfg.vcc_per_core == 2)
         p.wave_roles = 0xFEDCBA0000000000ull | 0x4298317650ull;
+    // (With two store units, eleven waves, the like of it was measured and is no gain over the wave order: not taken.)
 #ifdef VDC_PROFILE
     if (!ex->d_prof && hipMalloc(&ex->d_prof, 8 * (16 * 8 * (size_t)ex->cfg.n_cores + 2 * 65536 + 8)) != hipSuccess) return VDC_ENOMEM;
     p.prof = ex->d_prof;
