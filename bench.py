@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--tile-bytes", type=int, default=0, help="override the configuration's tile (I/O block) size: 2048, 4096, 8192 or 16384")
     ap.add_argument("--slot-bytes", type=int, default=0, help="override the configuration's slot size")
     ap.add_argument("--n-stu", type=int, default=0, help="store units per core: 1 or 2 (0: the library's default)")
+    ap.add_argument("--tile-rows", type=int, default=0, help="rows per matrix tile (0: the tiler's choice)")
     ap.add_argument("--heads", type=int, default=8, help="attention workloads: key/value heads per request")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device-to-device copy of MIB mebibytes --steps times: "
@@ -186,7 +187,7 @@ def main():
     torch.cuda.synchronize()
     log("inputs: %s rows=%d K=%d B=%d tile=%d ragged=%s copies=%d (%.1f s)" % (cfg.name, rows, K, B, cfg.tile_bytes, ragged, n_copies, time.time() - t0))
 
-    ex = vdc.Executor(slot_bytes=cfg.slot_bytes, n_stu=args.n_stu)
+    ex = vdc.Executor(slot_bytes=cfg.slot_bytes, n_stu=args.n_stu, tile_rows=args.tile_rows)
     stream = torch.cuda.current_stream()
 
     def step(i):
