@@ -157,3 +157,25 @@ def test_attention_regimes_at_benchmark_size(regime):
         want = (torch.arange(len(lengths), device="cuda", dtype=torch.float32) * 0.25 + 1.0)[:, None].expand(-1, d)
         assert bool((torch.abs(O - want) <= 1e-5 * want).all())
     _free()
+
+
+@pytest.mark.parametrize("n_stu", [1, 2])
+def test_memory_uops_over_the_sweep_range(n_stu):
+    """The block-size sweep's own range and launch configurations (4 GiB, 16 KB and 32 KB blocks, one and two store units):
+    every byte of a copy and of a fill, and nothing past the range."""
+    _free()
+    nbytes = 4096 << 20
+    g = torch.Generator(device="cuda").manual_seed(7)
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, ((nbytes + 64) // 4,), dtype=torch.int32, device="cuda", generator=g).view(torch.uint8)
+    dst = torch.full((nbytes + 64,), 0xEE, dtype=torch.uint8, device="cuda")
+    with vdc.Executor(n_stu=n_stu) as ex:
+        for T in (16384, 32768):
+            dst.fill_(0xEE)
+            ex.stream("copy", src, dst, nbytes, T)
+            ex.check()
+            assert torch.equal(dst[:nbytes], src[:nbytes]) and bool((dst[nbytes:] == 0xEE).all())
+        ex.stream("fill", None, dst, nbytes, 16384, value=0x5A5A1234)
+        ex.check()
+        assert bool((dst[:nbytes].view(torch.int32) == 0x5A5A1234).all()) and bool((dst[nbytes:] == 0xEE).all())
+    del src, dst
+    _free()
