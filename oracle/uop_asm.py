@@ -44,10 +44,11 @@ def descriptor(tensor, box_rows, row_bytes, lds_pitch, gpitch):
     return (tensor, box_rows, row_bytes, lds_pitch, gpitch & 0xFFFFFFFF, gpitch >> 32, 0, 0)
 
 
-def matvec_imm(B, R, lpr):
-    """Static geometry of a MATVEC: B vectors, R box rows per matrix tile, lpr 16-byte chunks per tile row."""
-    assert 1 <= B <= 8 and 1 <= R < 65536 and 1 <= lpr < 65536
-    return B | (R << 8) | (lpr << 24)
+def matvec_imm(B, R, lpr, xspan=0):
+    """Static geometry of a MATVEC: B vectors, R box rows per matrix tile, lpr 16-byte chunks per tile row; xspan >= 2:
+    one vector tile holds the pieces of xspan consecutive steps, one per row (B = 1 only)."""
+    assert 1 <= B <= 8 and 1 <= R < 65536 and 1 <= lpr < 65536 and 0 <= xspan < 128 and (xspan < 2 or B == 1)
+    return B | (R << 8) | (lpr << 24) | (xspan << 40)
 
 
 def rope_imm(B, R):
@@ -110,11 +111,13 @@ class Program:
                 np.array(descs, dtype=np.uint32).reshape(-1, 8))
 
 
-def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_core=2, nt=False, rope=False):
+def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_core=2, nt=False, rope=False, xspan=0):
     """A straightforward dense Y = M X program in the form of the paper's listing (Section 4.1):
     row blocks of R rows are dealt round-robin to the (core, vcc) pairs; each row block is one MATVEC
     over ceil(K/Kt) (matrix tile, vector tile) pairs, followed by a send+recv STORE of the result.
     No loops, no accumulators: every address is a literal.  Tensors: 0 = M, 1 = X, 2 = Y.
+    xspan >= 2 (B = 1, K a multiple of Kt): one vector tile of xspan rows serves xspan consecutive steps; it is loaded
+    before the first matrix tile of those steps.
 
     rope=True builds the fused form of the running example of Section 3 (O = M @ N; R = rope(O, T)):
     the matvec result never goes to memory; a store.local / load.local pair hands its region on to a
@@ -139,9 +142,16 @@ def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_cor
             kv = min(Kt, K - k0)
             dm = p.desc(0, R, kv * 4, Kt * 4, ld * 4)
             dx = p.desc(1, B, kv * 4, Kt * 4, K * 4)
+            if xspan >= 2 and kt % xspan == 0:
+                assert B == 1 and K % Kt == 0
+                steps = min(xspan, nk - kt)
+                dxs = p.desc(1, xspan, Kt * 4, Kt * 4, Kt * 4)      # xspan pieces of the vector, one per row
+                vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=-(-xspan * Kt * 4 // slot_bytes), size=steps,
+                               imm=k0 * 4, desc=dxs))
             vm.append(word(LOAD, F_SEND | (F_NT if nt else 0), vflow=2 * v, vcc=v, nslots=m_slots, size=rv,
                            imm=(r0 * ld + k0) * 4, desc=dm))
-            vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=x_slots, size=B, imm=k0 * 4, desc=dx))
+            if xspan < 2:
+                vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=x_slots, size=B, imm=k0 * 4, desc=dx))
         dy = p.desc(2, B, rv * 4, R * 4, rows * 4)
         if rope:
             assert rv % 2 == 0 and (rv * 4) % 16 == 0
@@ -151,7 +161,7 @@ def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_cor
             vm.append(word(LOAD, F_SEND | F_LOCAL, vflow=4 + v, vcc=v, nslots=0, size=B, imm=0, desc=do))
             vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=y_slots, size=B, imm=r0 * 4, desc=dt))
         vm.append(word(STORE, F_SEND | F_RECV, vflow=4 + v, vcc=v, nslots=y_slots, size=B, imm=r0 * 4, desc=dy))
-        p.vcc(core, v).append(word(MATVEC, size=nk, imm=matvec_imm(B, R, lpr)))
+        p.vcc(core, v).append(word(MATVEC, size=nk, imm=matvec_imm(B, R, lpr, xspan)))
         if rope:
             p.vcc(core, v).append(word(ROPE, size=1, imm=rope_imm(B, R)))
     return p

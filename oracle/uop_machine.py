@@ -388,9 +388,35 @@ class Machine:
         B = u.imm & 0xFF
         R = (u.imm >> 8) & 0xFFFF
         lpr = (u.imm >> 24) & 0xFFFF
+        xspan = (u.imm >> 40) & 0x7F
         Kt = lpr * 4
         c = np.zeros((B, R), dtype=np.float64)            # alloc_registers: the accumulators
-        for _ in range(u.size):
+        if xspan >= 2:
+            # The tile shape is the tiler's to choose (the listing fixes none): with one vector, a vector tile may hold
+            # the pieces of `xspan` consecutive steps, one per row.  It is popped before the first matrix tile it
+            # serves, kept while the matrix tiles of its steps come and go, and handed back after the last of them.
+            if B != 1:
+                raise ProgramError("matvec: a vector tile over several steps needs B = 1")
+            held = None
+            for i in range(u.size):
+                if i % xspan == 0:
+                    if held is not None:
+                        self._c2m_push(core, v, KIND_FREE, held[0], held[1])
+                    held = yield                           # b = m2c.pop_wait(), for this and the next xspan - 1 steps
+                    if held[2] < min(xspan, u.size - i) or held[3] != Kt * 4:
+                        raise ProgramError("matvec: vector tile does not hold the steps it is popped for")
+                a = yield                                  # a = m2c.pop_wait()
+                a_slot, a_n, a_rows, a_rb = a
+                if a_rows > R:
+                    raise ProgramError("matvec: tile geometry does not match the uop")
+                at = core.region(a_slot, a_n).view(np.float32)[:R * Kt].reshape(R, Kt).astype(np.float64)
+                j = i % xspan
+                bt = core.region(held[0], held[1]).view(np.float32)[j * Kt:(j + 1) * Kt].reshape(1, Kt).astype(np.float64)
+                c += bt @ at.T
+                self._c2m_push(core, v, KIND_FREE, a_slot, a_n)
+            if held is not None:
+                self._c2m_push(core, v, KIND_FREE, held[0], held[1])
+        for _ in range(u.size if xspan < 2 else 0):
             a = yield                                      # a = m2c.pop_wait()
             b = yield                                      # b = m2c.pop_wait()
             a_slot, a_n, a_rows, a_rb = a

@@ -90,6 +90,64 @@ def test_dense_program_equals_gemv(rows, K, B, R, Kt, slot, ncores):
     _check_result(M, X, Y)
 
 
+@pytest.mark.parametrize("rows,K,R,Kt,slot,ncores,xspan", [
+    (40, 512, 8, 64, 2048, 2, 8),        # eight steps: one vector tile for the whole row block
+    (40, 512, 8, 64, 2048, 2, 4),        # two vector tiles of four steps
+    (33, 448, 8, 64, 1024, 3, 4),        # seven steps: the second vector tile holds three
+    (16, 256, 4, 128, 4096, 1, 2),
+])
+def test_a_vector_tile_over_several_steps_equals_gemv(rows, K, R, Kt, slot, ncores, xspan):
+    """MATVEC with one vector tile per xspan steps (B = 1): the textbook product, and also the bits of the program that
+    loads the vector step by step (the same products in the same order); every schedule gives the same image; a single
+    non-zero entry lands where it belongs (a slip in the row of the vector tile would move or lose it)."""
+    M, X, Y = _inputs(rows, K, 1, seed=rows + K + xspan)
+    p = A.dense_matvec_program(rows, K, K, 1, R, Kt, slot, ncores, xspan=xspan)
+    m = _run(p, [M, X, Y], slot_bytes=slot, n_slots=12)
+    _check_result(M, X, Y)
+    Y1 = np.full_like(Y, np.nan)
+    _run(A.dense_matvec_program(rows, K, K, 1, R, Kt, slot, ncores), [M, X, Y1], slot_bytes=slot, n_slots=12)
+    assert np.array_equal(Y, Y1)
+    for seed in range(10):
+        Y2 = np.full_like(Y, np.nan)
+        w, sb, d = p.finish()
+        UM.Machine(w, sb, d, [M, X, Y2], n_cores=ncores, slot_bytes=slot, n_slots=12).run("random", seed).check_final()
+        assert np.array_equal(Y, Y2)
+    for (i, j) in [(0, 0), (rows - 1, K - 1), (rows // 2, Kt + 1), (3, K - Kt)]:
+        M0 = np.zeros((rows, K), np.float32)
+        M0[i, j] = 2.0
+        X0 = np.arange(1, K + 1, dtype=np.float32)[None, :]
+        Y0 = np.full((1, rows), np.nan, np.float32)
+        _run(p, [M0, X0, Y0], slot_bytes=slot, n_slots=12)
+        exp = np.zeros(rows, np.float32)
+        exp[i] = 2.0 * (j + 1)
+        assert np.array_equal(Y0[0], exp)
+    # fewer vector loads than steps, and the vector tile goes back after the matrix tiles of its steps
+    loads_x = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 1)
+    loads_m = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 0)
+    nk, nrb = K // Kt, -(-rows // R)
+    assert loads_m == nk * nrb and loads_x == -(-nk // xspan) * nrb
+
+
+def test_a_vector_tile_over_several_steps_needs_one_vector_and_enough_rows():
+    M, X, Y = _inputs(16, 256, 2, seed=1)
+    p = A.dense_matvec_program(16, 256, 256, 2, 8, 64, 2048, 1)
+    w, sb, d = p.finish()
+    w = np.array(w, copy=True)
+    i = int(np.flatnonzero((w[:, 0] & 0xFF) == A.MATVEC)[0])
+    w[i, 3] |= 2 << 8                                    # xspan = 2 in imm[47:40] on a B = 2 uop
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(w, sb, d, [M, X, Y], n_cores=1, slot_bytes=2048, n_slots=12).run()
+    # a vector tile that holds fewer rows than the steps it is popped for
+    M, X, Y = _inputs(16, 512, 1, seed=2)
+    p = A.dense_matvec_program(16, 512, 512, 1, 8, 64, 2048, 1, xspan=4)
+    w, sb, d = p.finish()
+    w = np.array(w, copy=True)
+    ix = [k for k in range(len(w)) if (w[k, 0] & 0xFF) == A.LOAD and UM.decode(w[k]).size == 4 and d[UM.decode(w[k]).desc][0] == 1]
+    w[ix[0], 1] = (w[ix[0], 1] & 0xFFFF0000) | 3         # only three valid rows
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(w, sb, d, [M, X, Y], n_cores=1, slot_bytes=2048, n_slots=12).run()
+
+
 def test_leading_dimension():
     M, X, Y = _inputs(24, 40, 2, seed=9, ld=52)
     p = A.dense_matvec_program(24, 40, 52, 2, 8, 16, 1024, 2)
