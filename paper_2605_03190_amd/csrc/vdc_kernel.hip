@@ -1455,6 +1455,17 @@ DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n, uint32_t kind) {
     compiler_barrier();
 }
 
+// A region that was popped earlier and kept (its ticket already counted in vs.head) goes back as used: the same
+// arrival protocol as vcc_done_with, with the payload the caller saved at the pop.
+DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
+    compiler_barrier();
+    const uint32_t v = c.unit;
+    const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
+    if (before & 1u) lds_and32_lanes(1ull, c.ctl + CTL_OFF(mask), ~slot_bits((payload >> 1) & 63u, (payload >> 7) & 63u));
+    vs.group++;
+    compiler_barrier();
+}
+
 // Cross-lane reductions of the compute uops without a trip through the LDS crossbar: data-parallel-primitive (DPP)
 // operands move values inside a row of 16 lanes (and from the last lane of a row into the next rows), v_readlane takes
 // one value per row of 16 to the scalar side.
@@ -1504,8 +1515,12 @@ DEV float dot4(f32x4 m, f32x4 x, float acc) {
 //           4*(t % lpr) .. +3 and, in pass i, row i * (128 / lpr) + t / lpr.
 //   J >= 1: a tile row has 128 * J chunks: pass i holds chunks (i % J) * 128 + t of row i / J.
 // The vector tile is [B][4 * lpr] floats with the same row pitch.
-template <int B, int NF, int J>
-DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lpr) {
+// xspan >= 2 (B = 1, J = 0): one vector tile of xspan rows serves xspan consecutive steps, row j step j.  It is popped
+// before the first matrix tile of those steps, kept while they pass, and handed back after the last (the same
+// out-of-order return as the query tile of attn): half the memory uops per step for the front end.
+template <int B, int NF, int J, bool SPANS = false>
+DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lpr, uint32_t xspan) {
+    static_assert(!SPANS || (B == 1 && J == 0), "a vector tile over several steps: one vector, rows inside a wave");
     const KParams *p = c.p;
     const uint32_t v = c.unit;
     const uint32_t slot_shift = __builtin_ctz(p->slot_bytes);
@@ -1520,10 +1535,27 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
     const uint32_t c4 = (J == 0) ? (t & (lpr - 1u)) : t;
     const uint32_t pitch = lpr * 16u;
 
+    constexpr bool spans = SPANS;
+    uint32_t x_pay = 0, x_base = 0, xs = 0;      // the vector tile that is held, and the step inside it
     for (uint32_t it = 0; it < size; it++) {
         Msg ma, mb;
-        if (!vcc_pop_wait(c, vs, 2u, 0u, ma, mb)) return false;      // a = m2c.pop_wait(); b = m2c.pop_wait()
-        const uint32_t a_off = ma.slot << slot_shift, b_off = mb.slot << slot_shift;
+        uint32_t b_off;
+        if (spans) {
+            if (xs == 0u) {
+                if (it != 0u) vcc_return_kept(c, vs, x_pay);
+                if (!vcc_pop_wait(c, vs, 1u, 0u, mb, ma)) return false;
+                x_pay = vs.pay0;
+                vs.head += 1u;                   // popped; handed back after its last step
+                x_base = mb.slot << slot_shift;
+            }
+            if (!vcc_pop_wait(c, vs, 1u, 0u, ma, mb)) return false;
+            b_off = x_base + xs * pitch;
+            xs = xs + 1u == xspan ? 0u : xs + 1u;
+        } else {
+            if (!vcc_pop_wait(c, vs, 2u, 0u, ma, mb)) return false;  // a = m2c.pop_wait(); b = m2c.pop_wait()
+            b_off = mb.slot << slot_shift;
+        }
+        const uint32_t a_off = ma.slot << slot_shift;
         f32x4 xv[JJ][B];
 #pragma unroll
         for (int j = 0; j < JJ; j++)
@@ -1540,8 +1572,9 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
             for (int b = 0; b < B; b++) acc[ai][b] = dot4(m[i], xv[xi][b], acc[ai][b]);   // matvec_tile_accumulate
         }
         // every LDS read of both tiles has returned once its value was used: the regions can go back
-        vcc_done_with(c, vs, 2u, 0u);                                // c2m.push(a, b)
+        vcc_done_with(c, vs, spans ? 1u : 2u, 0u);                   // c2m.push(a, b)
     }
+    if (spans) vcc_return_kept(c, vs, x_pay);
 
     Msg mo, unused;
     if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;      // c_shared = m2c.pop_wait()
@@ -1598,15 +1631,24 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
 }
 
 template <int B>
-DEV bool matvec_dispatch_b(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lpr, uint32_t nf, uint32_t j) {
+DEV bool matvec_dispatch_b(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lpr, uint32_t nf, uint32_t j, uint32_t xspan) {
 #define VDC_MV(NF_, J_) \
-    if (nf == NF_ && j == J_) return matvec_uop<B, NF_, J_>(c, vs, size, R, lpr);
+    if (nf == NF_ && j == J_ && xspan < 2u) return matvec_uop<B, NF_, J_>(c, vs, size, R, lpr, xspan);
     VDC_MV(1, 0) VDC_MV(2, 0) VDC_MV(4, 0) VDC_MV(8, 0)
     VDC_MV(1, 1) VDC_MV(2, 1) VDC_MV(4, 1) VDC_MV(8, 1)
     if constexpr (B * 2 <= 16) { VDC_MV(2, 2) VDC_MV(4, 2) VDC_MV(8, 2) }
     if constexpr (B * 4 <= 16) { VDC_MV(4, 4) VDC_MV(8, 4) }
     if constexpr (B * 8 <= 16) { VDC_MV(8, 8) }
 #undef VDC_MV
+    if constexpr (B == 1) {
+        // the variant that keeps a vector tile over several steps is a code path of its own: the usual one pays nothing
+        if (xspan >= 2u && j == 0u) {
+            if (nf == 1u) return matvec_uop<1, 1, 0, true>(c, vs, size, R, lpr, xspan);
+            if (nf == 2u) return matvec_uop<1, 2, 0, true>(c, vs, size, R, lpr, xspan);
+            if (nf == 4u) return matvec_uop<1, 4, 0, true>(c, vs, size, R, lpr, xspan);
+            if (nf == 8u) return matvec_uop<1, 8, 0, true>(c, vs, size, R, lpr, xspan);
+        }
+    }
     raise_error(c, -3 /* VDC_EPROGRAM */, 0xC00u);
     return false;
 }
@@ -1615,17 +1657,22 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     const uint32_t B = (uint32_t)f.imm & 0xFFu, R = (uint32_t)(f.imm >> 8) & 0xFFFFu, lpr = (uint32_t)(f.imm >> 24) & 0xFFFFu;
     const uint32_t nf = (R * lpr) >> 7;
     const uint32_t j = lpr <= 64u ? 0u : lpr >> 7;
+    const uint32_t xspan = matvec_xspan(f.imm);
+    if (xspan >= 2u && (B != 1u || j != 0u || xspan > kMaxXspan)) {
+        raise_error(c, -3 /* VDC_EPROGRAM */, 0xC10u);
+        return false;
+    }
     switch (B) {
-        case 1: return matvec_dispatch_b<1>(c, vs, f.size, R, lpr, nf, j);
+        case 1: return matvec_dispatch_b<1>(c, vs, f.size, R, lpr, nf, j, xspan);
 #ifndef VDC_ONLY_B1_AND_B8   /* set only by throw-away experiment builds to shorten the compile */
-        case 2: return matvec_dispatch_b<2>(c, vs, f.size, R, lpr, nf, j);
-        case 3: return matvec_dispatch_b<3>(c, vs, f.size, R, lpr, nf, j);
-        case 4: return matvec_dispatch_b<4>(c, vs, f.size, R, lpr, nf, j);
-        case 5: return matvec_dispatch_b<5>(c, vs, f.size, R, lpr, nf, j);
-        case 6: return matvec_dispatch_b<6>(c, vs, f.size, R, lpr, nf, j);
-        case 7: return matvec_dispatch_b<7>(c, vs, f.size, R, lpr, nf, j);
+        case 2: return matvec_dispatch_b<2>(c, vs, f.size, R, lpr, nf, j, xspan);
+        case 3: return matvec_dispatch_b<3>(c, vs, f.size, R, lpr, nf, j, xspan);
+        case 4: return matvec_dispatch_b<4>(c, vs, f.size, R, lpr, nf, j, xspan);
+        case 5: return matvec_dispatch_b<5>(c, vs, f.size, R, lpr, nf, j, xspan);
+        case 6: return matvec_dispatch_b<6>(c, vs, f.size, R, lpr, nf, j, xspan);
+        case 7: return matvec_dispatch_b<7>(c, vs, f.size, R, lpr, nf, j, xspan);
 #endif
-        case 8: return matvec_dispatch_b<8>(c, vs, f.size, R, lpr, nf, j);
+        case 8: return matvec_dispatch_b<8>(c, vs, f.size, R, lpr, nf, j, xspan);
         default:
             raise_error(c, -3 /* VDC_EPROGRAM */, 0xD00u);
             return false;
@@ -1726,17 +1773,6 @@ DEV bool copy_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t chunks) {
         vcc_done_with(c, vs, 1u, 1u);
     }
     return true;
-}
-
-// A region that was popped earlier and kept (its ticket already counted in vs.head) goes back as used: the same
-// arrival protocol as vcc_done_with, with the payload the caller saved at the pop.
-DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
-    compiler_barrier();
-    const uint32_t v = c.unit;
-    const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
-    if (before & 1u) lds_and32_lanes(1ull, c.ctl + CTL_OFF(mask), ~slot_bits((payload >> 1) & 63u, (payload >> 7) & 63u));
-    vs.group++;
-    compiler_barrier();
 }
 
 // Sum over the G = 4 or 8 consecutive lanes that share a key row; every lane of the group gets the sum.
