@@ -42,6 +42,18 @@ def test_random_dense_and_ragged_matvecs(ex):
         Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
         worst = float((np.abs(Y.cpu().numpy() - Yr) / (1e-5 * Ya + 1e-30)).max())
         assert worst <= 1.0, "dense case %d: rows %d K %d ld %d B %d tile %d: %.3g" % (case, rows, K, ld, B, tile, worst)
+    # one vector, K a whole number of tiles: the form with vector tiles over several steps
+    for case in range(16):
+        tile = int(rng.choice([2048, 4096, 8192, 16384]))
+        rows, K = int(rng.integers(1, 20000)), 256 * int(rng.integers(2, 40))
+        M = rng.standard_normal((rows, K)).astype(np.float32)
+        X = rng.standard_normal((1, K)).astype(np.float32)
+        Y = torch.full((1, rows), float("nan"), device="cuda")
+        ex.matvec(_dev(M), _dev(X), Y, tile)
+        ex.check()
+        Yr, Ya = gemv_ref.gemv_dense(M, X)
+        worst = float((np.abs(Y.cpu().numpy() - Yr) / (1e-5 * Ya + 1e-30)).max())
+        assert worst <= 1.0, "one-vector case %d: rows %d K %d tile %d: %.3g" % (case, rows, K, tile, worst)
     for case in range(12):
         n_seg = int(rng.integers(1, 40))
         lengths = rng.integers(0, 400, n_seg)
