@@ -1404,13 +1404,14 @@ int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const
     p->uses_dep = val.uses_dep;
     p->max_dep_id = val.max_dep;
     HIP_TRY(hipSetDevice(ex->cfg.device));
-    const size_t wb = (size_t)n_uops * sizeof(Word), sbb = (size_t)(n_streams + 1) * 4, db = (size_t)n_descs * sizeof(Desc);
+    const size_t wb = (size_t)n_uops * sizeof(Word), sbb = (size_t)(n_streams + 1) * 4, db = (size_t)std::max(n_descs, 1) * sizeof(Desc);   // never an empty table: the front end reads entry 0 for uops without one
     if (hipMalloc(&p->d_words, wb) != hipSuccess) return VDC_ENOMEM;
     if (hipMalloc(&p->d_stream_begin, sbb) != hipSuccess) { (void)hipFree(p->d_words); return VDC_ENOMEM; }
     if (hipMalloc(&p->d_descs, db) != hipSuccess) { (void)hipFree(p->d_words); (void)hipFree(p->d_stream_begin); return VDC_ENOMEM; }
     hipError_t e = hipMemcpy(p->d_words, uops, wb, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(p->d_stream_begin, stream_begin, sbb, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(p->d_descs, descs, db, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(p->d_descs, 0, db);
+    if (e == hipSuccess && n_descs > 0) e = hipMemcpy(p->d_descs, descs, (size_t)n_descs * sizeof(Desc), hipMemcpyHostToDevice);
     if (e != hipSuccess) { (void)hipFree(p->d_words); (void)hipFree(p->d_stream_begin); (void)hipFree(p->d_descs); return VDC_EDEVICE; }
     ex->programs.push_back(p.get());
     *out = p.release();

@@ -482,7 +482,26 @@ struct DecWin {
     uint64_t t0, t1;     // wave-uniform: lanes whose uop sends to compute core 0 / 1
 };
 
-DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) {
+// The descriptor table as the front end keeps it: lane l holds the six words it needs of descriptor l (programs rarely
+// have more than a handful; beyond 64 the table is read from memory as before).  It is fetched once, at the same time as
+// the stream's bounds, so decoding a window costs one trip to memory (the uops) instead of two dependent ones.
+struct DescRegs {
+    uint32_t w[6];
+    bool all;        // every descriptor of the program is in the lanes
+};
+
+DEV DescRegs desc_regs_load(Ctx &c) {
+    const KParams *p = c.p;
+    DescRegs r;
+    const uint32_t nd = p->n_descs ? p->n_descs : 1u;
+    const uint32_t *dp = (const uint32_t *)(p->descs + (c.lane < nd ? c.lane : nd - 1u));
+#pragma unroll
+    for (int k = 0; k < 6; k++) r.w[k] = dp[k];
+    r.all = p->n_descs <= 64u;
+    return r;
+}
+
+DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, const DescRegs &dr, uint32_t pc, uint32_t end) {
     const KParams *p = c.p;
     uint32_t idx = pc + c.lane;
     if (idx >= end) idx = end - 1u;             // the stream's HALT
@@ -491,8 +510,18 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, uint32_t pc, uint32_t end) 
     const Fields f = decode(w);
     const bool is_mem = f.opcode == OP_LOAD || f.opcode == OP_STORE;
     const uint32_t di = (is_mem && f.desc < p->n_descs) ? f.desc : 0u;
-    const uint32_t *dp = (const uint32_t *)(p->descs + di);
-    const uint32_t d_tensor = dp[0], d_box = dp[1], d_rowb = dp[2], d_pitch = dp[3], d_gplo = dp[4], d_gphi = dp[5];
+    uint32_t d_tensor, d_box, d_rowb, d_pitch, d_gplo, d_gphi;
+    if (dr.all) {
+        d_tensor = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(di * 4u), (int)dr.w[0]);
+        d_box = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(di * 4u), (int)dr.w[1]);
+        d_rowb = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(di * 4u), (int)dr.w[2]);
+        d_pitch = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(di * 4u), (int)dr.w[3]);
+        d_gplo = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(di * 4u), (int)dr.w[4]);
+        d_gphi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(di * 4u), (int)dr.w[5]);
+    } else {
+        const uint32_t *dp = (const uint32_t *)(p->descs + di);
+        d_tensor = dp[0]; d_box = dp[1]; d_rowb = dp[2]; d_pitch = dp[3]; d_gplo = dp[4]; d_gphi = dp[5];
+    }
     uint64_t tbase = 0;
 #pragma unroll
     for (int t = 0; t < kMaxTensors; t++) tbase = ((d_tensor & (kMaxTensors - 1)) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tbase;
@@ -567,6 +596,7 @@ DEV void cfu_main(Ctx &c) {
     const uint32_t n_slots = p->n_slots, n_ldu = p->n_ldu, n_units = p->n_ldu + p->n_stu;
     const uint32_t stream = c.core * (1u + p->V);
     Seq s;
+    const DescRegs dr = desc_regs_load(c);        // in flight together with the stream's bounds
     s.pc = cload(p->stream_begin, stream);
     s.end = cload(p->stream_begin, stream + 1u);
     s.depth = 0; s.rf_lo = 0; s.rf_hi = 0; s.win_base = 0; s.win = u32x4{0u, 0u, 0u, 0u};
@@ -574,7 +604,7 @@ DEV void cfu_main(Ctx &c) {
     CfuState st = {0, 0, 0, 0, 0, 0};
     uint32_t trace_n = 0;
     DecWin d;
-    bool ok = cfu_refill(c, d, st, s.pc, s.end);
+    bool ok = cfu_refill(c, d, st, dr, s.pc, s.end);
 
     // The innermost loop frame is kept in scalars (top_start, top_left); outer frames wait in lanes 8.. of the
     // register file.  Accumulators are updated by a masked vector add, so that a control uop never moves a value
@@ -589,7 +619,7 @@ DEV void cfu_main(Ctx &c) {
         uint32_t k = s.pc - d.base;
         if (__builtin_expect(k >= (uint32_t)kWin, 0)) {
             PHASE(c, 0u, 7u);
-            if (!cfu_refill(c, d, st, s.pc, s.end)) { ok = false; break; }
+            if (!cfu_refill(c, d, st, dr, s.pc, s.end)) { ok = false; break; }
             k = 0;
         }
         const uint32_t ctlw = rf_get(d.ctl, k);
