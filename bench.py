@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the factors a plain copy
 # kernel of known size gives); see profiles/ for the runs.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"cfg5": 8623518290}
+MEASURED_TRAFFIC_BYTES = {"cfg5": 8623334289}
 
 
 def log(*a):
