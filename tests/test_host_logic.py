@@ -29,8 +29,15 @@ def test_strerror_and_defaults_are_the_paper_deployment():
     assert vdc.strerror(0) == "ok" and "watchdog" in vdc.strerror(vdc.VDC_EDEADLOCK)
     with vdc.Executor(device=-1) as ex:
         c = ex.cfg
-        # Table 1 caption: 1 VMC + 2 VCCs per CU, 8 KB slots; Section 4.3: 128 threads per execution unit, 32-bit mask
-        assert (c.vcc_per_core, c.slot_bytes, c.threads_per_eu) == (2, 8192, 128)
+        # the values the paper prints (tests/golden/deployment_constants.txt): 1 VMC + 2 VCCs per CU, 8 KB slots,
+        # 128 threads per execution unit, a 32-bit mask
+        g = {}
+        for line in open(os.path.join(ROOT, "tests", "golden", "deployment_constants.txt")):
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                g[line[0]] = int(line[1])
+        assert (c.vcc_per_core, c.slot_bytes, c.threads_per_eu) == (g["vcc_per_core"], g["slot_bytes"], g["threads_per_eu"]) == (2, 8192, 128)
+        assert c.n_slots <= g["mask_bits"]
         assert 1 <= c.n_slots <= 32 and c.n_slots * c.slot_bytes <= 160 * 1024
         assert c.n_cores == 256 and c.n_ldu == 4 and c.n_stu == 1
 

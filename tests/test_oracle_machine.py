@@ -329,14 +329,33 @@ def test_dep_id_orders_a_store_before_a_dependent_load():
         assert m.dep[5] == 1
 
 
+def _golden_constants():
+    import os
+    out = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "deployment_constants.txt")):
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            out[line[0]] = int(line[1])
+    return out
+
+
 def test_paper_deployment_constants_are_the_defaults():
-    # Table 1 caption and Section 4.3: one VMC and two VCCs per core, 8 KB slots, a 32-bit slot mask
+    # the values the paper prints (tests/golden/deployment_constants.txt, each with the passage that states it):
+    # one VMC and two VCCs per core, 8 KB slots, a 32-bit slot mask
     import inspect
+    g = _golden_constants()
     sig = inspect.signature(UM.Machine.__init__).parameters
-    assert sig["vcc_per_core"].default == 2 and sig["slot_bytes"].default == 8192
+    assert sig["vcc_per_core"].default == g["vcc_per_core"] == 2 and sig["slot_bytes"].default == g["slot_bytes"] == 8192
+    assert g["mask_bits"] == 32 and g["vmc_per_core"] == 1
     with pytest.raises(AssertionError):
         UM.Machine(np.zeros((1, 4), np.uint32), np.zeros(4, np.uint32), np.zeros((1, 8), np.uint32), [],
-                   n_cores=1, n_slots=33)
+                   n_cores=1, n_slots=g["mask_bits"] + 1)
+    # Section 3's example: four core pairs, the matrix cut along its rows, every pair one row block; the product comes out
+    rows, K = 4 * 8, 64
+    M, X, Y = _inputs(rows, K, 1, seed=3)
+    m = _run(A.dense_matvec_program(rows, K, K, 1, 8, 64, 8192, g["example_cores"], vcc_per_core=1), [M, X, Y], slot_bytes=8192, n_slots=8)
+    _check_result(M, X, Y)
+    assert [sum(1 for r in t if r[1] == UM.STORE) for t in m.trace_vmc] == [1] * g["example_cores"]
 
 
 # ---- memory uops with no arithmetic behind them (Section 6.3, "Memory virtual core overhead") -------
