@@ -1217,13 +1217,23 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
     }
     for (int c = 0; c < C; c++)
         for (auto *lists : {&steps, &merges}) {
-            size_t longest = 0;
-            for (int v = 0; v < V; v++) longest = std::max(longest, (*lists)[(size_t)c * V + v].size());
-            for (size_t i = 0; i < longest; i++)
+            // the steps of the core's compute cores in turn, each list at its own pace, so that they end together (the
+            // lists of a core differ in length when contexts are uneven; strict alternation left one compute core alone
+            // at the end)
+            std::vector<size_t> at((size_t)V, 0);
+            for (;;) {
+                int pick = -1;
+                double best = 2.0;
                 for (int v = 0; v < V; v++) {
-                    auto &l = (*lists)[(size_t)c * V + v];
-                    if (i < l.size()) t.vmc(c).insert(t.vmc(c).end(), l[i].begin(), l[i].end());
+                    const auto &l = (*lists)[(size_t)c * V + v];
+                    if (at[(size_t)v] >= l.size()) continue;
+                    const double prog = (double)at[(size_t)v] / (double)l.size();
+                    if (prog < best) { best = prog; pick = v; }
                 }
+                if (pick < 0) break;
+                const auto &g = (*lists)[(size_t)c * V + pick][at[(size_t)pick]++];
+                t.vmc(c).insert(t.vmc(c).end(), g.begin(), g.end());
+            }
         }
     words.clear();
     sb.assign(1, 0);
