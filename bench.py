@@ -137,6 +137,7 @@ def main():
     ap.add_argument("--n-stu", type=int, default=0, help="store units per core: 1 or 2 (0: the library's default)")
     ap.add_argument("--tile-rows", type=int, default=0, help="rows per matrix tile (0: the tiler's choice)")
     ap.add_argument("--heads", type=int, default=8, help="attention workloads: key/value heads per request")
+    ap.add_argument("--per-launch", action="store_true", help="log the duration of every timed launch (stderr)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device-to-device copy of MIB mebibytes --steps times: "
                          "the known traffic that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -215,6 +216,8 @@ def main():
     kern_ms = [s.elapsed_time(e) for s, e in zip(starts, ends)]
     kern_avg_ms = float(np.mean(kern_ms))
     ms_per_step = t_total * 1e3 / args.steps
+    if args.per_launch:
+        log("per launch, ms: " + " ".join("%.4f" % x for x in kern_ms))
     elements = rows * K
     value = elements * args.steps / t_total
     alg = algorithmic_bytes(rows, K, B, w.X.shape[0])

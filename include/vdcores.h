@@ -109,8 +109,9 @@ int vdc_program_validate(vdc_executor *ex, const void *uops, int64_t n_uops, con
                          char *msg, int32_t msg_cap);
 
 /* Run a program (Section 3: submit the uop graph to the on-GPU executors, which run until it finishes).
- * tensor_bases: host array of n_tensors device pointers, each 16-byte aligned and at least as large as
- * declared at vdc_program_create.  Asynchronous on hip_stream. */
+ * tensor_bases: host array of n_tensors device pointers, each at least as large as declared at
+ * vdc_program_create; a tensor that some LOAD reads must be 16-byte aligned, any other 4-byte aligned
+ * (VDC_EINVAL otherwise).  Asynchronous on hip_stream. */
 int vdc_run(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors,
             void *hip_stream);
 
@@ -137,7 +138,11 @@ int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info);
  * shape), validates it and runs it.  Asynchronous on hip_stream.
  * The first call for a shape builds and uploads the program (device allocations, a synchronous copy); later calls
  * for the same shape only enqueue kernels, so a caller may capture them in a HIP graph.  The same holds for the
- * other operators below (vdc_matvec_rope, vdc_matvec_ragged, vdc_attn_decode, vdc_stream). */
+ * other operators below (vdc_matvec_rope, vdc_matvec_ragged, vdc_matvec_chain, vdc_attn_decode, vdc_stream).
+ * Cache policy: an executor keeps at most 64 operator programs, keyed by everything the uop graph depends on (shapes,
+ * tile size, every segment or context offset).  A call that needs a 65th destroys the least recently used one first,
+ * which waits for the device.  A caller whose offsets change on every call (contexts that grow by a token per step)
+ * therefore pays a rebuild per call; its memory use stays bounded. */
 int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
                int32_t B, int32_t tile_bytes, void *hip_stream);
 
@@ -205,7 +210,7 @@ int vdc_matvec_chain_program(vdc_executor *ex, const int64_t *dims, int32_t L, i
  * Q [n_seg][d], O [n_seg][d], K and V [row_off[n_seg]][d] (the contexts back to back): device, fp32, row-major,
  * 16-byte aligned, caller-owned; row_off: host, n_seg + 1 offsets, row_off[0] = 0, every request at least one row.
  * d = 128 or 64; tile_bytes in {4096, 8192, 16384} (tile_bytes / (4 d) context rows per key / value tile);
- * n_seg <= n_dep_ids.
+ * n_seg <= n_dep_ids.  scale > 0, or scale <= 0 for the usual d^(-1/2) (computed in fp32 as 1 / sqrtf(d)).
  * A context is cut into items of consecutive tiles that balance over the compute cores; every item leaves a partial row
  * (weighted values, running maximum, running sum) in a library-owned workspace and signals the request's depId; one
  * compute core per request merges its rows.  fp32 arithmetic, exp() of differences to the running maximum only.

@@ -296,14 +296,14 @@ class Executor:
         row_off: host offsets (n_seg + 1).  Asynchronous."""
         ro = np.ascontiguousarray(row_off, dtype=np.int64)
         d = Q.shape[1]
-        scale = float(d) ** -0.5 if scale is None else float(scale)
+        scale = 0.0 if scale is None else float(scale)     # 0: the library takes d ** -0.5
         _check(lib().vdc_attn_decode(self.handle, Q.data_ptr(), K.data_ptr(), V.data_ptr(), _np_ptr(ro), len(ro) - 1, d, scale,
                                      O.data_ptr(), tile_bytes, _stream_ptr(stream)), "vdc_attn_decode")
 
     def attn_decode_program(self, row_off, d, tile_bytes, scale=None):
         """The uop graph attn_decode would run: (words, stream_begin, descs, n_items)."""
         ro = np.ascontiguousarray(row_off, dtype=np.int64)
-        scale = float(d) ** -0.5 if scale is None else float(scale)
+        scale = 0.0 if scale is None else float(scale)     # 0: the library takes d ** -0.5
         n_w, n_d, n_i = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int64(0)
         f = lib().vdc_attn_decode_program
         _check(f(self.handle, _np_ptr(ro), len(ro) - 1, d, scale, tile_bytes, None, ctypes.byref(n_w), None, None, ctypes.byref(n_d),

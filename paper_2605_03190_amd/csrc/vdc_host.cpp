@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <deque>
@@ -28,20 +29,24 @@ struct vdc_program {
     int64_t tensor_bytes[kMaxTensors] = {0};
     bool uses_dep = false;
     uint32_t max_dep_id = 0;
+    uint32_t loaded_tensors = 0;   // bit t: some LOAD reads tensor t (its base must be 16-byte aligned: 128-bit loads)
     void *d_workspace = nullptr;   // matvec programs that split K: the [I | 0] tile and the partial results
     int32_t placement = 0;         // which roles share a SIMD, see vdc_program_set_placement
 };
 
-struct MatvecKey {
-    int64_t rows, K, ld;
-    int32_t B, tile_bytes, n_seg;
-    std::vector<int64_t> row_off;
-    bool rope = false;
-    bool operator==(const MatvecKey &o) const {
-        return rows == o.rows && K == o.K && ld == o.ld && B == o.B && tile_bytes == o.tile_bytes && n_seg == o.n_seg &&
-               row_off == o.row_off && rope == o.rope;
-    }
+// The operators cache the programs they build.  A key is the operator's kind followed by everything the uop graph
+// depends on (shapes, tile size, segment offsets, ...), as one vector of 64-bit words, looked up by hash and then by
+// content.  The cache is bounded: beyond kProgramCacheCap entries the least recently used program is destroyed (after a
+// device synchronisation, inside vdc_program_destroy), so a caller whose shapes change on every call (decode attention
+// with growing contexts) pays a rebuild per call but does not grow device memory without limit.
+constexpr size_t kProgramCacheCap = 64;
+struct CachedProgram {
+    uint64_t hash;
+    std::vector<int64_t> key;
+    vdc_program *prog;
+    uint64_t last_use;
 };
+enum ProgramKind : int64_t { PK_MATVEC = 1, PK_CHAIN = 2, PK_ATTN = 3, PK_STREAM = 4 };
 
 struct vdc_executor {
     vdc_config cfg{};
@@ -54,13 +59,8 @@ struct vdc_executor {
     unsigned long long *d_prof = nullptr;
 #endif
     std::vector<vdc_program *> programs;
-    std::vector<std::pair<MatvecKey, vdc_program *>> matvec_cache;
-    struct ChainKey { std::vector<int64_t> dims; int32_t B, tile_bytes; };
-    std::vector<std::pair<ChainKey, vdc_program *>> chain_cache;
-    struct AttnKey { std::vector<int64_t> row_off; int32_t d; float scale; int32_t tile_bytes; };
-    std::vector<std::pair<AttnKey, vdc_program *>> attn_cache;
-    struct StreamKey { int32_t mode; int64_t bytes; uint32_t value; int32_t tile_bytes; };
-    std::vector<std::pair<StreamKey, vdc_program *>> stream_cache;
+    std::vector<CachedProgram> cache;
+    uint64_t use_clock = 0;
 };
 
 namespace {
@@ -73,6 +73,52 @@ int hip_fail(hipError_t) { return VDC_EDEVICE; }
     } while (0)
 
 bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+
+uint64_t key_hash(const std::vector<int64_t> &k) {   // FNV-1a over the words
+    uint64_t h = 1469598103934665603ull;
+    for (int64_t w : k) {
+        h ^= (uint64_t)w;
+        h *= 1099511628211ull;
+    }
+    return h;
+}
+
+vdc_program *cache_find(vdc_executor *ex, const std::vector<int64_t> &key) {
+    const uint64_t h = key_hash(key);
+    for (CachedProgram &c : ex->cache)
+        if (c.hash == h && c.key == key) {
+            c.last_use = ++ex->use_clock;
+            return c.prog;
+        }
+    return nullptr;
+}
+
+// Adds a program; evicts the least recently used one first when the cache is full.
+void cache_insert(vdc_executor *ex, std::vector<int64_t> key, vdc_program *prog) {
+    if (ex->cache.size() >= kProgramCacheCap) {
+        size_t lru = 0;
+        for (size_t i = 1; i < ex->cache.size(); i++)
+            if (ex->cache[i].last_use < ex->cache[lru].last_use) lru = i;
+        vdc_program *victim = ex->cache[lru].prog;
+        ex->cache.erase(ex->cache.begin() + (long)lru);
+        (void)vdc_program_destroy(victim);     // waits for the device, then frees the program's device memory
+    }
+    const uint64_t h = key_hash(key);
+    ex->cache.push_back({h, std::move(key), prog, ++ex->use_clock});
+}
+
+// The factor on the scores: the caller's, or (scale <= 0) the usual d^(-1/2).  False for a value that is not a number.
+bool attn_scale_resolve(float &scale, int32_t d) {
+    if (scale != scale || d < 1) return false;
+    if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)d);
+    return true;
+}
+
+int64_t float_bits(float x) {
+    uint32_t b;
+    memcpy(&b, &x, 4);
+    return (int64_t)b;
+}
 
 // ------------------------------------------------------------------------------------------------------------
 // Validation: run the abstract machine without data.  Every core's front end walks its stream in program order,
@@ -131,6 +177,7 @@ struct Validator {
     std::string err;
     bool uses_dep = false;
     uint32_t max_dep = 0;
+    uint32_t loaded_tensors = 0;
     std::vector<uint32_t> dep;
     int64_t steps = 0;
 
@@ -164,12 +211,12 @@ struct Validator {
                 return 1;
             case OP_REPEAT:
                 if (s.loops.empty()) { fail("REPEAT without LOOP"); return -1; }
-                s.acc[f.acc] += f.imm;
+                if (__builtin_add_overflow(s.acc[f.acc], f.imm, &s.acc[f.acc])) { fail("accumulator overflow"); return -1; }
                 if (--s.loops.back().second > 0) s.pc = s.loops.back().first;
                 else { s.loops.pop_back(); s.pc++; }
                 return 1;
             case OP_ADD:
-                s.acc[f.acc] += f.imm;
+                if (__builtin_add_overflow(s.acc[f.acc], f.imm, &s.acc[f.acc])) { fail("accumulator overflow"); return -1; }
                 s.pc++;
                 return 1;
             case OP_SET:
@@ -223,6 +270,7 @@ struct Validator {
         }
         const uint64_t gpitch = (uint64_t)d.gpitch_lo | ((uint64_t)d.gpitch_hi << 32);
         if ((int)d.tensor >= n_tensors) { fail("tensor id out of range"); return -1; }
+        if (is_load) loaded_tensors |= 1u << d.tensor;
         if (d.box_rows < 1 || d.box_rows > 65535 || d.lds_pitch < 4 || d.lds_pitch > 65535 || d.row_bytes < 4 ||
             d.row_bytes > d.lds_pitch) { fail("bad descriptor box"); return -1; }
         if (is_load ? (d.lds_pitch % 16 || d.row_bytes % 16 || gpitch % 16) : (d.lds_pitch % 4 || d.row_bytes % 4 || gpitch % 4)) {
@@ -243,10 +291,16 @@ struct Validator {
             uses_dep = true;
             max_dep = std::max(max_dep, f.dep_id);
         }
-        const int64_t eff = f.imm + ((f.flags & F_DYNAMIC) ? s.acc[f.acc] : 0);
+        int64_t eff = f.imm;
+        if ((f.flags & F_DYNAMIC) && __builtin_add_overflow(eff, s.acc[f.acc], &eff)) { fail("effective address overflows"); return -1; }
         if (eff < 0 || (eff % (is_load ? 16 : 4)) != 0) { fail("effective address negative or misaligned"); return -1; }
-        const uint64_t last = (uint64_t)eff + (uint64_t)(f.size - 1) * gpitch + d.row_bytes;
-        if (!local && last > (uint64_t)tensor_bytes[d.tensor]) { fail("memory uop reaches beyond its tensor"); return -1; }
+        // the last byte the box touches, in arithmetic that cannot wrap: a pitch of 2^63 must not pass as zero
+        if (!local) {
+            const uint64_t tb = tensor_bytes[d.tensor] > 0 ? (uint64_t)tensor_bytes[d.tensor] : 0ull;
+            uint64_t span = 0, last = 0;
+            if (__builtin_mul_overflow((uint64_t)(f.size - 1), gpitch, &span) || __builtin_add_overflow((uint64_t)eff, span, &last) ||
+                __builtin_add_overflow(last, (uint64_t)d.row_bytes, &last) || last > tb) { fail("memory uop reaches beyond its tensor"); return -1; }
+        }
         // a DEP_RECV whose counter is not there yet blocks its unit, not the front end; in this in-order model the
         // front end waits as well, which is conservative
         if ((f.flags & F_DEP_RECV) && dep[f.dep_id] < std::max<uint32_t>(1u, f.dep_count)) return 0;
@@ -1284,7 +1338,9 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.descs = prog->d_descs;
     p.n_descs = (uint32_t)prog->n_descs;
     for (int i = 0; i < n_tensors; i++) {
-        if (!tensor_bases[i] || ((uintptr_t)tensor_bases[i] & 3u)) return VDC_EINVAL;
+        // tiles are loaded in 16-byte units, results stored in units of 4 bytes or more
+        const uintptr_t align = ((prog->loaded_tensors >> i) & 1u) ? 15u : 3u;
+        if (!tensor_bases[i] || ((uintptr_t)tensor_bases[i] & align)) return VDC_EINVAL;
         p.tensors[i] = (char *)tensor_bases[i];
     }
     p.dep = ex->d_dep;
@@ -1358,10 +1414,16 @@ int vdc_create(vdc_executor **out, const vdc_config *cfg_in) {
     if (hipMalloc(&ex->d_dep, sizeof(uint32_t) * cfg.n_dep_ids) != hipSuccess) return VDC_ENOMEM;
     if (hipMalloc(&ex->d_status, sizeof(uint32_t) * (ST_WORDS + 4)) != hipSuccess) { (void)hipFree(ex->d_dep); return VDC_ENOMEM; }
     if (hipHostMalloc(&ex->h_status, sizeof(uint32_t) * ST_WORDS) != hipSuccess) { (void)hipFree(ex->d_dep); (void)hipFree(ex->d_status); return VDC_ENOMEM; }
-    HIP_TRY(hipMemset(ex->d_dep, 0, sizeof(uint32_t) * cfg.n_dep_ids));
-    HIP_TRY(hipMemset(ex->d_status, 0, sizeof(uint32_t) * (ST_WORDS + 4)));   // the last four words: the sink of vdc_raw_stream
-    HIP_TRY(prepare_executor_kernels(lds_bytes_needed(cfg.n_slots, cfg.slot_bytes)));
-    HIP_TRY(hipDeviceSynchronize());
+    hipError_t e = hipMemset(ex->d_dep, 0, sizeof(uint32_t) * cfg.n_dep_ids);
+    if (e == hipSuccess) e = hipMemset(ex->d_status, 0, sizeof(uint32_t) * (ST_WORDS + 4));   // the last four words: the sink of vdc_raw_stream
+    if (e == hipSuccess) e = prepare_executor_kernels(lds_bytes_needed(cfg.n_slots, cfg.slot_bytes));
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipFree(ex->d_dep);
+        (void)hipFree(ex->d_status);
+        (void)hipHostFree(ex->h_status);
+        return VDC_EDEVICE;
+    }
     *out = ex.release();
     return VDC_OK;
 }
@@ -1413,6 +1475,7 @@ int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const
     for (int i = 0; i < n_tensors; i++) p->tensor_bytes[i] = tensor_bytes[i];
     p->uses_dep = val.uses_dep;
     p->max_dep_id = val.max_dep;
+    p->loaded_tensors = val.loaded_tensors;
     HIP_TRY(hipSetDevice(ex->cfg.device));
     const size_t wb = (size_t)n_uops * sizeof(Word), sbb = (size_t)(n_streams + 1) * 4, db = (size_t)std::max(n_descs, 1) * sizeof(Desc);   // never an empty table: the front end reads entry 0 for uops without one
     if (hipMalloc(&p->d_words, wb) != hipSuccess) return VDC_ENOMEM;
@@ -1452,14 +1515,8 @@ int vdc_program_destroy(vdc_program *prog) {
     (void)hipSetDevice(ex->cfg.device);
     (void)hipDeviceSynchronize();
     ex->programs.erase(std::remove(ex->programs.begin(), ex->programs.end(), prog), ex->programs.end());
-    for (auto it = ex->matvec_cache.begin(); it != ex->matvec_cache.end();)
-        it = (it->second == prog) ? ex->matvec_cache.erase(it) : it + 1;
-    for (auto it = ex->stream_cache.begin(); it != ex->stream_cache.end();)
-        it = (it->second == prog) ? ex->stream_cache.erase(it) : it + 1;
-    for (auto it = ex->chain_cache.begin(); it != ex->chain_cache.end();)
-        it = (it->second == prog) ? ex->chain_cache.erase(it) : it + 1;
-    for (auto it = ex->attn_cache.begin(); it != ex->attn_cache.end();)
-        it = (it->second == prog) ? ex->attn_cache.erase(it) : it + 1;
+    for (auto it = ex->cache.begin(); it != ex->cache.end();)
+        it = (it->prog == prog) ? ex->cache.erase(it) : it + 1;
     (void)hipFree(prog->d_words);
     (void)hipFree(prog->d_stream_begin);
     (void)hipFree(prog->d_descs);
@@ -1492,6 +1549,9 @@ int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info) {
     }
     if (ex->h_status[ST_ABORT] == 0) return VDC_OK;
     int code = -(int)ex->h_status[ST_CODE];
+    // an aborted run may have left depId counters and the count of finished cores anywhere: start the next one clean
+    HIP_TRY(launch_clear(ex->d_dep, (uint32_t)ex->cfg.n_dep_ids, s));
+    HIP_TRY(launch_clear(ex->d_status + ST_WORDS + 3, 1u, s));
     HIP_TRY(launch_clear(ex->d_status, ST_WORDS, s));
     HIP_TRY(hipStreamSynchronize(s));
     return code ? code : VDC_EDEVICE;
@@ -1515,11 +1575,9 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
     if (!ex || ex->cfg.device == -1 || !M || !X || !Y || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
     if (((uintptr_t)M & 15u) || ((uintptr_t)X & 15u) || ((uintptr_t)Y & 3u)) return VDC_EINVAL;
     if (rope && (!T || ((uintptr_t)T & 15u) || row_off)) return VDC_EINVAL;
-    MatvecKey key{rows, K, ld, B, tile_bytes, row_off ? n_seg : -1, {}, rope};
-    if (row_off) key.row_off.assign(row_off, row_off + n_seg + 1);
-    vdc_program *prog = nullptr;
-    for (auto &kv : ex->matvec_cache)
-        if (kv.first == key) { prog = kv.second; break; }
+    std::vector<int64_t> key{PK_MATVEC, rows, K, ld, B, tile_bytes, row_off ? n_seg : -1, rope ? 1 : 0};
+    if (row_off) key.insert(key.end(), row_off, row_off + n_seg + 1);
+    vdc_program *prog = cache_find(ex, key);
     if (!prog) {
         std::vector<Word> words;
         std::vector<uint32_t> sb;
@@ -1543,7 +1601,7 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
             if (!rope && choose_tile(ex->cfg, K, B, tile_bytes, R, Kt) && K <= Kt &&
                 rows / R >= 8 * (int64_t)ex->cfg.n_cores * ex->cfg.vcc_per_core) prog->placement = 1;   // and enough of them to matter
         }
-        ex->matvec_cache.push_back({key, prog});
+        cache_insert(ex, std::move(key), prog);
     }
     void *bases[4] = {(void *)M, (void *)X, (void *)Y, rope ? (void *)T : prog->d_workspace};
     return vdc_run(ex, prog, bases, (rope || prog->d_workspace) ? 4 : 3, hip_stream);
@@ -1624,10 +1682,9 @@ int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, 
 int vdc_matvec_chain(vdc_executor *ex, const float *W, float *A, const int64_t *dims, int32_t L, int32_t B, int32_t tile_bytes,
                      void *hip_stream) {
     if (!ex || ex->cfg.device == -1 || !W || !A || !dims || L < 1 || ((uintptr_t)W & 15u) || ((uintptr_t)A & 15u)) return VDC_EINVAL;
-    vdc_program *prog = nullptr;
-    for (auto &kv : ex->chain_cache)
-        if (kv.first.B == B && kv.first.tile_bytes == tile_bytes && (int32_t)kv.first.dims.size() == L + 1 &&
-            std::equal(kv.first.dims.begin(), kv.first.dims.end(), dims)) { prog = kv.second; break; }
+    std::vector<int64_t> key{PK_CHAIN, B, tile_bytes, L};
+    key.insert(key.end(), dims, dims + L + 1);
+    vdc_program *prog = cache_find(ex, key);
     if (!prog) {
         std::vector<Word> words;
         std::vector<uint32_t> sb;
@@ -1638,7 +1695,7 @@ int vdc_matvec_chain(vdc_executor *ex, const float *W, float *A, const int64_t *
         int64_t tb[3] = {w_bytes, a_bytes, a_bytes};
         rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb, 3, &prog);
         if (rc != VDC_OK) return rc;
-        ex->chain_cache.push_back({{std::vector<int64_t>(dims, dims + L + 1), B, tile_bytes}, prog});
+        cache_insert(ex, std::move(key), prog);
     }
     void *bases[3] = {(void *)W, (void *)A, (void *)A};
     return vdc_run(ex, prog, bases, 3, hip_stream);
@@ -1668,10 +1725,10 @@ int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const floa
                     int32_t d, float scale, float *O, int32_t tile_bytes, void *hip_stream) {
     if (!ex || ex->cfg.device == -1 || !Q || !K || !V || !O || !row_off || n_seg < 1) return VDC_EINVAL;
     if (((uintptr_t)Q & 15u) || ((uintptr_t)K & 15u) || ((uintptr_t)V & 15u) || ((uintptr_t)O & 15u)) return VDC_EINVAL;
-    vdc_program *prog = nullptr;
-    for (auto &kv : ex->attn_cache)
-        if (kv.first.d == d && kv.first.scale == scale && kv.first.tile_bytes == tile_bytes && (int32_t)kv.first.row_off.size() == n_seg + 1 &&
-            std::equal(kv.first.row_off.begin(), kv.first.row_off.end(), row_off)) { prog = kv.second; break; }
+    if (!attn_scale_resolve(scale, d)) return VDC_EINVAL;
+    std::vector<int64_t> key{PK_ATTN, d, float_bits(scale), tile_bytes, n_seg};
+    key.insert(key.end(), row_off, row_off + n_seg + 1);
+    vdc_program *prog = cache_find(ex, key);
     if (!prog) {
         std::vector<Word> words;
         std::vector<uint32_t> sb;
@@ -1684,7 +1741,7 @@ int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const floa
         rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb, 5, &prog);
         if (rc != VDC_OK) return rc;
         if (hipMalloc(&prog->d_workspace, (size_t)tb[4]) != hipSuccess) { vdc_program_destroy(prog); return VDC_ENOMEM; }
-        ex->attn_cache.push_back({{std::vector<int64_t>(row_off, row_off + n_seg + 1), d, scale, tile_bytes}, prog});
+        cache_insert(ex, std::move(key), prog);
     }
     void *bases[5] = {(void *)K, (void *)V, (void *)Q, (void *)O, prog->d_workspace};
     return vdc_run(ex, prog, bases, 5, hip_stream);
@@ -1693,6 +1750,7 @@ int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const floa
 int vdc_attn_decode_program(vdc_executor *ex, const int64_t *row_off, int32_t n_seg, int32_t d, float scale, int32_t tile_bytes,
                             void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs, int64_t *n_items) {
     if (!ex || !n_uops || !n_descs || !n_items) return VDC_EINVAL;
+    if (!attn_scale_resolve(scale, d)) return VDC_EINVAL;
     std::vector<Word> words;
     std::vector<uint32_t> sb;
     std::vector<Desc> ds;
@@ -1720,9 +1778,8 @@ int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64
     if (!ex || ex->cfg.device == -1 || mode < 0 || mode > 2) return VDC_EINVAL;
     if ((mode != 1 && (!src || ((uintptr_t)src & 15u))) || (mode != 0 && (!dst || ((uintptr_t)dst & 15u)))) return VDC_EINVAL;
     if (mode != 1) value = 0;
-    vdc_program *prog = nullptr;
-    for (auto &kv : ex->stream_cache)
-        if (kv.first.mode == mode && kv.first.bytes == bytes && kv.first.value == value && kv.first.tile_bytes == tile_bytes) { prog = kv.second; break; }
+    std::vector<int64_t> key{PK_STREAM, mode, bytes, (int64_t)value, tile_bytes};
+    vdc_program *prog = cache_find(ex, key);
     if (!prog) {
         std::vector<Word> words;
         std::vector<uint32_t> sb;
@@ -1735,7 +1792,7 @@ int vdc_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, int64
         if (rc != VDC_OK) return rc;
         // a store per block: bound by the store unit and the front end (copies of 32 KB blocks by the load units again)
         prog->placement = (mode == 1 || (mode == 2 && tile_bytes < 32768)) ? 1 : 0;
-        ex->stream_cache.push_back({{mode, bytes, value, tile_bytes}, prog});
+        cache_insert(ex, std::move(key), prog);
     }
     void *bases[2] = {mode == 1 ? dst : (void *)src, dst};
     return vdc_run(ex, prog, bases, mode == 2 ? 2 : 1, hip_stream);

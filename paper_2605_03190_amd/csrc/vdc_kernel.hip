@@ -63,6 +63,12 @@ constexpr int kMaxVm = 56;       // outstanding load instructions one LDU allows
 constexpr int kRecWords = 4;
 constexpr int kStatWords = 8;
 constexpr int kWin = 64;        // uops in the decoded window
+// A unit that polls takes issue slots from the compute wave on its SIMD (every vector instruction of a wave64 holds the
+// SIMD's ALU for four cycles, whatever it computes), so a unit that has found nothing to do several times in a row
+// looks less often: units of 64 cycles between two looks, and the idle looks after which the longer pause applies.
+constexpr int kStuIdleNap = 8;
+constexpr uint32_t kStuIdleAfter = 4;
+constexpr int kCfuPrio = 3, kLduPrio = 2, kStuPrio = 2;
 
 struct UnitRec {  // the per-execution part of a memory uop after the front end (16 bytes)
     uint32_t gaddr_lo, gaddr_hi;   // effective global address
@@ -264,9 +270,10 @@ struct Spin {
 // One back-off step of a poll loop.  `aborted` is the core's abort word as the caller's poll saw it.  Returns
 // false when the unit must give up: an error was raised somewhere, or the watchdog limit is reached, in which
 // case this unit raises VDC_EDEADLOCK.
+template <int NAP = 1>
 DEV bool spin_step(Ctx &c, Spin &s, uint32_t aborted, uint32_t detail) {
     if (aborted) return false;
-    __builtin_amdgcn_s_sleep(1);
+    __builtin_amdgcn_s_sleep(NAP);
     s.n++;
     if ((s.n & 255u) == 0u) {
         uint32_t g = uni(__hip_atomic_load(&c.p->status[ST_ABORT], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
@@ -801,12 +808,14 @@ DEV void cfu_main(Ctx &c) {
             const uint64_t early = __ballot(my_op == (uint32_t)OP_STORE && my_send) & bm;
             const uint64_t e = (uint64_t)(slot_vec | (my_nslots << 6) | ((d.aux & 0xFFFFu) << 12)) |
                                ((uint64_t)(((my_ticket + 1u) & 0xFFFFu) | (d.aux & 0xFFFF0000u)) << 32);
+            // the slots are marked taken before anything that names them is published: whoever frees them later (an
+            // atomic and on the same word) then always finds the bits set
+            lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), alloc_bits);
             lds_st64_lanes(early, ctl_m2c + (my_vcc * kM2C + (my_ticket & (kM2C - 1))) * 8u, e);
             const uint32_t off = ctl_uq + (my_unit * kUQ + (my_pos & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
             u32x4 rec = {(uint32_t)my_gaddr, (uint32_t)(my_gaddr >> 32), slot_vec | (c.lane << 6) | (table << 12), my_ticket};
             lds_st128_lanes(bm, off, rec);
             lds_st32_lanes(unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, new_tails);     // after the records
-            lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), alloc_bits);
         }
         st.uq_tail_rf = new_tails;
         st.ticket0 = new_t0;
@@ -907,9 +916,11 @@ struct Inflight {
 
 DEV void ldu_retire(Ctx &c, const Inflight &t) {
     lds_wait();   // zero fill of this tile (ds_write) is done as well
+    // A load that signals does so before it delivers: once the tile is delivered the compute core may finish and the
+    // core may leave, and the core that leaves last puts the counters back to zero; no signal may come after that.
+    if (__builtin_expect((t.ctl & 0x200u) != 0u, 0)) dep_signal(c, t.dep, false);
     lds_st64_lanes((t.ctl & 0x100u) ? 1ull : 0ull, c.ctl + CTL_OFF(m2c) + ((t.ctl >> 10) & 0x3FFu) * 8u,
                    (uint64_t)t.msg_lo | ((uint64_t)t.msg_hi << 32));
-    if (__builtin_expect((t.ctl & 0x200u) != 0u, 0)) dep_signal(c, t.dep, false);
 }
 
 // The static part of a record: lanes 0..7 = the StatRec the record's info word points at.
@@ -1370,7 +1381,9 @@ DEV void stu_main(Ctx &c) {
             continue;
         }
         PHASE(c, 1u + u, have ? 6u : 5u);
-        if (!spin_step(c, sp, rf_get(snap, 10), 0x700u | (have ? 0x80u : 0u))) ok = false;
+        if (!have && sp.n >= kStuIdleAfter) {
+            if (!spin_step<kStuIdleNap>(c, sp, rf_get(snap, 10), 0x700u)) ok = false;
+        } else if (!spin_step(c, sp, rf_get(snap, 10), 0x700u | (have ? 0x80u : 0u))) ok = false;
     }
     // The store unit that leaves last is the last of its core to touch a slot or a depId counter (every signal and every
     // wait of the core lies before the last region comes back).
@@ -1556,7 +1569,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
     const uint32_t slot_shift = __builtin_ctz(p->slot_bytes);
     constexpr int JJ = (J == 0) ? 1 : J;
     constexpr int NACC = NF / JJ;
-    float acc[NACC][B];                      // alloc_registers(NCREGS)
+    float acc[NACC][B];                      // the uop's register accumulators, kept over all its tile steps
 #pragma unroll
     for (int i = 0; i < NACC; i++)
 #pragma unroll
@@ -1582,7 +1595,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
             b_off = x_base + xs * pitch;
             xs = xs + 1u == xspan ? 0u : xs + 1u;
         } else {
-            if (!vcc_pop_wait(c, vs, 2u, 0u, ma, mb)) return false;  // a = m2c.pop_wait(); b = m2c.pop_wait()
+            if (!vcc_pop_wait(c, vs, 2u, 0u, ma, mb)) return false;  // wait for the step's matrix tile and vector tile
             b_off = mb.slot << slot_shift;
         }
         const uint32_t a_off = ma.slot << slot_shift;
@@ -1599,15 +1612,15 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
             const int ai = (J == 0) ? i : i / JJ;
             const int xi = (J == 0) ? 0 : i % JJ;
 #pragma unroll
-            for (int b = 0; b < B; b++) acc[ai][b] = dot4(m[i], xv[xi][b], acc[ai][b]);   // matvec_tile_accumulate
+            for (int b = 0; b < B; b++) acc[ai][b] = dot4(m[i], xv[xi][b], acc[ai][b]);   // the step's partial products
         }
         // every LDS read of both tiles has returned once its value was used: the regions can go back
-        vcc_done_with(c, vs, spans ? 1u : 2u, 0u);                   // c2m.push(a, b)
+        vcc_done_with(c, vs, spans ? 1u : 2u, 0u);                   // both regions go back to the memory core as used
     }
     if (spans) vcc_return_kept(c, vs, x_pay);
 
     Msg mo, unused;
-    if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;      // c_shared = m2c.pop_wait()
+    if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;      // wait for the output region
     const uint32_t o_off = mo.slot << slot_shift;
     if (J == 0) {
         const uint32_t lsh = __builtin_ctz(lpr);
@@ -1617,7 +1630,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
 #pragma unroll
             for (int b = 0; b < B; b++) {
                 const float x = lane_group_sum(acc[i][b], lpr);
-                if (c4 == lpr - 1u) lds_stf(o_off + ((uint32_t)b * R + (uint32_t)i * rpp + (t >> lsh)) * 4u, x);   // copy(c, c_shared)
+                if (c4 == lpr - 1u) lds_stf(o_off + ((uint32_t)b * R + (uint32_t)i * rpp + (t >> lsh)) * 4u, x);   // the row sums go into the region
             }
     } else {
         float mine = 0.0f;
@@ -1656,7 +1669,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
         vs.red_seq++;
     }
     lds_wait();
-    vcc_done_with(c, vs, 1u, 1u);                                     // push the produced region
+    vcc_done_with(c, vs, 1u, 1u);                                     // the region goes back as produced
     return true;
 }
 
@@ -1694,14 +1707,12 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     }
     switch (B) {
         case 1: return matvec_dispatch_b<1>(c, vs, f.size, R, lpr, nf, j, xspan);
-#ifndef VDC_ONLY_B1_AND_B8   /* set only by throw-away experiment builds to shorten the compile */
         case 2: return matvec_dispatch_b<2>(c, vs, f.size, R, lpr, nf, j, xspan);
         case 3: return matvec_dispatch_b<3>(c, vs, f.size, R, lpr, nf, j, xspan);
         case 4: return matvec_dispatch_b<4>(c, vs, f.size, R, lpr, nf, j, xspan);
         case 5: return matvec_dispatch_b<5>(c, vs, f.size, R, lpr, nf, j, xspan);
         case 6: return matvec_dispatch_b<6>(c, vs, f.size, R, lpr, nf, j, xspan);
         case 7: return matvec_dispatch_b<7>(c, vs, f.size, R, lpr, nf, j, xspan);
-#endif
         case 8: return matvec_dispatch_b<8>(c, vs, f.size, R, lpr, nf, j, xspan);
         default:
             raise_error(c, -3 /* VDC_EPROGRAM */, 0xD00u);
@@ -2084,17 +2095,17 @@ __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KPa
         c.role = ROLE_CFU; c.unit = 0;
         // the front end is a long dependent chain of cheap instructions: let it win the issue arbitration against the
         // compute wave that shares its SIMD
-        __builtin_amdgcn_s_setprio(3);
+        __builtin_amdgcn_s_setprio(kCfuPrio);
         cfu_main(c);
     } else if (wave <= p.n_ldu) {
         c.role = ROLE_LDU; c.unit = wave - 1u;
         c.stream_pc0 = cload(p.stream_begin, c.core * (1u + p.V));
-        __builtin_amdgcn_s_setprio(2);
+        __builtin_amdgcn_s_setprio(kLduPrio);
         ldu_main(c);
     } else if (wave <= p.n_ldu + p.n_stu) {
         c.role = ROLE_STU; c.unit = wave - 1u;
         c.stream_pc0 = cload(p.stream_begin, c.core * (1u + p.V));
-        __builtin_amdgcn_s_setprio(2);
+        __builtin_amdgcn_s_setprio(kStuPrio);
         stu_main(c);
 #ifdef VDC_PROFILE
     } else if (wave == 1u + p.n_ldu + p.n_stu + 2u * p.V) {

@@ -241,6 +241,37 @@ def test_validator_rejects_broken_programs():
         assert rc == vdc.VDC_EPROGRAM and "deadlock" in msg
 
 
+def test_validator_bounds_arithmetic_cannot_wrap():
+    """A row pitch or an accumulator chosen so that 64-bit arithmetic wraps must not slip a box past the tensor's end."""
+    with vdc.Executor(device=-1, n_cores=1, vcc_per_core=1, slot_bytes=1024, n_slots=4) as ex:
+        M, X, Y = 16 * 64 * 4, 64 * 4, 16 * 4
+
+        def check(mutate):
+            p = A.dense_matvec_program(16, 64, 64, 1, 16, 32, 1024, 1, vcc_per_core=1)
+            mutate(p)
+            w, sb, d = p.finish()
+            rc, msg = ex.program_validate(w, sb, d, [M, X, Y])
+            return rc, msg
+
+        assert check(lambda p: None)[0] == vdc.VDC_OK
+        # a pitch of 2^63 bytes: (rows - 1) * pitch is 0 modulo 2^64 for an odd number of further rows pairs
+        for pitch in (1 << 63, (1 << 63) + 16, (1 << 62), (1 << 64) - 16):
+            def huge_pitch(p, pitch=pitch):
+                u = UM.decode(p.vmc(0)[0])
+                t, box_rows, row_bytes, lds_pitch = p.descs[u.desc][:4]
+                p.descs[u.desc] = (t, box_rows, row_bytes, lds_pitch, pitch & 0xFFFFFFFF, pitch >> 32, 0, 0)
+            rc, msg = check(huge_pitch)
+            assert rc == vdc.VDC_EPROGRAM and "beyond" in msg, (hex(pitch), msg)
+        # an accumulator driven past 2^63 by repeated additions of the largest immediate
+        def acc_overflow(p):
+            big = (1 << 47) - 16
+            pre = [A.word(A.LOOP, imm=70000), A.word(A.LOOP, imm=1000)] + [A.word(A.ADD, acc=1, imm=big)] + [A.word(A.REPEAT, acc=1, imm=big), A.word(A.REPEAT, acc=1, imm=big)]
+            for i, w_ in enumerate(pre):
+                p.vmc(0).insert(i, w_)
+        rc, msg = check(acc_overflow)
+        assert rc == vdc.VDC_EPROGRAM and "overflow" in msg, msg
+
+
 def test_device_entry_points_refuse_a_host_only_executor():
     with vdc.Executor(device=-1, n_cores=2) as ex:
         w, sb, d = ex.matvec_program(64, 64, 64, 1, 4096)

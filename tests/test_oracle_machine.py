@@ -75,6 +75,35 @@ def test_decode_inverts_the_assembler_field_by_field():
         assert UM.decode(A.word(A.ADD, imm=imm)).imm == imm
 
 
+def _golden_words():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "uop_words.txt")
+    names = ("opcode", "flags", "vflow", "vcc", "acc", "nslots", "size", "dep_id", "imm", "desc", "dep_count")
+    out = []
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        left, right = line.split("|")
+        name, *hexw = left.split()
+        out.append((name, tuple(int(h, 16) for h in hexw), dict(zip(names, (int(x) for x in right.split())))))
+    return out
+
+
+def test_hand_written_instruction_words():
+    """The bit layout is fixed by words written out by hand (tests/golden/uop_words.txt), not by the assembler and the
+    decoder agreeing with each other: the assembler must produce exactly these words and the decoder exactly these
+    fields.  A field moved by a bit, a swapped pair of words or a wrong sign extension fails here."""
+    cases = _golden_words()
+    assert {c[2]["opcode"] for c in cases} >= {A.HALT, A.LOOP, A.REPEAT, A.SET, A.LOAD, A.STORE, A.MATVEC}
+    assert any(c[2]["imm"] < 0 for c in cases) and any(c[2]["dep_count"] for c in cases)
+    for name, words, f in cases:
+        assert len(words) == 4
+        assert tuple(A.word(**f)) == words, name
+        u = UM.decode(words)
+        assert {k: getattr(u, k) for k in f} == f, name
+
+
 # ---- result = textbook product -------------------------------------------------------------------
 @pytest.mark.parametrize("rows,K,B,R,Kt,slot,ncores", [
     (16, 64, 1, 8, 64, 4096, 1),
