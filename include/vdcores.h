@@ -38,7 +38,8 @@ enum {
     VDC_EPROGRAM = -3,  /* the uop program is malformed (found by host-side validation)            */
     VDC_EDEVICE = -4,   /* a HIP call failed                                                       */
     VDC_EDEADLOCK = -5, /* the device watchdog fired: some unit waited longer than the spin limit  */
-    VDC_ELEAK = -6      /* a run ended with local-memory slots still allocated                      */
+    VDC_ELEAK = -6,     /* a run ended with local-memory slots still allocated                      */
+    VDC_ETOOBIG = -7    /* vdc_matvec_noalloc: program + workspace exceed the static scratch        */
 };
 
 typedef struct vdc_executor vdc_executor; /* opaque, library-owned */
@@ -145,6 +146,24 @@ int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info);
  * therefore pays a rebuild per call; its memory use stays bounded. */
 int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
                int32_t B, int32_t tile_bytes, void *hip_stream);
+
+/* vdc_matvec for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same result, same kernels as vdc_matvec, but the call performs no
+ * allocation of any kind on the device (no hipMalloc, hipFree, or library routine that allocates): the uop program,
+ * the workspace of a shape that is also cut along K, the depId counters and the count of finished cores live in a
+ * static device array of VDC_NOALLOC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends
+ * (its address, a pinned staging buffer and an event are obtained once, in vdc_create).  The program image (stream
+ * offsets, descriptors, uops, workspace) must fit VDC_NOALLOC_SCRATCH_BYTES minus the 16 KB of counters, and the
+ * program may use at most 4094 depIds: VDC_ETOOBIG otherwise, and nothing is enqueued.
+ * The array is shared by all executors and all calls on that GPU and keeps the last call's content: a call with the
+ * shape and executor configuration of the one before it reuses the program in place; any other shape is built on the
+ * host and copied into the array asynchronously on hip_stream (the call first waits, on the host, for its staging
+ * buffer's previous copy); the counters are put to zero by a fill kernel at the start of every call.  Calls that
+ * overlap in time on one GPU (different streams, or different executors) race on the array: issue them on one stream.
+ * Errors as vdc_matvec, plus VDC_ETOOBIG. */
+#define VDC_NOALLOC_SCRATCH_BYTES (256 * 1024)
+int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,
+                       int32_t B, int32_t tile_bytes, void *hip_stream);
 
 /* The running example of Section 3 in its fused form: O = M X as above, then R = rope(O, T), with O never leaving
  * local memory (Section 4.2: a store.local / load.local pair hands the matvec's output region to the rope uop of

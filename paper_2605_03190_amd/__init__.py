@@ -13,7 +13,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvdcores.so")
 
-VDC_OK, VDC_EINVAL, VDC_ENOMEM, VDC_EPROGRAM, VDC_EDEVICE, VDC_EDEADLOCK, VDC_ELEAK = 0, -1, -2, -3, -4, -5, -6
+VDC_OK, VDC_EINVAL, VDC_ENOMEM, VDC_EPROGRAM, VDC_EDEVICE, VDC_EDEADLOCK, VDC_ELEAK, VDC_ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7
+NOALLOC_SCRATCH_BYTES = 256 * 1024
 
 
 class VdcError(RuntimeError):
@@ -53,6 +54,7 @@ def lib():
             "vdc_run_traced": [vp, vp, vp, i32, vp, vp, i32, vp],
             "vdc_sync_status": [vp, vp, vp],
             "vdc_matvec": [vp, vp, i64, i64, i64, vp, vp, i32, i32, vp],
+            "vdc_matvec_noalloc": [vp, vp, i64, i64, i64, vp, vp, i32, i32, vp],
             "vdc_matvec_ragged": [vp, vp, vp, i32, i64, vp, vp, i32, vp],
             "vdc_matvec_program": [vp, i64, i64, i64, i32, i32, vp, i32, vp, ctypes.POINTER(i64), vp, vp,
                                    ctypes.POINTER(i32)],
@@ -80,7 +82,7 @@ def lib():
 
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
-           "vdc_program_destroy", "vdc_program_set_placement", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_ragged",
+           "vdc_program_destroy", "vdc_program_set_placement", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_noalloc", "vdc_matvec_ragged",
            "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_matvec_chain", "vdc_matvec_chain_program", "vdc_attn_decode", "vdc_attn_decode_program",
            "vdc_stream", "vdc_raw_stream",
            "vdc_stream_program", "vdc_debug_alloc", "vdc_strerror"]
@@ -212,6 +214,18 @@ class Executor:
         assert Kx == K and tuple(Y.shape) == (B, rows)
         _check(lib().vdc_matvec(self.handle, M.data_ptr(), rows, K, ld, X.data_ptr(), Y.data_ptr(), B, tile_bytes,
                                 _stream_ptr(stream)), "vdc_matvec")
+
+    def matvec_noalloc(self, M, X, Y, tile_bytes, K=None, stream=None):
+        """matvec() through the entry point that allocates nothing on the device (program and workspace in the
+        library's static scratch array); VdcError(VDC_ETOOBIG) when the program does not fit it."""
+        rows, ld = M.shape
+        B, Kx = X.shape
+        K = Kx if K is None else K
+        assert M.is_cuda and X.is_cuda and Y.is_cuda and M.is_contiguous() and X.is_contiguous() and Y.is_contiguous()
+        assert M.dtype == X.dtype == Y.dtype and str(M.dtype) == "torch.float32"
+        assert Kx == K and tuple(Y.shape) == (B, rows)
+        _check(lib().vdc_matvec_noalloc(self.handle, M.data_ptr(), rows, K, ld, X.data_ptr(), Y.data_ptr(), B, tile_bytes,
+                                        _stream_ptr(stream)), "vdc_matvec_noalloc")
 
     def matvec_rope(self, M, X, T, Y, tile_bytes, K=None, stream=None):
         """Y = rope(M X, T): T and Y are [B, rows]; T holds (cos, sin) for every pair of rows."""

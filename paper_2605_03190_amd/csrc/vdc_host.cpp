@@ -61,7 +61,26 @@ struct vdc_executor {
     std::vector<vdc_program *> programs;
     std::vector<CachedProgram> cache;
     uint64_t use_clock = 0;
+    // for vdc_matvec_noalloc, all obtained at vdc_create: this device's static scratch array, a pinned staging buffer
+    // for the program image, and the event that tells when the last copy out of it has been done
+    unsigned char *scratch = nullptr;
+    unsigned char *h_stage = nullptr;
+    hipEvent_t stage_done = nullptr;
+    bool stage_pending = false;
 };
+
+// What the static scratch array of each device holds right now (it is shared by every executor on that device and keeps
+// its content from call to call): the key of the uploaded program and what a run needs to know about it.
+struct ScratchImage {
+    std::vector<int64_t> key;      // empty: nothing valid
+    int32_t n_descs = 0, n_tensors = 0, placement = 0;
+    int64_t tensor_bytes[kMaxTensors] = {0};
+    bool uses_dep = false;
+    uint32_t max_dep_id = 0, loaded_tensors = 0;
+    size_t off_sb = 0, off_descs = 0, off_words = 0, off_ws = 0;   // byte offsets from the start of the array
+    bool has_ws = false;
+};
+static ScratchImage g_scratch_image[64];
 
 namespace {
 
@@ -1329,7 +1348,7 @@ int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
 }
 
 int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, uint32_t *trace,
-                uint32_t *trace_count, int32_t trace_cap, hipStream_t stream) {
+                uint32_t *trace_count, int32_t trace_cap, hipStream_t stream, uint32_t *dep_table = nullptr, uint32_t *finished = nullptr) {
     if (!ex || !prog || prog->ex != ex || !tensor_bases || n_tensors != prog->n_tensors) return VDC_EINVAL;
     if (ex->cfg.device == -1) return VDC_EINVAL;
     KParams p{};
@@ -1343,7 +1362,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
         if (!tensor_bases[i] || ((uintptr_t)tensor_bases[i] & align)) return VDC_EINVAL;
         p.tensors[i] = (char *)tensor_bases[i];
     }
-    p.dep = ex->d_dep;
+    p.dep = dep_table ? dep_table : ex->d_dep;
     p.status = ex->d_status;
     p.trace = trace;
     p.trace_count = trace_count;
@@ -1368,7 +1387,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
 #endif
     HIP_TRY(hipSetDevice(ex->cfg.device));
     // the depId counters are zero between runs: the core that finishes last clears the ones its program used
-    p.finished = ex->d_status + ST_WORDS + 3;
+    p.finished = finished ? finished : ex->d_status + ST_WORDS + 3;
     p.n_dep_used = prog->uses_dep ? prog->max_dep_id + 1 : 0;
     if (trace_count) HIP_TRY(launch_clear(trace_count, (uint32_t)(ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core)), stream));
     HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, trace != nullptr, stream));
@@ -1417,11 +1436,20 @@ int vdc_create(vdc_executor **out, const vdc_config *cfg_in) {
     hipError_t e = hipMemset(ex->d_dep, 0, sizeof(uint32_t) * cfg.n_dep_ids);
     if (e == hipSuccess) e = hipMemset(ex->d_status, 0, sizeof(uint32_t) * (ST_WORDS + 4));   // the last four words: the sink of vdc_raw_stream
     if (e == hipSuccess) e = prepare_executor_kernels(lds_bytes_needed(cfg.n_slots, cfg.slot_bytes));
+    // set-up for the entry point that may not allocate: the address of this device's static scratch array (the device
+    // is current here), a pinned staging buffer and an event
+    void *scratch_ptr = nullptr;
+    if (e == hipSuccess) e = scratch_address(cfg.device, &scratch_ptr);
+    ex->scratch = (unsigned char *)scratch_ptr;
+    if (e == hipSuccess) e = hipHostMalloc((void **)&ex->h_stage, kScratchBytes);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ex->stage_done, hipEventDisableTiming);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipFree(ex->d_dep);
         (void)hipFree(ex->d_status);
         (void)hipHostFree(ex->h_status);
+        if (ex->h_stage) (void)hipHostFree(ex->h_stage);
+        if (ex->stage_done) (void)hipEventDestroy(ex->stage_done);
         return VDC_EDEVICE;
     }
     *out = ex.release();
@@ -1446,6 +1474,8 @@ int vdc_destroy(vdc_executor *ex) {
     (void)hipFree(ex->d_dep);
     (void)hipFree(ex->d_status);
     (void)hipHostFree(ex->h_status);
+    (void)hipHostFree(ex->h_stage);
+    (void)hipEventDestroy(ex->stage_done);
     delete ex;
     return VDC_OK;
 }
@@ -1610,6 +1640,94 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
 int vdc_matvec(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y, int32_t B,
                int32_t tile_bytes, void *hip_stream) {
     return matvec_common(ex, M, rows, K, ld, X, Y, B, tile_bytes, nullptr, 0, hip_stream);
+}
+
+// vdc_matvec for callers that cannot allocate.  Nothing here calls hipMalloc, hipFree or an allocating library routine:
+// the program image goes from the executor's pinned staging buffer into the device's static scratch array with an
+// asynchronous copy on the caller's stream, and the kernels read it there.  A program that is already in the array
+// (same executor configuration, same shape) is not built or copied again.
+int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y, int32_t B,
+                       int32_t tile_bytes, void *hip_stream) {
+    if (!ex || ex->cfg.device == -1 || !M || !X || !Y || rows < 1 || K < 4 || (K & 3) || ld < K || (ld & 3) || B < 1 || B > 8) return VDC_EINVAL;
+    if (((uintptr_t)M & 15u) || ((uintptr_t)X & 15u) || ((uintptr_t)Y & 3u)) return VDC_EINVAL;
+    const int dev = ex->cfg.device;
+    if (dev < 0 || dev >= 64 || !ex->scratch || !ex->h_stage) return VDC_EINVAL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(dev));
+    const vdc_config &c = ex->cfg;
+    std::vector<int64_t> key{PK_MATVEC, rows, K, ld, B, tile_bytes, c.n_cores, c.vcc_per_core, c.slot_bytes, c.n_slots, c.n_ldu, c.n_stu,
+                             c.n_dep_ids, c.tile_rows};
+    ScratchImage &img = g_scratch_image[dev];
+    auto up = [](size_t x) { return (x + 255u) & ~(size_t)255u; };
+    if (img.key != key) {
+        std::vector<Word> words;
+        std::vector<uint32_t> sb;
+        std::vector<Desc> descs;
+        int rc = build_matvec(c, rows, K, ld, B, tile_bytes, nullptr, 0, words, sb, descs, false);
+        if (rc != VDC_OK) return rc;
+        std::vector<float> ws;
+        workspace_init(c, rows, K, B, tile_bytes, false, ws);
+        ScratchImage n;
+        n.n_descs = (int32_t)descs.size();
+        n.n_tensors = ws.empty() ? 3 : 4;
+        n.tensor_bytes[0] = ((rows - 1) * ld + K) * 4;
+        n.tensor_bytes[1] = (int64_t)B * K * 4;
+        n.tensor_bytes[2] = (int64_t)B * rows * 4;
+        n.tensor_bytes[3] = (int64_t)ws.size() * 4;
+        n.off_sb = kScratchDepBytes;
+        n.off_descs = n.off_sb + up(sb.size() * 4);
+        n.off_words = n.off_descs + up(descs.size() * sizeof(Desc));
+        n.off_ws = n.off_words + up(words.size() * sizeof(Word));
+        n.has_ws = !ws.empty();
+        const size_t end = n.off_ws + up(ws.size() * 4);
+        if (end > kScratchBytes) return VDC_ETOOBIG;
+        Validator val{c, words.data(), (int64_t)words.size(), sb.data(), descs.data(), n.n_descs, n.tensor_bytes, n.n_tensors};
+        if (!val.run()) return VDC_EPROGRAM;
+        n.uses_dep = val.uses_dep;
+        n.max_dep_id = val.max_dep;
+        n.loaded_tensors = val.loaded_tensors;
+        if (n.uses_dep && ((size_t)n.max_dep_id + 2) * 4 > kScratchDepBytes) return VDC_ETOOBIG;
+        {
+            int R = 0, Kt = 0;   // the same choice of role placement as vdc_matvec makes
+            if (choose_tile(c, K, B, tile_bytes, R, Kt) && K <= Kt && rows / R >= 8 * (int64_t)c.n_cores * c.vcc_per_core) n.placement = 1;
+        }
+        // the staging buffer may still be the source of the copy of an earlier call
+        if (ex->stage_pending) HIP_TRY(hipEventSynchronize(ex->stage_done));
+        ex->stage_pending = false;
+        unsigned char *h = ex->h_stage;
+        memcpy(h + n.off_sb, sb.data(), sb.size() * 4);
+        memcpy(h + n.off_descs, descs.data(), descs.size() * sizeof(Desc));
+        memcpy(h + n.off_words, words.data(), words.size() * sizeof(Word));
+        if (n.has_ws) memcpy(h + n.off_ws, ws.data(), ws.size() * 4);
+        img.key.clear();      // whatever the array held is being replaced from here on
+        HIP_TRY(hipMemcpyAsync(ex->scratch + kScratchDepBytes, h + kScratchDepBytes, end - kScratchDepBytes, hipMemcpyHostToDevice, stream));
+        HIP_TRY(hipEventRecord(ex->stage_done, stream));
+        ex->stage_pending = true;
+        n.key = key;
+        img = n;
+    }
+    // The array keeps what the last call left: the depId counters a run starts from, and the count of finished cores,
+    // are put to zero by a small fill kernel (an aborted run, or a run of another executor, may have left them anywhere).
+    uint32_t *dep = (uint32_t *)ex->scratch;
+    uint32_t *finished = dep + kScratchDepBytes / 4 - 1;
+    if (img.uses_dep) {
+        HIP_TRY(launch_clear(dep, img.max_dep_id + 1u, stream));
+        HIP_TRY(launch_clear(finished, 1u, stream));
+    }
+    vdc_program prog;
+    prog.ex = ex;
+    prog.d_words = (Word *)(ex->scratch + img.off_words);
+    prog.d_stream_begin = (uint32_t *)(ex->scratch + img.off_sb);
+    prog.d_descs = (Desc *)(ex->scratch + img.off_descs);
+    prog.n_descs = img.n_descs;
+    prog.n_tensors = img.n_tensors;
+    for (int i = 0; i < kMaxTensors; i++) prog.tensor_bytes[i] = img.tensor_bytes[i];
+    prog.uses_dep = img.uses_dep;
+    prog.max_dep_id = img.max_dep_id;
+    prog.loaded_tensors = img.loaded_tensors;
+    prog.placement = img.placement;
+    void *bases[4] = {(void *)M, (void *)X, (void *)Y, img.has_ws ? (void *)(ex->scratch + img.off_ws) : nullptr};
+    return run_program(ex, &prog, bases, img.n_tensors, nullptr, nullptr, 0, stream, dep, finished);
 }
 
 int vdc_matvec_rope(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, const float *T, float *Y,
@@ -1851,6 +1969,7 @@ const char *vdc_strerror(int code) {
         case VDC_EDEVICE: return "HIP error";
         case VDC_EDEADLOCK: return "device watchdog: a unit waited past the spin limit";
         case VDC_ELEAK: return "run ended with local-memory slots still allocated";
+        case VDC_ETOOBIG: return "the uop program and its workspace do not fit the static scratch of the entry point that allocates nothing";
         default: return "unknown error";
     }
 }

@@ -56,6 +56,13 @@ hipError_t prepare_executor_kernels(size_t lds_bytes);
 hipError_t launch_clear(uint32_t *p, uint32_t n, hipStream_t stream);
 hipError_t launch_raw_stream(int mode, const void *src, void *dst, uint64_t bytes, uint32_t value, uint32_t *sink, int blocks,
                              hipStream_t stream);
+// The static device array behind the entry point that allocates nothing: kScratchBytes per GPU, laid out as
+// [0, kScratchDepBytes) depId counters and the count of finished cores, then the program image (stream_begin,
+// descriptors, uops, workspace).  scratch_address gives the array's address on `device`, which must be the current
+// device on the first call for it; the address is kept per device.
+constexpr size_t kScratchBytes = 256u << 10;
+constexpr size_t kScratchDepBytes = 16u << 10;     // 4095 depId counters + the finished-cores word
+hipError_t scratch_address(int device, void **out);
 hipError_t launch_debug_alloc(const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n,
                               hipStream_t stream);
 

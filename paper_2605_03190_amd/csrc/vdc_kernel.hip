@@ -2184,6 +2184,36 @@ hipError_t launch_raw_stream(int mode, const void *src, void *dst, uint64_t byte
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Static scratch for the entry point that may not allocate (vdc_matvec_noalloc): the uop program, the workspace of a
+// split-K program and the depId counters of one run live in this array instead of in allocated memory.  Every GPU holds
+// its own copy at its own address for the life of the process.  In host code the array's name is only a stand-in for
+// the symbol, not a device address: the address is asked for once per device (hipGetSymbolAddress) and kept; kernels
+// and copies are always given that pointer.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxScratchDevices = 64;
+static void *g_scratch_ptr[kMaxScratchDevices] = {nullptr};
+
+hipError_t scratch_address(int device, void **out) {
+    *out = nullptr;
+    if (device < 0 || device >= kMaxScratchDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return e;
+        if (cur != device) return hipErrorInvalidDevice;     // the symbol's address is the current device's
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 hipError_t launch_debug_alloc(const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n,
                               hipStream_t stream) {
     int blocks = n < 1024 ? (n > 0 ? n : 1) : 1024;
