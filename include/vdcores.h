@@ -98,9 +98,12 @@ int vdc_program_destroy(vdc_program *prog);
  * thread block; on this GPU a workgroup's waves are dealt round-robin over four SIMDs, and waves on one SIMD contend for
  * its issue slots).  placement 0 (default): every SIMD holds one compute wave next to the memory core's units, best
  * when the compute cores set the pace.  placement 1: the front end and the store unit share their SIMDs with load
- * units only and the compute waves pair up, best for graphs with a store per tile.  No effect on results; applies to
- * the default deployment (4 load units, 1 store unit, 2 compute cores) and is ignored otherwise.  The operators below
- * choose for their own programs.  VDC_EINVAL for another value. */
+ * units only and the compute waves pair up, best for graphs with a store per tile.  placement 2: the workgroup is
+ * launched with two more waves that leave at once, which shifts the others so that the front end shares its SIMD with
+ * one compute wave and nothing else, the store unit likewise, and the other two SIMDs hold two load units and one
+ * compute wave each: best for long loops over K, where the front end is the busiest wave.  No effect on results;
+ * applies to the default deployment (4 load units, 1 store unit, 2 compute cores) and is ignored otherwise.  The
+ * operators below choose for their own programs.  VDC_EINVAL for another value. */
 int vdc_program_set_placement(vdc_program *prog, int32_t placement);
 
 /* The validation of vdc_program_create alone (no device copy is made).  msg (host, may be NULL) receives a

@@ -55,7 +55,7 @@ struct vdc_executor {
     uint32_t *d_dep = nullptr;
     uint32_t *d_status = nullptr;
     uint32_t *h_status = nullptr;  // pinned
-#ifdef VDC_PROFILE
+#if defined(VDC_PROFILE) || defined(VDC_PROFILE_WAITS)
     unsigned long long *d_prof = nullptr;
 #endif
     std::vector<vdc_program *> programs;
@@ -1378,10 +1378,26 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     // bound by the front end and the store unit, keeps those two away from the compute waves: SIMD 0 = front end + load
     // units 0, 1; SIMD 1 = store unit + load units 2, 3; SIMDs 2 and 3 = one wave of each compute core.
     p.wave_roles = 0xFEDCBA9876543210ull;
-    if (prog->placement == 1 && ex->cfg.n_ldu == 4 && ex->cfg.n_stu == 1 && ex->cfg.vcc_per_core == 2)
+    uint32_t n_waves = 1u + p.n_ldu + p.n_stu + 2u * p.V;
+    constexpr int kForcePlacement = -1;      // experiments only
+    const int placement = kForcePlacement >= 0 ? kForcePlacement : prog->placement;
+    const bool default_units = ex->cfg.n_ldu == 4 && ex->cfg.n_stu == 1 && ex->cfg.vcc_per_core == 2;
+    if (placement == 1 && default_units)
         p.wave_roles = 0xFEDCBA0000000000ull | 0x4298317650ull;
-    // (With two store units, eleven waves, the like of it was measured and is no gain over the wave order: not taken.)
+    // Placement 2: twelve waves, two of which leave at once (position 15), so that the hardware's round-robin puts the
+    // front end on a SIMD with one compute wave and nothing else, the store unit likewise, and two load units (one of
+    // matrix tiles, one of vector tiles) with one compute wave on each of the other two SIMDs.
 #ifdef VDC_PROFILE
+    const bool room_for_twelve = false;      // the observer wave of profiling builds takes the twelfth place
+#else
+    const bool room_for_twelve = true;
+#endif
+    if (placement == 2 && default_units && room_for_twelve) {
+        p.wave_roles = 0xFFFFF98F74365210ull;    // wave 0..11: CFU, LDU0, LDU1, STU, VCC0.0, LDU2, LDU3, VCC0.1, idle, VCC1.0, VCC1.1, idle
+        n_waves = 12u;
+    }
+    // (With two store units, eleven waves, the like of it was measured and is no gain over the wave order: not taken.)
+#if defined(VDC_PROFILE) || defined(VDC_PROFILE_WAITS)
     if (!ex->d_prof && hipMalloc(&ex->d_prof, 8 * (16 * 8 * (size_t)ex->cfg.n_cores + 2 * 65536 + 8)) != hipSuccess) return VDC_ENOMEM;
     p.prof = ex->d_prof;
 #endif
@@ -1390,7 +1406,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.finished = finished ? finished : ex->d_status + ST_WORDS + 3;
     p.n_dep_used = prog->uses_dep ? prog->max_dep_id + 1 : 0;
     if (trace_count) HIP_TRY(launch_clear(trace_count, (uint32_t)(ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core)), stream));
-    HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, trace != nullptr, stream));
+    HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, n_waves, stream));
     return VDC_OK;
 }
 
@@ -1630,6 +1646,8 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
             int R = 0, Kt = 0;
             if (!rope && choose_tile(ex->cfg, K, B, tile_bytes, R, Kt) && K <= Kt &&
                 rows / R >= 8 * (int64_t)ex->cfg.n_cores * ex->cfg.vcc_per_core) prog->placement = 1;   // and enough of them to matter
+            // long sweeps over K: the front end's loop is the busiest wave; it gets a SIMD with one compute wave only
+            else if (Kt > 0 && K / Kt >= 64) prog->placement = 2;
         }
         cache_insert(ex, std::move(key), prog);
     }
@@ -1690,6 +1708,7 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
         {
             int R = 0, Kt = 0;   // the same choice of role placement as vdc_matvec makes
             if (choose_tile(c, K, B, tile_bytes, R, Kt) && K <= Kt && rows / R >= 8 * (int64_t)c.n_cores * c.vcc_per_core) n.placement = 1;
+            else if (Kt > 0 && K / Kt >= 64) n.placement = 2;
         }
         // the staging buffer may still be the source of the copy of an earlier call
         if (ex->stage_pending) HIP_TRY(hipEventSynchronize(ex->stage_done));
@@ -1886,7 +1905,7 @@ int vdc_attn_decode_program(vdc_executor *ex, const int64_t *row_off, int32_t n_
 }
 
 int vdc_program_set_placement(vdc_program *prog, int32_t placement) {
-    if (!prog || (placement != 0 && placement != 1)) return VDC_EINVAL;
+    if (!prog || placement < 0 || placement > 2) return VDC_EINVAL;
     prog->placement = placement;
     return VDC_OK;
 }
@@ -1951,7 +1970,7 @@ int vdc_debug_alloc(vdc_executor *ex, const uint32_t *masks, const int32_t *nslo
     return VDC_OK;
 }
 
-#ifdef VDC_PROFILE
+#if defined(VDC_PROFILE) || defined(VDC_PROFILE_WAITS)
 int vdc_prof_events(vdc_executor *ex, unsigned long long *out) {   // 2 * 65536 + 1 words: the observer's log, then its count
     return hipMemcpy(out, ex->d_prof + 16 * 8 * (size_t)ex->cfg.n_cores, 8 * (2 * 65536 + 1), hipMemcpyDeviceToHost) == hipSuccess ? 0 : VDC_EDEVICE;
 }

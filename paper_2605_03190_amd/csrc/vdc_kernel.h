@@ -39,7 +39,7 @@ struct KParams {
     uint32_t trace_cap;
     uint32_t n_slots, slot_bytes, n_ldu, n_stu, V;
     uint32_t watchdog;
-#ifdef VDC_PROFILE
+#if defined(VDC_PROFILE) || defined(VDC_PROFILE_WAITS)
     unsigned long long *prof;   // cores * 8 waves * 8 counters (profiling builds only)
 #endif
 };
@@ -49,7 +49,7 @@ size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes);
 size_t lds_control_bytes();
 
 // Launch the persistent virtual-core kernel: one workgroup per core.
-hipError_t launch_executor(const KParams &p, uint32_t n_cores, bool traced, hipStream_t stream);
+hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves, hipStream_t stream);
 // Raise the kernel's dynamic LDS limit; call once per device before the first launch.
 hipError_t prepare_executor_kernels(size_t lds_bytes);
 // Zero n words (a fill kernel; safe inside stream capture, unlike a memset node).

@@ -40,7 +40,7 @@ namespace vdc {
 
 // Instrumentation for throw-away profiling builds; the product build compiles none of it.  -DVDC_PROFILE adds an
 // observer wave (see observer_main).
-#ifdef VDC_PROFILE
+#if defined(VDC_PROFILE) || defined(VDC_PROFILE_WAITS)
 static __device__ __forceinline__ unsigned long long prof_now() {
     unsigned long long t;
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
@@ -116,6 +116,13 @@ static_assert(offsetof(Ctl, mask) == offsetof(Ctl, uq_head) + 4 * kMaxUnits && o
 static_assert(offsetof(Ctl, m2c) % 8 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0 && offsetof(Ctl, stat) % 16 == 0, "alignment");
 static_assert(sizeof(UnitRec) == 4 * kRecWords && sizeof(StatRec) == 4 * kStatWords, "record size");
 #define CTL_OFF(field) ((uint32_t)offsetof(Ctl, field))
+#ifdef VDC_PROFILE_SECTIONS
+#define SEC_BEGIN(c) ((c).w_mark = prof_now())
+#define SEC_END(c, i) do { const unsigned long long t_ = prof_now(); (c).w_sec[i] += t_ - (c).w_mark; (c).w_mark = t_; } while (0)
+#else
+#define SEC_BEGIN(c)
+#define SEC_END(c, i)
+#endif
 #if defined(VDC_PROFILE) && defined(VDC_PROFILE_PHASES)
 #define PHASE(c, w, id) do { if ((c).lane == 0) lds_vst32((c).ctl + CTL_OFF(phase) + (w) * 4u, (id)); reconverge(); } while (0)
 #define OBS(c, w, v)
@@ -242,6 +249,10 @@ struct Ctx {
     uint32_t stream_pc0;              // first word of this unit's stream
     uint32_t pc;                      // current word (for error reports)
     uint32_t spins_limit;
+#ifdef VDC_PROFILE_WAITS
+    unsigned long long w_wait = 0, w_spins = 0, w_vm = 0, w_t0 = 0, w_last = 0;   // profiling builds: cycles this wave spent waiting
+    unsigned long long w_sec[4] = {0, 0, 0, 0}, w_mark = 0;                           // and in sections of its loop
+#endif
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -273,6 +284,16 @@ struct Spin {
 template <int NAP = 1>
 DEV bool spin_step(Ctx &c, Spin &s, uint32_t aborted, uint32_t detail) {
     if (aborted) return false;
+#ifdef VDC_PROFILE_WAITS
+#ifdef VDC_PROFILE_WAIT_CYCLES
+    {   // time between consecutive failed looks of one wait (s.n is zero at its first)
+        const unsigned long long t = prof_now();
+        if (s.n != 0u) c.w_wait += t - c.w_last;
+        c.w_last = t;
+    }
+#endif
+    c.w_spins++;
+#endif
     __builtin_amdgcn_s_sleep(NAP);
     s.n++;
     if ((s.n & 255u) == 0u) {
@@ -478,15 +499,37 @@ struct DecWin {
     uint32_t a_lo, a_hi; // memory uop: tensor base + literal offset; control uop: the immediate
     uint32_t aux;        // valid rows [15:0] | valid row_bytes [31:16]   (for the early hand-over of an output region, and the trace)
     uint32_t desc;       // descriptor index (trace only)
-    // What a batch of consecutive memory uops needs, worked out once per window so that dispatching a batch is a few
-    // population counts: per lane, the window lanes below it that go to the same unit / send to the same compute core;
-    // in lane u, the window lanes that go to unit u; and the slot-count mask of the lane's uop.
-    uint32_t um_lt_lo, um_lt_hi;
-    uint32_t tm_lt_lo, tm_lt_hi;
-    uint32_t uu_lo, uu_hi;
-    uint32_t nsp_lo, nsp_hi;   // byte j: nslots of the uop j lanes further on (j = 0..7), 0 beyond the window
+    // What dispatching needs of each uop, worked out for all 64 lanes when the window is decoded:
+    uint32_t dynacc;     // the accumulator a memory uop's address moves with (8: none)
+    uint32_t rank;       // window lanes below this one whose uop goes to the same unit
+    uint32_t srank;      // window lanes below this one whose uop sends to the same compute core
+    uint32_t um_lo, um_hi;   // all window lanes whose uop goes to the same unit as this one's (0: not a memory uop)
+    uint32_t tm_lo, tm_hi;   // all window lanes whose uop sends to the same compute core (0: this one does not send)
+    uint32_t uu_lo, uu_hi;   // in lane u: the window lanes whose uop goes to unit u
+    uint32_t nsp_lo, nsp_hi; // byte j: nslots of the uop j lanes further on (j = 0..7), 0 beyond the window
+    uint32_t uq_off;     // where the unit's ring of records starts in LDS
+    uint32_t m2c_off;    // where the compute core's m2c ring starts
+    uint32_t e_lo, e_hi; // a STORE that sends: its m2c entry without slot and ticket
+    uint32_t info;       // the record's info word without the slot: window lane << 6 | table << 12
     uint64_t mem;        // wave-uniform: lanes that hold memory uops
     uint64_t t0, t1;     // wave-uniform: lanes whose uop sends to compute core 0 / 1
+    uint64_t early;      // wave-uniform: lanes that hold a STORE that sends (its empty region goes out at dispatch)
+};
+
+// What moves while the window is executed, per lane, for the uop that lane holds.  A memory uop's effective address
+// changes only when a control uop changes its accumulator; its position in its unit's ring and its m2c ticket are
+// fixed as long as execution runs straight through the window (every uop passed is dispatched, so "records pushed so
+// far" and "lanes passed so far" grow together), and move by a constant per lane whenever a loop jumps back: by the
+// number of uops of the loop body that go to the same unit / send to the same compute core.  Keeping the three up to
+// date costs a few masked vector additions per control uop; dispatching a batch then needs no gather and no
+// population count per lane.
+struct CfuLive {
+    uint32_t g_lo, g_hi;  // effective global address if the uop were dispatched now
+    uint32_t pos;         // position in the unit's ring when the pc reaches this lane in sequence
+    uint32_t tick;        // m2c ticket likewise (0xffffffff and never moved: the uop does not send)
+    // the last loop that jumped back inside the window: its body, and what it adds per trip
+    uint32_t loop_key;    // body start lane | REPEAT lane << 8 | windows decoded so far << 16
+    uint32_t dpos, dtick;
 };
 
 // The descriptor table as the front end keeps it: lane l holds the six words it needs of descriptor l (programs rarely
@@ -508,7 +551,7 @@ DEV DescRegs desc_regs_load(Ctx &c) {
     return r;
 }
 
-DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, const DescRegs &dr, uint32_t pc, uint32_t end) {
+DEV bool cfu_refill(Ctx &c, DecWin &d, CfuLive &lv, CfuState &st, const DescRegs &dr, uint32_t acc_rf_lo, uint32_t acc_rf_hi, uint32_t pc, uint32_t end) {
     const KParams *p = c.p;
     uint32_t idx = pc + c.lane;
     if (idx >= end) idx = end - 1u;             // the stream's HALT
@@ -542,23 +585,25 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, const DescRegs &dr, uint32_
     d.a_hi = (uint32_t)(a >> 32);
     d.aux = f.size | (d_rowb << 16);
     d.desc = f.desc;
+    const bool send = is_mem && (f.flags & F_SEND) != 0u;
     {
         const uint64_t lt = (1ull << c.lane) - 1ull;
         const uint32_t n_units = p->n_ldu + p->n_stu;
         uint64_t my_um = 0, uu = 0;
         for (uint32_t u = 0; u < n_units; u++) {
             const uint64_t b = __ballot(is_mem && unit == u);
-            my_um = unit == u ? b : my_um;
+            my_um = (is_mem && unit == u) ? b : my_um;
             uu = c.lane == u ? b : uu;
         }
-        const bool send = is_mem && (f.flags & F_SEND) != 0u;
         d.mem = uni64(__ballot(is_mem));
         d.t0 = uni64(__ballot(send && (f.vcc & 1u) == 0u));
         d.t1 = uni64(__ballot(send && (f.vcc & 1u) == 1u));
-        const uint64_t tm = send ? (((f.vcc & 1u) ? d.t1 : d.t0) & lt) : 0ull;
-        my_um &= lt;
-        d.um_lt_lo = (uint32_t)my_um; d.um_lt_hi = (uint32_t)(my_um >> 32);
-        d.tm_lt_lo = (uint32_t)tm; d.tm_lt_hi = (uint32_t)(tm >> 32);
+        d.early = uni64(__ballot(send && f.opcode == OP_STORE));
+        const uint64_t tm = send ? ((f.vcc & 1u) ? d.t1 : d.t0) : 0ull;
+        d.um_lo = (uint32_t)my_um; d.um_hi = (uint32_t)(my_um >> 32);
+        d.tm_lo = (uint32_t)tm; d.tm_hi = (uint32_t)(tm >> 32);
+        d.rank = (uint32_t)__builtin_popcountll(my_um & lt);
+        d.srank = (uint32_t)__builtin_popcountll(tm & lt);
         d.uu_lo = (uint32_t)uu; d.uu_hi = (uint32_t)(uu >> 32);
         uint64_t nsp = 0;
 #pragma unroll
@@ -567,6 +612,26 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuState &st, const DescRegs &dr, uint32_
             nsp |= (uint64_t)((c.lane + j < (uint32_t)kWin) ? (o & 0xFFu) : 0u) << (8u * j);
         }
         d.nsp_lo = (uint32_t)nsp; d.nsp_hi = (uint32_t)(nsp >> 32);
+    }
+    d.dynacc = (is_mem && (f.flags & F_DYNAMIC)) ? f.acc : 8u;
+    d.uq_off = c.ctl + CTL_OFF(uq) + unit * kUQ * (uint32_t)sizeof(UnitRec);
+    d.m2c_off = c.ctl + CTL_OFF(m2c) + (f.vcc & 1u) * kM2C * 8u;
+    d.e_lo = (f.nslots << 6) | (f.size << 12);
+    d.e_hi = d_rowb << 16;
+    d.info = (c.lane << 6) | ((st.n_refill & 1u) << 12);
+    // the moving values, as of now: the pc stands at the window's first lane
+    {
+        const uint32_t acc_lo = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((f.acc & 7u) * 4u), (int)acc_rf_lo);
+        const uint32_t acc_hi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((f.acc & 7u) * 4u), (int)acc_rf_hi);
+        const uint32_t tail = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(unit * 4u), (int)st.uq_tail_rf);
+        const uint64_t g = a + (d.dynacc < 8u ? ((uint64_t)acc_lo | ((uint64_t)acc_hi << 32)) : 0ull);
+        lv.g_lo = (uint32_t)g;
+        lv.g_hi = (uint32_t)(g >> 32);
+        lv.pos = tail + d.rank;
+        lv.tick = send ? ((f.vcc & 1u) ? st.ticket1 : st.ticket0) + d.srank : 0xFFFFFFFFu;
+        lv.loop_key = 0xFFFFFFFFu;
+        lv.dpos = 0;
+        lv.dtick = 0;
     }
     // The table this window writes was last used two windows ago.  Its records may still sit in a unit's queue:
     // wait until every unit has picked up everything that was dispatched from that window.
@@ -597,36 +662,246 @@ DEV uint32_t lanes_below(uint64_t m, uint32_t lane) {   // how many bits of m ar
     return (uint32_t)__builtin_popcountll(m & ((1ull << lane) - 1ull));
 }
 
+// What dispatching needs besides the window: constants of the run and the trace cursor.
+struct CfuEnv {
+    uint32_t n_units, stream;
+    uint64_t unit_lanes, busy_hi;
+    bool trace;
+    uint32_t trace_n;
+};
+
+// In-order first fit for a batch of up to four uops that take at most three slots each (Section 4.3: the first free
+// location, lowest position; the same function as slot_find, uop by uop, every later uop seeing the slots of the earlier
+// ones as taken).  nsp32: byte j = slots of the j-th uop; lim: how many uops to try; occ32: bit set = slot taken (every
+// position beyond the pool is marked taken, the pool has at most 32 slots, so 32-bit arithmetic is enough).  Stops at
+// the first uop that does not fit.  Returns the number that fit; pack: byte j = first slot of the j-th; bits: all slots
+// taken.  Straight-line code for the scalar unit, no branch: a branch costs this front end as much as five scalar
+// instructions, taken or not, and the allocation is the busiest scalar code of the whole executor.
+DEV uint32_t cfu_alloc4(uint32_t occ32, uint32_t nsp32, uint32_t lim, uint32_t &pack_out, uint32_t &bits_out) {
+    static_assert(kBatch <= 4 && kMaxSlots <= 32, "the packed slot counts and positions of a batch are 32 bits here");
+    uint32_t got, alloc, pack, ok, ns, f, g, h, pos, pb, b, v;
+#define VDC_ALLOC_STEP(I, BFE)                                                                                  \
+    "s_bfe_u32 %[ns], %[nsp], " BFE "\n\t"      /* slots of uop I */                                              \
+    "s_not_b32 %[f], %[occ]\n\t"                                                                                 \
+    "s_lshr_b32 %[g], %[f], 1\n\t"                                                                               \
+    "s_and_b32 %[g], %[g], %[f]\n\t"            /* starts of runs of two free slots */                           \
+    "s_lshr_b32 %[h], %[f], 2\n\t"                                                                               \
+    "s_and_b32 %[h], %[h], %[g]\n\t"            /* of three */                                                   \
+    "s_cmp_eq_u32 %[ns], 2\n\t"                                                                                  \
+    "s_cselect_b32 %[f], %[g], %[f]\n\t"                                                                         \
+    "s_cmp_eq_u32 %[ns], 3\n\t"                                                                                  \
+    "s_cselect_b32 %[f], %[h], %[f]\n\t"                                                                         \
+    "s_cmp_eq_u32 %[ns], 0\n\t"                                                                                  \
+    "s_cselect_b32 %[f], 1, %[f]\n\t"           /* nothing to allocate (load.local): position 0, no bits */     \
+    "s_ff1_i32_b32 %[pos], %[f]\n\t"                                                                             \
+    "s_lshl_b32 %[pb], %[pos], " #I " * 8\n\t"                                                                   \
+    "s_bfm_b32 %[b], %[ns], %[pos]\n\t"                                                                          \
+    "s_cmp_lg_u32 %[f], 0\n\t"                                                                                   \
+    "s_cselect_b32 %[v], %[ok], 0\n\t"          /* fits, and every uop before it did */                          \
+    "s_cmp_gt_u32 %[lim], " #I "\n\t"                                                                            \
+    "s_cselect_b32 %[ok], %[v], 0\n\t"          /* and it is one of those to try */                              \
+    "s_cmp_lg_u32 %[ok], 0\n\t"                                                                                  \
+    "s_cselect_b32 %[b], %[b], 0\n\t"                                                                            \
+    "s_cselect_b32 %[pb], %[pb], 0\n\t"                                                                          \
+    "s_or_b32 %[occ], %[occ], %[b]\n\t"                                                                          \
+    "s_or_b32 %[alloc], %[alloc], %[b]\n\t"                                                                      \
+    "s_or_b32 %[pack], %[pack], %[pb]\n\t"                                                                       \
+    "s_add_u32 %[got], %[got], %[ok]\n\t"
+    asm volatile(
+        "s_mov_b32 %[got], 0\n\t"
+        "s_mov_b32 %[alloc], 0\n\t"
+        "s_mov_b32 %[pack], 0\n\t"
+        "s_mov_b32 %[ok], 1\n\t"
+        VDC_ALLOC_STEP(0, "0x20000")
+        VDC_ALLOC_STEP(1, "0x20008")
+        VDC_ALLOC_STEP(2, "0x20010")
+        VDC_ALLOC_STEP(3, "0x20018")
+        : [got] "=&s"(got), [alloc] "=&s"(alloc), [pack] "=&s"(pack), [ok] "=&s"(ok), [occ] "+s"(occ32), [ns] "=&s"(ns), [f] "=&s"(f),
+          [g] "=&s"(g), [h] "=&s"(h), [pos] "=&s"(pos), [pb] "=&s"(pb), [b] "=&s"(b), [v] "=&s"(v)
+        : [nsp] "s"(nsp32), [lim] "s"(lim)
+        : "scc");
+#undef VDC_ALLOC_STEP
+    pack_out = pack;
+    bits_out = alloc;
+    return got;
+}
+
+// Publish n uops of the batch that starts at window lane k: mark the slots, hand the empty region of a STORE that
+// sends to its compute core, write the unit records and then the new ring tails (one piece: a unit sees all or
+// nothing), advance the front end's counters.  pos_pack: byte j = first slot of the j-th uop.
+DEV void cfu_publish(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, CfuEnv &env, uint32_t pc, uint32_t k, uint32_t n,
+                     uint64_t pos_pack, uint32_t alloc_bits) {
+    const KParams *p = c.p;
+    const uint64_t my_uu = (uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32);
+    const uint64_t bm = ((1ull << n) - 1ull) << k;
+    const uint32_t slot_vec = (uint32_t)(pos_pack >> (((c.lane - k) & 7u) * 8u)) & 0xFFu;   // lane (k + j): first slot of the j-th uop
+    const uint32_t add_vec = (uint32_t)__builtin_popcountll(my_uu & bm);                     // lane u: records this batch pushes to unit u
+    const uint32_t new_t0 = st.ticket0 + (uint32_t)__builtin_popcountll(d.t0 & bm), new_t1 = st.ticket1 + (uint32_t)__builtin_popcountll(d.t1 & bm);
+    const uint32_t new_tails = st.uq_tail_rf + add_vec;     // lane u = unit u
+    if (__builtin_expect(env.trace, 0)) {
+        const uint64_t my_gaddr = (uint64_t)lv.g_lo | ((uint64_t)lv.g_hi << 32);
+        const bool inb = ((bm >> c.lane) & 1ull) != 0ull;
+        const uint32_t tidx = env.trace_n + (c.lane - k);
+        uint64_t tb = 0;
+#pragma unroll
+        for (int t = 0; t < kMaxTensors; t++) tb = ((d.ctl >> 29) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tb;
+        if (inb && tidx < p->trace_cap) {
+            const uint64_t eff = my_gaddr - tb;
+            u32x4 tr = {pc + (c.lane - k) - c.stream_pc0, (d.ctl & 0xFFu) | (d.desc << 8) | ((d.aux & 0xFFFFu) << 16), (uint32_t)eff, (uint32_t)(eff >> 32)};
+            *(u32x4 *)(p->trace + ((size_t)env.stream * p->trace_cap + tidx) * 4) = tr;
+        }
+        reconverge();
+        if (c.lane == 0) p->trace_count[env.stream] = env.trace_n + n;
+        reconverge();
+        env.trace_n += n;
+    }
+    // the slots are marked taken before anything that names them is published: whoever frees them later (an atomic
+    // and on the same word) then always finds the bits set
+    lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), alloc_bits);
+    // a STORE that sends: the empty output region goes to the compute core at once; the store unit only waits for it
+    // to return
+    const uint64_t e = (uint64_t)(slot_vec | d.e_lo) | ((uint64_t)(((lv.tick + 1u) & 0xFFFFu) | d.e_hi) << 32);
+    lds_st64_lanes(d.early & bm, d.m2c_off + (lv.tick & (kM2C - 1)) * 8u, e);
+    u32x4 rec = {lv.g_lo, lv.g_hi, slot_vec | d.info, lv.tick};
+    lds_st128_lanes(bm, d.uq_off + (lv.pos & (kUQ - 1)) * (uint32_t)sizeof(UnitRec), rec);
+    lds_st32_lanes(env.unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, new_tails);     // after the records
+    st.uq_tail_rf = new_tails;
+    st.ticket0 = new_t0;
+    st.ticket1 = new_t1;
+}
+
+// Dispatch the run of consecutive memory uops that starts at window lane k as one batch, lane (k + j) working on the
+// j-th of them: every lane already holds its uop's effective address, ring position and ticket (CfuLive); only the
+// slot allocation walks the batch in program order (in-order allocation, Section 4.3), on the scalar unit.  nmax = uops
+// in the run (at most kBatch), nsp = their slot counts (a byte each), unit_k = the unit of the first.  Waits until at
+// least the first uop has its slots and its unit has room; returns how many were dispatched (they are published in
+// one piece), or 0 when the run was aborted.
+DEV uint32_t cfu_dispatch(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, CfuEnv &env, uint32_t pc, uint32_t k, uint32_t nmax,
+                          uint64_t nsp, uint32_t unit_k) {
+    const bool small_regions = (nsp & 0xFCFCFCFCFCFCFCFCull) == 0ull;    // every uop of the batch takes at most 3 slots
+    uint64_t pos_pack = 0;       // byte j: first slot of the j-th uop of the batch
+    uint32_t alloc_bits = 0;
+    uint32_t n = 0;
+    Spin sp;
+    PHASE(c, 0u, 3u);
+    SEC_END(c, 3);
+    for (;;) {
+        const uint32_t snap = cfu_poll(c);
+#ifdef VDC_PROFILE_SECTIONS
+        { const uint32_t snap_ = snap; asm volatile("s_waitcnt lgkmcnt(0)" :: "v"(snap_) : "memory"); }
+#endif
+        SEC_END(c, 1);   // the look at the queues and the slot mask
+        // room in the unit queues?  A batch adds at most kBatch records to a ring: when some ring has fewer free
+        // places than that, only the batch's first uop is tried, if its unit has room at all.
+        const uint32_t used = st.uq_tail_rf - snap;          // lane u: records unit u has not picked up yet
+        const bool over = __ballot(c.lane < env.n_units && used > (uint32_t)(kUQ - kBatch)) != 0ull;
+        const bool first_full = __ballot(c.lane == unit_k && used >= (uint32_t)kUQ) != 0ull;
+        uint32_t lim = over ? 1u : nmax;
+        lim = first_full ? 0u : lim;
+        // slots, uop by uop in program order: first fit, lowest position (Section 4.3)
+        uint64_t occ = (uint64_t)rf_get(snap, kPollMask) | env.busy_hi;
+        uint32_t got = 0;
+        alloc_bits = 0;
+        pos_pack = 0;
+        if (__builtin_expect(small_regions, 1)) {
+            // the same first fit for regions of at most 3 slots as a loop that leaves at the first uop that does not
+            // fit: a look that finds no room, the usual case while this path waits, costs a dozen instructions
+            uint32_t sh, ns, pos, pb, bits32, pack32 = 0, f, g, occ32 = (uint32_t)occ;
+            const uint32_t nsp32 = (uint32_t)nsp;
+            asm volatile(
+                "s_mov_b32 %[got], 0\n\t"
+                "s_mov_b32 %[alloc], 0\n\t"
+                "s_cmp_eq_u32 %[lim], 0\n\t"
+                "s_cbranch_scc1 2f\n"
+                "1:\n\t"
+                "s_lshl_b32 %[sh], %[got], 3\n\t"
+                "s_lshr_b32 %[ns], %[nsp], %[sh]\n\t"
+                "s_and_b32 %[ns], %[ns], 3\n\t"
+                "s_not_b32 %[f], %[occ]\n\t"
+                "s_cmp_eq_u32 %[ns], 1\n\t"
+                "s_cbranch_scc1 3f\n\t"
+                "s_lshr_b32 %[g], %[f], 1\n\t"
+                "s_and_b32 %[g], %[g], %[f]\n\t"
+                "s_lshr_b32 %[f], %[f], 2\n\t"
+                "s_and_b32 %[f], %[f], %[g]\n\t"
+                "s_cmp_eq_u32 %[ns], 2\n\t"
+                "s_cselect_b32 %[f], %[g], %[f]\n\t"
+                "s_cmp_eq_u32 %[ns], 0\n\t"
+                "s_cselect_b32 %[f], 1, %[f]\n"      // nothing to allocate (load.local): position 0, no bits
+                "3:\n\t"
+                "s_cmp_eq_u32 %[f], 0\n\t"
+                "s_cbranch_scc1 2f\n\t"
+                "s_ff1_i32_b32 %[pos], %[f]\n\t"
+                "s_bfm_b32 %[b32], %[ns], %[pos]\n\t"
+                "s_or_b32 %[occ], %[occ], %[b32]\n\t"
+                "s_or_b32 %[alloc], %[alloc], %[b32]\n\t"
+                "s_lshl_b32 %[pb], %[pos], %[sh]\n\t"
+                "s_or_b32 %[pack], %[pack], %[pb]\n\t"
+                "s_add_u32 %[got], %[got], 1\n\t"
+                "s_cmp_lt_u32 %[got], %[lim]\n\t"
+                "s_cbranch_scc1 1b\n"
+                "2:"
+                : [got] "=&s"(got), [alloc] "=&s"(alloc_bits), [pack] "+s"(pack32), [occ] "+s"(occ32), [sh] "=&s"(sh), [ns] "=&s"(ns),
+                  [pos] "=&s"(pos), [pb] "=&s"(pb), [b32] "=&s"(bits32), [f] "=&s"(f), [g] "=&s"(g)
+                : [nsp] "s"(nsp32), [lim] "s"(lim)
+                : "scc");
+            pos_pack = pack32;
+        } else {
+            for (; got < lim; got++) {
+                const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
+                const int pos = slot_find(occ, ns);
+                if (pos < 0) break;
+                const uint64_t bits = ((1ull << ns) - 1ull) << (uint32_t)pos;
+                occ |= bits;
+                alloc_bits |= (uint32_t)bits;
+                pos_pack |= (uint64_t)(uint32_t)pos << (8u * got);
+            }
+        }
+        n = got;
+        SEC_END(c, 2);   // the allocation
+        if (got > 0u) break;
+        PHASE(c, 0u, (first_full || over) ? 0u : ((uint32_t)__builtin_popcountll(~occ) >= ((uint32_t)nsp & 0xFFu) ? 4u : 5u));
+        if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | ((uint32_t)nsp & 0x3Fu) | (first_full ? 0x80u : 0u))) return 0u;
+    }
+    PHASE(c, 0u, 6u);
+    cfu_publish(c, d, lv, st, env, pc, k, n, pos_pack, alloc_bits);
+    return n;
+}
+
 DEV void cfu_main(Ctx &c) {
     const KParams *p = c.p;
-    const bool TRACE = p->trace != nullptr;
     const uint32_t n_slots = p->n_slots, n_ldu = p->n_ldu, n_units = p->n_ldu + p->n_stu;
-    const uint32_t stream = c.core * (1u + p->V);
     Seq s;
     const DescRegs dr = desc_regs_load(c);        // in flight together with the stream's bounds
-    s.pc = cload(p->stream_begin, stream);
-    s.end = cload(p->stream_begin, stream + 1u);
+    CfuEnv env;
+    env.n_units = n_units;
+    env.stream = c.core * (1u + p->V);
+    env.unit_lanes = (1ull << n_units) - 1ull;
+    env.busy_hi = slots_beyond(n_slots);
+    env.trace = p->trace != nullptr;
+    env.trace_n = 0;
+    s.pc = cload(p->stream_begin, env.stream);
+    s.end = cload(p->stream_begin, env.stream + 1u);
     s.depth = 0; s.rf_lo = 0; s.rf_hi = 0; s.win_base = 0; s.win = u32x4{0u, 0u, 0u, 0u};
     c.stream_pc0 = s.pc;
     CfuState st = {0, 0, 0, 0, 0, 0};
-    uint32_t trace_n = 0;
     DecWin d;
-    bool ok = cfu_refill(c, d, st, dr, s.pc, s.end);
+    CfuLive lv;
+    bool ok = cfu_refill(c, d, lv, st, dr, s.rf_lo, s.rf_hi, s.pc, s.end);
 
     // The innermost loop frame is kept in scalars (top_start, top_left); outer frames wait in lanes 8.. of the
     // register file.  Accumulators are updated by a masked vector add, so that a control uop never moves a value
     // from the vector to the scalar side and back.
     uint32_t top_start = 0, top_left = 0;
-    const uint64_t unit_lanes = (1ull << n_units) - 1ull;
-    const uint64_t busy_hi = slots_beyond(n_slots);
-    const uint32_t ctl_uq = c.ctl + CTL_OFF(uq), ctl_m2c = c.ctl + CTL_OFF(m2c);
+    SEC_BEGIN(c);
     while (ok) {
         c.pc = s.pc;
         PHASE(c, 0u, 1u);
+        SEC_END(c, 3);       // whatever lies between two sections: the post part of a batch, loop top
         uint32_t k = s.pc - d.base;
         if (__builtin_expect(k >= (uint32_t)kWin, 0)) {
             PHASE(c, 0u, 7u);
-            if (!cfu_refill(c, d, st, dr, s.pc, s.end)) { ok = false; break; }
+            if (!cfu_refill(c, d, lv, st, dr, s.rf_lo, s.rf_hi, s.pc, s.end)) { ok = false; break; }
             k = 0;
         }
         const uint32_t ctlw = rf_get(d.ctl, k);
@@ -646,18 +921,45 @@ DEV void cfu_main(Ctx &c) {
                 s.pc++;
                 continue;
             }
-            // REPEAT, ADD, SET: the accumulator
+            // REPEAT, ADD, SET: the accumulator, and the address of every memory uop of the window that moves with it
+            const uint32_t j = (ctlw >> 20) & 7u;
+            const uint64_t imm = (uint64_t)imm_lo | ((uint64_t)imm_hi << 32);
+            const bool me = c.lane == j, mine = d.dynacc == j;
             {
-                const bool me = c.lane == ((ctlw >> 20) & 7u);
+                const bool set = opcode == (uint32_t)OP_SET;
                 const uint64_t cur = (uint64_t)s.rf_lo | ((uint64_t)s.rf_hi << 32);
-                const uint64_t imm = (uint64_t)imm_lo | ((uint64_t)imm_hi << 32);
-                const uint64_t nv = opcode == (uint32_t)OP_SET ? imm : cur + imm;
+                const uint64_t nv = set ? imm : cur + imm;
                 s.rf_lo = me ? (uint32_t)nv : s.rf_lo;
                 s.rf_hi = me ? (uint32_t)(nv >> 32) : s.rf_hi;
+                const uint64_t g = (set ? ((uint64_t)d.a_lo | ((uint64_t)d.a_hi << 32)) : ((uint64_t)lv.g_lo | ((uint64_t)lv.g_hi << 32))) + imm;
+                lv.g_lo = mine ? (uint32_t)g : lv.g_lo;
+                lv.g_hi = mine ? (uint32_t)(g >> 32) : lv.g_hi;
             }
             const bool rep = opcode == (uint32_t)OP_REPEAT;
             const uint32_t left = rep ? top_left - 1u : top_left;
             const bool back = rep && left > 0u;
+            bool replay = false;
+            uint32_t sl = 0;
+            if (back) {
+                // the loop jumps back: inside the window every lane's ring position and ticket move by what the body
+                // dispatches to its unit / sends to its compute core (worked out once per loop); a jump out of the
+                // window decodes a new one at the top of the loop above
+                sl = top_start - d.base;
+                if (sl <= k) {
+                    const uint32_t key = sl | (k << 8) | (st.n_refill << 16);
+                    if (__builtin_expect(key != lv.loop_key, 0)) {
+                        const uint64_t body = (k >= 63u ? ~0ull : ((1ull << (k + 1u)) - 1ull)) & ~((1ull << sl) - 1ull);
+                        lv.dpos = (uint32_t)__builtin_popcountll(((uint64_t)d.um_lo | ((uint64_t)d.um_hi << 32)) & body);
+                        lv.dtick = (uint32_t)__builtin_popcountll(((uint64_t)d.tm_lo | ((uint64_t)d.tm_hi << 32)) & body);
+                        lv.loop_key = key;
+                    }
+                    lv.pos += lv.dpos;
+                    lv.tick += lv.dtick;
+                    // a body that is nothing but one batch of memory uops is replayed below without decoding anything
+                    const uint32_t n0 = k - sl;
+                    replay = n0 >= 1u && n0 <= (uint32_t)kBatch && ((~(d.mem >> sl)) & ((1ull << n0) - 1ull)) == 0ull;
+                }
+            }
             s.pc = back ? top_start : s.pc + 1u;
             top_left = left;
             if (__builtin_expect(rep && left == 0u, 0)) {
@@ -667,159 +969,94 @@ DEV void cfu_main(Ctx &c) {
                     top_left = rf_get(s.rf_hi, 7u + s.depth);
                 }
             }
+            SEC_END(c, 0);   // a control uop
+            if (!replay) continue;
+            // ---- loop replay: the rest of the trips of a loop whose body is one batch followed by this REPEAT.  Every
+            // trip is the batch and then, fused, what the REPEAT does: the accumulator and the addresses that move with
+            // it advance by the immediate, positions and tickets by the body's counts.  A batch that could only be
+            // dispatched in part (slots, room in a ring) ends the replay; the general path above takes over from there.
+            {
+                const uint32_t n0 = k - sl;
+                const uint64_t nsp_r = (uint64_t)rf_get(d.nsp_lo, sl) | ((uint64_t)rf_get(d.nsp_hi, sl) << 32);
+                const uint32_t nsp32 = (uint32_t)nsp_r & (n0 >= 4u ? 0xFFFFFFFFu : ((1u << (8u * n0)) - 1u));
+                const bool fast = (nsp32 & 0xFCFCFCFCu) == 0u && !env.trace;       // regions of at most three slots, no trace
+                const uint32_t dg_lo = mine ? imm_lo : 0u, dg_hi = mine ? imm_hi : 0u;
+                const uint32_t da_lo = me ? imm_lo : 0u, da_hi = me ? imm_hi : 0u;
+                // what a whole batch publishes is the same on every trip
+                const uint64_t bm0 = ((1ull << n0) - 1ull) << sl;
+                const uint32_t add0 = (uint32_t)__builtin_popcountll(((uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32)) & bm0);
+                const uint32_t dt0 = (uint32_t)__builtin_popcountll(d.t0 & bm0), dt1 = (uint32_t)__builtin_popcountll(d.t1 & bm0);
+                const uint64_t early0 = d.early & bm0;
+                const uint32_t jsh = ((c.lane - sl) & 7u) * 8u;
+                const uint32_t busy32 = (uint32_t)env.busy_hi;
+                const uint32_t need0 = (nsp32 & 0xFFu) + ((nsp32 >> 8) & 0xFFu) + ((nsp32 >> 16) & 0xFFu) + (nsp32 >> 24);
+                bool done = false;
+                while (fast) {
+                    // one trip without a branch but the two that end the loop: look, allocate the whole batch, publish it,
+                    // and do what the REPEAT does
+                    SEC_END(c, 3);
+                    const uint32_t snap = cfu_poll(c);
+#ifdef VDC_PROFILE_SECTIONS
+                    { const uint32_t snap_ = snap; asm volatile("s_waitcnt lgkmcnt(0)" :: "v"(snap_) : "memory"); }
+#endif
+                    SEC_END(c, 1);
+                    const uint32_t used = st.uq_tail_rf - snap;
+                    const bool crowded = __ballot((c.lane < env.n_units && used > (uint32_t)(kUQ - kBatch)) || (c.lane == kPollAbort && snap != 0u)) != 0ull;
+                    const uint32_t occ32 = rf_get(snap, kPollMask) | busy32;
+                    // fewer free slots than the batch takes in all: nothing to try here (the general path waits)
+                    if (crowded || (uint32_t)__builtin_popcount(~occ32) < need0) break;
+                    uint32_t pack32, bits;
+                    const uint32_t got = cfu_alloc4(occ32, nsp32, n0, pack32, bits);
+                    SEC_END(c, 2);
+                    if (got != n0) {
+                        // not all of it fits right now: publish what did and let the general path wait for the rest
+                        if (got != 0u) {
+                            cfu_publish(c, d, lv, st, env, s.pc, sl, got, pack32, bits);
+                            s.pc += got;
+                        }
+                        break;
+                    }
+                    const uint32_t slot_vec = (pack32 >> jsh) & 0xFFu;
+                    lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), bits);
+                    const uint64_t e = (uint64_t)(slot_vec | d.e_lo) | ((uint64_t)(((lv.tick + 1u) & 0xFFFFu) | d.e_hi) << 32);
+                    lds_st64_lanes(early0, d.m2c_off + (lv.tick & (kM2C - 1)) * 8u, e);
+                    u32x4 rec = {lv.g_lo, lv.g_hi, slot_vec | d.info, lv.tick};
+                    lds_st128_lanes(bm0, d.uq_off + (lv.pos & (kUQ - 1)) * (uint32_t)sizeof(UnitRec), rec);
+                    st.uq_tail_rf += add0;
+                    lds_st32_lanes(env.unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, st.uq_tail_rf);     // after the records
+                    st.ticket0 += dt0;
+                    st.ticket1 += dt1;
+                    // the REPEAT
+                    const uint64_t a2 = ((uint64_t)s.rf_lo | ((uint64_t)s.rf_hi << 32)) + ((uint64_t)da_lo | ((uint64_t)da_hi << 32));
+                    s.rf_lo = (uint32_t)a2; s.rf_hi = (uint32_t)(a2 >> 32);
+                    const uint64_t g2 = ((uint64_t)lv.g_lo | ((uint64_t)lv.g_hi << 32)) + ((uint64_t)dg_lo | ((uint64_t)dg_hi << 32));
+                    lv.g_lo = (uint32_t)g2; lv.g_hi = (uint32_t)(g2 >> 32);
+                    top_left--;
+                    if (top_left == 0u) { done = true; break; }
+                    lv.pos += lv.dpos;
+                    lv.tick += lv.dtick;
+                }
+                if (done) {
+                    s.pc = top_start + n0 + 1u;          // past the REPEAT: the loop is done
+                    s.depth--;
+                    if (s.depth > 0u) {
+                        top_start = rf_get(s.rf_lo, 7u + s.depth);
+                        top_left = rf_get(s.rf_hi, 7u + s.depth);
+                    }
+                }
+            }
             continue;
         }
-        // ---- memory uops.  The run of consecutive memory uops that starts here is handled as one batch, lane
-        // (k + j) working on the j-th of them: addresses, queue positions and tickets are computed by all lanes at
-        // once from the masks prepared when the window was decoded; only the slot allocation walks the batch in
-        // program order (in-order allocation), on the scalar unit. ----
+        // ---- memory uops: the run of consecutive memory uops that starts here is one batch ----
         PHASE(c, 0u, 2u);
-        const uint32_t my_op = d.ctl & 0xFFu, my_flags = (d.ctl >> 8) & 0xFFu, my_unit = (d.ctl >> 16) & 7u;
-        const uint32_t my_vcc = (d.ctl >> 19) & 1u, my_acc = (d.ctl >> 20) & 7u, my_nslots = (d.ctl >> 23) & 63u;
         const uint64_t not_mem = ~(d.mem >> k);                 // bit j clear = word k + j is a memory uop
         uint32_t nmax = (uint32_t)__builtin_ctzll(not_mem | (1ull << 63));
         nmax = nmax > (uint32_t)kBatch ? (uint32_t)kBatch : nmax;
         nmax = nmax > (uint32_t)kWin - k ? (uint32_t)kWin - k : nmax;
         nmax = nmax < 1u ? 1u : nmax;
-        // dynamic addresses: every lane picks its own accumulator out of the register file; its unit's queue tail too
-        const uint32_t acc_lo = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_lo);
-        const uint32_t acc_hi = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_acc * 4u), (int)s.rf_hi);
-        const uint32_t my_tail = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(my_unit * 4u), (int)st.uq_tail_rf);
-        const uint64_t my_acc64 = (my_flags & F_DYNAMIC) ? ((uint64_t)acc_lo | ((uint64_t)acc_hi << 32)) : 0ull;
-        const uint64_t my_gaddr = ((uint64_t)d.a_lo | ((uint64_t)d.a_hi << 32)) + my_acc64;
-        const uint64_t my_uu = (uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32);
-        const uint64_t cand = ((1ull << nmax) - 1ull) << k;     // nmax <= kUQ < 64
-        const uint32_t add_full = (uint32_t)__builtin_popcountll(my_uu & cand);   // lane u: uops of the batch for unit u
         const uint64_t nsp = (uint64_t)rf_get(d.nsp_lo, k) | ((uint64_t)rf_get(d.nsp_hi, k) << 32);   // slot counts of the batch
-        const bool small_regions = (nsp & 0xFCFCFCFCFCFCFCFCull) == 0ull;    // every uop of the batch takes at most 3 slots
-        const uint32_t unit_k = (ctlw >> 16) & 7u;
-
-        uint64_t pos_pack = 0;       // byte j: first slot of the j-th uop of the batch
-        uint32_t alloc_bits = 0;
-        uint32_t n = 0;
-        Spin sp;
-        PHASE(c, 0u, 3u);
-        for (;;) {
-            const uint32_t snap = cfu_poll(c);
-            // room in the unit queues for the whole batch?  Otherwise only its first uop is tried, if its unit has room.
-            const uint32_t used = st.uq_tail_rf - snap;          // lane u: records unit u has not picked up yet
-            const bool over = __ballot(c.lane < n_units && used + add_full > (uint32_t)kUQ) != 0ull;
-            const bool first_full = __ballot(c.lane == unit_k && used >= (uint32_t)kUQ) != 0ull;
-            uint32_t lim = over ? 1u : nmax;
-            lim = first_full ? 0u : lim;
-            // slots, uop by uop in program order: first fit, lowest position (Section 4.3)
-            uint64_t occ = (uint64_t)rf_get(snap, kPollMask) | busy_hi;
-            uint32_t got = 0;
-            alloc_bits = 0;
-            pos_pack = 0;
-            if (__builtin_expect(small_regions, 1)) {
-                // the same first fit as slot_find for regions of at most 3 slots, all of the batch, written out for the
-                // scalar unit: two dozen instructions and one taken branch per uop (this loop is the busiest scalar
-                // code of the whole executor, and the compiler's version is half as long again)
-                uint32_t sh, ns, pos, pb, bits32, pack32 = 0;
-                uint64_t f, g, h, bits64;
-                const uint32_t nsp32 = (uint32_t)nsp;
-                static_assert(kBatch <= 4, "the packed slot counts and positions of a batch are 32 bits here");
-                asm volatile(
-                    "s_mov_b32 %[got], 0\n\t"
-                    "s_mov_b32 %[alloc], 0\n\t"
-                    "s_cmp_eq_u32 %[lim], 0\n\t"
-                    "s_cbranch_scc1 2f\n"
-                    "1:\n\t"
-                    "s_lshl_b32 %[sh], %[got], 3\n\t"
-                    "s_lshr_b32 %[ns], %[nsp], %[sh]\n\t"
-                    "s_and_b32 %[ns], %[ns], 3\n\t"
-                    "s_not_b64 %[f], %[occ]\n\t"
-                    "s_lshr_b64 %[g], %[f], 1\n\t"
-                    "s_and_b64 %[g], %[g], %[f]\n\t"
-                    "s_lshr_b64 %[h], %[f], 2\n\t"
-                    "s_and_b64 %[h], %[h], %[g]\n\t"
-                    "s_cmp_eq_u32 %[ns], 2\n\t"
-                    "s_cselect_b64 %[f], %[g], %[f]\n\t"
-                    "s_cmp_eq_u32 %[ns], 3\n\t"
-                    "s_cselect_b64 %[f], %[h], %[f]\n\t"
-                    "s_cmp_eq_u64 %[f], 0\n\t"
-                    "s_cbranch_scc1 2f\n\t"
-                    "s_ff1_i32_b64 %[pos], %[f]\n\t"
-                    "s_bfm_b64 %[b64], %[ns], %[pos]\n\t"
-                    "s_or_b64 %[occ], %[occ], %[b64]\n\t"
-                    "s_bfm_b32 %[b32], %[ns], %[pos]\n\t"
-                    "s_or_b32 %[alloc], %[alloc], %[b32]\n\t"
-                    "s_lshl_b32 %[pb], %[pos], %[sh]\n\t"
-                    "s_or_b32 %[pack], %[pack], %[pb]\n\t"
-                    "s_add_u32 %[got], %[got], 1\n\t"
-                    "s_cmp_lt_u32 %[got], %[lim]\n\t"
-                    "s_cbranch_scc1 1b\n"
-                    "2:"
-                    : [got] "=&s"(got), [alloc] "=&s"(alloc_bits), [pack] "+s"(pack32), [occ] "+s"(occ), [sh] "=&s"(sh), [ns] "=&s"(ns),
-                      [pos] "=&s"(pos), [pb] "=&s"(pb), [b32] "=&s"(bits32), [f] "=&s"(f), [g] "=&s"(g), [h] "=&s"(h), [b64] "=&s"(bits64)
-                    : [nsp] "s"(nsp32), [lim] "s"(lim)
-                    : "scc");
-                pos_pack = pack32;
-            } else {
-                for (; got < lim; got++) {
-                    const uint32_t ns = (uint32_t)(nsp >> (8u * got)) & 0xFFu;
-                    const int pos = slot_find(occ, ns);
-                    if (pos < 0) break;
-                    const uint64_t bits = ((1ull << ns) - 1ull) << (uint32_t)pos;
-                    occ |= bits;
-                    alloc_bits |= (uint32_t)bits;
-                    pos_pack |= (uint64_t)(uint32_t)pos << (8u * got);
-                }
-            }
-            n = got;
-            if (got > 0u) break;
-            PHASE(c, 0u, (first_full || over) ? 0u : ((uint32_t)__builtin_popcountll(~occ) >= ((uint32_t)nsp & 0xFFu) ? 4u : 5u));
-            if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | ((uint32_t)nsp & 0x3Fu) | (first_full ? 0x80u : 0u))) { ok = false; break; }
-        }
-        if (!ok) break;
-        PHASE(c, 0u, 6u);
-        // positions in the unit queues and tickets, in program order
-        const uint64_t bm = ((1ull << n) - 1ull) << k;
-        const uint32_t slot_vec = (uint32_t)(pos_pack >> (((c.lane - k) & 7u) * 8u)) & 0xFFu;   // lane (k + j): first slot of the j-th uop
-        const uint32_t my_rank = (uint32_t)__builtin_popcountll(((uint64_t)d.um_lt_lo | ((uint64_t)d.um_lt_hi << 32)) & bm);
-        const uint32_t my_toff = (uint32_t)__builtin_popcountll(((uint64_t)d.tm_lt_lo | ((uint64_t)d.tm_lt_hi << 32)) & bm);
-        const uint32_t add_vec = (uint32_t)__builtin_popcountll(my_uu & bm);
-        const uint32_t my_pos = my_tail + my_rank;
-        const bool my_send = (my_flags & F_SEND) != 0u;
-        const uint32_t my_ticket = my_send ? (my_vcc == 0u ? st.ticket0 : st.ticket1) + my_toff : 0xFFFFFFFFu;
-        const uint32_t new_t0 = st.ticket0 + (uint32_t)__builtin_popcountll(d.t0 & bm), new_t1 = st.ticket1 + (uint32_t)__builtin_popcountll(d.t1 & bm);
-        const uint32_t table = (st.n_refill - 1u) & 1u;
-        const uint32_t new_tails = st.uq_tail_rf + add_vec;     // lane u = unit u
-        if (__builtin_expect(TRACE, 0)) {
-            const bool inb = ((bm >> c.lane) & 1ull) != 0ull;
-            const uint32_t tidx = trace_n + (c.lane - k);
-            uint64_t tb = 0;
-#pragma unroll
-            for (int t = 0; t < kMaxTensors; t++) tb = ((d.ctl >> 29) == (uint32_t)t) ? (uint64_t)(uintptr_t)p->tensors[t] : tb;
-            if (inb && tidx < p->trace_cap) {
-                const uint64_t eff = my_gaddr - tb;
-                u32x4 tr = {s.pc + (c.lane - k) - c.stream_pc0, my_op | (d.desc << 8) | ((d.aux & 0xFFFFu) << 16), (uint32_t)eff, (uint32_t)(eff >> 32)};
-                *(u32x4 *)(p->trace + ((size_t)stream * p->trace_cap + tidx) * 4) = tr;
-            }
-            reconverge();
-            if (c.lane == 0) p->trace_count[stream] = trace_n + n;
-            reconverge();
-            trace_n += n;
-        }
-        {
-            // a STORE that sends: the empty output region goes to the compute core at once; the store unit only waits
-            // for it to return
-            const uint64_t early = __ballot(my_op == (uint32_t)OP_STORE && my_send) & bm;
-            const uint64_t e = (uint64_t)(slot_vec | (my_nslots << 6) | ((d.aux & 0xFFFFu) << 12)) |
-                               ((uint64_t)(((my_ticket + 1u) & 0xFFFFu) | (d.aux & 0xFFFF0000u)) << 32);
-            // the slots are marked taken before anything that names them is published: whoever frees them later (an
-            // atomic and on the same word) then always finds the bits set
-            lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), alloc_bits);
-            lds_st64_lanes(early, ctl_m2c + (my_vcc * kM2C + (my_ticket & (kM2C - 1))) * 8u, e);
-            const uint32_t off = ctl_uq + (my_unit * kUQ + (my_pos & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
-            u32x4 rec = {(uint32_t)my_gaddr, (uint32_t)(my_gaddr >> 32), slot_vec | (c.lane << 6) | (table << 12), my_ticket};
-            lds_st128_lanes(bm, off, rec);
-            lds_st32_lanes(unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, new_tails);     // after the records
-        }
-        st.uq_tail_rf = new_tails;
-        st.ticket0 = new_t0;
-        st.ticket1 = new_t1;
+        const uint32_t n = cfu_dispatch(c, d, lv, st, env, s.pc, k, nmax, nsp, (ctlw >> 16) & 7u);
+        if (n == 0u) { ok = false; break; }
         s.pc += n;
     }
 
@@ -1026,7 +1263,13 @@ DEV void ldu_main(Ctx &c) {
                 const uint32_t k = fl_head & (kMaxInflight - 1);
                 Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
                 PHASE(c, 1u + u, 3u);
+#ifdef VDC_PROFILE_WAIT_CYCLES
+                const unsigned long long tv = prof_now();
+#endif
                 wait_vmcnt_le(vm_out - (o.ctl & 0xFFu));
+#ifdef VDC_PROFILE_WAIT_CYCLES
+                c.w_vm += prof_now() - tv;
+#endif
                 vm_out -= o.ctl & 0xFFu;
                 PHASE(c, 1u + u, 4u);
                 ldu_retire(c, o);
@@ -2067,11 +2310,7 @@ DEV void observer_main(Ctx &c, uint32_t V) {
 }
 #endif
 
-#ifdef VDC_PROFILE
-#define VDC_MAX_THREADS 768
-#else
-#define VDC_MAX_THREADS 704
-#endif
+#define VDC_MAX_THREADS 768     // twelve waves: three per SIMD, which leaves each 170 vector registers
 __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) {
     // The hardware deals the waves of a workgroup round-robin over the four SIMDs of the compute unit, so which roles
     // share a SIMD (and contend for its issue slots) is decided by which wave takes which role: the host chooses.
@@ -2090,6 +2329,10 @@ __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KPa
         for (uint32_t i = threadIdx.x; i < words; i += blockDim.x) lds_vst32(c.ctl + i * 4u, 0u);
     }
     __syncthreads();   // the only workgroup barrier: before the roles diverge
+    if (wave == 15u) return;   // a wave that is there only to shift the others to another SIMD
+#ifdef VDC_PROFILE_WAITS
+    c.w_t0 = prof_now();
+#endif
 
     if (wave == 0u) {
         c.role = ROLE_CFU; c.unit = 0;
@@ -2116,20 +2359,26 @@ __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KPa
         c.role = ROLE_VCC; c.unit = k >> 1;
         vcc_main(c, k & 1u);
     }
+#ifdef VDC_PROFILE_WAITS
+    if (c.lane == 0 && wave < 16u) {
+        unsigned long long *o = p.prof + ((size_t)blockIdx.x * 16 + wave) * 8;
+        o[0] = c.w_wait; o[1] = c.w_spins; o[2] = c.w_vm; o[3] = prof_now() - c.w_t0;
+        o[4] = c.w_sec[0]; o[5] = c.w_sec[1]; o[6] = c.w_sec[2]; o[7] = c.w_sec[3];
+    }
+#endif
 }
 
 hipError_t prepare_executor_kernels(size_t lds_bytes) {
     return hipFuncSetAttribute((const void *)vdc_executor_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
 }
 
-hipError_t launch_executor(const KParams &p, uint32_t n_cores, bool traced, hipStream_t stream) {
+hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves, hipStream_t stream) {
 #ifdef VDC_PROFILE
-    const uint32_t waves = 2u + p.n_ldu + p.n_stu + 2u * p.V;   // one more: the observer
+    const uint32_t waves = n_waves + 1u;   // one more: the observer
 #else
-    const uint32_t waves = 1u + p.n_ldu + p.n_stu + 2u * p.V;
+    const uint32_t waves = n_waves;
 #endif
     const size_t lds = lds_bytes_needed(p.n_slots, p.slot_bytes);
-    (void)traced;   // tracing is switched by p.trace
     hipLaunchKernelGGL(vdc_executor_kernel, dim3(n_cores), dim3(waves * 64u), lds, stream, p);
     return hipGetLastError();
 }

@@ -524,7 +524,7 @@ def test_two_store_units_serve_the_other_operators_too():
 
 
 def test_role_placement_changes_no_result(ex):
-    """Which units share a SIMD is a matter of speed alone: the same program under both placements gives the same bits
+    """Which units share a SIMD is a matter of speed alone: the same program under every placement gives the same bits
     (the order of every sum is fixed by the program), and the library refuses a placement it does not know."""
     rng = np.random.default_rng(12)
     for rows, K, B, T in ((3000, 128, 1, 8192), (9001, 2052, 3, 8192)):
@@ -535,17 +535,17 @@ def test_role_placement_changes_no_result(ex):
         prog = ex.program_create(w, sb, d, [M.nbytes, X.nbytes, B * rows * 4])
         try:
             got = []
-            for placement in (0, 1):
+            for placement in (0, 1, 2):
                 prog.set_placement(placement)
                 dY = torch.full((B, rows), float("nan"), device="cuda")
                 ex.run(prog, [dM, dX, dY])
                 ex.check()
                 got.append(dY.cpu().numpy())
-            assert np.array_equal(got[0], got[1])
+            assert np.array_equal(got[0], got[1]) and np.array_equal(got[0], got[2])
             Yr, Ya = gemv_ref.gemv_dense(M, X)
             _check(got[1], Yr, Ya, "placement 1 %s" % ((rows, K, B, T),))
             with pytest.raises(vdc.VdcError) as e:
-                prog.set_placement(2)
+                prog.set_placement(3)
             assert e.value.code == vdc.VDC_EINVAL
         finally:
             prog.destroy()
