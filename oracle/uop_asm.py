@@ -16,6 +16,7 @@ import numpy as np
 
 # opcodes
 HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
+CONTINUE_IF = 5      # the loop goes on while acc[acc] < imm; otherwise it is left: `size` = distance to its REPEAT
 LOAD, STORE = 8, 9
 MATVEC = 16
 ROPE = 17

@@ -22,6 +22,10 @@ machine in the paper's order and vocabulary and shares nothing with the HIP path
   after allocation may complete out of order.
 * Section 5 ("Dynamic address generation"): with `dynamic`, the address field is offset by
   an accumulator register that control uops update.
+* Section 4.1 names `continue_if` beside `loop` among the control uops that run on every kind of
+  core and says no more about it.  Reading taken here: a condition on a register decides whether
+  the innermost loop goes on.  While acc[acc] < imm the uop does nothing; otherwise the loop is
+  left at once (its frame is dropped, execution continues behind its REPEAT, `size` words on).
 * Section 4.1, listing of the `matvec` compute uop: for each of `size` tiles pop a matrix
   tile and a vector tile from m2c, accumulate, push both to c2m; then pop an output
   region, copy the accumulators into it and push it back.
@@ -58,7 +62,8 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-HALT, LOOP, REPEAT, ADD, SET = 0, 1, 2, 3, 4
+HALT, LOOP, REPEAT, ADD, SET, CONTINUE_IF = 0, 1, 2, 3, 4, 5
+CONTROL_OPS = (HALT, LOOP, REPEAT, ADD, SET, CONTINUE_IF)
 LOAD, STORE = 8, 9
 MATVEC, ROPE, DROP, COPY, FILL, ATTN, ATTN_MERGE = 16, 17, 18, 19, 20, 21, 22
 F_SEND, F_RECV, F_DYNAMIC, F_NT, F_DEP_SEND, F_DEP_RECV, F_LOCAL = 1, 2, 4, 8, 16, 32, 64
@@ -169,6 +174,29 @@ class _Seq:
         elif u.opcode == SET:
             self.acc[u.acc] = u.imm
             self.pc += 1
+        elif u.opcode == CONTINUE_IF:
+            # Section 4.1 names continue_if next to loop among the control uops and says no more.  The reading taken
+            # here: a condition on a register decides whether the innermost loop goes on.  While acc[acc] < imm the uop
+            # does nothing; otherwise the loop is left at once: its frame is dropped and execution continues behind its
+            # REPEAT, which stands `size` words further on (the generator knows the distance; the words in between
+            # must close every loop they open).
+            if not self.loops:
+                raise ProgramError("CONTINUE_IF outside a loop")
+            depth = 0
+            for q in range(self.pc + 1, self.pc + u.size):
+                if q >= self.end:
+                    break
+                op = decode(self.words[q]).opcode
+                depth += 1 if op == LOOP else (-1 if op == REPEAT else 0)
+                if depth < 0:
+                    break
+            if u.size < 1 or self.pc + u.size >= self.end or depth != 0 or decode(self.words[self.pc + u.size]).opcode != REPEAT:
+                raise ProgramError("CONTINUE_IF does not point at the REPEAT of its loop")
+            if self.acc[u.acc] < u.imm:
+                self.pc += 1
+            else:
+                self.loops.pop()
+                self.pc += u.size + 1
         else:
             return False
         return True
@@ -260,7 +288,7 @@ class Machine:
         if s.halted:
             return False
         u = s.fetch()
-        if u.opcode in (HALT, LOOP, REPEAT, ADD, SET):
+        if u.opcode in CONTROL_OPS:
             if commit:
                 s.control(u)
             return True
@@ -553,7 +581,7 @@ class Machine:
             if s.halted:
                 return False
             u = s.fetch()
-            if u.opcode in (HALT, LOOP, REPEAT, ADD, SET):
+            if u.opcode in CONTROL_OPS:
                 if commit:
                     s.control(u)
                 return True

@@ -1,8 +1,8 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times (one core per CU, default units).
 
-cfg3 and cfg4 are small enough for the fp64 oracle to compute every output.  For cfg5 (8 GiB matrix) the oracle
-computes sampled rows one by one, and properties that hold at any size cover every output: an all-rows closed form
-that is exact in fp32, and single non-zero entries at byte offsets beyond 2^32.
+The fp64 oracle computes every output of cfg3, cfg4 and cfg5 (B = 8 and B = 1; the 8 GiB matrix goes through the host in
+row blocks, one per thread).  Properties that hold at any size come on top: an all-rows closed form that is exact in fp32,
+and single non-zero entries at byte offsets beyond 2^32.
 """
 import numpy as np
 import pytest
@@ -50,28 +50,37 @@ def test_cfg4_ragged_every_output():
     _free()
 
 
+def _oracle_dense_all_rows(M_dev, Xh, threads=16):
+    """The fp64 oracle on every row of a matrix that lives on the GPU: row blocks go through the host one at a time per
+    thread (the C loops run outside the interpreter lock), so the 8 GiB matrix is never held twice."""
+    import concurrent.futures
+    rows = M_dev.shape[0]
+    blk = -(-rows // threads)
+
+    def part(i):
+        a, b = i * blk, min(rows, (i + 1) * blk)
+        return gemv_ref.gemv_dense(M_dev[a:b].cpu().numpy(), Xh)
+
+    with concurrent.futures.ThreadPoolExecutor(threads) as pool:
+        parts = list(pool.map(part, range(threads)))
+    return np.concatenate([p[0] for p in parts], axis=1), np.concatenate([p[1] for p in parts], axis=1)
+
+
 @pytest.mark.parametrize("name", ["cfg5", "cfg5_b1"])
-def test_cfg5_sampled_rows_against_the_oracle(name):
+def test_cfg5_every_output_against_the_oracle(name):
+    """All 32768 x B outputs of the headline configuration against the fp64 definition, in the launch configuration
+    bench.py times."""
     cfg = workloads.CONFIGS[name]
     w = workloads.make(cfg, device="cuda")
     Y = torch.full((cfg.B, cfg.rows), float("nan"), device="cuda")
     with vdc.Executor(slot_bytes=cfg.slot_bytes) as ex:
         ex.matvec(w.M, w.X, Y, cfg.tile_bytes)
         ex.check()
-        n_cores = ex.cfg.n_cores
     Yh = Y.cpu().numpy()
     assert np.isfinite(Yh).all(), "an output was never written"
-    # rows: first and last row of every core's share, both ends of the matrix, and a seeded random sample
-    per = cfg.rows // n_cores
-    rows = {0, cfg.rows - 1}
-    for c in range(n_cores):
-        rows.update((c * per, c * per + per - 1))
-    rng = np.random.default_rng(cfg.seed)
-    rows.update(int(r) for r in rng.integers(0, cfg.rows, 160))
-    rows = np.array(sorted(rows))
-    Ms = w.M[torch.from_numpy(rows).cuda()].cpu().numpy()
-    Yr, Ya = gemv_ref.gemv_dense(Ms, w.X.cpu().numpy())
-    assert _worst(Yh[:, rows], Yr, Ya) <= 1.0
+    Yr, Ya = _oracle_dense_all_rows(w.M, w.X.cpu().numpy())
+    assert Yr.shape == Yh.shape
+    assert _worst(Yh, Yr, Ya) <= 1.0
     del w, Y
     _free()
 
@@ -120,8 +129,7 @@ def test_cfg5_single_entries_beyond_4_gib():
 # ---- decode attention at the benchmark's sizes (bench.py --workload attn_*: 8 heads per request) ---------------
 @pytest.mark.parametrize("regime", ["attn_0.5k_b", "attn_64k", "attn_rand"])
 def test_attention_regimes_at_benchmark_size(regime):
-    """Sampled contexts against the fp64 definition (the first, the last, the longest and the shortest of the batch, one
-    by one), and properties that hold for every output: value rows that are all equal come back whatever the weights are,
+    """Every context against the fp64 definition, and properties that hold for every output: value rows that are all equal come back whatever the weights are,
     up to the rounding of the sums; every output lies between the smallest and largest value it
     averages."""
     from oracle import attn_ref
@@ -140,11 +148,10 @@ def test_attention_regimes_at_benchmark_size(regime):
         ex.check()
         Og = O.cpu().numpy()
         assert np.all(np.isfinite(Og))
-        pick = sorted({0, len(lengths) - 1, int(np.argmax(lengths)), int(np.argmin(lengths))})
-        for s in pick:
-            a, b = int(ro[s]), int(ro[s + 1])
-            Or, Ar, S = attn_ref.attn_decode(Q[s:s + 1].cpu().numpy(), K[a:b].cpu().numpy(), V[a:b].cpu().numpy(), np.array([0, b - a]), d ** -0.5)
-            assert np.all(np.abs(Og[s] - Or[0]) <= (2e-5 * S[0] + 2e-5) * Ar[0] + 1e-30), "context %d" % s
+        # every context of the batch against the fp64 definition
+        Or, Ar, S = attn_ref.attn_decode(Q.cpu().numpy(), K.cpu().numpy(), V.cpu().numpy(), ro, d ** -0.5)
+        bad = np.abs(Og - Or) > (2e-5 * S[:, None] + 2e-5) * Ar + 1e-30
+        assert not bad.any(), "contexts %s" % sorted(set(np.nonzero(bad)[0].tolist()))[:8]
         # every output is a weighted mean of its context's value rows
         seg = torch.repeat_interleave(torch.arange(len(lengths), device="cuda"), torch.from_numpy(lengths).cuda())
         lo = torch.full((len(lengths), d), float("inf"), device="cuda").scatter_reduce(0, seg[:, None].expand(-1, d), V, "amin")
