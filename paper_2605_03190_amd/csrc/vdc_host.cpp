@@ -242,6 +242,21 @@ struct Validator {
                 s.acc[f.acc] = f.imm;
                 s.pc++;
                 return 1;
+            case OP_CONTINUE_IF: {
+                if (s.loops.empty()) { fail("CONTINUE_IF outside a loop"); return -1; }
+                // `size` words on stands the REPEAT of the innermost loop; what lies between closes every loop it opens
+                int depth = 0;
+                bool ok = f.size >= 1 && (uint64_t)s.pc + f.size < (uint64_t)s.end;
+                for (uint32_t q = s.pc + 1; ok && q < s.pc + f.size; q++) {
+                    const uint32_t op = decode(words[q]).opcode;
+                    depth += op == OP_LOOP ? 1 : (op == OP_REPEAT ? -1 : 0);
+                    if (depth < 0) ok = false;
+                }
+                if (!ok || depth != 0 || decode(words[s.pc + f.size]).opcode != OP_REPEAT) { fail("CONTINUE_IF does not point at the REPEAT of its loop"); return -1; }
+                if (s.acc[f.acc] < f.imm) s.pc++;
+                else { s.loops.pop_back(); s.pc += f.size + 1; }
+                return 1;
+            }
             default:
                 return 0;
         }

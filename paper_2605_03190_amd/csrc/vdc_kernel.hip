@@ -393,6 +393,16 @@ DEV int seq_control(Seq &s, const Fields &f) {
             seq_acc_set(s, f.acc, f.imm);
             s.pc++;
             return 1;
+        case OP_CONTINUE_IF:
+            // the loop goes on while the register is below the bound; otherwise it is left: drop its frame, go on behind
+            // its REPEAT (the host checked that `size` words on is that REPEAT)
+            if (seq_acc(s, f.acc) < f.imm) {
+                s.pc++;
+            } else {
+                s.depth--;
+                s.pc += f.size + 1u;
+            }
+            return 1;
         default:
             return 0;
     }
@@ -921,8 +931,32 @@ DEV void cfu_main(Ctx &c) {
                 s.pc++;
                 continue;
             }
-            // REPEAT, ADD, SET: the accumulator, and the address of every memory uop of the window that moves with it
             const uint32_t j = (ctlw >> 20) & 7u;
+            if (__builtin_expect(opcode == (uint32_t)OP_CONTINUE_IF, 0)) {
+                const int64_t cur = (int64_t)((uint64_t)rf_get(s.rf_lo, j) | ((uint64_t)rf_get(s.rf_hi, j) << 32));
+                const int64_t bound = (int64_t)((uint64_t)imm_lo | ((uint64_t)imm_hi << 32));
+                if (cur < bound) {
+                    s.pc++;
+                } else {
+                    // the loop is left: the uops between here and its REPEAT are skipped, not dispatched, so every lane's
+                    // ring position and ticket move back by what the skipped lanes would have pushed (a jump out of the
+                    // window decodes a new one and starts from the counters)
+                    const uint32_t dist = rf_get(d.aux, k) & 0xFFFFu;
+                    if (k + dist < (uint32_t)kWin) {
+                        const uint64_t skipped = ((1ull << (k + dist + 1u)) - 1ull) & ~((1ull << (k + 1u)) - 1ull);
+                        lv.pos -= (uint32_t)__builtin_popcountll(((uint64_t)d.um_lo | ((uint64_t)d.um_hi << 32)) & skipped);
+                        lv.tick -= (uint32_t)__builtin_popcountll(((uint64_t)d.tm_lo | ((uint64_t)d.tm_hi << 32)) & skipped);
+                    }
+                    s.pc += dist + 1u;
+                    s.depth--;
+                    if (s.depth > 0u) {
+                        top_start = rf_get(s.rf_lo, 7u + s.depth);
+                        top_left = rf_get(s.rf_hi, 7u + s.depth);
+                    }
+                }
+                continue;
+            }
+            // REPEAT, ADD, SET: the accumulator, and the address of every memory uop of the window that moves with it
             const uint64_t imm = (uint64_t)imm_lo | ((uint64_t)imm_hi << 32);
             const bool me = c.lane == j, mine = d.dynacc == j;
             {

@@ -200,6 +200,54 @@ def test_programs_assembled_by_the_oracle_side_run_on_the_gpu():
             prog.destroy()
 
 
+def test_continue_if_cuts_loops_short_on_the_gpu():
+    """continue_if (Section 4.1) on both kinds of core: every row block's sweep over K is a LOOP of 1000 trips that the
+    memory core leaves when its offset register reaches the end of the row (so the trip count comes from a register, not
+    from the LOOP), with store and second row block behind it; the compute core's stream is cut short the same way.
+    Result against the fp64 product, the memory cores' traces against the interpreter's."""
+    rng = np.random.default_rng(21)
+    rows, K, B, R, Kt, C, slot = 96, 640, 2, 8, 128, 4, 4096
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    p = A.Program(C, 2)
+    dm, dx = p.desc(0, R, Kt * 4, Kt * 4, K * 4), p.desc(1, B, Kt * 4, Kt * 4, K * 4)
+    dy = p.desc(2, B, R * 4, R * 4, rows * 4)
+    nk = K // Kt
+    for rb in range(rows // R):
+        unit = rb % (C * 2)
+        core, v = unit // 2, unit % 2
+        vm = p.vmc(core)
+        vm += [A.word(A.SET, acc=2, imm=0), A.word(A.LOOP, imm=1000),
+               A.word(A.LOAD, A.F_SEND | A.F_DYNAMIC | A.F_NT, vflow=v, vcc=v, acc=2, nslots=1, size=R, imm=rb * R * K * 4, desc=dm),
+               A.word(A.LOAD, A.F_SEND | A.F_DYNAMIC, vflow=2 + v, vcc=v, acc=2, nslots=1, size=B, imm=0, desc=dx),
+               A.word(A.ADD, acc=2, imm=Kt * 4),
+               A.word(A.CONTINUE_IF, acc=2, imm=K * 4, size=1),
+               A.word(A.REPEAT, acc=7, imm=0),
+               A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=4 + v, vcc=v, nslots=1, size=B, imm=rb * R * 4, desc=dy)]
+        vc = p.vcc(core, v)
+        # one MATVEC per trip of a loop that a register ends after the first trip
+        vc += [A.word(A.SET, acc=1, imm=0), A.word(A.LOOP, imm=50), A.word(A.MATVEC, size=nk, imm=A.matvec_imm(B, R, Kt // 4)),
+               A.word(A.ADD, acc=1, imm=1), A.word(A.CONTINUE_IF, acc=1, imm=1, size=1), A.word(A.REPEAT, acc=0, imm=0)]
+    words, sb, descs = p.finish()
+    with vdc.Executor(n_cores=C, slot_bytes=slot, n_slots=12) as ex:
+        prog = ex.program_create(words, sb, descs, [M.nbytes, X.nbytes, B * rows * 4])
+        dY = torch.full((B, rows), float("nan"), device="cuda")
+        trace, count = ex.run(prog, [_dev(M), _dev(X), dY], trace_cap=1024)
+        ex.check()
+        Yr, Ya = gemv_ref.gemv_dense(M, X)
+        _check(dY.cpu().numpy(), Yr, Ya, "continue_if")
+        Yo = np.zeros((B, rows), np.float32)
+        m = UM.Machine(words, sb, descs, [M, X, Yo], n_cores=C, slot_bytes=slot, n_slots=12).run()
+        trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+        for core in range(C):
+            exp = [(pc, op | (d << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, d, off, n) in m.trace_vmc[core]]
+            blocks = sum(1 for rb in range(rows // R) if (rb % (C * 2)) // 2 == core)
+            assert len(exp) == blocks * (2 * nk + 1)      # per row block: nk trips of two loads (not 1000), one store
+            assert count[core * 3] == len(exp)
+            assert [tuple(int(x) for x in r) for r in trace[core * 3, :len(exp)]] == exp
+        prog.destroy()
+
+
 ROPE_CASES = [
     # rows, K, ld, B, tile_bytes
     (128, 128, 128, 1, 4096),

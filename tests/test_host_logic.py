@@ -230,6 +230,13 @@ def test_validator_rejects_broken_programs():
         def geom(p):
             p.vcc(0, 0)[0] = A.word(A.MATVEC, size=2, imm=A.matvec_imm(1, 16, 7))
         check(geom)
+        # continue_if outside a loop, and one whose distance does not end on its loop's REPEAT
+        assert "CONTINUE_IF" in check(lambda p: p.vmc(0).insert(0, A.word(A.CONTINUE_IF, acc=0, imm=1, size=1)))
+        assert "CONTINUE_IF" in check(lambda p: [p.vmc(0).insert(0, w_) for w_ in reversed(
+            [A.word(A.LOOP, imm=2), A.word(A.CONTINUE_IF, acc=0, imm=1, size=2), A.word(A.ADD), A.word(A.ADD), A.word(A.REPEAT)])])
+        # and a well-formed one is accepted
+        check(lambda p: [p.vmc(0).insert(0, w_) for w_ in reversed(
+            [A.word(A.LOOP, imm=2), A.word(A.CONTINUE_IF, acc=0, imm=1, size=2), A.word(A.ADD), A.word(A.REPEAT)])], expect_ok=True)
         # REPEAT without LOOP, memory opcode on a compute core
         check(lambda p: p.vmc(0).insert(0, A.word(A.REPEAT)))
         check(lambda p: p.vcc(0, 0).insert(0, A.word(A.LOAD)))
