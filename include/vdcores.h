@@ -172,7 +172,9 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
  * local memory (Section 4.2: a store.local / load.local pair hands the matvec's output region to the rope uop of
  * the same compute core).  T: device, [B][rows] floats: for vector b and the pair of rows (2i, 2i+1), T[b][2i] is the
  * cosine and T[b][2i+1] the sine of the pair's angle;  Y[b][2i] = O[b][2i] cos - O[b][2i+1] sin,
- * Y[b][2i+1] = O[b][2i] sin + O[b][2i+1] cos.  rows must be a multiple of 4; T 16-byte aligned.  Dense only. */
+ * Y[b][2i+1] = O[b][2i] sin + O[b][2i+1] cos.  rows must be a multiple of 4; T 16-byte aligned.  Dense only.
+ * The tiler writes the two operators as they come (O stored to a temporary tensor, loaded back for rope) and the
+ * generator's placement step turns every such pair into store.local / load.local; the temporary never exists. */
 int vdc_matvec_rope(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X,
                     const float *T, float *Y, int32_t B, int32_t tile_bytes, void *hip_stream);
 
@@ -271,6 +273,48 @@ int vdc_raw_stream(vdc_executor *ex, int32_t mode, const void *src, void *dst, i
  * vdc_matvec_program does. */
 int vdc_stream_program(vdc_executor *ex, int32_t mode, int64_t bytes, uint32_t value, int32_t tile_bytes, void *uops,
                        int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs);
+
+/* ---- the generator's lowering steps (Section 4.2, "Dependency Graph Lowering" and "Dynamic Data Placement and Fusion") ----
+ *
+ * A uop graph before lowering: memory uops with literal addresses, written down in any order that keeps, per compute
+ * core, the order in which that compute core takes their regions (that order is semantics); the compute cores' own
+ * streams; and edges (store, load) "this load reads what that store wrote".  No flows, no depIds, no local placement. */
+typedef struct {
+    int32_t op;       /* 8 = LOAD, 9 = STORE                                                               */
+    int32_t core;     /* memory core                                                                       */
+    int32_t vcc;      /* compute core that takes (LOAD) or produces (STORE) the region                     */
+    int32_t desc;     /* index into the descriptor table handed in                                         */
+    int64_t offset;   /* byte offset in the descriptor's tensor                                            */
+    int32_t rows;     /* valid rows of the box                                                             */
+    int32_t nslots;   /* slots the box takes                                                               */
+    int32_t group;    /* consumption group on its compute core: the regions one step of a compute uop holds
+                         together carry one number, numbers do not decrease along the compute core's order */
+    int32_t nt;       /* non-zero: streaming hint                                                          */
+} vdc_graph_memop;
+
+/* Lower a graph to bytecode for vdc_program_create, in the paper's steps:
+ *   1. dynamic data placement: an edge whose store and load are neighbours on one compute core, move the same box of a
+ *      tensor in `temp_tensors` (bit t = tensor t), and are each other's only producer / consumer becomes store.local /
+ *      load.local (the descriptor then names `geom_tensor`: geometry only);
+ *   2. virtual flow assignment: the loads of a compute core v from one tensor form a chain; chains take flows 2v, 2v+1
+ *      in the order they first appear (further chains share the second); stores and local pairs take flow 2V + v;
+ *   3. over-allocation: the stream of every memory core (the uops in the order given) is run without data under in-order
+ *      slot allocation; if it deadlocks, every memory core's stream is merged again one consumption group at a time,
+ *      round-robin over its compute cores;
+ *   4. dependencies: every load with producers waits for one depId that all its producers signal (counted; a store
+ *      signals one depId: VDC_EPROGRAM if its consumers do not share their producers), both sides marked device scope;
+ *      a wait that an earlier load on the same flow of the same memory core already made is dropped.
+ * ops (host, n_ops), edges (host, n_edges pairs of indices into ops: store, load), comp_uops / comp_begin (host: the
+ * compute cores' streams, n_cores * vcc_per_core + 1 offsets, compute core (c, v) at index c * V + v; HALTs are added),
+ * descs (host, n_descs of 32 bytes), tensor_bytes (host, n_tensors).  Outputs as vdc_matvec_program's (capacities in
+ * *n_uops, *n_descs_out on entry, needed counts on return; descriptors are renumbered).  stats (host, may be NULL): 5
+ * words: pairs placed, 1 if the streams were reordered, depIds used, waits kept, waits dropped.  The result has passed
+ * the validation of vdc_program_create.  Errors: VDC_EINVAL, VDC_EPROGRAM (also: no order this step knows fits the slots). */
+int vdc_graph_lower(vdc_executor *ex, const vdc_graph_memop *ops, int64_t n_ops, const int64_t *edges, int64_t n_edges,
+                    const void *comp_uops, const uint32_t *comp_begin, const void *descs, int32_t n_descs,
+                    uint32_t temp_tensors, int32_t geom_tensor, const int64_t *tensor_bytes, int32_t n_tensors,
+                    void *uops_out, int64_t *n_uops, uint32_t *stream_begin, void *descs_out, int32_t *n_descs_out,
+                    int32_t *stats);
 
 /* Run the slot allocator of the VMC (Section 4.3, "Virtual Memory Core": the first run of contiguous free slots in
  * the availability mask) on n independent (mask, nslots) requests with a pool of n_slots slots:

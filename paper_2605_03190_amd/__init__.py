@@ -70,6 +70,8 @@ def lib():
             "vdc_raw_stream": [vp, i32, vp, vp, i64, ctypes.c_uint32, vp],
             "vdc_stream_program": [vp, i32, i64, ctypes.c_uint32, i32, vp, ctypes.POINTER(i64), vp, vp, ctypes.POINTER(i32)],
             "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
+            "vdc_graph_lower": [vp, vp, i64, vp, i64, vp, vp, vp, i32, ctypes.c_uint32, i32, vp, i32, vp, ctypes.POINTER(i64), vp, vp,
+                                ctypes.POINTER(i32), vp],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -85,7 +87,7 @@ EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", 
            "vdc_program_destroy", "vdc_program_set_placement", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_noalloc", "vdc_matvec_ragged",
            "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_matvec_chain", "vdc_matvec_chain_program", "vdc_attn_decode", "vdc_attn_decode_program",
            "vdc_stream", "vdc_raw_stream",
-           "vdc_stream_program", "vdc_debug_alloc", "vdc_strerror"]
+           "vdc_stream_program", "vdc_debug_alloc", "vdc_graph_lower", "vdc_strerror"]
 
 
 def strerror(code):
@@ -341,6 +343,31 @@ class Executor:
         """The same bytes as stream(), moved by an ordinary grid-stride kernel: what stream() is measured against."""
         _check(lib().vdc_raw_stream(self.handle, self.STREAM_MODES[mode], src.data_ptr() if src is not None else None,
                                     dst.data_ptr() if dst is not None else None, nbytes, value, _stream_ptr(stream)), "vdc_raw_stream")
+
+    GRAPH_MEMOP = np.dtype([("op", "<i4"), ("core", "<i4"), ("vcc", "<i4"), ("desc", "<i4"), ("offset", "<i8"), ("rows", "<i4"),
+                            ("nslots", "<i4"), ("group", "<i4"), ("nt", "<i4")])
+
+    def graph_lower(self, ops, edges, comp_words, comp_begin, descs, tensor_bytes, temp_tensors=0, geom_tensor=0):
+        """vdc_graph_lower: ops = array of GRAPH_MEMOP, edges = [n, 2] int64 (store, load), comp_words [n, 4] uint32 with
+        comp_begin offsets per compute core, descs [n, 8] uint32.  Returns (words, stream_begin, descs, stats)."""
+        ops = np.ascontiguousarray(ops, dtype=self.GRAPH_MEMOP)
+        edges = np.ascontiguousarray(edges, dtype=np.int64).reshape(-1, 2)
+        comp_words = np.ascontiguousarray(comp_words, dtype=np.uint32).reshape(-1, 4)
+        comp_begin = np.ascontiguousarray(comp_begin, dtype=np.uint32)
+        descs = np.ascontiguousarray(descs, dtype=np.uint32).reshape(-1, 8)
+        tb = np.ascontiguousarray(tensor_bytes, dtype=np.int64)
+        n_w, n_d = ctypes.c_int64(0), ctypes.c_int32(0)
+        stats = np.zeros(5, dtype=np.int32)
+        f = lib().vdc_graph_lower
+        args = (self.handle, _np_ptr(ops), len(ops), _np_ptr(edges) if len(edges) else None, len(edges), _np_ptr(comp_words), _np_ptr(comp_begin),
+                _np_ptr(descs), len(descs), temp_tensors, geom_tensor, _np_ptr(tb), len(tb))
+        rc = f(*args, None, ctypes.byref(n_w), None, None, ctypes.byref(n_d), _np_ptr(stats))
+        _check(rc, "vdc_graph_lower (sizing)")
+        words = np.zeros((n_w.value, 4), dtype=np.uint32)
+        out_descs = np.zeros((n_d.value, 8), dtype=np.uint32)
+        sb = np.zeros(self.n_streams + 1, dtype=np.uint32)
+        _check(f(*args, _np_ptr(words), ctypes.byref(n_w), _np_ptr(sb), _np_ptr(out_descs), ctypes.byref(n_d), _np_ptr(stats)), "vdc_graph_lower")
+        return words, sb, out_descs, stats
 
     def stream_program(self, mode, nbytes, tile_bytes, value=0):
         """The uop graph stream() would run."""

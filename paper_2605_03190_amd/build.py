@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SO = os.path.join(HERE, "libvdcores.so")
-SOURCES = [os.path.join(HERE, "csrc", "vdc_kernel.hip"), os.path.join(HERE, "csrc", "vdc_host.cpp")]
+SOURCES = [os.path.join(HERE, "csrc", "vdc_kernel.hip"), os.path.join(HERE, "csrc", "vdc_host.cpp"), os.path.join(HERE, "csrc", "vdc_lower.cpp")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
          # packed fp32 arithmetic is kept out of the device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

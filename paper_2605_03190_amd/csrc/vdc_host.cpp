@@ -82,6 +82,11 @@ struct ScratchImage {
 };
 static ScratchImage g_scratch_image[64];
 
+namespace vdc {
+int place_local_in_streams(const vdc_config &cfg, std::vector<Word> &words, const std::vector<uint32_t> &sb, std::vector<Desc> &descs,
+                           uint32_t temp_mask, uint32_t geom_tensor);
+}
+
 namespace {
 
 int hip_fail(hipError_t) { return VDC_EDEVICE; }
@@ -602,6 +607,8 @@ struct Run {        // consecutive row blocks of one segment handled by one core
     int32_t tail;   // rows of a final partial block, 0 if none
 };
 
+constexpr uint32_t kRopeTempTensor = 4;     // the intermediate O = M X of the fused operator before the placement step
+
 struct Tiler {
     const vdc_config &cfg;
     int64_t K, ld, y_pitch;  // elements
@@ -636,10 +643,13 @@ struct Tiler {
     // compute core, a load brings the (cos, sin) tile, and the store writes what ROPE produced.
     void emit_result(std::vector<Word> &vm, int v, uint32_t flags_dyn, uint32_t acc, int64_t y_off, uint32_t dy, uint32_t rows_valid, uint32_t y_slots) {
         if (rope) {
-            const uint32_t d_o = desc(2, B, R * 4, R * 4, (uint64_t)y_pitch * 4);                 // geometry only: no memory access
+            // The two operators as they come: O = M X is stored to a temporary tensor (4, shaped like Y) and rope loads it
+            // back.  The generator's placement step (place_local_in_streams, Section 4.2) then finds the one-to-one pair
+            // and keeps O in local memory; the temporary tensor is never touched.
+            const uint32_t d_o = desc(kRopeTempTensor, B, rows_valid * 4, R * 4, (uint64_t)y_pitch * 4);
             const uint32_t d_t = desc(3, B, rows_valid * 4, R * 4, (uint64_t)y_pitch * 4);
-            vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_LOCAL, flow_y(v), v, 0, y_slots, B, 0, 0, d_o, 0));
-            vm.push_back(encode(OP_LOAD, F_SEND | F_LOCAL, flow_y(v), v, 0, 0, B, 0, 0, d_o, 0));
+            vm.push_back(encode(OP_STORE, F_SEND | F_RECV | flags_dyn, flow_y(v), v, acc, y_slots, B, 0, y_off, d_o, 0));
+            vm.push_back(encode(OP_LOAD, F_SEND | flags_dyn, flow_y(v), v, acc, y_slots, B, 0, y_off, d_o, 0));
             vm.push_back(encode(OP_LOAD, F_SEND | flags_dyn, flow_x(v), v, acc, y_slots, B, 0, y_off, d_t, 0));
         }
         vm.push_back(encode(OP_STORE, F_SEND | F_RECV | flags_dyn, flow_y(v), v, acc, y_slots, B, 0, y_off, dy, 0));
@@ -1001,6 +1011,16 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
     }
     descs = t.descs;
     if (descs.empty()) descs.push_back(Desc{0, 1, 16, 16, 0, 0, 0, 0});
+    if (rope) {
+        // dynamic data placement: every row block's store of O and the load behind it become store.local / load.local
+        const int placed = place_local_in_streams(cfg, words, sb, descs, 1u << kRopeTempTensor, 2u);
+        int64_t stores_left = 0;
+        for (const Word &w : words) {
+            const Fields f = decode(w);
+            if ((f.opcode == OP_LOAD || f.opcode == OP_STORE) && !(f.flags & F_LOCAL) && f.desc < descs.size() && descs[f.desc].tensor == kRopeTempTensor) stores_left++;
+        }
+        if (placed < 1 || stores_left != 0) return VDC_EPROGRAM;     // the intermediate would have to exist in memory
+    }
     if (descs.size() > 256) return VDC_EINVAL;
     return VDC_OK;
 }

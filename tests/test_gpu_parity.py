@@ -248,6 +248,61 @@ def test_continue_if_cuts_loops_short_on_the_gpu():
         prog.destroy()
 
 
+def test_graphs_lowered_by_the_library_run_on_the_gpu():
+    """Graphs go through the library's lowering steps (vdc_graph_lower: placement, flows, reordering, depIds) and then
+    through vdc_program_create / vdc_run: the running example against the fp64 product turned by the fp64 rotation, a chain
+    against the layer-by-layer product, a stream that over-commits the slots as written against the product."""
+    from oracle import uop_lower as L
+    from test_host_logic import _graph_arrays
+    rng = np.random.default_rng(31)
+    # matvec -> rope, the intermediate kept in local memory by the placement step
+    rows, K, B, R, Kt, slot, C = 384, 512, 4, 16, 128, 8192, 6
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    T = rope_ref.table(rng.uniform(-np.pi, np.pi, (B, rows // 2)))
+    g = L.matvec_rope_graph(rows, K, B, R, Kt, slot, C)
+    with vdc.Executor(n_cores=C, slot_bytes=slot, n_slots=12) as ex:
+        nb = [M.nbytes, X.nbytes, B * rows * 4, T.nbytes, B * rows * 4]
+        w, sb, d, stats = ex.graph_lower(*_graph_arrays(g), nb, temp_tensors=1 << 4, geom_tensor=2)
+        assert stats[0] == rows // R
+        prog = ex.program_create(w, sb, d, nb)
+        dY = torch.full((B, rows), float("nan"), device="cuda")
+        dO = torch.full((B, rows), float("nan"), device="cuda")
+        ex.run(prog, [_dev(M), _dev(X), dY, _dev(T), dO])
+        ex.check()
+        assert bool(torch.isnan(dO).all())                       # the intermediate never reached memory
+        O, Oa = gemv_ref.gemv_dense(M, X)
+        Rr, Ra = rope_ref.rope(O, T)
+        assert np.all(np.abs(dY.cpu().numpy() - Rr) <= 1e-5 * (Ra + Oa) + 1e-30)
+        prog.destroy()
+    # a chain of three layers with per-tile dependencies
+    dims, B, R, Kt, slot, C = (256, 512, 256, 128), 2, 16, 128, 8192, 3
+    Ls = len(dims) - 1
+    Ms = [(rng.standard_normal((dims[l + 1], dims[l])) / np.sqrt(dims[l])).astype(np.float32) for l in range(Ls)]
+    W = np.concatenate([m.ravel() for m in Ms])
+    X = rng.standard_normal((B, dims[0])).astype(np.float32)
+    g = L.chain_graph(dims, B, R, Kt, slot, C)
+    with vdc.Executor(n_cores=C, slot_bytes=slot, n_slots=12) as ex:
+        nA = B * sum(dims)
+        w, sb, d, stats = ex.graph_lower(*_graph_arrays(g), [W.nbytes, nA * 4, nA * 4])
+        assert stats[2] == sum(dims[l + 1] // Kt for l in range(Ls - 1)) and stats[4] > 0
+        prog = ex.program_create(w, sb, d, [W.nbytes, nA * 4, nA * 4])
+        for rnd in range(2):                                     # twice over the same buffers: the counters start from zero again
+            dA = torch.full((nA,), float("nan"), device="cuda")
+            dA[:B * dims[0]] = _dev((X * (rnd + 1)).ravel())
+            ex.run(prog, [_dev(W), dA, dA])
+            ex.check()
+            a = dA.cpu().numpy()
+            x, off = (X * (rnd + 1)).astype(np.float32), B * dims[0]
+            for l in range(Ls):
+                Yr, Ya = gemv_ref.gemv_dense(Ms[l], x)
+                got = a[off:off + B * dims[l + 1]].reshape(B, dims[l + 1])
+                _check(got, Yr, Ya, "lowered chain, layer %d" % l)
+                x = got
+                off += B * dims[l + 1]
+        prog.destroy()
+
+
 ROPE_CASES = [
     # rows, K, ld, B, tile_bytes
     (128, 128, 128, 1, 4096),

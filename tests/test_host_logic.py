@@ -445,3 +445,108 @@ def test_chain_program_rejects_what_it_cannot_chain():
         with pytest.raises(vdc.VdcError):
             ex.matvec_chain_program((4096, 4098), 1, 16384)            # not a multiple of 4
         ex.matvec_chain_program((4096, 4096), 1, 16384)
+
+
+# ---- the generator's lowering steps (Section 4.2): the library's against the oracle side's, word for word -------------
+def _graph_arrays(g):
+    """An oracle-side graph (oracle/uop_lower.py) in the arrays vdc_graph_lower takes: the memory uops in the order they
+    were written down, the descriptor table, the edges, the compute streams."""
+    from oracle import uop_lower as L
+    ops_list = sorted((m for c in range(g.n_cores) for v in range(g.V) for m in g.mem[c][v]), key=lambda m: m.seq)
+    index = {id(m): i for i, m in enumerate(ops_list)}
+    descs, ops = [], np.zeros(len(ops_list), dtype=vdc.Executor.GRAPH_MEMOP)
+    for i, m in enumerate(ops_list):
+        if m.desc not in descs:
+            descs.append(m.desc)
+        ops[i] = (m.op, m.core, m.vcc, descs.index(m.desc), m.offset, m.rows, m.nslots, m.group, int(m.nt))
+    edges = np.array([(index[id(s)], index[id(l)]) for s, l in g.edges], dtype=np.int64).reshape(-1, 2)
+    comp, begin = [], [0]
+    for c in range(g.n_cores):
+        for v in range(g.V):
+            comp.extend(g.comp[c][v])
+            begin.append(len(comp))
+    dtab = np.array([A.descriptor(*d) for d in descs], dtype=np.uint32)
+    return ops, edges, np.array(comp, dtype=np.uint32).reshape(-1, 4), np.array(begin, dtype=np.uint32), dtab
+
+
+def test_graph_lowering_matches_the_oracle_side_word_for_word():
+    """The same graphs through the library's lowering steps and through the oracle side's: identical bytecode (integer
+    work: bit for bit), for the running example (placement), for a chain (flows, depIds, removed waits) and for a stream
+    that over-commits the slots as written (reordering)."""
+    from oracle import uop_lower as L
+    # the running example of Section 3: matvec, then rope, the intermediate through a temporary tensor
+    rows, K, B, R, Kt, slot, C = 96, 256, 3, 8, 64, 1024, 3
+    nb = [rows * K * 4, B * K * 4, B * rows * 4, B * rows * 4, B * rows * 4]
+    g = L.matvec_rope_graph(rows, K, B, R, Kt, slot, C)
+    arrays = _graph_arrays(g)
+    assert L.place_local(g) == rows // R
+    L.assign_flows(g)
+    L.embed_deps(g)
+    w_ref, sb_ref, d_ref = L.assemble(g).finish()
+    with vdc.Executor(device=-1, n_cores=C, slot_bytes=slot, n_slots=12) as ex:
+        w, sb, d, stats = ex.graph_lower(*arrays, nb, temp_tensors=1 << 4, geom_tensor=2)
+        assert list(stats) == [rows // R, 0, 0, 0, 0]
+        assert np.array_equal(w, w_ref) and np.array_equal(sb, sb_ref) and np.array_equal(d, d_ref)
+        # and without permission to keep tensor 4 out of memory nothing is placed: every pair needs its wait
+        w2, sb2, d2, stats2 = ex.graph_lower(*arrays, nb, temp_tensors=0, geom_tensor=2)
+        assert list(stats2) == [0, 0, rows // R, rows // R, 0]
+    # a chain of three layers: one depId per vector tile, the waits that flow order implies removed
+    dims, B, R, Kt, slot, C = (128, 192, 128, 64), 2, 8, 64, 1024, 3
+    g = L.chain_graph(dims, B, R, Kt, slot, C)
+    arrays = _graph_arrays(g)
+    L.assign_flows(g)
+    n_ids, kept, dropped = L.embed_deps(g)
+    w_ref, sb_ref, d_ref = L.assemble(g).finish()
+    nA = B * sum(dims) * 4
+    with vdc.Executor(device=-1, n_cores=C, slot_bytes=slot, n_slots=12) as ex:
+        w, sb, d, stats = ex.graph_lower(*arrays, [sum(dims[l] * dims[l + 1] for l in range(3)) * 4, nA, nA])
+        assert list(stats) == [0, 0, n_ids, kept, dropped] and dropped > 0
+        assert np.array_equal(w, w_ref) and np.array_equal(sb, sb_ref) and np.array_equal(d, d_ref)
+    # one memory core, two compute cores, uops written down strictly alternating: two slots are over-committed
+    rows, K, B, R, Kt, slot = 32, 128, 1, 8, 64, 2048
+    g = L.new_graph(1, 2, slot)
+    dm, dx, dy = (0, R, Kt * 4, Kt * 4, K * 4), (1, B, Kt * 4, Kt * 4, K * 4), (2, B, R * 4, R * 4, rows * 4)
+    per_v = [[], []]
+    for rb in range(rows // R):
+        v = rb % 2
+        grp = (per_v[v][-1].group + 1) if per_v[v] else 0
+        for kt in range(K // Kt):
+            per_v[v] += [L.MemOp(A.LOAD, 0, v, dm, (rb * R * K + kt * Kt) * 4, R, 1, grp), L.MemOp(A.LOAD, 0, v, dx, kt * Kt * 4, B, 1, grp)]
+            grp += 1
+        per_v[v].append(L.MemOp(A.STORE, 0, v, dy, rb * R * 4, B, 1, grp))
+        g.comp[0][v].append(A.word(A.MATVEC, size=K // Kt, imm=A.matvec_imm(B, R, Kt // 4)))
+    for i in range(max(len(per_v[0]), len(per_v[1]))):          # written down in the starving order
+        for v in (0, 1):
+            if i < len(per_v[v]):
+                g.add(per_v[v][i])
+    arrays = _graph_arrays(g)
+    nb = [rows * K * 4, B * K * 4, B * rows * 4]
+    L.assign_flows(g)
+    assert L.schedule(g, nb, 2) is True
+    w_ref, sb_ref, d_ref = L.assemble(g).finish()
+    with vdc.Executor(device=-1, n_cores=1, slot_bytes=slot, n_slots=2) as ex:
+        w, sb, d, stats = ex.graph_lower(*arrays, nb)
+        assert list(stats) == [0, 1, 0, 0, 0]
+        assert np.array_equal(w, w_ref) and np.array_equal(sb, sb_ref) and np.array_equal(d, d_ref)
+    with vdc.Executor(device=-1, n_cores=1, slot_bytes=slot, n_slots=6) as ex:      # with room the written order stays
+        assert list(ex.graph_lower(*arrays, nb)[3]) == [0, 0, 0, 0, 0]
+    with vdc.Executor(device=-1, n_cores=1, slot_bytes=slot, n_slots=1) as ex:      # no order fits one slot
+        with pytest.raises(vdc.VdcError) as e:
+            ex.graph_lower(*arrays, nb)
+        assert e.value.code == vdc.VDC_EPROGRAM
+
+
+def test_fused_rope_program_comes_from_the_placement_step():
+    """vdc_matvec_rope's tiler writes the two operators as they come; the placement step must have turned every
+    store / load pair of the intermediate into a local pair, and nothing may name the temporary tensor any more."""
+    for rows, K, B, T, C in ((1000, 1000, 1, 4096, 3), (70000, 128, 2, 8192, 4), (512, 4096, 8, 16384, 2)):
+        rows -= rows % 4
+        with vdc.Executor(device=-1, n_cores=C, slot_bytes=min(T, 8192)) as ex:
+            w, sb, d = ex.matvec_rope_program(rows, K, K, B, T)
+        ops, flags, di = w[:, 0] & 0xFF, (w[:, 0] >> 8) & 0xFF, (w[:, 3] >> 16) & 0xFF
+        mem = (ops == A.LOAD) | (ops == A.STORE)
+        local_st = (ops == A.STORE) & ((flags & A.F_LOCAL) != 0)
+        local_ld = (ops == A.LOAD) & ((flags & A.F_LOCAL) != 0)
+        assert local_st.sum() == local_ld.sum() >= 1
+        assert np.all(local_ld[1:][local_st[:-1]])                                  # every store.local is followed by its load.local
+        assert not np.any(d[di[mem & ((flags & A.F_LOCAL) == 0)], 0] == 4)          # no memory uop touches tensor 4
