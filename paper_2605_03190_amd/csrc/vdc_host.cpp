@@ -1399,6 +1399,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     }
     p.dep = dep_table ? dep_table : ex->d_dep;
     p.status = ex->d_status;
+    p.seq_table = ex->d_status + ST_WORDS + 4;
     p.trace = trace;
     p.trace_count = trace_count;
     p.trace_cap = (uint32_t)trace_cap;
@@ -1482,10 +1483,16 @@ int vdc_create(vdc_executor **out, const vdc_config *cfg_in) {
     ex->cu_count = prop.multiProcessorCount;
     ex->lds_limit = (size_t)lds_max;
     if (hipMalloc(&ex->d_dep, sizeof(uint32_t) * cfg.n_dep_ids) != hipSuccess) return VDC_ENOMEM;
-    if (hipMalloc(&ex->d_status, sizeof(uint32_t) * (ST_WORDS + 4)) != hipSuccess) { (void)hipFree(ex->d_dep); return VDC_ENOMEM; }
+    // status words, four words for vdc_raw_stream's sink and the finished-cores count, then the table of sequence numbers
+    if (hipMalloc(&ex->d_status, sizeof(uint32_t) * (ST_WORDS + 4 + kSeqTableWords)) != hipSuccess) { (void)hipFree(ex->d_dep); return VDC_ENOMEM; }
     if (hipHostMalloc(&ex->h_status, sizeof(uint32_t) * ST_WORDS) != hipSuccess) { (void)hipFree(ex->d_dep); (void)hipFree(ex->d_status); return VDC_ENOMEM; }
     hipError_t e = hipMemset(ex->d_dep, 0, sizeof(uint32_t) * cfg.n_dep_ids);
     if (e == hipSuccess) e = hipMemset(ex->d_status, 0, sizeof(uint32_t) * (ST_WORDS + 4));   // the last four words: the sink of vdc_raw_stream
+    if (e == hipSuccess) {
+        std::vector<uint32_t> seq(kSeqTableWords);
+        for (uint32_t i = 0; i < kSeqTableWords; i++) seq[i] = i;
+        e = hipMemcpy(ex->d_status + ST_WORDS + 4, seq.data(), sizeof(uint32_t) * kSeqTableWords, hipMemcpyHostToDevice);
+    }
     if (e == hipSuccess) e = prepare_executor_kernels(lds_bytes_needed(cfg.n_slots, cfg.slot_bytes));
     // set-up for the entry point that may not allocate: the address of this device's static scratch array (the device
     // is current here), a pinned staging buffer and an event

@@ -34,6 +34,8 @@ struct KParams {
     uint64_t wave_roles;    // four bits per wave of the workgroup: the position in the role order (front end, load units,
                             // store units, compute waves) that this wave takes
     uint32_t *status;       // ST_WORDS words
+    const uint32_t *seq_table;  // kSeqTableWords words, word i = i: where the load units fetch the sequence numbers that
+                                // mark a loaded tile ready (the kernel's M2cEnt explains)
     uint32_t *trace;        // optional: n_streams * trace_cap * 4 words
     uint32_t *trace_count;  // optional: n_streams words
     uint32_t trace_cap;
@@ -43,6 +45,8 @@ struct KParams {
     unsigned long long *prof;   // cores * 8 waves * 8 counters (profiling builds only)
 #endif
 };
+
+constexpr uint32_t kSeqTableWords = 2052;
 
 // Bytes of dynamic LDS one workgroup needs for n_slots slots of slot_bytes plus the control block.
 size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes);

@@ -51,6 +51,7 @@ static __device__ __forceinline__ unsigned long long prof_now() {
 // ------------------------------------------------------------------------------------------------
 // LDS layout: [0, n_slots * slot_bytes) the slots, then the control block.
 // ------------------------------------------------------------------------------------------------
+#define DEV_EARLY __device__ __forceinline__
 constexpr int kUQ = 8;         // records per unit queue (CFU -> LDU/STU)
 constexpr int kBatch = 4;      // memory uops the front end dispatches at once (a batch is published in one piece: more is later)
 constexpr int kM2C = 32;       // m2c ring entries per VCC (>= slots, so a delivery never finds it full)
@@ -58,8 +59,6 @@ constexpr int kC2M = 64;       // c2m ring entries per VCC
 constexpr int kMbox = 32;      // produced regions waiting for their STORE, per VCC
 constexpr int kMaxUnits = 8;   // n_ldu + n_stu
 constexpr int kMaxV = 2;
-constexpr int kMaxInflight = 4;  // tiles one LDU keeps in flight
-constexpr int kMaxVm = 56;       // outstanding load instructions one LDU allows itself (vmcnt holds 63)
 constexpr int kRecWords = 4;
 constexpr int kStatWords = 8;
 constexpr int kWin = 64;        // uops in the decoded window
@@ -75,6 +74,24 @@ struct UnitRec {  // the per-execution part of a memory uop after the front end 
     uint32_t info;                 // slot [5:0] | window lane [11:6] | table [12]
     uint32_t ticket;               // m2c position when SEND
 };
+
+// One m2c entry (16 bytes).  The payload is written by the front end when it dispatches the sending uop (it knows the
+// slot, the shape and the ticket); `ready` says that the region may be used.  For a loaded tile `ready` is written by the
+// memory system itself: the load unit issues, behind the tile's direct-to-LDS loads, one more direct-to-LDS load of four
+// bytes that brings the expected sequence number from a small table in global memory into this word.  Loads of one wave
+// return in the order they were issued, so the word changes only after the whole tile is in place, and the load unit
+// never has to wait for a tile or come back to it: the copy completes, and announces itself, without a wave, as a
+// copy engine with a completion object would do it.  The sequence number of ticket t is (t / kM2C mod kSeqRounds) + 1: never
+// zero, and different from the one the same ring position carried kM2C tickets earlier.
+struct M2cEnt {
+    uint32_t lo;      // slot | nslots << 6 | rows << 12
+    uint32_t hi;      // (ticket + 1) & 0xffff | row_bytes << 16
+    uint32_t ready;   // the ticket's sequence number once the region may be used
+    uint32_t rsv;
+};
+constexpr uint32_t kSeqRounds = 2048;   // the table in global memory holds 0 .. kSeqRounds, word i = i
+static_assert(kSeqTableWords > kSeqRounds, "the table holds every sequence number");
+DEV_EARLY uint32_t m2c_seq(uint32_t ticket) { return ((ticket / (uint32_t)kM2C) & (kSeqRounds - 1u)) + 1u; }
 
 struct StatRec {  // the static part, written for all 64 uops of a window at once when it is decoded (32 bytes)
     uint32_t gp_lo, gp_hi;   // bytes between rows in global memory
@@ -102,7 +119,7 @@ struct Ctl {
     uint32_t red_ack[kMaxV];
     uint32_t win_gen;              // number of windows the front end has decoded so far
     uint32_t pad0[1];
-    uint64_t m2c[kMaxV][kM2C];     // low: slot | nslots << 6 | rows << 12; high: (ticket + 1) & 0xffff | row_bytes << 16
+    M2cEnt m2c[kMaxV][kM2C];       // see M2cEnt
     uint64_t c2m[kMaxV][kC2M];     // low: kind | slot << 1 | nslots << 7; high: position + 1
     UnitRec uq[kMaxUnits][kUQ];
     StatRec stat[2][kWin];         // two tables: the window being executed and the previous one
@@ -113,7 +130,7 @@ struct Ctl {
 #endif
 };
 static_assert(offsetof(Ctl, mask) == offsetof(Ctl, uq_head) + 4 * kMaxUnits && offsetof(Ctl, abort) == offsetof(Ctl, mask) + 4, "poll block");
-static_assert(offsetof(Ctl, m2c) % 8 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0 && offsetof(Ctl, stat) % 16 == 0, "alignment");
+static_assert(sizeof(M2cEnt) == 16 && offsetof(Ctl, m2c) % 16 == 0 && offsetof(Ctl, c2m) % 8 == 0 && offsetof(Ctl, uq) % 16 == 0 && offsetof(Ctl, stat) % 16 == 0, "alignment");
 static_assert(sizeof(UnitRec) == 4 * kRecWords && sizeof(StatRec) == 4 * kStatWords, "record size");
 #define CTL_OFF(field) ((uint32_t)offsetof(Ctl, field))
 #ifdef VDC_PROFILE_SECTIONS
@@ -464,12 +481,9 @@ DEV uint32_t slot_bits(uint32_t slot, uint32_t nslots) {
 }
 
 DEV void m2c_deliver(Ctx &c, uint32_t v, uint32_t ticket, uint32_t slot, uint32_t nslots, uint32_t rows, uint32_t row_bytes) {
-    if (c.lane == 0) {
-        uint64_t e = (uint64_t)(slot | (nslots << 6) | (rows << 12)) |
-                     ((uint64_t)(((ticket + 1u) & 0xFFFFu) | (row_bytes << 16)) << 32);
-        lds_vst64(c.ctl + CTL_OFF(m2c) + (v * kM2C + (ticket & (kM2C - 1))) * 8u, e);
-    }
-    reconverge();
+    // payload and sequence number in one 16-byte store: a reader sees all of it or none
+    const u32x4 e = {slot | (nslots << 6) | (rows << 12), ((ticket + 1u) & 0xFFFFu) | (row_bytes << 16), m2c_seq(ticket), 0u};
+    lds_st128_lanes(1ull, c.ctl + CTL_OFF(m2c) + (v * kM2C + (ticket & (kM2C - 1))) * (uint32_t)sizeof(M2cEnt), e);
 }
 
 DEV void slots_free(Ctx &c, uint32_t slot, uint32_t nslots) {
@@ -519,11 +533,11 @@ struct DecWin {
     uint32_t nsp_lo, nsp_hi; // byte j: nslots of the uop j lanes further on (j = 0..7), 0 beyond the window
     uint32_t uq_off;     // where the unit's ring of records starts in LDS
     uint32_t m2c_off;    // where the compute core's m2c ring starts
-    uint32_t e_lo, e_hi; // a STORE that sends: its m2c entry without slot and ticket
+    uint32_t e_lo, e_hi; // a uop that sends: its m2c entry without slot and ticket
+    uint32_t e_sel;      // all ones for a STORE that sends (its empty region is ready at once), else 0
     uint32_t info;       // the record's info word without the slot: window lane << 6 | table << 12
     uint64_t mem;        // wave-uniform: lanes that hold memory uops
     uint64_t t0, t1;     // wave-uniform: lanes whose uop sends to compute core 0 / 1
-    uint64_t early;      // wave-uniform: lanes that hold a STORE that sends (its empty region goes out at dispatch)
 };
 
 // What moves while the window is executed, per lane, for the uop that lane holds.  A memory uop's effective address
@@ -608,7 +622,6 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuLive &lv, CfuState &st, const DescRegs
         d.mem = uni64(__ballot(is_mem));
         d.t0 = uni64(__ballot(send && (f.vcc & 1u) == 0u));
         d.t1 = uni64(__ballot(send && (f.vcc & 1u) == 1u));
-        d.early = uni64(__ballot(send && f.opcode == OP_STORE));
         const uint64_t tm = send ? ((f.vcc & 1u) ? d.t1 : d.t0) : 0ull;
         d.um_lo = (uint32_t)my_um; d.um_hi = (uint32_t)(my_um >> 32);
         d.tm_lo = (uint32_t)tm; d.tm_hi = (uint32_t)(tm >> 32);
@@ -625,7 +638,8 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuLive &lv, CfuState &st, const DescRegs
     }
     d.dynacc = (is_mem && (f.flags & F_DYNAMIC)) ? f.acc : 8u;
     d.uq_off = c.ctl + CTL_OFF(uq) + unit * kUQ * (uint32_t)sizeof(UnitRec);
-    d.m2c_off = c.ctl + CTL_OFF(m2c) + (f.vcc & 1u) * kM2C * 8u;
+    d.m2c_off = c.ctl + CTL_OFF(m2c) + (f.vcc & 1u) * kM2C * (uint32_t)sizeof(M2cEnt);
+    d.e_sel = (send && f.opcode == OP_STORE) ? 0xFFFFFFFFu : 0u;
     d.e_lo = (f.nslots << 6) | (f.size << 12);
     d.e_hi = d_rowb << 16;
     d.info = (c.lane << 6) | ((st.n_refill & 1u) << 12);
@@ -768,10 +782,11 @@ DEV void cfu_publish(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, C
     // the slots are marked taken before anything that names them is published: whoever frees them later (an atomic
     // and on the same word) then always finds the bits set
     lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), alloc_bits);
-    // a STORE that sends: the empty output region goes to the compute core at once; the store unit only waits for it
-    // to return
-    const uint64_t e = (uint64_t)(slot_vec | d.e_lo) | ((uint64_t)(((lv.tick + 1u) & 0xFFFFu) | d.e_hi) << 32);
-    lds_st64_lanes(d.early & bm, d.m2c_off + (lv.tick & (kM2C - 1)) * 8u, e);
+    // every uop that sends: the payload of its m2c entry.  A STORE that sends: the empty output region goes to the compute
+    // core at once (the entry is ready), the store unit only waits for it to return; for a LOAD the entry becomes ready
+    // when the tile has landed
+    const u32x4 e = {slot_vec | d.e_lo, ((lv.tick + 1u) & 0xFFFFu) | d.e_hi, m2c_seq(lv.tick) & d.e_sel, 0u};
+    lds_st128_lanes((d.t0 | d.t1) & bm, d.m2c_off + (lv.tick & (kM2C - 1)) * (uint32_t)sizeof(M2cEnt), e);
     u32x4 rec = {lv.g_lo, lv.g_hi, slot_vec | d.info, lv.tick};
     lds_st128_lanes(bm, d.uq_off + (lv.pos & (kUQ - 1)) * (uint32_t)sizeof(UnitRec), rec);
     lds_st32_lanes(env.unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, new_tails);     // after the records
@@ -1020,7 +1035,7 @@ DEV void cfu_main(Ctx &c) {
                 const uint64_t bm0 = ((1ull << n0) - 1ull) << sl;
                 const uint32_t add0 = (uint32_t)__builtin_popcountll(((uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32)) & bm0);
                 const uint32_t dt0 = (uint32_t)__builtin_popcountll(d.t0 & bm0), dt1 = (uint32_t)__builtin_popcountll(d.t1 & bm0);
-                const uint64_t early0 = d.early & bm0;
+                const uint64_t send0 = (d.t0 | d.t1) & bm0;
                 const uint32_t jsh = ((c.lane - sl) & 7u) * 8u;
                 const uint32_t busy32 = (uint32_t)env.busy_hi;
                 const uint32_t need0 = (nsp32 & 0xFFu) + ((nsp32 >> 8) & 0xFFu) + ((nsp32 >> 16) & 0xFFu) + (nsp32 >> 24);
@@ -1052,8 +1067,8 @@ DEV void cfu_main(Ctx &c) {
                     }
                     const uint32_t slot_vec = (pack32 >> jsh) & 0xFFu;
                     lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), bits);
-                    const uint64_t e = (uint64_t)(slot_vec | d.e_lo) | ((uint64_t)(((lv.tick + 1u) & 0xFFFFu) | d.e_hi) << 32);
-                    lds_st64_lanes(early0, d.m2c_off + (lv.tick & (kM2C - 1)) * 8u, e);
+                    const u32x4 e = {slot_vec | d.e_lo, ((lv.tick + 1u) & 0xFFFFu) | d.e_hi, m2c_seq(lv.tick) & d.e_sel, 0u};
+                    lds_st128_lanes(send0, d.m2c_off + (lv.tick & (kM2C - 1)) * (uint32_t)sizeof(M2cEnt), e);
                     u32x4 rec = {lv.g_lo, lv.g_hi, slot_vec | d.info, lv.tick};
                     lds_st128_lanes(bm0, d.uq_off + (lv.pos & (kUQ - 1)) * (uint32_t)sizeof(UnitRec), rec);
                     st.uq_tail_rf += add0;
@@ -1113,30 +1128,6 @@ DEV void cfu_main(Ctx &c) {
 // ------------------------------------------------------------------------------------------------
 // LDU: tile loads, global -> LDS, without going through registers
 // ------------------------------------------------------------------------------------------------
-// Waits until at most n of this wave's loads are outstanding.  The count in s_waitcnt is an immediate, so the
-// threshold is rounded down to one of a few levels (waiting for fewer is always safe); nested uniform branches
-// rather than a switch, which the compiler lowers to a long chain here.
-DEV void wait_vmcnt_le(uint32_t n) {
-#define VDC_W(k) asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory")
-    if (n < 16u) {
-        if (n < 8u) {
-            if (n < 4u) {
-                if (n < 2u) { if (n < 1u) VDC_W(0); else VDC_W(1); }
-                else { if (n < 3u) VDC_W(2); else VDC_W(3); }
-            } else { if (n < 6u) VDC_W(4); else VDC_W(6); }
-        } else { if (n < 12u) VDC_W(8); else VDC_W(12); }
-    } else if (n < 32u) {
-        if (n < 24u) { if (n < 20u) VDC_W(16); else VDC_W(20); }
-        else { if (n < 28u) VDC_W(24); else VDC_W(28); }
-    } else if (n < 48u) {
-        if (n < 40u) { if (n < 36u) VDC_W(32); else VDC_W(36); }
-        else { if (n < 44u) VDC_W(40); else VDC_W(44); }
-    } else {
-        if (n < 52u) VDC_W(48); else if (n < 56u) VDC_W(52); else VDC_W(56);
-    }
-#undef VDC_W
-}
-
 DEV void load_lds_b128(uint32_t lds_addr_wave, const char *gptr, bool nt, bool device) {
     // LDS address = M0 + lane * 16 (wave-uniform base in M0, one 16-byte chunk per active lane)
     lds_addr_wave = uni(lds_addr_wave);
@@ -1178,22 +1169,6 @@ DEV void dep_signal(Ctx &c, uint32_t dep, bool written_through) {
     reconverge();
 }
 
-// What an LDU must do once the loads of a tile have landed: the m2c message is built when the loads are issued.
-struct Inflight {
-    uint32_t msg_lo, msg_hi;   // the m2c entry
-    uint32_t ctl;              // load instructions [7:0] | SEND [8] | DEP_SEND [9] | m2c entry offset / 8 [19:10]
-    uint32_t dep;
-};
-
-DEV void ldu_retire(Ctx &c, const Inflight &t) {
-    lds_wait();   // zero fill of this tile (ds_write) is done as well
-    // A load that signals does so before it delivers: once the tile is delivered the compute core may finish and the
-    // core may leave, and the core that leaves last puts the counters back to zero; no signal may come after that.
-    if (__builtin_expect((t.ctl & 0x200u) != 0u, 0)) dep_signal(c, t.dep, false);
-    lds_st64_lanes((t.ctl & 0x100u) ? 1ull : 0ull, c.ctl + CTL_OFF(m2c) + ((t.ctl >> 10) & 0x3FFu) * 8u,
-                   (uint64_t)t.msg_lo | ((uint64_t)t.msg_hi << 32));
-}
-
 // The static part of a record: lanes 0..7 = the StatRec the record's info word points at.
 DEV uint32_t stat_fetch(Ctx &c, uint32_t info) {
     const uint32_t base = c.ctl + CTL_OFF(stat) + (((info >> 12) & 1u) * kWin + ((info >> 6) & 63u)) * (uint32_t)sizeof(StatRec);
@@ -1208,8 +1183,7 @@ struct LduEnt {
     uint32_t ni;                // load instructions per tile
     uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path | 32 DEVICE
     uint32_t step_lo, step_hi;  // fast path: address step per load instruction
-    uint32_t msg_lo, msg_hi;    // m2c entry without slot and ticket
-    uint32_t m2c_base;          // vcc * kM2C
+    uint32_t m2c_ready;         // LDS byte offset of the ready word of entry 0 of the compute core's m2c ring
     uint32_t off_lo, off_hi;    // fast path, per lane: offset of the lane's first chunk from the tile address
 };
 
@@ -1220,7 +1194,7 @@ DEV void ldu_derive(Ctx &c, LduEnt &e, uint32_t key, uint32_t info) {
     const uint32_t rows_box = rf_get(e.val, 2), rb_pitch = rf_get(e.val, 3), w0 = rf_get(e.val, 4);
     const uint32_t rows = rows_box & 0xFFFFu, box_rows = rows_box >> 16, row_bytes = rb_pitch & 0xFFFFu, lds_pitch = rb_pitch >> 16;
     const uint32_t cpr = lds_pitch >> 4, vcr = row_bytes >> 4, total = box_rows * cpr;
-    const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u, nslots = (w0 >> 25) & 63u;
+    const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u;
     e.ni = (total + 63u) >> 6;
     const bool pow2 = (cpr & (cpr - 1u)) == 0u && cpr <= 64u;
     const bool fast = pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u;
@@ -1231,24 +1205,23 @@ DEV void ldu_derive(Ctx &c, LduEnt &e, uint32_t key, uint32_t info) {
     const uint64_t step = (uint64_t)drow * gpitch;
     e.step_lo = (uint32_t)step;
     e.step_hi = (uint32_t)(step >> 32);
-    e.msg_lo = (nslots << 6) | (rows << 12);
-    e.msg_hi = row_bytes << 16;
-    e.m2c_base = vcc * kM2C;
+    e.m2c_ready = c.ctl + CTL_OFF(m2c) + vcc * kM2C * (uint32_t)sizeof(M2cEnt) + (uint32_t)offsetof(M2cEnt, ready);
     const uint64_t off = (uint64_t)(c.lane >> sh) * gpitch + (uint64_t)(c.lane & (cpr - 1u)) * 16u;
     e.off_lo = (uint32_t)off;
     e.off_hi = (uint32_t)(off >> 32);
 }
 
+// A load unit pops its ring in order, issues the direct-to-LDS loads of the tile and, behind them, the four-byte load
+// that makes the tile's m2c entry ready when everything before it has landed (see M2cEnt).  It never waits for a tile:
+// as many tiles are in flight as there are slots for them, and a tile is delivered the moment it is complete.
 DEV void ldu_main(Ctx &c) {
     const uint32_t u = c.unit;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds0();
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
-    // tiles in flight: a ring in a lane register file (lane k = entry k), oldest at fl_head
-    uint32_t fl_lo = 0, fl_hi = 0, fl_ctl = 0, fl_dep = 0;
-    uint32_t fl_head = 0;
-    uint32_t n_fl = 0;
-    uint32_t vm_out = 0;      // load instructions issued and not yet known complete
+    const uint64_t seq_table = (uint64_t)(uintptr_t)c.p->seq_table;
     uint32_t head = 0;
+    // an upper bound of the wave's outstanding load instructions (the hardware counter holds 63)
+    uint32_t vm_bound = 0;
     // Keys are (table, window lane); both entries are dropped whenever the front end has decoded a new window,
     // which the poll sees in the same snapshot as any record dispatched from it.  `cur` is the entry of the uop
     // the unit handled last, with its wave-uniform fields in scalar registers.
@@ -1265,10 +1238,22 @@ DEV void ldu_main(Ctx &c) {
     const uint32_t poll_rec = (c.lane >= 1u && c.lane <= 4u) ? (uint32_t)sizeof(UnitRec) : 0u;
     Spin sp;
     bool ok = true;
+    SEC_BEGIN(c);
     while (ok) {
         PHASE(c, 1u + u, 1u);
+        SEC_END(c, 3);
         const uint32_t snap = lds_vld32(poll_off + poll_rec * (head & (kUQ - 1)));
-        const bool have = rf_get(snap, 0) != head;
+#ifdef VDC_PROFILE_SECTIONS
+        { const uint32_t snap_ = snap; asm volatile("s_waitcnt lgkmcnt(0)" :: "v"(snap_) : "memory"); }
+#endif
+        SEC_END(c, 0);
+        if (rf_get(snap, 0) == head) {
+            // nothing to do
+            if (rf_get(snap, 5) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
+            PHASE(c, 1u + u, 5u);
+            if (!spin_step(c, sp, rf_get(snap, 6), 0x600u | u)) ok = false;
+            continue;
+        }
         const uint32_t gen = rf_get(snap, 7);
         if (__builtin_expect(gen != seen_gen, 0)) {
             seen_gen = gen;
@@ -1276,7 +1261,7 @@ DEV void ldu_main(Ctx &c) {
         }
         const uint32_t info = rf_get(snap, 3);
         const uint32_t key = (info >> 6) & 0x7Fu;
-        if (have && key != cur.key) {
+        if (key != cur.key) {
             if (((key >> 2) ^ key) & 1u) {   // two entries: loop bodies alternate between lanes 1, 2 or 4 apart
                 if (e1.key != key) ldu_derive(c, e1, key, info);
                 cur = e1;
@@ -1285,73 +1270,30 @@ DEV void ldu_main(Ctx &c) {
                 cur = e0;
             }
             cur.ni = uni(cur.ni); cur.bits = uni(cur.bits); cur.key = uni(cur.key);
-            cur.step_lo = uni(cur.step_lo); cur.step_hi = uni(cur.step_hi);
-            cur.msg_lo = uni(cur.msg_lo); cur.msg_hi = uni(cur.msg_hi); cur.m2c_base = uni(cur.m2c_base);
+            cur.step_lo = uni(cur.step_lo); cur.step_hi = uni(cur.step_hi); cur.m2c_ready = uni(cur.m2c_ready);
         }
-        const uint32_t ni = cur.ni;
-        // retire the oldest tile when nothing can be issued on top of what is in flight; the record seen by this poll
-        // stays valid meanwhile, so it can be issued right after without looking again
-        bool can_issue = have && n_fl < (uint32_t)kMaxInflight && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
-        if (!can_issue) {
-            if (n_fl > 0) {
-                const uint32_t k = fl_head & (kMaxInflight - 1);
-                Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
-                PHASE(c, 1u + u, 3u);
-#ifdef VDC_PROFILE_WAIT_CYCLES
-                const unsigned long long tv = prof_now();
-#endif
-                wait_vmcnt_le(vm_out - (o.ctl & 0xFFu));
-#ifdef VDC_PROFILE_WAIT_CYCLES
-                c.w_vm += prof_now() - tv;
-#endif
-                vm_out -= o.ctl & 0xFFu;
-                PHASE(c, 1u + u, 4u);
-                ldu_retire(c, o);
-                OBS(c, 1u + u, fl_head + 1u);
-                fl_head++;
-                n_fl--;
-                sp.n = 0;
-                can_issue = have && (vm_out + ni <= (uint32_t)kMaxVm || n_fl == 0);
-                if (!can_issue) continue;
-            } else {
-                // idle
-                if (rf_get(snap, 5) && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) break;
-                PHASE(c, 1u + u, 5u);
-                if (!spin_step(c, sp, rf_get(snap, 6), 0x600u | u)) ok = false;
-                continue;
-            }
-        }
+        SEC_END(c, 1);
         // ---- issue the loads of the record ----
         PHASE(c, 1u + u, 2u);
-        const uint32_t val = cur.val, bits = cur.bits;
-        const uint32_t e_msg_lo = cur.msg_lo, e_msg_hi = cur.msg_hi, e_m2c = cur.m2c_base;
+        const uint32_t ni = cur.ni, val = cur.val, bits = cur.bits;
         const uint64_t gaddr = (uint64_t)rf_get(snap, 1) | ((uint64_t)rf_get(snap, 2) << 32);
         const uint32_t ticket = rf_get(snap, 4), slot = info & 63u, lds_off = slot << slot_shift;
-        c.pc = c.stream_pc0 + rf_get(val, 6);
-        if (bits & 8u) {
-            // an unresolved dependency blocks this unit, and only this unit (Section 4.3).  Whatever is already in
-            // flight is delivered first: the awaited signal may depend on it.  A dependency that is already there
-            // costs one look at its counter.
-            const uint32_t dep = rf_get(val, 5);
-            const bool acquire = (bits & 32u) == 0u;
-            if (dep_ready(c, dep)) {
-                if (acquire) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            } else {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                vm_out = 0;
-                for (; n_fl > 0; n_fl--, fl_head++) {
-                    const uint32_t k = fl_head & (kMaxInflight - 1);
-                    Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
-                    ldu_retire(c, o);
-                }
-                if (!dep_wait(c, dep, acquire)) { ok = false; break; }
-            }
+        if (__builtin_expect((bits & 8u) != 0u, 0)) {
+            // an unresolved dependency blocks this unit, and only this unit (Section 4.3); what it has in flight
+            // completes by itself meanwhile.  A dependency that is already there costs one look at its counter.
+            c.pc = c.stream_pc0 + rf_get(val, 6);
+            if (!dep_wait(c, rf_get(val, 5), (bits & 32u) == 0u)) { ok = false; break; }
         }
+        // the counter of outstanding loads must not run over: make room first when this tile might
+        if (__builtin_expect(vm_bound + ni + 1u > 60u, 0)) {
+            if (ni + 1u > 44u) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); vm_bound = 0; }
+            else { asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); vm_bound = 16; }
+        }
+        SEC_END(c, 2);
         if (bits & 16u) {
             // the usual case: whole tile, a power-of-two row of at most 64 chunks.  Every instruction moves 64 / cpr
             // whole rows, so the per-lane address just advances by a uniform step
             const uint64_t off = (uint64_t)cur.off_lo | ((uint64_t)cur.off_hi << 32);
-            const char *g = (const char *)(uintptr_t)(gaddr + off);
             const uint64_t step = (uint64_t)cur.step_lo | ((uint64_t)cur.step_hi << 32);
             uint32_t dst = lds_base + lds_off;
             // Four instructions per trip, straight-line: back to back they issue about four times faster than one per
@@ -1363,31 +1305,28 @@ DEV void ldu_main(Ctx &c) {
                  "s_add_u32 m0, m0, 0x400\n\tv_lshl_add_u64 %[g], %[g], 0, %[step]\n\tglobal_load_lds_dwordx4 %[g], off" NT "\n\t" \
                  "v_lshl_add_u64 %[g], %[g], 0, %[step]"                                                           \
                  : [g] "+v"(ga) : [dst] "s"(dst), [step] "s"(step) : "memory", "scc")
-            uint64_t ga = (uint64_t)(uintptr_t)g;
+#define VDC_LOAD_TILE(NT)                                                                                          \
+    for (; i + 4u <= ni; i += 4u) {                                                                                \
+        VDC_LOAD4(NT);                                                                                             \
+        dst += 4096u;                                                                                              \
+        if (__builtin_expect((i & 31u) == 28u && i + 4u < ni, 0)) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); \
+    }                                                                                                              \
+    for (; i < ni; i++) {                                                                                          \
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" NT ::"s"(dst), "v"(ga) : "memory"); \
+        dst += 1024u;                                                                                              \
+        ga += step;                                                                                                \
+    }
+            uint64_t ga = gaddr + off;
             uint32_t i = 0;
             if (bits & 32u) {
                 // device scope: the tile may have been written by another core during this run
-                for (; i + 4u <= ni; i += 4u) { VDC_LOAD4(" sc1"); dst += 4096u; }
-                for (; i < ni; i++) {
-                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off sc1" ::"s"(dst), "v"(ga) : "memory");
-                    dst += 1024u;
-                    ga += step;
-                }
+                VDC_LOAD_TILE(" sc1")
             } else if (bits & 1u) {
-                for (; i + 4u <= ni; i += 4u) { VDC_LOAD4(" nt"); dst += 4096u; }
-                for (; i < ni; i++) {
-                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(dst), "v"(ga) : "memory");
-                    dst += 1024u;
-                    ga += step;
-                }
+                VDC_LOAD_TILE(" nt")
             } else {
-                for (; i + 4u <= ni; i += 4u) { VDC_LOAD4(""); dst += 4096u; }
-                for (; i < ni; i++) {
-                    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(ga) : "memory");
-                    dst += 1024u;
-                    ga += step;
-                }
+                VDC_LOAD_TILE("")
             }
+#undef VDC_LOAD_TILE
 #undef VDC_LOAD4
         } else {
             const uint64_t gpitch = (uint64_t)rf_get(val, 0) | ((uint64_t)rf_get(val, 1) << 32);
@@ -1413,31 +1352,38 @@ DEV void ldu_main(Ctx &c) {
                 row += drow;
                 col += dcol;
                 if (col >= cpr) { col -= cpr; row++; }
+                if ((i & 31u) == 31u && i + 1u < ni) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
             }
+            // the zero fill is an ordinary LDS write of this wave: it must be in place before the completing load is
+            // even issued
+            lds_wait();
         }
+        vm_bound += ni + 1u;
         PHASE(c, 1u + u, 6u);
-        {
-            const uint32_t k = (fl_head + n_fl) & (kMaxInflight - 1);
-            fl_lo = rf_set(fl_lo, k, e_msg_lo | slot);
-            fl_hi = rf_set(fl_hi, k, e_msg_hi | ((ticket + 1u) & 0xFFFFu));
-            fl_ctl = rf_set(fl_ctl, k, ni | ((bits & 2u) ? 0x100u : 0u) | ((bits & 4u) ? 0x200u : 0u) | ((e_m2c + (ticket & (kM2C - 1))) << 10));
-            if (bits & 4u) fl_dep = rf_set(fl_dep, k, rf_get(val, 5));
+        if (__builtin_expect((bits & 4u) != 0u, 0)) {
+            // A load that signals does so once its data has landed and before it delivers: once the tile is delivered the
+            // compute core may finish and the core may leave, and the core that leaves last puts the counters back to
+            // zero; no signal may come after that.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            vm_bound = 0;
+            dep_signal(c, rf_get(val, 5), false);
         }
-        n_fl++;
-        vm_out += ni;
+        // the completing load: the entry's sequence number, fetched behind the tile
+        {
+            const uint32_t rdst = lds_base + cur.m2c_ready + (ticket & (kM2C - 1)) * (uint32_t)sizeof(M2cEnt);
+            const uint64_t fa = seq_table + (uint64_t)m2c_seq(ticket) * 4u;
+            const uint64_t lanes = (bits & 2u) ? 1ull : 0ull;
+            uint64_t saved;
+            asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %1\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %3, off\n\ts_mov_b64 exec, %0"
+                         : "=&s"(saved) : "s"(lanes), "s"(rdst), "v"(fa) : "memory");
+        }
         head++;
+        OBS(c, 1u + u, head);
         lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_head) + u * 4u, head);
         sp.n = 0;
     }
     // never leave with loads in flight: their LDS destination belongs to this workgroup only while it lives
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (ok) {
-        for (; n_fl > 0; n_fl--, fl_head++) {
-            const uint32_t k = fl_head & (kMaxInflight - 1);
-            Inflight o = {rf_get(fl_lo, k), rf_get(fl_hi, k), rf_get(fl_ctl, k), rf_get(fl_dep, k)};
-            ldu_retire(c, o);
-        }
-    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1493,12 +1439,18 @@ DEV void stu_main(Ctx &c) {
     uint32_t park_rf = 0, park_head = 0, park_tail = 0;   // regions a store.local took back, waiting for their load.local
     Spin sp;
     bool ok = true;
+    SEC_BEGIN(c);
     while (ok) {
         PHASE(c, 1u + u, 1u);
+        SEC_END(c, 3);
         // the c2m queues carry produced regions only (a compute core frees a used region itself, see vcc_done_with):
         // the poll brings the next entry of each along
         const uint32_t snap = stu_poll(c, u, ring0, head, c2m_head0, c2m_head1);
         PHASE(c, 1u + u, 2u);
+#ifdef VDC_PROFILE_SECTIONS
+        { const uint32_t snap_ = snap; asm volatile("s_waitcnt lgkmcnt(0)" :: "v"(snap_) : "memory"); }
+#endif
+        SEC_END(c, 0);
         bool moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0);
         if (n_rings > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
         if (moved) OBS(c, 5u, c2m_head0 | (c2m_head1 << 16));
@@ -1514,6 +1466,7 @@ DEV void stu_main(Ctx &c) {
             have = true;
             moved = true;
         }
+        SEC_END(c, 1);
         if (have) {
             const uint32_t w0 = rf_get(stat, 4), dep = rf_get(stat, 5);
             const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u, nslots = (w0 >> 25) & 63u;
@@ -1579,6 +1532,7 @@ DEV void stu_main(Ctx &c) {
                 const uint32_t lds_off = slot << slot_shift;
                 compiler_barrier();
                 PHASE(c, 1u + u, 4u);
+                SEC_END(c, 2);
                 bool through = false;            // stored at device scope (only the 16-byte path does that)
                 if (((r_glo | (uint32_t)gpitch | rb_pitch | (rb_pitch >> 16)) & 15u) == 0u) {
                     // whole 16-byte chunks: lane l takes chunks l, l + 64, ... of the box, four at a time.  The lane's
@@ -1708,20 +1662,22 @@ struct Msg {
     uint32_t slot, nslots, rows, row_bytes;
 };
 
-// lanes 0,1 = m2c entry of ticket head (low, high), lanes 2,3 = of ticket head + 1, lane 5 = abort
+// lanes 0..3 = m2c entry of ticket head (payload low, high, ready word, unused), lanes 4..7 = of ticket head + 1,
+// lane 8 = abort
+constexpr uint32_t kVccPollAbort = 8;
 DEV uint32_t vcc_poll(Ctx &c, uint32_t head) {
     const uint32_t v = c.unit;
-    const uint32_t e0 = c.ctl + CTL_OFF(m2c) + (v * kM2C + (head & (kM2C - 1))) * 8u;
-    const uint32_t e1 = c.ctl + CTL_OFF(m2c) + (v * kM2C + ((head + 1u) & (kM2C - 1))) * 8u;
+    const uint32_t e0 = c.ctl + CTL_OFF(m2c) + (v * kM2C + (head & (kM2C - 1))) * (uint32_t)sizeof(M2cEnt);
+    const uint32_t e1 = c.ctl + CTL_OFF(m2c) + (v * kM2C + ((head + 1u) & (kM2C - 1))) * (uint32_t)sizeof(M2cEnt);
     uint32_t off = c.ctl + CTL_OFF(abort);
-    off = c.lane < 4u ? e1 + (c.lane - 2u) * 4u : off;
-    off = c.lane < 2u ? e0 + c.lane * 4u : off;
+    off = c.lane < 8u ? e1 + (c.lane - 4u) * 4u : off;
+    off = c.lane < 4u ? e0 + c.lane * 4u : off;
     return lds_vld32(off);
 }
 
 DEV bool msg_ready(uint32_t snap, uint32_t which, uint32_t ticket, Msg &m) {
-    const uint32_t lo = rf_get(snap, which * 2u), hi = rf_get(snap, which * 2u + 1u);
-    if ((hi & 0xFFFFu) != ((ticket + 1u) & 0xFFFFu)) return false;
+    const uint32_t lo = rf_get(snap, which * 4u), hi = rf_get(snap, which * 4u + 1u);
+    if (rf_get(snap, which * 4u + 2u) != m2c_seq(ticket)) return false;
     m.slot = lo & 63u;
     m.nslots = (lo >> 6) & 63u;
     m.rows = lo >> 12;
@@ -1746,7 +1702,7 @@ DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, 
             OBS(c, 6u + c.unit * 2u + vs.wv, vs.head + n);
             return true;
         }
-        if (!spin_step(c, s, rf_get(snap, 5), 0x100u | c.unit)) return false;
+        if (!spin_step(c, s, rf_get(snap, kVccPollAbort), 0x100u | c.unit)) return false;
     }
 }
 
