@@ -1689,7 +1689,7 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
             if (!rope && choose_tile(ex->cfg, K, B, tile_bytes, R, Kt) && K <= Kt &&
                 rows / R >= 8 * (int64_t)ex->cfg.n_cores * ex->cfg.vcc_per_core) prog->placement = 1;   // and enough of them to matter
             // long sweeps over K: the front end's loop is the busiest wave; it gets a SIMD with one compute wave only
-            else if (Kt > 0 && K / Kt >= 64) prog->placement = 2;
+            else if (Kt > 0 && K / Kt >= 16) prog->placement = 2;
         }
         cache_insert(ex, std::move(key), prog);
     }
@@ -1750,7 +1750,7 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
         {
             int R = 0, Kt = 0;   // the same choice of role placement as vdc_matvec makes
             if (choose_tile(c, K, B, tile_bytes, R, Kt) && K <= Kt && rows / R >= 8 * (int64_t)c.n_cores * c.vcc_per_core) n.placement = 1;
-            else if (Kt > 0 && K / Kt >= 64) n.placement = 2;
+            else if (Kt > 0 && K / Kt >= 16) n.placement = 2;
         }
         // the staging buffer may still be the source of the copy of an earlier call
         if (ex->stage_pending) HIP_TRY(hipEventSynchronize(ex->stage_done));

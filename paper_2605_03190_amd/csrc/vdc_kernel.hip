@@ -33,6 +33,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "vdc_isa.h"
 #include "vdc_kernel.h"
 
@@ -54,6 +56,7 @@ static __device__ __forceinline__ unsigned long long prof_now() {
 #define DEV_EARLY __device__ __forceinline__
 constexpr int kUQ = 8;         // records per unit queue (CFU -> LDU/STU)
 constexpr int kBatch = 4;      // memory uops the front end dispatches at once (a batch is published in one piece: more is later)
+constexpr int kBatchOnes = 8;  // ... when every uop of the batch takes one slot: the lanes then allocate side by side
 constexpr int kM2C = 32;       // m2c ring entries per VCC (>= slots, so a delivery never finds it full)
 constexpr int kC2M = 64;       // c2m ring entries per VCC
 constexpr int kMbox = 32;      // produced regions waiting for their STORE, per VCC
@@ -538,6 +541,7 @@ struct DecWin {
     uint32_t info;       // the record's info word without the slot: window lane << 6 | table << 12
     uint64_t mem;        // wave-uniform: lanes that hold memory uops
     uint64_t t0, t1;     // wave-uniform: lanes whose uop sends to compute core 0 / 1
+    uint64_t ones;       // wave-uniform: lanes that hold a memory uop of exactly one slot
 };
 
 // What moves while the window is executed, per lane, for the uop that lane holds.  A memory uop's effective address
@@ -622,6 +626,7 @@ DEV bool cfu_refill(Ctx &c, DecWin &d, CfuLive &lv, CfuState &st, const DescRegs
         d.mem = uni64(__ballot(is_mem));
         d.t0 = uni64(__ballot(send && (f.vcc & 1u) == 0u));
         d.t1 = uni64(__ballot(send && (f.vcc & 1u) == 1u));
+        d.ones = uni64(__ballot(is_mem && f.nslots == 1u));
         const uint64_t tm = send ? ((f.vcc & 1u) ? d.t1 : d.t0) : 0ull;
         d.um_lo = (uint32_t)my_um; d.um_hi = (uint32_t)(my_um >> 32);
         d.tm_lo = (uint32_t)tm; d.tm_hi = (uint32_t)(tm >> 32);
@@ -753,12 +758,11 @@ DEV uint32_t cfu_alloc4(uint32_t occ32, uint32_t nsp32, uint32_t lim, uint32_t &
 // Publish n uops of the batch that starts at window lane k: mark the slots, hand the empty region of a STORE that
 // sends to its compute core, write the unit records and then the new ring tails (one piece: a unit sees all or
 // nothing), advance the front end's counters.  pos_pack: byte j = first slot of the j-th uop.
-DEV void cfu_publish(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, CfuEnv &env, uint32_t pc, uint32_t k, uint32_t n,
-                     uint64_t pos_pack, uint32_t alloc_bits) {
+DEV void cfu_publish_lanes(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, CfuEnv &env, uint32_t pc, uint32_t k, uint32_t n,
+                           uint32_t slot_vec, uint32_t alloc_bits) {
     const KParams *p = c.p;
     const uint64_t my_uu = (uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32);
     const uint64_t bm = ((1ull << n) - 1ull) << k;
-    const uint32_t slot_vec = (uint32_t)(pos_pack >> (((c.lane - k) & 7u) * 8u)) & 0xFFu;   // lane (k + j): first slot of the j-th uop
     const uint32_t add_vec = (uint32_t)__builtin_popcountll(my_uu & bm);                     // lane u: records this batch pushes to unit u
     const uint32_t new_t0 = st.ticket0 + (uint32_t)__builtin_popcountll(d.t0 & bm), new_t1 = st.ticket1 + (uint32_t)__builtin_popcountll(d.t1 & bm);
     const uint32_t new_tails = st.uq_tail_rf + add_vec;     // lane u = unit u
@@ -793,6 +797,59 @@ DEV void cfu_publish(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, C
     st.uq_tail_rf = new_tails;
     st.ticket0 = new_t0;
     st.ticket1 = new_t1;
+}
+
+DEV void cfu_publish(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, CfuEnv &env, uint32_t pc, uint32_t k, uint32_t n,
+                     uint64_t pos_pack, uint32_t alloc_bits) {
+    const uint32_t slot_vec = (uint32_t)(pos_pack >> (((c.lane - k) & 7u) * 8u)) & 0xFFu;   // lane (k + j): first slot of the j-th uop
+    cfu_publish_lanes(c, d, lv, st, env, pc, k, n, slot_vec, alloc_bits);
+}
+
+// First fit for n uops of one slot each, all at once: the j-th uop of the batch takes the j-th free slot from the bottom,
+// which is what n first fits one after the other give (Section 4.3 lets the lanes of the unit probe the mask side by
+// side; here lane l looks at slot l).  free32: bit set = slot free; n <= the number of free slots.  Lane l, if its slot
+// is among the n lowest free ones, sends l to the lane of the uop that gets it (lane k + rank, rank = free slots below
+// l) through the cross-lane network; every other lane sends to lane k - 1, which no uop of the batch occupies.
+// Returns, in lane k + j, the slot of the j-th uop; bits: the n slots taken.
+DEV uint32_t cfu_alloc_ones(Ctx &c, uint32_t free32, uint32_t n, uint32_t k, uint32_t &bits) {
+    const uint32_t rank = __builtin_amdgcn_mbcnt_lo(free32, 0u);
+    const bool take = c.lane < 32u && ((free32 >> (c.lane & 31u)) & 1u) != 0u && rank < n;
+    bits = (uint32_t)__ballot(take);
+    const uint32_t dst = take ? k + rank : (k + 63u) & 63u;
+    return (uint32_t)__builtin_amdgcn_ds_permute((int)(dst * 4u), (int)c.lane);
+}
+
+// Dispatch a run of up to nmax <= kBatchOnes consecutive memory uops of one slot each, starting at window lane k: as
+// many of them as there are free slots right now (at least one), provided every unit's ring has room for its share;
+// when some ring has not, only the first uop, if its unit has room.  In order, lowest slots first, published in one
+// piece.  Returns how many were dispatched, or 0 when the run was aborted.
+DEV uint32_t cfu_dispatch_ones(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &st, CfuEnv &env, uint32_t pc, uint32_t k, uint32_t nmax,
+                               uint32_t unit_k) {
+    const uint64_t my_uu = (uint64_t)d.uu_lo | ((uint64_t)d.uu_hi << 32);
+    const uint32_t busy32 = (uint32_t)env.busy_hi;
+    Spin sp;
+    PHASE(c, 0u, 3u);
+    for (;;) {
+        const uint32_t snap = cfu_poll(c);
+        const uint32_t free32 = ~(rf_get(snap, kPollMask) | busy32);
+        const uint32_t nfree = (uint32_t)__builtin_popcount(free32);
+        uint32_t n = nfree < nmax ? nfree : nmax;
+        const uint32_t used = st.uq_tail_rf - snap;          // lane u: records unit u has not picked up yet
+        const uint32_t add = (uint32_t)__builtin_popcountll(my_uu & (((1ull << n) - 1ull) << k));
+        const bool over = __ballot(c.lane < env.n_units && used + add > (uint32_t)kUQ) != 0ull;
+        const bool first_full = __ballot(c.lane == unit_k && used >= (uint32_t)kUQ) != 0ull;
+        n = over ? (n < 1u ? n : 1u) : n;
+        n = first_full ? 0u : n;
+        if (n > 0u) {
+            uint32_t bits;
+            const uint32_t slot_vec = cfu_alloc_ones(c, free32, n, k, bits);
+            PHASE(c, 0u, 6u);
+            cfu_publish_lanes(c, d, lv, st, env, pc, k, n, slot_vec, bits);
+            return n;
+        }
+        PHASE(c, 0u, first_full ? 0u : 5u);
+        if (!spin_step(c, sp, rf_get(snap, kPollAbort), 0x300u | 1u | (first_full ? 0x80u : 0u))) return 0u;
+    }
 }
 
 // Dispatch the run of consecutive memory uops that starts at window lane k as one batch, lane (k + j) working on the
@@ -1006,7 +1063,9 @@ DEV void cfu_main(Ctx &c) {
                     lv.tick += lv.dtick;
                     // a body that is nothing but one batch of memory uops is replayed below without decoding anything
                     const uint32_t n0 = k - sl;
-                    replay = n0 >= 1u && n0 <= (uint32_t)kBatch && ((~(d.mem >> sl)) & ((1ull << n0) - 1ull)) == 0ull;
+                    const uint64_t body0 = (1ull << n0) - 1ull;
+                    replay = n0 >= 1u && (~(d.mem >> sl) & body0) == 0ull &&
+                             (n0 <= (uint32_t)kBatch || (n0 <= (uint32_t)kBatchOnes && (~(d.ones >> sl) & body0) == 0ull));
                 }
             }
             s.pc = back ? top_start : s.pc + 1u;
@@ -1028,7 +1087,8 @@ DEV void cfu_main(Ctx &c) {
                 const uint32_t n0 = k - sl;
                 const uint64_t nsp_r = (uint64_t)rf_get(d.nsp_lo, sl) | ((uint64_t)rf_get(d.nsp_hi, sl) << 32);
                 const uint32_t nsp32 = (uint32_t)nsp_r & (n0 >= 4u ? 0xFFFFFFFFu : ((1u << (8u * n0)) - 1u));
-                const bool fast = (nsp32 & 0xFCFCFCFCu) == 0u && !env.trace;       // regions of at most three slots, no trace
+                const bool ones = n0 >= 2u && (~(d.ones >> sl) & ((1ull << n0) - 1ull)) == 0ull;   // one slot each: the wide allocation
+                const bool fast = (ones || (n0 <= (uint32_t)kBatch && (nsp32 & 0xFCFCFCFCu) == 0u)) && !env.trace;   // regions of at most three slots, no trace
                 const uint32_t dg_lo = mine ? imm_lo : 0u, dg_hi = mine ? imm_hi : 0u;
                 const uint32_t da_lo = me ? imm_lo : 0u, da_hi = me ? imm_hi : 0u;
                 // what a whole batch publishes is the same on every trip
@@ -1038,52 +1098,67 @@ DEV void cfu_main(Ctx &c) {
                 const uint64_t send0 = (d.t0 | d.t1) & bm0;
                 const uint32_t jsh = ((c.lane - sl) & 7u) * 8u;
                 const uint32_t busy32 = (uint32_t)env.busy_hi;
-                const uint32_t need0 = (nsp32 & 0xFFu) + ((nsp32 >> 8) & 0xFFu) + ((nsp32 >> 16) & 0xFFu) + (nsp32 >> 24);
+                const uint32_t need0 = ones ? n0 : (nsp32 & 0xFFu) + ((nsp32 >> 8) & 0xFFu) + ((nsp32 >> 16) & 0xFFu) + (nsp32 >> 24);
+                // lanes whose look at the queues can forbid a whole batch: a unit whose ring has no room for its share, or
+                // the abort word (the lanes from kPollAbort on all read it)
+                const uint32_t room_need = c.lane < env.n_units ? (uint32_t)kUQ - add0 : (c.lane >= kPollAbort ? 0u : 0xFFFFFFFFu);
                 bool done = false;
-                while (fast) {
-                    // one trip without a branch but the two that end the loop: look, allocate the whole batch, publish it,
-                    // and do what the REPEAT does
-                    SEC_END(c, 3);
-                    const uint32_t snap = cfu_poll(c);
+                // one trip without a branch but the two that end the loop: look, allocate the whole batch, publish it,
+                // and do what the REPEAT does
+                auto trips = [&](auto ones_tag) __attribute__((always_inline)) {
+                    constexpr bool ONES = decltype(ones_tag)::value;
+                    for (;;) {
+                        SEC_END(c, 3);
+                        const uint32_t snap = cfu_poll(c);
 #ifdef VDC_PROFILE_SECTIONS
-                    { const uint32_t snap_ = snap; asm volatile("s_waitcnt lgkmcnt(0)" :: "v"(snap_) : "memory"); }
+                        { const uint32_t snap_ = snap; asm volatile("s_waitcnt lgkmcnt(0)" :: "v"(snap_) : "memory"); }
 #endif
-                    SEC_END(c, 1);
-                    const uint32_t used = st.uq_tail_rf - snap;
-                    const bool crowded = __ballot((c.lane < env.n_units && used > (uint32_t)(kUQ - kBatch)) || (c.lane == kPollAbort && snap != 0u)) != 0ull;
-                    const uint32_t occ32 = rf_get(snap, kPollMask) | busy32;
-                    // fewer free slots than the batch takes in all: nothing to try here (the general path waits)
-                    if (crowded || (uint32_t)__builtin_popcount(~occ32) < need0) break;
-                    uint32_t pack32, bits;
-                    const uint32_t got = cfu_alloc4(occ32, nsp32, n0, pack32, bits);
-                    SEC_END(c, 2);
-                    if (got != n0) {
-                        // not all of it fits right now: publish what did and let the general path wait for the rest
-                        if (got != 0u) {
-                            cfu_publish(c, d, lv, st, env, s.pc, sl, got, pack32, bits);
-                            s.pc += got;
+                        SEC_END(c, 1);
+                        // lane u: records unit u has not picked up yet; from kPollAbort on: minus the abort word
+                        const uint32_t used = st.uq_tail_rf - snap;
+                        const bool crowded = __ballot(used > room_need) != 0ull;
+                        const uint32_t occ32 = rf_get(snap, kPollMask) | busy32;
+                        // fewer free slots than the batch takes in all: nothing to try here (the general path waits)
+                        if (crowded || (uint32_t)__builtin_popcount(~occ32) < need0) break;
+                        uint32_t slot_vec, bits;
+                        if (ONES) {
+                            slot_vec = cfu_alloc_ones(c, ~occ32, n0, sl, bits);
+                        } else {
+                            uint32_t pack32;
+                            const uint32_t got = cfu_alloc4(occ32, nsp32, n0, pack32, bits);
+                            if (got != n0) {
+                                // not all of it fits right now: publish what did and let the general path wait for the rest
+                                if (got != 0u) {
+                                    cfu_publish(c, d, lv, st, env, s.pc, sl, got, pack32, bits);
+                                    s.pc += got;
+                                }
+                                break;
+                            }
+                            slot_vec = (pack32 >> jsh) & 0xFFu;
                         }
-                        break;
+                        SEC_END(c, 2);
+                        lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), bits);
+                        const u32x4 e = {slot_vec | d.e_lo, ((lv.tick + 1u) & 0xFFFFu) | d.e_hi, m2c_seq(lv.tick) & d.e_sel, 0u};
+                        lds_st128_lanes(send0, d.m2c_off + (lv.tick & (kM2C - 1)) * (uint32_t)sizeof(M2cEnt), e);
+                        u32x4 rec = {lv.g_lo, lv.g_hi, slot_vec | d.info, lv.tick};
+                        lds_st128_lanes(bm0, d.uq_off + (lv.pos & (kUQ - 1)) * (uint32_t)sizeof(UnitRec), rec);
+                        st.uq_tail_rf += add0;
+                        lds_st32_lanes(env.unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, st.uq_tail_rf);     // after the records
+                        st.ticket0 += dt0;
+                        st.ticket1 += dt1;
+                        // the REPEAT
+                        const uint64_t a2 = ((uint64_t)s.rf_lo | ((uint64_t)s.rf_hi << 32)) + ((uint64_t)da_lo | ((uint64_t)da_hi << 32));
+                        s.rf_lo = (uint32_t)a2; s.rf_hi = (uint32_t)(a2 >> 32);
+                        const uint64_t g2 = ((uint64_t)lv.g_lo | ((uint64_t)lv.g_hi << 32)) + ((uint64_t)dg_lo | ((uint64_t)dg_hi << 32));
+                        lv.g_lo = (uint32_t)g2; lv.g_hi = (uint32_t)(g2 >> 32);
+                        top_left--;
+                        if (top_left == 0u) { done = true; break; }
+                        lv.pos += lv.dpos;
+                        lv.tick += lv.dtick;
                     }
-                    const uint32_t slot_vec = (pack32 >> jsh) & 0xFFu;
-                    lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), bits);
-                    const u32x4 e = {slot_vec | d.e_lo, ((lv.tick + 1u) & 0xFFFFu) | d.e_hi, m2c_seq(lv.tick) & d.e_sel, 0u};
-                    lds_st128_lanes(send0, d.m2c_off + (lv.tick & (kM2C - 1)) * (uint32_t)sizeof(M2cEnt), e);
-                    u32x4 rec = {lv.g_lo, lv.g_hi, slot_vec | d.info, lv.tick};
-                    lds_st128_lanes(bm0, d.uq_off + (lv.pos & (kUQ - 1)) * (uint32_t)sizeof(UnitRec), rec);
-                    st.uq_tail_rf += add0;
-                    lds_st32_lanes(env.unit_lanes, c.ctl + CTL_OFF(uq_tail) + c.lane * 4u, st.uq_tail_rf);     // after the records
-                    st.ticket0 += dt0;
-                    st.ticket1 += dt1;
-                    // the REPEAT
-                    const uint64_t a2 = ((uint64_t)s.rf_lo | ((uint64_t)s.rf_hi << 32)) + ((uint64_t)da_lo | ((uint64_t)da_hi << 32));
-                    s.rf_lo = (uint32_t)a2; s.rf_hi = (uint32_t)(a2 >> 32);
-                    const uint64_t g2 = ((uint64_t)lv.g_lo | ((uint64_t)lv.g_hi << 32)) + ((uint64_t)dg_lo | ((uint64_t)dg_hi << 32));
-                    lv.g_lo = (uint32_t)g2; lv.g_hi = (uint32_t)(g2 >> 32);
-                    top_left--;
-                    if (top_left == 0u) { done = true; break; }
-                    lv.pos += lv.dpos;
-                    lv.tick += lv.dtick;
+                };
+                if (fast) {
+                    if (ones) trips(std::true_type{}); else trips(std::false_type{});
                 }
                 if (done) {
                     s.pc = top_start + n0 + 1u;          // past the REPEAT: the loop is done
@@ -1103,6 +1178,16 @@ DEV void cfu_main(Ctx &c) {
         nmax = nmax > (uint32_t)kBatch ? (uint32_t)kBatch : nmax;
         nmax = nmax > (uint32_t)kWin - k ? (uint32_t)kWin - k : nmax;
         nmax = nmax < 1u ? 1u : nmax;
+        // a run of uops of one slot each goes the wide way
+        uint32_t run1 = (uint32_t)__builtin_ctzll(~(d.ones >> k) | (1ull << 63));
+        run1 = run1 > (uint32_t)kBatchOnes ? (uint32_t)kBatchOnes : run1;
+        run1 = run1 > (uint32_t)kWin - k ? (uint32_t)kWin - k : run1;
+        if (run1 >= 2u) {
+            const uint32_t n1 = cfu_dispatch_ones(c, d, lv, st, env, s.pc, k, run1, (ctlw >> 16) & 7u);
+            if (n1 == 0u) { ok = false; break; }
+            s.pc += n1;
+            continue;
+        }
         const uint64_t nsp = (uint64_t)rf_get(d.nsp_lo, k) | ((uint64_t)rf_get(d.nsp_hi, k) << 32);   // slot counts of the batch
         const uint32_t n = cfu_dispatch(c, d, lv, st, env, s.pc, k, nmax, nsp, (ctlw >> 16) & 7u);
         if (n == 0u) { ok = false; break; }
