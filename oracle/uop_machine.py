@@ -418,6 +418,36 @@ class Machine:
         lpr = (u.imm >> 24) & 0xFFFF
         xspan = (u.imm >> 40) & 0x7F
         Kt = lpr * 4
+        rowspan = u.desc                                   # a compute uop names no descriptor: on a MATVEC the field counts row blocks
+        if rowspan >= 2:
+            # The uop's tile is the tiler's to choose (the listing fixes none): when K fits one tile, a MATVEC may cover
+            # `rowspan` row blocks of R rows that share one vector tile, each block fetched as an I/O block of its own.
+            # Its output region ([B][rowspan * R], one STORE for all the blocks) is allocated first and kept, then the
+            # vector tile, then the matrix tiles come and go, block j giving rows j R .. j R + R - 1; the vector tile goes
+            # back after the last block and the region goes back as produced.
+            if u.size != 1 or xspan >= 2:
+                raise ProgramError("matvec over several row blocks: one tile step per block, a vector tile of its own")
+            o = yield                                      # the output region
+            o_slot, o_n, o_rows, o_rb = o
+            if o_rows != B or o_rb > rowspan * R * 4:
+                raise ProgramError("matvec: output region does not match the uop")
+            b = yield                                      # the vector tile
+            b_slot, b_n, b_rows, b_rb = b
+            if b_rows != B:
+                raise ProgramError("matvec: tile geometry does not match the uop")
+            bt = core.region(b_slot, b_n).view(np.float32)[:B * Kt].reshape(B, Kt).astype(np.float64)
+            out = core.region(o_slot, o_n).view(np.float32)[:B * rowspan * R].reshape(B, rowspan * R)
+            for j in range(rowspan):
+                a = yield                                  # the matrix tile of block j
+                a_slot, a_n, a_rows, a_rb = a
+                if a_rows > R:
+                    raise ProgramError("matvec: tile geometry does not match the uop")
+                at = core.region(a_slot, a_n).view(np.float32)[:R * Kt].reshape(R, Kt).astype(np.float64)
+                out[:, j * R:(j + 1) * R] = (bt @ at.T).astype(np.float32)
+                self._c2m_push(core, v, KIND_FREE, a_slot, a_n)
+            self._c2m_push(core, v, KIND_FREE, b_slot, b_n)
+            self._c2m_push(core, v, KIND_DATA, o_slot, o_n)
+            return
         c = np.zeros((B, R), dtype=np.float64)            # the accumulators the uop keeps over all its tile steps
         if xspan >= 2:
             # The tile shape is the tiler's to choose (the listing fixes none): with one vector, a vector tile may hold

@@ -177,6 +177,89 @@ def test_a_vector_tile_over_several_steps_needs_one_vector_and_enough_rows():
         UM.Machine(w, sb, d, [M, X, Y], n_cores=1, slot_bytes=2048, n_slots=12).run()
 
 
+@pytest.mark.parametrize("row_off,K,B,R,Kt,slot,ncores,span", [
+    ([0, 200], 64, 1, 8, 64, 2048, 2, 8),            # dense, one vector: 25 blocks in groups of 8, the last of one block
+    ([0, 77], 32, 3, 4, 32, 1024, 3, 4),             # dense, three vectors, a row tail inside the last group
+    ([0, 40, 47, 170, 186], 128, 1, 16, 128, 8192, 2, 8),   # ragged: segments of 40, 7, 123 and 16 rows, each its own vector
+    ([0, 9, 300], 100, 1, 8, 32 * 4, 4096, 1, 2),    # K tail inside the only tile (K < Kt)
+])
+def test_matvec_over_several_row_blocks_equals_gemv(row_off, K, B, R, Kt, slot, ncores, span):
+    """MATVEC over `span` row blocks that share one vector tile (K fits a tile): the textbook product per segment, the bits
+    of the one-block-per-uop program (the same products in the same order), the same image under every schedule, a single
+    non-zero entry lands in its own row (a slip in the block's row offset inside the output region would move it), one
+    vector load and one store per group instead of per block, and no slot is left behind."""
+    rows, n_seg = row_off[-1], len(row_off) - 1
+    ragged = n_seg > 1
+    rng = np.random.default_rng(rows + K + span)
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((n_seg if ragged else B, K)).astype(np.float32)
+    Y = np.full((rows,) if ragged else (B, rows), np.nan, np.float32)
+    p = A.rowspan_matvec_program(row_off, K, K, B, R, Kt, slot, ncores, span)
+    m = _run(p, [M, X, Y], slot_bytes=slot, n_slots=14)
+    m.check_final()
+    if ragged:
+        Yr, Ya = gemv_ref.gemv_ragged(M, np.array(row_off, dtype=np.int64), X)
+    else:
+        Yr, Ya = gemv_ref.gemv_dense(M, X)
+    assert np.all(np.abs(Y.astype(np.float64) - Yr) <= 6e-8 * np.abs(Yr) + 1e-12 * Ya + 1e-45)
+    # one block per uop (span is only the program builder's grouping; a group of one block is the listing's uop)
+    Y1 = np.full_like(Y, np.nan)
+    p1 = A.Program(ncores)
+    g = 0
+    for s in range(n_seg):
+        for r in range(row_off[s], row_off[s + 1], R):
+            core, v = (g % (ncores * 2)) // 2, g % 2
+            rv = min(R, row_off[s + 1] - r)
+            p1.vmc(core).append(A.word(A.LOAD, A.F_SEND, vflow=2 * v, vcc=v, nslots=-(-R * Kt * 4 // slot), size=rv, imm=r * K * 4,
+                                       desc=p1.desc(0, R, K * 4, Kt * 4, K * 4)))
+            p1.vmc(core).append(A.word(A.LOAD, A.F_SEND, vflow=2 * v + 1, vcc=v, nslots=-(-B * Kt * 4 // slot), size=B,
+                                       imm=(s * K * 4 if ragged else 0), desc=p1.desc(1, B, K * 4, Kt * 4, K * 4)))
+            p1.vmc(core).append(A.word(A.STORE, A.F_SEND | A.F_RECV, vflow=4 + v, vcc=v, nslots=-(-B * R * 4 // slot), size=B, imm=r * 4,
+                                       desc=p1.desc(2, B, rv * 4, R * 4, (0 if ragged else rows) * 4)))
+            p1.vcc(core, v).append(A.word(A.MATVEC, size=1, imm=A.matvec_imm(B, R, Kt // 4)))
+            g += 1
+    _run(p1, [M, X, Y1], slot_bytes=slot, n_slots=14)
+    assert np.array_equal(Y, Y1)
+    for seed in range(10):
+        Y2 = np.full_like(Y, np.nan)
+        w, sb, d = p.finish()
+        UM.Machine(w, sb, d, [M, X, Y2], n_cores=ncores, slot_bytes=slot, n_slots=14).run("random", seed).check_final()
+        assert np.array_equal(Y, Y2)
+    for (i, j) in [(0, 0), (rows - 1, K - 1), (rows // 2, 1), (min(rows - 1, R + 1), K // 2)]:
+        M0 = np.zeros((rows, K), np.float32)
+        M0[i, j] = 2.0
+        X0 = np.tile(np.arange(1, K + 1, dtype=np.float32)[None, :], (X.shape[0], 1))
+        Y0 = np.full_like(Y, np.nan)
+        _run(p, [M0, X0, Y0], slot_bytes=slot, n_slots=14)
+        exp = np.zeros_like(Y0)
+        exp[..., i] = 2.0 * (j + 1)
+        assert np.array_equal(Y0, exp)
+    # per group: one vector load and one store
+    groups = sum(-(-(row_off[s + 1] - row_off[s]) // (span * R)) for s in range(n_seg))
+    blocks = sum(-(-(row_off[s + 1] - row_off[s]) // R) for s in range(n_seg))
+    loads_x = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 1)
+    loads_m = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 0)
+    stores = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.STORE)
+    assert loads_m == blocks and loads_x == groups and stores == groups
+
+
+def test_matvec_over_several_row_blocks_needs_one_step_and_a_fitting_region():
+    M = np.ones((32, 64), np.float32)
+    X = np.ones((1, 64), np.float32)
+    Y = np.zeros((1, 32), np.float32)
+    p = A.rowspan_matvec_program([0, 32], 64, 64, 1, 8, 64, 2048, 1, 4)
+    w, sb, d = p.finish()
+    bad = np.array(w, copy=True)
+    i = int(np.flatnonzero((bad[:, 0] & 0xFF) == A.MATVEC)[0])
+    bad[i, 1] = (bad[i, 1] & 0xFFFF0000) | 2             # two tile steps on a uop over several row blocks
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(bad, sb, d, [M, X, Y], n_cores=1, slot_bytes=2048, n_slots=14).run()
+    bad = np.array(w, copy=True)
+    bad[i, 3] = (bad[i, 3] & ~np.uint32(0xFF << 16)) | np.uint32(2 << 16)   # says two blocks: the region of four is too wide
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(bad, sb, d, [M, X, Y], n_cores=1, slot_bytes=2048, n_slots=14).run()
+
+
 def test_leading_dimension():
     M, X, Y = _inputs(24, 40, 2, seed=9, ld=52)
     p = A.dense_matvec_program(24, 40, 52, 2, 8, 16, 1024, 2)
