@@ -172,10 +172,12 @@ struct VccH {
     bool in_uop = false;
     uint32_t left = 0, B = 0, R = 0, lpr = 0;
     uint32_t xspan = 0, xstep = 0;   // MATVEC with a vector tile over several steps: steps per tile, steps done on the one held
+    uint32_t rowspan = 0;            // MATVEC over several row blocks: how many
     bool holds_x = false;
     int phase = 0;                // MATVEC: 0 expect a, 1 expect b, 2 expect out, 3 expect a vector tile over several steps; ROPE: 10 expect values, 11 expect angles, 12 expect out;
                                   // DROP: 20; FILL: 21; COPY: 22 expect in, 23 expect out;
-                                  // ATTN: 30 expect q, 31 expect K tile, 32 expect V tile, 33 expect out; ATTN_MERGE: 40 expect rows, 41 expect out
+                                  // ATTN: 30 expect q, 31 expect K tile, 32 expect V tile, 33 expect out; ATTN_MERGE: 40 expect rows, 41 expect out;
+                                  // MATVEC over several row blocks: 50 expect out, 51 expect the vector tile, 52 expect a matrix tile
     SentMsg q{};
     uint32_t chunks = 0;
     SentMsg a{}, b{};
@@ -419,9 +421,13 @@ struct Validator {
             v.xspan = matvec_xspan(f.imm);
             if (v.xspan >= 2 && (v.B != 1 || v.xspan > kMaxXspan || v.lpr > 64)) { fail("matvec: a vector tile over several steps needs B = 1, at most 8 steps and rows inside one wave"); return -1; }
             if (f.size < 1) { fail("matvec over zero tiles"); return -1; }
-            if ((uint64_t)v.B * v.R * 4 > (uint64_t)cfg.slot_bytes * cfg.n_slots) { fail("matvec output too large"); return -1; }
-            v.left = f.size;
-            v.phase = v.xspan >= 2 ? 3 : 0;
+            v.rowspan = matvec_rowspan(f);
+            if (v.rowspan >= 2 && (f.size != 1 || v.xspan >= 2 || v.lpr > 64 || v.rowspan > kMaxRowspan || v.B > kMaxRowspanB)) {
+                fail("matvec over several row blocks needs one tile step per block, a vector tile of its own, rows inside one wave, at most 16 blocks and at most 4 vectors"); return -1;
+            }
+            if ((uint64_t)v.B * v.R * std::max(1u, v.rowspan) * 4 > (uint64_t)cfg.slot_bytes * cfg.n_slots) { fail("matvec output too large"); return -1; }
+            v.left = v.rowspan >= 2 ? v.rowspan : f.size;
+            v.phase = v.rowspan >= 2 ? 50 : (v.xspan >= 2 ? 3 : 0);
             v.holds_x = false;
             v.in_uop = true;
             return 1;
@@ -429,6 +435,26 @@ struct Validator {
         if (v.m2c.empty()) return 0;
         SentMsg m = v.m2c.front();
         v.m2c.pop_front();
+        if (v.phase >= 50) {
+            // MATVEC over several row blocks: the output region first, then the vector tile, then one matrix tile per block
+            if (v.phase == 50) {
+                if (!m.is_store || m.rows != v.B || m.lds_pitch != v.rowspan * v.R * 4 || m.row_bytes > v.rowspan * v.R * 4) { fail("matvec: output region does not match the uop"); return -1; }
+                v.q = m; v.phase = 51;
+            } else if (v.phase == 51) {
+                if (m.is_store || m.box_rows != v.B || m.rows != v.B || m.lds_pitch != v.lpr * 16) { fail("matvec: vector tile does not match the uop"); return -1; }
+                v.b = m; v.phase = 52;
+            } else {
+                if (m.is_store || m.box_rows != v.R || m.lds_pitch != v.lpr * 16) { fail("matvec: matrix tile does not match the uop"); return -1; }
+                release(c, m);
+                if (--v.left == 0) {
+                    release(c, v.b);
+                    if (!store_returns(c, v.q)) return -1;
+                    v.in_uop = false;
+                    v.s.pc++;
+                }
+            }
+            return 1;
+        }
         if (v.phase >= 30) {
             const uint32_t row = v.lpr * 16, prow = row + 16;     // bytes of a key / value row, of a partial row
             switch (v.phase) {
@@ -619,6 +645,7 @@ struct Tiler {
     bool rope = false;     // fused form: O = M X stays in local memory and a ROPE uop turns it (tensor 3 = T) before the store
     bool x_span_ok = true; // one vector tile for several steps where the shape allows it
     uint32_t vcc_xspan = 0;
+    int rowspan = 0;       // K fits one tile: row blocks per MATVEC (0, 1: one, the uop of the listing)
     int k_unroll = 1;      // measured: 2 saves front-end work but makes every load unit alternate between two static records; slower
     bool k_skew = false;   // measured on cfg5: no gain (the vector tiles are not what the cores wait for)
 
@@ -854,7 +881,44 @@ struct Tiler {
         }
     }
 
+    // K fits one tile and there are many row blocks per compute core: a MATVEC covers up to `rowspan` consecutive blocks of
+    // a segment, which share the segment's vector tile and one STORE (the uop's tile is tall, its I/O blocks keep the
+    // configured size).  Per group: the STORE first (the compute core holds the output region throughout), the vector
+    // tile, the matrix tiles; groups alternate between the compute cores; every address is a literal.
+    void emit_core_rows(int core, const std::vector<Run> &runs) {
+        const int V = cfg.vcc_per_core;
+        auto &vm = vmc(core);
+        const uint32_t kbytes = (uint32_t)K * 4;
+        const uint32_t dm = desc(0, R, kbytes, Kt * 4, (uint64_t)ld * 4), dx = desc(1, B, kbytes, Kt * 4, (uint64_t)K * 4);
+        const uint32_t m_slots = slots_for((uint64_t)R * Kt * 4), x_slots = slots_for((uint64_t)B * Kt * 4);
+        const uint32_t m_flags = F_SEND | (nt ? F_NT : 0);
+        int g = 0;
+        for (const Run &r : runs) {
+            const int64_t blocks = r.n_full + (r.tail ? 1 : 0), rows_run = r.n_full * R + r.tail;
+            for (int64_t done = 0; done < blocks;) {
+                const int64_t nb = std::min<int64_t>(rowspan, blocks - done);
+                const int64_t rows_valid = std::min<int64_t>(nb * R, rows_run - done * R);
+                const int v = g++ % V;
+                const uint32_t dy = desc(2, B, (uint32_t)rows_valid * 4, (uint32_t)(nb * R * 4), (uint64_t)y_pitch * 4);
+                const uint32_t y_slots = slots_for((uint64_t)B * nb * R * 4);
+                if (nb >= 2) vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, r.y_off + done * R * 4, dy, 0));
+                if (nb >= 2) vm.push_back(encode(OP_LOAD, F_SEND, flow_x(v), v, 0, x_slots, B, 0, r.x_off, dx, 0));
+                for (int64_t j = 0; j < nb; j++) {
+                    const uint32_t rv = (uint32_t)std::min<int64_t>(R, rows_valid - j * R);
+                    vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, 0, m_slots, rv, 0, r.m_off + (done + j) * R * ld * 4, dm, 0));
+                }
+                if (nb < 2) {      // a single block: the uop of the listing (matrix tile, vector tile, then the output region)
+                    vm.push_back(encode(OP_LOAD, F_SEND, flow_x(v), v, 0, x_slots, B, 0, r.x_off, dx, 0));
+                    vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, r.y_off + done * R * 4, dy, 0));
+                }
+                vcc(core, v).push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, 1, 0, matvec_imm(B, R, Kt / 4), nb >= 2 ? (uint32_t)nb : 0u, 0));
+                done += nb;
+            }
+        }
+    }
+
     void emit_core(int core, const std::vector<Run> &runs) {
+        if (rowspan >= 2) return emit_core_rows(core, runs);
         const int V = cfg.vcc_per_core;
         int next_v = 0;
         for (const Run &r : runs) {
@@ -934,6 +998,30 @@ SplitPlan plan_split(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, 
     return sp;
 }
 
+// K fits one tile: with at least two groups of row blocks per compute core a MATVEC covers several blocks, as many as keep
+// its output region inside one slot, at most 8 (0: the form is not used).  nb: row blocks in all.
+int rowspan_for(const vdc_config &cfg, int64_t nb, int64_t K, int32_t B, int32_t R, int32_t Kt) {
+    if (K > Kt || Kt > 256 || B > (int32_t)kMaxRowspanB) return 0;
+    int64_t G = std::min<int64_t>(8, nb / ((int64_t)cfg.n_cores * cfg.vcc_per_core * 2));
+    G = std::min<int64_t>(G, (int64_t)cfg.slot_bytes / ((int64_t)B * R * 4));
+    return G >= 2 ? (int)G : 0;
+}
+
+// Which roles share a SIMD (vdc_program_set_placement) for a matvec program: measured per form of the graph.
+int matvec_placement(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, int32_t tile_bytes, bool rope) {
+    int R = 0, Kt = 0;
+    if (!choose_tile(cfg, K, B, tile_bytes, R, Kt)) return 0;
+    if (!rope && K <= Kt) {
+        // one tile per row block.  MATVECs over several row blocks: the compute waves set the pace (placement 2).  One
+        // tile, one MATVEC and one STORE per row block: the front end and the store unit do (placement 1), if there are
+        // enough blocks to matter
+        if (rowspan_for(cfg, (rows + R - 1) / R, K, B, R, Kt) >= 2) return 2;
+        return rows / R >= 8 * (int64_t)cfg.n_cores * cfg.vcc_per_core ? 1 : 0;
+    }
+    // long sweeps over K: the front end's loop is the busiest wave; it gets a SIMD with one compute wave only
+    return K / Kt >= 16 ? 2 : 0;
+}
+
 int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                  const int64_t *row_off, int32_t n_seg, std::vector<Word> &words, std::vector<uint32_t> &sb,
                  std::vector<Desc> &descs, bool rope = false) {
@@ -961,6 +1049,7 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
         nb = segs[0].n_blocks;
     }
     const SplitPlan sp = rope ? SplitPlan{} : plan_split(cfg, rows, K, B, R, Kt, row_off != nullptr);
+    if (!rope && sp.S == 1) t.rowspan = rowspan_for(cfg, nb, K, B, R, Kt);
     if (sp.S > 1) {
         // items in the order (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  Only items of the last
         // range wait, and only for items of earlier ranges, which earlier positions of the same or of earlier cores
@@ -1683,14 +1772,7 @@ static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t
             if (hipMalloc(&prog->d_workspace, ws.size() * 4) != hipSuccess) { vdc_program_destroy(prog); return VDC_ENOMEM; }
             if (hipMemcpy(prog->d_workspace, ws.data(), ws.size() * 4, hipMemcpyHostToDevice) != hipSuccess) { vdc_program_destroy(prog); return VDC_EDEVICE; }
         }
-        {
-            // one tile, one MATVEC and one STORE per row block: the front end and the store unit set the pace
-            int R = 0, Kt = 0;
-            if (!rope && choose_tile(ex->cfg, K, B, tile_bytes, R, Kt) && K <= Kt &&
-                rows / R >= 8 * (int64_t)ex->cfg.n_cores * ex->cfg.vcc_per_core) prog->placement = 1;   // and enough of them to matter
-            // long sweeps over K: the front end's loop is the busiest wave; it gets a SIMD with one compute wave only
-            else if (Kt > 0 && K / Kt >= 16) prog->placement = 2;
-        }
+        prog->placement = matvec_placement(ex->cfg, rows, K, B, tile_bytes, rope);
         cache_insert(ex, std::move(key), prog);
     }
     void *bases[4] = {(void *)M, (void *)X, (void *)Y, rope ? (void *)T : prog->d_workspace};
@@ -1747,11 +1829,7 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
         n.max_dep_id = val.max_dep;
         n.loaded_tensors = val.loaded_tensors;
         if (n.uses_dep && ((size_t)n.max_dep_id + 2) * 4 > kScratchDepBytes) return VDC_ETOOBIG;
-        {
-            int R = 0, Kt = 0;   // the same choice of role placement as vdc_matvec makes
-            if (choose_tile(c, K, B, tile_bytes, R, Kt) && K <= Kt && rows / R >= 8 * (int64_t)c.n_cores * c.vcc_per_core) n.placement = 1;
-            else if (Kt > 0 && K / Kt >= 16) n.placement = 2;
-        }
+        n.placement = matvec_placement(c, rows, K, B, tile_bytes, false);   // the same choice of role placement as vdc_matvec makes
         // the staging buffer may still be the source of the copy of an earlier call
         if (ex->stage_pending) HIP_TRY(hipEventSynchronize(ex->stage_done));
         ex->stage_pending = false;

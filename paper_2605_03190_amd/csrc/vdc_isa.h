@@ -118,6 +118,15 @@ inline int64_t matvec_imm(uint32_t B, uint32_t R, uint32_t lpr, uint32_t xspan =
     return (int64_t)B | ((int64_t)R << 8) | ((int64_t)lpr << 24) | ((int64_t)xspan << 40);
 }
 VDC_HD uint32_t matvec_xspan(int64_t imm) { return (uint32_t)(imm >> 40) & 0x7Fu; }
+// MATVEC over several row blocks (when K fits one tile): a compute uop names no descriptor, and on a MATVEC the field
+// [55:48] counts the row blocks the uop covers: 0 or 1 = the uop of the listing; n >= 2 (n <= kMaxRowspan, size = 1, no
+// xspan, lpr <= 64, B <= kMaxRowspanB) = n blocks of R rows that share one vector tile.  The uop pops its output region first and keeps it
+// ([B][n * R] fp32, row pitch n * R * 4: one STORE for all the blocks), then the vector tile, then n matrix tiles, block
+// j giving rows j * R ..; every matrix tile goes back when it is done, the vector tile after the last, then the region
+// as produced.
+constexpr uint32_t kMaxRowspan = 16;
+constexpr uint32_t kMaxRowspanB = 4;    // vectors a MATVEC over several row blocks takes at most
+VDC_HD uint32_t matvec_rowspan(const Fields &f) { return f.desc; }
 
 // ROPE imm: B [7:0], R [23:8]: the value tile, the tile of (cos, sin) pairs and the output region are all [B][R]
 // fp32 with a row pitch of R * 4 bytes; R even, B * R <= 1024

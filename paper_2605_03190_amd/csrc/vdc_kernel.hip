@@ -1827,6 +1827,20 @@ DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
     compiler_barrier();
 }
 
+// A produced region that was popped earlier and kept (its ticket already counted in vs.head) goes to the store unit: the
+// arrival protocol of vcc_done_with, with the payload the caller saved at the pop.
+DEV void vcc_push_kept(Ctx &c, VccState &vs, uint32_t payload) {
+    compiler_barrier();
+    const uint32_t v = c.unit;
+    const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
+    const uint32_t pos = vs.c2m_pos;
+    if (before & 1u)
+        lds_st64_lanes(1ull, c.ctl + CTL_OFF(c2m) + (v * kC2M + (pos & (kC2M - 1))) * 8u, (uint64_t)payload | ((uint64_t)(pos + 1u) << 32));
+    vs.c2m_pos = pos + 1u;
+    vs.group++;
+    compiler_barrier();
+}
+
 // Cross-lane reductions of the compute uops without a trip through the LDS crossbar: data-parallel-primitive (DPP)
 // operands move values inside a row of 16 lanes (and from the last lane of a row into the next rows), v_readlane takes
 // one value per row of 16 to the scalar side.
@@ -1862,6 +1876,19 @@ DEV float lane_group_sum(float x, uint32_t lpr) {
     return x;
 }
 
+
+// The same sum for a group size known when the code is compiled: one DPP step per level and nothing else.
+template <int LPR>
+DEV float lane_group_sum_fixed(float x) {
+    if (LPR >= 2) x += dpp_f32<kDppXor1>(x);
+    if (LPR >= 4) x += dpp_f32<kDppXor2>(x);
+    if (LPR == 8) x += dpp_f32_banks<kDppShl4, 0x5>(x, 0.0f) + dpp_f32_banks<kDppShr4, 0xA>(x, 0.0f);   // lane ^ 4
+    if (LPR >= 16) x += dpp_f32<kDppRor4>(x);
+    if (LPR >= 16) x += dpp_f32<kDppRor8>(x);
+    if (LPR >= 32) x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kDppBcast15, 0xA, 0xF, false));
+    if (LPR >= 64) x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), kDppBcast31, 0xC, 0xF, false));
+    return x;
+}
 
 DEV float dot4(f32x4 m, f32x4 x, float acc) {
     acc = __builtin_fmaf(m.x, x.x, acc);
@@ -1991,6 +2018,95 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
     return true;
 }
 
+// The matvec uop over `nrb` row blocks of R rows that share one vector tile (K fits one tile; a tile row lies inside one
+// wave).  The output region ([B][nrb * R] fp32) is popped first and kept, then the vector tile, which is read into
+// registers once; every matrix tile is multiplied, its row sums go straight into the region at the block's rows, and
+// the tile goes back; the vector tile goes back after the last block and the region as produced.
+template <int B, int NF>
+DEV bool matvec_rows_uop(Ctx &c, VccState &vs, uint32_t nrb, uint32_t R, uint32_t lpr) {
+    const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
+    const uint32_t t = vs.t, c4 = t & (lpr - 1u), pitch = lpr * 16u;
+    const uint32_t lsh = __builtin_ctz(lpr), rpp = 128u >> lsh;
+    Msg mo, mx, ma, unused;
+    if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;       // the output region
+    const uint32_t o_pay = vs.pay0;
+    vs.head += 1u;                                                     // popped; pushed as produced at the end
+    if (!vcc_pop_wait(c, vs, 1u, 0u, mx, unused)) return false;       // the vector tile
+    const uint32_t x_pay = vs.pay0;
+    vs.head += 1u;                                                     // popped; handed back after the last block
+    const uint32_t o_off = mo.slot << slot_shift, x_off = mx.slot << slot_shift;
+    f32x4 xv[B];
+#pragma unroll
+    for (int b = 0; b < B; b++) xv[b] = lds_ld128(x_off + (uint32_t)b * pitch + c4 * 16u);
+    const uint32_t opitch = nrb * R;                                   // values per row of the output region
+    const uint64_t last_lanes = __ballot(c4 == lpr - 1u);              // the lanes that hold a row's sum after the reduction
+    const uint32_t o_lane = o_off + (t >> lsh) * 4u;
+    // the row sums of one matrix tile (block j) go straight into the region
+    auto block = [&](const f32x4 (&m)[NF], uint32_t j) __attribute__((always_inline)) {
+        float r[NF][B];
+#pragma unroll
+        for (int i = 0; i < NF; i++)
+#pragma unroll
+            for (int b = 0; b < B; b++) r[i][b] = dot4(m[i], xv[b], 0.0f);
+        // the usual tile widths have the reduction without a select per level
+        if (lpr == 32u) {
+#pragma unroll
+            for (int i = 0; i < NF; i++)
+#pragma unroll
+                for (int b = 0; b < B; b++) r[i][b] = lane_group_sum_fixed<32>(r[i][b]);
+        } else if (lpr == 64u) {
+#pragma unroll
+            for (int i = 0; i < NF; i++)
+#pragma unroll
+                for (int b = 0; b < B; b++) r[i][b] = lane_group_sum_fixed<64>(r[i][b]);
+        } else if (lpr == 16u) {
+#pragma unroll
+            for (int i = 0; i < NF; i++)
+#pragma unroll
+                for (int b = 0; b < B; b++) r[i][b] = lane_group_sum_fixed<16>(r[i][b]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NF; i++)
+#pragma unroll
+                for (int b = 0; b < B; b++) r[i][b] = lane_group_sum(r[i][b], lpr);
+        }
+#pragma unroll
+        for (int i = 0; i < NF; i++)
+#pragma unroll
+            for (int b = 0; b < B; b++)
+                lds_st32_lanes(last_lanes, o_lane + ((uint32_t)b * opitch + j * R + (uint32_t)i * rpp) * 4u, __builtin_bit_cast(uint32_t, r[i][b]));
+    };
+    // two blocks at a time while two are left: one look at the queue and one hand-back for both
+    for (uint32_t j = 0; j < nrb; j += 2u) {
+        const uint32_t n = nrb - j >= 2u ? 2u : 1u;
+        Msg mb;
+        if (!vcc_pop_wait(c, vs, n, 0u, ma, mb)) return false;
+        const uint32_t a_off = ma.slot << slot_shift, b_off = (n == 2u ? mb.slot : ma.slot) << slot_shift;
+        f32x4 m0[NF], m1[NF];
+#pragma unroll
+        for (int i = 0; i < NF; i++) m0[i] = lds_ld128(a_off + ((uint32_t)i * 128u + t) * 16u);
+#pragma unroll
+        for (int i = 0; i < NF; i++) m1[i] = lds_ld128(b_off + ((uint32_t)i * 128u + t) * 16u);
+        block(m0, j);
+        if (n == 2u) block(m1, j + 1u);
+        vcc_done_with(c, vs, n, 0u);
+    }
+    vcc_return_kept(c, vs, x_pay);
+    lds_wait();
+    vcc_push_kept(c, vs, o_pay);
+    return true;
+}
+
+template <int B>
+DEV bool matvec_rows_dispatch_b(Ctx &c, VccState &vs, uint32_t nrb, uint32_t R, uint32_t lpr, uint32_t nf) {
+    if (nf == 1u) return matvec_rows_uop<B, 1>(c, vs, nrb, R, lpr);
+    if (nf == 2u) return matvec_rows_uop<B, 2>(c, vs, nrb, R, lpr);
+    if (nf == 4u) return matvec_rows_uop<B, 4>(c, vs, nrb, R, lpr);
+    if (nf == 8u) return matvec_rows_uop<B, 8>(c, vs, nrb, R, lpr);
+    raise_error(c, -3 /* VDC_EPROGRAM */, 0xC20u);
+    return false;
+}
+
 template <int B>
 DEV bool matvec_dispatch_b(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lpr, uint32_t nf, uint32_t j, uint32_t xspan) {
 #define VDC_MV(NF_, J_) \
@@ -2022,6 +2138,22 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     if (xspan >= 2u && (B != 1u || j != 0u || xspan > kMaxXspan)) {
         raise_error(c, -3 /* VDC_EPROGRAM */, 0xC10u);
         return false;
+    }
+    const uint32_t rowspan = matvec_rowspan(f);
+    if (rowspan >= 2u) {
+        if (j != 0u || f.size != 1u || xspan >= 2u || rowspan > kMaxRowspan || B > kMaxRowspanB) {
+            raise_error(c, -3 /* VDC_EPROGRAM */, 0xC30u);
+            return false;
+        }
+        switch (B) {
+            case 1: return matvec_rows_dispatch_b<1>(c, vs, rowspan, R, lpr, nf);
+            case 2: return matvec_rows_dispatch_b<2>(c, vs, rowspan, R, lpr, nf);
+            case 3: return matvec_rows_dispatch_b<3>(c, vs, rowspan, R, lpr, nf);
+            case 4: return matvec_rows_dispatch_b<4>(c, vs, rowspan, R, lpr, nf);
+            default:
+                raise_error(c, -3 /* VDC_EPROGRAM */, 0xD00u);
+                return false;
+        }
     }
     switch (B) {
         case 1: return matvec_dispatch_b<1>(c, vs, f.size, R, lpr, nf, j, xspan);

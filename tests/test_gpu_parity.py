@@ -56,7 +56,11 @@ DENSE_CASES = [
     (1000, 1000, 1000, 1, 4096),       # row and K tails everywhere
     (517, 2052, 2060, 3, 8192),        # leading dimension, odd sizes, B = 3
     (2048, 4096, 4096, 8, 16384),
-    (70000, 128, 128, 2, 8192),        # many row blocks per core, one K tile
+    (70000, 128, 128, 2, 8192),        # many row blocks per core, one K tile: MATVECs over several row blocks
+    (131077, 64, 72, 3, 4096),         # the same form with a leading dimension, a row tail and three vectors
+    (200003, 256, 256, 1, 8192),       # ... with tile rows as wide as a wave
+    (100001, 128, 128, 4, 8192),       # ... with the most vectors the form takes
+    (100001, 128, 128, 5, 8192),       # one vector more: a MATVEC per row block
     (3, 8, 8, 1, 2048),                # less than one tile
     (4096, 512, 512, 5, 2048),
     (1024, 8192, 8192, 7, 16384),
@@ -779,6 +783,58 @@ def test_ragged_batch(ex):
     ex.check()
     Yr, Ya = gemv_ref.gemv_ragged(M, row_off, X)
     _check(dY.cpu().numpy(), Yr, Ya, "ragged")
+
+
+def test_matvec_over_several_row_blocks_traces_and_ragged_result():
+    """K fits one tile and there are many row blocks per compute core: the tiler's MATVECs cover several row blocks.  On a
+    small executor the traces of every unit are bit-exact against the interpreter running the same graph (dense, three
+    vectors, a row tail); on the full executor a ragged batch with empty, tiny and long segments matches the fp64 GEMV, with
+    one and with two store units."""
+    rng = np.random.default_rng(11)
+    rows, K, B, T = 3001, 64, 3, 4096
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    with vdc.Executor(n_cores=6, slot_bytes=4096) as ex:
+        nc, ns = ex.cfg.n_cores, ex.cfg.n_slots
+        words, sb, descs = ex.matvec_program(rows, K, K, B, T)
+        spans = {(int(x[3]) >> 16) & 0xFF for x in words[(words[:, 0] & 0xFF) == A.MATVEC]}
+        assert max(spans) >= 2
+        prog = ex.program_create(words, sb, descs, [M.nbytes, X.nbytes, B * rows * 4])
+        dY = torch.full((B, rows), float("nan"), device="cuda")
+        cap = 4096
+        trace, count = ex.run(prog, [_dev(M), _dev(X), dY], trace_cap=cap)
+        ex.check()
+        trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+    Yo = np.full((B, rows), np.nan, np.float32)
+    m = UM.Machine(words, sb, descs, [M, X, Yo], n_cores=nc, slot_bytes=4096, n_slots=ns).run()
+    for core in range(nc):
+        s = core * 3
+        exp = [(pc, op | (d << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, d, off, n) in m.trace_vmc[core]]
+        assert count[s] == len(exp) <= cap
+        assert [tuple(int(x) for x in r) for r in trace[s, :len(exp)]] == exp
+        for v in range(2):
+            exp = [(pc, op | (n << 16), imm & 0xFFFFFFFF, imm >> 32) for (pc, op, n, imm) in m.trace_vcc[core][v]]
+            assert count[s + 1 + v] == len(exp)
+            assert [tuple(int(x) for x in r) for r in trace[s + 1 + v, :len(exp)]] == exp
+    Yr, Ya = gemv_ref.gemv_dense(M, X)
+    _check(dY.cpu().numpy(), Yr, Ya, "several row blocks per uop")
+    _check(Yo, Yr, Ya, "several row blocks per uop (interpreter)")
+    K = 128
+    lengths = [0, 5, 70000, 16, 1, 33000, 17, 0, 250, 9000]
+    row_off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    rows = int(row_off[-1])
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((len(lengths), K)).astype(np.float32)
+    Yr, Ya = gemv_ref.gemv_ragged(M, row_off, X)
+    dM, dX = _dev(M), _dev(X)
+    for n_stu in (1, 2):
+        with vdc.Executor(n_stu=n_stu) as ex:
+            words, _, _ = ex.matvec_program(rows, K, K, 1, 8192, row_off=row_off)
+            assert max((int(x[3]) >> 16) & 0xFF for x in words[(words[:, 0] & 0xFF) == A.MATVEC]) >= 2
+            dY = torch.full((rows,), float("nan"), device="cuda")
+            ex.matvec_ragged(dM, row_off, dX, dY, 8192)
+            ex.check()
+            _check(dY.cpu().numpy(), Yr, Ya, "ragged, several row blocks per uop, %d store unit(s)" % n_stu)
 
 
 def test_dep_id_chain_between_two_memory_cores():

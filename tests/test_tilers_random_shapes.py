@@ -112,6 +112,44 @@ def test_ragged_matvec_programs(lengths, k4, tile, ncores, seed):
 
 
 @settings(**COMMON)
+@given(lengths=st.lists(st.integers(1, 400), min_size=1, max_size=6), k4=st.integers(1, 32), B=st.integers(1, 4),
+       tile=st.sampled_from([2048, 4096]), ncores=st.integers(1, 2), n_stu=st.sampled_from([1, 2]), seed=st.integers(0, 1000))
+def test_short_k_programs_cover_several_row_blocks_per_uop(lengths, k4, B, tile, ncores, n_stu, seed):
+    """K fits one tile and there are many row blocks per compute core: the tiler lets a MATVEC cover several row blocks
+    that share a vector tile and a STORE (the count stands in the uop's descriptor field).  Dense (the lengths added up,
+    B vectors) and ragged (one vector per segment): validated, run under a random schedule, equal to the GEMV, and with
+    fewer stores and vector loads than row blocks wherever the form is used."""
+    K = 4 * k4
+    rng = np.random.default_rng(seed)
+    for ragged in (False, True):
+        ro = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64) if ragged else np.array([0, sum(lengths)], np.int64)
+        rows, Bv = int(ro[-1]), (1 if ragged else B)
+        M = rng.standard_normal((rows, K)).astype(np.float32)
+        X = rng.standard_normal((len(ro) - 1 if ragged else Bv, K)).astype(np.float32)
+        with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=2048, n_slots=14, n_stu=n_stu) as ex:
+            try:
+                w, sb, d = ex.matvec_program(rows, K, K, Bv, tile, row_off=ro if ragged else None)
+            except vdc.VdcError:
+                continue
+            ws = ex.matvec_workspace(rows, K, K, Bv, tile) if not ragged else np.zeros(0, np.float32)
+            rc, msg = ex.program_validate(w, sb, d, [M.nbytes, X.nbytes, Bv * rows * 4] + ([ws.nbytes] if ws.size else []))
+            assert rc == vdc.VDC_OK, msg
+        Y = np.full((rows,) if ragged else (Bv, rows), np.nan, np.float32)
+        m = UM.Machine(w, sb, d, [M, X, Y] + ([ws] if ws.size else []), n_cores=ncores, slot_bytes=2048, n_slots=14, n_dep_ids=1024, n_stu=n_stu)
+        m.run("random", seed)
+        m.check_final()
+        Yr, Ya = gemv_ref.gemv_ragged(M, ro, X) if ragged else gemv_ref.gemv_dense(M, X)
+        assert np.all(np.abs(Y - Yr) <= 2e-6 * Ya + 1e-30)
+        mv = w[(w[:, 0] & 0xFF) == 16]
+        spans = [(int(x[3]) >> 16) & 0xFF for x in mv]
+        if max(spans) >= 2:
+            loads_x = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 1)
+            loads_m = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 0)
+            stores = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.STORE)
+            assert loads_x == len(mv) and stores == len(mv) and loads_m == sum(max(1, x) for x in spans) and len(mv) < loads_m
+
+
+@settings(**COMMON)
 @given(lengths=st.lists(st.integers(1, 200), min_size=1, max_size=7), tile=st.sampled_from([4096, 8192, 16384]),
        ncores=st.integers(1, 4), seed=st.integers(0, 1000), d=st.sampled_from([64, 128]))
 def test_attention_programs(lengths, tile, ncores, seed, d):
