@@ -61,7 +61,11 @@ typedef struct {
     int32_t n_dep_ids;      /* size of the global depId table; default 4096                           */
     int32_t watchdog_spins; /* polls before a waiting unit reports VDC_EDEADLOCK; default 1<<22       */
     int32_t tile_rows;      /* tuning knob of the matvec tiler: rows per matrix tile; 0 => automatic  */
-    int32_t reserved[5];    /* must be zero                                                           */
+    int32_t issue_batch;    /* memory uops the front end dispatches at once at most, 1..8; 0 => 8.  For   */
+                            /* measuring the issue path (Section 6.3); no effect on results              */
+    int32_t issue_flags;    /* bit 0: the front end does not replay loop bodies, every trip is decoded   */
+                            /* and dispatched through its general path (same purpose); other bits zero   */
+    int32_t reserved[3];    /* must be zero                                                           */
 } vdc_config;
 
 /* Create the executor on cfg->device (Section 4.3: the cores every run launches once as a persistent

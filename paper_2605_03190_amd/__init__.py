@@ -26,7 +26,7 @@ class VdcError(RuntimeError):
 class vdc_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "device", "n_cores", "vcc_per_core", "threads_per_eu", "slot_bytes", "n_slots", "n_ldu", "n_stu",
-        "n_dep_ids", "watchdog_spins", "tile_rows")] + [("reserved", ctypes.c_int32 * 5)]
+        "n_dep_ids", "watchdog_spins", "tile_rows", "issue_batch", "issue_flags")] + [("reserved", ctypes.c_int32 * 3)]
 
 
 _lib = None

@@ -1297,16 +1297,18 @@ int build_stream(const vdc_config &cfg, int32_t mode, int64_t bytes, uint32_t va
             s0[v] = u * (NBk / U) + std::min(u, NBk % U);
         }
         const int64_t common = V == 2 ? std::min(n[0], n[1]) : n[0];
-        const int64_t trips = common / 2;
+        // blocks per compute core and trip: eight memory uops per trip, as many as the front end dispatches at once
+        const int64_t J = (mode == 2 ? 4 : 8) / V;
+        const int64_t trips = common / J;
         if (trips > 0xFFFFFFFFll) return VDC_EINVAL;
         if (trips > 0) {
             vm.push_back(encode(OP_SET, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0));
             vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, trips, 0, 0));
-            for (int j = 0; j < 2; j++)
+            for (int j = 0; j < (int)J; j++)
                 for (int v = 0; v < V; v++) emit_block(vm, v, j, true, (s0[v] + j) * tile_bytes, d_in, d_out, nslots, box_rows);
-            vm.push_back(encode(OP_REPEAT, 0, 0, 0, 0, 0, 0, 0, 2ll * tile_bytes, 0, 0));
+            vm.push_back(encode(OP_REPEAT, 0, 0, 0, 0, 0, 0, 0, J * tile_bytes, 0, 0));
         }
-        for (int64_t i = 2 * trips; i < std::max(n[0], n[1]); i++)
+        for (int64_t i = J * trips; i < std::max(n[0], n[1]); i++)
             for (int v = 0; v < V; v++)
                 if (i < n[v]) emit_block(vm, v, (int)(i & 1), false, (s0[v] + i) * tile_bytes, d_in, d_out, nslots, box_rows);
         for (int v = 0; v < V; v++) emit_uop(t.vcc(c, v), n[v], (uint32_t)tile_bytes / 16u);
@@ -1445,8 +1447,10 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
 }
 
 int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
-    for (int i = 0; i < 5; i++)
+    for (int i = 0; i < 3; i++)
         if (c.reserved[i]) return VDC_EINVAL;
+    if (c.issue_batch < 0 || c.issue_batch > 8 || (c.issue_flags & ~1)) return VDC_EINVAL;
+    if (c.issue_batch == 0) c.issue_batch = 8;
     if (c.n_cores == 0) c.n_cores = cu_count;
     if (c.vcc_per_core == 0) c.vcc_per_core = 2;
     if (c.threads_per_eu == 0) c.threads_per_eu = 128;
@@ -1498,6 +1502,8 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     p.n_stu = ex->cfg.n_stu;
     p.V = ex->cfg.vcc_per_core;
     p.watchdog = (uint32_t)ex->cfg.watchdog_spins;
+    p.issue_batch = (uint32_t)ex->cfg.issue_batch;
+    p.no_replay = (uint32_t)(ex->cfg.issue_flags & 1);
     // Wave w of a workgroup runs on SIMD w % 4.  Placement 0 takes the roles in wave order (front end, load units, store
     // unit, compute waves): with the default ten waves every SIMD then holds one compute wave.  Placement 1, for graphs
     // bound by the front end and the store unit, keeps those two away from the compute waves: SIMD 0 = front end + load
@@ -1798,7 +1804,7 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
     HIP_TRY(hipSetDevice(dev));
     const vdc_config &c = ex->cfg;
     std::vector<int64_t> key{PK_MATVEC, rows, K, ld, B, tile_bytes, c.n_cores, c.vcc_per_core, c.slot_bytes, c.n_slots, c.n_ldu, c.n_stu,
-                             c.n_dep_ids, c.tile_rows};
+                             c.n_dep_ids, c.tile_rows, c.issue_batch, c.issue_flags};
     ScratchImage &img = g_scratch_image[dev];
     auto up = [](size_t x) { return (x + 255u) & ~(size_t)255u; };
     if (img.key != key) {

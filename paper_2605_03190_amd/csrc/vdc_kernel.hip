@@ -1064,7 +1064,7 @@ DEV void cfu_main(Ctx &c) {
                     // a body that is nothing but one batch of memory uops is replayed below without decoding anything
                     const uint32_t n0 = k - sl;
                     const uint64_t body0 = (1ull << n0) - 1ull;
-                    replay = n0 >= 1u && (~(d.mem >> sl) & body0) == 0ull &&
+                    replay = n0 >= 1u && n0 <= p->issue_batch && p->no_replay == 0u && (~(d.mem >> sl) & body0) == 0ull &&
                              (n0 <= (uint32_t)kBatch || (n0 <= (uint32_t)kBatchOnes && (~(d.ones >> sl) & body0) == 0ull));
                 }
             }
@@ -1177,11 +1177,13 @@ DEV void cfu_main(Ctx &c) {
         uint32_t nmax = (uint32_t)__builtin_ctzll(not_mem | (1ull << 63));
         nmax = nmax > (uint32_t)kBatch ? (uint32_t)kBatch : nmax;
         nmax = nmax > (uint32_t)kWin - k ? (uint32_t)kWin - k : nmax;
+        nmax = nmax > p->issue_batch ? p->issue_batch : nmax;
         nmax = nmax < 1u ? 1u : nmax;
         // a run of uops of one slot each goes the wide way
         uint32_t run1 = (uint32_t)__builtin_ctzll(~(d.ones >> k) | (1ull << 63));
         run1 = run1 > (uint32_t)kBatchOnes ? (uint32_t)kBatchOnes : run1;
         run1 = run1 > (uint32_t)kWin - k ? (uint32_t)kWin - k : run1;
+        run1 = run1 > p->issue_batch ? p->issue_batch : run1;
         if (run1 >= 2u) {
             const uint32_t n1 = cfu_dispatch_ones(c, d, lv, st, env, s.pc, k, run1, (ctlw >> 16) & 7u);
             if (n1 == 0u) { ok = false; break; }
