@@ -39,7 +39,9 @@ enum {
     VDC_EDEVICE = -4,   /* a HIP call failed                                                       */
     VDC_EDEADLOCK = -5, /* the device watchdog fired: some unit waited longer than the spin limit  */
     VDC_ELEAK = -6,     /* a run ended with local-memory slots still allocated                      */
-    VDC_ETOOBIG = -7    /* vdc_matvec_noalloc: program + workspace exceed the static scratch        */
+    VDC_ETOOBIG = -7,   /* vdc_matvec_noalloc: program + workspace exceed the static scratch        */
+    VDC_ESTATE = -8,    /* the call does not fit the executor's state (vdc_resident_*)              */
+    VDC_ETIMEOUT = -9   /* vdc_resident_wait: the graph was not complete within the time given      */
 };
 
 typedef struct vdc_executor vdc_executor; /* opaque, library-owned */
@@ -136,6 +138,39 @@ int vdc_run_traced(vdc_executor *ex, const vdc_program *prog, void *const *tenso
  * error a core raised (VDC_EDEADLOCK, VDC_ELEAK, VDC_EPROGRAM for a geometry the device rejected).
  * info (host, may be NULL) receives 4 words: core, role, stream pc, detail.  Clears the status. */
 int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info);
+
+/* ---- the resident form (Section 4.3: the virtual cores are launched once as a persistent kernel, and the runtime streams
+ * new uop graphs to them as requests arrive) ----
+ *
+ * vdc_resident_start launches the cores on a stream of the library's own and leaves them up: between graphs they watch a
+ * mailbox in pinned host memory.  vdc_resident_submit posts one graph (a program and its tensors, as for vdc_run) and
+ * returns its ticket (1, 2, ...) without waiting; graphs run one after the other, in the order posted, each complete on
+ * every core before the next starts, and one graph's stores are visible to the next: the results are those of as many
+ * vdc_run calls on one stream, without a launch per graph.  At most 8 posted graphs may be incomplete (a further
+ * submit waits for room).  vdc_resident_wait returns when graph `ticket` is complete: VDC_OK, the error the graph ended
+ * in (VDC_EDEADLOCK, VDC_ELEAK, VDC_EPROGRAM; info as for vdc_sync_status), VDC_ETIMEOUT after timeout_ms, or
+ * VDC_ESTATE when the cores have left without running it.  vdc_resident_stop tells the cores to leave, waits until they
+ * have, and returns the executor to its ordinary state.
+ * The cores never wait without a bound: when no graph arrives for idle_ms milliseconds (0: 1000; the bound is counted in
+ * looks at the mailbox, so the time is approximate) they leave by themselves, as they do after a graph that ended in an
+ * error; a caller that dies therefore leaves no kernel behind.  vdc_resident_state returns 0 (not started), 1 (up) or
+ * 2 (the cores have left, or are leaving; vdc_resident_stop is still to be called) and the number of completed graphs.
+ * While the cores are resident they hold every compute unit: vdc_run, the operators below, vdc_program_create and
+ * vdc_program_destroy return VDC_ESTATE (programs are created before vdc_resident_start; a graph is a program plus
+ * the tensors it is posted with, so one program serves any number of requests), other GPU work of the process that
+ * needs a compute unit's whole local memory waits for them, and so may calls that allocate or free device or pinned
+ * memory: buffers are allocated beforehand.
+ * The caller's own streams are not involved: it waits with vdc_resident_wait before it touches a graph's results.  While
+ * the cores are up, other GPU work of the process may wait until they have left: anything on the legacy default stream
+ * (a blocking hipMemcpy included), and kernels, the runtime's small copies among them, that the runtime queues behind the
+ * resident grid.  Results are therefore read after vdc_resident_stop, or a graph writes them where the host can see
+ * them (an output tensor in pinned, mapped host memory: the cores' last stores are visible before the ticket is). */
+int vdc_resident_start(vdc_executor *ex, int32_t idle_ms);
+int vdc_resident_submit(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors,
+                        uint32_t *ticket);
+int vdc_resident_wait(vdc_executor *ex, uint32_t ticket, int32_t timeout_ms, uint32_t *info);
+int vdc_resident_state(vdc_executor *ex, uint32_t *completed);
+int vdc_resident_stop(vdc_executor *ex);
 
 /* ---- high level: the matvec operator (Section 3, O = M @ N, the matrix cut into tiles along its row dimension) ----
  *

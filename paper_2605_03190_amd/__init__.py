@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvdcores.so")
 
 VDC_OK, VDC_EINVAL, VDC_ENOMEM, VDC_EPROGRAM, VDC_EDEVICE, VDC_EDEADLOCK, VDC_ELEAK, VDC_ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7
+VDC_ESTATE, VDC_ETIMEOUT = -8, -9
 NOALLOC_SCRATCH_BYTES = 256 * 1024
 
 
@@ -53,6 +54,11 @@ def lib():
             "vdc_run": [vp, vp, vp, i32, vp],
             "vdc_run_traced": [vp, vp, vp, i32, vp, vp, i32, vp],
             "vdc_sync_status": [vp, vp, vp],
+            "vdc_resident_start": [vp, i32],
+            "vdc_resident_submit": [vp, vp, vp, i32, ctypes.POINTER(ctypes.c_uint32)],
+            "vdc_resident_wait": [vp, ctypes.c_uint32, i32, vp],
+            "vdc_resident_state": [vp, ctypes.POINTER(ctypes.c_uint32)],
+            "vdc_resident_stop": [vp],
             "vdc_matvec": [vp, vp, i64, i64, i64, vp, vp, i32, i32, vp],
             "vdc_matvec_noalloc": [vp, vp, i64, i64, i64, vp, vp, i32, i32, vp],
             "vdc_matvec_ragged": [vp, vp, vp, i32, i64, vp, vp, i32, vp],
@@ -84,7 +90,8 @@ def lib():
 
 
 EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", "vdc_program_validate",
-           "vdc_program_destroy", "vdc_program_set_placement", "vdc_run", "vdc_run_traced", "vdc_sync_status", "vdc_matvec", "vdc_matvec_noalloc", "vdc_matvec_ragged",
+           "vdc_program_destroy", "vdc_program_set_placement", "vdc_run", "vdc_run_traced", "vdc_sync_status",
+           "vdc_resident_start", "vdc_resident_submit", "vdc_resident_wait", "vdc_resident_state", "vdc_resident_stop", "vdc_matvec", "vdc_matvec_noalloc", "vdc_matvec_ragged",
            "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_matvec_chain", "vdc_matvec_chain_program", "vdc_attn_decode", "vdc_attn_decode_program",
            "vdc_stream", "vdc_raw_stream",
            "vdc_stream_program", "vdc_debug_alloc", "vdc_graph_lower", "vdc_strerror"]
@@ -193,6 +200,31 @@ class Executor:
             return trace, count
         _check(lib().vdc_run(self.handle, prog.handle, bases, len(tensors), _stream_ptr(stream)), "vdc_run")
         return None
+
+    # ---- the resident form ----------------------------------------------------------------------
+    def resident_start(self, idle_ms=0):
+        _check(lib().vdc_resident_start(self.handle, idle_ms), "vdc_resident_start")
+
+    def resident_submit(self, prog, tensors):
+        """Posts one graph; returns its ticket."""
+        bases = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+        ticket = ctypes.c_uint32(0)
+        _check(lib().vdc_resident_submit(self.handle, prog.handle, bases, len(tensors), ctypes.byref(ticket)), "vdc_resident_submit")
+        return ticket.value
+
+    def resident_wait(self, ticket, timeout_ms=10000):
+        """Returns (code, info[4])."""
+        info = (ctypes.c_uint32 * 4)()
+        rc = lib().vdc_resident_wait(self.handle, ticket, timeout_ms, info)
+        return rc, list(info)
+
+    def resident_state(self):
+        """Returns (state, completed): state 0 not started, 1 up, 2 the cores have left."""
+        done = ctypes.c_uint32(0)
+        return lib().vdc_resident_state(self.handle, ctypes.byref(done)), done.value
+
+    def resident_stop(self):
+        _check(lib().vdc_resident_stop(self.handle), "vdc_resident_stop")
 
     def sync_status(self, stream=None):
         """Waits for the stream; returns (code, info[4])."""

@@ -11,6 +11,8 @@
 #include <memory>
 #include <new>
 #include <string>
+#include <chrono>
+#include <thread>
 #include <vector>
 
 #include "../../include/vdcores.h"
@@ -67,6 +69,13 @@ struct vdc_executor {
     unsigned char *h_stage = nullptr;
     hipEvent_t stage_done = nullptr;
     bool stage_pending = false;
+    // the resident form (vdc_resident_*): the mailbox in pinned host memory, the device words behind it, the stream the
+    // grid runs on, graphs posted so far
+    volatile uint32_t *r_mailbox = nullptr;
+    uint32_t *r_dev = nullptr;
+    hipStream_t r_stream = nullptr;
+    uint32_t r_posted = 0;
+    bool r_up = false;             // vdc_resident_start has been called and vdc_resident_stop has not
 };
 
 // What the static scratch array of each device holds right now (it is shared by every executor on that device and keeps
@@ -1475,11 +1484,12 @@ int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     return VDC_OK;
 }
 
-int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, uint32_t *trace,
-                uint32_t *trace_count, int32_t trace_cap, hipStream_t stream, uint32_t *dep_table = nullptr, uint32_t *finished = nullptr) {
+// The kernel parameters of one run of `prog` on `tensor_bases`, and the waves per core it wants.
+int prepare_params(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, uint32_t *trace,
+                   uint32_t *trace_count, int32_t trace_cap, uint32_t *dep_table, uint32_t *finished, KParams &p, uint32_t &n_waves) {
     if (!ex || !prog || prog->ex != ex || !tensor_bases || n_tensors != prog->n_tensors) return VDC_EINVAL;
     if (ex->cfg.device == -1) return VDC_EINVAL;
-    KParams p{};
+    p = KParams{};
     p.words = prog->d_words;
     p.stream_begin = prog->d_stream_begin;
     p.descs = prog->d_descs;
@@ -1509,7 +1519,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     // bound by the front end and the store unit, keeps those two away from the compute waves: SIMD 0 = front end + load
     // units 0, 1; SIMD 1 = store unit + load units 2, 3; SIMDs 2 and 3 = one wave of each compute core.
     p.wave_roles = 0xFEDCBA9876543210ull;
-    uint32_t n_waves = 1u + p.n_ldu + p.n_stu + 2u * p.V;
+    n_waves = 1u + p.n_ldu + p.n_stu + 2u * p.V;
     constexpr int kForcePlacement = -1;      // experiments only
     const int placement = kForcePlacement >= 0 ? kForcePlacement : prog->placement;
     const bool default_units = ex->cfg.n_ldu == 4 && ex->cfg.n_stu == 1 && ex->cfg.vcc_per_core == 2;
@@ -1532,13 +1542,36 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     if (!ex->d_prof && hipMalloc(&ex->d_prof, 8 * (16 * 8 * (size_t)ex->cfg.n_cores + 2 * 65536 + 8)) != hipSuccess) return VDC_ENOMEM;
     p.prof = ex->d_prof;
 #endif
-    HIP_TRY(hipSetDevice(ex->cfg.device));
     // the depId counters are zero between runs: the core that finishes last clears the ones its program used
     p.finished = finished ? finished : ex->d_status + ST_WORDS + 3;
     p.n_dep_used = prog->uses_dep ? prog->max_dep_id + 1 : 0;
+    return VDC_OK;
+}
+
+int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, uint32_t *trace,
+                uint32_t *trace_count, int32_t trace_cap, hipStream_t stream, uint32_t *dep_table = nullptr, uint32_t *finished = nullptr) {
+    KParams p;
+    uint32_t n_waves = 0;
+    int rc = prepare_params(ex, prog, tensor_bases, n_tensors, trace, trace_count, trace_cap, dep_table, finished, p, n_waves);
+    if (rc != VDC_OK) return rc;
+    if (ex->r_up) return VDC_ESTATE;      // the resident grid holds every compute unit: a launch would only wait for it
+    HIP_TRY(hipSetDevice(ex->cfg.device));
     if (trace_count) HIP_TRY(launch_clear(trace_count, (uint32_t)(ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core)), stream));
     HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, n_waves, stream));
     return VDC_OK;
+}
+
+// Stop the resident grid, wait for it to leave and give its resources back.
+int resident_down(vdc_executor *ex) {
+    if (!ex->r_up) return VDC_OK;
+    __atomic_store_n(&ex->r_mailbox[MB_STOP], 1u, __ATOMIC_RELEASE);
+    hipError_t e = hipStreamSynchronize(ex->r_stream);      // every wait of the grid is bounded: this returns
+    (void)hipStreamDestroy(ex->r_stream);
+    (void)hipFree(ex->r_dev);
+    (void)hipHostFree((void *)ex->r_mailbox);
+    ex->r_stream = nullptr; ex->r_dev = nullptr; ex->r_mailbox = nullptr;
+    ex->r_up = false;
+    return e == hipSuccess ? VDC_OK : VDC_EDEVICE;
 }
 
 }  // namespace
@@ -1616,6 +1649,7 @@ int vdc_destroy(vdc_executor *ex) {
         return VDC_OK;
     }
     (void)hipSetDevice(ex->cfg.device);
+    (void)resident_down(ex);
     (void)hipDeviceSynchronize();
     for (vdc_program *p : ex->programs) {
         (void)hipFree(p->d_words);
@@ -1646,6 +1680,7 @@ int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const
         !tensor_bytes || n_tensors < 0 || n_tensors > kMaxTensors || !out)
         return VDC_EINVAL;
     if (ex->cfg.device == -1) return VDC_EINVAL;
+    if (ex->r_up) return VDC_ESTATE;      // it allocates device memory, which may wait for the resident grid to leave
     const int n_streams = ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core);
     if (stream_begin[0] != 0 || (int64_t)stream_begin[n_streams] != n_uops) return VDC_EPROGRAM;
     Validator val{ex->cfg, (const Word *)uops, n_uops, stream_begin, (const Desc *)descs, n_descs, tensor_bytes, n_tensors};
@@ -1695,6 +1730,7 @@ int vdc_program_validate(vdc_executor *ex, const void *uops, int64_t n_uops, con
 int vdc_program_destroy(vdc_program *prog) {
     if (!prog) return VDC_EINVAL;
     vdc_executor *ex = prog->ex;
+    if (ex->r_up) return VDC_ESTATE;      // a resident grid may still be reading it, and its memory must not be handed out again
     (void)hipSetDevice(ex->cfg.device);
     (void)hipDeviceSynchronize();
     ex->programs.erase(std::remove(ex->programs.begin(), ex->programs.end(), prog), ex->programs.end());
@@ -1716,6 +1752,123 @@ int vdc_run_traced(vdc_executor *ex, const vdc_program *prog, void *const *tenso
                    uint32_t *trace_count, int32_t trace_cap, void *hip_stream) {
     if (!trace || !trace_count || trace_cap < 1) return VDC_EINVAL;
     return run_program(ex, prog, tensor_bases, n_tensors, trace, trace_count, trace_cap, (hipStream_t)hip_stream);
+}
+
+int vdc_resident_start(vdc_executor *ex, int32_t idle_ms) {
+    if (!ex || ex->cfg.device == -1 || idle_ms < 0) return VDC_EINVAL;
+    if (ex->r_up) return VDC_ESTATE;
+    HIP_TRY(hipSetDevice(ex->cfg.device));
+    HIP_TRY(hipDeviceSynchronize());
+    const size_t mb_words = MB_JOBS + (size_t)kResidentJobs * kResidentJobWords;
+    void *mb = nullptr;
+    if (hipHostMalloc(&mb, mb_words * 4, hipHostMallocCoherent) != hipSuccess) return VDC_ENOMEM;
+    memset(mb, 0, mb_words * 4);
+    hipError_t e = hipMalloc(&ex->r_dev, RD_WORDS * 4);
+    if (e == hipSuccess) e = hipMemset(ex->r_dev, 0, RD_WORDS * 4);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ex->r_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess) {
+        ex->r_mailbox = (volatile uint32_t *)mb;
+        ex->r_mailbox[MB_STATE] = 1u;
+        ResidentParams rp{};
+        rp.mailbox = (uint32_t *)mb;
+        rp.dev = ex->r_dev;
+        rp.status = ex->d_status;
+        // the watcher looks about every four microseconds (a nap and two reads of host memory)
+        const uint64_t polls = (uint64_t)(idle_ms ? idle_ms : 1000) * 250u;
+        rp.idle_polls = (uint32_t)std::min<uint64_t>(polls, 1u << 30);
+        rp.backstop_polls = (uint32_t)std::min<uint64_t>((uint64_t)rp.idle_polls * 16u + (1u << 22), 0xFFFFFFF0u);
+        e = launch_resident(rp, (uint32_t)ex->cfg.n_cores, 1u + (uint32_t)ex->cfg.n_ldu + (uint32_t)ex->cfg.n_stu + 2u * (uint32_t)ex->cfg.vcc_per_core,
+                            lds_bytes_needed(ex->cfg.n_slots, ex->cfg.slot_bytes), ex->r_stream);
+    }
+    if (e != hipSuccess) {
+        if (ex->r_stream) (void)hipStreamDestroy(ex->r_stream);
+        (void)hipFree(ex->r_dev);
+        (void)hipHostFree(mb);
+        ex->r_stream = nullptr; ex->r_dev = nullptr; ex->r_mailbox = nullptr;
+        return VDC_EDEVICE;
+    }
+    ex->r_posted = 0;
+    ex->r_up = true;
+    return VDC_OK;
+}
+
+int vdc_resident_submit(vdc_executor *ex, const vdc_program *prog, void *const *tensor_bases, int32_t n_tensors, uint32_t *ticket) {
+    if (!ex || !ticket) return VDC_EINVAL;
+    if (!ex->r_up) return VDC_ESTATE;
+    KParams p;
+    uint32_t n_waves = 0;
+    int rc = prepare_params(ex, prog, tensor_bases, n_tensors, nullptr, nullptr, 0, nullptr, nullptr, p, n_waves);
+    if (rc != VDC_OK) return rc;
+#if defined(VDC_PROFILE) || defined(VDC_PROFILE_WAITS)
+    return VDC_EINVAL;
+#endif
+    // The resident grid has one wave per unit and no more: on two of a compute unit's four SIMDs that leaves registers for
+    // a wave of another kernel (the small copy kernels of the runtime among them), which twelve waves per core would
+    // not.  A program that asks for the twelve-wave placement runs in wave order instead; results do not depend on it.
+    const uint32_t r_waves = 1u + p.n_ldu + p.n_stu + 2u * p.V;
+    if (n_waves > r_waves) p.wave_roles = 0xFEDCBA9876543210ull;
+    for (uint32_t w = r_waves; w < 16u; w++) p.wave_roles |= 0xFull << (4u * w);
+    // room in the mailbox: at most kResidentJobs graphs posted and not complete
+    const uint32_t seq = ex->r_posted + 1u;
+    for (;;) {
+        if (__atomic_load_n(&ex->r_mailbox[MB_STATE], __ATOMIC_ACQUIRE) == 2u) return VDC_ESTATE;      // the grid has left
+        if (seq - __atomic_load_n(&ex->r_mailbox[MB_DONE], __ATOMIC_ACQUIRE) <= kResidentJobs) break;
+        std::this_thread::yield();
+    }
+    uint32_t img[kResidentJobWords] = {0};
+    static_assert(sizeof(KParams) <= sizeof(img), "a graph's parameter block fits one mailbox entry");
+    memcpy(img, &p, sizeof(KParams));
+    volatile uint32_t *slot = ex->r_mailbox + MB_JOBS + (seq % kResidentJobs) * kResidentJobWords;
+    for (uint32_t i = 0; i < kResidentJobWords; i++) slot[i] = img[i];
+    __atomic_store_n(&ex->r_mailbox[MB_TAIL], seq, __ATOMIC_RELEASE);
+    ex->r_posted = seq;
+    *ticket = seq;
+    return VDC_OK;
+}
+
+int vdc_resident_wait(vdc_executor *ex, uint32_t ticket, int32_t timeout_ms, uint32_t *info) {
+    if (!ex || ticket == 0 || timeout_ms < 0) return VDC_EINVAL;
+    if (!ex->r_up || ticket > ex->r_posted) return VDC_ESTATE;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (;;) {
+        if ((int32_t)(__atomic_load_n(&ex->r_mailbox[MB_DONE], __ATOMIC_ACQUIRE) - ticket) >= 0) break;
+        if (__atomic_load_n(&ex->r_mailbox[MB_STATE], __ATOMIC_ACQUIRE) == 2u) {
+            // the grid has left; a graph it completed on its way out still counts
+            if ((int32_t)(__atomic_load_n(&ex->r_mailbox[MB_DONE], __ATOMIC_ACQUIRE) - ticket) >= 0) break;
+            return VDC_ESTATE;
+        }
+        if (std::chrono::duration_cast<std::chrono::milliseconds>(std::chrono::steady_clock::now() - t0).count() > timeout_ms) return VDC_ETIMEOUT;
+        std::this_thread::yield();
+    }
+    const volatile uint32_t *st = ex->r_mailbox + MB_STATUS;
+    if (info) { info[0] = st[ST_CORE]; info[1] = st[ST_ROLE]; info[2] = st[ST_PC]; info[3] = st[ST_DETAIL]; }
+    if (st[ST_ABORT] == 0) return VDC_OK;
+    const int code = -(int)st[ST_CODE];
+    return code ? code : VDC_EDEVICE;
+}
+
+int vdc_resident_state(vdc_executor *ex, uint32_t *completed) {
+    if (!ex) return VDC_EINVAL;
+    if (completed) *completed = ex->r_up ? __atomic_load_n(&ex->r_mailbox[MB_DONE], __ATOMIC_ACQUIRE) : 0u;
+    if (!ex->r_up) return 0;
+    return __atomic_load_n(&ex->r_mailbox[MB_STATE], __ATOMIC_ACQUIRE) == 2u ? 2 : 1;
+}
+
+int vdc_resident_stop(vdc_executor *ex) {
+    if (!ex || ex->cfg.device == -1) return VDC_EINVAL;
+    if (!ex->r_up) return VDC_ESTATE;
+    HIP_TRY(hipSetDevice(ex->cfg.device));
+    const bool aborted = ex->r_mailbox[MB_STATUS + ST_ABORT] != 0u;
+    int rc = resident_down(ex);
+    if (rc == VDC_OK && aborted) {
+        // a graph that ended in an error may have left depId counters and the count of finished cores anywhere
+        HIP_TRY(launch_clear(ex->d_dep, (uint32_t)ex->cfg.n_dep_ids, nullptr));
+        HIP_TRY(launch_clear(ex->d_status + ST_WORDS + 3, 1u, nullptr));
+        HIP_TRY(launch_clear(ex->d_status, ST_WORDS, nullptr));
+        HIP_TRY(hipDeviceSynchronize());
+    }
+    return rc;
 }
 
 int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info) {
@@ -2114,6 +2267,8 @@ const char *vdc_strerror(int code) {
         case VDC_EDEVICE: return "HIP error";
         case VDC_EDEADLOCK: return "device watchdog: a unit waited past the spin limit";
         case VDC_ELEAK: return "run ended with local-memory slots still allocated";
+        case VDC_ESTATE: return "the call does not fit the executor's state (resident grid up, not up, or already gone)";
+        case VDC_ETIMEOUT: return "the graph was not complete within the time given";
         case VDC_ETOOBIG: return "the uop program and its workspace do not fit the static scratch of the entry point that allocates nothing";
         default: return "unknown error";
     }

@@ -50,6 +50,24 @@ struct KParams {
 
 constexpr uint32_t kSeqTableWords = 2052;
 
+// The resident form of the executor: the grid stays up and takes uop graphs from a mailbox in pinned host memory.
+// Mailbox (words): MB_TAIL graphs posted so far, MB_STOP non-zero = leave, MB_DONE graphs completed so far, MB_STATE
+// 1 = the grid is up, 2 = it has left (or is leaving), MB_STATUS.. the status words after the last completed graph,
+// MB_JOBS.. kResidentJobs entries of kResidentJobWords words, graph seq in entry seq % kResidentJobs: its KParams.
+// Device words: RD_JOB.. the parameter block of the graph being run, RD_TAIL the graph every wave may start (or STOP),
+// RD_CORES cores done with it, RD_DONE graphs completed so far.
+enum : uint32_t { MB_TAIL = 0, MB_STOP = 1, MB_DONE = 2, MB_STATE = 3, MB_STATUS = 8, MB_JOBS = 64 };
+enum : uint32_t { RD_JOB = 0, RD_TAIL = 64, RD_CORES = 65, RD_DONE = 66, RD_WORDS = 128 };
+constexpr uint32_t kResidentJobs = 8, kResidentJobWords = 64;
+struct ResidentParams {
+    uint32_t *mailbox;        // pinned host memory, MB_JOBS + kResidentJobs * kResidentJobWords words
+    uint32_t *dev;            // device memory, RD_WORDS words, zero at the launch
+    uint32_t *status;         // the executor's status words
+    uint32_t idle_polls;      // looks of the watcher without a new graph before the grid leaves by itself
+    uint32_t backstop_polls;  // bound of every other wait between graphs
+};
+hipError_t launch_resident(const ResidentParams &rp, uint32_t n_cores, uint32_t n_waves, size_t lds_bytes, hipStream_t stream);
+
 // Bytes of dynamic LDS one workgroup needs for n_slots slots of slot_bytes plus the control block.
 size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes);
 size_t lds_control_bytes();

@@ -2520,7 +2520,8 @@ DEV void observer_main(Ctx &c, uint32_t V) {
 #endif
 
 #define VDC_MAX_THREADS 768     // twelve waves: three per SIMD, which leaves each 170 vector registers
-__global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) {
+// One uop graph on one core, from a zeroed control block to the last unit leaving: every wave of the workgroup calls it.
+DEV void run_core(const KParams &p) {
     // The hardware deals the waves of a workgroup round-robin over the four SIMDs of the compute unit, so which roles
     // share a SIMD (and contend for its issue slots) is decided by which wave takes which role: the host chooses.
     const uint32_t wave = uni((uint32_t)(p.wave_roles >> ((threadIdx.x >> 6) * 4u)) & 15u);
@@ -2576,6 +2577,118 @@ __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KPa
     }
 #endif
 }
+
+__global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) { run_core(p); }
+
+// ------------------------------------------------------------------------------------------------
+// The resident form (Section 4.3: the virtual cores are launched once and new uop graphs are streamed to them as requests
+// arrive).  The grid stays up between graphs.  The first wave of core 0 watches a mailbox in pinned host memory; when
+// the host has posted graph number seq it copies the graph's parameter block into device memory and publishes seq in a
+// device word that every wave of the grid waits for; every core then runs the graph exactly as a launch of its own
+// would, cores count themselves out, and the last one reports the number to the host.  A graph is published only when
+// the one before is complete on every core (what a kernel boundary would give), with a release and an acquire at device
+// scope around it so that one graph's stores are read by the next on whatever compute unit.
+// Every wait has an end of its own: the watcher gives up after idle_polls looks without a new graph or when the host
+// says stop, and publishes STOP, at which every wave leaves; the other waves wait for the device word with a much larger
+// bound of their own.  When the host goes quiet or dies the grid therefore drains by itself.
+// ------------------------------------------------------------------------------------------------
+#ifndef VDC_PROFILE
+constexpr uint32_t kResidentStop = 0xFFFFFFFFu;
+static_assert(sizeof(KParams) <= 4 * kResidentJobWords, "a graph's parameter block fits one mailbox entry");
+
+DEV uint32_t sys_load(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM); }
+DEV uint32_t dev_load(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// The watcher's part before graph `seq`.  Returns nothing: what it decides is published in the device word.
+DEV void resident_watch(const ResidentParams &rp, uint32_t seq, uint32_t lane) {
+    uint32_t *dev_tail = rp.dev + RD_TAIL;
+    bool stop = false;
+    // the graph before must be complete on every core (each of its waits is bounded, so this one ends)
+    if (seq > 1u) {
+        uint32_t n = 0;
+        while (uni(dev_load(rp.dev + RD_DONE)) < seq - 1u) {
+            if (++n > rp.backstop_polls) { stop = true; break; }
+            __builtin_amdgcn_s_sleep(16);
+        }
+        // a graph that ended in an error ends the residency
+        if (uni(dev_load(rp.status + ST_ABORT)) != 0u) stop = true;
+    }
+    bool got = false;
+    for (uint32_t n = 0; !stop && !got; n++) {
+        const uint32_t tail = uni(__hip_atomic_load(rp.mailbox + MB_TAIL, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM));
+        const uint32_t quit = uni(sys_load(rp.mailbox + MB_STOP));
+        if ((int32_t)(tail - seq) >= 0) got = true;
+        else if (quit != 0u || n >= rp.idle_polls) stop = true;
+        else __builtin_amdgcn_s_sleep(64);
+    }
+    if (got && !stop) {
+        // the graph's parameter block: one word per lane, host memory -> device memory
+        const uint32_t w = sys_load(rp.mailbox + MB_JOBS + (seq % kResidentJobs) * kResidentJobWords + lane);
+        __hip_atomic_store(rp.dev + RD_JOB + lane, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (lane == 0) __hip_atomic_store(dev_tail, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        reconverge();
+    } else {
+        if (lane == 0) {
+            __hip_atomic_store(rp.mailbox + MB_STATE, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(dev_tail, kResidentStop, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        reconverge();
+    }
+}
+
+__global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_resident_kernel(const ResidentParams rp) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const bool watcher = blockIdx.x == 0u && (threadIdx.x >> 6) == 0u;
+    for (uint32_t seq = 1u;; seq++) {
+        if (watcher) resident_watch(rp, seq, lane);
+        uint32_t t = 0;
+        for (uint32_t n = 0;; n++) {
+            t = uni(dev_load(rp.dev + RD_TAIL));
+            if (t >= seq) break;                              // the graph, or STOP
+            if (n >= rp.backstop_polls) { t = kResidentStop; break; }
+            __builtin_amdgcn_s_sleep(16);
+        }
+        if (t == kResidentStop) break;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        // the parameter block into this wave's registers: lane l holds word l
+        const uint32_t img = dev_load(rp.dev + RD_JOB + lane);
+        KParams jp;
+        {
+            uint32_t raw[sizeof(KParams) / 4];
+#pragma unroll
+            for (uint32_t i = 0; i < (uint32_t)(sizeof(KParams) / 4); i++) raw[i] = rf_get(img, i);
+            __builtin_memcpy(&jp, raw, sizeof(KParams));
+        }
+        __builtin_amdgcn_s_setprio(0);                        // whatever role the wave had in the graph before
+        run_core(jp);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        __syncthreads();                                      // every wave of the core is done with the graph
+        if (threadIdx.x == 0) {
+            const uint32_t before = __hip_atomic_fetch_add(rp.dev + RD_CORES, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            if (before == gridDim.x - 1u) {
+                // the last core: the graph is complete.  The host reads results and the status after it has seen the number.
+                __hip_atomic_store(rp.dev + RD_CORES, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (uint32_t i = 0; i < (uint32_t)ST_WORDS; i++)
+                    __hip_atomic_store(rp.mailbox + MB_STATUS + i, dev_load(rp.status + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(rp.mailbox + MB_DONE, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+                __hip_atomic_store(rp.dev + RD_DONE, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_resident(const ResidentParams &rp, uint32_t n_cores, uint32_t n_waves, size_t lds_bytes, hipStream_t stream) {
+    hipError_t e = hipFuncSetAttribute((const void *)vdc_resident_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(vdc_resident_kernel, dim3(n_cores), dim3(n_waves * 64u), lds_bytes, stream, rp);
+    return hipGetLastError();
+}
+#else
+hipError_t launch_resident(const ResidentParams &, uint32_t, uint32_t, size_t, hipStream_t) { return hipErrorNotSupported; }
+#endif
 
 hipError_t prepare_executor_kernels(size_t lds_bytes) {
     return hipFuncSetAttribute((const void *)vdc_executor_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
