@@ -32,6 +32,7 @@ struct vdc_program {
     bool uses_dep = false;
     uint32_t max_dep_id = 0;
     uint32_t loaded_tensors = 0;   // bit t: some LOAD reads tensor t (its base must be 16-byte aligned: 128-bit loads)
+    uint32_t ops = 0;              // families of compute uops the program uses (OPS_*): picks the kernel variant
     void *d_workspace = nullptr;   // matvec programs that split K: the [I | 0] tile and the partial results
     int32_t placement = 0;         // which roles share a SIMD, see vdc_program_set_placement
 };
@@ -85,7 +86,7 @@ struct ScratchImage {
     int32_t n_descs = 0, n_tensors = 0, placement = 0;
     int64_t tensor_bytes[kMaxTensors] = {0};
     bool uses_dep = false;
-    uint32_t max_dep_id = 0, loaded_tensors = 0;
+    uint32_t max_dep_id = 0, loaded_tensors = 0, ops = 0;
     size_t off_sb = 0, off_descs = 0, off_words = 0, off_ws = 0;   // byte offsets from the start of the array
     bool has_ws = false;
 };
@@ -213,6 +214,7 @@ struct Validator {
     bool uses_dep = false;
     uint32_t max_dep = 0;
     uint32_t loaded_tensors = 0;
+    uint32_t ops = 0;              // OPS_* families of the compute uops met
     std::vector<uint32_t> dep;
     int64_t steps = 0;
 
@@ -395,6 +397,10 @@ struct Validator {
             int k = control(v.s, f);
             if (k < 0) return -1;
             if (k > 0) return 1;
+            ops |= f.opcode == OP_MATVEC ? (matvec_rowspan(f) >= 2 ? (OPS_MATVEC | OPS_ROWS) : OPS_MATVEC)
+                   : f.opcode == OP_ROPE ? OPS_ROPE
+                   : (f.opcode == OP_ATTN || f.opcode == OP_ATTN_MERGE) ? OPS_ATTN
+                   : (f.opcode == OP_DROP || f.opcode == OP_COPY || f.opcode == OP_FILL) ? OPS_STREAM : 0u;
             if (f.opcode == OP_ROPE) {
                 v.B = (uint32_t)f.imm & 0xFFu;
                 v.R = (uint32_t)(f.imm >> 8) & 0xFFFFu;
@@ -1557,7 +1563,7 @@ int run_program(vdc_executor *ex, const vdc_program *prog, void *const *tensor_b
     if (ex->r_up) return VDC_ESTATE;      // the resident grid holds every compute unit: a launch would only wait for it
     HIP_TRY(hipSetDevice(ex->cfg.device));
     if (trace_count) HIP_TRY(launch_clear(trace_count, (uint32_t)(ex->cfg.n_cores * (1 + ex->cfg.vcc_per_core)), stream));
-    HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, n_waves, stream));
+    HIP_TRY(launch_executor(p, (uint32_t)ex->cfg.n_cores, n_waves, prog->ops, stream));
     return VDC_OK;
 }
 
@@ -1694,6 +1700,7 @@ int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const
     p->uses_dep = val.uses_dep;
     p->max_dep_id = val.max_dep;
     p->loaded_tensors = val.loaded_tensors;
+    p->ops = val.ops;
     HIP_TRY(hipSetDevice(ex->cfg.device));
     const size_t wb = (size_t)n_uops * sizeof(Word), sbb = (size_t)(n_streams + 1) * 4, db = (size_t)std::max(n_descs, 1) * sizeof(Desc);   // never an empty table: the front end reads entry 0 for uops without one
     if (hipMalloc(&p->d_words, wb) != hipSuccess) return VDC_ENOMEM;
@@ -1987,6 +1994,7 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
         n.uses_dep = val.uses_dep;
         n.max_dep_id = val.max_dep;
         n.loaded_tensors = val.loaded_tensors;
+        n.ops = val.ops;
         if (n.uses_dep && ((size_t)n.max_dep_id + 2) * 4 > kScratchDepBytes) return VDC_ETOOBIG;
         n.placement = matvec_placement(c, rows, K, B, tile_bytes, false);   // the same choice of role placement as vdc_matvec makes
         // the staging buffer may still be the source of the copy of an earlier call
@@ -2023,6 +2031,7 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
     prog.uses_dep = img.uses_dep;
     prog.max_dep_id = img.max_dep_id;
     prog.loaded_tensors = img.loaded_tensors;
+    prog.ops = img.ops;
     prog.placement = img.placement;
     void *bases[4] = {(void *)M, (void *)X, (void *)Y, img.has_ws ? (void *)(ex->scratch + img.off_ws) : nullptr};
     return run_program(ex, &prog, bases, img.n_tensors, nullptr, nullptr, 0, stream, dep, finished);

@@ -73,7 +73,10 @@ size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes);
 size_t lds_control_bytes();
 
 // Launch the persistent virtual-core kernel: one workgroup per core.
-hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves, hipStream_t stream);
+// The families of compute uops a program uses: the kernel is built in several variants, each with the handlers of some
+// families only, and a program is launched on the smallest variant that has all of its own.
+enum : uint32_t { OPS_MATVEC = 1, OPS_ROWS = 2, OPS_ROPE = 4, OPS_STREAM = 8, OPS_ATTN = 16, OPS_ALL = 31 };
+hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves, uint32_t ops, hipStream_t stream);
 // Raise the kernel's dynamic LDS limit; call once per device before the first launch.
 hipError_t prepare_executor_kernels(size_t lds_bytes);
 // Zero n words (a fill kernel; safe inside stream capture, unlike a memset node).

@@ -2132,6 +2132,7 @@ DEV bool matvec_dispatch_b(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint
     return false;
 }
 
+template <uint32_t OPS>
 DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     const uint32_t B = (uint32_t)f.imm & 0xFFu, R = (uint32_t)(f.imm >> 8) & 0xFFFFu, lpr = (uint32_t)(f.imm >> 24) & 0xFFFFu;
     const uint32_t nf = (R * lpr) >> 7;
@@ -2143,6 +2144,10 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     }
     const uint32_t rowspan = matvec_rowspan(f);
     if (rowspan >= 2u) {
+        if constexpr ((OPS & OPS_ROWS) == 0u) {
+            raise_error(c, -3 /* VDC_EPROGRAM */, 0xC40u);
+            return false;
+        } else {
         if (j != 0u || f.size != 1u || xspan >= 2u || rowspan > kMaxRowspan || B > kMaxRowspanB) {
             raise_error(c, -3 /* VDC_EPROGRAM */, 0xC30u);
             return false;
@@ -2155,6 +2160,7 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
             default:
                 raise_error(c, -3 /* VDC_EPROGRAM */, 0xD00u);
                 return false;
+        }
         }
     }
     switch (B) {
@@ -2411,6 +2417,9 @@ DEV bool attn_merge_uop(Ctx &c, VccState &vs, uint32_t P, uint32_t lpr) {
 
 // The control-flow unit of a VCC runs on the execution unit's own threads (Section 4.3, "Virtual Compute Core"):
 // each of its two waves decodes the stream, runs control uops itself and then yields to the uop handler.
+// OPS: the compute uops this build of the kernel has handlers for (a program runs on the variant compiled for what it uses:
+// the kernel is one function, and every handler in it weighs on the register allocation of all the others).
+template <uint32_t OPS>
 DEV void vcc_main(Ctx &c, uint32_t wv) {
     const KParams *p = c.p;
     const bool TRACE = p->trace != nullptr;
@@ -2430,11 +2439,11 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         if (ctl == 2) break;
         if (ctl == 1) continue;
         if (TRACE && wv == 0u) trace_put(c, stream, trace_n, s.pc - c.stream_pc0, f.opcode | (f.size << 16), (uint64_t)f.imm);
-        if (f.opcode == OP_MATVEC) {
-            ok = matvec_dispatch(c, vs, f);
-        } else if (f.opcode == OP_ROPE) {
+        if ((OPS & OPS_MATVEC) != 0u && f.opcode == OP_MATVEC) {
+            ok = matvec_dispatch<OPS>(c, vs, f);
+        } else if ((OPS & OPS_ROPE) != 0u && f.opcode == OP_ROPE) {
             ok = rope_uop(c, vs, (uint32_t)f.imm & 0xFFu, (uint32_t)(f.imm >> 8) & 0xFFFFu);
-        } else if (f.opcode == OP_ATTN) {
+        } else if ((OPS & OPS_ATTN) != 0u && f.opcode == OP_ATTN) {
             const uint32_t lpr = (uint32_t)f.imm & 0xFFu, R = (uint32_t)(f.imm >> 8) & 0xFFu;
             const float scale = __builtin_bit_cast(float, (uint32_t)(f.imm >> 16));
             if (lpr == 32u && R == 32u) ok = attn_uop<32, 32>(c, vs, f.size, scale);
@@ -2447,13 +2456,13 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
                 raise_error(c, -3 /* VDC_EPROGRAM */, 0xE00u | f.opcode);
                 ok = false;
             }
-        } else if (f.opcode == OP_ATTN_MERGE) {
+        } else if ((OPS & OPS_ATTN) != 0u && f.opcode == OP_ATTN_MERGE) {
             ok = attn_merge_uop(c, vs, f.size, (uint32_t)f.imm & 0xFFu);
-        } else if (f.opcode == OP_DROP) {
+        } else if ((OPS & OPS_STREAM) != 0u && f.opcode == OP_DROP) {
             ok = drop_uop(c, vs, f.size);
-        } else if (f.opcode == OP_FILL) {
+        } else if ((OPS & OPS_STREAM) != 0u && f.opcode == OP_FILL) {
             ok = fill_uop(c, vs, f.size, (uint32_t)f.imm, (uint32_t)(f.imm >> 32) & 0xFFFFu);
-        } else if (f.opcode == OP_COPY) {
+        } else if ((OPS & OPS_STREAM) != 0u && f.opcode == OP_COPY) {
             ok = copy_uop(c, vs, f.size, (uint32_t)f.imm & 0xFFFFu);
         } else {
             raise_error(c, -3 /* VDC_EPROGRAM */, 0xE00u | f.opcode);
@@ -2521,6 +2530,7 @@ DEV void observer_main(Ctx &c, uint32_t V) {
 
 #define VDC_MAX_THREADS 768     // twelve waves: three per SIMD, which leaves each 170 vector registers
 // One uop graph on one core, from a zeroed control block to the last unit leaving: every wave of the workgroup calls it.
+template <uint32_t OPS>
 DEV void run_core(const KParams &p) {
     // The hardware deals the waves of a workgroup round-robin over the four SIMDs of the compute unit, so which roles
     // share a SIMD (and contend for its issue slots) is decided by which wave takes which role: the host chooses.
@@ -2567,7 +2577,7 @@ DEV void run_core(const KParams &p) {
     } else {
         const uint32_t k = wave - 1u - p.n_ldu - p.n_stu;
         c.role = ROLE_VCC; c.unit = k >> 1;
-        vcc_main(c, k & 1u);
+        vcc_main<OPS>(c, k & 1u);
     }
 #ifdef VDC_PROFILE_WAITS
     if (c.lane == 0 && wave < 16u) {
@@ -2578,7 +2588,8 @@ DEV void run_core(const KParams &p) {
 #endif
 }
 
-__global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) { run_core(p); }
+template <uint32_t OPS>
+__global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) { run_core<OPS>(p); }
 
 // ------------------------------------------------------------------------------------------------
 // The resident form (Section 4.3: the virtual cores are launched once and new uop graphs are streamed to them as requests
@@ -2665,7 +2676,7 @@ __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_resident_kernel(const Res
             __builtin_memcpy(&jp, raw, sizeof(KParams));
         }
         __builtin_amdgcn_s_setprio(0);                        // whatever role the wave had in the graph before
-        run_core(jp);
+        run_core<OPS_ALL>(jp);
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");      // this wave's stores have reached the L2
         __syncthreads();                                      // every wave of the core is done with the graph
         if ((threadIdx.x >> 6) == 0u) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");     // and the L2 is written back
@@ -2695,19 +2706,45 @@ hipError_t launch_resident(const ResidentParams &rp, uint32_t n_cores, uint32_t 
 hipError_t launch_resident(const ResidentParams &, uint32_t, uint32_t, size_t, hipStream_t) { return hipErrorNotSupported; }
 #endif
 
-hipError_t prepare_executor_kernels(size_t lds_bytes) {
-    return hipFuncSetAttribute((const void *)vdc_executor_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+// The variants of the kernel, from few handlers to all; a program runs on the first that has every handler it needs.
+#ifdef VDC_PROFILE
+constexpr uint32_t kVariants[] = {OPS_ALL};
+#else
+constexpr uint32_t kVariants[] = {OPS_MATVEC, OPS_MATVEC | OPS_ROWS, OPS_MATVEC | OPS_ROPE, OPS_STREAM, OPS_ATTN, OPS_ALL};
+#endif
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+template <int I>
+static const void *variant_entry(int i) {
+    if constexpr (I < kNumVariants) {
+        if (i == I) return (const void *)vdc_executor_kernel<kVariants[I]>;
+        return variant_entry<I + 1>(i);
+    } else {
+        return nullptr;
+    }
 }
 
-hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves, hipStream_t stream) {
+hipError_t prepare_executor_kernels(size_t lds_bytes) {
+    for (int i = 0; i < kNumVariants; i++) {
+        hipError_t e = hipFuncSetAttribute(variant_entry<0>(i), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves, uint32_t ops, hipStream_t stream) {
 #ifdef VDC_PROFILE
     const uint32_t waves = n_waves + 1u;   // one more: the observer
 #else
     const uint32_t waves = n_waves;
 #endif
     const size_t lds = lds_bytes_needed(p.n_slots, p.slot_bytes);
-    hipLaunchKernelGGL(vdc_executor_kernel, dim3(n_cores), dim3(waves * 64u), lds, stream, p);
-    return hipGetLastError();
+    int pick = kNumVariants - 1;
+    for (int i = kNumVariants - 1; i >= 0; i--)
+        if ((ops & ~kVariants[i]) == 0u) pick = i;
+    KParams args = p;
+    void *kargs[] = {&args};
+    return hipLaunchKernel(variant_entry<0>(pick), dim3(n_cores), dim3(waves * 64u), kargs, lds, stream);
 }
 
 hipError_t launch_clear(uint32_t *ptr, uint32_t n, hipStream_t stream) {
