@@ -131,3 +131,66 @@ def test_every_schedule_gives_the_same_image_and_the_query_tile_goes_back_last()
     first_alloc = m.alloc_log[0][0][2]
     frees = [p for (p, n) in m.cores[0].free_log]
     assert frees.index(first_alloc) == 6          # after three key tiles and three value tiles
+
+
+def _run_whole(lengths, d, R, chunk, seed, schedule="program", sseed=0, ncores=2, slot=1024, nslots=12, Q=None):
+    Q0, K, V, ro = _case(lengths, d, seed)
+    Q = Q0 if Q is None else Q
+    p, n_items = A.attn_decode_program(ro, d, R, slot, ncores, chunk_tiles=chunk, whole=True)
+    w, sb, ds = p.finish()
+    O = np.full((len(lengths), d), np.nan, np.float32)
+    W = np.full((max(n_items, 1), d + 4), np.nan, np.float32)
+    m = UM.Machine(w, sb, ds, [K, V, Q, O, W], n_cores=ncores, slot_bytes=slot, n_slots=nslots, n_dep_ids=64).run(schedule, sseed)
+    m.check_final()
+    return (Q, K, V, ro), O, W, n_items, m
+
+
+def test_an_attn_uop_that_sees_a_whole_context_writes_the_result_itself():
+    # Section 4.1 names one attn uop.  Given a region of d values instead of a partial row it writes o / l, the request's
+    # result, and nothing is merged.  Contexts of one item and contexts cut into several, in one batch.
+    lengths, d, R, chunk = [9, 4, 40, 1, 16, 23], 8, 4, 4          # tiles: 3, 1, 10, 1, 4, 6 -> whole, whole, cut, whole, whole, cut
+    (Q, K, V, ro), O, W, n_items, m = _run_whole(lengths, d, R, chunk, seed=77)
+    assert n_items == 3 + 2                                          # partial rows only for the two cut contexts
+    Or, Ar, S = attn_ref.attn_decode(Q, K, V, ro, 1.0 / np.sqrt(d))
+    assert np.all(np.abs(O - Or) <= 4e-7 * Ar + 1e-30)
+    # a whole context's result is one rounding of the fp64 result (with the scale as the uop carries it, in fp32):
+    # closer than the merged form's bound
+    Or32 = attn_ref.attn_decode(Q, K, V, ro, float(np.float32(1.0 / np.sqrt(d))))[0]
+    for s in (0, 1, 3, 4):
+        assert np.all(np.abs(O[s] - Or32[s]) <= 2.0 ** -24 * (1 + 1e-6) * np.abs(Or32[s]))
+    # the merged form of the same batch agrees to the rounding of its partial rows
+    (_, _, _, _), O2, _, _ = _run(lengths, d, R, chunk, seed=77)
+    assert np.all(np.abs(O2.astype(np.float64) - O) <= 8e-7 * Ar + 1e-30)
+    # every schedule gives the same image
+    for i in range(10):
+        _, O3, W3, _, m3 = _run_whole(lengths, d, R, chunk, seed=77, schedule="random", sseed=i)
+        assert O3.tobytes() == O.tobytes() and W3.tobytes() == W.tobytes() and m3.trace_vcc == m.trace_vcc
+
+
+def test_whole_context_result_in_closed_form():
+    # a zero query scores every row alike: the result is the mean of the value rows, whatever the keys are
+    lengths, d = [12, 3], 8
+    (Q, K, V, ro), O, W, n_items, m = _run_whole(lengths, d, 4, 4, seed=5, Q=np.zeros((2, 8), np.float32))
+    assert n_items == 0 and np.all(np.isnan(W))
+    for s in range(2):
+        mean = V[ro[s]:ro[s + 1]].astype(np.float64).mean(axis=0)
+        assert np.all(np.abs(O[s] - mean) <= 2.0 ** -24 * (1 + 1e-6) * np.abs(mean))
+    # one row: the result is that value row, bit for bit
+    (Q, K, V, ro), O, W, n_items, m = _run_whole([1], d, 4, 4, seed=6)
+    assert np.array_equal(O[0], V[0])
+
+
+def test_attn_rejects_an_output_region_of_another_shape():
+    Q, K, V, ro = _case([4], 8, 1)
+    p, _ = A.attn_decode_program(ro, 8, 4, 1024, 1, chunk_tiles=4, whole=True)
+    # the STORE's region becomes two rows of d values
+    bad = p.desc(3, 2, 8 * 4, 8 * 4, 8 * 4)
+    vm = p.vmc(0)
+    for i, wd in enumerate(vm):
+        u = UM.decode(wd)
+        if u.opcode == UM.STORE:
+            vm[i] = A.word(UM.STORE, UM.F_SEND | UM.F_RECV, vflow=u.vflow, vcc=u.vcc, nslots=u.nslots, size=2, imm=u.imm, desc=bad)
+    w, sb, ds = p.finish()
+    O = np.zeros((2, 8), np.float32)
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(w, sb, ds, [K, V, Q, O, np.zeros((1, 12), np.float32)], n_cores=1, slot_bytes=1024, n_slots=12, n_dep_ids=64).run()
