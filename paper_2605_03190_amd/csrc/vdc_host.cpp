@@ -488,7 +488,9 @@ struct Validator {
                     if (--v.left == 0) { release(c, v.q); v.phase = 33; } else v.phase = 31;
                     break;
                 case 33:
-                    if (!m.is_store || m.rows != 1 || m.row_bytes != prow) { fail("attn: the output region is not one partial row"); return -1; }
+                    // a partial row (o, m, l, 0, 0) of a context that other items share, or the finished row of d values of a
+                    // context the uop saw all of
+                    if (!m.is_store || m.rows != 1 || (m.row_bytes != prow && m.row_bytes != row)) { fail("attn: the output region is neither a partial row nor a result row"); return -1; }
                     if (!store_returns(c, m)) return -1;
                     v.in_uop = false; v.s.pc++;
                     break;
@@ -1356,12 +1358,14 @@ int build_stream(const vdc_config &cfg, int32_t mode, int64_t bytes, uint32_t va
 
 // Decode attention, one query per request, over ragged contexts (Section 6.2, "Dynamic Attention Length"), as a uop
 // graph.  Tensors: 0 = K, 1 = V ([rows][d], the contexts back to back), 2 = Q ([n_seg][d]), 3 = O ([n_seg][d]),
-// 4 = W, the partial rows ([n_items][d + 4]).  A context is cut into tiles of R rows and into items of at most
-// `chunk` tiles, so that the items balance over the compute cores however uneven the contexts are (a single long
-// context is shared by many cores; at most kAttnMaxPartials items per request).  Consecutive items go to the same
-// compute core, in proportion to their tiles.  An item is: LOAD the query row, `n` x {LOAD key tile, LOAD value tile},
-// STORE the partial row and signal the request's depId.  Request s is then merged on one compute core: a load.dep of
-// its partial rows that waits for all of them, an ATTN_MERGE, the STORE of the result.  Every stream holds all its
+// 4 = W, the partial rows ([n_items][d + 4]).  A context is cut into tiles of R rows.  The tiles of all contexts, in
+// order, are dealt to the compute cores in equal contiguous shares, and an item is a run of tiles of one context on one
+// compute core: LOAD the query row, `n` x {LOAD key tile, LOAD value tile}, one STORE.  A context that lies inside one
+// share is one item whose ATTN uop is handed a region of d values and writes the request's result itself.  A context
+// that crosses shares is cut where they meet: its items store partial rows and signal the request's depId, and the
+// request is merged on the compute core of its first item (the last of that core's list; the context's other items stand
+// first in theirs): a load.dep of the partial rows that waits for all of them, an ATTN_MERGE, the STORE of the result.
+// A context longer than kAttnMaxPartials shares is cut into that many equal items instead.  Every stream holds all its
 // items before its first merge, and items wait for nothing: a waiting load never stands in front of a producer
 // (Section 4.3, "Avoiding Deadlock").  The memory core's stream takes the steps of its compute cores in turn.
 int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int32_t d, float scale, int32_t tile_bytes,
@@ -1372,17 +1376,14 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
     if (!attn_geometry_ok(lpr, R)) return VDC_EINVAL;
     const int C = cfg.n_cores, V = cfg.vcc_per_core;
     const int64_t units = (int64_t)C * V;
-    int64_t NT = 0, maxT = 0;
+    int64_t NT = 0;
     for (int s = 0; s < n_seg; s++) {
         const int64_t L = row_off[s + 1] - row_off[s];
         if (L < 1) return VDC_EINVAL;
         const int64_t T = (L + R - 1) / R;
+        if ((T + kAttnMaxPartials - 1) / kAttnMaxPartials > 65535) return VDC_EINVAL;
         NT += T;
-        maxT = std::max(maxT, T);
     }
-    int64_t chunk = std::max<int64_t>(1, (NT + 4 * units - 1) / (4 * units));
-    chunk = std::max(chunk, (maxT + kAttnMaxPartials - 1) / kAttnMaxPartials);
-    if (chunk > 65535) return VDC_EINVAL;
     Tiler t{cfg, 0, 0, 0, 1, 1, 4};
     t.streams.resize((size_t)C * (1 + V));
     uint32_t scale_bits;
@@ -1391,15 +1392,34 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
     const uint32_t d_k = t.desc(0, R, row, row, row), d_v = t.desc(1, R, row, row, row), d_q = t.desc(2, 1, row, row, row);
     const uint32_t d_o = t.desc(3, 1, row, row, row), d_w = t.desc(4, 1, prow, prow, prow);
     std::vector<std::vector<std::vector<Word>>> steps((size_t)units), merges((size_t)units);   // per compute core: groups of memory uops
-    struct SegItems { int64_t first, count; };
+    struct SegItems { int64_t first, count, unit; };
     std::vector<SegItems> seg_items((size_t)n_seg);
+    // share u holds the tiles [u * NT / units, (u + 1) * NT / units) of the sequence of all tiles
+    auto share_of = [&](int64_t g) { return std::min(units - 1, ((g + 1) * units - 1) / NT); };
+    auto share_end = [&](int64_t u) { return (u + 1) * NT / units; };
     int64_t item = 0, tiles_before = 0;
     for (int s = 0; s < n_seg; s++) {
         const int64_t L = row_off[s + 1] - row_off[s], T = (L + R - 1) / R;
+        // the cuts of the context: where shares meet, or equal items when that would be too many partial rows
+        std::vector<int64_t> cuts{0};
+        for (int64_t t0 = 0; t0 < T;) {
+            const int64_t u = share_of(tiles_before + t0);
+            const int64_t t1 = std::min(T, std::max(t0 + 1, share_end(u) - tiles_before));
+            cuts.push_back(t1);
+            t0 = t1;
+        }
+        if ((int64_t)cuts.size() - 1 > (int64_t)kAttnMaxPartials) {
+            const int64_t chunk = (T + kAttnMaxPartials - 1) / kAttnMaxPartials;
+            cuts.assign(1, 0);
+            for (int64_t t0 = 0; t0 < T; t0 += chunk) cuts.push_back(std::min(T, t0 + chunk));
+        }
+        const bool whole = cuts.size() == 2;
         seg_items[s].first = item;
-        for (int64_t t0 = 0; t0 < T; t0 += chunk) {
-            const int64_t t1 = std::min(T, t0 + chunk);
-            const int64_t u = std::min(units - 1, tiles_before * units / NT);
+        seg_items[s].unit = -1;
+        for (size_t ci = 0; ci + 1 < cuts.size(); ci++) {
+            const int64_t t0 = cuts[ci], t1 = cuts[ci + 1];
+            const int64_t u = share_of(tiles_before + t0);
+            if (seg_items[s].unit < 0) seg_items[s].unit = u;
             const int v = (int)(u % V);
             auto &st = steps[(size_t)u];
             st.push_back({encode(OP_LOAD, F_SEND, t.flow_x(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_q, 0)});
@@ -1409,19 +1429,24 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
                 st.push_back({encode(OP_LOAD, F_SEND | F_NT, t.flow_m(v), v, 0, kv_slots, rv, 0, r0 * row, d_k, 0),
                               encode(OP_LOAD, F_SEND | F_NT, t.flow_x(v), v, 0, kv_slots, rv, 0, r0 * row, d_v, 0)});
             }
-            st.push_back({encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, t.flow_y(v), v, 0, w_slots, 1, (uint32_t)s, item * prow, d_w, 0)});
+            if (whole) {
+                st.push_back({encode(OP_STORE, F_SEND | F_RECV, t.flow_y(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_o, 0)});
+            } else {
+                st.push_back({encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, t.flow_y(v), v, 0, w_slots, 1, (uint32_t)s, item * prow, d_w, 0)});
+                item++;
+            }
             t.vcc((int)(u / V), v).push_back(encode(OP_ATTN, 0, 0, 0, 0, 0, (uint32_t)(t1 - t0), 0, attn_imm(lpr, R, scale_bits), 0, 0));
-            tiles_before += t1 - t0;
-            item++;
         }
+        tiles_before += T;
         seg_items[s].count = item - seg_items[s].first;
         if (seg_items[s].count > kAttnMaxPartials) return VDC_EINVAL;
     }
-    n_items = item;
+    n_items = std::max<int64_t>(item, 1);       // the workspace is never empty
     for (int s = 0; s < n_seg; s++) {
-        const int64_t u = (int64_t)s * units / n_seg;
-        const int v = (int)(u % V);
         const uint32_t P = (uint32_t)seg_items[s].count;
+        if (P == 0) continue;                   // the request's one item wrote the result
+        const int64_t u = seg_items[s].unit;
+        const int v = (int)(u % V);
         const uint32_t d_t = t.desc(4, P, prow, prow, prow);
         const uint32_t t_slots = t.slots_for((uint64_t)P * prow);
         if ((int)(t_slots + q_slots) > cfg.n_slots) return VDC_EINVAL;
@@ -2162,7 +2187,7 @@ int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const floa
         int rc = build_attn(ex->cfg, row_off, n_seg, d, scale, tile_bytes, words, sb, descs, n_items);
         if (rc != VDC_OK) return rc;
         const int64_t rows = row_off[n_seg], row = (int64_t)d * 4;
-        int64_t tb[5] = {rows * row, rows * row, n_seg * row, n_seg * row, n_items * (row + 16)};
+        int64_t tb[5] = {rows * row, rows * row, n_seg * row, n_seg * row, n_items * (row + 16)};   // n_items >= 1
         rc = vdc_program_create(ex, words.data(), (int64_t)words.size(), sb.data(), descs.data(), (int32_t)descs.size(), tb, 5, &prog);
         if (rc != VDC_OK) return rc;
         if (hipMalloc(&prog->d_workspace, (size_t)tb[4]) != hipSuccess) { vdc_program_destroy(prog); return VDC_ENOMEM; }

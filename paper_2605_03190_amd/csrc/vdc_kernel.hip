@@ -154,10 +154,14 @@ static_assert(sizeof(UnitRec) == 4 * kRecWords && sizeof(StatRec) == 4 * kStatWo
 #define OBS(c, w, v)
 #endif
 
+// The build compiles this file once per variant of the executor kernel (-DVDC_PART=i: nothing but that variant, see the
+// end of the file) and once for everything else (-DVDC_SPLIT), all in parallel; without either macro it is one unit.
+#ifndef VDC_PART
 size_t lds_control_bytes() { return (sizeof(Ctl) + 255) & ~(size_t)255; }
 size_t lds_bytes_needed(uint32_t n_slots, uint32_t slot_bytes) {
     return (size_t)n_slots * slot_bytes + lds_control_bytes();
 }
+#endif
 
 extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -463,6 +467,7 @@ DEV int slot_find(uint64_t busy, uint32_t n) {
 }
 DEV uint64_t slots_beyond(uint32_t n_slots) { return n_slots >= 64u ? 0ull : (~0ull << n_slots); }
 
+#ifndef VDC_PART
 __global__ void debug_alloc_kernel(const uint32_t *masks, const int32_t *nslots, int32_t n_slots, int32_t *pos, int32_t n) {
     uint32_t lane = threadIdx.x & 63u;
     for (int i = blockIdx.x; i < n; i += gridDim.x) {
@@ -475,6 +480,7 @@ __global__ void clear_kernel(uint32_t *p, uint32_t n) {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
 }
+#endif
 
 // ------------------------------------------------------------------------------------------------
 // Queue primitives
@@ -1268,7 +1274,7 @@ struct LduEnt {
     uint32_t key;               // table | window lane, 0xffffffff = empty
     uint32_t val;               // the static record itself: lanes 0..7
     uint32_t ni;                // load instructions per tile
-    uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path | 32 DEVICE
+    uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path | 32 DEVICE | lanes of a last, partial instruction << 8
     uint32_t step_lo, step_hi;  // fast path: address step per load instruction
     uint32_t m2c_ready;         // LDS byte offset of the ready word of entry 0 of the compute core's m2c ring
     uint32_t off_lo, off_hi;    // fast path, per lane: offset of the lane's first chunk from the tile address
@@ -1284,16 +1290,20 @@ DEV void ldu_derive(Ctx &c, LduEnt &e, uint32_t key, uint32_t info) {
     const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u;
     e.ni = (total + 63u) >> 6;
     const bool pow2 = (cpr & (cpr - 1u)) == 0u && cpr <= 64u;
-    const bool fast = pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u;
+    // a box whose rows follow each other without a gap, in memory as in the region, is one run of `total` chunks whatever
+    // its row length: 64 chunks per instruction, and a last instruction of `tail` lanes
+    const bool contig = gpitch == (uint64_t)lds_pitch && row_bytes == lds_pitch && rows == box_rows;
+    const uint32_t tail = contig ? (total & 63u) : 0u;
+    const bool fast = (pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u) || contig;
     e.bits = ((flags & F_NT) ? 1u : 0u) | ((flags & F_SEND) ? 2u : 0u) | ((flags & F_DEP_SEND) ? 4u : 0u) |
-             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u) | ((flags & F_DEVICE) ? 32u : 0u);
+             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u) | ((flags & F_DEVICE) ? 32u : 0u) | (tail << 8);
     uint32_t sh = 0, drow = 0;
     if (pow2) { sh = __builtin_ctz(cpr); drow = 64u >> sh; }
-    const uint64_t step = (uint64_t)drow * gpitch;
+    const uint64_t step = contig ? 1024ull : (uint64_t)drow * gpitch;
     e.step_lo = (uint32_t)step;
     e.step_hi = (uint32_t)(step >> 32);
     e.m2c_ready = c.ctl + CTL_OFF(m2c) + vcc * kM2C * (uint32_t)sizeof(M2cEnt) + (uint32_t)offsetof(M2cEnt, ready);
-    const uint64_t off = (uint64_t)(c.lane >> sh) * gpitch + (uint64_t)(c.lane & (cpr - 1u)) * 16u;
+    const uint64_t off = contig ? (uint64_t)c.lane * 16u : (uint64_t)(c.lane >> sh) * gpitch + (uint64_t)(c.lane & (cpr - 1u)) * 16u;
     e.off_lo = (uint32_t)off;
     e.off_hi = (uint32_t)(off >> 32);
 }
@@ -1393,18 +1403,19 @@ DEV void ldu_main(Ctx &c) {
                  "v_lshl_add_u64 %[g], %[g], 0, %[step]"                                                           \
                  : [g] "+v"(ga) : [dst] "s"(dst), [step] "s"(step) : "memory", "scc")
 #define VDC_LOAD_TILE(NT)                                                                                          \
-    for (; i + 4u <= ni; i += 4u) {                                                                                \
+    for (; i + 4u <= nfull; i += 4u) {                                                                             \
         VDC_LOAD4(NT);                                                                                             \
         dst += 4096u;                                                                                              \
         if (__builtin_expect((i & 31u) == 28u && i + 4u < ni, 0)) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); \
     }                                                                                                              \
-    for (; i < ni; i++) {                                                                                          \
+    for (; i < nfull; i++) {                                                                                       \
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" NT ::"s"(dst), "v"(ga) : "memory"); \
         dst += 1024u;                                                                                              \
         ga += step;                                                                                                \
     }
             uint64_t ga = gaddr + off;
             uint32_t i = 0;
+            const uint32_t tail = bits >> 8, nfull = tail ? ni - 1u : ni;
             if (bits & 32u) {
                 // device scope: the tile may have been written by another core during this run
                 VDC_LOAD_TILE(" sc1")
@@ -1415,6 +1426,10 @@ DEV void ldu_main(Ctx &c) {
             }
 #undef VDC_LOAD_TILE
 #undef VDC_LOAD4
+            if (__builtin_expect(tail != 0u, 0)) {
+                if (c.lane < tail) load_lds_b128(dst, (const char *)(uintptr_t)ga, (bits & 1u) != 0u, (bits & 32u) != 0u);
+                reconverge();
+            }
         } else {
             const uint64_t gpitch = (uint64_t)rf_get(val, 0) | ((uint64_t)rf_get(val, 1) << 32);
             const uint32_t rows_box = rf_get(val, 2), rb_pitch = rf_get(val, 3);
@@ -2383,28 +2398,45 @@ DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
     Msg mo;
     if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
     const uint32_t out_off = mo.slot << slot_shift;
-    lds_st32_lanes(COLS == 64u ? ~0ull : 0xFFFFFFFFull, out_off + col * 4u, __builtin_bit_cast(uint32_t, o));
-    if (vs.t < 4u) lds_stf(out_off + ROW + vs.t * 4u, vs.t == 0u ? m : (vs.t == 1u ? l : 0.0f));
+    // The region says what is wanted: one row of d values takes the finished result o / l (the uop saw the whole context),
+    // a row of d + 4 values the partial row (o, m, l, 0, 0) that an ATTN_MERGE joins with those of the context's other items.
+    const bool whole = mo.row_bytes == ROW;
+    lds_st32_lanes(COLS == 64u ? ~0ull : 0xFFFFFFFFull, out_off + col * 4u, __builtin_bit_cast(uint32_t, whole ? o / l : o));
+    lds_st32_lanes(whole || vs.wv != 0u ? 0ull : 0xFull, out_off + ROW + c.lane * 4u, __builtin_bit_cast(uint32_t, c.lane == 0u ? m : (c.lane == 1u ? l : 0.0f)));
     lds_wait();
     vcc_done_with(c, vs, 1u, 1u);
     return true;
 }
 
-// attn_merge: `P` partial rows (o[0..d), m, l, 0, 0) of one request become its result; thread t owns column t (d = 4 lpr).
+// attn_merge: `P` <= 64 partial rows (o[0..d), m, l, 0, 0) of one request become its result; thread t owns column t
+// (d = 4 lpr).  Lane i of every wave takes row i's maximum and sum, so the weights exp(m_i - M) are one exponential per
+// lane and M and the denominator are reductions over the wave; the weighted sum then takes one LDS read per row, the
+// weight coming from the scalar side.
 DEV bool attn_merge_uop(Ctx &c, VccState &vs, uint32_t P, uint32_t lpr) {
     const uint32_t D4 = lpr * 16u, PROW = D4 + 16u;
     const uint32_t tcol = vs.t < lpr * 4u ? vs.t : 0u;
     const uint32_t slot_shift = __builtin_ctz(c.p->slot_bytes);
     Msg mt, mo, unused;
+    if (P > 64u) {
+        raise_error(c, -3 /* VDC_EPROGRAM */, 0xE40u);
+        return false;
+    }
     if (!vcc_pop_wait(c, vs, 1u, 0u, mt, unused)) return false;
     const uint32_t t_off = mt.slot << slot_shift;
-    float M = -__builtin_inff();
-    for (uint32_t i = 0; i < P; i++) M = __builtin_fmaxf(M, lds_ldf(t_off + i * PROW + D4));
-    float num = 0.0f, den = 0.0f;
+    const bool mine = c.lane < P;
+    const uint32_t r_off = t_off + (mine ? c.lane : 0u) * PROW + D4;
+    const float mi = mine ? lds_ldf(r_off) : -__builtin_inff(), li = mine ? lds_ldf(r_off + 4u) : 0.0f;
+    float M = mi;
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) M = __builtin_fmaxf(M, __shfl_xor(M, s, 64));
+    const float w = mine ? expf(mi - M) : 0.0f;
+    float den = w * li;
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) den += __shfl_xor(den, s, 64);
+    float num = 0.0f;
     for (uint32_t i = 0; i < P; i++) {
-        const float w = expf(lds_ldf(t_off + i * PROW + D4) - M);
-        num = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + tcol * 4u), num);
-        den = __builtin_fmaf(w, lds_ldf(t_off + i * PROW + D4 + 4u), den);
+        const float wi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), (int)i));
+        num = __builtin_fmaf(wi, lds_ldf(t_off + i * PROW + tcol * 4u), num);
     }
     const float res = num / den;
     vcc_done_with(c, vs, 1u, 0u);
@@ -2591,6 +2623,22 @@ DEV void run_core(const KParams &p) {
 template <uint32_t OPS>
 __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KParams p) { run_core<OPS>(p); }
 
+// The variants of the kernel, from few handlers to all; a program runs on the first that has every handler it needs.
+#ifdef VDC_PROFILE
+constexpr uint32_t kVariants[] = {OPS_ALL};
+#else
+constexpr uint32_t kVariants[] = {OPS_MATVEC, OPS_MATVEC | OPS_ROWS, OPS_MATVEC | OPS_ROPE, OPS_STREAM, OPS_ATTN, OPS_ALL};
+#endif
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+#ifdef VDC_PART
+// A unit of the split build: this variant of the kernel and the function that hands out its address, nothing else.
+#define VDC_PART_NAME2(I) vdc_variant_entry_##I
+#define VDC_PART_NAME(I) VDC_PART_NAME2(I)
+extern "C" const void *VDC_PART_NAME(VDC_PART)() { return (const void *)vdc_executor_kernel<kVariants[VDC_PART]>; }
+}  // namespace vdc
+#else
+
 // ------------------------------------------------------------------------------------------------
 // The resident form (Section 4.3: the virtual cores are launched once and new uop graphs are streamed to them as requests
 // arrive).  The grid stays up between graphs.  The first wave of core 0 watches a mailbox in pinned host memory; when
@@ -2706,27 +2754,38 @@ hipError_t launch_resident(const ResidentParams &rp, uint32_t n_cores, uint32_t 
 hipError_t launch_resident(const ResidentParams &, uint32_t, uint32_t, size_t, hipStream_t) { return hipErrorNotSupported; }
 #endif
 
-// The variants of the kernel, from few handlers to all; a program runs on the first that has every handler it needs.
-#ifdef VDC_PROFILE
-constexpr uint32_t kVariants[] = {OPS_ALL};
-#else
-constexpr uint32_t kVariants[] = {OPS_MATVEC, OPS_MATVEC | OPS_ROWS, OPS_MATVEC | OPS_ROPE, OPS_STREAM, OPS_ATTN, OPS_ALL};
-#endif
-constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
-
-template <int I>
+#if defined(VDC_SPLIT) && !defined(VDC_PROFILE)
+// the variants are compiled in units of their own (see the end of the file): each exports the address of its kernel
+#define VDC_DECLARE_PART(I) extern "C" const void *vdc_variant_entry_##I();
+VDC_DECLARE_PART(0) VDC_DECLARE_PART(1) VDC_DECLARE_PART(2) VDC_DECLARE_PART(3) VDC_DECLARE_PART(4) VDC_DECLARE_PART(5)
+#undef VDC_DECLARE_PART
+static_assert(kNumVariants == 6, "one unit per variant");
 static const void *variant_entry(int i) {
+    switch (i) {
+        case 0: return vdc_variant_entry_0();
+        case 1: return vdc_variant_entry_1();
+        case 2: return vdc_variant_entry_2();
+        case 3: return vdc_variant_entry_3();
+        case 4: return vdc_variant_entry_4();
+        default: return vdc_variant_entry_5();
+    }
+}
+#else
+template <int I>
+static const void *variant_entry_at(int i) {
     if constexpr (I < kNumVariants) {
         if (i == I) return (const void *)vdc_executor_kernel<kVariants[I]>;
-        return variant_entry<I + 1>(i);
+        return variant_entry_at<I + 1>(i);
     } else {
         return nullptr;
     }
 }
+static const void *variant_entry(int i) { return variant_entry_at<0>(i); }
+#endif
 
 hipError_t prepare_executor_kernels(size_t lds_bytes) {
     for (int i = 0; i < kNumVariants; i++) {
-        hipError_t e = hipFuncSetAttribute(variant_entry<0>(i), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        hipError_t e = hipFuncSetAttribute(variant_entry(i), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -2744,7 +2803,7 @@ hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves,
         if ((ops & ~kVariants[i]) == 0u) pick = i;
     KParams args = p;
     void *kargs[] = {&args};
-    return hipLaunchKernel(variant_entry<0>(pick), dim3(n_cores), dim3(waves * 64u), kargs, lds, stream);
+    return hipLaunchKernel(variant_entry(pick), dim3(n_cores), dim3(waves * 64u), kargs, lds, stream);
 }
 
 hipError_t launch_clear(uint32_t *ptr, uint32_t n, hipStream_t stream) {
@@ -2835,3 +2894,4 @@ hipError_t launch_debug_alloc(const uint32_t *masks, const int32_t *nslots, int3
 }
 
 }  // namespace vdc
+#endif   // VDC_PART
