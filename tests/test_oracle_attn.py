@@ -194,3 +194,89 @@ def test_attn_rejects_an_output_region_of_another_shape():
     O = np.zeros((2, 8), np.float32)
     with pytest.raises(UM.ProgramError):
         UM.Machine(w, sb, ds, [K, V, Q, O, np.zeros((1, 12), np.float32)], n_cores=1, slot_bytes=1024, n_slots=12, n_dep_ids=64).run()
+
+
+def _run_join(lengths, d, R, chunk, seed, schedule="program", sseed=0, ncores=2, slot=1024, nslots=12, Q=None, whole=True):
+    Q0, K, V, ro = _case(lengths, d, seed)
+    Q = Q0 if Q is None else Q
+    p, n_items = A.attn_decode_program(ro, d, R, slot, ncores, chunk_tiles=chunk, whole=whole, join=True)
+    w, sb, ds = p.finish()
+    O = np.full((len(lengths), d), np.nan, np.float32)
+    W = np.full((max(n_items, 1), d + 4), np.nan, np.float32)
+    m = UM.Machine(w, sb, ds, [K, V, Q, O, W], n_cores=ncores, slot_bytes=slot, n_slots=nslots, n_dep_ids=64).run(schedule, sseed)
+    m.check_final()
+    return (Q, K, V, ro), O, W, n_items, (w, m)
+
+
+@pytest.mark.parametrize("lengths,d,R,chunk", [
+    ([40], 8, 4, 3),                   # four items: three partial rows joined by the first
+    ([4, 9, 1, 23], 8, 4, 2),
+    ([100, 3, 64], 16, 8, 3),
+    ([300], 32, 8, 5),                 # eight items
+    ([37, 12, 70, 5], 8, 4, 4),
+])
+def test_an_attn_uop_joins_the_partial_rows_of_the_other_items(lengths, d, R, chunk):
+    # a cut context without ATTN_MERGE: its first item takes the other items' partial rows behind its last pair
+    (Q, K, V, ro), O, W, n_items, (w, m) = _run_join(lengths, d, R, chunk, seed=sum(lengths))
+    ops = np.array([UM.decode(x).opcode for x in w])
+    assert (ops == UM.ATTN_MERGE).sum() == 0
+    tiles = [-(-L // R) for L in lengths]
+    assert n_items == sum(-(-t // chunk) - 1 for t in tiles)            # one partial row per item but the joining one
+    Or, Ar, S = attn_ref.attn_decode(Q, K, V, ro, 1.0 / np.sqrt(d))
+    assert np.all(np.abs(O - Or) <= 4e-7 * Ar + 1e-30)
+    # the merged form of the same cut agrees to the rounding of the partial rows
+    (_, _, _, _), O2, _, _ = _run(lengths, d, R, chunk, seed=sum(lengths))
+    assert np.all(np.abs(O2.astype(np.float64) - O) <= 8e-7 * Ar + 1e-30)
+    # every schedule gives the same image and the same traces
+    for i in range(8):
+        _, O3, W3, _, (_, m3) = _run_join(lengths, d, R, chunk, seed=sum(lengths), schedule="random", sseed=i)
+        assert O3.tobytes() == O.tobytes() and W3.tobytes() == W.tobytes() and m3.trace_vcc == m.trace_vcc
+
+
+def test_joined_result_in_closed_form():
+    # a zero query weighs every row alike whatever the cut: the mean of all value rows of the context
+    lengths, d = [29, 50], 8
+    (Q, K, V, ro), O, W, n_items, _ = _run_join(lengths, d, 4, 3, seed=11, Q=np.zeros((2, 8), np.float32))
+    for s in range(2):
+        mean = V[ro[s]:ro[s + 1]].astype(np.float64).mean(axis=0)
+        assert np.all(np.abs(O[s] - mean) <= 3 * 2.0 ** -24 * np.abs(mean) + 1e-9)
+    # the partial rows of the other items: maximum 0, sum = rows of the item
+    assert np.all(W[:, 8] == 0)
+    assert sorted(W[:, 9].tolist()) == sorted([12.0, 5.0, 12.0, 12.0, 12.0, 2.0])
+    # a dominant key row in an item that is not the joining one carries the result: its value row
+    Q, K, V, ro = _case([40], 8, 3)
+    K[:] = 0
+    K[30] = 50.0 * Q[0] / np.dot(Q[0], Q[0])                 # score 50 / sqrt(8) against zeros elsewhere
+    p, n_items = A.attn_decode_program(ro, 8, 4, 1024, 2, chunk_tiles=3, join=True)
+    w, sb, ds = p.finish()
+    O = np.full((1, 8), np.nan, np.float32)
+    W = np.full((n_items, 12), np.nan, np.float32)
+    UM.Machine(w, sb, ds, [K, V, Q, O, W], n_cores=2, slot_bytes=1024, n_slots=12, n_dep_ids=64).run()
+    assert np.allclose(O[0], V[30], rtol=1e-5, atol=1e-6)
+
+
+def test_attn_join_rejects_wrong_tiles():
+    Q, K, V, ro = _case([40], 8, 3)
+    for what in ("rows", "out"):
+        p, n_items = A.attn_decode_program(ro, 8, 4, 1024, 2, chunk_tiles=3, join=True)
+        for core in range(2):
+            vm = p.vmc(core)
+            for i, wd in enumerate(vm):
+                u = UM.decode(wd)
+                if what == "rows" and u.opcode == UM.LOAD and (u.flags & UM.F_DEP_RECV):
+                    bad = p.desc(4, 2, 12 * 4, 12 * 4, 12 * 4)      # two partial rows where the uop expects three
+                    vm[i] = A.word(UM.LOAD, u.flags, vflow=u.vflow, vcc=u.vcc, nslots=u.nslots, size=2, dep_id=u.dep_id, dep_count=3, imm=u.imm, desc=bad)
+        if what == "out":
+            # the joining uop is handed a partial-row region instead of a result row
+            for core in range(2):
+                vm = p.vmc(core)
+                for i, wd in enumerate(vm):
+                    u = UM.decode(wd)
+                    if u.opcode == UM.STORE and not (u.flags & UM.F_DEP_SEND):
+                        bad = p.desc(4, 1, 12 * 4, 12 * 4, 12 * 4)
+                        vm[i] = A.word(UM.STORE, u.flags, vflow=u.vflow, vcc=u.vcc, nslots=u.nslots, size=1, imm=0, desc=bad)
+        w, sb, ds = p.finish()
+        O = np.zeros((1, 8), np.float32)
+        W = np.zeros((max(n_items, 1) + 1, 12), np.float32)
+        with pytest.raises(UM.ProgramError):
+            UM.Machine(w, sb, ds, [K, V, Q, O, W], n_cores=2, slot_bytes=1024, n_slots=12, n_dep_ids=64).run()
