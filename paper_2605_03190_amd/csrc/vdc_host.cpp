@@ -186,10 +186,11 @@ struct VccH {
     bool holds_x = false;
     int phase = 0;                // MATVEC: 0 expect a, 1 expect b, 2 expect out, 3 expect a vector tile over several steps; ROPE: 10 expect values, 11 expect angles, 12 expect out;
                                   // DROP: 20; FILL: 21; COPY: 22 expect in, 23 expect out;
-                                  // ATTN: 30 expect q, 31 expect K tile, 32 expect V tile, 33 expect out; ATTN_MERGE: 40 expect rows, 41 expect out;
+                                  // ATTN: 30 expect q, 31 expect K tile, 32 expect V tile, 34 expect the partial rows to join, 33 expect out; ATTN_MERGE: 40 expect rows, 41 expect out;
                                   // MATVEC over several row blocks: 50 expect out, 51 expect the vector tile, 52 expect a matrix tile
     SentMsg q{};
     uint32_t chunks = 0;
+    uint32_t join = 0;             // attn: partial rows of other items joined behind the last pair
     SentMsg a{}, b{};
 };
 
@@ -423,6 +424,8 @@ struct Validator {
                 v.R = f.opcode == OP_ATTN ? (uint32_t)(f.imm >> 8) & 0xFFu : 16u;     // a merge has no tile rows: any supported value
                 if (!attn_geometry_ok(v.lpr, v.R)) { fail("attn geometry not supported"); return -1; }
                 if (f.size < 1 || (f.opcode == OP_ATTN_MERGE && f.size > kAttnMaxPartials)) { fail("attn: bad size"); return -1; }
+                v.join = f.opcode == OP_ATTN ? attn_join(f) : 0u;
+                if (v.join > kAttnMaxPartials) { fail("attn: too many partial rows to join"); return -1; }
                 v.left = f.size;
                 v.phase = f.opcode == OP_ATTN ? 30 : 40;
                 v.in_uop = true;
@@ -485,12 +488,17 @@ struct Validator {
                     if (m.is_store || m.box_rows != v.R || m.lds_pitch != row || m.row_bytes != row || m.rows != v.a.rows) { fail("attn: value tile does not match the key tile"); return -1; }
                     release(c, v.a);
                     release(c, m);
-                    if (--v.left == 0) { release(c, v.q); v.phase = 33; } else v.phase = 31;
+                    if (--v.left == 0) { release(c, v.q); v.phase = v.join ? 34 : 33; } else v.phase = 31;
+                    break;
+                case 34:
+                    if (m.is_store || m.rows != v.join || m.row_bytes != prow || m.lds_pitch != prow) { fail("attn: the tile behind the last pair is not the partial rows to join"); return -1; }
+                    release(c, m);
+                    v.phase = 33;
                     break;
                 case 33:
                     // a partial row (o, m, l, 0, 0) of a context that other items share, or the finished row of d values of a
-                    // context the uop saw all of
-                    if (!m.is_store || m.rows != 1 || (m.row_bytes != prow && m.row_bytes != row)) { fail("attn: the output region is neither a partial row nor a result row"); return -1; }
+                    // context the uop saw all of or joined the rest of
+                    if (!m.is_store || m.rows != 1 || (m.row_bytes != prow && m.row_bytes != row) || (v.join && m.row_bytes != row)) { fail("attn: the output region is neither a partial row nor a result row"); return -1; }
                     if (!store_returns(c, m)) return -1;
                     v.in_uop = false; v.s.pc++;
                     break;
@@ -1362,12 +1370,14 @@ int build_stream(const vdc_config &cfg, int32_t mode, int64_t bytes, uint32_t va
 // order, are dealt to the compute cores in equal contiguous shares, and an item is a run of tiles of one context on one
 // compute core: LOAD the query row, `n` x {LOAD key tile, LOAD value tile}, one STORE.  A context that lies inside one
 // share is one item whose ATTN uop is handed a region of d values and writes the request's result itself.  A context
-// that crosses shares is cut where they meet: its items store partial rows and signal the request's depId, and the
-// request is merged on the compute core of its first item (the last of that core's list; the context's other items stand
-// first in theirs): a load.dep of the partial rows that waits for all of them, an ATTN_MERGE, the STORE of the result.
-// A context longer than kAttnMaxPartials shares is cut into that many equal items instead.  Every stream holds all its
-// items before its first merge, and items wait for nothing: a waiting load never stands in front of a producer
-// (Section 4.3, "Avoiding Deadlock").  The memory core's stream takes the steps of its compute cores in turn.
+// that crosses shares is cut where they meet.  Its first item stands last in its compute core's list and the others
+// first in theirs (or alone): the others store partial rows and signal the request's depId; the first loads those
+// partial rows behind its last pair (a load.dep that waits for all of them: by then they have long been written), its
+// ATTN uop joins them to its own running state and writes the result.  No partial row of the item that finishes the
+// request goes through memory, and nothing is left to do after a core's last tile but one STORE.  A context longer than
+// kAttnMaxPartials + 1 shares is cut into that many equal items instead.  In every memory stream all items that signal
+// stand before the first load that waits: a waiting load never stands in front of a producer (Section 4.3, "Avoiding
+// Deadlock").  The memory core's stream takes the steps of its compute cores in turn.
 int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int32_t d, float scale, int32_t tile_bytes,
                std::vector<Word> &words, std::vector<uint32_t> &sb, std::vector<Desc> &descs, int64_t &n_items) {
     if (!row_off || n_seg < 1 || n_seg > cfg.n_dep_ids || (d != 128 && d != 64) || row_off[0] != 0) return VDC_EINVAL;
@@ -1376,12 +1386,13 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
     if (!attn_geometry_ok(lpr, R)) return VDC_EINVAL;
     const int C = cfg.n_cores, V = cfg.vcc_per_core;
     const int64_t units = (int64_t)C * V;
+    constexpr int64_t kMaxPieces = (int64_t)kAttnMaxPartials + 1;
     int64_t NT = 0;
     for (int s = 0; s < n_seg; s++) {
         const int64_t L = row_off[s + 1] - row_off[s];
         if (L < 1) return VDC_EINVAL;
         const int64_t T = (L + R - 1) / R;
-        if ((T + kAttnMaxPartials - 1) / kAttnMaxPartials > 65535) return VDC_EINVAL;
+        if ((T + kMaxPieces - 1) / kMaxPieces > 65535) return VDC_EINVAL;
         NT += T;
     }
     Tiler t{cfg, 0, 0, 0, 1, 1, 4};
@@ -1391,9 +1402,10 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
     const uint32_t kv_slots = t.slots_for((uint64_t)tile_bytes), q_slots = t.slots_for(row), w_slots = t.slots_for(prow);
     const uint32_t d_k = t.desc(0, R, row, row, row), d_v = t.desc(1, R, row, row, row), d_q = t.desc(2, 1, row, row, row);
     const uint32_t d_o = t.desc(3, 1, row, row, row), d_w = t.desc(4, 1, prow, prow, prow);
-    std::vector<std::vector<std::vector<Word>>> steps((size_t)units), merges((size_t)units);   // per compute core: groups of memory uops
-    struct SegItems { int64_t first, count, unit; };
-    std::vector<SegItems> seg_items((size_t)n_seg);
+    // per compute core: groups of memory uops that are dispatched together; signals: the group belongs to an item that
+    // signals a depId; waits: the group holds a load that waits for one
+    struct Group { std::vector<Word> uops; bool signals, waits; };
+    std::vector<std::vector<Group>> steps((size_t)units);
     // share u holds the tiles [u * NT / units, (u + 1) * NT / units) of the sequence of all tiles
     auto share_of = [&](int64_t g) { return std::min(units - 1, ((g + 1) * units - 1) / NT); };
     auto share_end = [&](int64_t u) { return (u + 1) * NT / units; };
@@ -1408,72 +1420,78 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
             cuts.push_back(t1);
             t0 = t1;
         }
-        if ((int64_t)cuts.size() - 1 > (int64_t)kAttnMaxPartials) {
-            const int64_t chunk = (T + kAttnMaxPartials - 1) / kAttnMaxPartials;
+        if ((int64_t)cuts.size() - 1 > kMaxPieces) {
+            const int64_t chunk = (T + kMaxPieces - 1) / kMaxPieces;
             cuts.assign(1, 0);
             for (int64_t t0 = 0; t0 < T; t0 += chunk) cuts.push_back(std::min(T, t0 + chunk));
         }
-        const bool whole = cuts.size() == 2;
-        seg_items[s].first = item;
-        seg_items[s].unit = -1;
+        const uint32_t others = (uint32_t)cuts.size() - 2;      // items of the context besides the first
+        if (others > kAttnMaxPartials) return VDC_EINVAL;
+        const int64_t first_partial = item;
         for (size_t ci = 0; ci + 1 < cuts.size(); ci++) {
             const int64_t t0 = cuts[ci], t1 = cuts[ci + 1];
             const int64_t u = share_of(tiles_before + t0);
-            if (seg_items[s].unit < 0) seg_items[s].unit = u;
             const int v = (int)(u % V);
+            const bool finishes = ci == 0, signals = !finishes;
             auto &st = steps[(size_t)u];
-            st.push_back({encode(OP_LOAD, F_SEND, t.flow_x(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_q, 0)});
+            st.push_back({{encode(OP_LOAD, F_SEND, t.flow_x(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_q, 0)}, signals, false});
             for (int64_t ti = t0; ti < t1; ti++) {
                 const int64_t r0 = row_off[s] + ti * R;
                 const uint32_t rv = (uint32_t)std::min<int64_t>(R, row_off[s + 1] - r0);
-                st.push_back({encode(OP_LOAD, F_SEND | F_NT, t.flow_m(v), v, 0, kv_slots, rv, 0, r0 * row, d_k, 0),
-                              encode(OP_LOAD, F_SEND | F_NT, t.flow_x(v), v, 0, kv_slots, rv, 0, r0 * row, d_v, 0)});
+                st.push_back({{encode(OP_LOAD, F_SEND | F_NT, t.flow_m(v), v, 0, kv_slots, rv, 0, r0 * row, d_k, 0),
+                               encode(OP_LOAD, F_SEND | F_NT, t.flow_x(v), v, 0, kv_slots, rv, 0, r0 * row, d_v, 0)}, signals, false});
             }
-            if (whole) {
-                st.push_back({encode(OP_STORE, F_SEND | F_RECV, t.flow_y(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_o, 0)});
+            if (finishes) {
+                std::vector<Word> g;
+                if (others > 0) {
+                    const uint32_t d_t = t.desc(4, others, prow, prow, prow);
+                    const uint32_t t_slots = t.slots_for((uint64_t)others * prow);
+                    if ((int)(t_slots + q_slots) > cfg.n_slots) return VDC_EINVAL;
+                    g.push_back(encode(OP_LOAD, F_SEND | F_DEP_RECV, t.flow_x(v), v, 0, t_slots, others, (uint32_t)s, first_partial * prow, d_t, others));
+                }
+                g.push_back(encode(OP_STORE, F_SEND | F_RECV, t.flow_y(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_o, 0));
+                st.push_back({g, false, others > 0});
             } else {
-                st.push_back({encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, t.flow_y(v), v, 0, w_slots, 1, (uint32_t)s, item * prow, d_w, 0)});
+                st.push_back({{encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, t.flow_y(v), v, 0, w_slots, 1, (uint32_t)s, item * prow, d_w, 0)}, true, false});
                 item++;
             }
-            t.vcc((int)(u / V), v).push_back(encode(OP_ATTN, 0, 0, 0, 0, 0, (uint32_t)(t1 - t0), 0, attn_imm(lpr, R, scale_bits), 0, 0));
+            t.vcc((int)(u / V), v).push_back(encode(OP_ATTN, 0, 0, 0, 0, 0, (uint32_t)(t1 - t0), 0, attn_imm(lpr, R, scale_bits), finishes ? others : 0u, 0));
         }
         tiles_before += T;
-        seg_items[s].count = item - seg_items[s].first;
-        if (seg_items[s].count > kAttnMaxPartials) return VDC_EINVAL;
     }
     n_items = std::max<int64_t>(item, 1);       // the workspace is never empty
-    for (int s = 0; s < n_seg; s++) {
-        const uint32_t P = (uint32_t)seg_items[s].count;
-        if (P == 0) continue;                   // the request's one item wrote the result
-        const int64_t u = seg_items[s].unit;
-        const int v = (int)(u % V);
-        const uint32_t d_t = t.desc(4, P, prow, prow, prow);
-        const uint32_t t_slots = t.slots_for((uint64_t)P * prow);
-        if ((int)(t_slots + q_slots) > cfg.n_slots) return VDC_EINVAL;
-        merges[(size_t)u].push_back({encode(OP_LOAD, F_SEND | F_DEP_RECV, t.flow_x(v), v, 0, t_slots, P, (uint32_t)s, seg_items[s].first * prow, d_t, P),
-                                     encode(OP_STORE, F_SEND | F_RECV, t.flow_y(v), v, 0, q_slots, 1, 0, (int64_t)s * row, d_o, 0)});
-        t.vcc((int)(u / V), v).push_back(encode(OP_ATTN_MERGE, 0, 0, 0, 0, 0, P, 0, (int64_t)lpr, 0, 0));
-    }
-    for (int c = 0; c < C; c++)
-        for (auto *lists : {&steps, &merges}) {
-            // the steps of the core's compute cores in turn, each list at its own pace, so that they end together (the
-            // lists of a core differ in length when contexts are uneven; strict alternation left one compute core alone
-            // at the end)
-            std::vector<size_t> at((size_t)V, 0);
-            for (;;) {
-                int pick = -1;
-                double best = 2.0;
-                for (int v = 0; v < V; v++) {
-                    const auto &l = (*lists)[(size_t)c * V + v];
-                    if (at[(size_t)v] >= l.size()) continue;
-                    const double prog = (double)at[(size_t)v] / (double)l.size();
-                    if (prog < best) { best = prog; pick = v; }
-                }
-                if (pick < 0) break;
-                const auto &g = (*lists)[(size_t)c * V + pick][at[(size_t)pick]++];
-                t.vmc(c).insert(t.vmc(c).end(), g.begin(), g.end());
+    for (int c = 0; c < C; c++) {
+        // the steps of the core's compute cores in turn, each list at its own pace, so that they end together (the
+        // lists of a core differ in length when contexts are uneven; strict alternation left one compute core alone
+        // at the end).  A group with a waiting load goes out only when every group of the core's signalling items has.
+        std::vector<size_t> at((size_t)V, 0);
+        auto signals_left = [&]() {
+            for (int v = 0; v < V; v++) {
+                const auto &l = steps[(size_t)c * V + v];
+                for (size_t i = at[(size_t)v]; i < l.size(); i++)
+                    if (l[i].signals) return true;
             }
+            return false;
+        };
+        for (;;) {
+            int pick = -1;
+            double best = 2.0;
+            bool held = false;
+            for (int v = 0; v < V; v++) {
+                const auto &l = steps[(size_t)c * V + v];
+                if (at[(size_t)v] >= l.size()) continue;
+                if (l[at[(size_t)v]].waits && signals_left()) { held = true; continue; }
+                const double prog = (double)at[(size_t)v] / (double)l.size();
+                if (prog < best) { best = prog; pick = v; }
+            }
+            if (pick < 0) {
+                if (held) return VDC_EINVAL;      // cannot happen: a list's signalling items stand before its waiting load
+                break;
+            }
+            const auto &g = steps[(size_t)c * V + pick][at[(size_t)pick]++];
+            t.vmc(c).insert(t.vmc(c).end(), g.uops.begin(), g.uops.end());
         }
+    }
     words.clear();
     sb.assign(1, 0);
     for (auto &st : t.streams) {

@@ -2321,7 +2321,7 @@ DEV float rows_reduce(float x) {
 // The query tile is allocated first and handed back last, after every key and value tile: slots return in another
 // order than they went out (Section 4.3).  Rows of a short last tile score minus infinity.
 template <int R, int LPR>
-DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
+DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale, uint32_t join) {
     constexpr int RP = R > 16 ? 16 : R;            // key rows per pass
     constexpr int NP = R / RP;                     // passes per tile
     constexpr uint32_t G = 64u / (uint32_t)RP;     // lanes per key row: 4 or 8
@@ -2395,6 +2395,38 @@ DEV bool attn_uop(Ctx &c, VccState &vs, uint32_t size, float scale) {
         vcc_done_with(c, vs, 2u, 0u);
     }
     vcc_return_kept(c, vs, q_pay);
+    if (join != 0u) {
+        // The context has `join` <= 64 other items: their partial rows (o, m, l, 0, 0) come as one more tile and are joined
+        // to this uop's own state, the same rescaling as from tile to tile.  Lane i takes row i's maximum and sum, so the
+        // weights are one exponential per lane; the weighted sum takes one LDS read per row, the weight from the scalar side.
+        constexpr uint32_t PROW = ROW + 16u;
+        Msg mt;
+        if (join > 64u) {
+            raise_error(c, -3 /* VDC_EPROGRAM */, 0xE50u);
+            return false;
+        }
+        if (!vcc_pop_wait(c, vs, 1u, 0u, mt, unused)) return false;
+        const uint32_t t_off = mt.slot << slot_shift;
+        const bool mine = c.lane < join;
+        const uint32_t r_off = t_off + (mine ? c.lane : 0u) * PROW + ROW;
+        const float mi = mine ? lds_ldf(r_off) : -__builtin_inff(), li = mine ? lds_ldf(r_off + 4u) : 0.0f;
+        float M = mi;
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) M = __builtin_fmaxf(M, __shfl_xor(M, s, 64));
+        M = __builtin_fmaxf(M, m);
+        const float w = mine ? expf(mi - M) : 0.0f, w_own = expf(m - M);
+        float ls = w * li;
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) ls += __shfl_xor(ls, s, 64);
+        l = __builtin_fmaf(l, w_own, ls);
+        o *= w_own;
+        for (uint32_t i = 0; i < join; i++) {
+            const float wi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), (int)i));
+            o = __builtin_fmaf(wi, lds_ldf(t_off + i * PROW + col * 4u), o);
+        }
+        m = M;
+        vcc_done_with(c, vs, 1u, 0u);
+    }
     Msg mo;
     if (!vcc_pop_wait(c, vs, 1u, 1u, mo, unused)) return false;
     const uint32_t out_off = mo.slot << slot_shift;
@@ -2476,14 +2508,14 @@ DEV void vcc_main(Ctx &c, uint32_t wv) {
         } else if ((OPS & OPS_ROPE) != 0u && f.opcode == OP_ROPE) {
             ok = rope_uop(c, vs, (uint32_t)f.imm & 0xFFu, (uint32_t)(f.imm >> 8) & 0xFFFFu);
         } else if ((OPS & OPS_ATTN) != 0u && f.opcode == OP_ATTN) {
-            const uint32_t lpr = (uint32_t)f.imm & 0xFFu, R = (uint32_t)(f.imm >> 8) & 0xFFu;
+            const uint32_t lpr = (uint32_t)f.imm & 0xFFu, R = (uint32_t)(f.imm >> 8) & 0xFFu, join = attn_join(f);
             const float scale = __builtin_bit_cast(float, (uint32_t)(f.imm >> 16));
-            if (lpr == 32u && R == 32u) ok = attn_uop<32, 32>(c, vs, f.size, scale);
-            else if (lpr == 32u && R == 16u) ok = attn_uop<16, 32>(c, vs, f.size, scale);
-            else if (lpr == 32u && R == 8u) ok = attn_uop<8, 32>(c, vs, f.size, scale);
-            else if (lpr == 16u && R == 64u) ok = attn_uop<64, 16>(c, vs, f.size, scale);
-            else if (lpr == 16u && R == 32u) ok = attn_uop<32, 16>(c, vs, f.size, scale);
-            else if (lpr == 16u && R == 16u) ok = attn_uop<16, 16>(c, vs, f.size, scale);
+            if (lpr == 32u && R == 32u) ok = attn_uop<32, 32>(c, vs, f.size, scale, join);
+            else if (lpr == 32u && R == 16u) ok = attn_uop<16, 32>(c, vs, f.size, scale, join);
+            else if (lpr == 32u && R == 8u) ok = attn_uop<8, 32>(c, vs, f.size, scale, join);
+            else if (lpr == 16u && R == 64u) ok = attn_uop<64, 16>(c, vs, f.size, scale, join);
+            else if (lpr == 16u && R == 32u) ok = attn_uop<32, 16>(c, vs, f.size, scale, join);
+            else if (lpr == 16u && R == 16u) ok = attn_uop<16, 16>(c, vs, f.size, scale, join);
             else {
                 raise_error(c, -3 /* VDC_EPROGRAM */, 0xE00u | f.opcode);
                 ok = false;
