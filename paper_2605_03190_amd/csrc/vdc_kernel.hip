@@ -1274,7 +1274,7 @@ struct LduEnt {
     uint32_t key;               // table | window lane, 0xffffffff = empty
     uint32_t val;               // the static record itself: lanes 0..7
     uint32_t ni;                // load instructions per tile
-    uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path | 32 DEVICE | lanes of a last, partial instruction << 8
+    uint32_t bits;              // 1 NT | 2 SEND | 4 DEP_SEND | 8 DEP_RECV | 16 fast path | 32 DEVICE | lanes of a last, partial instruction << 8 | chunks of zeros behind the run << 14
     uint32_t step_lo, step_hi;  // fast path: address step per load instruction
     uint32_t m2c_ready;         // LDS byte offset of the ready word of entry 0 of the compute core's m2c ring
     uint32_t off_lo, off_hi;    // fast path, per lane: offset of the lane's first chunk from the tile address
@@ -1292,11 +1292,13 @@ DEV void ldu_derive(Ctx &c, LduEnt &e, uint32_t key, uint32_t info) {
     const bool pow2 = (cpr & (cpr - 1u)) == 0u && cpr <= 64u;
     // a box whose rows follow each other without a gap, in memory as in the region, is one run of `total` chunks whatever
     // its row length: 64 chunks per instruction, and a last instruction of `tail` lanes
-    const bool contig = gpitch == (uint64_t)lds_pitch && row_bytes == lds_pitch && rows == box_rows;
-    const uint32_t tail = contig ? (total & 63u) : 0u;
+    // (a box with fewer valid rows than it has: the valid rows are the run, the rest of the box is filled with zeros)
+    const bool contig = gpitch == (uint64_t)lds_pitch && row_bytes == lds_pitch && rows <= box_rows && total - rows * cpr < 2048u;
+    const uint32_t run = rows * cpr, tail = contig ? (run & 63u) : 0u, zeros = contig ? total - run : 0u;
     const bool fast = (pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u) || contig;
+    if (contig) e.ni = (run + 63u) >> 6;
     e.bits = ((flags & F_NT) ? 1u : 0u) | ((flags & F_SEND) ? 2u : 0u) | ((flags & F_DEP_SEND) ? 4u : 0u) |
-             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u) | ((flags & F_DEVICE) ? 32u : 0u) | (tail << 8);
+             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u) | ((flags & F_DEVICE) ? 32u : 0u) | (tail << 8) | (zeros << 14);
     uint32_t sh = 0, drow = 0;
     if (pow2) { sh = __builtin_ctz(cpr); drow = 64u >> sh; }
     const uint64_t step = contig ? 1024ull : (uint64_t)drow * gpitch;
@@ -1387,9 +1389,10 @@ DEV void ldu_main(Ctx &c) {
             else { asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); vm_bound = 16; }
         }
         SEC_END(c, 2);
-        if (bits & 16u) {
-            // the usual case: whole tile, a power-of-two row of at most 64 chunks.  Every instruction moves 64 / cpr
-            // whole rows, so the per-lane address just advances by a uniform step
+        if ((bits & 0xFFFFFF10u) == 0x10u) {
+            // the usual case: whole tile, a power-of-two row of at most 64 chunks (or any gap-free run of whole
+            // instructions).  Every instruction moves 64 / cpr whole rows, so the per-lane address just advances by a
+            // uniform step
             const uint64_t off = (uint64_t)cur.off_lo | ((uint64_t)cur.off_hi << 32);
             const uint64_t step = (uint64_t)cur.step_lo | ((uint64_t)cur.step_hi << 32);
             uint32_t dst = lds_base + lds_off;
@@ -1403,19 +1406,18 @@ DEV void ldu_main(Ctx &c) {
                  "v_lshl_add_u64 %[g], %[g], 0, %[step]"                                                           \
                  : [g] "+v"(ga) : [dst] "s"(dst), [step] "s"(step) : "memory", "scc")
 #define VDC_LOAD_TILE(NT)                                                                                          \
-    for (; i + 4u <= nfull; i += 4u) {                                                                             \
+    for (; i + 4u <= ni; i += 4u) {                                                                                \
         VDC_LOAD4(NT);                                                                                             \
         dst += 4096u;                                                                                              \
         if (__builtin_expect((i & 31u) == 28u && i + 4u < ni, 0)) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); \
     }                                                                                                              \
-    for (; i < nfull; i++) {                                                                                       \
+    for (; i < ni; i++) {                                                                                          \
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" NT ::"s"(dst), "v"(ga) : "memory"); \
         dst += 1024u;                                                                                              \
         ga += step;                                                                                                \
     }
             uint64_t ga = gaddr + off;
             uint32_t i = 0;
-            const uint32_t tail = bits >> 8, nfull = tail ? ni - 1u : ni;
             if (bits & 32u) {
                 // device scope: the tile may have been written by another core during this run
                 VDC_LOAD_TILE(" sc1")
@@ -1426,9 +1428,29 @@ DEV void ldu_main(Ctx &c) {
             }
 #undef VDC_LOAD_TILE
 #undef VDC_LOAD4
-            if (__builtin_expect(tail != 0u, 0)) {
-                if (c.lane < tail) load_lds_b128(dst, (const char *)(uintptr_t)ga, (bits & 1u) != 0u, (bits & 32u) != 0u);
+        } else if (bits & 16u) {
+            // a gap-free run that ends inside an instruction (a query row, a few partial rows, the last tile of a context),
+            // and the rows of the box that the tensor does not have: those read as zero
+            const uint32_t tail = (bits >> 8) & 63u, zeros = bits >> 14, nfull = tail ? ni - 1u : ni;
+            const bool nt = (bits & 1u) != 0u, device = (bits & 32u) != 0u;
+            uint64_t ga = gaddr + ((uint64_t)cur.off_lo | ((uint64_t)cur.off_hi << 32));
+            uint32_t dst = lds_base + lds_off;
+            for (uint32_t i = 0; i < nfull; i++) {
+                load_lds_b128(dst, (const char *)(uintptr_t)ga, nt, device);
+                dst += 1024u;
+                ga += 1024u;
+                if ((i & 31u) == 31u && i + 1u < ni) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            }
+            if (tail != 0u) {
+                if (c.lane < tail) load_lds_b128(dst, (const char *)(uintptr_t)ga, nt, device);
                 reconverge();
+            }
+            if (zeros != 0u) {
+                // ordinary LDS writes of this wave: in place before the completing load is issued
+                const uint32_t z0 = lds_off + (nfull * 64u + tail) * 16u;
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                for (uint32_t i = c.lane; i < zeros; i += 64u) lds_st128(z0 + i * 16u, z);
+                lds_wait();
             }
         } else {
             const uint64_t gpitch = (uint64_t)rf_get(val, 0) | ((uint64_t)rf_get(val, 1) << 32);
@@ -1493,12 +1515,13 @@ DEV void ldu_main(Ctx &c) {
 // ------------------------------------------------------------------------------------------------
 // lanes 0,1 = next c2m entry of the unit's first VCC `ring0` (low, high), lanes 2,3 = of VCC 1 (looked at only by a unit
 // that serves both), lane 4 = uq_tail[u], lanes 5..8 = the record at `head`, lane 9 = cfu_halted, lane 10 = abort,
-// lane 11 = vcc_done, lane 12 = slot mask
+// lane 11 = vcc_done, lane 12 = slot mask, lane 13 = win_gen
 DEV uint32_t stu_poll(Ctx &c, uint32_t u, uint32_t ring0, uint32_t head, uint32_t c2m_head0, uint32_t c2m_head1) {
     const uint32_t e0 = c.ctl + CTL_OFF(c2m) + (ring0 * kC2M + (c2m_head0 & (kC2M - 1))) * 8u;
     const uint32_t e1 = c.ctl + CTL_OFF(c2m) + (kC2M + (c2m_head1 & (kC2M - 1))) * 8u;
     const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
     uint32_t off = c.ctl + CTL_OFF(mask);
+    off = c.lane == 13u ? c.ctl + CTL_OFF(win_gen) : off;
     off = c.lane == 11u ? c.ctl + CTL_OFF(vcc_done) : off;
     off = c.lane == 10u ? c.ctl + CTL_OFF(abort) : off;
     off = c.lane == 9u ? c.ctl + CTL_OFF(cfu_halted) : off;
@@ -1539,6 +1562,10 @@ DEV void stu_main(Ctx &c) {
     bool have = false;                              // a STORE has been picked up and is waiting
     uint32_t r_glo = 0, r_ghi = 0, r_info = 0, r_ticket = 0, stat = 0;
     uint32_t park_rf = 0, park_head = 0, park_tail = 0;   // regions a store.local took back, waiting for their load.local
+    // What the unit remembers of the STOREs it has seen, by window lane mod 8 (a loop body alternates between few): lane k =
+    // the key (table | window lane) of entry k, the first word of its uop, and whether it is a plain store of one gap-free
+    // run of 16-byte chunks (bit 31) with the chunk count.  Dropped when the front end has decoded a new window.
+    uint32_t ck_rf = 0xFFFFFFFFu, cw_rf = 0, ci_rf = 0, seen_gen = 0;
     Spin sp;
     bool ok = true;
     SEC_BEGIN(c);
@@ -1547,12 +1574,104 @@ DEV void stu_main(Ctx &c) {
         SEC_END(c, 3);
         // the c2m queues carry produced regions only (a compute core frees a used region itself, see vcc_done_with):
         // the poll brings the next entry of each along
-        const uint32_t snap = stu_poll(c, u, ring0, head, c2m_head0, c2m_head1);
+        uint32_t snap;
+        // ---- The usual STORE, one look each: nothing is held, the next record is a plain store of one gap-free run of
+        // 16-byte chunks whose region is the next message of its compute core.  What the unit knows of the uop comes from
+        // its register files; every condition is folded into one flag and one branch (a branch costs this target as much
+        // as four or five other instructions, taken or not); no second trip to local memory for the static record, no
+        // parking of the region, nothing per lane but the run's own reads and writes.
+        for (;;) {
+            snap = stu_poll(c, u, ring0, head, c2m_head0, c2m_head1);
+            if ((uint32_t)have | (uint32_t)(rf_get(snap, 4) == head)) break;      // an idle look stays short
+            const uint32_t info = rf_get(snap, 7), key = (info >> 6) & 0x7Fu, k = key & 7u;
+            const uint32_t ci = rf_get(ci_rf, k), w0 = rf_get(cw_rf, k);
+            const uint32_t vi = ((w0 >> 20) & 3u) - ring0, vs = vi < n_rings ? vi : 0u;
+            const uint32_t lo = rf_get(snap, vs * 2u), hi = rf_get(snap, vs * 2u + 1u), r_lo = rf_get(snap, 5);
+            const uint32_t ch = vs == 0u ? c2m_head0 : c2m_head1;
+            const uint32_t slot = info & 63u, nslots = (w0 >> 25) & 63u;
+            const uint32_t boxed = vs == 0u ? box_head0 ^ box_tail0 : box_head1 ^ box_tail1;   // regions the general path holds go first
+            const uint32_t stop = (rf_get(snap, 13) ^ seen_gen) | (rf_get(ck_rf, k) ^ key) |
+                                  (~ci >> 31) | (uint32_t)(vi >= n_rings) | (r_lo & 15u) | boxed | (hi ^ (ch + 1u)) |
+                                  (lo ^ (1u | (slot << 1) | (nslots << 7))) | rf_get(snap, 10);
+            if (stop != 0u) break;
+#ifdef VDC_PROFILE_WAITS
+            c.w_wait++;
+#endif
+            const uint64_t gaddr = (uint64_t)r_lo | ((uint64_t)rf_get(snap, 6) << 32);
+            const uint32_t total = ci & 0xFFFFu, lds_off = slot << slot_shift;
+            head++;
+            done++;
+            c2m_head0 += vs == 0u ? 1u : 0u;
+            c2m_head1 += vs == 0u ? 0u : 1u;
+            lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_head) + u * 4u, head);     // the record has been read: its place is free
+            uint32_t i0 = 0;
+            do {
+                f32x4 v[4];
+                uint64_t on[4];
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const uint32_t i = i0 + (uint32_t)q * 64u + c.lane;
+                    const bool in = i < total;
+                    on[q] = __ballot(in);
+                    v[q] = lds_ld128(lds_off + (in ? i : 0u) * 16u);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; q++) gst128_lanes(on[q], gaddr + (uint64_t)(i0 + (uint32_t)q * 64u + c.lane) * 16u, v[q]);
+                i0 += 256u;
+            } while (i0 < total);
+            // the data is in registers on its way out: the region is free as soon as the reads have returned
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            lds_and32_lanes(1ull, c.ctl + CTL_OFF(mask), ~slot_bits(slot, nslots));
+            lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_done) + u * 4u, done);
+            sp.n = 0;
+        }
         PHASE(c, 1u + u, 2u);
 #ifdef VDC_PROFILE_SECTIONS
         { const uint32_t snap_ = snap; asm volatile("s_waitcnt lgkmcnt(0)" :: "v"(snap_) : "memory"); }
 #endif
         SEC_END(c, 0);
+        // Why the loop above stopped, where that is for this unit to mend: a new window (what is remembered is dropped), a
+        // uop seen for the first time (its static record is read, once), a region that is still with the compute core
+        // (wait for it here).  Everything else (other kinds of STORE, local uops, nothing to do, leaving) is the
+        // general path's, below.
+        if (!have && rf_get(snap, 4) != head) {
+            const uint32_t gen = rf_get(snap, 13);
+            const bool new_window = gen != seen_gen;
+            if (__builtin_expect(new_window, 0)) { seen_gen = gen; ck_rf = 0xFFFFFFFFu; }
+            const uint32_t info = rf_get(snap, 7), key = (info >> 6) & 0x7Fu, k = key & 7u;
+            if (__builtin_expect(rf_get(ck_rf, k) != key, 0)) {
+                const uint32_t sr = stat_fetch(c, info);
+                const uint32_t gp_lo = rf_get(sr, 0), gp_hi = rf_get(sr, 1), rows = rf_get(sr, 2) & 0xFFFFu, rb_pitch = rf_get(sr, 3), w0s = rf_get(sr, 4);
+                const uint32_t rb = rb_pitch & 0xFFFFu, lp = rb_pitch >> 16, fl = (w0s >> 8) & 0xFFu;
+                const bool plain = (w0s & 0xFFu) == (uint32_t)OP_STORE && (fl & ~(uint32_t)(F_SEND | F_DYNAMIC | F_NT)) == (uint32_t)F_RECV;
+                const bool run = (rb & 15u) == 0u && rb != 0u && (rows == 1u || (gp_hi == 0u && gp_lo == rb && lp == rb));
+                const uint32_t chunks = rows * (rb >> 4);
+                ck_rf = rf_set(ck_rf, k, key);
+                cw_rf = rf_set(cw_rf, k, w0s);
+                ci_rf = rf_set(ci_rf, k, (plain && run && chunks != 0u && chunks < 0x10000u ? 0x80000000u : 0u) | (chunks & 0xFFFFu));
+                continue;
+            }
+            const uint32_t ci = rf_get(ci_rf, k), w0 = rf_get(cw_rf, k);
+            const uint32_t vi = ((w0 >> 20) & 3u) - ring0;
+            if ((ci >> 31) != 0u && vi < n_rings && (rf_get(snap, 5) & 15u) == 0u && (vi == 0u ? box_head0 == box_tail0 : box_head1 == box_tail1)) {
+                if (new_window) continue;
+                // (a message that is there and is not the region this STORE names is the general path's to report)
+                const uint32_t ch = vi == 0u ? c2m_head0 : c2m_head1;
+                if (rf_get(snap, vi * 2u + 1u) != ch + 1u) {
+                    // wait for that one message and look at nothing else meanwhile: a short look, so that the compute wave
+                    // on this SIMD keeps its issue slots
+                    PHASE(c, 1u + u, 6u);
+                    const uint32_t e_hi = c.ctl + CTL_OFF(c2m) + ((ring0 + vi) * kC2M + (ch & (kC2M - 1))) * 8u + 4u;
+                    const uint32_t w_off = c.lane == 0u ? e_hi : c.ctl + CTL_OFF(abort);
+                    for (;;) {
+                        const uint32_t two = lds_vld32(w_off);
+                        if (rf_get(two, 0) == ch + 1u) break;
+                        if (!spin_step(c, sp, rf_get(two, 1), 0x780u)) { ok = false; break; }
+                    }
+                    continue;
+                }
+            }
+        }
         bool moved = stu_receive(c, rf_get(snap, 0), rf_get(snap, 1), c2m_head0, box_rf0, box_tail0);
         if (n_rings > 1u) moved = stu_receive(c, rf_get(snap, 2), rf_get(snap, 3), c2m_head1, box_rf1, box_tail1) || moved;
         if (moved) OBS(c, 5u, c2m_head0 | (c2m_head1 << 16));
