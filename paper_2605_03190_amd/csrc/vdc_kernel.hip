@@ -1516,10 +1516,15 @@ DEV void ldu_main(Ctx &c) {
 // lanes 0,1 = next c2m entry of the unit's first VCC `ring0` (low, high), lanes 2,3 = of VCC 1 (looked at only by a unit
 // that serves both), lane 4 = uq_tail[u], lanes 5..8 = the record at `head`, lane 9 = cfu_halted, lane 10 = abort,
 // lane 11 = vcc_done, lane 12 = slot mask, lane 13 = win_gen
-DEV uint32_t stu_poll(Ctx &c, uint32_t u, uint32_t ring0, uint32_t head, uint32_t c2m_head0, uint32_t c2m_head1) {
-    const uint32_t e0 = c.ctl + CTL_OFF(c2m) + (ring0 * kC2M + (c2m_head0 & (kC2M - 1))) * 8u;
-    const uint32_t e1 = c.ctl + CTL_OFF(c2m) + (kC2M + (c2m_head1 & (kC2M - 1))) * 8u;
-    const uint32_t rec = c.ctl + CTL_OFF(uq) + (u * kUQ + (head & (kUQ - 1))) * (uint32_t)sizeof(UnitRec);
+// Each lane's offset is a fixed part plus its share of the three positions that move (the record at `head`, the next
+// message of each c2m queue): worked out once, three multiply-adds per look.
+struct StuPoll {
+    uint32_t base, k_rec, k_e0, k_e1;   // per lane: fixed offset, and bytes per step of head / c2m_head0 / c2m_head1
+};
+DEV StuPoll stu_poll_init(Ctx &c, uint32_t u, uint32_t ring0) {
+    StuPoll p;
+    const uint32_t e0 = c.ctl + CTL_OFF(c2m) + ring0 * kC2M * 8u, e1 = c.ctl + CTL_OFF(c2m) + kC2M * 8u;
+    const uint32_t rec = c.ctl + CTL_OFF(uq) + u * kUQ * (uint32_t)sizeof(UnitRec);
     uint32_t off = c.ctl + CTL_OFF(mask);
     off = c.lane == 13u ? c.ctl + CTL_OFF(win_gen) : off;
     off = c.lane == 11u ? c.ctl + CTL_OFF(vcc_done) : off;
@@ -1529,7 +1534,14 @@ DEV uint32_t stu_poll(Ctx &c, uint32_t u, uint32_t ring0, uint32_t head, uint32_
     off = c.lane == 4u ? c.ctl + CTL_OFF(uq_tail) + u * 4u : off;
     off = c.lane < 4u ? e1 + (c.lane - 2u) * 4u : off;
     off = c.lane < 2u ? e0 + c.lane * 4u : off;
-    return lds_vld32(off);
+    p.base = off;
+    p.k_rec = (c.lane >= 5u && c.lane <= 8u) ? (uint32_t)sizeof(UnitRec) : 0u;
+    p.k_e0 = c.lane < 2u ? 8u : 0u;
+    p.k_e1 = (c.lane >= 2u && c.lane < 4u) ? 8u : 0u;
+    return p;
+}
+DEV uint32_t stu_poll(const StuPoll &p, uint32_t head, uint32_t c2m_head0, uint32_t c2m_head1) {
+    return lds_vld32(p.base + p.k_rec * (head & (kUQ - 1)) + p.k_e0 * (c2m_head0 & (kC2M - 1)) + p.k_e1 * (c2m_head1 & (kC2M - 1)));
 }
 
 // Take the next message of one c2m queue out of the snapshot: a used region goes back to the pool (Section 4.3:
@@ -1566,6 +1578,8 @@ DEV void stu_main(Ctx &c) {
     // the key (table | window lane) of entry k, the first word of its uop, and whether it is a plain store of one gap-free
     // run of 16-byte chunks (bit 31) with the chunk count.  Dropped when the front end has decoded a new window.
     uint32_t ck_rf = 0xFFFFFFFFu, cw_rf = 0, ci_rf = 0, seen_gen = 0;
+    const StuPoll poll = stu_poll_init(c, u, ring0);
+    const uint32_t pub_off = c.ctl + (c.lane == 0u ? CTL_OFF(uq_head) : CTL_OFF(uq_done)) + u * 4u;
     Spin sp;
     bool ok = true;
     SEC_BEGIN(c);
@@ -1581,7 +1595,7 @@ DEV void stu_main(Ctx &c) {
         // as four or five other instructions, taken or not); no second trip to local memory for the static record, no
         // parking of the region, nothing per lane but the run's own reads and writes.
         for (;;) {
-            snap = stu_poll(c, u, ring0, head, c2m_head0, c2m_head1);
+            snap = stu_poll(poll, head, c2m_head0, c2m_head1);
             if ((uint32_t)have | (uint32_t)(rf_get(snap, 4) == head)) break;      // an idle look stays short
             const uint32_t info = rf_get(snap, 7), key = (info >> 6) & 0x7Fu, k = key & 7u;
             const uint32_t ci = rf_get(ci_rf, k), w0 = rf_get(cw_rf, k);
@@ -1603,7 +1617,6 @@ DEV void stu_main(Ctx &c) {
             done++;
             c2m_head0 += vs == 0u ? 1u : 0u;
             c2m_head1 += vs == 0u ? 0u : 1u;
-            lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_head) + u * 4u, head);     // the record has been read: its place is free
             uint32_t i0 = 0;
             do {
                 f32x4 v[4];
@@ -1622,7 +1635,7 @@ DEV void stu_main(Ctx &c) {
             // the data is in registers on its way out: the region is free as soon as the reads have returned
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             lds_and32_lanes(1ull, c.ctl + CTL_OFF(mask), ~slot_bits(slot, nslots));
-            lds_st32_lanes(1ull, c.ctl + CTL_OFF(uq_done) + u * 4u, done);
+            lds_st32_lanes(3ull, pub_off, c.lane == 0u ? head : done);         // the record's place in the ring is free, the STORE is done
             sp.n = 0;
         }
         PHASE(c, 1u + u, 2u);
@@ -1827,7 +1840,7 @@ DEV void stu_main(Ctx &c) {
         // nothing to do right now.  The store units leave last: the front end has halted, every STORE is written, the
         // compute cores are done and the unit's c2m queues are empty.
         if (!have && rf_get(snap, 9) && rf_get(snap, 11) == 2u * V && uni(lds_vld32(c.ctl + CTL_OFF(uq_tail) + u * 4u)) == head) {
-            const uint32_t last = stu_poll(c, u, ring0, head, c2m_head0, c2m_head1);
+            const uint32_t last = stu_poll(poll, head, c2m_head0, c2m_head1);
             const bool more = rf_get(last, 1) == c2m_head0 + 1u || (n_rings > 1u && rf_get(last, 3) == c2m_head1 + 1u);
             if (!more) break;
             continue;
