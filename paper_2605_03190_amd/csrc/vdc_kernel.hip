@@ -1290,29 +1290,22 @@ DEV void ldu_derive(Ctx &c, LduEnt &e, uint32_t key, uint32_t info) {
     const uint32_t flags = (w0 >> 8) & 0xFFu, vcc = (w0 >> 20) & 3u;
     e.ni = (total + 63u) >> 6;
     const bool pow2 = (cpr & (cpr - 1u)) == 0u && cpr <= 64u;
-    uint32_t fast = (pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u) ? 16u : 0u;
+    // a box whose rows follow each other without a gap, in memory as in the region, is one run of `total` chunks whatever
+    // its row length: 64 chunks per instruction, and a last instruction of `tail` lanes
+    // (a box with fewer valid rows than it has: the valid rows are the run, the rest of the box is filled with zeros)
+    const bool contig = gpitch == (uint64_t)lds_pitch && row_bytes == lds_pitch && rows <= box_rows && total - rows * cpr < 2048u;
+    const uint32_t run = rows * cpr, tail = contig ? (run & 63u) : 0u, zeros = contig ? total - run : 0u;
+    const bool fast = (pow2 && rows == box_rows && vcr == cpr && (total & 63u) == 0u) || contig;
+    if (contig) e.ni = (run + 63u) >> 6;
+    e.bits = ((flags & F_NT) ? 1u : 0u) | ((flags & F_SEND) ? 2u : 0u) | ((flags & F_DEP_SEND) ? 4u : 0u) |
+             ((flags & F_DEP_RECV) ? 8u : 0u) | (fast ? 16u : 0u) | ((flags & F_DEVICE) ? 32u : 0u) | (tail << 8) | (zeros << 14);
     uint32_t sh = 0, drow = 0;
     if (pow2) { sh = __builtin_ctz(cpr); drow = 64u >> sh; }
-    uint64_t step = (uint64_t)drow * gpitch;
-    uint64_t off = (uint64_t)(c.lane >> sh) * gpitch + (uint64_t)(c.lane & (cpr - 1u)) * 16u;
-    // (streams without loops come here for every tile: the usual tile pays for nothing below)
-    if (__builtin_expect(fast == 0u, 0)) {
-        // A box whose rows follow each other without a gap, in memory as in the region, is one run of chunks whatever its
-        // row length: 64 chunks per instruction and a last instruction of `tail` lanes.  With fewer valid rows than the
-        // box has, the valid rows are the run and the rest of the box is filled with zeros.
-        const uint32_t run = rows * cpr;
-        if (gpitch == (uint64_t)lds_pitch && row_bytes == lds_pitch && rows <= box_rows && total - run < 2048u) {
-            fast = 16u | ((run & 63u) << 8) | ((total - run) << 14);
-            e.ni = (run + 63u) >> 6;
-            step = 1024ull;
-            off = (uint64_t)c.lane * 16u;
-        }
-    }
-    e.bits = ((flags & F_NT) ? 1u : 0u) | ((flags & F_SEND) ? 2u : 0u) | ((flags & F_DEP_SEND) ? 4u : 0u) |
-             ((flags & F_DEP_RECV) ? 8u : 0u) | fast | ((flags & F_DEVICE) ? 32u : 0u);
+    const uint64_t step = contig ? 1024ull : (uint64_t)drow * gpitch;
     e.step_lo = (uint32_t)step;
     e.step_hi = (uint32_t)(step >> 32);
     e.m2c_ready = c.ctl + CTL_OFF(m2c) + vcc * kM2C * (uint32_t)sizeof(M2cEnt) + (uint32_t)offsetof(M2cEnt, ready);
+    const uint64_t off = contig ? (uint64_t)c.lane * 16u : (uint64_t)(c.lane >> sh) * gpitch + (uint64_t)(c.lane & (cpr - 1u)) * 16u;
     e.off_lo = (uint32_t)off;
     e.off_hi = (uint32_t)(off >> 32);
 }
