@@ -274,16 +274,20 @@ int vdc_matvec_chain_program(vdc_executor *ex, const int64_t *dims, int32_t L, i
  * 16-byte aligned, caller-owned; row_off: host, n_seg + 1 offsets, row_off[0] = 0, every request at least one row.
  * d = 128 or 64; tile_bytes in {4096, 8192, 16384} (tile_bytes / (4 d) context rows per key / value tile);
  * n_seg <= n_dep_ids.  scale > 0, or scale <= 0 for the usual d^(-1/2) (computed in fp32 as 1 / sqrtf(d)).
- * A context is cut into items of consecutive tiles that balance over the compute cores; every item leaves a partial row
- * (weighted values, running maximum, running sum) in a library-owned workspace and signals the request's depId; one
- * compute core per request merges its rows.  fp32 arithmetic, exp() of differences to the running maximum only.
+ * The tiles of all contexts, in order, are dealt to the compute cores in equal contiguous shares.  A context inside one
+ * share is one item whose attn uop writes the request's result itself.  A context that crosses shares is cut where they
+ * meet: its later items leave partial rows (weighted values, running maximum, running sum) in a library-owned workspace
+ * and signal the request's depId; its first item loads those rows behind its last tile pair, joins them to its own
+ * running state and writes the result (at most 64 partial rows per request; a longer context is cut into 65 equal
+ * items).  fp32 arithmetic, exp() of differences to the running maximum only.
  * Asynchronous on hip_stream; programs are cached by (row_off, d, scale, tile_bytes).  Errors: VDC_EINVAL (arguments),
  * VDC_ENOMEM, VDC_EPROGRAM, VDC_EDEVICE. */
 int vdc_attn_decode(vdc_executor *ex, const float *Q, const float *K, const float *V, const int64_t *row_off,
                     int32_t n_seg, int32_t d, float scale, float *O, int32_t tile_bytes, void *hip_stream);
 
 /* The uop program vdc_attn_decode runs, handed out like vdc_matvec_program does.  Tensors: 0 = K, 1 = V, 2 = Q, 3 = O,
- * 4 = the workspace of *n_items rows of d + 4 floats (no initial content needed). */
+ * 4 = the workspace of *n_items rows of d + 4 floats (no initial content needed; one row per item that leaves a partial
+ * row, at least one). */
 int vdc_attn_decode_program(vdc_executor *ex, const int64_t *row_off, int32_t n_seg, int32_t d, float scale,
                             int32_t tile_bytes, void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs,
                             int32_t *n_descs, int64_t *n_items);
