@@ -538,6 +538,39 @@ def test_attention_traces_match_the_interpreter_and_oracle_assembled_programs_ru
         ex.check()
         _check_attn(dO.cpu().numpy(), Q, K, V, ro, d ** -0.5, "oracle-assembled program")
         prog.destroy()
+        # the oracle-side assembler's other forms: contexts of one item write their result themselves, and the first item
+        # of a cut context joins the others' partial rows (no ATTN_MERGE)
+        for chunk in (3, 6):
+            p, n_items = A.attn_decode_program(ro, d, 8, 4096, 4, chunk_tiles=chunk, whole=True, join=True)
+            words, sb, descs = p.finish()
+            assert not any((int(w0) & 0xFF) == A.ATTN_MERGE for w0 in np.asarray(words).reshape(-1, 4)[:, 0])
+            n_w = max(n_items, 1)
+            prog = ex.program_create(words, sb, descs, [K.nbytes, V.nbytes, Q.nbytes, Q.nbytes, n_w * (d + 4) * 4])
+            dO.fill_(float("nan"))
+            dW = torch.full((n_w, d + 4), float("nan"), device="cuda")
+            ex.run(prog, [_dev(K), _dev(V), _dev(Q), dO, dW])
+            ex.check()
+            _check_attn(dO.cpu().numpy(), Q, K, V, ro, d ** -0.5, "oracle-assembled program, whole contexts and joins, items of %d tiles" % chunk)
+            prog.destroy()
+
+
+def test_attention_shares_at_their_limits():
+    # more contexts than tiles in a share (most compute cores hold several whole contexts, some none); one context over
+    # more compute cores than a request may have partial rows (it is cut into 65 equal items instead of at the shares)
+    rng = np.random.default_rng(12)
+    for lengths, T, ncores, d in ((list(rng.integers(1, 4, 700)), 4096, 0, 128), ([40000], 4096, 40, 128), ([9000, 5, 30000], 8192, 48, 64)):
+        Q, K, V, ro = _attn_inputs(lengths, seed=len(lengths), d=d)
+        with (vdc.Executor() if ncores == 0 else vdc.Executor(n_cores=ncores)) as ex:
+            words, sb, descs, n_items = ex.attn_decode_program(ro, d, T)
+            ops = np.asarray(words).reshape(-1, 4)[:, 0] & 0xFF
+            joins = (np.asarray(words).reshape(-1, 4)[:, 3] >> 16) & 0xFF
+            assert int(joins[ops == A.ATTN].max()) <= 64
+            if lengths == [40000]:
+                assert int(joins[ops == A.ATTN].max()) == 64 and int((ops == A.ATTN).sum()) == 65
+            dO = torch.full((len(lengths), d), float("nan"), device="cuda")
+            ex.attn_decode(_dev(Q), _dev(K), _dev(V), ro, dO, T)
+            ex.check()
+            _check_attn(dO.cpu().numpy(), Q, K, V, ro, d ** -0.5, "attention at the limits of the shares, %d contexts" % len(lengths))
 
 
 def test_attention_refuses_what_it_does_not_support(ex):
