@@ -140,7 +140,9 @@ def test_short_k_programs_cover_several_row_blocks_per_uop(lengths, k4, B, tile,
         m.check_final()
         Yr, Ya = gemv_ref.gemv_ragged(M, ro, X) if ragged else gemv_ref.gemv_dense(M, X)
         assert np.all(np.abs(Y - Yr) <= 2e-6 * Ya + 1e-30)
-        mv = w[(w[:, 0] & 0xFF) == 16]
+        # the MATVECs as executed (a stretch of whole groups is a loop): their words through the compute cores' traces
+        V = 2
+        mv = [w[sb[c * (1 + V) + 1 + v] + r[0]] for c in range(ncores) for v in range(V) for r in m.trace_vcc[c][v] if r[1] == 16]
         spans = [(int(x[3]) >> 16) & 0xFF for x in mv]
         if max(spans) >= 2:
             loads_x = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 1)
