@@ -67,7 +67,12 @@ typedef struct {
                             /* measuring the issue path (Section 6.3); no effect on results              */
     int32_t issue_flags;    /* bit 0: the front end does not replay loop bodies, every trip is decoded   */
                             /* and dispatched through its general path (same purpose); other bits zero   */
-    int32_t reserved[3];    /* must be zero                                                           */
+    int32_t sched_threshold_pct; /* adaptive tiling (Section 4.2): a critical path is dominant when it costs more  */
+                            /* than (100 + this) % of the average per compute core; 0 => 10                   */
+    int32_t sched_min_gain_pct;  /* a finer tiling is taken only if it shortens its operator by at least this many */
+                            /* per cent of the path; 0 => 3                                                   */
+    int32_t sched_force_parts;   /* 0: adaptive.  n >= 1: no scheduling, every matvec cuts K into min(n, what it    */
+                            /* may) ranges; for measuring the cost model.  No effect on what is computed      */
 } vdc_config;
 
 /* Create the executor on cfg->device (Section 4.3: the cores every run launches once as a persistent
@@ -358,6 +363,44 @@ int vdc_graph_lower(vdc_executor *ex, const vdc_graph_memop *ops, int64_t n_ops,
                     uint32_t temp_tensors, int32_t geom_tensor, const int64_t *tensor_bytes, int32_t n_tensors,
                     void *uops_out, int64_t *n_uops, uint32_t *stream_begin, void *descs_out, int32_t *n_descs_out,
                     int32_t *stats);
+
+/* ---- the generator's adaptive tiling step (Section 4.2, "Adaptive Scheduling and Tiling") ----
+ *
+ * The operators of a graph are scheduled onto the virtual cores in their coarsest decompositions; while the longest path
+ * through the operator DAG costs more than the average per compute core by more than the threshold (a dominant critical
+ * path), the operator on it whose finer tiling shortens it most takes that tiling, until the best gain is marginal or
+ * nothing finer is left.  An operator is a matvec of n_blocks row blocks over nk tile steps of K; decomposition S cuts
+ * the K range of every row block into S ranges (range s = steps [nk s / S, nk (s + 1) / S)), the items in the order
+ * (range, row block) are dealt in contiguous shares (core c: items [NI c / C, NI (c + 1) / C), to its compute cores in
+ * turn), the items of ranges 0 .. S - 2 store partial sums and signal, the item of the last range joins them. */
+typedef struct {
+    int64_t n_blocks;   /* row blocks, >= 1                                                                   */
+    int64_t nk;         /* tile steps along K per row block, >= 1                                             */
+    int32_t max_parts;  /* finest decomposition the operator's builder offers, 1 .. nk                        */
+    int32_t reserved;   /* zero                                                                               */
+} vdc_sched_op;
+
+typedef struct {        /* integers in one unit of the caller's choice (the library's own model: nanoseconds) */
+    int64_t step;       /* one tile step of a compute core (matrix tile and vector tile loaded and used), >= 1 */
+    int64_t item;       /* per work item on top of its steps: output region, row sums, store                  */
+    int64_t join;       /* per partial result that a joining item adds                                        */
+    int64_t edge;       /* from the end of a producing item to the moment the joining item can use its result */
+} vdc_cost_model;
+
+/* parts[o] (host, n_ops) = the decomposition chosen for operator o.  ops (host); pred_begin (host, n_ops + 1 offsets
+ * into preds) and preds (host): the operators that must have ended before operator o starts, all with indices below o;
+ * both may be NULL (no edges).  cost: NULL selects the library's model for tiles of tile_bytes (otherwise tile_bytes is
+ * ignored).  Threshold and margin are the executor's (sched_threshold_pct, sched_min_gain_pct).  log (host, may be
+ * NULL): 5 words per look at the graph: path cost, average per compute core, refined operator or -1, its new S, gain;
+ * *n_looks: capacity in looks on entry, looks taken on return (n_looks may be NULL when log is).  Works on a host-only
+ * executor.  VDC_EINVAL for anything malformed (an operator with more than 2^24 items among them). */
+int vdc_schedule(vdc_executor *ex, const vdc_sched_op *ops, int32_t n_ops, const int32_t *pred_begin, const int32_t *preds,
+                 const vdc_cost_model *cost, int32_t tile_bytes, int32_t *parts, int64_t *log, int32_t *n_looks);
+
+/* What the matvec tiler decides for a dense shape (vdc_matvec, vdc_matvec_program): out (host, 6 words) = rows per
+ * matrix tile, tile width in floats, row blocks, tile steps along K, the finest K cut the shape allows (1: the tiler
+ * has no other decomposition for it), the cut taken.  Works on a host-only executor. */
+int vdc_matvec_tiling(vdc_executor *ex, int64_t rows, int64_t K, int32_t B, int32_t tile_bytes, int64_t *out);
 
 /* Run the slot allocator of the VMC (Section 4.3, "Virtual Memory Core": the first run of contiguous free slots in
  * the availability mask) on n independent (mask, nslots) requests with a pool of n_slots slots:

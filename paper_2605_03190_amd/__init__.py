@@ -27,7 +27,16 @@ class VdcError(RuntimeError):
 class vdc_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "device", "n_cores", "vcc_per_core", "threads_per_eu", "slot_bytes", "n_slots", "n_ldu", "n_stu",
-        "n_dep_ids", "watchdog_spins", "tile_rows", "issue_batch", "issue_flags")] + [("reserved", ctypes.c_int32 * 3)]
+        "n_dep_ids", "watchdog_spins", "tile_rows", "issue_batch", "issue_flags", "sched_threshold_pct", "sched_min_gain_pct",
+        "sched_force_parts")]
+
+
+class vdc_sched_op(ctypes.Structure):
+    _fields_ = [("n_blocks", ctypes.c_int64), ("nk", ctypes.c_int64), ("max_parts", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class vdc_cost_model(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("step", "item", "join", "edge")]
 
 
 _lib = None
@@ -78,6 +87,8 @@ def lib():
             "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
             "vdc_graph_lower": [vp, vp, i64, vp, i64, vp, vp, vp, i32, ctypes.c_uint32, i32, vp, i32, vp, ctypes.POINTER(i64), vp, vp,
                                 ctypes.POINTER(i32), vp],
+            "vdc_schedule": [vp, vp, i32, vp, vp, vp, i32, vp, vp, ctypes.POINTER(i32)],
+            "vdc_matvec_tiling": [vp, i64, i64, i32, i32, vp],
         }
         for name, args in sig.items():
             f = getattr(L, name)
@@ -94,7 +105,7 @@ EXPORTS = ["vdc_create", "vdc_destroy", "vdc_get_config", "vdc_program_create", 
            "vdc_resident_start", "vdc_resident_submit", "vdc_resident_wait", "vdc_resident_state", "vdc_resident_stop", "vdc_matvec", "vdc_matvec_noalloc", "vdc_matvec_ragged",
            "vdc_matvec_program", "vdc_matvec_rope", "vdc_matvec_rope_program", "vdc_matvec_workspace", "vdc_matvec_chain", "vdc_matvec_chain_program", "vdc_attn_decode", "vdc_attn_decode_program",
            "vdc_stream", "vdc_raw_stream",
-           "vdc_stream_program", "vdc_debug_alloc", "vdc_graph_lower", "vdc_strerror"]
+           "vdc_stream_program", "vdc_debug_alloc", "vdc_graph_lower", "vdc_schedule", "vdc_matvec_tiling", "vdc_strerror"]
 
 
 def strerror(code):
@@ -318,6 +329,35 @@ class Executor:
         if n.value:
             _check(lib().vdc_matvec_workspace(self.handle, rows, K, ld, B, tile_bytes, _np_ptr(ws), ctypes.byref(n)), "vdc_matvec_workspace")
         return ws
+
+    def matvec_tiling(self, rows, K, B, tile_bytes):
+        """vdc_matvec_tiling: (rows per tile, tile width, row blocks, steps along K, finest K cut offered, K cut taken)."""
+        out = np.zeros(6, dtype=np.int64)
+        _check(lib().vdc_matvec_tiling(self.handle, rows, K, B, tile_bytes, _np_ptr(out)), "vdc_matvec_tiling")
+        return tuple(int(x) for x in out)
+
+    def schedule(self, ops, preds=None, cost=None, tile_bytes=16384):
+        """vdc_schedule: ops = [(n_blocks, nk, max_parts)], preds = per operator the operators it waits for, cost =
+        (step, item, join, edge) or None for the library's model.  Returns (parts, log) with log = [(path cost, average,
+        refined operator or -1, new S, gain)]."""
+        n = len(ops)
+        arr = (vdc_sched_op * max(n, 1))()
+        for o, (nb, nk, mp) in enumerate(ops):
+            arr[o] = vdc_sched_op(nb, nk, mp, 0)
+        pb = pr = None
+        if preds is not None:
+            pb = np.zeros(n + 1, dtype=np.int32)
+            pb[1:] = np.cumsum([len(p) for p in preds])
+            pr = np.array([q for p in preds for q in p] + [0], dtype=np.int32)
+        cm = vdc_cost_model(*cost) if cost is not None else None
+        parts = np.zeros(max(n, 1), dtype=np.int32)
+        cap = 2 + sum(mp for _, _, mp in ops)
+        log = np.zeros((cap, 5), dtype=np.int64)
+        looks = ctypes.c_int32(cap)
+        _check(lib().vdc_schedule(self.handle, ctypes.cast(arr, ctypes.c_void_p), n, _np_ptr(pb) if pb is not None else None,
+                                  _np_ptr(pr) if pr is not None else None, ctypes.cast(ctypes.pointer(cm), ctypes.c_void_p) if cm else None,
+                                  tile_bytes, _np_ptr(parts), _np_ptr(log), ctypes.byref(looks)), "vdc_schedule")
+        return [int(x) for x in parts[:n]], [tuple(int(x) for x in r) for r in log[:looks.value]]
 
     def matvec_chain(self, W, A, dims, B, tile_bytes, stream=None):
         """Y_0 = M_0 X, Y_l = M_l Y_(l-1) in one launch.  W: the matrices back to back; A: X then every Y_l, back to back

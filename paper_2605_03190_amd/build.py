@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 SO = os.path.join(HERE, "libvdcores.so")
 KERNEL = os.path.join(HERE, "csrc", "vdc_kernel.hip")
-HOST = [os.path.join(HERE, "csrc", "vdc_host.cpp"), os.path.join(HERE, "csrc", "vdc_lower.cpp")]
+HOST = [os.path.join(HERE, "csrc", f) for f in ("vdc_host.cpp", "vdc_lower.cpp", "vdc_sched.cpp")]
 SOURCES = [KERNEL] + HOST
 N_VARIANTS = 6      # kVariants in csrc/vdc_kernel.hip
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

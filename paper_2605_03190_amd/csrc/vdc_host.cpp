@@ -18,6 +18,7 @@
 #include "../../include/vdcores.h"
 #include "vdc_isa.h"
 #include "vdc_kernel.h"
+#include "vdc_sched.h"
 
 using namespace vdc;
 
@@ -997,26 +998,44 @@ bool choose_tile(const vdc_config &cfg, int64_t K, int32_t B, int32_t tile_bytes
     return matvec_geometry_ok((uint32_t)B, (uint32_t)R, (uint32_t)lpr, nullptr, nullptr);
 }
 
-// When a dense matrix has far fewer row blocks than there are compute cores, K is cut into S ranges and every
-// (range, row block) pair becomes a work item; the partial sums travel from range to range through a workspace and
-// depId signals (Section 4.1, inter-memory-uop dependencies).  S == 1: no split.
+// K of a dense matrix may be cut into S ranges: every (range, row block) pair is then a work item; the partial sums travel
+// from range to range through a workspace and depId signals (Section 4.1, inter-memory-uop dependencies).  S == 1: no cut.
+// S is the tiling the adaptive step of the generator chooses for the operator (Section 4.2, "Adaptive Scheduling and
+// Tiling"): a matrix with fewer row blocks than compute cores, or with a number of row blocks that leaves some cores one
+// block more than others, is a dominant critical path, and cutting K is the finer decomposition that removes it.
 struct SplitPlan {
-    int S = 1;
+    int S = 1, S_max = 1;
     int64_t NB = 0, prow = 0, ident_floats = 0, bytes = 0;   // workspace: [I | 0] tile, then S - 1 partial results [B][prow]
 };
 
-SplitPlan plan_split(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, int32_t R, int32_t Kt, bool ragged) {
+// The finest cut the builder offers for a shape: the joining step multiplies by an [I | 0] tile, so a tile must be at least
+// as wide as it is tall; every range keeps at least four tile steps; one depId per (range but the last, row block); a core's
+// stream of items stays short (the cut is for shapes with few blocks per compute core: with many the deal is even enough).
+int split_max_parts(const vdc_config &cfg, int64_t NB, int64_t nk, int32_t R, int32_t Kt, bool ragged) {
+    if (ragged || (R & 3) || R > Kt) return 1;
+    const int64_t lanes = (int64_t)cfg.n_cores * cfg.vcc_per_core;
+    int64_t S = std::min<int64_t>(16, nk / 4);
+    S = std::min<int64_t>(S, (int64_t)cfg.n_dep_ids / NB + 1);
+    S = std::min<int64_t>(S, std::max<int64_t>(1, 8 * lanes / NB));            // at most eight items per compute core
+    return (int)std::max<int64_t>(S, 1);
+}
+
+SplitPlan plan_split(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, int32_t R, int32_t Kt, int32_t tile_bytes, bool ragged) {
     SplitPlan sp;
     sp.NB = (rows + R - 1) / R;
-    if (ragged || (R & 3) || R > Kt) return sp;
-    const int64_t lanes = (int64_t)cfg.n_cores * cfg.vcc_per_core, nk = (K + Kt - 1) / Kt;
-    if (sp.NB * 2 > lanes) return sp;
-    int64_t S = lanes / sp.NB;
-    S = std::min<int64_t>(S, 16);
-    S = std::min<int64_t>(S, nk / 4);                               // at least four tiles per range
-    S = std::min<int64_t>(S, (int64_t)cfg.n_dep_ids / sp.NB + 1);   // one depId per (range but the last, row block)
+    const int64_t nk = (K + Kt - 1) / Kt;
+    sp.S_max = split_max_parts(cfg, sp.NB, nk, R, Kt, ragged);
+    if (sp.S_max < 2) return sp;
+    int32_t S = 1;
+    if (cfg.sched_force_parts > 0) {
+        S = std::min<int32_t>(cfg.sched_force_parts, sp.S_max);
+    } else {
+        const vdc_sched_op op{sp.NB, nk, sp.S_max, 0};
+        if (sched_adaptive(&op, 1, nullptr, nullptr, cfg.n_cores, cfg.vcc_per_core, sched_default_cost(tile_bytes), cfg.sched_threshold_pct,
+                           cfg.sched_min_gain_pct, &S, nullptr, nullptr) != VDC_OK) S = 1;
+    }
     if (S < 2) return sp;
-    sp.S = (int)S;
+    sp.S = S;
     sp.prow = sp.NB * R;
     sp.ident_floats = (int64_t)R * Kt;
     sp.bytes = (sp.ident_floats + (int64_t)(S - 1) * B * sp.prow) * 4;
@@ -1073,7 +1092,7 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
         segs.push_back({0, rows, 0, (rows + R - 1) / R});
         nb = segs[0].n_blocks;
     }
-    const SplitPlan sp = rope ? SplitPlan{} : plan_split(cfg, rows, K, B, R, Kt, row_off != nullptr);
+    const SplitPlan sp = rope ? SplitPlan{} : plan_split(cfg, rows, K, B, R, Kt, tile_bytes, row_off != nullptr);
     if (!rope && sp.S == 1) t.rowspan = rowspan_for(cfg, nb, K, B, R, Kt);
     if (sp.S > 1) {
         // items in the order (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  Only items of the last
@@ -1505,8 +1524,10 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
 }
 
 int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
-    for (int i = 0; i < 3; i++)
-        if (c.reserved[i]) return VDC_EINVAL;
+    if (c.sched_threshold_pct < 0 || c.sched_threshold_pct > 1000 || c.sched_min_gain_pct < 0 || c.sched_min_gain_pct > 100 ||
+        c.sched_force_parts < 0 || c.sched_force_parts > 16) return VDC_EINVAL;
+    if (c.sched_threshold_pct == 0) c.sched_threshold_pct = kSchedThresholdPct;
+    if (c.sched_min_gain_pct == 0) c.sched_min_gain_pct = kSchedMinGainPct;
     if (c.issue_batch < 0 || c.issue_batch > 8 || (c.issue_flags & ~1)) return VDC_EINVAL;
     if (c.issue_batch == 0) c.issue_batch = 8;
     if (c.n_cores == 0) c.n_cores = cu_count;
@@ -1949,7 +1970,7 @@ static void workspace_init(const vdc_config &cfg, int64_t rows, int64_t K, int32
     ws.clear();
     int32_t R = 0, Kt = 0;
     if (!choose_tile(cfg, K, B, tile_bytes, R, Kt)) return;
-    const SplitPlan sp = plan_split(cfg, rows, K, B, R, Kt, ragged);
+    const SplitPlan sp = plan_split(cfg, rows, K, B, R, Kt, tile_bytes, ragged);
     if (sp.S < 2) return;
     ws.assign((size_t)(sp.bytes / 4), 0.0f);
     for (int r = 0; r < R; r++) ws[(size_t)r * Kt + r] = 1.0f;
@@ -2144,6 +2165,15 @@ int vdc_matvec_workspace(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, 
         if (cap < *bytes) return VDC_EINVAL;
         memcpy(init, ws.data(), ws.size() * 4);
     }
+    return VDC_OK;
+}
+
+int vdc_matvec_tiling(vdc_executor *ex, int64_t rows, int64_t K, int32_t B, int32_t tile_bytes, int64_t *out) {
+    if (!ex || !out || rows < 1 || K < 4 || (K & 3) || B < 1 || B > 8) return VDC_EINVAL;
+    int32_t R = 0, Kt = 0;
+    if (!choose_tile(ex->cfg, K, B, tile_bytes, R, Kt)) return VDC_EINVAL;
+    const SplitPlan sp = plan_split(ex->cfg, rows, K, B, R, Kt, tile_bytes, false);
+    out[0] = R; out[1] = Kt; out[2] = sp.NB; out[3] = (K + Kt - 1) / Kt; out[4] = sp.S_max; out[5] = sp.S;
     return VDC_OK;
 }
 

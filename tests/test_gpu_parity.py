@@ -69,6 +69,10 @@ DENSE_CASES = [
     (256, 32768, 32768, 3, 8192),
     (100, 8200, 8204, 2, 4096),        # row tail and K tail in a split program
     (16, 4096, 4096, 8, 16384),
+    # one and a half row blocks per compute core: the adaptive tiling step cuts K although every compute core has work
+    (12288, 8192, 8192, 1, 16384),
+    (12280, 8192, 8192, 8, 16384),     # ... eight vectors, a ragged last block
+    (9216, 16392, 16400, 1, 16384),    # ... a K tail and a leading dimension in the last range
 ]
 
 
@@ -83,6 +87,33 @@ def test_dense_matvec_against_fp64_gemv(ex, rows, K, ld, B, T):
     ex.check()
     Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
     _check(dY.cpu().numpy(), Yr, Ya, "dense %s" % ((rows, K, ld, B, T),))
+
+
+@pytest.mark.parametrize("cfg,shape", [
+    (dict(sched_force_parts=3, n_cores=7), (100, 4096, 4100, 2, 4096)),       # five or six items per core: partial results and joining items share cores
+    (dict(sched_force_parts=2, n_cores=1), (16, 2048, 2048, 1, 2048)),        # everything on one core
+    (dict(sched_force_parts=16, n_cores=64), (300, 16384, 16384, 3, 8192)),   # the finest cut the builder offers
+    (dict(sched_force_parts=1), (64, 65536, 65536, 1, 16384)),                # and none at all where the scheduler would cut
+    (dict(sched_threshold_pct=300), (12288, 8192, 8192, 1, 16384)),           # a threshold nothing exceeds: left uncut
+])
+def test_cuts_of_k_the_scheduler_would_not_take(cfg, shape):
+    """Every decomposition the builder offers gives the GEMV, whatever the cost model thinks of it (sched_force_parts), with
+    several work items per compute core and producers and consumers of partial results on the same core."""
+    rows, K, ld, B, T = shape
+    rng = np.random.default_rng(rows + K)
+    M = rng.standard_normal((rows, ld)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    with vdc.Executor(**cfg) as e:
+        s_max, s = e.matvec_tiling(rows, K, B, T)[4:]
+        if "sched_force_parts" in cfg:
+            assert s == min(cfg["sched_force_parts"], s_max)
+        else:
+            assert s == 1 and s_max > 1
+        dY = torch.full((B, rows), float("nan"), device="cuda")
+        e.matvec(_dev(M), _dev(X), dY, T, K=K)
+        e.check()
+        Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
+        _check(dY.cpu().numpy(), Yr, Ya, "dense %s with %s" % (shape, cfg))
 
 
 @pytest.mark.parametrize("cfg", [

@@ -1,0 +1,127 @@
+"""The library's adaptive tiling step (vdc_schedule; Section 4.2, "Adaptive Scheduling and Tiling") against the oracle
+side's, look for look, and what the matvec tiler does with it: the cut of K it takes for a dense shape is the oracle's
+choice under the library's cost model, and the programs it then writes (several work items per compute core, partial
+results and joining items of one row block on different cores or on the same one) are validated, run on the interpreter
+under a random schedule and equal the fp64 GEMV.  Host logic only: no GPU."""
+import numpy as np
+import pytest
+from hypothesis import HealthCheck, given, settings, strategies as st
+
+import paper_2605_03190_amd as vdc
+from oracle import gemv_ref, uop_machine as UM, uop_schedule as S
+
+COMMON = dict(deadline=None, max_examples=80, derandomize=True, suppress_health_check=[HealthCheck.too_slow])
+
+
+def library_cost(tile_bytes):
+    """The cost model the header documents for the tilers: nanoseconds for tiles of tile_bytes."""
+    step = 510 + tile_bytes // 20
+    return S.Cost(step=step, item=500, join=step, edge=4000)
+
+
+@settings(**COMMON)
+@given(data=st.data(), n_ops=st.integers(0, 6), C=st.integers(1, 7), V=st.integers(1, 2), thr=st.integers(1, 40), mg=st.integers(1, 20))
+def test_the_library_takes_the_looks_the_oracle_takes(data, n_ops, C, V, thr, mg):
+    ops, preds = [], []
+    for o in range(n_ops):
+        nk = data.draw(st.integers(1, 40))
+        ops.append((data.draw(st.integers(1, 40)), nk, data.draw(st.integers(1, min(nk, 8)))))
+        preds.append(tuple(p for p in range(o) if data.draw(st.booleans())))
+    cost = tuple(data.draw(st.integers(lo, 50)) for lo in (1, 0, 0, 0))
+    want_parts, want_log = S.adaptive_tiling([S.Op(nb, nk, mp, pr) for (nb, nk, mp), pr in zip(ops, preds)], C, V, S.Cost(*cost), thr, mg)
+    with vdc.Executor(device=-1, n_cores=C, vcc_per_core=V, sched_threshold_pct=thr, sched_min_gain_pct=mg) as ex:
+        parts, log = ex.schedule(ops, preds, cost)
+        assert parts == want_parts
+        assert log == [(pc, avg, o, s, g) for pc, avg, _, o, s, g in want_log]
+        if all(not p for p in preds):
+            assert ex.schedule(ops, None, cost) == (parts, log)
+
+
+def test_malformed_graphs_are_refused():
+    with vdc.Executor(device=-1, n_cores=4) as ex:
+        for ops, preds, cost in [([(0, 4, 1)], None, (1, 0, 0, 0)), ([(4, 0, 1)], None, (1, 0, 0, 0)), ([(4, 4, 5)], None, (1, 0, 0, 0)),
+                                 ([(4, 4, 0)], None, (1, 0, 0, 0)), ([(4, 4, 2)], None, (0, 0, 0, 0)), ([(4, 4, 2)], None, (1, -1, 0, 0)),
+                                 ([(4, 4, 2), (4, 4, 2)], [(1,), ()], (1, 0, 0, 0)), ([(4, 4, 2)], [(0,)], (1, 0, 0, 0)),
+                                 ([(1 << 23, 8, 4)], None, (1, 0, 0, 0))]:
+            with pytest.raises(vdc.VdcError) as e:
+                ex.schedule(ops, preds, cost)
+            assert e.value.code == vdc.VDC_EINVAL
+        with pytest.raises(vdc.VdcError):
+            ex.schedule([(4, 4, 2)], None, None, tile_bytes=100)
+    for bad in (dict(sched_threshold_pct=-1), dict(sched_min_gain_pct=101), dict(sched_force_parts=17)):
+        with pytest.raises(vdc.VdcError):
+            vdc.Executor(device=-1, **bad)
+
+
+@settings(**COMMON)
+@given(rows=st.integers(1, 4000), nk=st.integers(1, 64), B=st.sampled_from([1, 2, 8]), tile=st.sampled_from([4096, 8192, 16384]),
+       C=st.sampled_from([3, 16, 256]))
+def test_the_matvec_tiler_takes_the_cut_the_oracle_would(rows, nk, B, tile, C):
+    with vdc.Executor(device=-1, n_cores=C) as ex:
+        R, Kt, NB, nk_, s_max, s = ex.matvec_tiling(rows, 256 * nk, B, tile)
+        assert NB == -(-rows // R) and nk_ == -(-256 * nk // Kt) and 1 <= s <= s_max
+        want, _ = S.adaptive_tiling([S.Op(NB, nk_, s_max)], C, 2, library_cost(tile))
+        assert [s] == want
+        # what the builder offers: at least four steps a range, a depId per partial result, a short stream per core
+        assert s_max == 1 or (s_max <= min(16, nk_ // 4) and (s_max - 1) * NB <= 4096 and s_max * NB <= max(NB, 8 * 2 * C) and R % 4 == 0 and R <= Kt)
+
+
+def test_shapes_of_the_benchmark_configurations_and_awkward_ones():
+    with vdc.Executor(device=-1, n_cores=256) as ex:
+        assert ex.matvec_tiling(32768, 65536, 8, 16384)[2:] == (1024, 512, 4, 1)        # two row blocks a compute core: left alone
+        assert ex.matvec_tiling(8192, 8192, 1, 8192)[2:] == (1024, 32, 4, 1)
+        R, Kt, NB, nk, s_max, s = ex.matvec_tiling(12288, 8192, 1, 16384)              # one and a half: cut
+        assert (NB, nk) == (768, 32) and s >= 2
+        R, Kt, NB, nk, s_max, s = ex.matvec_tiling(1024, 16384, 1, 16384)              # an eighth of the compute cores busy: cut
+        assert NB == 64 and s >= 4
+
+
+def _run(ex, rows, K, B, tile, ncores, slot, nslots, seed):
+    w, sb, d = ex.matvec_program(rows, K, K, B, tile)
+    ws = ex.matvec_workspace(rows, K, K, B, tile)
+    rng = np.random.default_rng(seed)
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    sizes = [M.nbytes, X.nbytes, B * rows * 4] + ([ws.nbytes] if ws.size else [])
+    rc, msg = ex.program_validate(w, sb, d, sizes)
+    assert rc == vdc.VDC_OK, msg
+    Y = np.full((B, rows), np.nan, np.float32)
+    m = UM.Machine(w, sb, d, [M, X, Y] + ([ws] if ws.size else []), n_cores=ncores, slot_bytes=slot, n_slots=nslots, n_dep_ids=4096)
+    m.run("random", seed)
+    m.check_final()
+    Yr, Ya = gemv_ref.gemv_dense(M, X)
+    assert np.all(np.abs(Y - Yr) <= 2e-6 * Ya + 1e-30)
+    signals = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.STORE) - (-(-rows // ex.matvec_tiling(rows, K, B, tile)[0]))
+    return signals
+
+
+CUT_SEEN = []
+
+
+@settings(**COMMON)
+@given(blocks_x2=st.integers(1, 15), extra=st.integers(0, 3), nk=st.integers(8, 40), B=st.sampled_from([1, 2, 3]), ncores=st.integers(1, 4),
+       seed=st.integers(0, 1000))
+def test_programs_of_cut_shapes_equal_the_gemv(blocks_x2, extra, nk, B, ncores, seed):
+    """Row-block counts around half-integer multiples of the number of compute cores (where the adaptive step cuts K), with a
+    ragged last block; tiles of 2 KB = 4 rows x 128 columns."""
+    slot, nslots, tile = 2048, 16, 2048
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
+        R, Kt = ex.matvec_tiling(4, 128 * nk, B, tile)[:2]
+        rows = max(1, blocks_x2 * ncores * R - extra)                # NB = blocks_x2 / 2 per compute core, give or take
+        s = ex.matvec_tiling(rows, Kt * nk, B, tile)[5]
+        signals = _run(ex, rows, Kt * nk, B, tile, ncores, slot, nslots, seed)
+        assert signals == (s - 1) * -(-rows // R)                    # every partial result is one more store
+        CUT_SEEN.append(s)
+
+
+def test_the_adaptive_step_did_cut_some_of_those_shapes():
+    assert CUT_SEEN and max(CUT_SEEN) >= 2 and min(CUT_SEEN) == 1
+
+
+@pytest.mark.parametrize("ncores,force,rows,nk", [(1, 2, 24, 8), (1, 4, 40, 16), (2, 3, 28, 12), (3, 16, 36, 64), (2, 2, 4, 9)])
+def test_forced_cuts_with_partial_and_joining_items_on_one_core(ncores, force, rows, nk):
+    """sched_force_parts takes the scheduler out: every K cut the builder offers can be run, also where it would not pay."""
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=2048, n_slots=16, sched_force_parts=force) as ex:
+        R, Kt, NB, nk_, s_max, s = ex.matvec_tiling(rows, 128 * nk, 2, 2048)
+        assert s == min(force, s_max)
+        _run(ex, rows, 128 * nk, 2, 2048, ncores, 2048, 16, rows)
