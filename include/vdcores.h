@@ -372,18 +372,19 @@ int vdc_graph_lower(vdc_executor *ex, const vdc_graph_memop *ops, int64_t n_ops,
  * nothing finer is left.  An operator is a matvec of n_blocks row blocks over nk tile steps of K; decomposition S cuts
  * the K range of every row block into S ranges (range s = steps [nk s / S, nk (s + 1) / S)), the items in the order
  * (range, row block) are dealt in contiguous shares (core c: items [NI c / C, NI (c + 1) / C), to its compute cores in
- * turn), the items of ranges 0 .. S - 2 store partial sums and signal, the item of the last range joins them. */
+ * turn), the items of ranges 0 .. S - 2 store partial sums and signal, the item of the last range joins them,
+ * join_group of them per extra step. */
 typedef struct {
     int64_t n_blocks;   /* row blocks, >= 1                                                                   */
     int64_t nk;         /* tile steps along K per row block, >= 1                                             */
     int32_t max_parts;  /* finest decomposition the operator's builder offers, 1 .. nk                        */
-    int32_t reserved;   /* zero                                                                               */
+    int32_t join_group; /* partial results that one joining step of the last range adds; 0 => 1                */
 } vdc_sched_op;
 
 typedef struct {        /* integers in one unit of the caller's choice (the library's own model: nanoseconds) */
     int64_t step;       /* one tile step of a compute core (matrix tile and vector tile loaded and used), >= 1 */
     int64_t item;       /* per work item on top of its steps: output region, row sums, store                  */
-    int64_t join;       /* per partial result that a joining item adds                                        */
+    int64_t join;       /* per joining step of an item of the last range                                      */
     int64_t edge;       /* from the end of a producing item to the moment the joining item can use its result */
 } vdc_cost_model;
 

@@ -12,12 +12,12 @@ expected benefit is marginal or no dominant path is left.  The paper gives this 
 * operator: a matvec of `n_blocks` row blocks whose K range is `nk` tile steps long.  Its decompositions: the K range of
   every row block cut into S = 1 .. `max_parts` ranges (range s = steps [nk s / S, nk (s + 1) / S)), one work item per
   (range, row block), items in that order.  The items of ranges 0 .. S - 2 store partial sums and signal; the item of the
-  last range of a row block waits for them, adds them (one more step each) and stores the result.
+  last range of a row block waits for them, adds them (`group` of them per joining step) and stores the result.
 * schedule: the NI = n_blocks * S items of an operator are dealt in contiguous shares, core c taking items
   [NI c / C, NI (c + 1) / C) and its j-th item going to its compute core j mod V.  A compute core is a lane; lanes work
   through their items in order.
 * cost model (integers): a tile step costs `step`, every item `item` on top (output region and store), every partial
-  result a joining item adds `join`, and a dependency edge `edge` between the end of the producing item and the moment
+  joining step `join`, and a dependency edge `edge` between the end of the producing item and the moment
   the joining item may use it.  A joining item first works through its own range, then waits if it must.  The span of
   an operator is the time its last lane ends; its work is the sum of its items' costs without waiting.
 * critical path: the longest path through the operator DAG, an operator weighing its span (an operator starts when all
@@ -36,6 +36,7 @@ class Op:
     nk: int
     max_parts: int = 1
     preds: tuple = ()           # indices of operators that must have ended before this one starts (all smaller than its own)
+    group: int = 1              # partial results that one joining step adds
 
 
 @dataclass(frozen=True)
@@ -72,8 +73,9 @@ def op_cost(op, S, C, V, cost):
             work += own + cost.item
         else:
             ready = max(finish[sp * NB + rb] for sp in range(S - 1)) + cost.edge
-            t = max(lane_t[lane] + own, ready) + (S - 1) * cost.join + cost.item
-            work += own + (S - 1) * cost.join + cost.item
+            joins = -(-(S - 1) // op.group)
+            t = max(lane_t[lane] + own, ready) + joins * cost.join + cost.item
+            work += own + joins * cost.join + cost.item
         finish[i] = t
         lane_t[lane] = t
     return max(lane_t) if NI else 0, work

@@ -32,7 +32,7 @@ class vdc_config(ctypes.Structure):
 
 
 class vdc_sched_op(ctypes.Structure):
-    _fields_ = [("n_blocks", ctypes.c_int64), ("nk", ctypes.c_int64), ("max_parts", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+    _fields_ = [("n_blocks", ctypes.c_int64), ("nk", ctypes.c_int64), ("max_parts", ctypes.c_int32), ("join_group", ctypes.c_int32)]
 
 
 class vdc_cost_model(ctypes.Structure):
@@ -337,13 +337,13 @@ class Executor:
         return tuple(int(x) for x in out)
 
     def schedule(self, ops, preds=None, cost=None, tile_bytes=16384):
-        """vdc_schedule: ops = [(n_blocks, nk, max_parts)], preds = per operator the operators it waits for, cost =
+        """vdc_schedule: ops = [(n_blocks, nk, max_parts[, join_group])], preds = per operator the operators it waits for, cost =
         (step, item, join, edge) or None for the library's model.  Returns (parts, log) with log = [(path cost, average,
         refined operator or -1, new S, gain)]."""
         n = len(ops)
         arr = (vdc_sched_op * max(n, 1))()
-        for o, (nb, nk, mp) in enumerate(ops):
-            arr[o] = vdc_sched_op(nb, nk, mp, 0)
+        for o, op in enumerate(ops):
+            arr[o] = vdc_sched_op(op[0], op[1], op[2], op[3] if len(op) > 3 else 0)
         pb = pr = None
         if preds is not None:
             pb = np.zeros(n + 1, dtype=np.int32)
@@ -351,7 +351,7 @@ class Executor:
             pr = np.array([q for p in preds for q in p] + [0], dtype=np.int32)
         cm = vdc_cost_model(*cost) if cost is not None else None
         parts = np.zeros(max(n, 1), dtype=np.int32)
-        cap = 2 + sum(mp for _, _, mp in ops)
+        cap = 2 + sum(op[2] for op in ops)
         log = np.zeros((cap, 5), dtype=np.int64)
         looks = ctypes.c_int32(cap)
         _check(lib().vdc_schedule(self.handle, ctypes.cast(arr, ctypes.c_void_p), n, _np_ptr(pb) if pb is not None else None,

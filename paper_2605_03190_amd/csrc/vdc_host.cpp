@@ -849,12 +849,14 @@ struct Tiler {
     }
 
     // One K range [kt0, kt1) (in tiles; the last range also takes the K tail) of one row block per compute core in
-    // `vs`.  Every range but the last stores its partial sums to the workspace (tensor 3) and signals its own depId.
-    // The last range then adds them, one more tile step each: the matrix tile is [I | 0] from the workspace and the
-    // vector tile is a partial result, fetched with a load that waits for its depId (Section 4.1: a load with an
+    // `vs`.  Every range but the last stores its partial sums to the workspace (tensor 3) and signals its row block's depId.
+    // The workspace keeps the S - 1 partial results of a row block side by side, [row block][B][S - 1][R], so that G =
+    // Kt / R of them are one vector tile ([B] rows of G R values).  The last range then adds them, G per extra tile step:
+    // the matrix tile is [I I .. I | 0] (G unit matrices, from the workspace) and the vector tile holds G partial results
+    // (the rest of its row reads as zero), fetched with a load that waits for the depId (Section 4.1: a load with an
     // inter-memory-uop dependency), and stores to Y.  The order of the additions is fixed by the program.
     void emit_split(int core, const std::vector<int> &vs, const std::vector<int64_t> &rbs, int s, int S, int64_t kt0, int64_t kt1,
-                    int64_t rows_total, int64_t NB, int64_t prow, int64_t p_base) {
+                    int64_t rows_total, int64_t p_base) {
         auto &vm = vmc(core);
         const int64_t nk_all = K / Kt, ktail = K % Kt;
         const int n = (int)vs.size();
@@ -864,8 +866,9 @@ struct Tiler {
         const uint32_t m_flags = F_SEND | F_DYNAMIC | (nt ? F_NT : 0);
         const uint32_t dx = desc(1, B, Kt * 4, Kt * 4, (uint64_t)K * 4);
         const uint32_t dxt = ktail ? desc(1, B, (uint32_t)ktail * 4, Kt * 4, (uint64_t)K * 4) : 0;
-        const uint32_t d_id = desc(3, R, Kt * 4, Kt * 4, (uint64_t)Kt * 4);                    // [I | 0]
-        const uint32_t d_pl = desc(3, B, R * 4, Kt * 4, (uint64_t)prow * 4);                   // previous partial as a vector tile
+        const int64_t G = Kt / R, prow = (int64_t)(S - 1) * R;       // partial results per join step; values per row of a block's partial results
+        const int64_t nq = (S - 1 + G - 1) / G;                      // join steps
+        const uint32_t d_id = desc(3, R, Kt * 4, Kt * 4, (uint64_t)Kt * 4);                    // [I I .. I | 0]
         const uint32_t d_ps = desc(3, B, R * 4, R * 4, (uint64_t)prow * 4);                    // partial result store
         vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, kt0 * Kt * 4, 0, 0));
         std::vector<uint32_t> rows_valid(n);
@@ -885,24 +888,30 @@ struct Tiler {
         }
         if (with_tail) tile_pairs(true);
         if (s == S - 1) {
-            for (int sp = 0; sp < S - 1; sp++)
+            // Every partial result of row block rb signals depId rb; the first load of them waits until all S - 1 have
+            // (one round trip to the counter per joining item, not one per partial result), the others follow it on the same
+            // load unit and need no wait of their own.  All are read at device scope: the waiting unit then needs no
+            // acquire, which would empty its whole L2.
+            for (int64_t q = 0; q < nq; q++)
                 for (int i = 0; i < n; i++) {
                     const int v = vs[i];
+                    const int64_t g = std::min<int64_t>(G, S - 1 - q * G);                     // partial results of this step
+                    const uint32_t d_pl = desc(3, B, (uint32_t)(g * R * 4), Kt * 4, (uint64_t)prow * 4);
                     vm.push_back(encode(OP_LOAD, F_SEND, flow_m(v), v, 0, m_slots, R, 0, 0, d_id, 0));
-                    vm.push_back(encode(OP_LOAD, F_SEND | F_DEP_RECV, flow_x(v), v, 0, x_slots, B, (uint32_t)(sp * NB + rbs[i]),
-                                        p_base + ((int64_t)sp * B * prow + rbs[i] * R) * 4, d_pl, 1));
+                    vm.push_back(encode(OP_LOAD, F_SEND | F_DEVICE | (q == 0 ? F_DEP_RECV : 0u), flow_x(v), v, 0, x_slots, B, q == 0 ? (uint32_t)rbs[i] : 0u,
+                                        p_base + (rbs[i] * B * prow + q * G * R) * 4, d_pl, q == 0 ? (uint32_t)(S - 1) : 0u));
                 }
         }
         for (int i = 0; i < n; i++) {
             const int v = vs[i];
             if (s < S - 1) {
-                vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, flow_y(v), v, 0, y_slots, B, (uint32_t)(s * NB + rbs[i]),
-                                    p_base + ((int64_t)s * B * prow + rbs[i] * R) * 4, d_ps, 0));
+                vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, flow_y(v), v, 0, y_slots, B, (uint32_t)rbs[i],
+                                    p_base + (rbs[i] * B * prow + (int64_t)s * R) * 4, d_ps, 0));
             } else {
                 const uint32_t dy = desc(2, B, rows_valid[i] * 4, R * 4, (uint64_t)y_pitch * 4);
                 vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, rbs[i] * R * 4, dy, 0));
             }
-            const uint32_t nk = (uint32_t)(full + (with_tail ? 1 : 0) + (s == S - 1 ? S - 1 : 0));
+            const uint32_t nk = (uint32_t)(full + (with_tail ? 1 : 0) + (s == S - 1 ? nq : 0));
             vcc(core, v).push_back(encode(OP_MATVEC, 0, 0, 0, 0, 0, nk, 0, matvec_imm(B, R, Kt / 4), 0, 0));
         }
     }
@@ -1005,17 +1014,17 @@ bool choose_tile(const vdc_config &cfg, int64_t K, int32_t B, int32_t tile_bytes
 // block more than others, is a dominant critical path, and cutting K is the finer decomposition that removes it.
 struct SplitPlan {
     int S = 1, S_max = 1;
-    int64_t NB = 0, prow = 0, ident_floats = 0, bytes = 0;   // workspace: [I | 0] tile, then S - 1 partial results [B][prow]
+    int64_t NB = 0, ident_floats = 0, bytes = 0;   // workspace: the tile [I I .. I | 0], then the partial results [NB][B][S - 1][R]
 };
 
 // The finest cut the builder offers for a shape: the joining step multiplies by an [I | 0] tile, so a tile must be at least
-// as wide as it is tall; every range keeps at least four tile steps; one depId per (range but the last, row block); a core's
+// as wide as it is tall; every range keeps at least four tile steps; one depId per row block; a core's
 // stream of items stays short (the cut is for shapes with few blocks per compute core: with many the deal is even enough).
 int split_max_parts(const vdc_config &cfg, int64_t NB, int64_t nk, int32_t R, int32_t Kt, bool ragged) {
     if (ragged || (R & 3) || R > Kt) return 1;
     const int64_t lanes = (int64_t)cfg.n_cores * cfg.vcc_per_core;
     int64_t S = std::min<int64_t>(16, nk / 4);
-    S = std::min<int64_t>(S, (int64_t)cfg.n_dep_ids / NB + 1);
+    if (NB > (int64_t)cfg.n_dep_ids) return 1;                                  // one depId per row block
     S = std::min<int64_t>(S, std::max<int64_t>(1, 8 * lanes / NB));            // at most eight items per compute core
     return (int)std::max<int64_t>(S, 1);
 }
@@ -1030,15 +1039,14 @@ SplitPlan plan_split(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, 
     if (cfg.sched_force_parts > 0) {
         S = std::min<int32_t>(cfg.sched_force_parts, sp.S_max);
     } else {
-        const vdc_sched_op op{sp.NB, nk, sp.S_max, 0};
+        const vdc_sched_op op{sp.NB, nk, sp.S_max, Kt / R};       // a joining step adds Kt / R partial results
         if (sched_adaptive(&op, 1, nullptr, nullptr, cfg.n_cores, cfg.vcc_per_core, sched_default_cost(tile_bytes), cfg.sched_threshold_pct,
                            cfg.sched_min_gain_pct, &S, nullptr, nullptr) != VDC_OK) S = 1;
     }
     if (S < 2) return sp;
     sp.S = S;
-    sp.prow = sp.NB * R;
     sp.ident_floats = (int64_t)R * Kt;
-    sp.bytes = (sp.ident_floats + (int64_t)(S - 1) * B * sp.prow) * 4;
+    sp.bytes = (sp.ident_floats + (int64_t)(S - 1) * B * sp.NB * R) * 4;
     return sp;
 }
 
@@ -1108,7 +1116,7 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
                 std::vector<int64_t> rbs{i0 % sp.NB};
                 if (V == 2 && i0 + 1 < i1 && (int)((i0 + 1) / sp.NB) == s0) { vs = {0, 1}; rbs.push_back((i0 + 1) % sp.NB); }
                 else next_v ^= 1;
-                t.emit_split(c, vs, rbs, s0, sp.S, nk * s0 / sp.S, nk * (s0 + 1) / sp.S, rows, sp.NB, sp.prow, sp.ident_floats * 4);
+                t.emit_split(c, vs, rbs, s0, sp.S, nk * s0 / sp.S, nk * (s0 + 1) / sp.S, rows, sp.ident_floats * 4);
                 i0 += (int64_t)vs.size();
             }
         }
@@ -1964,8 +1972,8 @@ int vdc_sync_status(vdc_executor *ex, void *hip_stream, uint32_t *info) {
     return code ? code : VDC_EDEVICE;
 }
 
-// Initial content of the workspace (tensor 3) of a matvec program that splits K: the tile [I | 0] (R rows of Kt
-// floats), then the partial results, zero.  Empty when the program does not split.
+// Initial content of the workspace (tensor 3) of a matvec program that splits K: the tile [I I .. I | 0] (R rows of Kt
+// floats, Kt / R unit matrices side by side), then the partial results, zero.  Empty when the program does not split.
 static void workspace_init(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, int32_t tile_bytes, bool ragged, std::vector<float> &ws) {
     ws.clear();
     int32_t R = 0, Kt = 0;
@@ -1973,7 +1981,8 @@ static void workspace_init(const vdc_config &cfg, int64_t rows, int64_t K, int32
     const SplitPlan sp = plan_split(cfg, rows, K, B, R, Kt, tile_bytes, ragged);
     if (sp.S < 2) return;
     ws.assign((size_t)(sp.bytes / 4), 0.0f);
-    for (int r = 0; r < R; r++) ws[(size_t)r * Kt + r] = 1.0f;
+    for (int g = 0; g < Kt / R; g++)
+        for (int r = 0; r < R; r++) ws[(size_t)r * Kt + (size_t)g * R + r] = 1.0f;
 }
 
 static int matvec_common(vdc_executor *ex, const float *M, int64_t rows, int64_t K, int64_t ld, const float *X, float *Y,

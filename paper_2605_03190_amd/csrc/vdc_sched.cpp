@@ -9,8 +9,8 @@
 // every row block into S = 1 .. max_parts ranges (range s = steps [nk s / S, nk (s + 1) / S)); the work items, in the
 // order (range, row block), are dealt in contiguous shares: core c takes items [NI c / C, NI (c + 1) / C) and deals them
 // to its compute cores in turn.  The items of all ranges but the last store partial sums and signal a depId, the item of
-// the last range adds them to its own (one more step each, behind a load that waits for the depId).  Costs are integers: a tile
-// step, an item (its output region and store), a joined partial result, a dependency edge (from the end of the producing
+// the last range adds them to its own (join_group of them per extra step, behind a load that waits for the depId).  Costs are integers: a tile
+// step, an item (its output region and store), a joining step, a dependency edge (from the end of the producing
 // item to the moment the joining item can use the result).  A compute core is a lane and works through its items in order;
 // a joining item does its own steps first and waits then.
 #include <algorithm>
@@ -40,8 +40,9 @@ void sched_op_cost(const vdc_sched_op &op, int64_t S, int64_t C, int64_t V, cons
             } else {
                 int64_t ready = 0;
                 for (int64_t sp = 0; sp < S - 1; sp++) ready = std::max(ready, finish[(size_t)(sp * NB + rb)]);
-                lt = std::max(lt + own, ready + cm.edge) + (S - 1) * cm.join + cm.item;
-                work += own + (S - 1) * cm.join + cm.item;
+                const int64_t G = op.join_group > 0 ? op.join_group : 1, joins = (S - 1 + G - 1) / G;
+                lt = std::max(lt + own, ready + cm.edge) + joins * cm.join + cm.item;
+                work += own + joins * cm.join + cm.item;
             }
             finish[(size_t)i] = lt;
         }
@@ -128,15 +129,16 @@ int sched_adaptive(const vdc_sched_op *ops, int32_t n_ops, const int32_t *pred_b
     return VDC_OK;
 }
 
-// Nanoseconds on an MI355X, from whole runs of the executor: a compute core streams tiles of 16 KB at its share (1 / 512)
-// of 6.4 TB/s and smaller tiles at what the per-tile cost leaves of it (8 KB: 62 %, 4 KB: 37 % of the memory's peak); an
-// item's row sums, output region and store; a joined partial result is one more tile step whose tiles come out of the
-// L2; a dependency edge is a store written through at device scope, the counter, and the waiting load's next look at it.
+// Nanoseconds on an MI355X, fitted to whole runs of dense matvecs under every cut the builder offers (sched_bench): a compute
+// core streams tiles of 16 KB at its share (1 / 512) of 6.3 TB/s and smaller tiles at what the per-tile cost leaves of it
+// (8 KB: 62 %, 4 KB: 37 % of the memory's peak); an item costs the refill of the pipeline when a compute core moves to
+// another row block, its row sums and its store; a joining step is a tile step whose uops the front end cannot replay;
+// a dependency edge is a store written through at device scope, the counter, and the waiting load's next look at it.
 vdc_cost_model sched_default_cost(int32_t tile_bytes) {
     vdc_cost_model cm;
     cm.step = 510 + tile_bytes / 20;
-    cm.item = 500;
-    cm.join = cm.step;
+    cm.item = 3000;
+    cm.join = cm.step + 1200;
     cm.edge = 4000;
     return cm;
 }
@@ -151,7 +153,7 @@ extern "C" int vdc_schedule(vdc_executor *ex, const vdc_sched_op *ops, int32_t n
         return VDC_EINVAL;
     if (!cost && (tile_bytes < 256 || tile_bytes > 32768)) return VDC_EINVAL;
     for (int32_t o = 0; o < n_ops; o++)
-        if (ops[o].reserved) return VDC_EINVAL;
+        if (ops[o].join_group < 0) return VDC_EINVAL;
     const vdc_cost_model cm = cost ? *cost : vdc::sched_default_cost(tile_bytes);
     return vdc::sched_adaptive(ops, n_ops, pred_begin, preds, cfg.n_cores, cfg.vcc_per_core, cm, cfg.sched_threshold_pct, cfg.sched_min_gain_pct,
                                parts, log, n_looks);

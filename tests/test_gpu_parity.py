@@ -71,7 +71,7 @@ DENSE_CASES = [
     (16, 4096, 4096, 8, 16384),
     # one and a half row blocks per compute core: the adaptive tiling step cuts K although every compute core has work
     (12288, 8192, 8192, 1, 16384),
-    (12280, 8192, 8192, 8, 16384),     # ... eight vectors, a ragged last block
+    (24570, 4096, 4096, 8, 16384),     # ... eight vectors, a ragged last block
     (9216, 16392, 16400, 1, 16384),    # ... a K tail and a leading dimension in the last range
 ]
 

@@ -16,7 +16,7 @@ COMMON = dict(deadline=None, max_examples=80, derandomize=True, suppress_health_
 def library_cost(tile_bytes):
     """The cost model the header documents for the tilers: nanoseconds for tiles of tile_bytes."""
     step = 510 + tile_bytes // 20
-    return S.Cost(step=step, item=500, join=step, edge=4000)
+    return S.Cost(step=step, item=3000, join=step + 1200, edge=4000)
 
 
 @settings(**COMMON)
@@ -25,10 +25,10 @@ def test_the_library_takes_the_looks_the_oracle_takes(data, n_ops, C, V, thr, mg
     ops, preds = [], []
     for o in range(n_ops):
         nk = data.draw(st.integers(1, 40))
-        ops.append((data.draw(st.integers(1, 40)), nk, data.draw(st.integers(1, min(nk, 8)))))
+        ops.append((data.draw(st.integers(1, 40)), nk, data.draw(st.integers(1, min(nk, 8))), data.draw(st.integers(1, 5))))
         preds.append(tuple(p for p in range(o) if data.draw(st.booleans())))
     cost = tuple(data.draw(st.integers(lo, 50)) for lo in (1, 0, 0, 0))
-    want_parts, want_log = S.adaptive_tiling([S.Op(nb, nk, mp, pr) for (nb, nk, mp), pr in zip(ops, preds)], C, V, S.Cost(*cost), thr, mg)
+    want_parts, want_log = S.adaptive_tiling([S.Op(nb, nk, mp, pr, g) for (nb, nk, mp, g), pr in zip(ops, preds)], C, V, S.Cost(*cost), thr, mg)
     with vdc.Executor(device=-1, n_cores=C, vcc_per_core=V, sched_threshold_pct=thr, sched_min_gain_pct=mg) as ex:
         parts, log = ex.schedule(ops, preds, cost)
         assert parts == want_parts
@@ -42,7 +42,7 @@ def test_malformed_graphs_are_refused():
         for ops, preds, cost in [([(0, 4, 1)], None, (1, 0, 0, 0)), ([(4, 0, 1)], None, (1, 0, 0, 0)), ([(4, 4, 5)], None, (1, 0, 0, 0)),
                                  ([(4, 4, 0)], None, (1, 0, 0, 0)), ([(4, 4, 2)], None, (0, 0, 0, 0)), ([(4, 4, 2)], None, (1, -1, 0, 0)),
                                  ([(4, 4, 2), (4, 4, 2)], [(1,), ()], (1, 0, 0, 0)), ([(4, 4, 2)], [(0,)], (1, 0, 0, 0)),
-                                 ([(1 << 23, 8, 4)], None, (1, 0, 0, 0))]:
+                                 ([(1 << 23, 8, 4)], None, (1, 0, 0, 0)), ([(4, 4, 2, -1)], None, (1, 0, 0, 0))]:
             with pytest.raises(vdc.VdcError) as e:
                 ex.schedule(ops, preds, cost)
             assert e.value.code == vdc.VDC_EINVAL
@@ -60,10 +60,10 @@ def test_the_matvec_tiler_takes_the_cut_the_oracle_would(rows, nk, B, tile, C):
     with vdc.Executor(device=-1, n_cores=C) as ex:
         R, Kt, NB, nk_, s_max, s = ex.matvec_tiling(rows, 256 * nk, B, tile)
         assert NB == -(-rows // R) and nk_ == -(-256 * nk // Kt) and 1 <= s <= s_max
-        want, _ = S.adaptive_tiling([S.Op(NB, nk_, s_max)], C, 2, library_cost(tile))
+        want, _ = S.adaptive_tiling([S.Op(NB, nk_, s_max, (), Kt // R)], C, 2, library_cost(tile))
         assert [s] == want
-        # what the builder offers: at least four steps a range, a depId per partial result, a short stream per core
-        assert s_max == 1 or (s_max <= min(16, nk_ // 4) and (s_max - 1) * NB <= 4096 and s_max * NB <= max(NB, 8 * 2 * C) and R % 4 == 0 and R <= Kt)
+        # what the builder offers: at least four steps a range, a depId per row block, a short stream per core
+        assert s_max == 1 or (s_max <= min(16, nk_ // 4) and NB <= 4096 and s_max * NB <= max(NB, 8 * 2 * C) and R % 4 == 0 and R <= Kt)
 
 
 def test_shapes_of_the_benchmark_configurations_and_awkward_ones():
@@ -118,10 +118,16 @@ def test_the_adaptive_step_did_cut_some_of_those_shapes():
     assert CUT_SEEN and max(CUT_SEEN) >= 2 and min(CUT_SEEN) == 1
 
 
-@pytest.mark.parametrize("ncores,force,rows,nk", [(1, 2, 24, 8), (1, 4, 40, 16), (2, 3, 28, 12), (3, 16, 36, 64), (2, 2, 4, 9)])
-def test_forced_cuts_with_partial_and_joining_items_on_one_core(ncores, force, rows, nk):
+@pytest.mark.parametrize("ncores,force,rows,nk,B,tile,slot,nslots", [
+    (1, 2, 24, 8, 2, 2048, 2048, 16), (1, 4, 8, 16, 2, 2048, 2048, 16), (2, 3, 28, 12, 2, 2048, 2048, 16), (3, 16, 36, 64, 2, 2048, 2048, 16),
+    (2, 2, 4, 9, 2, 2048, 2048, 16),
+    (2, 16, 70, 64, 8, 16384, 8192, 19),      # tiles of 32 rows x 128 columns: four partial results per joining step, fifteen to join
+    (3, 7, 100, 30, 8, 16384, 8192, 19),      # ... six: a full step and a short one
+])
+def test_forced_cuts_with_partial_and_joining_items_on_one_core(ncores, force, rows, nk, B, tile, slot, nslots):
     """sched_force_parts takes the scheduler out: every K cut the builder offers can be run, also where it would not pay."""
-    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=2048, n_slots=16, sched_force_parts=force) as ex:
-        R, Kt, NB, nk_, s_max, s = ex.matvec_tiling(rows, 128 * nk, 2, 2048)
-        assert s == min(force, s_max)
-        _run(ex, rows, 128 * nk, 2, 2048, ncores, 2048, 16, rows)
+    with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots, sched_force_parts=force) as ex:
+        R, Kt, NB, nk_, s_max, s = ex.matvec_tiling(rows, 128 * nk, B, tile)
+        assert s == min(force, s_max) and s >= 2
+        signals = _run(ex, rows, 128 * nk, B, tile, ncores, slot, nslots, rows)
+        assert signals == (s - 1) * NB

@@ -16,7 +16,7 @@ COMMON = dict(deadline=None, max_examples=150, derandomize=True, suppress_health
 def tick_simulation(op, parts, C, V, cost):
     """Every lane works through its items one clock tick at a time.  An item of an earlier K range is `own` ticks of steps
     and `item` ticks of storing; the item of the last range does its own steps, then stands still until every partial
-    result of its row block has been finished for `edge` ticks, then adds them and stores.  Returns the tick at which the
+    result of its row block has been finished for `edge` ticks, then adds them, `group` per joining step, and stores.  Returns the tick at which the
     last lane has nothing left."""
     NB, nk = op.n_blocks, op.nk
     NI = NB * parts
@@ -29,7 +29,8 @@ def tick_simulation(op, parts, C, V, cost):
             if parts == 1 or s < parts - 1:
                 q += [("work", own + cost.item), ("done", i)]
             else:
-                q += [("work", own), ("wait", [sp * NB + rb for sp in range(parts - 1)]), ("work", (parts - 1) * cost.join + cost.item), ("done", i)]
+                q += [("work", own), ("wait", [sp * NB + rb for sp in range(parts - 1)]),
+                      ("work", len(range(0, parts - 1, op.group)) * cost.join + cost.item), ("done", i)]
     ptr = [0] * len(lanes)
     rem = [q[0][1] if q else 0 for q in lanes]
     finished = {}
@@ -117,14 +118,14 @@ def test_items_are_dealt_in_contiguous_shares():
 
 @settings(**COMMON)
 @given(nb=st.integers(1, 9), nk=st.integers(1, 9), parts=st.integers(1, 5), C=st.integers(1, 4), V=st.integers(1, 2),
-       step=st.integers(1, 4), item=st.integers(0, 3), join=st.integers(0, 3), edge=st.integers(0, 5))
-def test_cost_of_a_decomposition_equals_a_tick_by_tick_simulation(nb, nk, parts, C, V, step, item, join, edge):
+       step=st.integers(1, 4), item=st.integers(0, 3), join=st.integers(0, 3), edge=st.integers(0, 5), group=st.integers(1, 4))
+def test_cost_of_a_decomposition_equals_a_tick_by_tick_simulation(nb, nk, parts, C, V, step, item, join, edge, group):
     parts = min(parts, nk)
-    op, cost = S.Op(nb, nk, parts), S.Cost(step, item, join, edge)
+    op, cost = S.Op(nb, nk, parts, (), group), S.Cost(step, item, join, edge)
     span, work = S.op_cost(op, parts, C, V, cost)
     assert span == tick_simulation(op, parts, C, V, cost)
-    # work: every step once, every item its store, every partial result joined once
-    assert work == nb * nk * step + nb * parts * item + nb * (parts - 1) * join
+    # work: every step once, every item its store, the partial results of a row block joined `group` at a time
+    assert work == nb * nk * step + nb * parts * item + nb * -(-(parts - 1) // group) * join
 
 
 def test_closed_forms_of_the_uncut_operator():
@@ -142,7 +143,7 @@ def test_what_the_loop_promises(data, n_ops, C, V, thr, mg):
     for o in range(n_ops):
         nk = data.draw(st.integers(1, 12))
         preds = tuple(p for p in range(o) if data.draw(st.booleans()))
-        ops.append(S.Op(data.draw(st.integers(1, 14)), nk, data.draw(st.integers(1, min(nk, 6))), preds))
+        ops.append(S.Op(data.draw(st.integers(1, 14)), nk, data.draw(st.integers(1, min(nk, 6))), preds, data.draw(st.integers(1, 3))))
     cost = S.Cost(data.draw(st.integers(1, 9)), data.draw(st.integers(0, 9)), data.draw(st.integers(0, 9)), data.draw(st.integers(0, 20)))
     parts, log = S.adaptive_tiling(ops, C, V, cost, thr, mg)
     assert all(1 <= p <= op.max_parts for p, op in zip(parts, ops))
