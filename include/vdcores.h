@@ -71,8 +71,9 @@ typedef struct {
                             /* than (100 + this) % of the average per compute core; 0 => 10                   */
     int32_t sched_min_gain_pct;  /* a finer tiling is taken only if it shortens its operator by at least this many */
                             /* per cent of the path; 0 => 3                                                   */
-    int32_t sched_force_parts;   /* 0: adaptive.  n >= 1: no scheduling, every matvec cuts K into min(n, what it    */
-                            /* may) ranges; for measuring the cost model.  No effect on what is computed      */
+    int32_t sched_force_parts;   /* 0: adaptive.  n = 1..16: no scheduling, every matvec cuts K into min(n, what it */
+                            /* may) ranges; 100 + n: the same cut on the surplus row blocks alone where the   */
+                            /* shape has a surplus.  For measuring the cost model; no effect on what is computed */
 } vdc_config;
 
 /* Create the executor on cfg->device (Section 4.3: the cores every run launches once as a persistent
@@ -379,6 +380,9 @@ typedef struct {
     int64_t nk;         /* tile steps along K per row block, >= 1                                             */
     int32_t max_parts;  /* finest decomposition the operator's builder offers, 1 .. nk                        */
     int32_t join_group; /* partial results that one joining step of the last range adds; 0 => 1                */
+    int64_t surplus;    /* T > 0 (T < n_blocks): the builder offers every cut a second time for the last T row  */
+                        /* blocks alone; the first n_blocks - T then stay whole and are dealt first, in shares  */
+                        /* of their own.  0: no such decompositions                                             */
 } vdc_sched_op;
 
 typedef struct {        /* integers in one unit of the caller's choice (the library's own model: nanoseconds) */
@@ -388,7 +392,8 @@ typedef struct {        /* integers in one unit of the caller's choice (the libr
     int64_t edge;       /* from the end of a producing item to the moment the joining item can use its result */
 } vdc_cost_model;
 
-/* parts[o] (host, n_ops) = the decomposition chosen for operator o.  ops (host); pred_begin (host, n_ops + 1 offsets
+/* parts[o] (host, n_ops) = the decomposition S chosen for operator o, tails[o] (host, n_ops; may be NULL when no operator
+ * has a surplus) = 0 when all its row blocks are cut, T when only its surplus is.  ops (host); pred_begin (host, n_ops + 1 offsets
  * into preds) and preds (host): the operators that must have ended before operator o starts, all with indices below o;
  * both may be NULL (no edges).  cost: NULL selects the library's model for tiles of tile_bytes (otherwise tile_bytes is
  * ignored).  Threshold and margin are the executor's (sched_threshold_pct, sched_min_gain_pct).  log (host, may be
@@ -396,11 +401,12 @@ typedef struct {        /* integers in one unit of the caller's choice (the libr
  * *n_looks: capacity in looks on entry, looks taken on return (n_looks may be NULL when log is).  Works on a host-only
  * executor.  VDC_EINVAL for anything malformed (an operator with more than 2^24 items among them). */
 int vdc_schedule(vdc_executor *ex, const vdc_sched_op *ops, int32_t n_ops, const int32_t *pred_begin, const int32_t *preds,
-                 const vdc_cost_model *cost, int32_t tile_bytes, int32_t *parts, int64_t *log, int32_t *n_looks);
+                 const vdc_cost_model *cost, int32_t tile_bytes, int32_t *parts, int32_t *tails, int64_t *log, int32_t *n_looks);
 
-/* What the matvec tiler decides for a dense shape (vdc_matvec, vdc_matvec_program): out (host, 6 words) = rows per
+/* What the matvec tiler decides for a dense shape (vdc_matvec, vdc_matvec_program): out (host, 7 words) = rows per
  * matrix tile, tile width in floats, row blocks, tile steps along K, the finest K cut the shape allows (1: the tiler
- * has no other decomposition for it), the cut taken.  Works on a host-only executor. */
+ * has no other decomposition for it), the cut taken, the number of trailing row blocks it is taken on (0: all).
+ * Works on a host-only executor. */
 int vdc_matvec_tiling(vdc_executor *ex, int64_t rows, int64_t K, int32_t B, int32_t tile_bytes, int64_t *out);
 
 /* Run the slot allocator of the VMC (Section 4.3, "Virtual Memory Core": the first run of contiguous free slots in

@@ -32,7 +32,8 @@ class vdc_config(ctypes.Structure):
 
 
 class vdc_sched_op(ctypes.Structure):
-    _fields_ = [("n_blocks", ctypes.c_int64), ("nk", ctypes.c_int64), ("max_parts", ctypes.c_int32), ("join_group", ctypes.c_int32)]
+    _fields_ = [("n_blocks", ctypes.c_int64), ("nk", ctypes.c_int64), ("max_parts", ctypes.c_int32), ("join_group", ctypes.c_int32),
+                ("surplus", ctypes.c_int64)]
 
 
 class vdc_cost_model(ctypes.Structure):
@@ -87,7 +88,7 @@ def lib():
             "vdc_debug_alloc": [vp, vp, vp, i32, vp, i32, vp],
             "vdc_graph_lower": [vp, vp, i64, vp, i64, vp, vp, vp, i32, ctypes.c_uint32, i32, vp, i32, vp, ctypes.POINTER(i64), vp, vp,
                                 ctypes.POINTER(i32), vp],
-            "vdc_schedule": [vp, vp, i32, vp, vp, vp, i32, vp, vp, ctypes.POINTER(i32)],
+            "vdc_schedule": [vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, ctypes.POINTER(i32)],
             "vdc_matvec_tiling": [vp, i64, i64, i32, i32, vp],
         }
         for name, args in sig.items():
@@ -331,19 +332,20 @@ class Executor:
         return ws
 
     def matvec_tiling(self, rows, K, B, tile_bytes):
-        """vdc_matvec_tiling: (rows per tile, tile width, row blocks, steps along K, finest K cut offered, K cut taken)."""
-        out = np.zeros(6, dtype=np.int64)
+        """vdc_matvec_tiling: (rows per tile, tile width, row blocks, steps along K, finest K cut offered, K cut taken,
+        trailing row blocks it is taken on or 0 for all)."""
+        out = np.zeros(7, dtype=np.int64)
         _check(lib().vdc_matvec_tiling(self.handle, rows, K, B, tile_bytes, _np_ptr(out)), "vdc_matvec_tiling")
         return tuple(int(x) for x in out)
 
     def schedule(self, ops, preds=None, cost=None, tile_bytes=16384):
-        """vdc_schedule: ops = [(n_blocks, nk, max_parts[, join_group])], preds = per operator the operators it waits for, cost =
-        (step, item, join, edge) or None for the library's model.  Returns (parts, log) with log = [(path cost, average,
-        refined operator or -1, new S, gain)]."""
+        """vdc_schedule: ops = [(n_blocks, nk, max_parts[, join_group[, surplus]])], preds = per operator the operators it
+        waits for, cost = (step, item, join, edge) or None for the library's model.  Returns (parts, tails, log) with log =
+        [(path cost, average, refined operator or -1, new S, gain)]."""
         n = len(ops)
         arr = (vdc_sched_op * max(n, 1))()
         for o, op in enumerate(ops):
-            arr[o] = vdc_sched_op(op[0], op[1], op[2], op[3] if len(op) > 3 else 0)
+            arr[o] = vdc_sched_op(op[0], op[1], op[2], op[3] if len(op) > 3 else 0, op[4] if len(op) > 4 else 0)
         pb = pr = None
         if preds is not None:
             pb = np.zeros(n + 1, dtype=np.int32)
@@ -351,13 +353,14 @@ class Executor:
             pr = np.array([q for p in preds for q in p] + [0], dtype=np.int32)
         cm = vdc_cost_model(*cost) if cost is not None else None
         parts = np.zeros(max(n, 1), dtype=np.int32)
+        tails = np.zeros(max(n, 1), dtype=np.int32)
         cap = 2 + sum(op[2] for op in ops)
         log = np.zeros((cap, 5), dtype=np.int64)
         looks = ctypes.c_int32(cap)
         _check(lib().vdc_schedule(self.handle, ctypes.cast(arr, ctypes.c_void_p), n, _np_ptr(pb) if pb is not None else None,
                                   _np_ptr(pr) if pr is not None else None, ctypes.cast(ctypes.pointer(cm), ctypes.c_void_p) if cm else None,
-                                  tile_bytes, _np_ptr(parts), _np_ptr(log), ctypes.byref(looks)), "vdc_schedule")
-        return [int(x) for x in parts[:n]], [tuple(int(x) for x in r) for r in log[:looks.value]]
+                                  tile_bytes, _np_ptr(parts), _np_ptr(tails), _np_ptr(log), ctypes.byref(looks)), "vdc_schedule")
+        return [int(x) for x in parts[:n]], [int(x) for x in tails[:n]], [tuple(int(x) for x in r) for r in log[:looks.value]]
 
     def matvec_chain(self, W, A, dims, B, tile_bytes, stream=None):
         """Y_0 = M_0 X, Y_l = M_l Y_(l-1) in one launch.  W: the matrices back to back; A: X then every Y_l, back to back

@@ -850,13 +850,14 @@ struct Tiler {
 
     // One K range [kt0, kt1) (in tiles; the last range also takes the K tail) of one row block per compute core in
     // `vs`.  Every range but the last stores its partial sums to the workspace (tensor 3) and signals its row block's depId.
-    // The workspace keeps the S - 1 partial results of a row block side by side, [row block][B][S - 1][R], so that G =
+    // The workspace keeps the S - 1 partial results of a cut row block (counted from rb0, the first of them) side by side,
+    // [row block - rb0][B][S - 1][R], so that G =
     // Kt / R of them are one vector tile ([B] rows of G R values).  The last range then adds them, G per extra tile step:
     // the matrix tile is [I I .. I | 0] (G unit matrices, from the workspace) and the vector tile holds G partial results
     // (the rest of its row reads as zero), fetched with a load that waits for the depId (Section 4.1: a load with an
     // inter-memory-uop dependency), and stores to Y.  The order of the additions is fixed by the program.
     void emit_split(int core, const std::vector<int> &vs, const std::vector<int64_t> &rbs, int s, int S, int64_t kt0, int64_t kt1,
-                    int64_t rows_total, int64_t p_base) {
+                    int64_t rows_total, int64_t rb0, int64_t p_base) {
         auto &vm = vmc(core);
         const int64_t nk_all = K / Kt, ktail = K % Kt;
         const int n = (int)vs.size();
@@ -898,15 +899,15 @@ struct Tiler {
                     const int64_t g = std::min<int64_t>(G, S - 1 - q * G);                     // partial results of this step
                     const uint32_t d_pl = desc(3, B, (uint32_t)(g * R * 4), Kt * 4, (uint64_t)prow * 4);
                     vm.push_back(encode(OP_LOAD, F_SEND, flow_m(v), v, 0, m_slots, R, 0, 0, d_id, 0));
-                    vm.push_back(encode(OP_LOAD, F_SEND | F_DEVICE | (q == 0 ? F_DEP_RECV : 0u), flow_x(v), v, 0, x_slots, B, q == 0 ? (uint32_t)rbs[i] : 0u,
-                                        p_base + (rbs[i] * B * prow + q * G * R) * 4, d_pl, q == 0 ? (uint32_t)(S - 1) : 0u));
+                    vm.push_back(encode(OP_LOAD, F_SEND | F_DEVICE | (q == 0 ? F_DEP_RECV : 0u), flow_x(v), v, 0, x_slots, B, q == 0 ? (uint32_t)(rbs[i] - rb0) : 0u,
+                                        p_base + ((rbs[i] - rb0) * B * prow + q * G * R) * 4, d_pl, q == 0 ? (uint32_t)(S - 1) : 0u));
                 }
         }
         for (int i = 0; i < n; i++) {
             const int v = vs[i];
             if (s < S - 1) {
-                vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, flow_y(v), v, 0, y_slots, B, (uint32_t)rbs[i],
-                                    p_base + (rbs[i] * B * prow + (int64_t)s * R) * 4, d_ps, 0));
+                vm.push_back(encode(OP_STORE, F_SEND | F_RECV | F_DEP_SEND, flow_y(v), v, 0, y_slots, B, (uint32_t)(rbs[i] - rb0),
+                                    p_base + ((rbs[i] - rb0) * B * prow + (int64_t)s * R) * 4, d_ps, 0));
             } else {
                 const uint32_t dy = desc(2, B, rows_valid[i] * 4, R * 4, (uint64_t)y_pitch * 4);
                 vm.push_back(encode(OP_STORE, F_SEND | F_RECV, flow_y(v), v, 0, y_slots, B, 0, rbs[i] * R * 4, dy, 0));
@@ -1014,18 +1015,24 @@ bool choose_tile(const vdc_config &cfg, int64_t K, int32_t B, int32_t tile_bytes
 // block more than others, is a dominant critical path, and cutting K is the finer decomposition that removes it.
 struct SplitPlan {
     int S = 1, S_max = 1;
-    int64_t NB = 0, ident_floats = 0, bytes = 0;   // workspace: the tile [I I .. I | 0], then the partial results [NB][B][S - 1][R]
+    int64_t NB = 0, T = 0;                         // row blocks; how many of them (the last T) are cut
+    int64_t ident_floats = 0, bytes = 0;           // workspace: the tile [I I .. I | 0], then the partial results [T][B][S - 1][R]
 };
 
 // The finest cut the builder offers for a shape: the joining step multiplies by an [I | 0] tile, so a tile must be at least
-// as wide as it is tall; every range keeps at least four tile steps; one depId per row block; a core's
+// as wide as it is tall; every range keeps at least four tile steps; one depId per cut row block; a core's
 // stream of items stays short (the cut is for shapes with few blocks per compute core: with many the deal is even enough).
-int split_max_parts(const vdc_config &cfg, int64_t NB, int64_t nk, int32_t R, int32_t Kt, bool ragged) {
+int split_max_parts(const vdc_config &cfg, int64_t NB, int64_t nk, int32_t R, int32_t Kt, bool ragged, int64_t &surplus) {
+    surplus = 0;
     if (ragged || (R & 3) || R > Kt) return 1;
     const int64_t lanes = (int64_t)cfg.n_cores * cfg.vcc_per_core;
+    // more row blocks than compute cores and some left over when they go round: those alone may be cut as well
+    if (NB > lanes && NB % lanes) surplus = NB % lanes;
+    const int64_t cut = surplus ? surplus : NB;                                 // the fewest blocks a cut may apply to
+    if (cut > (int64_t)cfg.n_dep_ids) return 1;                                 // one depId per cut row block
     int64_t S = std::min<int64_t>(16, nk / 4);
-    if (NB > (int64_t)cfg.n_dep_ids) return 1;                                  // one depId per row block
-    S = std::min<int64_t>(S, std::max<int64_t>(1, 8 * lanes / NB));            // at most eight items per compute core
+    S = std::min<int64_t>(S, std::max<int64_t>(1, 8 * lanes / cut));           // at most eight items of cut blocks per compute core
+    if (S < 2) surplus = 0;
     return (int)std::max<int64_t>(S, 1);
 }
 
@@ -1033,20 +1040,24 @@ SplitPlan plan_split(const vdc_config &cfg, int64_t rows, int64_t K, int32_t B, 
     SplitPlan sp;
     sp.NB = (rows + R - 1) / R;
     const int64_t nk = (K + Kt - 1) / Kt;
-    sp.S_max = split_max_parts(cfg, sp.NB, nk, R, Kt, ragged);
+    int64_t surplus = 0;
+    sp.S_max = split_max_parts(cfg, sp.NB, nk, R, Kt, ragged, surplus);
     if (sp.S_max < 2) return sp;
-    int32_t S = 1;
+    int32_t S = 1, tail = 0;
     if (cfg.sched_force_parts > 0) {
-        S = std::min<int32_t>(cfg.sched_force_parts, sp.S_max);
+        S = std::min<int32_t>(cfg.sched_force_parts % 100, sp.S_max);
+        tail = cfg.sched_force_parts > 100 ? (int32_t)surplus : 0;
     } else {
-        const vdc_sched_op op{sp.NB, nk, sp.S_max, Kt / R};       // a joining step adds Kt / R partial results
+        const vdc_sched_op op{sp.NB, nk, sp.S_max, Kt / R, surplus};       // a joining step adds Kt / R partial results
         if (sched_adaptive(&op, 1, nullptr, nullptr, cfg.n_cores, cfg.vcc_per_core, sched_default_cost(tile_bytes), cfg.sched_threshold_pct,
-                           cfg.sched_min_gain_pct, &S, nullptr, nullptr) != VDC_OK) S = 1;
+                           cfg.sched_min_gain_pct, &S, &tail, nullptr, nullptr) != VDC_OK) S = 1;
     }
     if (S < 2) return sp;
+    sp.T = tail > 0 ? tail : sp.NB;
+    if (sp.T > (int64_t)cfg.n_dep_ids || sp.T * S > ((int64_t)1 << 20)) return sp;   // (a cut of all blocks the builder cannot write: left whole)
     sp.S = S;
     sp.ident_floats = (int64_t)R * Kt;
-    sp.bytes = (sp.ident_floats + (int64_t)(S - 1) * B * sp.NB * R) * 4;
+    sp.bytes = (sp.ident_floats + (int64_t)(S - 1) * B * sp.T * R) * 4;
     return sp;
 }
 
@@ -1102,46 +1113,52 @@ int build_matvec(const vdc_config &cfg, int64_t rows, int64_t K, int64_t ld, int
     }
     const SplitPlan sp = rope ? SplitPlan{} : plan_split(cfg, rows, K, B, R, Kt, tile_bytes, row_off != nullptr);
     if (!rope && sp.S == 1) t.rowspan = rowspan_for(cfg, nb, K, B, R, Kt);
+    // whole row blocks: the first nw of the global list, core c takes blocks [c*nw/C, (c+1)*nw/C)
+    auto deal_whole = [&](int64_t nw) {
+        size_t si = 0;
+        for (int c = 0; c < C; c++) {
+            int64_t b0 = nw * c / C, b1 = nw * (c + 1) / C;
+            std::vector<Run> runs;
+            while (b0 < b1) {
+                while (si < segs.size() && segs[si].first_block + segs[si].n_blocks <= b0) si++;
+                const Seg &sg = segs[si];
+                int64_t e = std::min(b1, sg.first_block + sg.n_blocks);
+                int64_t lb0 = b0 - sg.first_block, lb1 = e - sg.first_block;   // local block range in the segment
+                int64_t r0 = lb0 * R, r1 = std::min(sg.len, lb1 * R);
+                Run r;
+                r.m_off = (sg.row0 + r0) * ld * 4;
+                r.x_off = row_off ? (int64_t)si * K * 4 : 0;
+                r.y_off = (sg.row0 + r0) * 4;
+                r.n_full = (r1 - r0) / R;
+                r.tail = (int32_t)((r1 - r0) % R);
+                runs.push_back(r);
+                b0 = e;
+            }
+            t.emit_core(c, runs);
+        }
+    };
     if (sp.S > 1) {
-        // items in the order (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  Only items of the last
-        // range wait, and only for items of earlier ranges, which earlier positions of the same or of earlier cores
-        // hold: no cycles.
-        const int64_t NI = sp.NB * sp.S, nk = (K + Kt - 1) / Kt;
+        // The last T row blocks are cut (all of them, or the surplus that is left when the others go round the compute
+        // cores evenly: those stay whole and come first in every core's stream).  Items of the cut blocks in the order
+        // (range, row block); core c takes items [c*NI/C, (c+1)*NI/C).  Only items of the last range wait, and only for
+        // items of earlier ranges, which earlier positions of the same or of earlier cores hold: no cycles.
+        const int64_t NW = sp.NB - sp.T, NI = sp.T * sp.S, nk = (K + Kt - 1) / Kt;
+        if (NW > 0) deal_whole(NW);
         for (int c = 0; c < C; c++) {
             int64_t i0 = NI * c / C, i1 = NI * (c + 1) / C;
             int next_v = 0;
             while (i0 < i1) {
-                const int s0 = (int)(i0 / sp.NB);
+                const int s0 = (int)(i0 / sp.T);
                 std::vector<int> vs{V == 2 ? next_v : 0};
-                std::vector<int64_t> rbs{i0 % sp.NB};
-                if (V == 2 && i0 + 1 < i1 && (int)((i0 + 1) / sp.NB) == s0) { vs = {0, 1}; rbs.push_back((i0 + 1) % sp.NB); }
+                std::vector<int64_t> rbs{NW + i0 % sp.T};
+                if (V == 2 && i0 + 1 < i1 && (int)((i0 + 1) / sp.T) == s0) { vs = {0, 1}; rbs.push_back(NW + (i0 + 1) % sp.T); }
                 else next_v ^= 1;
-                t.emit_split(c, vs, rbs, s0, sp.S, nk * s0 / sp.S, nk * (s0 + 1) / sp.S, rows, sp.ident_floats * 4);
+                t.emit_split(c, vs, rbs, s0, sp.S, nk * s0 / sp.S, nk * (s0 + 1) / sp.S, rows, NW, sp.ident_floats * 4);
                 i0 += (int64_t)vs.size();
             }
         }
     } else {
-    size_t si = 0;
-    for (int c = 0; c < C; c++) {
-        int64_t b0 = nb * c / C, b1 = nb * (c + 1) / C;
-        std::vector<Run> runs;
-        while (b0 < b1) {
-            while (si < segs.size() && segs[si].first_block + segs[si].n_blocks <= b0) si++;
-            const Seg &sg = segs[si];
-            int64_t e = std::min(b1, sg.first_block + sg.n_blocks);
-            int64_t lb0 = b0 - sg.first_block, lb1 = e - sg.first_block;   // local block range in the segment
-            int64_t r0 = lb0 * R, r1 = std::min(sg.len, lb1 * R);
-            Run r;
-            r.m_off = (sg.row0 + r0) * ld * 4;
-            r.x_off = row_off ? (int64_t)si * K * 4 : 0;
-            r.y_off = (sg.row0 + r0) * 4;
-            r.n_full = (r1 - r0) / R;
-            r.tail = (int32_t)((r1 - r0) % R);
-            runs.push_back(r);
-            b0 = e;
-        }
-        t.emit_core(c, runs);
-    }
+        deal_whole(nb);
     }
     words.clear();
     sb.assign(1, 0);
@@ -1533,7 +1550,7 @@ int build_attn(const vdc_config &cfg, const int64_t *row_off, int32_t n_seg, int
 
 int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
     if (c.sched_threshold_pct < 0 || c.sched_threshold_pct > 1000 || c.sched_min_gain_pct < 0 || c.sched_min_gain_pct > 100 ||
-        c.sched_force_parts < 0 || c.sched_force_parts > 16) return VDC_EINVAL;
+        c.sched_force_parts < 0 || (c.sched_force_parts > 16 && (c.sched_force_parts < 101 || c.sched_force_parts > 116))) return VDC_EINVAL;
     if (c.sched_threshold_pct == 0) c.sched_threshold_pct = kSchedThresholdPct;
     if (c.sched_min_gain_pct == 0) c.sched_min_gain_pct = kSchedMinGainPct;
     if (c.issue_batch < 0 || c.issue_batch > 8 || (c.issue_flags & ~1)) return VDC_EINVAL;
@@ -2183,6 +2200,7 @@ int vdc_matvec_tiling(vdc_executor *ex, int64_t rows, int64_t K, int32_t B, int3
     if (!choose_tile(ex->cfg, K, B, tile_bytes, R, Kt)) return VDC_EINVAL;
     const SplitPlan sp = plan_split(ex->cfg, rows, K, B, R, Kt, tile_bytes, false);
     out[0] = R; out[1] = Kt; out[2] = sp.NB; out[3] = (K + Kt - 1) / Kt; out[4] = sp.S_max; out[5] = sp.S;
+    out[6] = sp.S > 1 && sp.T < sp.NB ? sp.T : 0;
     return VDC_OK;
 }
 

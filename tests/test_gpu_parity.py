@@ -69,10 +69,10 @@ DENSE_CASES = [
     (256, 32768, 32768, 3, 8192),
     (100, 8200, 8204, 2, 4096),        # row tail and K tail in a split program
     (16, 4096, 4096, 8, 16384),
-    # one and a half row blocks per compute core: the adaptive tiling step cuts K although every compute core has work
-    (12288, 8192, 8192, 1, 16384),
-    (24570, 4096, 4096, 8, 16384),     # ... eight vectors, a ragged last block
-    (9216, 16392, 16400, 1, 16384),    # ... a K tail and a leading dimension in the last range
+    # more row blocks than compute cores and some left over: the adaptive tiling step cuts K of the surplus blocks alone
+    (10240, 8192, 8192, 1, 16384),     # 640 row blocks on 512 compute cores: 128 cut in four
+    (9216, 16392, 16400, 1, 16384),    # ... a K tail and a leading dimension in the last range; 64 cut in eight
+    (8180, 8192, 8192, 8, 16384),      # half as many row blocks as compute cores, eight vectors, a ragged last block: all cut in two
 ]
 
 
@@ -95,6 +95,8 @@ def test_dense_matvec_against_fp64_gemv(ex, rows, K, ld, B, T):
     (dict(sched_force_parts=16, n_cores=64), (300, 16384, 16384, 3, 8192)),   # the finest cut the builder offers
     (dict(sched_force_parts=1), (64, 65536, 65536, 1, 16384)),                # and none at all where the scheduler would cut
     (dict(sched_threshold_pct=300), (12288, 8192, 8192, 1, 16384)),           # a threshold nothing exceeds: left uncut
+    (dict(sched_force_parts=103, n_cores=8), (300, 4096, 4100, 2, 4096)),     # 38 row blocks on 16 compute cores: 32 whole, 6 cut in three
+    (dict(sched_force_parts=116), (9200, 16384, 16384, 1, 16384)),            # 575 on 512: the 63 surplus blocks in sixteen ranges
 ])
 def test_cuts_of_k_the_scheduler_would_not_take(cfg, shape):
     """Every decomposition the builder offers gives the GEMV, whatever the cost model thinks of it (sched_force_parts), with
@@ -104,9 +106,9 @@ def test_cuts_of_k_the_scheduler_would_not_take(cfg, shape):
     M = rng.standard_normal((rows, ld)).astype(np.float32)
     X = rng.standard_normal((B, K)).astype(np.float32)
     with vdc.Executor(**cfg) as e:
-        s_max, s = e.matvec_tiling(rows, K, B, T)[4:]
+        s_max, s, tail = e.matvec_tiling(rows, K, B, T)[4:]
         if "sched_force_parts" in cfg:
-            assert s == min(cfg["sched_force_parts"], s_max)
+            assert s == min(cfg["sched_force_parts"] % 100, s_max) and (tail > 0) == (cfg["sched_force_parts"] > 100)
         else:
             assert s == 1 and s_max > 1
         dY = torch.full((B, rows), float("nan"), device="cuda")

@@ -16,7 +16,7 @@ COMMON = dict(deadline=None, max_examples=80, derandomize=True, suppress_health_
 def library_cost(tile_bytes):
     """The cost model the header documents for the tilers: nanoseconds for tiles of tile_bytes."""
     step = 510 + tile_bytes // 20
-    return S.Cost(step=step, item=3000, join=step + 1200, edge=4000)
+    return S.Cost(step=step, item=1500, join=step + 1200, edge=16000)
 
 
 @settings(**COMMON)
@@ -25,16 +25,18 @@ def test_the_library_takes_the_looks_the_oracle_takes(data, n_ops, C, V, thr, mg
     ops, preds = [], []
     for o in range(n_ops):
         nk = data.draw(st.integers(1, 40))
-        ops.append((data.draw(st.integers(1, 40)), nk, data.draw(st.integers(1, min(nk, 8))), data.draw(st.integers(1, 5))))
+        nb = data.draw(st.integers(1, 40))
+        ops.append((nb, nk, data.draw(st.integers(1, min(nk, 8))), data.draw(st.integers(1, 5)), nb % (C * V) if nb > C * V else 0))
         preds.append(tuple(p for p in range(o) if data.draw(st.booleans())))
     cost = tuple(data.draw(st.integers(lo, 50)) for lo in (1, 0, 0, 0))
-    want_parts, want_log = S.adaptive_tiling([S.Op(nb, nk, mp, pr, g) for (nb, nk, mp, g), pr in zip(ops, preds)], C, V, S.Cost(*cost), thr, mg)
+    want_parts, want_tails, want_log = S.adaptive_tiling([S.Op(nb, nk, mp, pr, g, su) for (nb, nk, mp, g, su), pr in zip(ops, preds)], C, V,
+                                                         S.Cost(*cost), thr, mg)
     with vdc.Executor(device=-1, n_cores=C, vcc_per_core=V, sched_threshold_pct=thr, sched_min_gain_pct=mg) as ex:
-        parts, log = ex.schedule(ops, preds, cost)
-        assert parts == want_parts
+        parts, tails, log = ex.schedule(ops, preds, cost)
+        assert parts == want_parts and tails == want_tails
         assert log == [(pc, avg, o, s, g) for pc, avg, _, o, s, g in want_log]
         if all(not p for p in preds):
-            assert ex.schedule(ops, None, cost) == (parts, log)
+            assert ex.schedule(ops, None, cost) == (parts, tails, log)
 
 
 def test_malformed_graphs_are_refused():
@@ -42,13 +44,14 @@ def test_malformed_graphs_are_refused():
         for ops, preds, cost in [([(0, 4, 1)], None, (1, 0, 0, 0)), ([(4, 0, 1)], None, (1, 0, 0, 0)), ([(4, 4, 5)], None, (1, 0, 0, 0)),
                                  ([(4, 4, 0)], None, (1, 0, 0, 0)), ([(4, 4, 2)], None, (0, 0, 0, 0)), ([(4, 4, 2)], None, (1, -1, 0, 0)),
                                  ([(4, 4, 2), (4, 4, 2)], [(1,), ()], (1, 0, 0, 0)), ([(4, 4, 2)], [(0,)], (1, 0, 0, 0)),
-                                 ([(1 << 23, 8, 4)], None, (1, 0, 0, 0)), ([(4, 4, 2, -1)], None, (1, 0, 0, 0))]:
+                                 ([(1 << 23, 8, 4)], None, (1, 0, 0, 0)), ([(4, 4, 2, -1)], None, (1, 0, 0, 0)),
+                                 ([(4, 4, 2, 1, 4)], None, (1, 0, 0, 0)), ([(4, 4, 2, 1, -1)], None, (1, 0, 0, 0))]:
             with pytest.raises(vdc.VdcError) as e:
                 ex.schedule(ops, preds, cost)
             assert e.value.code == vdc.VDC_EINVAL
         with pytest.raises(vdc.VdcError):
             ex.schedule([(4, 4, 2)], None, None, tile_bytes=100)
-    for bad in (dict(sched_threshold_pct=-1), dict(sched_min_gain_pct=101), dict(sched_force_parts=17)):
+    for bad in (dict(sched_threshold_pct=-1), dict(sched_min_gain_pct=101), dict(sched_force_parts=17), dict(sched_force_parts=100), dict(sched_force_parts=117)):
         with pytest.raises(vdc.VdcError):
             vdc.Executor(device=-1, **bad)
 
@@ -58,22 +61,27 @@ def test_malformed_graphs_are_refused():
        C=st.sampled_from([3, 16, 256]))
 def test_the_matvec_tiler_takes_the_cut_the_oracle_would(rows, nk, B, tile, C):
     with vdc.Executor(device=-1, n_cores=C) as ex:
-        R, Kt, NB, nk_, s_max, s = ex.matvec_tiling(rows, 256 * nk, B, tile)
+        R, Kt, NB, nk_, s_max, s, tail = ex.matvec_tiling(rows, 256 * nk, B, tile)
         assert NB == -(-rows // R) and nk_ == -(-256 * nk // Kt) and 1 <= s <= s_max
-        want, _ = S.adaptive_tiling([S.Op(NB, nk_, s_max, (), Kt // R)], C, 2, library_cost(tile))
-        assert [s] == want
-        # what the builder offers: at least four steps a range, a depId per row block, a short stream per core
-        assert s_max == 1 or (s_max <= min(16, nk_ // 4) and NB <= 4096 and s_max * NB <= max(NB, 8 * 2 * C) and R % 4 == 0 and R <= Kt)
+        # what the builder offers: the surplus row blocks alone where there are any; at least four steps a range, a depId per
+        # cut row block, a short stream of cut items per core
+        lanes = 2 * C
+        surplus = NB % lanes if NB > lanes and R % 4 == 0 and R <= Kt and min(16, nk_ // 4, 8 * lanes // (NB % lanes or NB)) >= 2 else 0
+        cut = surplus or NB
+        assert s_max == 1 or (s_max <= min(16, nk_ // 4) and cut <= 4096 and s_max * cut <= max(cut, 8 * lanes) and R % 4 == 0 and R <= Kt)
+        want, want_tail, _ = S.adaptive_tiling([S.Op(NB, nk_, s_max, (), Kt // R, surplus)], C, 2, library_cost(tile))
+        assert ([s], [tail]) == (want, want_tail) and tail in (0, surplus)
 
 
 def test_shapes_of_the_benchmark_configurations_and_awkward_ones():
     with vdc.Executor(device=-1, n_cores=256) as ex:
-        assert ex.matvec_tiling(32768, 65536, 8, 16384)[2:] == (1024, 512, 4, 1)        # two row blocks a compute core: left alone
-        assert ex.matvec_tiling(8192, 8192, 1, 8192)[2:] == (1024, 32, 4, 1)
-        R, Kt, NB, nk, s_max, s = ex.matvec_tiling(12288, 8192, 1, 16384)              # one and a half: cut
-        assert (NB, nk) == (768, 32) and s >= 2
-        R, Kt, NB, nk, s_max, s = ex.matvec_tiling(1024, 16384, 1, 16384)              # an eighth of the compute cores busy: cut
-        assert NB == 64 and s >= 4
+        assert ex.matvec_tiling(32768, 65536, 8, 16384)[2:] == (1024, 512, 4, 1, 0)     # two row blocks a compute core: left alone
+        assert ex.matvec_tiling(8192, 8192, 1, 8192)[2:] == (1024, 32, 4, 1, 0)
+        R, Kt, NB, nk, s_max, s, tail = ex.matvec_tiling(9216, 16384, 1, 16384)        # 64 blocks over: those alone are cut
+        assert (NB, nk, tail) == (576, 64, 64) and s >= 4
+        assert ex.matvec_tiling(12288, 8192, 1, 16384)[2:] == (768, 32, 8, 1, 0)       # 256 over, short rows: no cut is worth its dependency
+        R, Kt, NB, nk, s_max, s, tail = ex.matvec_tiling(1024, 16384, 1, 16384)        # an eighth of the compute cores busy: cut
+        assert NB == 64 and s >= 4 and tail == 0
 
 
 def _run(ex, rows, K, B, tile, ncores, slot, nslots, seed):
@@ -108,14 +116,15 @@ def test_programs_of_cut_shapes_equal_the_gemv(blocks_x2, extra, nk, B, ncores, 
     with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots) as ex:
         R, Kt = ex.matvec_tiling(4, 128 * nk, B, tile)[:2]
         rows = max(1, blocks_x2 * ncores * R - extra)                # NB = blocks_x2 / 2 per compute core, give or take
-        s = ex.matvec_tiling(rows, Kt * nk, B, tile)[5]
+        s, tail = ex.matvec_tiling(rows, Kt * nk, B, tile)[5:]
         signals = _run(ex, rows, Kt * nk, B, tile, ncores, slot, nslots, seed)
-        assert signals == (s - 1) * -(-rows // R)                    # every partial result is one more store
-        CUT_SEEN.append(s)
+        assert signals == (s - 1) * (tail or -(-rows // R))          # every partial result is one more store
+        CUT_SEEN.append((s, tail))
 
 
 def test_the_adaptive_step_did_cut_some_of_those_shapes():
-    assert CUT_SEEN and max(CUT_SEEN) >= 2 and min(CUT_SEEN) == 1
+    assert CUT_SEEN and max(s for s, _ in CUT_SEEN) >= 2 and min(s for s, _ in CUT_SEEN) == 1
+    assert any(t > 0 for _, t in CUT_SEEN) and any(s > 1 and t == 0 for s, t in CUT_SEEN)       # the surplus alone, and all blocks
 
 
 @pytest.mark.parametrize("ncores,force,rows,nk,B,tile,slot,nslots", [
@@ -123,11 +132,16 @@ def test_the_adaptive_step_did_cut_some_of_those_shapes():
     (2, 2, 4, 9, 2, 2048, 2048, 16),
     (2, 16, 70, 64, 8, 16384, 8192, 19),      # tiles of 32 rows x 128 columns: four partial results per joining step, fifteen to join
     (3, 7, 100, 30, 8, 16384, 8192, 19),      # ... six: a full step and a short one
+    # the surplus row blocks alone: whole blocks first (looped or unrolled form), then the items of the cut blocks
+    (2, 102, 27, 16, 2, 2048, 2048, 16),      # 7 row blocks on 4 compute cores: 4 whole, 3 cut in two
+    (1, 104, 90, 16, 1, 2048, 2048, 16),      # 23 on 2: 22 whole (the looped form), 1 cut in four
+    (3, 103, 50, 12, 3, 2048, 2048, 16),      # 13 on 6, a ragged last block among the cut ones
+    (2, 116, 200, 64, 8, 16384, 8192, 19),    # 7 on 4 with tiles of 32 rows: 3 cut in sixteen, four joining steps
 ])
 def test_forced_cuts_with_partial_and_joining_items_on_one_core(ncores, force, rows, nk, B, tile, slot, nslots):
     """sched_force_parts takes the scheduler out: every K cut the builder offers can be run, also where it would not pay."""
     with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=slot, n_slots=nslots, sched_force_parts=force) as ex:
-        R, Kt, NB, nk_, s_max, s = ex.matvec_tiling(rows, 128 * nk, B, tile)
-        assert s == min(force, s_max) and s >= 2
+        R, Kt, NB, nk_, s_max, s, tail = ex.matvec_tiling(rows, 128 * nk, B, tile)
+        assert s == min(force % 100, s_max) and s >= 2 and (tail > 0) == (force > 100)
         signals = _run(ex, rows, 128 * nk, B, tile, ncores, slot, nslots, rows)
-        assert signals == (s - 1) * NB
+        assert signals == (s - 1) * (tail or NB)
