@@ -107,7 +107,7 @@ CUT_SEEN = []
 
 
 @settings(**COMMON)
-@given(blocks_x2=st.integers(1, 15), extra=st.integers(0, 3), nk=st.integers(8, 40), B=st.sampled_from([1, 2, 3]), ncores=st.integers(1, 4),
+@given(blocks_x2=st.integers(1, 15), extra=st.integers(0, 3), nk=st.integers(8, 200), B=st.sampled_from([1, 2, 3]), ncores=st.integers(1, 4),
        seed=st.integers(0, 1000))
 def test_programs_of_cut_shapes_equal_the_gemv(blocks_x2, extra, nk, B, ncores, seed):
     """Row-block counts around half-integer multiples of the number of compute cores (where the adaptive step cuts K), with a
