@@ -210,6 +210,49 @@ def test_uop_traces_and_result_match_the_interpreter(name):
     _check(Yo, Yr, Ya, name + " (interpreter)")
 
 
+@pytest.mark.parametrize("cfg,shape", [
+    (dict(sched_force_parts=4), (96, 8192, 8192, 2, 4096)),          # all 12 row blocks in four ranges on 16 compute cores
+    (dict(sched_force_parts=103), (300, 4096, 4100, 2, 4096)),       # 38 row blocks: 32 whole, the 6 left over in three ranges
+    (dict(sched_force_parts=16), (160, 8192 + 36, 8192 + 36, 8, 16384)),    # 5 blocks of 32 rows, 15 partial results joined four a step, a K tail
+])
+def test_uop_traces_of_cut_programs_match_the_interpreter(cfg, shape):
+    """Programs in which the adaptive tiling step's decompositions are forced (K cut for all row blocks, for the surplus
+    alone): every unit's trace (pc, uop, generated address), the depId waits among them, is bit-exact against the interpreter
+    running the same graph, and the result is the fp64 GEMV."""
+    rows, K, ld, B, T = shape
+    rng = np.random.default_rng(rows + K)
+    M = rng.standard_normal((rows, ld)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    with vdc.Executor(n_cores=8, **cfg) as ex:
+        nc, ns, slot = ex.cfg.n_cores, ex.cfg.n_slots, ex.cfg.slot_bytes
+        s, tail = ex.matvec_tiling(rows, K, B, T)[5:]
+        assert s == cfg["sched_force_parts"] % 100 and (tail > 0) == (cfg["sched_force_parts"] > 100)
+        words, sb, descs = ex.matvec_program(rows, K, ld, B, T)
+        ws = ex.matvec_workspace(rows, K, ld, B, T)
+        assert ws.size
+        prog = ex.program_create(words, sb, descs, [((rows - 1) * ld + K) * 4, X.nbytes, B * rows * 4, ws.nbytes])
+        dY = torch.full((B, rows), float("nan"), device="cuda")
+        cap = 8192
+        trace, count = ex.run(prog, [_dev(M), _dev(X), dY, _dev(ws)], trace_cap=cap)
+        ex.check()
+        trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+    Yo = np.full((B, rows), np.nan, np.float32)
+    m = UM.Machine(words, sb, descs, [M, X, Yo, ws.copy()], n_cores=nc, slot_bytes=slot, n_slots=ns).run()
+    V = 2
+    for core in range(nc):
+        st = core * (1 + V)
+        exp = [(pc, op | (d << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, d, off, n) in m.trace_vmc[core]]
+        assert count[st] == len(exp) <= cap
+        assert [tuple(int(x) for x in r) for r in trace[st, :len(exp)]] == exp
+        for v in range(V):
+            exp = [(pc, op | (n << 16), imm & 0xFFFFFFFF, imm >> 32) for (pc, op, n, imm) in m.trace_vcc[core][v]]
+            assert count[st + 1 + v] == len(exp)
+            assert [tuple(int(x) for x in r) for r in trace[st + 1 + v, :len(exp)]] == exp
+    Yr, Ya = gemv_ref.gemv_dense(M, X, ld=ld)
+    _check(dY.cpu().numpy(), Yr, Ya, "cut %s %s" % (cfg, shape))
+    _check(Yo, Yr, Ya, "cut %s %s (interpreter)" % (cfg, shape))
+
+
 def test_programs_assembled_by_the_oracle_side_run_on_the_gpu():
     """uop graphs that no product code produced (oracle-side assembler), through vdc_program_create / vdc_run."""
     rng = np.random.default_rng(3)
