@@ -243,8 +243,9 @@ int vdc_matvec_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, in
 int vdc_matvec_rope_program(vdc_executor *ex, int64_t rows, int64_t K, int64_t ld, int32_t B, int32_t tile_bytes,
                             void *uops, int64_t *n_uops, uint32_t *stream_begin, void *descs, int32_t *n_descs);
 
-/* A dense matrix with far fewer row blocks than there are compute cores is also cut along K: each (K range,
- * row block) pair is a work item, and the partial sums pass from range to range through a library-owned workspace
+/* Where the adaptive tiling step finds it worth while (vdc_matvec_tiling; Section 4.2), a dense matrix whose row blocks
+ * do not fill the compute cores evenly is also cut along K, all its row blocks or the surplus ones: each (K range,
+ * row block) pair is a work item, and the partial sums pass to the item of the last range through a library-owned workspace
  * with depId signals (Section 4.1, dependencies between memory uops; Section 4.3, the global depId queue).  The
  * emitted program then names a fourth tensor, 3 = the workspace.  This call gives its size in *bytes (0: the shape
  * is not split, the program uses tensors 0..2 only) and, if init != NULL, its initial content (host buffer of
