@@ -47,8 +47,8 @@ def descriptor(tensor, box_rows, row_bytes, lds_pitch, gpitch):
 
 def matvec_imm(B, R, lpr, xspan=0):
     """Static geometry of a MATVEC: B vectors, R box rows per matrix tile, lpr 16-byte chunks per tile row; xspan >= 2:
-    one vector tile holds the pieces of xspan consecutive steps, one per row (B = 1 only)."""
-    assert 1 <= B <= 8 and 1 <= R < 65536 and 1 <= lpr < 65536 and 0 <= xspan < 128 and (xspan < 2 or B == 1)
+    one vector tile holds the pieces of xspan consecutive steps (B = 1: one per row; B > 1: B rows of xspan pieces)."""
+    assert 1 <= B <= 8 and 1 <= R < 65536 and 1 <= lpr < 65536 and 0 <= xspan < 128
     return B | (R << 8) | (lpr << 24) | (xspan << 40)
 
 
@@ -117,8 +117,8 @@ def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_cor
     row blocks of R rows are dealt round-robin to the (core, vcc) pairs; each row block is one MATVEC
     over ceil(K/Kt) (matrix tile, vector tile) pairs, followed by a send+recv STORE of the result.
     No loops, no accumulators: every address is a literal.  Tensors: 0 = M, 1 = X, 2 = Y.
-    xspan >= 2 (B = 1, K a multiple of Kt): one vector tile of xspan rows serves xspan consecutive steps; it is loaded
-    before the first matrix tile of those steps.
+    xspan >= 2 (K a multiple of Kt): one vector tile serves xspan consecutive steps (B = 1: xspan rows, one piece each;
+    B > 1: B rows of xspan pieces side by side); it is loaded before the first matrix tile of those steps.
 
     rope=True builds the fused form of the running example of Section 3 (O = M @ N; R = rope(O, T)):
     the matvec result never goes to memory; a store.local / load.local pair hands its region on to a
@@ -144,11 +144,16 @@ def dense_matvec_program(rows, K, ld, B, R, Kt, slot_bytes, n_cores, vcc_per_cor
             dm = p.desc(0, R, kv * 4, Kt * 4, ld * 4)
             dx = p.desc(1, B, kv * 4, Kt * 4, K * 4)
             if xspan >= 2 and kt % xspan == 0:
-                assert B == 1 and K % Kt == 0
+                assert K % Kt == 0
                 steps = min(xspan, nk - kt)
-                dxs = p.desc(1, xspan, Kt * 4, Kt * 4, Kt * 4)      # xspan pieces of the vector, one per row
-                vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=-(-xspan * Kt * 4 // slot_bytes), size=steps,
-                               imm=k0 * 4, desc=dxs))
+                if B == 1:
+                    dxs = p.desc(1, xspan, Kt * 4, Kt * 4, Kt * 4)      # xspan pieces of the vector, one per row
+                    vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=-(-xspan * Kt * 4 // slot_bytes), size=steps,
+                                   imm=k0 * 4, desc=dxs))
+                else:
+                    dxs = p.desc(1, B, steps * Kt * 4, xspan * Kt * 4, K * 4)   # B rows, the pieces of the steps side by side
+                    vm.append(word(LOAD, F_SEND, vflow=2 * v + 1, vcc=v, nslots=-(-B * xspan * Kt * 4 // slot_bytes), size=B,
+                                   imm=k0 * 4, desc=dxs))
             vm.append(word(LOAD, F_SEND | (F_NT if nt else 0), vflow=2 * v, vcc=v, nslots=m_slots, size=rv,
                            imm=(r0 * ld + k0) * 4, desc=dm))
             if xspan < 2:

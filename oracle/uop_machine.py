@@ -450,18 +450,20 @@ class Machine:
             return
         c = np.zeros((B, R), dtype=np.float64)            # the accumulators the uop keeps over all its tile steps
         if xspan >= 2:
-            # The tile shape is the tiler's to choose (the listing fixes none): with one vector, a vector tile may hold
-            # the pieces of `xspan` consecutive steps, one per row.  It is popped before the first matrix tile it
-            # serves, kept while the matrix tiles of its steps come and go, and handed back after the last of them.
-            if B != 1:
-                raise ProgramError("matvec: a vector tile over several steps needs B = 1")
+            # The tile shape is the tiler's to choose (the listing fixes none): a vector tile may hold the pieces of `xspan`
+            # consecutive steps.  With one vector: one piece per row.  With B vectors: B rows of xspan pieces side by
+            # side, i.e. the vectors' next xspan * Kt columns as they lie in memory.  It is popped before the first matrix
+            # tile it serves, kept while the matrix tiles of its steps come and go, and handed back after the last of them.
             held = None
             for i in range(u.size):
                 if i % xspan == 0:
                     if held is not None:
                         self._c2m_push(core, v, KIND_FREE, held[0], held[1])
                     held = yield                           # wait for the vector tile of this and the next xspan - 1 steps
-                    if held[2] < min(xspan, u.size - i) or held[3] != Kt * 4:
+                    need = min(xspan, u.size - i)
+                    if B == 1 and (held[2] < need or held[3] != Kt * 4):
+                        raise ProgramError("matvec: vector tile does not hold the steps it is popped for")
+                    if B > 1 and (held[2] != B or held[3] < need * Kt * 4 or held[3] > xspan * Kt * 4):
                         raise ProgramError("matvec: vector tile does not hold the steps it is popped for")
                 a = yield                                  # wait for the matrix tile
                 a_slot, a_n, a_rows, a_rb = a
@@ -469,7 +471,11 @@ class Machine:
                     raise ProgramError("matvec: tile geometry does not match the uop")
                 at = core.region(a_slot, a_n).view(np.float32)[:R * Kt].reshape(R, Kt).astype(np.float64)
                 j = i % xspan
-                bt = core.region(held[0], held[1]).view(np.float32)[j * Kt:(j + 1) * Kt].reshape(1, Kt).astype(np.float64)
+                hv = core.region(held[0], held[1]).view(np.float32)
+                if B == 1:
+                    bt = hv[j * Kt:(j + 1) * Kt].reshape(1, Kt).astype(np.float64)
+                else:
+                    bt = hv[:B * xspan * Kt].reshape(B, xspan * Kt)[:, j * Kt:(j + 1) * Kt].astype(np.float64)
                 c += bt @ at.T
                 self._c2m_push(core, v, KIND_FREE, a_slot, a_n)
             if held is not None:

@@ -119,6 +119,53 @@ def test_dense_program_equals_gemv(rows, K, B, R, Kt, slot, ncores):
     _check_result(M, X, Y)
 
 
+@pytest.mark.parametrize("rows,K,R,Kt,slot,ncores,xspan,B", [
+    (40, 512, 8, 64, 2048, 2, 2, 3),     # three vectors: a vector tile is three rows of two pieces side by side
+    (33, 448, 8, 64, 4096, 3, 4, 4),     # seven steps: the second vector tile holds three pieces a row
+    (64, 1024, 32, 128, 8192, 1, 2, 8),  # the shape of the headline workload's tiles: 8 vectors, 32 rows x 128 columns
+])
+def test_a_vector_tile_over_several_steps_with_several_vectors(rows, K, R, Kt, slot, ncores, xspan, B):
+    """The same with B > 1: the vector tile holds B rows of xspan pieces as they lie in memory.  The textbook product, the
+    bits of the step-by-step program, every schedule the same image, single entries of the matrix against vectors whose
+    every entry is different (a slip in row or piece would pick another value), the load counts."""
+    M, X, Y = _inputs(rows, K, B, seed=rows + K + xspan)
+    p = A.dense_matvec_program(rows, K, K, B, R, Kt, slot, ncores, xspan=xspan)
+    m = _run(p, [M, X, Y], slot_bytes=slot, n_slots=12)
+    _check_result(M, X, Y)
+    Y1 = np.full_like(Y, np.nan)
+    _run(A.dense_matvec_program(rows, K, K, B, R, Kt, slot, ncores), [M, X, Y1], slot_bytes=slot, n_slots=12)
+    assert np.array_equal(Y, Y1)
+    for seed in range(5):
+        Y2 = np.full_like(Y, np.nan)
+        w, sb, d = p.finish()
+        UM.Machine(w, sb, d, [M, X, Y2], n_cores=ncores, slot_bytes=slot, n_slots=12).run("random", seed).check_final()
+        assert np.array_equal(Y, Y2)
+    X0 = (np.arange(1, K + 1, dtype=np.float32)[None, :] + 4096.0 * np.arange(B, dtype=np.float32)[:, None])
+    for (i, j) in [(0, 0), (rows - 1, K - 1), (rows // 2, Kt + 1), (3, K - Kt)]:
+        M0 = np.zeros((rows, K), np.float32)
+        M0[i, j] = 2.0
+        Y0 = np.full((B, rows), np.nan, np.float32)
+        _run(p, [M0, X0, Y0], slot_bytes=slot, n_slots=12)
+        exp = np.zeros((B, rows), np.float32)
+        exp[:, i] = 2.0 * X0[:, j]
+        assert np.array_equal(Y0, exp)
+    loads_x = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 1)
+    loads_m = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 0)
+    nk, nrb = K // Kt, -(-rows // R)
+    assert loads_m == nk * nrb and loads_x == -(-nk // xspan) * nrb
+    # a vector tile with a row too few, or with rows too short for the steps it is popped for, is refused
+    w, sb, d = p.finish()
+    ix = [k for k in range(len(w)) if (w[k, 0] & 0xFF) == A.LOAD and d[UM.decode(w[k]).desc][0] == 1]
+    w2 = np.array(w, copy=True)
+    w2[ix[0], 1] = (w2[ix[0], 1] & 0xFFFF0000) | (B - 1)
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(w2, sb, d, [M, X, Y], n_cores=ncores, slot_bytes=slot, n_slots=12).run()
+    d2 = np.array(d, copy=True)
+    d2[UM.decode(w[ix[0]]).desc][2] = Kt * 4             # one piece a row where the uop needs xspan
+    with pytest.raises(UM.ProgramError):
+        UM.Machine(w, sb, d2, [M, X, Y], n_cores=ncores, slot_bytes=slot, n_slots=12).run()
+
+
 @pytest.mark.parametrize("rows,K,R,Kt,slot,ncores,xspan", [
     (40, 512, 8, 64, 2048, 2, 8),        # eight steps: one vector tile for the whole row block
     (40, 512, 8, 64, 2048, 2, 4),        # two vector tiles of four steps
@@ -157,13 +204,13 @@ def test_a_vector_tile_over_several_steps_equals_gemv(rows, K, R, Kt, slot, ncor
     assert loads_m == nk * nrb and loads_x == -(-nk // xspan) * nrb
 
 
-def test_a_vector_tile_over_several_steps_needs_one_vector_and_enough_rows():
+def test_a_vector_tile_over_several_steps_must_hold_the_pieces_of_its_steps():
     M, X, Y = _inputs(16, 256, 2, seed=1)
     p = A.dense_matvec_program(16, 256, 256, 2, 8, 64, 2048, 1)
     w, sb, d = p.finish()
     w = np.array(w, copy=True)
     i = int(np.flatnonzero((w[:, 0] & 0xFF) == A.MATVEC)[0])
-    w[i, 3] |= 2 << 8                                    # xspan = 2 in imm[47:40] on a B = 2 uop
+    w[i, 3] |= 2 << 8                                    # xspan = 2 in imm[47:40] on a B = 2 uop whose vector tiles hold one piece a row
     with pytest.raises(UM.ProgramError):
         UM.Machine(w, sb, d, [M, X, Y], n_cores=1, slot_bytes=2048, n_slots=12).run()
     # a vector tile that holds fewer rows than the steps it is popped for
