@@ -66,7 +66,9 @@ typedef struct {
     int32_t issue_batch;    /* memory uops the front end dispatches at once at most, 1..8; 0 => 8.  For   */
                             /* measuring the issue path (Section 6.3); no effect on results              */
     int32_t issue_flags;    /* bit 0: the front end does not replay loop bodies, every trip is decoded   */
-                            /* and dispatched through its general path (same purpose); other bits zero   */
+                            /* and dispatched through its general path (same purpose); bit 1: the matvec */
+                            /* tiler gives eight vectors a vector tile over two steps where the shape    */
+                            /* allows it (for measuring that form: slower); other bits zero              */
     int32_t sched_threshold_pct; /* adaptive tiling (Section 4.2): a critical path is dominant when it costs more  */
                             /* than (100 + this) % of the average per compute core; 0 => 10                   */
     int32_t sched_min_gain_pct;  /* a finer tiling is taken only if it shortens its operator by at least this many */

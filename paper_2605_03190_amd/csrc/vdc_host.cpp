@@ -438,7 +438,7 @@ struct Validator {
             v.lpr = (uint32_t)(f.imm >> 24) & 0xFFFFu;
             if (!matvec_geometry_ok(v.B, v.R, v.lpr, nullptr, nullptr)) { fail("matvec geometry not supported"); return -1; }
             v.xspan = matvec_xspan(f.imm);
-            if (v.xspan >= 2 && (v.B != 1 || v.xspan > kMaxXspan || v.lpr > 64)) { fail("matvec: a vector tile over several steps needs B = 1, at most 8 steps and rows inside one wave"); return -1; }
+            if (v.xspan >= 2 && (v.xspan > kMaxXspan || v.lpr > 64 || !matvec_xspan_ok(v.B, v.R, v.lpr))) { fail("matvec: a vector tile over several steps needs at most 8 steps, rows inside one wave, and one vector or a geometry the compute uop has with several"); return -1; }
             if (f.size < 1) { fail("matvec over zero tiles"); return -1; }
             v.rowspan = matvec_rowspan(f);
             if (v.rowspan >= 2 && (f.size != 1 || v.xspan >= 2 || v.lpr > 64 || v.rowspan > kMaxRowspan || v.B > kMaxRowspanB)) {
@@ -550,7 +550,11 @@ struct Validator {
         }
         if (v.phase == 3) {
             // the vector tile of the next min(xspan, left) steps
-            if (m.is_store || m.lds_pitch != v.lpr * 16 || m.row_bytes != v.lpr * 16 || m.rows < std::min(v.xspan, v.left)) { fail("matvec: vector tile does not hold the steps it is popped for"); return -1; }
+            const uint32_t need = std::min(v.xspan, v.left);
+            const bool ok1 = v.B == 1 && m.lds_pitch == v.lpr * 16 && m.row_bytes == v.lpr * 16 && m.rows >= need;
+            // several vectors: B rows of xspan pieces side by side
+            const bool okb = v.B > 1 && m.rows == v.B && m.box_rows == v.B && m.lds_pitch == v.xspan * v.lpr * 16 && m.row_bytes >= need * v.lpr * 16 && m.row_bytes <= m.lds_pitch;
+            if (m.is_store || !(ok1 || okb)) { fail("matvec: vector tile does not hold the steps it is popped for"); return -1; }
             v.b = m;
             v.holds_x = true;
             v.xstep = 0;
@@ -755,6 +759,29 @@ struct Tiler {
                 };
                 sweep(k0, nk_full - k0);
                 sweep(0, k0);
+                for (int i = 0; i < n; i++) emit_result(vm, vs[i], 0, 0, y_off + (it * n + i) * R * 4, dy, rows_valid, y_slots);
+            }
+        } else if (count <= 8 && B > 1 && (cfg.issue_flags & 2) && !ktail && nk_full >= 4 && nk_full % 2 == 0 && Kt <= 256 &&
+                   matvec_xspan_ok((uint32_t)B, (uint32_t)R, (uint32_t)Kt / 4) && (uint64_t)B * 2 * Kt * 4 <= (uint64_t)cfg.slot_bytes) {
+            // Several vectors whose tile fills half a slot at most: a vector tile holds the pieces of two steps (B rows of
+            // two pieces side by side, one slot), so a trip of two steps is one vector tile and two matrix tiles per compute
+            // core: a slot less per step in flight and three memory uops instead of four.  On request only (measured on
+            // 32768 x 65536 with eight vectors: 63 % of the HBM peak against 85 % step by step: a trip now takes ten of the
+            // nineteen slots, so the front end never finds room for a whole trip and issues it piece by piece).
+            vcc_xspan = 2;
+            const uint32_t dx2 = desc(1, B, 2 * Kt * 4, 2 * Kt * 4, (uint64_t)K * 4);
+            for (int64_t it = 0; it < count; it++) {
+                vm.push_back(encode(OP_SET, 0, 0, 0, 2, 0, 0, 0, 0, 0, 0));
+                vm.push_back(encode(OP_LOOP, 0, 0, 0, 0, 0, 0, 0, nk_full / 2, 0, 0));
+                for (int i = 0; i < n; i++)
+                    vm.push_back(encode(OP_LOAD, F_SEND | F_DYNAMIC, flow_x(vs[i]), vs[i], 2, 1, B, 0, x_off, dx2, 0));
+                for (int u = 0; u < 2; u++)
+                    for (int i = 0; i < n; i++) {
+                        const int64_t blk = it * n + i;
+                        vm.push_back(encode(OP_LOAD, m_flags, u ? flow_x(vs[i]) : flow_m(vs[i]), vs[i], 2, m_slots, rows_valid, 0,
+                                            m_off + blk * R * ld * 4 + (int64_t)u * Kt * 4, dm, 0));
+                    }
+                vm.push_back(encode(OP_REPEAT, 0, 0, 0, 2, 0, 0, 0, 2 * (int64_t)Kt * 4, 0, 0));
                 for (int i = 0; i < n; i++) emit_result(vm, vs[i], 0, 0, y_off + (it * n + i) * R * 4, dy, rows_valid, y_slots);
             }
         } else if (count <= 8) {
@@ -1553,7 +1580,7 @@ int resolve_config(vdc_config &c, int cu_count, size_t lds_limit) {
         c.sched_force_parts < 0 || (c.sched_force_parts > 16 && (c.sched_force_parts < 101 || c.sched_force_parts > 116))) return VDC_EINVAL;
     if (c.sched_threshold_pct == 0) c.sched_threshold_pct = kSchedThresholdPct;
     if (c.sched_min_gain_pct == 0) c.sched_min_gain_pct = kSchedMinGainPct;
-    if (c.issue_batch < 0 || c.issue_batch > 8 || (c.issue_flags & ~1)) return VDC_EINVAL;
+    if (c.issue_batch < 0 || c.issue_batch > 8 || (c.issue_flags & ~3)) return VDC_EINVAL;
     if (c.issue_batch == 0) c.issue_batch = 8;
     if (c.n_cores == 0) c.n_cores = cu_count;
     if (c.vcc_per_core == 0) c.vcc_per_core = 2;

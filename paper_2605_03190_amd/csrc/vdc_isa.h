@@ -114,9 +114,14 @@ inline Word encode(uint32_t opcode, uint32_t flags, uint32_t vflow, uint32_t vcc
 }
 
 // MATVEC imm: B [7:0], R [23:8] (box rows of a matrix tile), lpr [39:24] (16-byte chunks per tile row), xspan [46:40]:
-// 0 or 1 = a vector tile per step; n >= 2 (B = 1 only, n <= kMaxXspan) = one vector tile of n rows serves n consecutive
+// 0 or 1 = a vector tile per step; n >= 2 (n <= kMaxXspan; B = 1, or matvec_xspan_ok) = one vector tile of n rows serves n consecutive
 // steps, row j step j: it is popped before the first matrix tile of those steps and handed back after the last.
 constexpr uint32_t kMaxXspan = 8;
+// With several vectors (the tile then holds B rows of n pieces side by side) the compute uop has the form for B = 8 and
+// tiles of 512 or 1024 chunks whose rows lie inside one wave.
+VDC_HD bool matvec_xspan_ok(uint32_t B, uint32_t R, uint32_t lpr) {
+    return B == 1u || (B == 8u && lpr <= 64u && (R * lpr == 512u || R * lpr == 1024u));
+}
 inline int64_t matvec_imm(uint32_t B, uint32_t R, uint32_t lpr, uint32_t xspan = 0) {
     return (int64_t)B | ((int64_t)R << 8) | ((int64_t)lpr << 24) | ((int64_t)xspan << 40);
 }

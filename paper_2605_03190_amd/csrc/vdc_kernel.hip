@@ -57,6 +57,8 @@ static __device__ __forceinline__ unsigned long long prof_now() {
 constexpr int kUQ = 8;         // records per unit queue (CFU -> LDU/STU)
 constexpr int kBatch = 4;      // memory uops the front end dispatches at once (a batch is published in one piece: more is later)
 constexpr int kBatchOnes = 8;  // ... when every uop of the batch takes one slot: the lanes then allocate side by side
+constexpr int kBatchWide = 6;  // ... when the batch is the whole body of a loop that is replayed (a trip of two steps: a vector
+                               // tile and two matrix tiles per compute core)
 constexpr int kM2C = 32;       // m2c ring entries per VCC (>= slots, so a delivery never finds it full)
 constexpr int kC2M = 64;       // c2m ring entries per VCC
 constexpr int kMbox = 32;      // produced regions waiting for their STORE, per VCC
@@ -761,6 +763,62 @@ DEV uint32_t cfu_alloc4(uint32_t occ32, uint32_t nsp32, uint32_t lim, uint32_t &
     return got;
 }
 
+// The same in-order first fit for a batch of up to six uops (the body of a replayed loop): slot counts and first slots
+// of the fifth and sixth uop stand in the low bytes of a second word.
+DEV uint32_t cfu_alloc6(uint32_t occ32, uint32_t nsp_lo, uint32_t nsp_hi, uint32_t lim, uint32_t &pack_lo_out, uint32_t &pack_hi_out,
+                        uint32_t &bits_out) {
+    static_assert(kBatchWide <= 6 && kMaxSlots <= 32, "six steps, two words of packed slot counts and positions");
+    uint32_t got, alloc, pack, packh, ok, ns, f, g, h, pos, pb, b, v;
+#define VDC_ALLOC_STEP(I, BYTE, BFE, NSP, PACK)                                                                  \
+    "s_bfe_u32 %[ns], %[" NSP "], " BFE "\n\t"  /* slots of uop I */                                              \
+    "s_not_b32 %[f], %[occ]\n\t"                                                                                 \
+    "s_lshr_b32 %[g], %[f], 1\n\t"                                                                               \
+    "s_and_b32 %[g], %[g], %[f]\n\t"            /* starts of runs of two free slots */                           \
+    "s_lshr_b32 %[h], %[f], 2\n\t"                                                                               \
+    "s_and_b32 %[h], %[h], %[g]\n\t"            /* of three */                                                   \
+    "s_cmp_eq_u32 %[ns], 2\n\t"                                                                                  \
+    "s_cselect_b32 %[f], %[g], %[f]\n\t"                                                                         \
+    "s_cmp_eq_u32 %[ns], 3\n\t"                                                                                  \
+    "s_cselect_b32 %[f], %[h], %[f]\n\t"                                                                         \
+    "s_cmp_eq_u32 %[ns], 0\n\t"                                                                                  \
+    "s_cselect_b32 %[f], 1, %[f]\n\t"           /* nothing to allocate: position 0, no bits */                   \
+    "s_ff1_i32_b32 %[pos], %[f]\n\t"                                                                             \
+    "s_lshl_b32 %[pb], %[pos], " #BYTE " * 8\n\t"                                                                \
+    "s_bfm_b32 %[b], %[ns], %[pos]\n\t"                                                                          \
+    "s_cmp_lg_u32 %[f], 0\n\t"                                                                                   \
+    "s_cselect_b32 %[v], %[ok], 0\n\t"          /* fits, and every uop before it did */                          \
+    "s_cmp_gt_u32 %[lim], " #I "\n\t"                                                                            \
+    "s_cselect_b32 %[ok], %[v], 0\n\t"          /* and it is one of those to try */                              \
+    "s_cmp_lg_u32 %[ok], 0\n\t"                                                                                  \
+    "s_cselect_b32 %[b], %[b], 0\n\t"                                                                            \
+    "s_cselect_b32 %[pb], %[pb], 0\n\t"                                                                          \
+    "s_or_b32 %[occ], %[occ], %[b]\n\t"                                                                          \
+    "s_or_b32 %[alloc], %[alloc], %[b]\n\t"                                                                      \
+    "s_or_b32 %[" PACK "], %[" PACK "], %[pb]\n\t"                                                               \
+    "s_add_u32 %[got], %[got], %[ok]\n\t"
+    asm volatile(
+        "s_mov_b32 %[got], 0\n\t"
+        "s_mov_b32 %[alloc], 0\n\t"
+        "s_mov_b32 %[pack], 0\n\t"
+        "s_mov_b32 %[packh], 0\n\t"
+        "s_mov_b32 %[ok], 1\n\t"
+        VDC_ALLOC_STEP(0, 0, "0x20000", "nsp", "pack")
+        VDC_ALLOC_STEP(1, 1, "0x20008", "nsp", "pack")
+        VDC_ALLOC_STEP(2, 2, "0x20010", "nsp", "pack")
+        VDC_ALLOC_STEP(3, 3, "0x20018", "nsp", "pack")
+        VDC_ALLOC_STEP(4, 0, "0x20000", "nsph", "packh")
+        VDC_ALLOC_STEP(5, 1, "0x20008", "nsph", "packh")
+        : [got] "=&s"(got), [alloc] "=&s"(alloc), [pack] "=&s"(pack), [packh] "=&s"(packh), [ok] "=&s"(ok), [occ] "+s"(occ32), [ns] "=&s"(ns),
+          [f] "=&s"(f), [g] "=&s"(g), [h] "=&s"(h), [pos] "=&s"(pos), [pb] "=&s"(pb), [b] "=&s"(b), [v] "=&s"(v)
+        : [nsp] "s"(nsp_lo), [nsph] "s"(nsp_hi), [lim] "s"(lim)
+        : "scc");
+#undef VDC_ALLOC_STEP
+    pack_lo_out = pack;
+    pack_hi_out = packh;
+    bits_out = alloc;
+    return got;
+}
+
 // Publish n uops of the batch that starts at window lane k: mark the slots, hand the empty region of a STORE that
 // sends to its compute core, write the unit records and then the new ring tails (one piece: a unit sees all or
 // nothing), advance the front end's counters.  pos_pack: byte j = first slot of the j-th uop.
@@ -1071,7 +1129,7 @@ DEV void cfu_main(Ctx &c) {
                     const uint32_t n0 = k - sl;
                     const uint64_t body0 = (1ull << n0) - 1ull;
                     replay = n0 >= 1u && n0 <= p->issue_batch && p->no_replay == 0u && (~(d.mem >> sl) & body0) == 0ull &&
-                             (n0 <= (uint32_t)kBatch || (n0 <= (uint32_t)kBatchOnes && (~(d.ones >> sl) & body0) == 0ull));
+                             (n0 <= (uint32_t)kBatchWide || (n0 <= (uint32_t)kBatchOnes && (~(d.ones >> sl) & body0) == 0ull));
                 }
             }
             s.pc = back ? top_start : s.pc + 1u;
@@ -1094,7 +1152,9 @@ DEV void cfu_main(Ctx &c) {
                 const uint64_t nsp_r = (uint64_t)rf_get(d.nsp_lo, sl) | ((uint64_t)rf_get(d.nsp_hi, sl) << 32);
                 const uint32_t nsp32 = (uint32_t)nsp_r & (n0 >= 4u ? 0xFFFFFFFFu : ((1u << (8u * n0)) - 1u));
                 const bool ones = n0 >= 2u && (~(d.ones >> sl) & ((1ull << n0) - 1ull)) == 0ull;   // one slot each: the wide allocation
-                const bool fast = (ones || (n0 <= (uint32_t)kBatch && (nsp32 & 0xFCFCFCFCu) == 0u)) && !env.trace;   // regions of at most three slots, no trace
+                const uint32_t nsp_hi32 = n0 > 4u ? (uint32_t)(nsp_r >> 32) & ((1u << (8u * (n0 - 4u))) - 1u) : 0u;   // n0 <= 6 where it is used
+                const bool wide = n0 > (uint32_t)kBatch;     // five or six uops that are not all of one slot: the longer allocation
+                const bool fast = (ones || (n0 <= (uint32_t)kBatchWide && ((nsp32 | nsp_hi32) & 0xFCFCFCFCu) == 0u)) && !env.trace;   // regions of at most three slots, no trace
                 const uint32_t dg_lo = mine ? imm_lo : 0u, dg_hi = mine ? imm_hi : 0u;
                 const uint32_t da_lo = me ? imm_lo : 0u, da_hi = me ? imm_hi : 0u;
                 // what a whole batch publishes is the same on every trip
@@ -1104,15 +1164,16 @@ DEV void cfu_main(Ctx &c) {
                 const uint64_t send0 = (d.t0 | d.t1) & bm0;
                 const uint32_t jsh = ((c.lane - sl) & 7u) * 8u;
                 const uint32_t busy32 = (uint32_t)env.busy_hi;
-                const uint32_t need0 = ones ? n0 : (nsp32 & 0xFFu) + ((nsp32 >> 8) & 0xFFu) + ((nsp32 >> 16) & 0xFFu) + (nsp32 >> 24);
+                const uint32_t need0 = ones ? n0 : (nsp32 & 0xFFu) + ((nsp32 >> 8) & 0xFFu) + ((nsp32 >> 16) & 0xFFu) + (nsp32 >> 24) +
+                                                   (nsp_hi32 & 0xFFu) + ((nsp_hi32 >> 8) & 0xFFu);
                 // lanes whose look at the queues can forbid a whole batch: a unit whose ring has no room for its share, or
                 // the abort word (the lanes from kPollAbort on all read it)
                 const uint32_t room_need = c.lane < env.n_units ? (uint32_t)kUQ - add0 : (c.lane >= kPollAbort ? 0u : 0xFFFFFFFFu);
                 bool done = false;
                 // one trip without a branch but the two that end the loop: look, allocate the whole batch, publish it,
                 // and do what the REPEAT does
-                auto trips = [&](auto ones_tag) __attribute__((always_inline)) {
-                    constexpr bool ONES = decltype(ones_tag)::value;
+                auto trips = [&](auto kind_tag) __attribute__((always_inline)) {
+                    constexpr bool ONES = decltype(kind_tag)::value == 1, WIDE = decltype(kind_tag)::value == 2;
                     for (;;) {
                         SEC_END(c, 3);
                         const uint32_t snap = cfu_poll(c);
@@ -1129,6 +1190,18 @@ DEV void cfu_main(Ctx &c) {
                         uint32_t slot_vec, bits;
                         if (ONES) {
                             slot_vec = cfu_alloc_ones(c, ~occ32, n0, sl, bits);
+                        } else if (WIDE) {
+                            uint32_t pack_lo, pack_hi;
+                            const uint32_t got = cfu_alloc6(occ32, nsp32, nsp_hi32, n0, pack_lo, pack_hi, bits);
+                            const uint64_t pack64 = (uint64_t)pack_lo | ((uint64_t)pack_hi << 32);
+                            if (got != n0) {
+                                if (got != 0u) {
+                                    cfu_publish(c, d, lv, st, env, s.pc, sl, got, pack64, bits);
+                                    s.pc += got;
+                                }
+                                break;
+                            }
+                            slot_vec = (uint32_t)(pack64 >> jsh) & 0xFFu;
                         } else {
                             uint32_t pack32;
                             const uint32_t got = cfu_alloc4(occ32, nsp32, n0, pack32, bits);
@@ -1164,7 +1237,9 @@ DEV void cfu_main(Ctx &c) {
                     }
                 };
                 if (fast) {
-                    if (ones) trips(std::true_type{}); else trips(std::false_type{});
+                    if (ones) trips(std::integral_constant<int, 1>{});
+                    else if (wide) trips(std::integral_constant<int, 2>{});
+                    else trips(std::integral_constant<int, 0>{});
                 }
                 if (done) {
                     s.pc = top_start + n0 + 1u;          // past the REPEAT: the loop is done
@@ -2057,7 +2132,7 @@ DEV float dot4(f32x4 m, f32x4 x, float acc) {
 // out-of-order return as the query tile of attn): half the memory uops per step for the front end.
 template <int B, int NF, int J, bool SPANS = false>
 DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lpr, uint32_t xspan) {
-    static_assert(!SPANS || (B == 1 && J == 0), "a vector tile over several steps: one vector, rows inside a wave");
+    static_assert(!SPANS || J == 0, "a vector tile over several steps: rows inside a wave");
     const KParams *p = c.p;
     const uint32_t v = c.unit;
     const uint32_t slot_shift = __builtin_ctz(p->slot_bytes);
@@ -2071,6 +2146,8 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
     const uint32_t t = vs.t;
     const uint32_t c4 = (J == 0) ? (t & (lpr - 1u)) : t;
     const uint32_t pitch = lpr * 16u;
+    // a vector tile over several steps with several vectors: B rows of xspan pieces side by side
+    const uint32_t xpitch = (SPANS && B > 1) ? xspan * pitch : pitch;
 
     constexpr bool spans = SPANS;
     uint32_t x_pay = 0, x_base = 0, xs = 0;      // the vector tile that is held, and the step inside it
@@ -2097,7 +2174,7 @@ DEV bool matvec_uop(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint32_t lp
 #pragma unroll
         for (int j = 0; j < JJ; j++)
 #pragma unroll
-            for (int b = 0; b < B; b++) xv[j][b] = lds_ld128(b_off + (uint32_t)b * pitch + ((uint32_t)j * 128u + c4) * 16u);
+            for (int b = 0; b < B; b++) xv[j][b] = lds_ld128(b_off + (uint32_t)b * xpitch + ((uint32_t)j * 128u + c4) * 16u);
         f32x4 m[NF];
 #pragma unroll
         for (int i = 0; i < NF; i++) m[i] = lds_ld128(a_off + ((uint32_t)i * 128u + t) * 16u);
@@ -2266,6 +2343,13 @@ DEV bool matvec_dispatch_b(Ctx &c, VccState &vs, uint32_t size, uint32_t R, uint
     if constexpr (B * 4 <= 16) { VDC_MV(4, 4) VDC_MV(8, 4) }
     if constexpr (B * 8 <= 16) { VDC_MV(8, 8) }
 #undef VDC_MV
+    if constexpr (B == 8) {
+        // several vectors and a vector tile over several steps: the tiles of the largest batch (matvec_xspan_ok)
+        if (xspan >= 2u && j == 0u) {
+            if (nf == 4u) return matvec_uop<8, 4, 0, true>(c, vs, size, R, lpr, xspan);
+            if (nf == 8u) return matvec_uop<8, 8, 0, true>(c, vs, size, R, lpr, xspan);
+        }
+    }
     if constexpr (B == 1) {
         // the variant that keeps a vector tile over several steps is a code path of its own: the usual one pays nothing
         if (xspan >= 2u && j == 0u) {
@@ -2285,7 +2369,7 @@ DEV bool matvec_dispatch(Ctx &c, VccState &vs, const Fields &f) {
     const uint32_t nf = (R * lpr) >> 7;
     const uint32_t j = lpr <= 64u ? 0u : lpr >> 7;
     const uint32_t xspan = matvec_xspan(f.imm);
-    if (xspan >= 2u && (B != 1u || j != 0u || xspan > kMaxXspan)) {
+    if (xspan >= 2u && (j != 0u || xspan > kMaxXspan || !matvec_xspan_ok(B, R, lpr))) {
         raise_error(c, -3 /* VDC_EPROGRAM */, 0xC10u);
         return false;
     }

@@ -253,6 +253,54 @@ def test_uop_traces_of_cut_programs_match_the_interpreter(cfg, shape):
     _check(Yo, Yr, Ya, "cut %s %s (interpreter)" % (cfg, shape))
 
 
+@pytest.mark.parametrize("rows,nk,T", [(2048, 64, 16384), (1000, 32, 8192)])
+def test_eight_vectors_with_a_vector_tile_over_two_steps(rows, nk, T):
+    """issue_flags bit 1: eight vectors take vector tiles that hold the pieces of two steps (a loop body of six memory uops
+    on every memory core).  Run once with traces (the front end's general path), every unit's trace bit for bit the
+    interpreter's, and once without (the loop body replayed as one batch of six): both results are the fp64 GEMV, and both
+    have the bits of the step-by-step program's result."""
+    K, B = 128 * nk, 8
+    rng = np.random.default_rng(rows)
+    M = rng.standard_normal((rows, K)).astype(np.float32)
+    X = rng.standard_normal((B, K)).astype(np.float32)
+    dM, dX = _dev(M), _dev(X)
+    res = {}
+    for fl in (2, 0):
+        with vdc.Executor(n_cores=16, issue_flags=fl, sched_force_parts=1) as ex:
+            nc, ns, slot = ex.cfg.n_cores, ex.cfg.n_slots, ex.cfg.slot_bytes
+            words, sb, descs = ex.matvec_program(rows, K, K, B, T)
+            xspans = {(int(x[3]) >> 8) & 0x7F for x in words[(words[:, 0] & 0xFF) == 16]}
+            assert xspans == ({2} if fl == 2 else {0})
+            prog = ex.program_create(words, sb, descs, [M.nbytes, X.nbytes, B * rows * 4])
+            dY = torch.full((B, rows), float("nan"), device="cuda")
+            ex.run(prog, [dM, dX, dY])
+            ex.check()
+            res[fl] = dY.cpu().numpy()
+            if fl == 2:
+                dY2 = torch.full((B, rows), float("nan"), device="cuda")
+                cap = 8192
+                trace, count = ex.run(prog, [dM, dX, dY2], trace_cap=cap)
+                ex.check()
+                trace, count = trace.cpu().numpy().view(np.uint32), count.cpu().numpy()
+                assert np.array_equal(dY2.cpu().numpy(), res[2])
+                Yo = np.full((B, rows), np.nan, np.float32)
+                m = UM.Machine(words, sb, descs, [M, X, Yo], n_cores=nc, slot_bytes=slot, n_slots=ns).run()
+                V = 2
+                for core in range(nc):
+                    st = core * (1 + V)
+                    exp = [(pc, op | (d << 8) | (n << 16), off & 0xFFFFFFFF, off >> 32) for (pc, op, d, off, n) in m.trace_vmc[core]]
+                    assert count[st] == len(exp) <= cap
+                    assert [tuple(int(x) for x in r) for r in trace[st, :len(exp)]] == exp
+                    for v in range(V):
+                        exp = [(pc, op | (n << 16), imm & 0xFFFFFFFF, imm >> 32) for (pc, op, n, imm) in m.trace_vcc[core][v]]
+                        assert count[st + 1 + v] == len(exp)
+                        assert [tuple(int(x) for x in r) for r in trace[st + 1 + v, :len(exp)]] == exp
+    Yr, Ya = gemv_ref.gemv_dense(M, X)
+    _check(res[2], Yr, Ya, "vector tile over two steps")
+    _check(Yo, Yr, Ya, "vector tile over two steps (interpreter)")
+    assert np.array_equal(res[0], res[2])
+
+
 def test_programs_assembled_by_the_oracle_side_run_on_the_gpu():
     """uop graphs that no product code produced (oracle-side assembler), through vdc_program_create / vdc_run."""
     rng = np.random.default_rng(3)

@@ -145,3 +145,33 @@ def test_forced_cuts_with_partial_and_joining_items_on_one_core(ncores, force, r
         assert s == min(force % 100, s_max) and s >= 2 and (tail > 0) == (force > 100)
         signals = _run(ex, rows, 128 * nk, B, tile, ncores, slot, nslots, rows)
         assert signals == (s - 1) * (tail or NB)
+
+
+@pytest.mark.parametrize("rows,nk,tile,ncores", [(200, 8, 16384, 2), (100, 6, 8192, 3), (64, 4, 16384, 1)])
+def test_eight_vectors_take_a_vector_tile_over_two_steps_on_request(rows, nk, tile, ncores):
+    """Eight vectors, tiles of 32 (16) rows x 128 columns, few row blocks per compute core, an even number of steps: with
+    issue_flags bit 1 the tiler gives a MATVEC vector tiles that hold the pieces of two steps (8 rows of two pieces, one
+    slot): validated, run under a random schedule, the GEMV; half as many vector loads as matrix loads.  Without the bit it
+    keeps the step-by-step form, with the same bits in the result."""
+    K = 128 * nk
+    out = []
+    for fl in (2, 0):
+        with vdc.Executor(device=-1, n_cores=ncores, slot_bytes=8192, n_slots=19, issue_flags=fl, sched_force_parts=1) as ex:
+            w, sb, d = ex.matvec_program(rows, K, K, 8, tile)
+            rng = np.random.default_rng(rows)
+            M = rng.standard_normal((rows, K)).astype(np.float32)
+            X = rng.standard_normal((8, K)).astype(np.float32)
+            rc, msg = ex.program_validate(w, sb, d, [M.nbytes, X.nbytes, 8 * rows * 4])
+            assert rc == vdc.VDC_OK, msg
+        Y = np.full((8, rows), np.nan, np.float32)
+        m = UM.Machine(w, sb, d, [M, X, Y], n_cores=ncores, slot_bytes=8192, n_slots=19)
+        m.run("random", 5)
+        m.check_final()
+        Yr, Ya = gemv_ref.gemv_dense(M, X)
+        assert np.all(np.abs(Y - Yr) <= 1e-6 * Ya + 1e-30)
+        loads_x = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 1)
+        loads_m = sum(1 for t in m.trace_vmc for r in t if r[1] == UM.LOAD and m.descs[r[2]].tensor == 0)
+        xspans = {(int(x[3]) >> 8) & 0x7F for x in w[(w[:, 0] & 0xFF) == 16]}
+        assert (xspans == {2} and 2 * loads_x == loads_m) if fl == 2 else (xspans == {0} and loads_x == loads_m)
+        out.append(Y)
+    assert np.array_equal(out[0], out[1])
