@@ -969,7 +969,9 @@ struct Tiler {
                 if (nb >= 2) vm.push_back(encode(OP_LOAD, F_SEND, flow_x(v), v, 0, x_slots, B, 0, r.x_off, dx, 0));
                 for (int64_t j = 0; j < nb; j++) {
                     const uint32_t rv = (uint32_t)std::min<int64_t>(R, rows_valid - j * R);
-                    vm.push_back(encode(OP_LOAD, m_flags, flow_m(v), v, 0, m_slots, rv, 0, r.m_off + (done + j) * R * ld * 4, dm, 0));
+                    // the matrix tiles of a compute core take turns on its two flows: with four load units every unit then
+                    // carries a quarter of them (a load unit's cost is per uop: two units alone set the pace on 8 KB tiles)
+                    vm.push_back(encode(OP_LOAD, m_flags, (j & 1) ? flow_x(v) : flow_m(v), v, 0, m_slots, rv, 0, r.m_off + (done + j) * R * ld * 4, dm, 0));
                 }
                 if (nb < 2) {      // a single block: the uop of the listing (matrix tile, vector tile, then the output region)
                     vm.push_back(encode(OP_LOAD, F_SEND, flow_x(v), v, 0, x_slots, B, 0, r.x_off, dx, 0));
