@@ -587,11 +587,19 @@ DEV DescRegs desc_regs_load(Ctx &c) {
     return r;
 }
 
-DEV bool cfu_refill(Ctx &c, DecWin &d, CfuLive &lv, CfuState &st, const DescRegs &dr, uint32_t acc_rf_lo, uint32_t acc_rf_hi, uint32_t pc, uint32_t end) {
-    const KParams *p = c.p;
-    uint32_t idx = pc + c.lane;
+// The words of the window that starts at pc: lane l = word pc + l, the stream's HALT beyond its end.
+DEV u32x4 cfu_window_words(const KParams *p, uint32_t lane, uint32_t pc, uint32_t end) {
+    uint32_t idx = pc + lane;
     if (idx >= end) idx = end - 1u;             // the stream's HALT
-    const u32x4 raw = ((const u32x4 *)p->words)[idx];
+    return ((const u32x4 *)p->words)[idx];
+}
+
+// `fetched`: the window's words if the caller has asked for them already (cfu_window_words), else null.
+DEV bool cfu_refill(Ctx &c, DecWin &d, CfuLive &lv, CfuState &st, const DescRegs &dr, uint32_t acc_rf_lo, uint32_t acc_rf_hi, uint32_t pc, uint32_t end,
+                    const u32x4 *fetched = nullptr) {
+    const KParams *p = c.p;
+    const u32x4 raw = fetched ? *fetched : cfu_window_words(p, c.lane, pc, end);
+    const uint32_t idx = pc + c.lane < end ? pc + c.lane : end - 1u;    // the word this lane holds
     Word w = {raw.x, raw.y, raw.z, raw.w};
     const Fields f = decode(w);
     const bool is_mem = f.opcode == OP_LOAD || f.opcode == OP_STORE;
@@ -1014,11 +1022,30 @@ DEV uint32_t cfu_dispatch(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState &
     return n;
 }
 
-DEV void cfu_main(Ctx &c) {
+// What the front end needs from memory before it can decode anything: the bounds of its stream, the first window's words
+// (a second, dependent trip) and the descriptors.
+struct CfuStart {
+    uint32_t pc, end;
+    u32x4 words;
+    DescRegs dr;
+};
+
+DEV CfuStart cfu_start_fetch(Ctx &c) {
+    const KParams *p = c.p;
+    CfuStart f;
+    f.dr = desc_regs_load(c);                     // in flight together with the stream's bounds
+    const uint32_t stream = c.core * (1u + p->V);
+    f.pc = cload(p->stream_begin, stream);
+    f.end = cload(p->stream_begin, stream + 1u);
+    f.words = cfu_window_words(p, c.lane, f.pc, f.end);
+    return f;
+}
+
+DEV void cfu_main(Ctx &c, const CfuStart &start) {
     const KParams *p = c.p;
     const uint32_t n_slots = p->n_slots, n_ldu = p->n_ldu, n_units = p->n_ldu + p->n_stu;
     Seq s;
-    const DescRegs dr = desc_regs_load(c);        // in flight together with the stream's bounds
+    const DescRegs dr = start.dr;
     CfuEnv env;
     env.n_units = n_units;
     env.stream = c.core * (1u + p->V);
@@ -1026,14 +1053,14 @@ DEV void cfu_main(Ctx &c) {
     env.busy_hi = slots_beyond(n_slots);
     env.trace = p->trace != nullptr;
     env.trace_n = 0;
-    s.pc = cload(p->stream_begin, env.stream);
-    s.end = cload(p->stream_begin, env.stream + 1u);
+    s.pc = start.pc;
+    s.end = start.end;
     s.depth = 0; s.rf_lo = 0; s.rf_hi = 0; s.win_base = 0; s.win = u32x4{0u, 0u, 0u, 0u};
     c.stream_pc0 = s.pc;
     CfuState st = {0, 0, 0, 0, 0, 0};
     DecWin d;
     CfuLive lv;
-    bool ok = cfu_refill(c, d, lv, st, dr, s.rf_lo, s.rf_hi, s.pc, s.end);
+    bool ok = cfu_refill(c, d, lv, st, dr, s.rf_lo, s.rf_hi, s.pc, s.end, &start.words);
 
     // The innermost loop frame is kept in scalars (top_start, top_left); outer frames wait in lanes 8.. of the
     // register file.  Accumulators are updated by a masked vector add, so that a control uop never moves a value
@@ -2823,12 +2850,18 @@ DEV void run_core(const KParams &p) {
     c.spins_limit = p.watchdog;
     c.stream_pc0 = 0;
     c.pc = 0;
+    // the front end's two trips to memory for its first window start here, so that they overlap the clearing of the
+    // control block and the barrier (the wave clears its share once the stream's bounds are there; the words follow)
+    CfuStart start = {};
+    if (wave == 0u) start = cfu_start_fetch(c);
     // the control block starts at zero (slots need no initialisation)
     {
         const uint32_t words = (uint32_t)(sizeof(Ctl) / 4);
         for (uint32_t i = threadIdx.x; i < words; i += blockDim.x) lds_vst32(c.ctl + i * 4u, 0u);
     }
-    __syncthreads();   // the only workgroup barrier: before the roles diverge
+    // the only workgroup barrier: before the roles diverge.  It orders the clearing stores to local memory alone; the front
+    // end's loads from memory stay in flight across it
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (wave == 15u) return;   // a wave that is there only to shift the others to another SIMD
 #ifdef VDC_PROFILE_WAITS
     c.w_t0 = prof_now();
@@ -2839,7 +2872,7 @@ DEV void run_core(const KParams &p) {
         // the front end is a long dependent chain of cheap instructions: let it win the issue arbitration against the
         // compute wave that shares its SIMD
         __builtin_amdgcn_s_setprio(kCfuPrio);
-        cfu_main(c);
+        cfu_main(c, start);
     } else if (wave <= p.n_ldu) {
         c.role = ROLE_LDU; c.unit = wave - 1u;
         c.stream_pc0 = cload(p.stream_begin, c.core * (1u + p.V));
