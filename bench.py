@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published peak HBM3E bandwidth
 # reported only for the exact configuration it was measured on (no --tile-bytes / --slot-bytes / --n-stu / --tile-rows
 # override); every other run prints null.
 MEASURED_TRAFFIC = {
-    "cfg5": (8650656865, "profiles/vdc_executor_kernel_cfg5_hbm_traffic.txt"),
+    "cfg5": (8650709316, "profiles/vdc_executor_kernel_cfg5_hbm_traffic.txt"),
 }
 
 

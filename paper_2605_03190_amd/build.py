@@ -15,7 +15,8 @@ SO = os.path.join(HERE, "libvdcores.so")
 KERNEL = os.path.join(HERE, "csrc", "vdc_kernel.hip")
 HOST = [os.path.join(HERE, "csrc", f) for f in ("vdc_host.cpp", "vdc_lower.cpp", "vdc_sched.cpp")]
 SOURCES = [KERNEL] + HOST
-N_VARIANTS = 6      # kVariants in csrc/vdc_kernel.hip
+N_VARIANTS = 8      # kVariants in csrc/vdc_kernel.hip
+WAVE_MASK_VARIANTS = (6, 7)     # ... of which these are built with -DVDC_WAVE_MASKS (see Ctl::mask there)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          # packed fp32 arithmetic is kept out of the device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -45,7 +46,8 @@ def build(verbose=False, observer=False):
         return SO_OBSERVER
     tmp = tempfile.mkdtemp(prefix="vdc_build_")
     try:
-        jobs = [(["-DVDC_PART=%d" % i, KERNEL], os.path.join(tmp, "part%d.o" % i)) for i in range(N_VARIANTS)]
+        jobs = [(["-DVDC_PART=%d" % i] + (["-DVDC_WAVE_MASKS"] if i in WAVE_MASK_VARIANTS else []) + [KERNEL], os.path.join(tmp, "part%d.o" % i))
+                for i in range(N_VARIANTS)]
         jobs.append((["-DVDC_SPLIT", KERNEL], os.path.join(tmp, "kernel.o")))
         jobs += [([src], os.path.join(tmp, os.path.basename(src) + ".o")) for src in HOST]
         workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", "0")) or os.cpu_count() or 1))

@@ -217,6 +217,7 @@ struct Validator {
     uint32_t max_dep = 0;
     uint32_t loaded_tensors = 0;
     uint32_t ops = 0;              // OPS_* families of the compute uops met
+    bool big_regions = false;      // some memory uop's region takes more than one slot
     std::vector<uint32_t> dep;
     int64_t steps = 0;
 
@@ -302,6 +303,7 @@ struct Validator {
         const Desc &d = descs[f.desc];
         const bool is_load = f.opcode == OP_LOAD;
         const bool local = (f.flags & F_LOCAL) != 0;
+        if (f.nslots > 1) big_regions = true;
         if (local) {
             // store.local / load.local: no memory access.  The load names no region of its own: it hands on the oldest
             // region a store.local of this core has taken back.
@@ -1819,7 +1821,7 @@ int vdc_program_create(vdc_executor *ex, const void *uops, int64_t n_uops, const
     p->uses_dep = val.uses_dep;
     p->max_dep_id = val.max_dep;
     p->loaded_tensors = val.loaded_tensors;
-    p->ops = val.ops;
+    p->ops = val.ops | (val.big_regions ? 0u : OPS_ONE_SLOT);
     HIP_TRY(hipSetDevice(ex->cfg.device));
     const size_t wb = (size_t)n_uops * sizeof(Word), sbb = (size_t)(n_streams + 1) * 4, db = (size_t)std::max(n_descs, 1) * sizeof(Desc);   // never an empty table: the front end reads entry 0 for uops without one
     if (hipMalloc(&p->d_words, wb) != hipSuccess) return VDC_ENOMEM;
@@ -2114,7 +2116,7 @@ int vdc_matvec_noalloc(vdc_executor *ex, const float *M, int64_t rows, int64_t K
         n.uses_dep = val.uses_dep;
         n.max_dep_id = val.max_dep;
         n.loaded_tensors = val.loaded_tensors;
-        n.ops = val.ops;
+        n.ops = val.ops | (val.big_regions ? 0u : OPS_ONE_SLOT);
         if (n.uses_dep && ((size_t)n.max_dep_id + 2) * 4 > kScratchDepBytes) return VDC_ETOOBIG;
         n.placement = matvec_placement(c, rows, K, B, tile_bytes, false);   // the same choice of role placement as vdc_matvec makes
         // the staging buffer may still be the source of the copy of an earlier call

@@ -76,6 +76,9 @@ size_t lds_control_bytes();
 // The families of compute uops a program uses: the kernel is built in several variants, each with the handlers of some
 // families only, and a program is launched on the smallest variant that has all of its own.
 enum : uint32_t { OPS_MATVEC = 1, OPS_ROWS = 2, OPS_ROPE = 4, OPS_STREAM = 8, OPS_ATTN = 16, OPS_ALL = 31 };
+// beside the families, in a program's `ops`: every region of the program takes one slot (tiles of a slot at most: the
+// compute waves' fixed work per tile sets the pace there, and the variants of the kernel built for it pay)
+constexpr uint32_t OPS_ONE_SLOT = 0x80000000u;
 hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves, uint32_t ops, hipStream_t stream);
 // Raise the kernel's dynamic LDS limit; call once per device before the first launch.
 hipError_t prepare_executor_kernels(size_t lds_bytes);

@@ -111,7 +111,11 @@ struct StatRec {  // the static part, written for all 64 uops of a window at onc
 struct Ctl {
     // --- polled together by the CFU with one gathered LDS read: keep these ten words contiguous ---
     uint32_t uq_head[kMaxUnits];   // records picked up by each unit
-    uint32_t mask;                 // slot availability: bit set = in use (Section 4.3: 32-bit mask in shared memory)
+    uint32_t mask;                 // slot availability: bit set = in use (Section 4.3: 32-bit mask in shared memory).  In the
+                                   // variants built with VDC_WAVE_MASKS a slot is in use while its bit stands in this
+                                   // word or in mask1: the two waves of a compute core each clear one of them when they
+                                   // are done with a region (no count of the waves, no answer to wait for), whoever
+                                   // else frees clears both, the front end sets both
     uint32_t abort;                // set when any unit of this core gives up
     // ---
     uint32_t cfu_halted;
@@ -123,7 +127,7 @@ struct Ctl {
     uint32_t red_flag[kMaxV];      // cross-wave reduction hand-shake of a VCC
     uint32_t red_ack[kMaxV];
     uint32_t win_gen;              // number of windows the front end has decoded so far
-    uint32_t pad0[1];
+    uint32_t mask1;                // see mask
     M2cEnt m2c[kMaxV][kM2C];       // see M2cEnt
     uint64_t c2m[kMaxV][kC2M];     // low: kind | slot << 1 | nslots << 7; high: position + 1
     UnitRec uq[kMaxUnits][kUQ];
@@ -497,7 +501,20 @@ DEV void m2c_deliver(Ctx &c, uint32_t v, uint32_t ticket, uint32_t slot, uint32_
     lds_st128_lanes(1ull, c.ctl + CTL_OFF(m2c) + (v * kM2C + (ticket & (kM2C - 1))) * (uint32_t)sizeof(M2cEnt), e);
 }
 
+#ifdef VDC_WAVE_MASKS
+// lanes 0 and 1: the two words of the slot mask
+DEV uint32_t mask_words(Ctx &c) { return c.ctl + (c.lane == 1u ? CTL_OFF(mask1) : CTL_OFF(mask)); }
+#endif
+
 DEV void slots_free(Ctx &c, uint32_t slot, uint32_t nslots) {
+#ifdef VDC_WAVE_MASKS
+    if (c.lane < 2u) {
+        __hip_atomic_fetch_and((__attribute__((address_space(3))) uint32_t *)(lds0() + mask_words(c)),
+                               ~slot_bits(slot, nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    reconverge();
+    return;
+#endif
     if (c.lane == 0) {
         __hip_atomic_fetch_and((__attribute__((address_space(3))) uint32_t *)(lds0() + c.ctl + CTL_OFF(mask)),
                                ~slot_bits(slot, nslots), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -518,10 +535,20 @@ struct CfuState {
 
 // One gathered read of what the front end looks at: lanes 0..7 = uq_head[0..7], lane 8 = slot mask, lane 9 = abort.
 constexpr uint32_t kPollMask = kMaxUnits, kPollAbort = kMaxUnits + 1;
+#ifdef VDC_WAVE_MASKS
+// ... and lane 63 = the slot mask's second word, which lane 8 takes in: a slot is in use while either word says so
+constexpr uint32_t kPollMask1 = 63;
+DEV uint32_t cfu_poll(Ctx &c) {
+    const uint32_t l = c.lane < kPollAbort ? c.lane : kPollAbort;
+    const uint32_t v = lds_vld32(c.lane == kPollMask1 ? c.ctl + CTL_OFF(mask1) : c.ctl + CTL_OFF(uq_head) + l * 4u);
+    return c.lane == kPollMask ? v | rf_get(v, kPollMask1) : v;
+}
+#else
 DEV uint32_t cfu_poll(Ctx &c) {
     const uint32_t l = c.lane < kPollAbort ? c.lane : kPollAbort;
     return lds_vld32(c.ctl + CTL_OFF(uq_head) + l * 4u);
 }
+#endif
 
 // The decoded uop window of the front end: lane l describes word win_base + l.  Decoding (field extraction,
 // descriptor lookup, flow -> unit mapping, tensor base + literal address) is done for 64 uops at once, one per
@@ -857,7 +884,11 @@ DEV void cfu_publish_lanes(Ctx &c, const DecWin &d, const CfuLive &lv, CfuState 
     }
     // the slots are marked taken before anything that names them is published: whoever frees them later (an atomic
     // and on the same word) then always finds the bits set
+#ifdef VDC_WAVE_MASKS
+    lds_or32_lanes(3ull, mask_words(c), alloc_bits);
+#else
     lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), alloc_bits);
+#endif
     // every uop that sends: the payload of its m2c entry.  A STORE that sends: the empty output region goes to the compute
     // core at once (the entry is ready), the store unit only waits for it to return; for a LOAD the entry becomes ready
     // when the tile has landed
@@ -1195,7 +1226,11 @@ DEV void cfu_main(Ctx &c, const CfuStart &start) {
                                                    (nsp_hi32 & 0xFFu) + ((nsp_hi32 >> 8) & 0xFFu);
                 // lanes whose look at the queues can forbid a whole batch: a unit whose ring has no room for its share, or
                 // the abort word (the lanes from kPollAbort on all read it)
+#ifdef VDC_WAVE_MASKS
+                const uint32_t room_need = c.lane < env.n_units ? (uint32_t)kUQ - add0 : (c.lane >= kPollAbort && c.lane != kPollMask1 ? 0u : 0xFFFFFFFFu);
+#else
                 const uint32_t room_need = c.lane < env.n_units ? (uint32_t)kUQ - add0 : (c.lane >= kPollAbort ? 0u : 0xFFFFFFFFu);
+#endif
                 bool done = false;
                 // one trip without a branch but the two that end the loop: look, allocate the whole batch, publish it,
                 // and do what the REPEAT does
@@ -1243,7 +1278,11 @@ DEV void cfu_main(Ctx &c, const CfuStart &start) {
                             slot_vec = (pack32 >> jsh) & 0xFFu;
                         }
                         SEC_END(c, 2);
+#ifdef VDC_WAVE_MASKS
+                        lds_or32_lanes(3ull, mask_words(c), bits);
+#else
                         lds_or32_lanes(1ull, c.ctl + CTL_OFF(mask), bits);
+#endif
                         const u32x4 e = {slot_vec | d.e_lo, ((lv.tick + 1u) & 0xFFFFu) | d.e_hi, m2c_seq(lv.tick) & d.e_sel, 0u};
                         lds_st128_lanes(send0, d.m2c_off + (lv.tick & (kM2C - 1)) * (uint32_t)sizeof(M2cEnt), e);
                         u32x4 rec = {lv.g_lo, lv.g_hi, slot_vec | d.info, lv.tick};
@@ -1736,7 +1775,11 @@ DEV void stu_main(Ctx &c) {
             } while (i0 < total);
             // the data is in registers on its way out: the region is free as soon as the reads have returned
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#ifdef VDC_WAVE_MASKS
+            lds_and32_lanes(3ull, mask_words(c), ~slot_bits(slot, nslots));
+#else
             lds_and32_lanes(1ull, c.ctl + CTL_OFF(mask), ~slot_bits(slot, nslots));
+#endif
             lds_st32_lanes(3ull, pub_off, c.lane == 0u ? head : done);         // the record's place in the ring is free, the STORE is done
             sp.n = 0;
         }
@@ -1958,7 +2001,11 @@ DEV void stu_main(Ctx &c) {
     if (lds_add_rtn_lane0(c.ctl + CTL_OFF(stu_left), 1u) + 1u != c.p->n_stu) return;
     // After a run that came to its end every slot must be free again.
     if (ok) {
+#ifdef VDC_WAVE_MASKS
+        const uint32_t mask = uni(lds_vld32(c.ctl + CTL_OFF(mask))) | uni(lds_vld32(c.ctl + CTL_OFF(mask1)));
+#else
         const uint32_t mask = uni(lds_vld32(c.ctl + CTL_OFF(mask)));
+#endif
         if (mask != 0u) raise_error(c, -6 /* VDC_ELEAK */, mask);
     }
     // The core that leaves last, of all cores, puts the counters the program used back to zero for the next run: no
@@ -2049,6 +2096,17 @@ DEV bool vcc_pop_wait(Ctx &c, VccState &vs, uint32_t n, uint32_t kind, Msg &m0, 
 DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n, uint32_t kind) {
     compiler_barrier();
     const uint32_t v = c.unit;
+#ifdef VDC_WAVE_MASKS
+    if (kind == 0u) {
+        // each wave clears its own word of the mask: nothing to wait for, and no count of the waves
+        const uint32_t payload = c.lane == 0u ? vs.pay0 : vs.pay1;     // lane j < n: ticket head + j
+        lds_and32_lanes((1ull << n) - 1ull, c.ctl + (vs.wv == 1u ? CTL_OFF(mask1) : CTL_OFF(mask)), ~slot_bits((payload >> 1) & 63u, (payload >> 7) & 63u));
+        vs.head += n;
+        vs.group++;
+        compiler_barrier();
+        return;
+    }
+#endif
     const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
     if (before & 1u) {
         OBS(c, 10u + v, vs.head + n);
@@ -2072,6 +2130,13 @@ DEV void vcc_done_with(Ctx &c, VccState &vs, uint32_t n, uint32_t kind) {
 DEV void vcc_return_kept(Ctx &c, VccState &vs, uint32_t payload) {
     compiler_barrier();
     const uint32_t v = c.unit;
+#ifdef VDC_WAVE_MASKS
+    (void)v;
+    lds_and32_lanes(1ull, c.ctl + (vs.wv == 1u ? CTL_OFF(mask1) : CTL_OFF(mask)), ~slot_bits((payload >> 1) & 63u, (payload >> 7) & 63u));
+    vs.group++;
+    compiler_barrier();
+    return;
+#endif
     const uint32_t before = lds_add_rtn_lane0(c.ctl + CTL_OFF(arrive) + (v * 32u + (vs.group & 31u)) * 4u, 1u);
     if (before & 1u) lds_and32_lanes(1ull, c.ctl + CTL_OFF(mask), ~slot_bits((payload >> 1) & 63u, (payload >> 7) & 63u));
     vs.group++;
@@ -2907,6 +2972,10 @@ __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KPa
 // The variants of the kernel, from few handlers to all; a program runs on the first that has every handler it needs.
 #ifdef VDC_PROFILE
 constexpr uint32_t kVariants[] = {OPS_ALL};
+#elif defined(VDC_SPLIT) || defined(VDC_PART)
+// the last two: matvec programs whose regions all take one slot, built with VDC_WAVE_MASKS (see Ctl::mask)
+constexpr uint32_t kVariants[] = {OPS_MATVEC, OPS_MATVEC | OPS_ROWS, OPS_MATVEC | OPS_ROPE, OPS_STREAM, OPS_ATTN, OPS_ALL,
+                                  OPS_ONE_SLOT | OPS_MATVEC, OPS_ONE_SLOT | OPS_MATVEC | OPS_ROWS};
 #else
 constexpr uint32_t kVariants[] = {OPS_MATVEC, OPS_MATVEC | OPS_ROWS, OPS_MATVEC | OPS_ROPE, OPS_STREAM, OPS_ATTN, OPS_ALL};
 #endif
@@ -3039,8 +3108,9 @@ hipError_t launch_resident(const ResidentParams &, uint32_t, uint32_t, size_t, h
 // the variants are compiled in units of their own (see the end of the file): each exports the address of its kernel
 #define VDC_DECLARE_PART(I) extern "C" const void *vdc_variant_entry_##I();
 VDC_DECLARE_PART(0) VDC_DECLARE_PART(1) VDC_DECLARE_PART(2) VDC_DECLARE_PART(3) VDC_DECLARE_PART(4) VDC_DECLARE_PART(5)
+VDC_DECLARE_PART(6) VDC_DECLARE_PART(7)
 #undef VDC_DECLARE_PART
-static_assert(kNumVariants == 6, "one unit per variant");
+static_assert(kNumVariants == 8, "one unit per variant");
 static const void *variant_entry(int i) {
     switch (i) {
         case 0: return vdc_variant_entry_0();
@@ -3048,6 +3118,8 @@ static const void *variant_entry(int i) {
         case 2: return vdc_variant_entry_2();
         case 3: return vdc_variant_entry_3();
         case 4: return vdc_variant_entry_4();
+        case 6: return vdc_variant_entry_6();
+        case 7: return vdc_variant_entry_7();
         default: return vdc_variant_entry_5();
     }
 }
@@ -3079,9 +3151,17 @@ hipError_t launch_executor(const KParams &p, uint32_t n_cores, uint32_t n_waves,
     const uint32_t waves = n_waves;
 #endif
     const size_t lds = lds_bytes_needed(p.n_slots, p.slot_bytes);
-    int pick = kNumVariants - 1;
-    for (int i = kNumVariants - 1; i >= 0; i--)
-        if ((ops & ~kVariants[i]) == 0u) pick = i;
+    // the first variant that has every handler the program needs; for a program whose regions all take one slot, the first
+    // of the variants built for those, if one of them has
+    const uint32_t fam = ops & ~OPS_ONE_SLOT;
+    int pick = -1;
+    if (ops & OPS_ONE_SLOT)
+        for (int i = kNumVariants - 1; i >= 0; i--)
+            if ((kVariants[i] & OPS_ONE_SLOT) && (fam & ~kVariants[i]) == 0u) pick = i;
+    if (pick < 0)
+        for (int i = kNumVariants - 1; i >= 0; i--)
+            if (!(kVariants[i] & OPS_ONE_SLOT) && (fam & ~kVariants[i]) == 0u) pick = i;
+    if (pick < 0) return hipErrorInvalidValue;
     KParams args = p;
     void *kargs[] = {&args};
     return hipLaunchKernel(variant_entry(pick), dim3(n_cores), dim3(waves * 64u), kargs, lds, stream);
