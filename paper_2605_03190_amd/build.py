@@ -15,8 +15,8 @@ SO = os.path.join(HERE, "libvdcores.so")
 KERNEL = os.path.join(HERE, "csrc", "vdc_kernel.hip")
 HOST = [os.path.join(HERE, "csrc", f) for f in ("vdc_host.cpp", "vdc_lower.cpp", "vdc_sched.cpp")]
 SOURCES = [KERNEL] + HOST
-N_VARIANTS = 8      # kVariants in csrc/vdc_kernel.hip
-WAVE_MASK_VARIANTS = (6, 7)     # ... of which these are built with -DVDC_WAVE_MASKS (see Ctl::mask there)
+N_VARIANTS = 9      # kVariants in csrc/vdc_kernel.hip
+WAVE_MASK_VARIANTS = (6, 7, 8)     # ... of which these are built with -DVDC_WAVE_MASKS (see Ctl::mask there)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          # packed fp32 arithmetic is kept out of the device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -2973,9 +2973,9 @@ __global__ void __launch_bounds__(VDC_MAX_THREADS) vdc_executor_kernel(const KPa
 #ifdef VDC_PROFILE
 constexpr uint32_t kVariants[] = {OPS_ALL};
 #elif defined(VDC_SPLIT) || defined(VDC_PART)
-// the last two: matvec programs whose regions all take one slot, built with VDC_WAVE_MASKS (see Ctl::mask)
+// the last three: matvec and stream programs whose regions all take one slot, built with VDC_WAVE_MASKS (see Ctl::mask)
 constexpr uint32_t kVariants[] = {OPS_MATVEC, OPS_MATVEC | OPS_ROWS, OPS_MATVEC | OPS_ROPE, OPS_STREAM, OPS_ATTN, OPS_ALL,
-                                  OPS_ONE_SLOT | OPS_MATVEC, OPS_ONE_SLOT | OPS_MATVEC | OPS_ROWS};
+                                  OPS_ONE_SLOT | OPS_MATVEC, OPS_ONE_SLOT | OPS_MATVEC | OPS_ROWS, OPS_ONE_SLOT | OPS_STREAM};
 #else
 constexpr uint32_t kVariants[] = {OPS_MATVEC, OPS_MATVEC | OPS_ROWS, OPS_MATVEC | OPS_ROPE, OPS_STREAM, OPS_ATTN, OPS_ALL};
 #endif
@@ -3108,9 +3108,9 @@ hipError_t launch_resident(const ResidentParams &, uint32_t, uint32_t, size_t, h
 // the variants are compiled in units of their own (see the end of the file): each exports the address of its kernel
 #define VDC_DECLARE_PART(I) extern "C" const void *vdc_variant_entry_##I();
 VDC_DECLARE_PART(0) VDC_DECLARE_PART(1) VDC_DECLARE_PART(2) VDC_DECLARE_PART(3) VDC_DECLARE_PART(4) VDC_DECLARE_PART(5)
-VDC_DECLARE_PART(6) VDC_DECLARE_PART(7)
+VDC_DECLARE_PART(6) VDC_DECLARE_PART(7) VDC_DECLARE_PART(8)
 #undef VDC_DECLARE_PART
-static_assert(kNumVariants == 8, "one unit per variant");
+static_assert(kNumVariants == 9, "one unit per variant");
 static const void *variant_entry(int i) {
     switch (i) {
         case 0: return vdc_variant_entry_0();
@@ -3120,6 +3120,7 @@ static const void *variant_entry(int i) {
         case 4: return vdc_variant_entry_4();
         case 6: return vdc_variant_entry_6();
         case 7: return vdc_variant_entry_7();
+        case 8: return vdc_variant_entry_8();
         default: return vdc_variant_entry_5();
     }
 }

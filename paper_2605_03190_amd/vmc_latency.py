@@ -103,7 +103,7 @@ def main():
         t_first = median_ms(lambda: ex.stream("read", src, None, one, 1024), args.steps) * 1e3
         ex.check()
         print("%-58s %8.2f us" % ("start-up: launch of an empty graph (start, drain, leave)", t_empty))
-        print("%-58s %8.2f us   (+%.2f us for the first uop)" % ("start-up: launch of a graph with one 1 KB load per compute core", t_first, t_first - t_empty))
+        print("%-58s %8.2f us   (%+.2f us for the first uop)" % ("start-up: launch of a graph with one 1 KB load per compute core", t_first, t_first - t_empty))
         trips, adds = 20000, 6
         ctl = control_program(ex, trips, adds)
         t_ctl = median_ms(lambda: ex.run(ctl, [dummy]), args.steps) * 1e6
